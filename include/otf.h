@@ -1,0 +1,156 @@
+/*
+ * otf.h -- C ABI of the on-the-fly ranking hot path for MI355X (gfx950).
+ *
+ * The library ranks a large, GPU-resident store of compact image features by the score of
+ * a linear SVM, s_i = <w, x_i> + b, and returns the k best rows; it also performs the
+ * Pegasos mini-batch update of w.  These are the two operations the GPU back-end of
+ * "Efficient On-the-fly Category Retrieval using ConvNets and GPUs" (arXiv 1407.4764)
+ * alternates between (Sec. 4, "On-line (GPU back-end)").
+ *
+ * Conventions shared by every entry point
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller owns
+ *     every buffer; the library allocates nothing and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it and the call returns without synchronising; outputs are valid once
+ *     the caller has synchronised the stream.
+ *   - Matrices are row-major.  Row starts must be 16-byte aligned (base pointer and
+ *     leading dimension), otherwise OTF_ERR_INVALID_ARG.
+ *   - Row indices are int32: N must be below 2^31, otherwise OTF_ERR_UNSUPPORTED.
+ *   - Ranked lists hold k entries, best first: score descending, equal scores by ascending
+ *     row index.  1 <= k <= min(N, OTF_MAX_K).  A score of -0.0 is reported as +0.0.
+ *     Scores must be finite; NaN/Inf inputs give unspecified (but in-range) rankings.
+ *   - Return value: OTF_OK (0) or a negative otf_status.  Argument errors are detected on
+ *     the host before anything is enqueued: then no buffer has been written.
+ *   - `ws` is scratch device memory of at least otf_workspace_bytes(N, k, Q) bytes,
+ *     256-byte aligned.  Its contents are undefined on entry and on exit.  Two calls that
+ *     overlap in time (different streams) need different workspaces.
+ */
+#ifndef OTF_H_
+#define OTF_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    OTF_OK = 0,
+    OTF_ERR_INVALID_ARG = -1, /* NULL pointer, non-positive size, k out of range, misalignment */
+    OTF_ERR_UNSUPPORTED = -2, /* a shape this build has no kernel for (see each function)   */
+    OTF_ERR_WORKSPACE = -3,   /* ws is NULL, misaligned or smaller than otf_workspace_bytes */
+    OTF_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed                 */
+} otf_status;
+
+typedef enum { OTF_F32 = 0, OTF_F16 = 1 } otf_dtype;
+
+/* Largest k any ranking call accepts. */
+#define OTF_MAX_K 8192
+
+/* Host.  Name of a status code (static string). */
+const char *otf_status_string(int status);
+
+/* Host.  Upper bound on the scratch bytes any otf_rank_* / otf_topk call needs for N rows,
+ * list length k and Q simultaneous classifiers.  Returns 0 for invalid arguments. */
+size_t otf_workspace_bytes(int64_t N, int32_t k, int32_t Q);
+
+/*
+ * Dense store (paper Sec. 4: the pre-computed ConvNet features of the target dataset kept
+ * in GPU memory, Table 2 rows "2048" / "128", 4 bytes per dimension; ranking = scoring all
+ * of them with the current model, then sorting).
+ *
+ *   scores[q][i] = bias[q] + sum_d W[q][d] * X[i][d]      accumulated in fp32
+ *
+ *   X     N x D, dtype xdt, leading dimension ldx (elements, >= D).
+ *   W     Q x D, dtype wdt, contiguous.  Q >= 1.
+ *   bias  Q floats, or NULL for zero.
+ *   out_scores, out_idx   Q x k, the ranked list of each classifier.
+ *   all_scores            Q x N floats, or NULL when the caller wants only the lists.
+ *
+ * Supported: xdt = F32 with wdt = F32; xdt = F16 with wdt = F32 or F16.  D a multiple of 4
+ * (F32) or 8 (F16).  With Q > 1 and F16/F16 inputs, Q a multiple of 32 and D a multiple of
+ * 64, scoring runs as an MFMA matrix product; other Q > 1 shapes are scored one classifier
+ * at a time.  Anything else: OTF_ERR_UNSUPPORTED.
+ */
+int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t ldx,
+                   const void *W, otf_dtype wdt, int32_t Q, const float *bias,
+                   int32_t k, float *out_scores, int32_t *out_idx,
+                   float *all_scores, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Product-quantised store (paper Sec. 3, "Product quantization (PQ)": the feature is cut
+ * into M sub-blocks of dsub dimensions, each replaced by the index of the nearest of K
+ * centres of that sub-block's own vocabulary; Table 2: one byte per sub-block, so K = 256).
+ * The paper does not say how coded rows are scored; this library scores the reconstructed
+ * row, sum_m <w_m, C[m][code_m]>, through a table of the K partial products per sub-block.
+ *
+ * otf_pq_build_lut:  lut[m][k] = sum_{j<dsub} w[m*dsub + j] * codebooks[m][k][j]   (fp32)
+ *   codebooks  M x K x dsub floats, contiguous.   w  M*dsub floats.   lut  M x K floats.
+ *   Any M, K, dsub >= 1.
+ *
+ * otf_rank_pq:       scores[i] = bias + sum_m lut[m][codes[i][m]]                  (fp32)
+ *   codes  N x M bytes, contiguous rows (leading dimension M).  lut as built above.
+ *   K must be 256 and M one of 16, 32, 64 or a multiple of 128 (up to 1024); other shapes
+ *   return OTF_ERR_UNSUPPORTED.
+ */
+int otf_pq_build_lut(const float *codebooks, int32_t M, int32_t K, int32_t dsub,
+                     const float *w, float *lut, void *stream);
+
+int otf_rank_pq(const uint8_t *codes, int64_t N, int32_t M, int32_t K, const float *lut,
+                float bias, int32_t k, float *out_scores, int32_t *out_idx,
+                float *all_scores, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Binarised store (paper Sec. 3, "Binarization", Eq. (1): codes in {0,1}^D, ranked by a
+ * linear SVM).  Dimension d of row i is bit (d mod 32), least significant first, of 32-bit
+ * word (d div 32) of that row.  A bit enters the model as +1 (set) or -1 (clear):
+ *
+ *   scores[i] = bias + sum_d w[d] * (2 * bit_{i,d} - 1)                           (fp32)
+ *
+ *   bits  N x (D/32) uint32, contiguous rows.   w  D floats.
+ *   D must be a multiple of 1024 (up to 8192) or one of 128, 256, 512; other values return
+ *   OTF_ERR_UNSUPPORTED.
+ */
+int otf_rank_binary(const uint32_t *bits, int64_t N, int32_t D, const float *w, float bias,
+                    int32_t k, float *out_scores, int32_t *out_idx,
+                    float *all_scores, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Ranking alone (paper Sec. 4: the scores are sorted on the GPU and the head of the list is
+ * handed to the front-end).  For each of the Q rows of `scores` (row stride ld floats,
+ * ld >= N) returns the k largest entries, sorted.
+ */
+int otf_topk(const float *scores, int64_t N, int64_t ld, int32_t Q, int32_t k,
+             float *out_scores, int32_t *out_idx, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * One Pegasos mini-batch step on the hinge loss with L2 regulariser lambda (paper Sec. 4,
+ * "Training": learning rate 1/(lambda t), each batch half positives, half negatives).
+ * The batch is rows Xpos[idx_pos[0..n_pos)] with label +1 and rows Xneg[idx_neg[0..n_neg)]
+ * with label -1 (sampling is the caller's job); B = n_pos + n_neg.
+ *
+ *   eta  = 1 / (lambda * t)
+ *   m_j  = y_j * (<w, x_j> + b)        with w, b as they are on entry
+ *   V    = { j : m_j < 1 }
+ *   w   <- (1 - eta*lambda) * w + (eta / B) * sum_{j in V} y_j * x_j
+ *   b   <- b + (eta / B) * sum_{j in V} y_j      only if update_bias != 0
+ *
+ *   w  D floats, updated in place.  b  one float (may be NULL: bias 0, never updated).
+ *   Xpos, Xneg  fp32 pools with leading dimensions ld_pos, ld_neg (elements, >= D).
+ *   idx_pos, idx_neg  int32 row numbers into the pools (device memory).
+ *   D a multiple of 4; 1 <= B <= 4096; t >= 1; lambda > 0.
+ *   ws  at least otf_sgd_workspace_bytes(B) bytes.
+ */
+size_t otf_sgd_workspace_bytes(int32_t B);
+
+int otf_svm_sgd_step(float *w, float *b, int32_t D,
+                     const float *Xpos, int64_t ld_pos, const int32_t *idx_pos, int32_t n_pos,
+                     const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int32_t n_neg,
+                     float lambda, int64_t t, int32_t update_bias,
+                     void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OTF_H_ */

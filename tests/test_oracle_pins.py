@@ -1,0 +1,344 @@
+"""Pins for the CPU oracle: every oracle function is checked against something that is not
+the oracle -- numpy's fp64 matmul, numpy's own half/bit decoders, brute-force python loops on
+tiny inputs, closed forms of the Pegasos update, and invariants that a dropped term, a wrong
+sign, a transposed operand or an off-by-one index would break.  CPU only."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from paper_1407_4764_amd import synth
+
+RNG = np.random.default_rng(1407)
+
+
+# ------------------------------------------------------------------------------ dense
+def test_dense_equals_numpy_fp64_matmul(oracle):
+    N, D, Q = 257, 96, 3                      # non-square on purpose: a transposed operand fails
+    X = RNG.standard_normal((N, D)).astype(np.float32)
+    W = RNG.standard_normal((Q, D)).astype(np.float32)
+    b = RNG.standard_normal(Q).astype(np.float32)
+    got = oracle.dense_scores(X, W, b)
+    ref = W.astype(np.float64) @ X.astype(np.float64).T + b.astype(np.float64)[:, None]
+    assert got.shape == (Q, N)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+
+
+def test_dense_planted_row_ranks_first(oracle):
+    N, D = 500, 128
+    X = synth.dense_features(N, D, seed=1).numpy()
+    w = RNG.standard_normal(D).astype(np.float32)
+    b = np.float32(0.75)
+    planted = 123
+    X[planted] = (w / np.linalg.norm(w)).astype(np.float32)
+    s = oracle.dense_scores(X, w, [b])[0]
+    idx, val = oracle.topk(s, 5)
+    assert idx[0] == planted
+    # Cauchy-Schwarz: <w, w/|w|> = |w| is the maximum over unit rows
+    assert abs(val[0] - (np.linalg.norm(w.astype(np.float64)) + float(b))) < 1e-5
+
+
+def test_dense_linearity_and_permutation(oracle):
+    N, D = 64, 40
+    X = RNG.standard_normal((N, D)).astype(np.float32)
+    w1 = RNG.standard_normal(D).astype(np.float32)
+    w2 = RNG.standard_normal(D).astype(np.float32)
+    s1 = oracle.dense_scores(X, w1)[0]
+    s2 = oracle.dense_scores(X, w2)[0]
+    s12 = oracle.dense_scores(X, np.stack([w1, w2]), [1.0, -2.0])
+    np.testing.assert_allclose(s12[0], s1 + 1.0, atol=1e-12)
+    np.testing.assert_allclose(s12[1], s2 - 2.0, atol=1e-12)
+    # exact doubling of w doubles the score exactly (power-of-two scaling is exact)
+    np.testing.assert_array_equal(oracle.dense_scores(X, 2 * w1)[0], 2 * s1)
+    perm = RNG.permutation(N)
+    np.testing.assert_array_equal(oracle.dense_scores(X[perm], w1)[0], s1[perm])
+
+
+def test_dense_edge_shapes(oracle):
+    X = np.array([[3.0]], dtype=np.float32)
+    assert oracle.dense_scores(X, np.array([2.0], dtype=np.float32), [1.0])[0, 0] == 7.0
+    X = np.arange(6, dtype=np.float32).reshape(1, 6)
+    w = np.ones(6, dtype=np.float32)
+    assert oracle.dense_scores(X, w)[0, 0] == 15.0
+    # one-hot w picks out a single column: catches any index slip in d
+    X = RNG.standard_normal((7, 9)).astype(np.float32)
+    for d in range(9):
+        w = np.zeros(9, dtype=np.float32)
+        w[d] = 1.0
+        np.testing.assert_array_equal(oracle.dense_scores(X, w)[0], X[:, d].astype(np.float64))
+
+
+def test_half_decoder_matches_numpy_for_every_pattern(oracle):
+    pats = np.arange(65536, dtype=np.uint16)
+    ref = pats.view(np.float16).astype(np.float64)
+    for p in itertools.chain(range(0, 65536, 97), [0, 1, 0x03ff, 0x0400, 0x7bff, 0x8000, 0x8001, 0xfbff, 0x3c00]):
+        got = oracle.half_to_double(p)
+        assert got == ref[p] or (np.isnan(got) and np.isnan(ref[p])), hex(p)
+    assert oracle.half_to_double(0x7c00) == np.inf and oracle.half_to_double(0xfc00) == -np.inf
+
+
+def test_dense_f16_paths_equal_numpy(oracle):
+    N, D, Q = 100, 64, 4
+    X = (RNG.standard_normal((N, D)) * 0.1).astype(np.float16)
+    W16 = (RNG.standard_normal((Q, D)) * 0.05).astype(np.float16)
+    W32 = RNG.standard_normal((Q, D)).astype(np.float32)
+    ref16 = W16.astype(np.float64) @ X.astype(np.float64).T
+    ref32 = W32.astype(np.float64) @ X.astype(np.float64).T
+    np.testing.assert_allclose(oracle.dense_scores(X, W16), ref16, atol=1e-13)
+    np.testing.assert_allclose(oracle.dense_scores(X, W32), ref32, atol=1e-12)
+
+
+# ------------------------------------------------------------------------------ PQ
+def _pq_case(N, M, K, dsub, seed):
+    cb = synth.pq_codebooks(M, K, dsub, seed).numpy()
+    codes = synth.pq_codes(N, M, K, seed + 1).numpy()
+    w = RNG.standard_normal(M * dsub).astype(np.float32)
+    return cb, codes, w
+
+
+def test_pq_lut_sum_equals_dot_with_reconstruction(oracle):
+    cb, codes, w = _pq_case(300, 12, 256, 5, seed=3)
+    s_rec = oracle.pq_scores_reconstruct(codes, cb, w, 0.25)
+    s_lut = oracle.pq_scores_lut(codes, oracle.pq_lut(cb, w), 0.25)
+    np.testing.assert_allclose(s_lut, s_rec, rtol=1e-12, atol=1e-12)
+    # and the reconstruction route equals the dense oracle run on explicitly gathered rows
+    xhat = np.concatenate([cb[m, codes[:, m], :] for m in range(12)], axis=1)
+    np.testing.assert_allclose(s_rec, oracle.dense_scores(xhat, w, [0.25])[0], atol=1e-12)
+    np.testing.assert_allclose(s_rec, xhat.astype(np.float64) @ w.astype(np.float64) + 0.25, atol=1e-12)
+
+
+def test_pq_brute_force_tiny(oracle):
+    M, K, dsub, N = 3, 4, 2, 6
+    cb, codes, w = _pq_case(N, M, K, dsub, seed=5)
+    got = oracle.pq_scores_reconstruct(codes, cb, w, -1.0)
+    for i in range(N):
+        acc = -1.0
+        for m in range(M):
+            for j in range(dsub):
+                acc += float(w[m * dsub + j]) * float(cb[m][codes[i][m]][j])
+        assert abs(got[i] - acc) < 1e-12
+
+
+def test_pq_lut_matches_einsum_and_special_cases(oracle):
+    cb, codes, w = _pq_case(50, 8, 256, 4, seed=7)
+    lut = oracle.pq_lut(cb, w)
+    ref = np.einsum("mkj,mj->mk", cb.astype(np.float64), w.astype(np.float64).reshape(8, 4))
+    np.testing.assert_allclose(lut, ref, atol=1e-13)
+    # M = 1: the score is bias + one table entry
+    cb1, codes1, w1 = _pq_case(20, 1, 256, 4, seed=9)
+    lut1 = oracle.pq_lut(cb1, w1)
+    np.testing.assert_array_equal(oracle.pq_scores_lut(codes1, lut1, 2.0), 2.0 + lut1[0, codes1[:, 0]])
+    # K = 1: every row reconstructs to the same vector
+    cbk, _, wk = _pq_case(1, 5, 1, 3, seed=11)
+    s = oracle.pq_scores_reconstruct(np.zeros((9, 5), np.uint8), cbk, wk, 0.0)
+    assert np.all(s == s[0])
+    # changing one code byte moves the score by exactly the difference of two table entries
+    base = oracle.pq_scores_lut(codes, lut, 0.0)
+    codes2 = codes.copy()
+    old = codes2[17, 3]
+    codes2[17, 3] = (int(old) + 101) % 256
+    moved = oracle.pq_scores_lut(codes2, lut, 0.0)
+    assert np.all(moved[np.arange(50) != 17] == base[np.arange(50) != 17])
+    assert abs((moved[17] - base[17]) - (lut[3, codes2[17, 3]] - lut[3, old])) < 1e-12
+
+
+def test_pq_rejects_code_out_of_range(oracle):
+    cb, codes, w = _pq_case(4, 2, 16, 2, seed=13)
+    codes[1, 1] = 200
+    with pytest.raises(RuntimeError):
+        oracle.pq_scores_reconstruct(codes, cb, w, 0.0)
+
+
+# ------------------------------------------------------------------------------ binary
+def test_binary_identity_sum_minus_twice_zero_bits(oracle):
+    N, D = 200, 256
+    bits = synth.as_uint32(synth.binary_bits_from_features(N, D, seed=21).numpy())
+    w = RNG.standard_normal(D).astype(np.float32)
+    s = oracle.binary_scores(bits, D, w, 0.5)
+    # numpy's own unpacker, little-endian bit order, on the little-endian byte view
+    unpacked = np.unpackbits(bits.view(np.uint8), axis=1, bitorder="little")[:, :D]
+    wd = w.astype(np.float64)
+    ref = 0.5 + wd.sum() - 2.0 * ((1 - unpacked) * wd).sum(axis=1)
+    np.testing.assert_allclose(s, ref, atol=1e-10)
+    # cross-path: the dense oracle on the +/-1 expanded matrix
+    pm = (2.0 * unpacked - 1.0).astype(np.float32)
+    np.testing.assert_allclose(s, oracle.dense_scores(pm, w, [0.5])[0], atol=1e-10)
+
+
+def test_binary_extremes_and_single_bit_words(oracle):
+    D = 96
+    w = RNG.standard_normal(D).astype(np.float32)
+    wd = w.astype(np.float64)
+    ones = np.full((1, 3), 0xFFFFFFFF, dtype=np.uint32)
+    zeros = np.zeros((1, 3), dtype=np.uint32)
+    assert abs(oracle.binary_scores(ones, D, w, 1.0)[0] - (1.0 + wd.sum())) < 1e-12
+    assert abs(oracle.binary_scores(zeros, D, w, 1.0)[0] - (1.0 - wd.sum())) < 1e-12
+    # every single-bit row: exactly dimension d is +, the rest are -
+    rows = np.zeros((D, 3), dtype=np.uint32)
+    for d in range(D):
+        rows[d, d // 32] = np.uint32(1) << np.uint32(d % 32)
+    s = oracle.binary_scores(rows, D, w, 0.0)
+    np.testing.assert_allclose(s, -wd.sum() + 2.0 * wd, atol=1e-12)
+    # flipping bit d of a random row moves the score by +-2 w_d
+    row = RNG.integers(0, 2 ** 32, size=(1, 3), dtype=np.uint64).astype(np.uint32)
+    base = oracle.binary_scores(row, D, w, 0.0)[0]
+    for d in (0, 1, 31, 32, 63, 64, 95):
+        r2 = row.copy()
+        r2[0, d // 32] ^= np.uint32(1) << np.uint32(d % 32)
+        was_set = (int(row[0, d // 32]) >> (d % 32)) & 1
+        delta = oracle.binary_scores(r2, D, w, 0.0)[0] - base
+        assert abs(delta - (-2.0 if was_set else 2.0) * wd[d]) < 1e-12
+
+
+def test_sign_convention_zero_is_bit_zero():
+    import torch
+    f = torch.tensor([[0.0, -0.0, 1e-30, -1e-30] + [0.0] * 28])
+    word = int(synth.pack_sign_bits(f).numpy().view(np.uint32)[0, 0])
+    assert word == 0b0100                      # only the strictly positive entry sets its bit (Eq. (1))
+
+
+# ------------------------------------------------------------------------------ top-k
+def _brute_topk(s, k):
+    order = sorted(range(len(s)), key=lambda i: (-s[i], i))
+    return np.array(order[:k]), np.array([s[i] for i in order[:k]])
+
+
+def test_topk_equals_brute_force_full_sort(oracle):
+    for N, k in [(1, 1), (10, 3), (1000, 100), (1000, 1000), (4097, 1)]:
+        s = RNG.standard_normal(N)
+        s[RNG.integers(0, N, size=N // 3)] = 0.25          # many duplicates
+        idx, val = oracle.topk(s, k)
+        bidx, bval = _brute_topk(list(s), k)
+        np.testing.assert_array_equal(idx, bidx)
+        np.testing.assert_array_equal(val, bval)
+    # numpy lexsort as a second, library-based definition
+    s = np.round(RNG.standard_normal(5000), 1)
+    idx, _ = oracle.topk(s, 777)
+    np.testing.assert_array_equal(idx, np.lexsort((np.arange(5000), -s))[:777])
+
+
+def test_topk_special_cases(oracle):
+    s = np.full(50, 3.0)
+    idx, val = oracle.topk(s, 7)
+    np.testing.assert_array_equal(idx, np.arange(7))
+    s = RNG.standard_normal(300)
+    assert oracle.topk(s, 1)[0][0] == int(np.argmax(s))
+    with pytest.raises(RuntimeError):
+        oracle.topk(np.array([1.0, np.nan]), 1)
+    with pytest.raises(RuntimeError):
+        oracle.topk(np.array([1.0, 2.0]), 3)
+
+
+# ------------------------------------------------------------------------------ Pegasos step
+def _pools(D=32, n_pos=20, n_neg=40, seed=31):
+    pos, neg = synth.sgd_pools(D, n_pos, n_neg, seed, n_shift_dims=5)
+    return pos.numpy(), neg.numpy()
+
+
+def test_sgd_hand_worked_example(oracle):
+    # lambda=0.5, t=2 -> eta=1.  Positive (0.5,1): margin 0.5 < 1, violates.  Negative (-2,0):
+    # margin -(1*-2) = 2, does not.  w' = (1-0.5)(1,0) + (1/2)(0.5,1) = (0.75, 0.5).
+    w = np.array([1.0, 0.0], dtype=np.float32)
+    Xp = np.array([[0.5, 1.0]], dtype=np.float32)
+    Xn = np.array([[-2.0, 0.0]], dtype=np.float32)
+    w2, b2, m = oracle.sgd_step(w, 0.0, Xp, [0], Xn, [0], lam=0.5, t=2)
+    np.testing.assert_allclose(w2, [0.75, 0.5], atol=1e-15)
+    np.testing.assert_allclose(m, [0.5, 2.0], atol=1e-15)
+    assert b2 == 0.0
+    # with the bias updated: b' = 0 + (1/2)(+1) = 0.5
+    _, b3, _ = oracle.sgd_step(w, 0.0, Xp, [0], Xn, [0], lam=0.5, t=2, update_bias=True)
+    assert abs(b3 - 0.5) < 1e-15
+    # a margin of exactly 1 is not a violator (strict inequality): w only shrinks
+    Xk = np.array([[1.0, 5.0]], dtype=np.float32)
+    w4, _, m4 = oracle.sgd_step(w, 0.0, Xk, [0], Xn, [0], lam=0.5, t=2)
+    assert m4[0] == 1.0
+    np.testing.assert_allclose(w4, [0.5, 0.0], atol=1e-15)
+
+
+def test_sgd_closed_forms(oracle):
+    Xp, Xn = _pools()
+    D = Xp.shape[1]
+    ip = np.array([3, 3, 7, 0, 19, 5], dtype=np.int32)       # repeats allowed
+    ineg = np.array([1, 39, 2, 8, 8, 30], dtype=np.int32)
+    B = 12
+    lam = 0.01
+    # w0 = 0, b0 = 0: every margin is 0 < 1, so w1 = (1/(lam B)) (sum pos - sum neg)
+    w1, b1, m = oracle.sgd_step(np.zeros(D, np.float32), 0.0, Xp, ip, Xn, ineg, lam, 1, update_bias=True)
+    ref = (Xp[ip].astype(np.float64).sum(0) - Xn[ineg].astype(np.float64).sum(0)) / (lam * B)
+    np.testing.assert_allclose(w1, ref, rtol=1e-13)
+    assert np.all(m == 0.0) and abs(b1 - (6 - 6) / (lam * B)) < 1e-15
+    # t = 1 with any w0: the shrink factor is 0, w0 only decides who violates
+    w0 = (RNG.standard_normal(D) * 3).astype(np.float32)
+    w1, _, m = oracle.sgd_step(w0, 0.2, Xp, ip, Xn, ineg, lam, 1)
+    y = np.array([1.0] * 6 + [-1.0] * 6)
+    Xb = np.concatenate([Xp[ip], Xn[ineg]]).astype(np.float64)
+    np.testing.assert_allclose(m, y * (Xb @ w0.astype(np.float64) + 0.2), atol=1e-12)
+    V = m < 1
+    assert 0 < V.sum() < B                                   # the case is not degenerate
+    np.testing.assert_allclose(w1, (y[V, None] * Xb[V]).sum(0) / (lam * B), rtol=1e-12, atol=1e-12)
+    # no violators: w_{t+1} = (1 - 1/t) w_t exactly.  Features are non-negative, so a large
+    # positive bias satisfies the positives and a flipped setup satisfies the negatives.
+    wz = np.zeros(D, np.float32)
+    w5, _, m5 = oracle.sgd_step(wz + 0.0, 5.0, Xp, ip, Xn, np.array([], np.int32), lam, 4)
+    assert np.all(m5 >= 1)
+    np.testing.assert_array_equal(w5, 0.75 * wz)
+    wbig = np.full(D, 10.0, np.float32)
+    w6, _, m6 = oracle.sgd_step(wbig, 0.0, Xp, ip, Xn, np.array([], np.int32), lam, 4)
+    assert np.all(m6 >= 1)
+    np.testing.assert_allclose(w6, 0.75 * wbig.astype(np.float64), rtol=1e-15)
+
+
+def test_sgd_label_sign_and_learning_rate(oracle):
+    Xp, Xn = _pools()
+    D = Xp.shape[1]
+    z = np.zeros(D, np.float32)
+    # only negatives, w0=0: w1 = -(1/(lam B)) sum neg  (sign of the label)
+    w1, b1, _ = oracle.sgd_step(z, 0.0, Xp, np.array([], np.int32), Xn, [4, 5], 0.5, 1, update_bias=True)
+    np.testing.assert_allclose(w1, -Xn[[4, 5]].astype(np.float64).sum(0) / (0.5 * 2), rtol=1e-13)
+    assert abs(b1 - (-2) / (0.5 * 2)) < 1e-15
+    # learning rate 1/(lambda t): at step t the gradient part scales as 1/t
+    wa, _, _ = oracle.sgd_step(z, 0.0, Xp, [1], Xn, [2], 0.25, 1)
+    wb, _, _ = oracle.sgd_step(z, 0.0, Xp, [1], Xn, [2], 0.25, 8)
+    np.testing.assert_allclose(wb, wa / 8.0, rtol=1e-13)
+
+
+def test_sgd_pass_lowers_the_objective(oracle):
+    Xp, Xn = _pools(D=64, n_pos=100, n_neg=400, seed=37)
+    lam = 1e-2
+    w = np.zeros(64, np.float32)
+    b = 0.0
+    pos_idx, neg_idx = synth.sgd_batches(100, 400, 32, 25, seed=41)
+    start = oracle.svm_objective(w.astype(np.float64), b, Xp, Xn, lam)
+    assert abs(start - 1.0) < 1e-12           # w = 0: every hinge term is exactly 1
+    for t in range(1, 26):
+        w64, b, _ = oracle.sgd_step(w, b, Xp, pos_idx[t - 1], Xn, neg_idx[t - 1], lam, t, update_bias=True)
+        w = w64.astype(np.float32)
+    end = oracle.svm_objective(w.astype(np.float64), b, Xp, Xn, lam)
+    assert end < 0.9 * start
+    # objective helper against numpy
+    Xall = np.concatenate([Xp, Xn]).astype(np.float64)
+    y = np.array([1.0] * 100 + [-1.0] * 400)
+    ref = 0.5 * lam * float(w.astype(np.float64) @ w.astype(np.float64)) + np.maximum(0, 1 - y * (Xall @ w.astype(np.float64) + b)).mean()
+    assert abs(end - ref) < 1e-12
+
+
+# ------------------------------------------------------------------------------ storage layouts
+def test_table2_storage_arithmetic():
+    """Bytes per stored row of the three layouts reproduce the storage column of Table 2."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "table2_storage.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    import torch
+    for name, dim, param, printed_value, printed_unit in rows:
+        dim, param, printed_value = int(dim), int(param), float(printed_value)
+        if name == "dense_fp32":
+            row_bytes = synth.dense_features(2, dim, 0).element_size() * dim
+        elif name == "pq":                      # param = dimensions per sub-block, one byte each
+            M = dim // param
+            row_bytes = synth.pq_codes(2, M, 256, 0).element_size() * M
+        else:
+            raise AssertionError(name)
+        per_million = row_bytes * 1e6 / (2 ** 30 if printed_unit == "GB" else 2 ** 20)
+        assert abs(per_million - printed_value) <= 0.06 * max(1.0, printed_value / 100), (name, dim, per_million)
+    # binary codes: 2048 bits are 256 bytes = 64 words per row (the table's "8" bytes cannot hold them)
+    assert synth.binary_bits_random(2, 2048 // 32, 0).shape[1] * 4 == 256
