@@ -69,9 +69,9 @@ size_t otf_workspace_bytes(int64_t N, int32_t k, int32_t Q);
  *   all_scores            Q x N floats, or NULL when the caller wants only the lists.
  *
  * Supported: xdt = F32 with wdt = F32; xdt = F16 with wdt = F32 or F16.  D a multiple of 4
- * (F32) or 8 (F16).  With Q > 1 and F16/F16 inputs, Q a multiple of 32 and D a multiple of
- * 64, scoring runs as an MFMA matrix product; other Q > 1 shapes are scored one classifier
- * at a time.  Anything else: OTF_ERR_UNSUPPORTED.
+ * (F32) or 8 (F16), at most 16384.  With Q > 1 and F16/F16 inputs, Q a multiple of 32 and D
+ * a multiple of 128, scoring runs as an MFMA matrix product; other Q > 1 shapes are scored
+ * one classifier at a time (X is then read Q times).  Anything else: OTF_ERR_UNSUPPORTED.
  */
 int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t ldx,
                    const void *W, otf_dtype wdt, int32_t Q, const float *bias,
@@ -149,6 +149,17 @@ int otf_svm_sgd_step(float *w, float *b, int32_t D,
                      const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int32_t n_neg,
                      float lambda, int64_t t, int32_t update_bias,
                      void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Diagnostics (host, not part of the paper's method; for benchmarks that must time the
+ * scoring kernel by itself).  Between otf_profile_begin and otf_profile_end every otf_rank_*
+ * call brackets its scoring kernel(s) with a pair of HIP events on the call's stream, at most
+ * max_records calls.  otf_profile_end waits for the recorded events, returns the summed
+ * kernel time in milliseconds and the number of calls recorded, and releases the events.
+ * Process-wide state, not thread-safe; returns OTF_ERR_INVALID_ARG when misused.
+ */
+int otf_profile_begin(int32_t max_records);
+int otf_profile_end(double *scan_ms_total, int32_t *n_records);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,305 @@
+// C ABI of libotf: argument validation, workspace layout and the launch sequences.
+// All validation happens on the host before the first HIP call, so a rejected call has
+// enqueued nothing and written nothing.
+#include "otf.h"
+
+#include <atomic>
+#include <vector>
+
+#include "otf_internal.h"
+
+namespace otf {
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static int64_t padded_rows(int64_t N) { return (N + 63) / 64 * 64; }
+
+WsLayout ws_layout(int64_t N, int32_t Q) {
+    WsLayout L;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    L.st = take((size_t)Q * sizeof(SelState));
+    L.hist1 = take((size_t)Q * kBins1 * 4);
+    L.hist2 = take((size_t)Q * kBins2 * 4);
+    L.blockhist3 = take((size_t)Q * kSelBlocks * kBins3 * 4);
+    L.eqoff = take((size_t)Q * kSelBlocks * 4);
+    L.cand = take((size_t)Q * kCandCap * 8);
+    L.lut_image = take(kLutImageBytes);
+    L.scores = take((size_t)Q * (size_t)padded_rows(N) * 4);
+    L.total = off;
+    return L;
+}
+
+SelectWs select_ws(void *ws, const WsLayout &L) {
+    uint8_t *p = reinterpret_cast<uint8_t *>(ws);
+    SelectWs sw;
+    sw.st = reinterpret_cast<SelState *>(p + L.st);
+    sw.hist1 = reinterpret_cast<uint32_t *>(p + L.hist1);
+    sw.hist2 = reinterpret_cast<uint32_t *>(p + L.hist2);
+    sw.blockhist3 = reinterpret_cast<uint32_t *>(p + L.blockhist3);
+    sw.eqoff = reinterpret_cast<uint32_t *>(p + L.eqoff);
+    sw.cand = reinterpret_cast<unsigned long long *>(p + L.cand);
+    return sw;
+}
+
+int device_cu_count() {
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int v = cached[dev].load(std::memory_order_relaxed);
+    if (v > 0) return v;
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    cached[dev].store(cus, std::memory_order_relaxed);
+    return cus;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int hip_status(hipError_t e) {
+    if (e == hipSuccess) return OTF_OK;
+    (void)hipGetLastError();   // clear the sticky error so that it is not reported twice
+    return OTF_ERR_HIP;
+}
+
+// Checks shared by all ranking calls.  Returns OTF_OK or the status to hand back.
+static int check_rank_common(int64_t N, int32_t k, int32_t Q, const float *out_scores, const int32_t *out_idx,
+                             const void *ws, size_t ws_bytes, WsLayout *L) {
+    if (N < 1 || Q < 1 || k < 1 || !out_scores || !out_idx) return OTF_ERR_INVALID_ARG;
+    if (N >= ((int64_t)1 << 31)) return OTF_ERR_UNSUPPORTED;
+    if (k > N || k > OTF_MAX_K) return OTF_ERR_INVALID_ARG;
+    if (Q > 65535) return OTF_ERR_UNSUPPORTED;
+    *L = ws_layout(N, Q);
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || ws_bytes < L->total) return OTF_ERR_WORKSPACE;
+    return OTF_OK;
+}
+
+// Optional event pairs around the scoring kernels (see otf_profile_begin in otf.h).
+struct ProfileState {
+    std::vector<hipEvent_t> start, stop;
+    int used = 0;
+    bool on = false;
+};
+static ProfileState g_prof;
+
+struct ScanTimer {
+    int slot = -1;
+    hipStream_t s;
+    explicit ScanTimer(hipStream_t stream) : s(stream) {
+        if (g_prof.on && g_prof.used < (int)g_prof.start.size()) {
+            slot = g_prof.used++;
+            (void)hipEventRecord(g_prof.start[slot], s);
+        }
+    }
+    void stop() {
+        if (slot >= 0) (void)hipEventRecord(g_prof.stop[slot], s);
+    }
+};
+
+}  // namespace otf
+
+using namespace otf;
+
+extern "C" {
+
+const char *otf_status_string(int status) {
+    switch (status) {
+        case OTF_OK: return "OTF_OK";
+        case OTF_ERR_INVALID_ARG: return "OTF_ERR_INVALID_ARG";
+        case OTF_ERR_UNSUPPORTED: return "OTF_ERR_UNSUPPORTED";
+        case OTF_ERR_WORKSPACE: return "OTF_ERR_WORKSPACE";
+        case OTF_ERR_HIP: return "OTF_ERR_HIP";
+        default: return "OTF_ERR_UNKNOWN";
+    }
+}
+
+size_t otf_workspace_bytes(int64_t N, int32_t k, int32_t Q) {
+    if (N < 1 || k < 1 || Q < 1 || Q > 65535 || N >= ((int64_t)1 << 31)) return 0;
+    return ws_layout(N, Q).total;
+}
+
+int otf_topk(const float *scores, int64_t N, int64_t ld, int32_t Q, int32_t k, float *out_scores, int32_t *out_idx,
+             void *ws, size_t ws_bytes, void *stream) {
+    WsLayout L;
+    if (!scores) return OTF_ERR_INVALID_ARG;
+    int rc = check_rank_common(N, k, Q, out_scores, out_idx, ws, ws_bytes, &L);
+    if (rc != OTF_OK) return rc;
+    if (ld < N) return OTF_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    SelectWs sw = select_ws(ws, L);
+    hipError_t e = launch_select_init(sw, Q, s);
+    if (e == hipSuccess) e = launch_hist1(scores, N, ld, Q, k, sw, s);
+    if (e == hipSuccess) e = launch_select_tail(scores, N, ld, Q, k, sw, out_scores, out_idx, s);
+    return hip_status(e);
+}
+
+int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t ldx, const void *W, otf_dtype wdt,
+                   int32_t Q, const float *bias, int32_t k, float *out_scores, int32_t *out_idx, float *all_scores,
+                   void *ws, size_t ws_bytes, void *stream) {
+    WsLayout L;
+    if (!X || !W || D < 1) return OTF_ERR_INVALID_ARG;
+    if ((xdt != OTF_F32 && xdt != OTF_F16) || (wdt != OTF_F32 && wdt != OTF_F16)) return OTF_ERR_INVALID_ARG;
+    int rc = check_rank_common(N, k, Q, out_scores, out_idx, ws, ws_bytes, &L);
+    if (rc != OTF_OK) return rc;
+    if (ldx < D) return OTF_ERR_INVALID_ARG;
+    const int xsize = xdt == OTF_F16 ? 2 : 4;
+    if (!aligned16(X) || ((size_t)ldx * xsize) % 16 != 0) return OTF_ERR_INVALID_ARG;
+    if (xdt == OTF_F32 && wdt != OTF_F32) return OTF_ERR_UNSUPPORTED;
+    if (D % (16 / xsize) != 0 || D > kDenseMaxD) return OTF_ERR_UNSUPPORTED;
+
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    SelectWs sw = select_ws(ws, L);
+    float *S = all_scores ? all_scores : reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + L.scores);
+    const int64_t ldS = all_scores ? N : (int64_t)((N + 63) / 64 * 64);
+    const int x_half = xdt == OTF_F16, w_half = wdt == OTF_F16;
+    const size_t wsize = w_half ? 2 : 4;
+
+    hipError_t e = launch_select_init(sw, Q, s);
+    const bool mfma = Q > 1 && x_half && w_half && Q % 32 == 0 && D % 128 == 0 && aligned16(W);
+    ScanTimer timer(s);
+    if (e == hipSuccess && mfma) {
+        for (int q0 = 0; q0 < Q && e == hipSuccess; ) {
+            const int qn = (Q - q0 >= 64) ? 64 : 32;
+            e = launch_dense_mfma(X, N, D, ldx, reinterpret_cast<const uint8_t *>(W) + (size_t)q0 * D * wsize, qn,
+                                  bias ? bias + q0 : nullptr, S + (size_t)q0 * ldS, ldS, s);
+            q0 += qn;
+        }
+        timer.stop();
+        if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, k, sw, s);
+    } else if (e == hipSuccess) {
+        for (int q = 0; q < Q && e == hipSuccess; ++q)
+            e = launch_dense_scan(X, x_half, N, D, ldx, reinterpret_cast<const uint8_t *>(W) + (size_t)q * D * wsize,
+                                  w_half, bias, q, S + (size_t)q * ldS, sw.st + q, sw.hist1 + (size_t)q * kBins1, k, s);
+        timer.stop();
+    }
+    if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, s);
+    return hip_status(e);
+}
+
+int otf_pq_build_lut(const float *codebooks, int32_t M, int32_t K, int32_t dsub, const float *w, float *lut,
+                     void *stream) {
+    if (!codebooks || !w || !lut || M < 1 || K < 1 || dsub < 1) return OTF_ERR_INVALID_ARG;
+    if ((int64_t)M * K * dsub >= ((int64_t)1 << 40)) return OTF_ERR_UNSUPPORTED;
+    return hip_status(launch_pq_build_lut(codebooks, M, K, dsub, w, lut, reinterpret_cast<hipStream_t>(stream)));
+}
+
+static bool table_row_bytes_ok(int32_t rb) {
+    return rb == 16 || rb == 32 || rb == 64 || (rb >= 128 && rb % 128 == 0 && rb <= 1024);
+}
+
+int otf_rank_pq(const uint8_t *codes, int64_t N, int32_t M, int32_t K, const float *lut, float bias, int32_t k,
+                float *out_scores, int32_t *out_idx, float *all_scores, void *ws, size_t ws_bytes, void *stream) {
+    WsLayout L;
+    if (!codes || !lut || M < 1 || K < 1) return OTF_ERR_INVALID_ARG;
+    int rc = check_rank_common(N, k, 1, out_scores, out_idx, ws, ws_bytes, &L);
+    if (rc != OTF_OK) return rc;
+    if (K != 256 || !table_row_bytes_ok(M)) return OTF_ERR_UNSUPPORTED;
+    if (!aligned16(codes)) return OTF_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    SelectWs sw = select_ws(ws, L);
+    uint8_t *wsb = reinterpret_cast<uint8_t *>(ws);
+    float *image = reinterpret_cast<float *>(wsb + L.lut_image);
+    float *S = all_scores ? all_scores : reinterpret_cast<float *>(wsb + L.scores);
+    hipError_t e = launch_pq_prepare(lut, M, image, sw, s);
+    ScanTimer timer(s);
+    if (e == hipSuccess) e = launch_table_scan(codes, N, M, image, bias, S, sw.st, sw.hist1, k, s);
+    timer.stop();
+    if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, s);
+    return hip_status(e);
+}
+
+int otf_rank_binary(const uint32_t *bits, int64_t N, int32_t D, const float *w, float bias, int32_t k,
+                    float *out_scores, int32_t *out_idx, float *all_scores, void *ws, size_t ws_bytes, void *stream) {
+    WsLayout L;
+    if (!bits || !w || D < 1) return OTF_ERR_INVALID_ARG;
+    int rc = check_rank_common(N, k, 1, out_scores, out_idx, ws, ws_bytes, &L);
+    if (rc != OTF_OK) return rc;
+    if (D % 32 != 0 || !table_row_bytes_ok(D / 8)) return OTF_ERR_UNSUPPORTED;
+    if (!aligned16(bits)) return OTF_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    SelectWs sw = select_ws(ws, L);
+    uint8_t *wsb = reinterpret_cast<uint8_t *>(ws);
+    float *image = reinterpret_cast<float *>(wsb + L.lut_image);
+    float *S = all_scores ? all_scores : reinterpret_cast<float *>(wsb + L.scores);
+    hipError_t e = launch_binary_prepare(w, D, image, sw, s);
+    ScanTimer timer(s);
+    if (e == hipSuccess)
+        e = launch_table_scan(reinterpret_cast<const uint8_t *>(bits), N, D / 8, image, bias, S, sw.st, sw.hist1, k, s);
+    timer.stop();
+    if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, s);
+    return hip_status(e);
+}
+
+size_t otf_sgd_workspace_bytes(int32_t B) {
+    if (B < 1 || B > 4096) return 0;
+    return (size_t)4096 * sizeof(float);
+}
+
+int otf_svm_sgd_step(float *w, float *b, int32_t D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,
+                     int32_t n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int32_t n_neg,
+                     float lambda, int64_t t, int32_t update_bias, void *ws, size_t ws_bytes, void *stream) {
+    if (!w || D < 1 || n_pos < 0 || n_neg < 0 || n_pos + n_neg < 1 || t < 1 || !(lambda > 0.f))
+        return OTF_ERR_INVALID_ARG;
+    if (n_pos > 0 && (!Xpos || !idx_pos || ld_pos < D)) return OTF_ERR_INVALID_ARG;
+    if (n_neg > 0 && (!Xneg || !idx_neg || ld_neg < D)) return OTF_ERR_INVALID_ARG;
+    if (D % 4 != 0 || n_pos + n_neg > 4096) return OTF_ERR_UNSUPPORTED;
+    if (!aligned16(w) || (n_pos > 0 && (!aligned16(Xpos) || ld_pos % 4 != 0)) ||
+        (n_neg > 0 && (!aligned16(Xneg) || ld_neg % 4 != 0)))
+        return OTF_ERR_INVALID_ARG;
+    if (!ws || ws_bytes < otf_sgd_workspace_bytes(n_pos + n_neg) || (reinterpret_cast<uintptr_t>(ws) & 15u))
+        return OTF_ERR_WORKSPACE;
+    return hip_status(launch_sgd_step(w, b, D, Xpos, ld_pos, idx_pos, n_pos, Xneg, ld_neg, idx_neg, n_neg, lambda, t,
+                                      update_bias, reinterpret_cast<float *>(ws),
+                                      reinterpret_cast<hipStream_t>(stream)));
+}
+
+int otf_profile_begin(int32_t max_records) {
+    if (g_prof.on || max_records < 1 || max_records > 65536) return OTF_ERR_INVALID_ARG;
+    g_prof.start.assign(max_records, nullptr);
+    g_prof.stop.assign(max_records, nullptr);
+    for (int i = 0; i < max_records; ++i) {
+        if (hipEventCreate(&g_prof.start[i]) != hipSuccess || hipEventCreate(&g_prof.stop[i]) != hipSuccess) {
+            for (int j = 0; j <= i; ++j) {
+                if (g_prof.start[j]) (void)hipEventDestroy(g_prof.start[j]);
+                if (g_prof.stop[j]) (void)hipEventDestroy(g_prof.stop[j]);
+            }
+            g_prof.start.clear();
+            g_prof.stop.clear();
+            return hip_status(hipErrorOutOfMemory);
+        }
+    }
+    g_prof.used = 0;
+    g_prof.on = true;
+    return OTF_OK;
+}
+
+int otf_profile_end(double *scan_ms_total, int32_t *n_records) {
+    if (!g_prof.on || !scan_ms_total || !n_records) return OTF_ERR_INVALID_ARG;
+    double total = 0.0;
+    int rc = OTF_OK;
+    for (int i = 0; i < g_prof.used; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]) != hipSuccess)
+            rc = OTF_ERR_HIP;
+        total += ms;
+    }
+    for (size_t i = 0; i < g_prof.start.size(); ++i) {
+        (void)hipEventDestroy(g_prof.start[i]);
+        (void)hipEventDestroy(g_prof.stop[i]);
+    }
+    *scan_ms_total = total;
+    *n_records = g_prof.used;
+    g_prof.start.clear();
+    g_prof.stop.clear();
+    g_prof.used = 0;
+    g_prof.on = false;
+    if (rc != OTF_OK) (void)hipGetLastError();
+    return rc;
+}
+
+}  // extern "C"

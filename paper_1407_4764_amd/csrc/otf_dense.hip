@@ -1,0 +1,298 @@
+// Dense scan, one classifier: s_i = b + <w, x_i> for every stored row (paper Sec. 4, "Ranking":
+// every pre-computed dataset feature is scored with the current linear model; Sec. 3.2: the
+// predictor is <w, phi(I)>).  0.5 flop per byte: the kernel is a pure HBM stream.
+//
+// Layout: a row is read by `LPR` adjacent lanes, 16 bytes per lane per load, so every wave
+// load covers whole 1 KiB-contiguous pieces of the store; w sits in registers (each lane keeps
+// the columns it reads).  Rows are dealt to waves round-robin and several rows are in flight
+// per wave.  Each finished score is written once and counted into the block's pass-1
+// histogram of the top-k selection, so ranking needs no further pass over the store.
+#include <hip/hip_fp16.h>
+
+#include <algorithm>
+
+#include "otf_internal.h"
+
+namespace otf {
+
+struct alignas(16) Chunk16 {
+    uint32_t u[4];
+};
+
+__device__ __forceinline__ Chunk16 load_stream16(const void *p) {
+    Chunk16 c;
+    const uint32_t *q = reinterpret_cast<const uint32_t *>(p);
+    // streaming data is read exactly once: non-temporal so that it does not evict the tables
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    u4 v = __builtin_nontemporal_load(reinterpret_cast<const u4 *>(q));
+    c.u[0] = v.x; c.u[1] = v.y; c.u[2] = v.z; c.u[3] = v.w;
+    return c;
+}
+
+template <bool HALF>
+struct Elem;
+template <>
+struct Elem<false> {
+    static constexpr int kPer16 = 4;
+    __device__ static __forceinline__ void unpack(const Chunk16 &c, float *f) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) f[j] = __uint_as_float(c.u[j]);
+    }
+};
+template <>
+struct Elem<true> {
+    static constexpr int kPer16 = 8;
+    __device__ static __forceinline__ void unpack(const Chunk16 &c, float *f) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            __half2 h = *reinterpret_cast<const __half2 *>(&c.u[j]);
+            float2 t = __half22float2(h);
+            f[2 * j] = t.x;
+            f[2 * j + 1] = t.y;
+        }
+    }
+};
+
+__device__ __forceinline__ float load_w(const void *w, int w_is_half, int d) {
+    return w_is_half ? __half2float(reinterpret_cast<const __half *>(w)[d]) : reinterpret_cast<const float *>(w)[d];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Wide rows: one wave per row, V 16-byte chunks per lane (D <= 64 * V * elems-per-chunk).
+template <bool XHALF, int V>
+__global__ __launch_bounds__(256) void dense_wide_kernel(const uint8_t *__restrict__ X, long long N, int D,
+                                                         long long row_bytes, const void *__restrict__ w,
+                                                         int w_is_half, const float *__restrict__ bias_ptr, int bias_index,
+        float *__restrict__ scores,
+                                                         SelState *st, uint32_t *hist1, int k) {
+    constexpr int E = Elem<XHALF>::kPer16;
+    __shared__ uint32_t lhist[kBins1];
+    __shared__ uint32_t s_flag;
+    for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
+    __syncthreads();
+
+    const float bias = bias_ptr ? bias_ptr[bias_index] : 0.f;
+    const int lane = threadIdx.x & 63;
+    float wr[V][E];
+    bool live[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        const int col = (j * 64 + lane) * E;
+        live[j] = col < D;
+#pragma unroll
+        for (int e = 0; e < E; ++e) wr[j][e] = live[j] ? load_w(w, w_is_half, col + e) : 0.f;
+    }
+    const long long waves_total = (long long)gridDim.x * (blockDim.x >> 6);
+    const long long wave_id = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const size_t lane_off = (size_t)lane * 16;
+
+    for (long long r0 = wave_id; r0 < N; r0 += 2 * waves_total) {
+        const long long r1 = r0 + waves_total;
+        const bool has1 = r1 < N;
+        const uint8_t *p0 = X + (size_t)r0 * row_bytes + lane_off;
+        const uint8_t *p1 = X + (size_t)(has1 ? r1 : r0) * row_bytes + lane_off;
+        Chunk16 c0[V], c1[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            if (live[j]) c0[j] = load_stream16(p0 + (size_t)j * 1024);
+        }
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            if (live[j]) c1[j] = load_stream16(p1 + (size_t)j * 1024);
+        }
+        float a0 = 0.f, a1 = 0.f;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            if (live[j]) {
+                float f0[E], f1[E];
+                Elem<XHALF>::unpack(c0[j], f0);
+                Elem<XHALF>::unpack(c1[j], f1);
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    a0 = fmaf(f0[e], wr[j][e], a0);
+                    a1 = fmaf(f1[e], wr[j][e], a1);
+                }
+            }
+        }
+        a0 = wave_sum(a0) + bias;
+        a1 = wave_sum(a1) + bias;
+        if (lane == 0) {
+            scores[r0] = a0;
+            atomicAdd(&lhist[float_to_key(a0) >> 20], 1u);
+            if (has1) {
+                scores[r1] = a1;
+                atomicAdd(&lhist[float_to_key(a1) >> 20], 1u);
+            }
+        }
+    }
+    finish_pass1(lhist, hist1, st, (uint32_t)k, gridDim.x, &s_flag);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Narrow rows: LPR = 1..32 lanes per row (a power of two), one 16-byte chunk per lane, so one
+// wave load covers 64/LPR consecutive rows; U loads in flight per wave.
+template <bool XHALF, int LPR>
+__global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__restrict__ X, long long N, int D,
+                                                           long long row_bytes, const void *__restrict__ w,
+                                                           int w_is_half, const float *__restrict__ bias_ptr, int bias_index,
+        float *__restrict__ scores,
+                                                           SelState *st, uint32_t *hist1, int k) {
+    constexpr int E = Elem<XHALF>::kPer16;
+    constexpr int RPW = 64 / LPR;   // rows per wave load
+    constexpr int U = 4;
+    __shared__ uint32_t lhist[kBins1];
+    __shared__ uint32_t s_flag;
+    for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
+    __syncthreads();
+
+    const float bias = bias_ptr ? bias_ptr[bias_index] : 0.f;
+    const int lane = threadIdx.x & 63;
+    const int sub = lane % LPR, rr = lane / LPR;
+    const int col = sub * E;
+    const bool live = col < D;
+    float wr[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) wr[e] = live ? load_w(w, w_is_half, col + e) : 0.f;
+
+    const long long waves_total = (long long)gridDim.x * (blockDim.x >> 6);
+    const long long wave_id = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const long long rows_per_iter = (long long)RPW * U;
+
+    for (long long base = wave_id * rows_per_iter; base < N; base += waves_total * rows_per_iter) {
+        Chunk16 c[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const long long row = base + (long long)u * RPW + rr;
+            ok[u] = live && row < N;
+            if (ok[u]) c[u] = load_stream16(X + (size_t)row * row_bytes + (size_t)sub * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float acc = 0.f;
+            if (ok[u]) {
+                float f[E];
+                Elem<XHALF>::unpack(c[u], f);
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc = fmaf(f[e], wr[e], acc);
+            }
+#pragma unroll
+            for (int o = LPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+            const long long row = base + (long long)u * RPW + rr;
+            if (sub == 0 && row < N) {
+                acc += bias;
+                scores[row] = acc;
+                atomicAdd(&lhist[float_to_key(acc) >> 20], 1u);
+            }
+        }
+    }
+    finish_pass1(lhist, hist1, st, (uint32_t)k, gridDim.x, &s_flag);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Very wide rows (D beyond what fits the register copy of w): w in shared memory as fp32,
+// one wave per row, 64 * E columns per step.
+template <bool XHALF>
+__global__ __launch_bounds__(256) void dense_huge_kernel(const uint8_t *__restrict__ X, long long N, int D,
+                                                         long long row_bytes, const void *__restrict__ w,
+                                                         int w_is_half, const float *__restrict__ bias_ptr, int bias_index,
+        float *__restrict__ scores,
+                                                         SelState *st, uint32_t *hist1, int k) {
+    constexpr int E = Elem<XHALF>::kPer16;
+    extern __shared__ float w_lds[];   // D floats
+    __shared__ uint32_t lhist[kBins1];
+    __shared__ uint32_t s_flag;
+    for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
+    for (int d = threadIdx.x; d < D; d += blockDim.x) w_lds[d] = load_w(w, w_is_half, d);
+    __syncthreads();
+    const float bias = bias_ptr ? bias_ptr[bias_index] : 0.f;
+    const int lane = threadIdx.x & 63;
+    const long long waves_total = (long long)gridDim.x * (blockDim.x >> 6);
+    const long long wave_id = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int steps = (D + 64 * E - 1) / (64 * E);
+    for (long long r = wave_id; r < N; r += waves_total) {
+        const uint8_t *p = X + (size_t)r * row_bytes + (size_t)lane * 16;
+        float acc = 0.f;
+        for (int j0 = 0; j0 < steps; j0 += 4) {
+            Chunk16 c[4];
+            bool ok[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int col = ((j0 + u) * 64 + lane) * E;
+                ok[u] = (j0 + u) < steps && col < D;
+                if (ok[u]) c[u] = load_stream16(p + (size_t)(j0 + u) * 1024);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (ok[u]) {
+                    const int col = ((j0 + u) * 64 + lane) * E;
+                    float f[E];
+                    Elem<XHALF>::unpack(c[u], f);
+#pragma unroll
+                    for (int e = 0; e < E; ++e) acc = fmaf(f[e], w_lds[col + e], acc);
+                }
+            }
+        }
+        acc = wave_sum(acc) + bias;
+        if (lane == 0) {
+            scores[r] = acc;
+            atomicAdd(&lhist[float_to_key(acc) >> 20], 1u);
+        }
+    }
+    finish_pass1(lhist, hist1, st, (uint32_t)k, gridDim.x, &s_flag);
+}
+
+template <bool XHALF>
+static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t row_bytes, const void *w,
+                                     int w_is_half, const float *bias_ptr, int bias_index, float *scores,
+                                     SelState *st, uint32_t *hist1, int k, hipStream_t s) {
+    constexpr int E = Elem<XHALF>::kPer16;
+    const int chunks = (D + E - 1) / E;              // 16-byte chunks per row
+    const int cus = device_cu_count();
+    int grid;
+#define OTF_ARGS X, (long long)N, D, (long long)row_bytes, w, w_is_half, bias_ptr, bias_index, scores, st, hist1, k
+    if (chunks <= 32) {
+        int lpr = 1;
+        while (lpr < chunks) lpr <<= 1;
+        const int64_t rows_per_wave_iter = (64 / lpr) * 4;
+        int64_t waves = (N + rows_per_wave_iter - 1) / rows_per_wave_iter;
+        grid = (int)std::min<int64_t>((waves + 3) / 4, (int64_t)cus * 8);
+        if (grid < 1) grid = 1;
+        switch (lpr) {
+            case 1: dense_narrow_kernel<XHALF, 1><<<grid, 256, 0, s>>>(OTF_ARGS); break;
+            case 2: dense_narrow_kernel<XHALF, 2><<<grid, 256, 0, s>>>(OTF_ARGS); break;
+            case 4: dense_narrow_kernel<XHALF, 4><<<grid, 256, 0, s>>>(OTF_ARGS); break;
+            case 8: dense_narrow_kernel<XHALF, 8><<<grid, 256, 0, s>>>(OTF_ARGS); break;
+            case 16: dense_narrow_kernel<XHALF, 16><<<grid, 256, 0, s>>>(OTF_ARGS); break;
+            default: dense_narrow_kernel<XHALF, 32><<<grid, 256, 0, s>>>(OTF_ARGS); break;
+        }
+    } else {
+        grid = (int)std::min<int64_t>((N + 3) / 4, (int64_t)cus * 8);
+        if (grid < 1) grid = 1;
+        const int V = (chunks + 63) / 64;
+        if (V <= 1) dense_wide_kernel<XHALF, 1><<<grid, 256, 0, s>>>(OTF_ARGS);
+        else if (V <= 2) dense_wide_kernel<XHALF, 2><<<grid, 256, 0, s>>>(OTF_ARGS);
+        else if (V <= 4) dense_wide_kernel<XHALF, 4><<<grid, 256, 0, s>>>(OTF_ARGS);
+        else if (V <= 8) dense_wide_kernel<XHALF, 8><<<grid, 256, 0, s>>>(OTF_ARGS);
+        else {
+            if (D > kDenseMaxD) return hipErrorInvalidValue;
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dense_huge_kernel<XHALF>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kDenseMaxD * 4);
+            if (e != hipSuccess) return e;
+            dense_huge_kernel<XHALF><<<grid, 256, (size_t)D * 4, s>>>(OTF_ARGS);
+        }
+    }
+#undef OTF_ARGS
+    return hipGetLastError();
+}
+
+hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int64_t ldx, const void *w,
+                             int w_is_half, const float *bias_ptr, int bias_index, float *scores, SelState *st,
+                             uint32_t *hist1, int k, hipStream_t s) {
+    const uint8_t *Xb = reinterpret_cast<const uint8_t *>(X);
+    if (x_is_half)
+        return launch_dense_typed<true>(Xb, N, D, ldx * 2, w, w_is_half, bias_ptr, bias_index, scores, st, hist1, k, s);
+    return launch_dense_typed<false>(Xb, N, D, ldx * 4, w, w_is_half, bias_ptr, bias_index, scores, st, hist1, k, s);
+}
+
+}  // namespace otf

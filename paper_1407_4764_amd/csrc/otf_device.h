@@ -1,0 +1,160 @@
+// Device-side helpers shared by the libotf kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace otf {
+
+constexpr int kWave = 64;
+constexpr int kBins1 = 4096;   // radix pass 1: key bits 31..20
+constexpr int kBins2 = 4096;   // radix pass 2: key bits 19..8
+constexpr int kBins3 = 256;    // radix pass 3: key bits 7..0
+constexpr int kCandCap = 8192; // capacity of the candidate list that the final sort takes
+constexpr int kSelBlocks = 256; // blocks per classifier in the selection passes over scores
+
+// Order-preserving map float -> uint32 (larger float <=> larger key); -0.0 maps onto +0.0
+// so that the two compare equal, as they do as numbers.
+__device__ __forceinline__ uint32_t float_to_key(float f) {
+    uint32_t u = __float_as_uint(f);
+    if (u == 0x80000000u) u = 0u;
+    return u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__device__ __forceinline__ float key_to_float(uint32_t k) {
+    uint32_t u = (k & 0x80000000u) ? (k ^ 0x80000000u) : ~k;
+    return __uint_as_float(u);
+}
+
+// Selection state of one classifier (one row of scores).  Lives in the workspace.
+struct SelState {
+    uint32_t mode;     // 0: resolved after pass 1, 1: after pass 2, 2: after pass 3 (ties split by index)
+    uint32_t b1;       // pass-1 bin of the k-th largest key
+    uint32_t need1;    // how many of the k lie inside bin b1
+    uint32_t p24;      // top 24 bits of the k-th largest key (mode >= 1)
+    uint32_t need2;    // how many of the k lie inside prefix p24
+    uint32_t T;        // the k-th largest key (mode 2)
+    uint32_t r;        // how many rows with key == T belong to the list (mode 2), lowest indices first
+    uint32_t ncand;    // entries the gather pass writes to the candidate list
+    long long tex;     // gather every key with (long long)key > tex
+    uint32_t cursor;   // append cursor of the gather pass
+    uint32_t done1, done2, done3;  // block tickets of the three histogram passes
+    uint32_t pad[2];
+};
+static_assert(sizeof(SelState) == 64, "SelState layout");
+
+__device__ __forceinline__ uint32_t ld_coherent(const uint32_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Inclusive suffix sum over the 64 lanes of a wave: lane l receives sum of lanes l..63.
+__device__ __forceinline__ uint32_t wave_suffix_sum(uint32_t v) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t t = __shfl_down(v, o, 64);
+        if (lane + o < 64) v += t;
+    }
+    return v;
+}
+
+// Copies a global histogram (produced by other blocks with atomics or fenced stores) into
+// shared memory with device-coherent loads.  All threads of the block call; ends with a barrier.
+__device__ __forceinline__ void block_load_hist(uint32_t *lds, const uint32_t *ghist, int nbins) {
+    for (int b = threadIdx.x; b < nbins; b += blockDim.x) lds[b] = ld_coherent(ghist + b);
+    __syncthreads();
+}
+
+// Called by ONE full wave (64 lanes) on a histogram in shared memory with 64*per_lane bins
+// (per_lane <= 64).  Finds the bin b with  count(bins > b) < need <= count(bins >= b)  and
+// returns it; *above receives count(bins > b) and *inbin the population of b.
+// Requires total count >= need >= 1.
+__device__ __forceinline__ uint32_t wave_find_bin(const uint32_t *hist, int per_lane, uint32_t need,
+                                                  uint32_t *above, uint32_t *inbin) {
+    const int lane = threadIdx.x & 63;
+    uint32_t mine = 0;
+    for (int j = 0; j < per_lane; ++j) mine += hist[lane * per_lane + j];
+    uint32_t suf = wave_suffix_sum(mine);                  // bins of lanes >= lane
+    // the owning lane is the highest lane whose suffix still reaches `need`
+    unsigned long long reach = __ballot(suf >= need);
+    int owner = 63 - __builtin_clzll(reach | 1ull);
+    uint32_t above_owner = __shfl(suf - mine, owner, 64);  // count in lanes > owner
+    // second level: the per_lane bins of the owner, one per lane (lanes >= per_lane hold 0)
+    uint32_t binv = (lane < per_lane) ? hist[owner * per_lane + lane] : 0u;
+    uint32_t suf2 = wave_suffix_sum(binv) + above_owner;   // count in bins >= this bin
+    unsigned long long reach2 = __ballot(lane < per_lane && suf2 >= need);
+    int lb = 63 - __builtin_clzll(reach2 | 1ull);
+    *inbin = __shfl(binv, lb, 64);
+    *above = __shfl(suf2 - binv, lb, 64);
+    return (uint32_t)(owner * per_lane + lb);
+}
+
+// End of radix pass 1, run by wave 0 of the block that finished last; hist1 is the complete
+// histogram, already copied to shared memory.
+__device__ __forceinline__ void resolve_pass1(SelState *st, const uint32_t *hist1, uint32_t k) {
+    uint32_t above, inbin;
+    uint32_t b1 = wave_find_bin(hist1, kBins1 / 64, k, &above, &inbin);
+    if ((threadIdx.x & 63) == 0) {
+        st->b1 = b1;
+        st->need1 = k - above;
+        uint32_t c1 = above + inbin;
+        if (c1 <= (uint32_t)kCandCap) {
+            st->mode = 0;
+            st->ncand = c1;
+            st->tex = ((long long)b1 << 20) - 1;
+        } else {
+            st->mode = 1;   // provisional: pass 2 decides between 1 and 2
+        }
+    }
+}
+
+// Adds a block's shared-memory histogram into the global one, then tells whether this block
+// is the last of `nblocks` to have done so (the caller then resolves the pass).  All threads
+// must call; returns the same value to all threads.
+__device__ __forceinline__ bool merge_hist_and_ticket(const uint32_t *lhist, int nbins, uint32_t *ghist,
+                                                      uint32_t *ticket_counter, uint32_t nblocks,
+                                                      uint32_t *s_flag) {
+    for (int b = threadIdx.x; b < nbins; b += blockDim.x) {
+        uint32_t c = lhist[b];
+        if (c) atomicAdd(ghist + b, c);
+    }
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = atomicAdd(ticket_counter, 1u);
+        *s_flag = (t == nblocks - 1) ? 1u : 0u;
+    }
+    __syncthreads();
+    bool last = *s_flag != 0;
+    if (last) __threadfence();
+    return last;
+}
+
+// Tail of every kernel that built a pass-1 histogram in shared memory: merge it, and let the
+// block that finishes last resolve the pass.  lhist must hold kBins1 words and is clobbered.
+__device__ __forceinline__ void finish_pass1(uint32_t *lhist, uint32_t *ghist1, SelState *st, uint32_t k,
+                                             uint32_t nblocks, uint32_t *s_flag) {
+    __syncthreads();
+    bool last = merge_hist_and_ticket(lhist, kBins1, ghist1, &st->done1, nblocks, s_flag);
+    if (last) {
+        block_load_hist(lhist, ghist1, kBins1);
+        if (threadIdx.x < 64) resolve_pass1(st, lhist, k);
+    }
+}
+
+// Rows [begin, end) of the chunk that selection block b of kSelBlocks owns; chunks are
+// contiguous, ascending in b, and a multiple of 1024 rows long (except the last).
+__device__ __forceinline__ void sel_chunk(long long N, int b, long long *begin, long long *end) {
+    long long per = (N + kSelBlocks - 1) / kSelBlocks;
+    per = (per + 1023) / 1024 * 1024;
+    long long s = per * b;
+    long long e = s + per;
+    *begin = s < N ? s : N;
+    *end = e < N ? e : N;
+}
+
+}  // namespace otf

@@ -1,0 +1,123 @@
+"""Host-side checks of the C ABI: the library loads, exports every function the header
+declares, and rejects bad arguments before anything is enqueued (so these run without a GPU:
+a rejected call makes no HIP call and dereferences no pointer)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1407_4764_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # a 256-aligned non-NULL address that must never be dereferenced
+BIG = 1 << 40
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_1407_4764_amd import build
+        build.build_library()
+    return binding.lib()
+
+
+def test_header_functions_are_exported(L):
+    header = open(os.path.join(ROOT, "include", "otf.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(otf_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_status_strings(L):
+    assert binding.status_string(0) == "OTF_OK"
+    assert binding.status_string(-1) == "OTF_ERR_INVALID_ARG"
+    assert binding.status_string(-3) == "OTF_ERR_WORKSPACE"
+    assert binding.status_string(-99) == "OTF_ERR_UNKNOWN"
+
+
+def test_workspace_query(L):
+    assert binding.workspace_bytes(0, 1, 1) == 0
+    assert binding.workspace_bytes(10, 0, 1) == 0
+    assert binding.workspace_bytes(1 << 31, 1, 1) == 0
+    a = binding.workspace_bytes(1000, 10, 1)
+    b = binding.workspace_bytes(1000000, 10, 1)
+    c = binding.workspace_bytes(1000000, 10, 4)
+    assert 0 < a < b < c and a % 256 == 0
+    assert b - a >= (1000000 - 1000) * 4 - 4096      # room for one score per row
+    assert L.otf_sgd_workspace_bytes(0) == 0 and L.otf_sgd_workspace_bytes(256) > 0
+
+
+def _topk(L, scores=FAKE, N=100, ld=100, Q=1, k=10, os_=FAKE, oi=FAKE, ws=FAKE, wsb=BIG):
+    return L.otf_topk(scores, N, ld, Q, k, os_, oi, ws, wsb, None)
+
+
+def test_topk_argument_errors(L):
+    assert _topk(L, scores=None) == binding.OTF_ERR_INVALID_ARG
+    assert _topk(L, N=0) == binding.OTF_ERR_INVALID_ARG
+    assert _topk(L, k=0) == binding.OTF_ERR_INVALID_ARG
+    assert _topk(L, k=101) == binding.OTF_ERR_INVALID_ARG
+    assert _topk(L, N=100000, ld=100000, k=binding.OTF_MAX_K + 1) == binding.OTF_ERR_INVALID_ARG
+    assert _topk(L, ld=99) == binding.OTF_ERR_INVALID_ARG
+    assert _topk(L, os_=None) == binding.OTF_ERR_INVALID_ARG
+    assert _topk(L, N=1 << 31, ld=1 << 31) == binding.OTF_ERR_UNSUPPORTED
+    assert _topk(L, ws=None) == binding.OTF_ERR_WORKSPACE
+    assert _topk(L, ws=FAKE + 8) == binding.OTF_ERR_WORKSPACE
+    assert _topk(L, wsb=binding.workspace_bytes(100, 10, 1) - 1) == binding.OTF_ERR_WORKSPACE
+
+
+def _dense(L, X=FAKE, xdt=0, N=1000, D=128, ldx=128, W=FAKE, wdt=0, Q=1, k=10, ws=FAKE, wsb=BIG):
+    return L.otf_rank_dense(X, xdt, N, D, ldx, W, wdt, Q, None, k, FAKE, FAKE, None, ws, wsb, None)
+
+
+def test_rank_dense_argument_errors(L):
+    assert _dense(L, X=None) == binding.OTF_ERR_INVALID_ARG
+    assert _dense(L, W=None) == binding.OTF_ERR_INVALID_ARG
+    assert _dense(L, D=0) == binding.OTF_ERR_INVALID_ARG
+    assert _dense(L, ldx=64) == binding.OTF_ERR_INVALID_ARG
+    assert _dense(L, X=FAKE + 4) == binding.OTF_ERR_INVALID_ARG            # misaligned base
+    assert _dense(L, D=126, ldx=126) == binding.OTF_ERR_INVALID_ARG        # row stride not 16-byte
+    assert _dense(L, D=6, ldx=8) == binding.OTF_ERR_UNSUPPORTED            # D not a multiple of 4
+    assert _dense(L, xdt=7) == binding.OTF_ERR_INVALID_ARG
+    assert _dense(L, xdt=0, wdt=1) == binding.OTF_ERR_UNSUPPORTED          # fp32 store, fp16 model
+    assert _dense(L, D=32768, ldx=32768) == binding.OTF_ERR_UNSUPPORTED
+    assert _dense(L, wsb=1024) == binding.OTF_ERR_WORKSPACE
+    assert _dense(L, k=2000) == binding.OTF_ERR_INVALID_ARG                # k > N
+
+
+def test_pq_and_binary_argument_errors(L):
+    def pq(codes=FAKE, N=1000, M=128, K=256, lut=FAKE, k=10, wsb=BIG):
+        return L.otf_rank_pq(codes, N, M, K, lut, 0.0, k, FAKE, FAKE, None, FAKE, wsb, None)
+    assert pq(codes=None) == binding.OTF_ERR_INVALID_ARG
+    assert pq(K=128) == binding.OTF_ERR_UNSUPPORTED
+    assert pq(M=48) == binding.OTF_ERR_UNSUPPORTED
+    assert pq(M=2048) == binding.OTF_ERR_UNSUPPORTED
+    assert pq(wsb=0) == binding.OTF_ERR_WORKSPACE
+    assert pq(codes=FAKE + 1) == binding.OTF_ERR_INVALID_ARG
+
+    def binr(bits=FAKE, N=1000, D=2048, w=FAKE, k=10, wsb=BIG):
+        return L.otf_rank_binary(bits, N, D, w, 0.0, k, FAKE, FAKE, None, FAKE, wsb, None)
+    assert binr(bits=None) == binding.OTF_ERR_INVALID_ARG
+    assert binr(D=100) == binding.OTF_ERR_UNSUPPORTED
+    assert binr(D=768) == binding.OTF_ERR_UNSUPPORTED
+    assert binr(k=0) == binding.OTF_ERR_INVALID_ARG
+    assert L.otf_pq_build_lut(None, 1, 1, 1, FAKE, FAKE, None) == binding.OTF_ERR_INVALID_ARG
+    assert L.otf_pq_build_lut(FAKE, 0, 1, 1, FAKE, FAKE, None) == binding.OTF_ERR_INVALID_ARG
+
+
+def test_sgd_argument_errors(L):
+    def sgd(w=FAKE, D=128, Xp=FAKE, ldp=128, ip=FAKE, npos=4, Xn=FAKE, ldn=128, ineg=FAKE, nneg=4, lam=1.0, t=1,
+            ws=FAKE, wsb=BIG):
+        return L.otf_svm_sgd_step(w, None, D, Xp, ldp, ip, npos, Xn, ldn, ineg, nneg, lam, t, 0, ws, wsb, None)
+    assert sgd(w=None) == binding.OTF_ERR_INVALID_ARG
+    assert sgd(t=0) == binding.OTF_ERR_INVALID_ARG
+    assert sgd(lam=0.0) == binding.OTF_ERR_INVALID_ARG
+    assert sgd(npos=0, nneg=0) == binding.OTF_ERR_INVALID_ARG
+    assert sgd(Xp=None) == binding.OTF_ERR_INVALID_ARG
+    assert sgd(ldp=64) == binding.OTF_ERR_INVALID_ARG
+    assert sgd(D=126, ldp=128, ldn=128) == binding.OTF_ERR_UNSUPPORTED
+    assert sgd(npos=4000, nneg=4000) == binding.OTF_ERR_UNSUPPORTED
+    assert sgd(ws=None) == binding.OTF_ERR_WORKSPACE
+    assert sgd(wsb=16) == binding.OTF_ERR_WORKSPACE

@@ -1,0 +1,313 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by element, on
+seeded synthetic inputs that span several tiles and ragged tails, plus the edge cases of the
+top-k selection.  Tolerances (the benchmark spec): relative 1e-4 for fp32 inputs, 2e-3 for fp16 inputs,
+taken against max(|score|, spread of the scores); indices and bit work are exact."""
+import numpy as np
+import pytest
+import torch
+
+from paper_1407_4764_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+RTOL32 = 1e-4
+RTOL16 = 2e-3
+SEED = synth.BASE_SEED
+DEV = "cuda"
+
+
+def _sync():
+    torch.cuda.synchronize()
+
+
+def assert_scores_close(oracle, got, ref, rtol, what):
+    got = np.asarray(got, dtype=np.float64)
+    tol = oracle.score_tolerance(ref, rtol)
+    err = np.abs(got - ref)
+    bad = np.nonzero(err > tol)[0]
+    assert bad.size == 0, "%s: %d scores off, worst row %d got %r ref %r" % (
+        what, bad.size, bad[0], got[bad[0]], ref[bad[0]])
+
+
+def assert_topk_ok(oracle, ref_scores, k, idx, val, rtol, what):
+    ok, msg = oracle.topk_parity_ok(ref_scores, k, idx, val, rtol)
+    assert ok, "%s: %s" % (what, msg)
+
+
+def assert_same_as_sorting_own_scores(oracle, gpu_all_scores, k, idx, val, what):
+    """Selection is index work: on the fp32 scores the GPU itself produced, the list must be
+    exactly the first k of the full sort (score descending, row ascending)."""
+    oidx, oval = oracle.topk(np.asarray(gpu_all_scores, dtype=np.float64), k)
+    np.testing.assert_array_equal(np.asarray(idx, dtype=np.int64), oidx, err_msg=what)
+    np.testing.assert_array_equal(np.asarray(val, dtype=np.float64), oval, err_msg=what)
+
+
+# ---------------------------------------------------------------------------------- dense
+DENSE_CASES = [
+    # N, D, dtype_x, dtype_w, k, ldx_extra
+    (10000, 128, torch.float32, torch.float32, 100, 0),     # the tiny reference configuration
+    (3001, 2048, torch.float32, torch.float32, 50, 0),      # one wave per row, 8 chunks per lane
+    (777, 96, torch.float32, torch.float32, 777, 0),        # narrow rows with dead lanes, k = N
+    (1500, 260, torch.float32, torch.float32, 10, 4),       # partial last chunk, padded row stride
+    (300, 4096, torch.float32, torch.float32, 7, 0),        # w in shared memory
+    (1, 128, torch.float32, torch.float32, 1, 0),
+    (2, 4, torch.float32, torch.float32, 2, 0),
+    (5003, 2048, torch.float16, torch.float32, 100, 0),
+    (5003, 2048, torch.float16, torch.float16, 100, 0),
+    (4100, 128, torch.float16, torch.float32, 64, 8),
+]
+
+
+@pytest.mark.parametrize("N,D,dx,dw,k,pad", DENSE_CASES)
+def test_rank_dense_single_classifier(oracle, N, D, dx, dw, k, pad):
+    X = synth.dense_features(N, D, SEED + 1, dtype=dx)
+    w = synth.normal_vector(D, 1.0, SEED + 11, dtype=dw)
+    b = synth.normal_vector(1, 1.0, SEED + 12)
+    ref = oracle.dense_scores(X.numpy(), w.numpy(), b.numpy())[0]
+    Xd = torch.zeros((N, D + pad), dtype=dx, device=DEV)
+    Xd[:, :D] = X.to(DEV)
+    Xv = Xd[:, :D]
+    ws = binding.make_workspace(N, k)
+    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
+    val, idx = binding.rank_dense(Xv, w.to(DEV), b.to(DEV), k, ws, all_scores=all_scores)
+    _sync()
+    rtol = RTOL32 if dx == torch.float32 else RTOL16
+    got = all_scores.cpu().numpy()
+    assert_scores_close(oracle, got, ref, rtol, "dense all_scores")
+    assert_topk_ok(oracle, ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), rtol, "dense top-k")
+    assert_same_as_sorting_own_scores(oracle, got, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), "dense top-k")
+    # without the all_scores output (scores kept in the workspace) the lists are identical
+    val2, idx2 = binding.rank_dense(Xv, w.to(DEV), b.to(DEV), k, ws)
+    _sync()
+    assert torch.equal(idx, idx2) and torch.equal(val, val2)
+
+
+def test_rank_dense_several_classifiers_one_by_one(oracle):
+    N, D, Q, k = 2000, 128, 3, 20
+    X = synth.dense_features(N, D, SEED + 2)
+    W = synth.normal_matrix(Q, D, 1.0, SEED + 13)
+    b = synth.normal_vector(Q, 1.0, SEED + 14)
+    ref = oracle.dense_scores(X.numpy(), W.numpy(), b.numpy())
+    ws = binding.make_workspace(N, k, Q)
+    all_scores = torch.empty((Q, N), dtype=torch.float32, device=DEV)
+    val, idx = binding.rank_dense(X.to(DEV), W.to(DEV), b.to(DEV), k, ws, all_scores=all_scores)
+    _sync()
+    for q in range(Q):
+        assert_scores_close(oracle, all_scores[q].cpu().numpy(), ref[q], RTOL32, "dense Q=3 q=%d" % q)
+        assert_topk_ok(oracle, ref[q], k, idx[q].cpu().numpy(), val[q].cpu().numpy(), RTOL32, "dense Q=3 q=%d" % q)
+
+
+@pytest.mark.parametrize("N,D,Q,k,with_all", [(1000, 256, 64, 50, True), (4133, 2048, 64, 100, False),
+                                                (515, 128, 32, 5, True), (900, 384, 96, 9, True)])
+def test_rank_dense_matrix_core_path(oracle, N, D, Q, k, with_all):
+    X = synth.dense_features(N, D, SEED + 5, dtype=torch.float16)
+    W = synth.normal_matrix(Q, D, 0.05, SEED + 15, dtype=torch.float16)
+    b = synth.normal_vector(Q, 0.01, SEED + 16)
+    ref = oracle.dense_scores(X.numpy(), W.numpy(), b.numpy())
+    ws = binding.make_workspace(N, k, Q)
+    all_scores = torch.empty((Q, N), dtype=torch.float32, device=DEV) if with_all else None
+    val, idx = binding.rank_dense(X.to(DEV), W.to(DEV), b.to(DEV), k, ws, all_scores=all_scores)
+    _sync()
+    for q in range(Q):
+        if with_all:
+            assert_scores_close(oracle, all_scores[q].cpu().numpy(), ref[q], RTOL16, "mfma q=%d" % q)
+        assert_topk_ok(oracle, ref[q], k, idx[q].cpu().numpy(), val[q].cpu().numpy(), RTOL16, "mfma q=%d" % q)
+
+
+# ---------------------------------------------------------------------------------- PQ
+@pytest.mark.parametrize("N,M,dsub,k", [(5000, 128, 16, 100), (40003, 128, 16, 1000), (1, 128, 4, 1),
+                                         (1025, 16, 8, 33), (3000, 32, 4, 10), (2047, 64, 4, 64),
+                                         (2500, 256, 8, 25), (1300, 512, 4, 13)])
+def test_pq_lut_and_rank(oracle, N, M, dsub, k):
+    K = 256
+    cb = synth.pq_codebooks(M, K, dsub, SEED + 3)
+    codes = synth.pq_codes(N, M, K, SEED + 4)
+    w = synth.normal_vector(M * dsub, 1.0, SEED + 17)
+    bias = 0.375
+    lut = binding.pq_build_lut(cb.to(DEV), w.to(DEV))
+    _sync()
+    lut_ref = oracle.pq_lut(cb.numpy(), w.numpy())
+    np.testing.assert_allclose(lut.cpu().numpy(), lut_ref, rtol=0, atol=1e-5 * np.abs(lut_ref).max())
+    ref = oracle.pq_scores_reconstruct(codes.numpy(), cb.numpy(), w.numpy(), bias)
+    ws = binding.make_workspace(N, k)
+    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
+    val, idx = binding.rank_pq(codes.to(DEV), lut, bias, k, ws, all_scores=all_scores)
+    _sync()
+    got = all_scores.cpu().numpy()
+    assert_scores_close(oracle, got, ref, RTOL32, "pq M=%d" % M)
+    assert_topk_ok(oracle, ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), RTOL32, "pq M=%d" % M)
+    assert_same_as_sorting_own_scores(oracle, got, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), "pq M=%d" % M)
+
+
+def test_pq_gather_is_exact_for_integer_tables(oracle):
+    """With an integer-valued table every fp32 partial sum is exact, so any slip in the byte
+    extraction or the table layout shows as a non-zero difference."""
+    N, M, K = 4099, 128, 256
+    codes = synth.pq_codes(N, M, K, SEED + 6)
+    g = torch.Generator().manual_seed(SEED + 7)
+    lut = torch.randint(-1000, 1000, (M, K), generator=g).to(torch.float32)
+    ref = oracle.pq_scores_lut(codes.numpy(), lut.numpy().astype(np.float64), 5.0)
+    ws = binding.make_workspace(N, 10)
+    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
+    binding.rank_pq(codes.to(DEV), lut.to(DEV), 5.0, 10, ws, all_scores=all_scores)
+    _sync()
+    np.testing.assert_array_equal(all_scores.cpu().numpy().astype(np.float64), ref)
+
+
+# ---------------------------------------------------------------------------------- binary
+@pytest.mark.parametrize("N,D,k", [(3000, 2048, 100), (20011, 2048, 1000), (1, 2048, 1), (5000, 1024, 50),
+                                    (4097, 128, 17), (999, 256, 9), (1234, 512, 12), (700, 4096, 7)])
+def test_rank_binary(oracle, N, D, k):
+    bits = synth.binary_bits_from_features(N, D, SEED + 8)
+    w = synth.normal_vector(D, 1.0, SEED + 18)
+    bias = -0.5
+    ref = oracle.binary_scores(synth.as_uint32(bits.numpy()), D, w.numpy(), bias)
+    ws = binding.make_workspace(N, k)
+    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
+    val, idx = binding.rank_binary(bits.to(DEV), D, w.to(DEV), bias, k, ws, all_scores=all_scores)
+    _sync()
+    got = all_scores.cpu().numpy()
+    assert_scores_close(oracle, got, ref, RTOL32, "binary D=%d" % D)
+    assert_topk_ok(oracle, ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), RTOL32, "binary D=%d" % D)
+    assert_same_as_sorting_own_scores(oracle, got, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), "binary")
+
+
+def test_binary_bit_unpack_is_exact(oracle):
+    """Integer weights make every partial sum exact: the scores must equal the oracle's bit for
+    bit, for random rows and for every single-bit row."""
+    D = 2048
+    g = torch.Generator().manual_seed(SEED + 9)
+    w = torch.randint(-512, 512, (D,), generator=g).to(torch.float32)
+    rand = synth.binary_bits_random(1000, D // 32, SEED + 10)
+    single = torch.zeros((D, D // 32), dtype=torch.int64)
+    d = torch.arange(D)
+    single[d, d // 32] = 1 << (d % 32)
+    single = torch.where(single >= 2 ** 31, single - 2 ** 32, single).to(torch.int32)
+    bits = torch.cat([rand, single, torch.zeros((1, D // 32), dtype=torch.int32),
+                      torch.full((1, D // 32), -1, dtype=torch.int32)])
+    N = bits.shape[0]
+    ref = oracle.binary_scores(synth.as_uint32(bits.numpy()), D, w.numpy(), 3.0)
+    ws = binding.make_workspace(N, 10)
+    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
+    binding.rank_binary(bits.to(DEV), D, w.to(DEV), 3.0, 10, ws, all_scores=all_scores)
+    _sync()
+    np.testing.assert_array_equal(all_scores.cpu().numpy().astype(np.float64), ref)
+
+
+# ---------------------------------------------------------------------------------- top-k
+def _run_topk(scores_np, k, ld_extra=0):
+    S = np.atleast_2d(scores_np).astype(np.float32)
+    Q, N = S.shape
+    Sd = torch.zeros((Q, N + ld_extra), dtype=torch.float32, device=DEV)
+    Sd[:, :N] = torch.from_numpy(S).to(DEV)
+    ws = binding.make_workspace(N, k, Q)
+    val, idx = binding.topk(Sd[:, :N], k, ws)
+    _sync()
+    return val.cpu().numpy(), idx.cpu().numpy()
+
+
+def _check_topk_exact(oracle, scores_np, k, ld_extra=0):
+    S = np.atleast_2d(scores_np).astype(np.float32)
+    val, idx = _run_topk(S, k, ld_extra)
+    for q in range(S.shape[0]):
+        oidx, oval = oracle.topk(S[q].astype(np.float64), k)
+        np.testing.assert_array_equal(idx[q].astype(np.int64), oidx)
+        np.testing.assert_array_equal(val[q].astype(np.float64), oval)
+
+
+def test_topk_random_scores(oracle):
+    rng = np.random.default_rng(SEED)
+    _check_topk_exact(oracle, rng.standard_normal(100003), 1000)
+    _check_topk_exact(oracle, rng.standard_normal((3, 50001)), 257, ld_extra=7)
+    _check_topk_exact(oracle, rng.standard_normal(10000), 100)
+    _check_topk_exact(oracle, rng.standard_normal(9000), binding.OTF_MAX_K)
+    _check_topk_exact(oracle, rng.standard_normal(5), 5)
+    _check_topk_exact(oracle, np.array([2.5]), 1)
+    _check_topk_exact(oracle, -np.abs(rng.standard_normal(70000)) - 3.0, 300)       # all negative
+
+
+def test_topk_ties_are_broken_by_row_index(oracle):
+    rng = np.random.default_rng(SEED + 1)
+    _check_topk_exact(oracle, np.full(50000, 1.0), 100)                       # every score equal
+    _check_topk_exact(oracle, np.round(rng.standard_normal(200000), 1), 1000)  # heavy duplicates
+    s = rng.standard_normal(300000)
+    s[rng.integers(0, 300000, 20000)] = 0.0
+    s[rng.integers(0, 300000, 20000)] = -0.0                                   # +0 and -0 are one value
+    val, idx = _run_topk(np.minimum(s, 0.0), 5000)
+    oidx, oval = oracle.topk(np.minimum(s, 0.0).astype(np.float32).astype(np.float64), 5000)
+    np.testing.assert_array_equal(idx[0].astype(np.int64), oidx)
+    assert np.all(val[0][:10] == 0.0)
+
+
+def test_topk_clustered_scores_need_the_finer_passes(oracle):
+    rng = np.random.default_rng(SEED + 2)
+    # all scores inside one coarse bin (same sign, exponent and top mantissa bits)
+    _check_topk_exact(oracle, 1000.0 + rng.random(250000), 1000)
+    # ... and so tightly packed that thousands share the top 24 key bits
+    _check_topk_exact(oracle, 1000.0 + np.round(rng.random(250000) * 8) / 1024.0, 1000)
+
+
+def test_ranking_is_reproducible(oracle):
+    N, D, k = 20000, 2048, 500
+    X = synth.dense_features(N, D, SEED + 20).to(DEV)
+    w = synth.normal_vector(D, 0.05, SEED + 21).to(DEV)
+    ws = binding.make_workspace(N, k)
+    a = binding.rank_dense(X, w, None, k, ws)
+    _sync()
+    a = (a[0].clone(), a[1].clone())
+    b = binding.rank_dense(X, w, None, k, ws)
+    _sync()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+# ---------------------------------------------------------------------------------- Pegasos step
+@pytest.mark.parametrize("D,n_pos_pool,n_neg_pool,batch,lam,update_bias", [
+    (2048, 1000, 16000, 256, 1e-4, False),      # the full-size training configuration
+    (128, 200, 1600, 32, 1.0, True),            # the paper's own batch size and regulariser
+    (260, 50, 70, 6, 0.01, True),
+])
+def test_sgd_steps_teacher_forced(oracle, D, n_pos_pool, n_neg_pool, batch, lam, update_bias):
+    Xp, Xn = synth.sgd_pools(D, n_pos_pool, n_neg_pool, SEED + 30)
+    steps = 12
+    ipos, ineg = synth.sgd_batches(n_pos_pool, n_neg_pool, batch, steps, SEED + 31)
+    Xpd, Xnd = Xp.to(DEV), Xn.to(DEV)
+    ws = binding.sgd_workspace(batch)
+    w = np.zeros(D, dtype=np.float32)
+    b = 0.0
+    for t in range(1, steps + 1):
+        w_ref, b_ref, margins = oracle.sgd_step(w, b, Xp.numpy(), ipos[t - 1], Xn.numpy(), ineg[t - 1], lam, t,
+                                                update_bias)
+        wd = torch.from_numpy(w).to(DEV)
+        bd = torch.tensor([b], dtype=torch.float32, device=DEV)
+        binding.svm_sgd_step(wd, bd, Xpd, torch.from_numpy(ipos[t - 1]).to(DEV), Xnd,
+                             torch.from_numpy(ineg[t - 1]).to(DEV), lam, t, update_bias, ws)
+        _sync()
+        got = wd.cpu().numpy().astype(np.float64)
+        # rows whose margin sits within rounding of the kink may legitimately flip sides
+        near_kink = np.abs(1.0 - margins) < 1e-5
+        scale = np.abs(w_ref).max()
+        slack = near_kink.sum() * (1.0 / (lam * t * batch)) * 1.0     # |x| = 1 per flipped row
+        assert np.abs(got - w_ref).max() <= RTOL32 * scale + slack, "step %d" % t
+        assert abs(float(bd.cpu()[0]) - b_ref) <= RTOL32 * max(1.0, abs(b_ref)) + near_kink.sum() / (lam * t * batch)
+        w = w_ref.astype(np.float32)          # teacher forcing: both sides restart from the oracle's model
+        b = float(np.float32(b_ref))
+
+
+def test_sgd_closed_forms_on_gpu(oracle):
+    D = 128
+    Xp, Xn = synth.sgd_pools(D, 20, 40, SEED + 32, n_shift_dims=5)
+    ip = torch.tensor([3, 3, 7, 0], dtype=torch.int32)
+    ineg = torch.tensor([1, 39, 2, 8], dtype=torch.int32)
+    ws = binding.sgd_workspace(8)
+    lam = 0.5
+    # w0 = 0: every row violates, w1 = (sum pos - sum neg) / (lam B)
+    w = torch.zeros(D, device=DEV)
+    binding.svm_sgd_step(w, None, Xp.to(DEV), ip.to(DEV), Xn.to(DEV), ineg.to(DEV), lam, 1, False, ws)
+    _sync()
+    ref = (Xp[ip.long()].double().sum(0) - Xn[ineg.long()].double().sum(0)) / (lam * 8)
+    np.testing.assert_allclose(w.cpu().numpy(), ref.numpy(), rtol=1e-5, atol=1e-7)
+    # no violators (huge w on non-negative features, positives only): pure shrink by (1 - 1/t)
+    w = torch.full((D,), 10.0, device=DEV)
+    binding.svm_sgd_step(w, None, Xp.to(DEV), ip.to(DEV), None, None, lam, 4, False, ws)
+    _sync()
+    np.testing.assert_allclose(w.cpu().numpy(), np.full(D, 7.5), rtol=1e-6)
