@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Throughput of the ranking hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dense|pq|binary|multiquery]
+                    [--no-others] [--no-cpu-baseline]
+
+A step is one ranking pass of the workload: score every stored row with the current model and
+return the sorted top-k (one otf_rank_* call: scan + selection).  The store is generated on the
+GPU before the clock starts.  The default workload is the full-size dense store (1,000,000 x
+2048 fp32, k = 1000) on which the headline metric is quoted; the PQ, binary and multi-classifier
+stores and the Pegasos training pass are measured the same way and reported inside the same JSON
+line under "other_workloads".
+
+The one JSON line also carries
+  roofline      achieved HBM GB/s of the scoring kernel (algorithmic bytes = every stored row read
+                once) against the 8 TB/s peak; the kernel time comes from HIP events the library
+                records around that kernel on its stream during the timed steps
+  cpu_baseline  the CPU oracle (oracle/, plain C, fp64, OpenMP over rows) timed on this host on
+                a stated sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch of the scoring kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); filled in per workload once measured, None until then.
+MEASURED_TRAFFIC_BYTES = {
+    "dense": None,
+    "pq": None,
+    "binary": None,
+    "multiquery": None,
+}
+
+WORKLOADS = {
+    "dense": dict(name="dense_1Mx2048_fp32_top1000", N=1_000_000, D=2048, k=1000, row_bytes=8192, dtype="f32"),
+    "pq": dict(name="pq_20Mx128B_M128_K256_top1000", N=20_000_000, M=128, K=256, dsub=16, k=1000, row_bytes=128,
+               dtype="f32"),
+    "binary": dict(name="binary_50Mx2048bit_top1000", N=50_000_000, D=2048, k=1000, row_bytes=256, dtype="f32"),
+    "multiquery": dict(name="multiquery_5Mx2048_fp16_Q64_top1000", N=5_000_000, D=2048, Q=64, k=1000,
+                       row_bytes=4096, dtype="f16"),
+}
+
+
+def make_workload(kind, scale, torch, binding, synth):
+    """Returns (step_fn, info).  step_fn() enqueues one ranking pass on the current stream."""
+    cfg = dict(WORKLOADS[kind])
+    N = max(1024, int(cfg["N"] * scale))
+    cfg["N"] = N
+    dev = "cuda"
+    seed = synth.BASE_SEED + {"dense": 2, "pq": 3, "binary": 4, "multiquery": 5}[kind]
+    k = cfg["k"]
+    if kind == "dense":
+        X = synth.dense_features(N, cfg["D"], seed, device=dev)
+        w = synth.normal_vector(cfg["D"], 0.05, seed + 100, device=dev)
+        ws = binding.make_workspace(N, k, 1, dev)
+        out = binding._outputs(1, k, dev)
+        step = lambda: binding.rank_dense(X, w, None, k, ws, out=out)
+        keep = (X, w)
+    elif kind == "pq":
+        codes = synth.pq_codes(N, cfg["M"], cfg["K"], seed, device=dev)
+        cb = synth.pq_codebooks(cfg["M"], cfg["K"], cfg["dsub"], seed + 100, device=dev)
+        w = synth.normal_vector(cfg["M"] * cfg["dsub"], 1.0, seed + 200, device=dev)
+        lut = torch.empty((cfg["M"], cfg["K"]), dtype=torch.float32, device=dev)
+        ws = binding.make_workspace(N, k, 1, dev)
+        out = binding._outputs(1, k, dev)
+
+        def step():                      # a new model means a new table: the build is part of the pass
+            binding.pq_build_lut(cb, w, lut)
+            return binding.rank_pq(codes, lut, 0.0, k, ws, out=out)
+        keep = (codes, cb, w)
+    elif kind == "binary":
+        bits = synth.binary_bits_random(N, cfg["D"] // 32, seed, device=dev)
+        w = synth.normal_vector(cfg["D"], 1.0, seed + 100, device=dev)
+        ws = binding.make_workspace(N, k, 1, dev)
+        out = binding._outputs(1, k, dev)
+        step = lambda: binding.rank_binary(bits, cfg["D"], w, 0.0, k, ws, out=out)
+        keep = (bits, w)
+    elif kind == "multiquery":
+        X = synth.dense_features(N, cfg["D"], seed, device=dev, dtype=torch.float16)
+        W = synth.normal_matrix(cfg["Q"], cfg["D"], 0.05, seed + 100, device=dev, dtype=torch.float16)
+        ws = binding.make_workspace(N, k, cfg["Q"], dev)
+        out = binding._outputs(cfg["Q"], k, dev)
+        step = lambda: binding.rank_dense(X, W, None, k, ws, out=out)
+        keep = (X, W)
+    else:
+        raise ValueError(kind)
+    cfg["_keep"] = keep
+    return step, cfg
+
+
+def time_steps(step, steps, warmup, torch, binding):
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.profile_begin(steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    scan_ms_total, nrec = binding.profile_end()
+    return (t1 - t0) / steps, (scan_ms_total / nrec if nrec else None)
+
+
+def measure(kind, steps, warmup, scale, torch, binding, synth):
+    step, cfg = make_workload(kind, scale, torch, binding, synth)
+    sec_per_step, scan_ms = time_steps(step, steps, warmup, torch, binding)
+    N = cfg["N"]
+    alg_bytes = N * cfg["row_bytes"]
+    res = {
+        "workload": cfg["name"] if scale == 1.0 else cfg["name"] + "_x%g" % scale,
+        "N": N,
+        "k": cfg["k"],
+        "value": N / sec_per_step,
+        "unit": "vectors/s",
+        "ms_per_step": sec_per_step * 1e3,
+        "dtype": cfg["dtype"],
+        "whole_path_GBps": alg_bytes / sec_per_step / 1e9,
+        "whole_path_frac_of_hbm_peak": alg_bytes / sec_per_step / 1e9 / HBM_PEAK_GBS,
+    }
+    if scan_ms:
+        achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
+        res["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(kind),
+                           "kernel_ms": scan_ms, "algorithmic_bytes": alg_bytes}
+    return res, cfg
+
+
+def measure_sgd(torch, binding, synth):
+    """One training pass: 125 Pegasos steps of batch 256 over 1,000 positives / 16,000 negatives."""
+    D, n_pos, n_neg, batch, steps, lam = 2048, 1000, 16000, 256, 125, 1e-4
+    Xp, Xn = synth.sgd_pools(D, n_pos, n_neg, synth.BASE_SEED + 2, device="cuda")
+    ip, ineg = synth.sgd_batches(n_pos, n_neg, batch, steps, synth.BASE_SEED + 2)
+    ip = torch.from_numpy(ip).cuda()
+    ineg = torch.from_numpy(ineg).cuda()
+    ws = binding.sgd_workspace(batch, "cuda")
+    w = torch.zeros(D, device="cuda")
+
+    def one_pass():
+        w.zero_()
+        for t in range(1, steps + 1):
+            binding.svm_sgd_step(w, None, Xp, ip[t - 1], Xn, ineg[t - 1], lam, t, False, ws)
+    one_pass()
+    torch.cuda.synchronize()
+    reps = 5
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        one_pass()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    return {"workload": "pegasos_pass_125steps_B256_D2048", "ms_per_pass": dt * 1e3, "us_per_step": dt / steps * 1e6}
+
+
+def cpu_baseline(kind, cfg, torch):
+    """Times the CPU oracle on this host on a bounded sample of the workload's own rows."""
+    from oracle import otf_oracle as orc
+    import numpy as np
+    cores = orc.num_threads()
+    keep = cfg["_keep"]
+    k = cfg["k"]
+    budget_s = 8.0
+    if kind == "dense":
+        rows = min(cfg["N"], 262144)
+        X = keep[0][:rows].cpu().numpy()
+        w = keep[1].cpu().numpy()
+        run = lambda: orc.topk(orc.dense_scores(X, w)[0], min(k, rows))
+        sample = "first %d rows of the store, scored and fully sorted" % rows
+    elif kind == "pq":
+        rows = min(cfg["N"], 1 << 20)
+        codes = keep[0][:rows].cpu().numpy()
+        cb, w = keep[1].cpu().numpy(), keep[2].cpu().numpy()
+        run = lambda: orc.topk(orc.pq_scores_reconstruct(codes, cb, w, 0.0), min(k, rows))
+        sample = "first %d rows, scored by explicit reconstruction and fully sorted" % rows
+    elif kind == "binary":
+        rows = min(cfg["N"], 1 << 20)
+        bits = keep[0][:rows].cpu().numpy().view(np.uint32)
+        w = keep[1].cpu().numpy()
+        run = lambda: orc.topk(orc.binary_scores(bits, cfg["D"], w, 0.0), min(k, rows))
+        sample = "first %d rows, scored bit by bit and fully sorted" % rows
+    else:
+        rows = min(cfg["N"], 16384)
+        X = keep[0][:rows].cpu().numpy()
+        W = keep[1].cpu().numpy()
+
+        def run():
+            s = orc.dense_scores(X, W)
+            for q in range(s.shape[0]):
+                orc.topk(s[q], min(k, rows))
+        sample = "first %d rows against all %d classifiers, each fully sorted" % (rows, cfg["Q"])
+    run()                                         # warm the pages
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        run()
+        reps += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or reps >= 50:
+            break
+    return {"value": rows * reps / el, "unit": "vectors/s", "cores": cores, "kind": "oracle",
+            "sample": "%s; %d repetitions in %.1f s" % (sample, reps, el)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="dense", choices=sorted(WORKLOADS))
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only; the result is then not the named workload)")
+    ap.add_argument("--no-others", action="store_true", help="skip the other stores and the training pass")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (each GPU would rank its own "
+                 "row shard; see DESIGN.md). Run with --gpus 1.")
+    import torch
+    from paper_1407_4764_amd import binding, synth
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    binding.lib()                                  # fail loudly if the HIP library is missing
+
+    res, cfg = measure(args.workload, args.steps, args.warmup, args.scale, torch, binding, synth)
+    line = {
+        "metric": "dataset vectors scored+top-k'd per sec (1 GPU)",
+        "value": res["value"],
+        "unit": "vectors/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": res["dtype"],
+        "data": "synthetic",
+        "config": {"workload": res["workload"], "N": res["N"], "k": res["k"],
+                   "step": "one otf_rank_* call: scan of the whole store + exact sorted top-k"},
+        "whole_path_frac_of_hbm_peak": res["whole_path_frac_of_hbm_peak"],
+        "roofline": res.get("roofline"),
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(args.workload, cfg, torch)
+    del cfg
+    torch.cuda.empty_cache()
+    if not args.no_others:
+        others = []
+        for kind in sorted(WORKLOADS):
+            if kind == args.workload:
+                continue
+            r, c = measure(kind, args.steps, args.warmup, args.scale, torch, binding, synth)
+            del c
+            torch.cuda.empty_cache()
+            others.append(r)
+        others.append(measure_sgd(torch, binding, synth))
+        line["other_workloads"] = others
+    line["paper_context"] = "paper: ~0.01 s to score + ~0.002 s to sort 1M x 128-D fp32 on a GTX Titan (Sec. 4)"
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
