@@ -4,6 +4,7 @@
 #include "otf.h"
 
 #include <atomic>
+#include <cstdlib>
 #include <vector>
 
 #include "otf_internal.h"
@@ -56,6 +57,15 @@ int device_cu_count() {
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
     cached[dev].store(cus, std::memory_order_relaxed);
     return cus;
+}
+
+int tune_int(const char *name, int fallback) {
+    const char *v = std::getenv(name);
+    if (!v || !*v) return fallback;
+    char *endp = nullptr;
+    long x = std::strtol(v, &endp, 10);
+    if (endp == v || x < 1 || x > 65536) return fallback;
+    return (int)x;
 }
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -59,12 +59,21 @@ __device__ __forceinline__ float load_w(const void *w, int w_is_half, int d) {
 
 // ---------------------------------------------------------------------------------------------
 // Wide rows: one wave per row, V 16-byte chunks per lane (D <= 64 * V * elems-per-chunk).
-template <bool XHALF, int V>
+// Each block owns one contiguous range of rows, its waves taking rows of the range in turn, so
+// a block streams one contiguous region of the store.
+//
+// FULL (D == 64 * V * elems-per-chunk exactly, e.g. 2048 fp32 with V = 8): branch-free and
+// software-pipelined.  The loads of the wave's next row are issued before the current row is
+// reduced, so 2*V 16-byte loads per lane stay in flight; with few, long-lived waves this is what
+// saturates HBM (many waves with shallow queues do not).  Prefetches past the wave's last row
+// are redirected to its last valid row instead of being skipped: an unconditional load keeps the
+// in-order wait counters exact, a conditional one would force a full drain every iteration.
+template <bool XHALF, int V, bool FULL>
 __global__ __launch_bounds__(256) void dense_wide_kernel(const uint8_t *__restrict__ X, long long N, int D,
                                                          long long row_bytes, const void *__restrict__ w,
-                                                         int w_is_half, const float *__restrict__ bias_ptr, int bias_index,
-        float *__restrict__ scores,
-                                                         SelState *st, uint32_t *hist1, int k) {
+                                                         int w_is_half, const float *__restrict__ bias_ptr,
+                                                         int bias_index, float *__restrict__ scores, SelState *st,
+                                                         uint32_t *hist1, int k) {
     constexpr int E = Elem<XHALF>::kPer16;
     __shared__ uint32_t lhist[kBins1];
     __shared__ uint32_t s_flag;
@@ -72,57 +81,77 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const uint8_t *__restri
     __syncthreads();
 
     const float bias = bias_ptr ? bias_ptr[bias_index] : 0.f;
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     float wr[V][E];
     bool live[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) {
         const int col = (j * 64 + lane) * E;
-        live[j] = col < D;
+        live[j] = FULL || col < D;
+        if (w_is_half) {
 #pragma unroll
-        for (int e = 0; e < E; ++e) wr[j][e] = live[j] ? load_w(w, w_is_half, col + e) : 0.f;
+            for (int e = 0; e < E; ++e)
+                wr[j][e] = live[j] ? __half2float(reinterpret_cast<const __half *>(w)[col + e]) : 0.f;
+        } else {
+#pragma unroll
+            for (int e = 0; e < E; ++e) wr[j][e] = live[j] ? reinterpret_cast<const float *>(w)[col + e] : 0.f;
+        }
     }
-    const long long waves_total = (long long)gridDim.x * (blockDim.x >> 6);
-    const long long wave_id = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    const size_t lane_off = (size_t)lane * 16;
+    const long long per = (N + gridDim.x - 1) / gridDim.x;
+    const long long begin = per * blockIdx.x;
+    long long end = begin + per;
+    if (end > N) end = N;
 
-    for (long long r0 = wave_id; r0 < N; r0 += 2 * waves_total) {
-        const long long r1 = r0 + waves_total;
-        const bool has1 = r1 < N;
-        const uint8_t *p0 = X + (size_t)r0 * row_bytes + lane_off;
-        const uint8_t *p1 = X + (size_t)(has1 ? r1 : r0) * row_bytes + lane_off;
-        Chunk16 c0[V], c1[V];
-#pragma unroll
-        for (int j = 0; j < V; ++j) {
-            if (live[j]) c0[j] = load_stream16(p0 + (size_t)j * 1024);
-        }
-#pragma unroll
-        for (int j = 0; j < V; ++j) {
-            if (live[j]) c1[j] = load_stream16(p1 + (size_t)j * 1024);
-        }
+    auto dot = [&](const Chunk16 *c) {
         float a0 = 0.f, a1 = 0.f;
 #pragma unroll
         for (int j = 0; j < V; ++j) {
-            if (live[j]) {
-                float f0[E], f1[E];
-                Elem<XHALF>::unpack(c0[j], f0);
-                Elem<XHALF>::unpack(c1[j], f1);
+            float f[E];
+            Elem<XHALF>::unpack(c[j], f);
 #pragma unroll
-                for (int e = 0; e < E; ++e) {
-                    a0 = fmaf(f0[e], wr[j][e], a0);
-                    a1 = fmaf(f1[e], wr[j][e], a1);
-                }
+            for (int e = 0; e < E; e += 2) {
+                a0 = fmaf(f[e], wr[j][e], a0);
+                a1 = fmaf(f[e + 1], wr[j][e + 1], a1);
             }
         }
-        a0 = wave_sum(a0) + bias;
-        a1 = wave_sum(a1) + bias;
+        return wave_sum_to_lane0(a0 + a1) + bias;
+    };
+    auto emit = [&](long long r, float sc) {
         if (lane == 0) {
-            scores[r0] = a0;
-            atomicAdd(&lhist[float_to_key(a0) >> 20], 1u);
-            if (has1) {
-                scores[r1] = a1;
-                atomicAdd(&lhist[float_to_key(a1) >> 20], 1u);
+            scores[r] = sc;
+            atomicAdd(&lhist[float_to_key(sc) >> 20], 1u);
+        }
+    };
+
+    if (FULL) {
+        if (begin + wave < end) {                           // uniform per wave
+            const long long last = begin + wave + ((end - 1 - begin - wave) / nwaves) * nwaves;  // wave's last row
+            const uint8_t *base = X + (size_t)lane * 16;
+            auto fetch = [&](Chunk16 *c, long long r) {
+                const uint8_t *p = base + (size_t)(r <= last ? r : last) * (size_t)row_bytes;
+#pragma unroll
+                for (int j = 0; j < V; ++j) c[j] = load_stream16(p + (size_t)j * 1024);
+            };
+            Chunk16 a[V], b[V];
+            fetch(a, begin + wave);
+            for (long long r = begin + wave; r <= last; r += 2 * nwaves) {
+                fetch(b, r + nwaves);
+                emit(r, dot(a));
+                fetch(a, r + 2 * nwaves);
+                const float sb = dot(b);
+                if (r + nwaves <= last) emit(r + nwaves, sb);
             }
+        }
+    } else {
+        for (long long r = begin + wave; r < end; r += nwaves) {
+            const uint8_t *p = X + (size_t)r * (size_t)row_bytes + (size_t)lane * 16;
+            Chunk16 c[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                c[j] = Chunk16{{0u, 0u, 0u, 0u}};
+                if (live[j]) c[j] = load_stream16(p + (size_t)j * 1024);
+            }
+            emit(r, dot(c));
         }
     }
     finish_pass1(lhist, hist1, st, (uint32_t)k, gridDim.x, &s_flag);
@@ -267,13 +296,20 @@ static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t
             default: dense_narrow_kernel<XHALF, 32><<<grid, 256, 0, s>>>(OTF_ARGS); break;
         }
     } else {
-        grid = (int)std::min<int64_t>((N + 3) / 4, (int64_t)cus * 8);
+        grid = (int)std::min<int64_t>((N + 3) / 4, (int64_t)cus * tune_int("OTF_DENSE_BLOCKS_PER_CU", 1));
         if (grid < 1) grid = 1;
         const int V = (chunks + 63) / 64;
-        if (V <= 1) dense_wide_kernel<XHALF, 1><<<grid, 256, 0, s>>>(OTF_ARGS);
-        else if (V <= 2) dense_wide_kernel<XHALF, 2><<<grid, 256, 0, s>>>(OTF_ARGS);
-        else if (V <= 4) dense_wide_kernel<XHALF, 4><<<grid, 256, 0, s>>>(OTF_ARGS);
-        else if (V <= 8) dense_wide_kernel<XHALF, 8><<<grid, 256, 0, s>>>(OTF_ARGS);
+        const bool full = chunks == V * 64;
+#define OTF_WIDE(VV)                                                                        \
+    do {                                                                                    \
+        if (full) dense_wide_kernel<XHALF, VV, true><<<grid, 256, 0, s>>>(OTF_ARGS);        \
+        else dense_wide_kernel<XHALF, VV, false><<<grid, 256, 0, s>>>(OTF_ARGS);            \
+    } while (0)
+        if (V <= 1) OTF_WIDE(1);
+        else if (V <= 2) OTF_WIDE(2);
+        else if (V <= 4) OTF_WIDE(4);
+        else if (V <= 8) OTF_WIDE(8);
+#undef OTF_WIDE
         else {
             if (D > kDenseMaxD) return hipErrorInvalidValue;
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dense_huge_kernel<XHALF>),

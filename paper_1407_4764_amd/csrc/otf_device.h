@@ -51,6 +51,26 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+// Sum over the 64 lanes using cross-lane data-parallel moves (no shared-memory traffic); the
+// total is returned in every lane (the last step goes through scalar registers).
+__device__ __forceinline__ float wave_sum_to_lane0(float v) {
+    v += dpp_mov_f32<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_mov_f32<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_mov_f32<0x141>(v);   // row_half_mirror
+    v += dpp_mov_f32<0x140>(v);   // row_mirror: every lane now holds the sum of its row of 16
+    const int iv = __float_as_int(v);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(iv, 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(iv, 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(iv, 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(iv, 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
 // Inclusive suffix sum over the 64 lanes of a wave: lane l receives sum of lanes l..63.
 __device__ __forceinline__ uint32_t wave_suffix_sum(uint32_t v) {
     const int lane = threadIdx.x & 63;

@@ -58,4 +58,7 @@ hipError_t launch_sgd_step(float *w, float *b, int D, const float *Xpos, int64_t
 
 int device_cu_count();
 
+// Launch-shape knobs for tuning runs: integer environment variable `name`, else `fallback`.
+int tune_int(const char *name, int fallback);
+
 }  // namespace otf

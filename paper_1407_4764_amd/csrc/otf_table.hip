@@ -27,8 +27,8 @@ namespace otf {
 constexpr int kSegBytes = 128;                       // row bytes handled per phase
 constexpr int kImageFloats = 256 * kSegBytes;        // one table image: 256 values x 128 columns
 constexpr int kImageBytes = kImageFloats * 4;        // 128 KiB
-constexpr int kScanThreads = 1024;
-constexpr int kScanUnroll = 4;                       // 16-byte loads in flight per lane
+constexpr int kScanMaxThreads = 1024;
+constexpr int kScanThreads = 512;
 
 __device__ __forceinline__ int image_column(int pos) {   // pos = byte position inside a 128-byte segment
     const int c = pos >> 4, tq = (pos >> 2) & 3, b = pos & 3;
@@ -105,9 +105,17 @@ __device__ __forceinline__ float group_sum(float v) {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Scan.  LPR = lanes per stored row within one phase = min(M, 128) / 16.
-template <int LPR>
-__global__ __launch_bounds__(kScanThreads) void table_scan_kernel(const uint8_t *__restrict__ codes, long long N,
+// Scan.  LPR = lanes per stored row within one phase = min(M, 128) / 16;  U = 16-byte loads per
+// lane per tile;  SPLIT = rows longer than 128 bytes (several phases, partial sums carried in
+// the score array).
+//
+// The main loop is branch-free and software-pipelined: the loads of the wave's next tile are
+// issued before the current tile is looked up, and tiles or rows past the end are redirected
+// to the block's last row rather than skipped (an unconditional load keeps the in-order wait
+// counters exact).  After the lookups the U row sums of a lane group are moved into U different
+// lanes so that storing, histogramming and (SPLIT) carrying happen once per tile, not per row.
+template <int LPR, int U, bool SPLIT, int MODE = 0>
+__global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(const uint8_t *__restrict__ codes, long long N,
                                                                   int M, int nsplit,
                                                                   const float *__restrict__ image, float bias,
                                                                   float *__restrict__ scores, SelState *st,
@@ -117,7 +125,9 @@ __global__ __launch_bounds__(kScanThreads) void table_scan_kernel(const uint8_t 
     __shared__ uint32_t lhist[kBins1];
     __shared__ uint32_t s_flag;
     constexpr int RPW = 64 / LPR;                // rows per wave load
-    constexpr int TILE = RPW * kScanUnroll;      // rows per wave iteration
+    constexpr int TILE = RPW * U;                // rows per wave iteration
+    constexpr int ACTIVE = LPR < U ? LPR : U;    // lanes of a group that own an output row per round
+    constexpr int ROUNDS = U / ACTIVE;           // output rounds per tile
 
     for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
 
@@ -133,13 +143,39 @@ __global__ __launch_bounds__(kScanThreads) void table_scan_kernel(const uint8_t 
         colbyte[tb] = 4u * (uint32_t)(4 * c + b);
     }
 
-    // this block's rows: a contiguous range, a multiple of 1024 rows long
+    // this block's rows: a contiguous range, a multiple of 1024 rows long (TILE divides 1024, so
+    // only the last block of the grid can end in a partial tile)
     long long per = (N + gridDim.x - 1) / gridDim.x;
     per = (per + 1023) / 1024 * 1024;
     long long begin = per * blockIdx.x, end = begin + per;
     if (begin > N) begin = N;
     if (end > N) end = N;
-    const long long ntiles = (end - begin + TILE - 1) / TILE;
+    const long long nfull = (end - begin) / TILE;          // full tiles
+    const int rem = (int)((end - begin) % TILE);           // rows of the partial tile, if any
+    const size_t tile_bytes = (size_t)TILE * (size_t)M;
+    const size_t u_bytes = (size_t)RPW * (size_t)M;        // distance between the U loads of a lane
+    const int out_u = sub % ACTIVE;                        // which of a round's rows this lane stores
+
+    auto lookup16 = [&](const u32x4 &d) {
+        if (MODE == 1) return __uint_as_float((d[0] ^ d[1] ^ d[2] ^ d[3]) & 0x3fffffffu);
+        uint32_t addr[16];
+#pragma unroll
+        for (int tq = 0; tq < 4; ++tq)
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb)
+                addr[4 * tq + tb] = (__builtin_amdgcn_ubfe(d[tq], shift[tb], 8u) << 9) + colbyte[tb];
+        float t[16];
+#pragma unroll
+        for (int tq = 0; tq < 4; ++tq)
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb)
+                t[4 * tq + tb] = *reinterpret_cast<const float *>(lds_raw + addr[4 * tq + tb] + 128 * tq);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] += t[i + 8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] += t[i + 4];
+        return group_sum<LPR>((t[0] + t[1]) + (t[2] + t[3]));
+    };
 
     for (int sp = 0; sp < nsplit; ++sp) {
         __syncthreads();                          // previous phase done with the table
@@ -150,48 +186,81 @@ __global__ __launch_bounds__(kScanThreads) void table_scan_kernel(const uint8_t 
         }
         __syncthreads();
         const bool first = sp == 0, lastp = sp == nsplit - 1;
-        const size_t col_off = (size_t)sp * kSegBytes + (size_t)sub * 16;
+        // lane's address in tile 0 of the block: row (begin + rr), this phase's columns
+        const uint8_t *lane_codes = codes + (size_t)(begin + rr) * (size_t)M + (size_t)sp * kSegBytes + (size_t)sub * 16;
+        // first row this lane stores in tile 0 (round 0)
+        float *lane_scores = scores + begin + (long long)out_u * RPW + rr;
 
-        for (long long tile = wave; tile < ntiles; tile += nwaves) {
-            const long long row0 = begin + tile * TILE;
-            u32x4 d[kScanUnroll];
-            float carry[kScanUnroll];
-            bool ok[kScanUnroll];
+        // one output round: the U row sums of a lane group go to U different lanes, which store
+        auto emit = [&](const float *s, const float *carry, float *dst, int e, bool ok) {
+            float mine = s[e * ACTIVE];
 #pragma unroll
-            for (int u = 0; u < kScanUnroll; ++u) {
-                const long long row = row0 + (long long)u * RPW + rr;
-                ok[u] = row < end;
-                d[u] = (u32x4){0u, 0u, 0u, 0u};
-                carry[u] = 0.f;
-                if (ok[u]) {
-                    d[u] = __builtin_nontemporal_load(
-                        reinterpret_cast<const u32x4 *>(codes + (size_t)row * (size_t)M + col_off));
-                    if (!first && sub == 0) carry[u] = scores[row];
+            for (int a = 1; a < ACTIVE; ++a) mine = out_u == a ? s[e * ACTIVE + a] : mine;
+            if (sub < ACTIVE && ok) {
+                if (SPLIT && !first) mine += carry[e];
+                if (lastp) {
+                    mine += bias;
+                    atomicAdd(&lhist[float_to_key(mine) >> 20], 1u);
                 }
+                *dst = mine;
+            }
+        };
+
+        if (wave < nfull) {                       // uniform per wave
+            auto fetch = [&](u32x4 *d, float *carry, long long tile) {
+                if (tile > nfull - 1) tile = nfull - 1;      // uniform: prefetch past the end re-reads the last tile
+                if (MODE == 2 && tile >= 2 * nwaves) return;
+                const uint8_t *p = lane_codes + (size_t)tile * tile_bytes;
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    d[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + (size_t)u * u_bytes));
+                if (SPLIT) {
+                    const float *q = lane_scores + tile * TILE;
+#pragma unroll
+                    for (int e = 0; e < ROUNDS; ++e) carry[e] = q[e * ACTIVE * RPW];
+                }
+            };
+            auto consume = [&](const u32x4 *d, const float *carry, long long tile) {
+                float s[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) s[u] = lookup16(d[u]);
+                float *q = lane_scores + tile * TILE;
+#pragma unroll
+                for (int e = 0; e < ROUNDS; ++e) emit(s, carry, q + e * ACTIVE * RPW, e, true);
+            };
+            u32x4 da[U], db[U];
+            float ca[ROUNDS], cb[ROUNDS];
+            fetch(da, ca, wave);
+            for (long long tile = wave; tile < nfull; tile += 2 * nwaves) {
+                fetch(db, cb, tile + nwaves);
+                consume(da, ca, tile);
+                fetch(da, ca, tile + 2 * nwaves);
+                if (tile + nwaves < nfull) consume(db, cb, tile + nwaves);
+            }
+        }
+        if (rem > 0 && wave == (int)(nfull % nwaves)) {   // the partial tile: same steps, row-checked
+            const long long row0 = begin + nfull * TILE;
+            u32x4 d[U];
+            float carry[ROUNDS], s[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const long long row = row0 + (long long)u * RPW + rr;
+                d[u] = (u32x4){0u, 0u, 0u, 0u};
+                if (row < end)
+                    d[u] = *reinterpret_cast<const u32x4 *>(codes + (size_t)row * (size_t)M + (size_t)sp * kSegBytes +
+                                                            (size_t)sub * 16);
             }
 #pragma unroll
-            for (int u = 0; u < kScanUnroll; ++u) {
-                float acc[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int e = 0; e < ROUNDS; ++e) {
+                const long long row = row0 + (long long)(e * ACTIVE + out_u) * RPW + rr;
+                carry[e] = (SPLIT && !first && row < end) ? scores[row] : 0.f;
+            }
 #pragma unroll
-                for (int tq = 0; tq < 4; ++tq) {
-                    const uint32_t word = d[u][tq];
+            for (int u = 0; u < U; ++u) s[u] = lookup16(d[u]);
 #pragma unroll
-                    for (int tb = 0; tb < 4; ++tb) {
-                        const uint32_t v = __builtin_amdgcn_ubfe(word, shift[tb], 8u);
-                        const uint32_t addr = (v << 9) + colbyte[tb];
-                        acc[tq] += *reinterpret_cast<const float *>(lds_raw + addr + 128 * tq);
-                    }
-                }
-                float s = group_sum<LPR>((acc[0] + acc[1]) + (acc[2] + acc[3]));
-                if (sub == 0 && ok[u]) {
-                    const long long row = row0 + (long long)u * RPW + rr;
-                    s += carry[u];
-                    if (lastp) {
-                        s += bias;
-                        atomicAdd(&lhist[float_to_key(s) >> 20], 1u);
-                    }
-                    scores[row] = s;
-                }
+            for (int e = 0; e < ROUNDS; ++e) {
+                const long long row = row0 + (long long)(e * ACTIVE + out_u) * RPW + rr;
+                emit(s, carry, scores + row, e, row < end);
             }
         }
     }
@@ -220,19 +289,35 @@ hipError_t launch_binary_prepare(const float *w, int D, float *image, const Sele
     return hipGetLastError();
 }
 
-template <int LPR>
-static hipError_t launch_scan_lpr(const uint8_t *codes, int64_t N, int M, int nsplit, const float *image, float bias,
+template <int LPR, int U, bool SPLIT, int MODE = 0>
+static hipError_t launch_scan_cfg(const uint8_t *codes, int64_t N, int M, int nsplit, const float *image, float bias,
                                   float *scores, SelState *st, uint32_t *hist1, int k, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&table_scan_kernel<LPR>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&table_scan_kernel<LPR, U, SPLIT, MODE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kImageBytes);
     if (e != hipSuccess) return e;
     int grid = device_cu_count();
     const int64_t max_useful = (N + 1023) / 1024;
     if (grid > max_useful) grid = (int)max_useful;
     if (grid < 1) grid = 1;
-    table_scan_kernel<LPR><<<grid, kScanThreads, kImageBytes, s>>>(codes, (long long)N, M, nsplit, image, bias, scores,
-                                                                 st, hist1, k);
+    const int threads = tune_int("OTF_SCAN_THREADS", kScanThreads);
+    table_scan_kernel<LPR, U, SPLIT, MODE><<<grid, threads, kImageBytes, s>>>(codes, (long long)N, M, nsplit, image, bias,
+                                                                        scores, st, hist1, k);
     return hipGetLastError();
+}
+
+template <int LPR>
+static hipError_t launch_scan_lpr(const uint8_t *codes, int64_t N, int M, int nsplit, const float *image, float bias,
+                                  float *scores, SelState *st, uint32_t *hist1, int k, hipStream_t s) {
+    const int u = tune_int("OTF_SCAN_UNROLL", 8);
+    const int mode = tune_int("OTF_SCAN_MODE", 0);
+    if (LPR == 8 && mode == 1) return launch_scan_cfg<LPR, 4, false, 1>(codes, N, M, 1, image, bias, scores, st, hist1, k, s);
+    if (LPR == 8 && mode == 2) return launch_scan_cfg<LPR, 4, false, 2>(codes, N, M, 1, image, bias, scores, st, hist1, k, s);
+    if (nsplit > 1) {
+        if (u == 8) return launch_scan_cfg<LPR, 8, true>(codes, N, M, nsplit, image, bias, scores, st, hist1, k, s);
+        return launch_scan_cfg<LPR, 4, true>(codes, N, M, nsplit, image, bias, scores, st, hist1, k, s);
+    }
+    if (u == 8) return launch_scan_cfg<LPR, 8, false>(codes, N, M, nsplit, image, bias, scores, st, hist1, k, s);
+    return launch_scan_cfg<LPR, 4, false>(codes, N, M, nsplit, image, bias, scores, st, hist1, k, s);
 }
 
 // M = stored bytes per row: 16, 32, 64 or a multiple of 128.
