@@ -188,6 +188,13 @@ def svm_sgd_step(w, b, Xpos, idx_pos, Xneg, idx_neg, lam, t, update_bias, ws):
         raise OtfError(rc, "otf_svm_sgd_step")
 
 
+def debug_fallback_taken(ws):
+    """True if the last ranking call on this workspace abandoned its filtered scan and redid the
+    ranking by full selection (reads the flag the kernels leave in the workspace; test use only)."""
+    torch.cuda.synchronize()
+    return int(ws[60:64].view(torch.int32).item()) != 0
+
+
 def profile_begin(max_records):
     rc = lib().otf_profile_begin(int(max_records))
     if rc != OTF_OK:

@@ -29,6 +29,11 @@ WsLayout ws_layout(int64_t N, int32_t Q) {
     L.blockhist3 = take((size_t)Q * kSelBlocks * kBins3 * 4);
     L.eqoff = take((size_t)Q * kSelBlocks * 4);
     L.cand = take((size_t)Q * kCandCap * 8);
+    L.sample_st = take((size_t)Q * sizeof(SelState));
+    L.sample_hist1 = take((size_t)Q * kBins1 * 4);
+    L.sample_hist2 = take((size_t)Q * kBins2 * 4);
+    L.sample_ld = padded_rows(sample_rows(N) + kSampleGroup);
+    L.sample_scores = take((size_t)Q * (size_t)L.sample_ld * 4);
     L.lut_image = take(kLutImageBytes);
     L.scores = take((size_t)Q * (size_t)padded_rows(N) * 4);
     L.total = off;
@@ -45,6 +50,34 @@ SelectWs select_ws(void *ws, const WsLayout &L) {
     sw.eqoff = reinterpret_cast<uint32_t *>(p + L.eqoff);
     sw.cand = reinterpret_cast<unsigned long long *>(p + L.cand);
     return sw;
+}
+
+// The sample thresholding only runs passes 1 and 2, so it has no pass-3 or candidate storage.
+SelectWs sample_select_ws(void *ws, const WsLayout &L) {
+    uint8_t *p = reinterpret_cast<uint8_t *>(ws);
+    SelectWs sw;
+    sw.st = reinterpret_cast<SelState *>(p + L.sample_st);
+    sw.hist1 = reinterpret_cast<uint32_t *>(p + L.sample_hist1);
+    sw.hist2 = reinterpret_cast<uint32_t *>(p + L.sample_hist2);
+    sw.blockhist3 = nullptr;
+    sw.eqoff = nullptr;
+    sw.cand = nullptr;
+    return sw;
+}
+
+// Filtered scan or full selection?  The filtered scan needs a sample large enough to place the
+// threshold (>= 16 groups) and a list that holds ~4x the requested rows.
+static bool filter_eligible(int64_t N, int32_t k, const float *all_scores) {
+    if (all_scores || k > kFilterMaxK) return false;
+    if (sample_rows(N) < 16 * kSampleGroup) return false;
+    return tune_int("OTF_RANK_PATH", 0) != 1;      // 1 forces the full selection (testing, comparison)
+}
+
+// Rank of the sample key that becomes the threshold: the sample holds Nv of N rows, so the m-th
+// largest sample key leaves about m * N / Nv = kFilterExpect rows of the store at or above it.
+static int sample_rank(int64_t N, int64_t Nv) {
+    int64_t m = ((int64_t)kFilterExpect * Nv + N / 2) / N;
+    return (int)(m < 32 ? 32 : m);
 }
 
 int device_cu_count() {
@@ -142,8 +175,8 @@ int otf_topk(const float *scores, int64_t N, int64_t ld, int32_t Q, int32_t k, f
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     SelectWs sw = select_ws(ws, L);
     hipError_t e = launch_select_init(sw, Q, s);
-    if (e == hipSuccess) e = launch_hist1(scores, N, ld, Q, k, sw, s);
-    if (e == hipSuccess) e = launch_select_tail(scores, N, ld, Q, k, sw, out_scores, out_idx, s);
+    if (e == hipSuccess) e = launch_hist1(scores, N, ld, Q, k, sw, 0, s);
+    if (e == hipSuccess) e = launch_select_tail(scores, N, ld, Q, k, sw, out_scores, out_idx, 0, s);
     return hip_status(e);
 }
 
@@ -168,25 +201,55 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
     const int x_half = xdt == OTF_F16, w_half = wdt == OTF_F16;
     const size_t wsize = w_half ? 2 : 4;
 
-    hipError_t e = launch_select_init(sw, Q, s);
     const bool mfma = Q > 1 && x_half && w_half && Q % 32 == 0 && D % 128 == 0 && aligned16(W);
-    ScanTimer timer(s);
-    if (e == hipSuccess && mfma) {
-        for (int q0 = 0; q0 < Q && e == hipSuccess; ) {
+    const uint8_t *Wb = reinterpret_cast<const uint8_t *>(W);
+    hipError_t e = launch_select_init(sw, Q, s);
+
+    // One matrix-core launch per group of 64 (or a last 32) classifiers.
+    auto mfma_scan = [&](int64_t rows, ScanEmit emit, float *dst, int64_t ld, const SelState *tau, SelState *st,
+                         unsigned long long *cand, const SelState *gate) {
+        hipError_t err = hipSuccess;
+        for (int q0 = 0; q0 < Q && err == hipSuccess;) {
             const int qn = (Q - q0 >= 64) ? 64 : 32;
-            e = launch_dense_mfma(X, N, D, ldx, reinterpret_cast<const uint8_t *>(W) + (size_t)q0 * D * wsize, qn,
-                                  bias ? bias + q0 : nullptr, S + (size_t)q0 * ldS, ldS, s);
+            err = launch_dense_mfma(X, rows, D, ldx, Wb + (size_t)q0 * D * wsize, qn, bias ? bias + q0 : nullptr, emit,
+                                    dst ? dst + (size_t)q0 * ld : nullptr, ld, tau ? tau + q0 : nullptr,
+                                    st ? st + q0 : nullptr, cand ? cand + (size_t)q0 * kCandCap : nullptr, gate, s);
             q0 += qn;
         }
+        return err;
+    };
+
+    if (mfma && filter_eligible(N, k, all_scores)) {
+        // sample -> per-classifier thresholds -> filtered scan -> sort; full selection behind a gate
+        SelectWs ssw = sample_select_ws(ws, L);
+        float *sample = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + L.sample_scores);
+        const int64_t Nv = sample_rows(N);
+        const int m = sample_rank(N, Nv);
+        if (e == hipSuccess) e = launch_select_init(ssw, Q, s);
+        if (e == hipSuccess) e = mfma_scan(Nv, kEmitSample, sample, L.sample_ld, nullptr, nullptr, nullptr, nullptr);
+        if (e == hipSuccess) e = launch_hist1(sample, Nv, L.sample_ld, Q, m, ssw, 0, s);
+        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, Q, m, ssw, s);
+        ScanTimer timer(s);
+        if (e == hipSuccess) e = mfma_scan(N, kEmitFilter, nullptr, 0, ssw.st, sw.st, sw.cand, nullptr);
         timer.stop();
-        if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, k, sw, s);
+        if (e == hipSuccess) e = launch_filter_sort(sw, Q, k, out_scores, out_idx, s);
+        if (e == hipSuccess) e = mfma_scan(N, kEmitScores, S, ldS, nullptr, nullptr, nullptr, sw.st);
+        if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, k, sw, 1, s);
+        if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, 1, s);
+        return hip_status(e);
+    }
+    ScanTimer timer(s);
+    if (e == hipSuccess && mfma) {
+        e = mfma_scan(N, kEmitScores, S, ldS, nullptr, nullptr, nullptr, nullptr);
+        timer.stop();
+        if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, k, sw, 0, s);
     } else if (e == hipSuccess) {
         for (int q = 0; q < Q && e == hipSuccess; ++q)
-            e = launch_dense_scan(X, x_half, N, D, ldx, reinterpret_cast<const uint8_t *>(W) + (size_t)q * D * wsize,
-                                  w_half, bias, q, S + (size_t)q * ldS, sw.st + q, sw.hist1 + (size_t)q * kBins1, k, s);
+            e = launch_dense_scan(X, x_half, N, D, ldx, Wb + (size_t)q * D * wsize, w_half, bias, q,
+                                  S + (size_t)q * ldS, sw.st + q, sw.hist1 + (size_t)q * kBins1, k, s);
         timer.stop();
     }
-    if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, s);
+    if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, 0, s);
     return hip_status(e);
 }
 
@@ -201,6 +264,43 @@ static bool table_row_bytes_ok(int32_t rb) {
     return rb == 16 || rb == 32 || rb == 64 || (rb >= 128 && rb % 128 == 0 && rb <= 1024);
 }
 
+// Shared tail of otf_rank_pq / otf_rank_binary once the table image is in place.
+static hipError_t rank_table(const uint8_t *codes, int64_t N, int row_bytes, int seven_bit, const float *image,
+                             float bias, int32_t k, float *out_scores, int32_t *out_idx, float *all_scores, void *ws,
+                             const WsLayout &L, hipStream_t s) {
+    SelectWs sw = select_ws(ws, L);
+    uint8_t *wsb = reinterpret_cast<uint8_t *>(ws);
+    float *S = all_scores ? all_scores : reinterpret_cast<float *>(wsb + L.scores);
+    const bool one_phase = seven_bit || row_bytes <= 128;
+    hipError_t e = hipSuccess;
+    if (one_phase && filter_eligible(N, k, all_scores)) {
+        SelectWs ssw = sample_select_ws(ws, L);
+        float *sample = reinterpret_cast<float *>(wsb + L.sample_scores);
+        const int64_t Nv = sample_rows(N);
+        const int m = sample_rank(N, Nv);
+        e = launch_table_scan(codes, Nv, row_bytes, seven_bit, image, bias, kEmitSample, sample, ssw.st, ssw.hist1, m,
+                              nullptr, nullptr, nullptr, s);
+        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, s);
+        ScanTimer timer(s);
+        if (e == hipSuccess)
+            e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitFilter, nullptr, sw.st, nullptr, k,
+                                  ssw.st, sw.cand, nullptr, s);
+        timer.stop();
+        if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
+        if (e == hipSuccess)
+            e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitScores, S, sw.st, sw.hist1, k,
+                                  nullptr, nullptr, sw.st, s);
+        if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 1, s);
+        return e;
+    }
+    ScanTimer timer(s);
+    e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitScores, S, sw.st, sw.hist1, k, nullptr,
+                          nullptr, nullptr, s);
+    timer.stop();
+    if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 0, s);
+    return e;
+}
+
 int otf_rank_pq(const uint8_t *codes, int64_t N, int32_t M, int32_t K, const float *lut, float bias, int32_t k,
                 float *out_scores, int32_t *out_idx, float *all_scores, void *ws, size_t ws_bytes, void *stream) {
     WsLayout L;
@@ -210,15 +310,9 @@ int otf_rank_pq(const uint8_t *codes, int64_t N, int32_t M, int32_t K, const flo
     if (K != 256 || !table_row_bytes_ok(M)) return OTF_ERR_UNSUPPORTED;
     if (!aligned16(codes)) return OTF_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    SelectWs sw = select_ws(ws, L);
-    uint8_t *wsb = reinterpret_cast<uint8_t *>(ws);
-    float *image = reinterpret_cast<float *>(wsb + L.lut_image);
-    float *S = all_scores ? all_scores : reinterpret_cast<float *>(wsb + L.scores);
-    hipError_t e = launch_pq_prepare(lut, M, image, sw, s);
-    ScanTimer timer(s);
-    if (e == hipSuccess) e = launch_table_scan(codes, N, M, image, bias, S, sw.st, sw.hist1, k, s);
-    timer.stop();
-    if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, s);
+    float *image = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + L.lut_image);
+    hipError_t e = launch_pq_prepare(lut, M, image, select_ws(ws, L), sample_select_ws(ws, L), s);
+    if (e == hipSuccess) e = rank_table(codes, N, M, 0, image, bias, k, out_scores, out_idx, all_scores, ws, L, s);
     return hip_status(e);
 }
 
@@ -231,16 +325,11 @@ int otf_rank_binary(const uint32_t *bits, int64_t N, int32_t D, const float *w, 
     if (D % 32 != 0 || !table_row_bytes_ok(D / 8)) return OTF_ERR_UNSUPPORTED;
     if (!aligned16(bits)) return OTF_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    SelectWs sw = select_ws(ws, L);
-    uint8_t *wsb = reinterpret_cast<uint8_t *>(ws);
-    float *image = reinterpret_cast<float *>(wsb + L.lut_image);
-    float *S = all_scores ? all_scores : reinterpret_cast<float *>(wsb + L.scores);
-    hipError_t e = launch_binary_prepare(w, D, image, sw, s);
-    ScanTimer timer(s);
+    float *image = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + L.lut_image);
+    hipError_t e = launch_binary_prepare(w, D, image, select_ws(ws, L), sample_select_ws(ws, L), s);
     if (e == hipSuccess)
-        e = launch_table_scan(reinterpret_cast<const uint8_t *>(bits), N, D / 8, image, bias, S, sw.st, sw.hist1, k, s);
-    timer.stop();
-    if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, s);
+        e = rank_table(reinterpret_cast<const uint8_t *>(bits), N, D / 8, D == 2048, image, bias, k, out_scores,
+                       out_idx, all_scores, ws, L, s);
     return hip_status(e);
 }
 

@@ -11,6 +11,12 @@ constexpr int kBins2 = 4096;   // radix pass 2: key bits 19..8
 constexpr int kBins3 = 256;    // radix pass 3: key bits 7..0
 constexpr int kCandCap = 8192; // capacity of the candidate list that the final sort takes
 constexpr int kSelBlocks = 256; // blocks per classifier in the selection passes over scores
+// Filtered scans: a strided sample of the store (every kSampleStride-th group of kSampleGroup rows)
+// is scored first; the threshold is set so that about kFilterExpect rows of the full store pass it.
+constexpr int kSampleGroup = 1024;
+constexpr int kSampleStride = 64;
+constexpr int kFilterExpect = 4096;
+constexpr int kFilterMaxK = 1024;
 
 // Order-preserving map float -> uint32 (larger float <=> larger key); -0.0 maps onto +0.0
 // so that the two compare equal, as they do as numbers.
@@ -37,7 +43,8 @@ struct SelState {
     long long tex;     // gather every key with (long long)key > tex
     uint32_t cursor;   // append cursor of the gather pass
     uint32_t done1, done2, done3;  // block tickets of the three histogram passes
-    uint32_t pad[2];
+    uint32_t tau_key;  // filter threshold: rows with key >= tau_key are candidates (filtered scans)
+    uint32_t fallback; // set by the filtered path when its candidate list cannot serve: redo by full selection
 };
 static_assert(sizeof(SelState) == 64, "SelState layout");
 
@@ -130,6 +137,24 @@ __device__ __forceinline__ void resolve_pass1(SelState *st, const uint32_t *hist
             st->mode = 1;   // provisional: pass 2 decides between 1 and 2
         }
     }
+}
+
+// Histogram increment for a whole wave when many lanes are likely to hit the same bin (scores of
+// one classifier cluster in a few coarse bins): the bins held by the lowest active lanes are
+// counted with one atomic each, the rest individually.  All 64 lanes must call.
+__device__ __forceinline__ void hist_add_wave(uint32_t *lhist, uint32_t bin, bool active) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll 1
+    for (int it = 0; it < 4; ++it) {
+        const unsigned long long act = __ballot(active);
+        if (act == 0ull) return;                                   // uniform
+        const int leader = __builtin_ctzll(act);
+        const uint32_t lb = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
+        const unsigned long long same = __ballot(active && bin == lb);
+        if (lane == leader) atomicAdd(&lhist[lb], (uint32_t)__popcll(same));
+        if (bin == lb) active = false;
+    }
+    if (active) atomicAdd(&lhist[bin], 1u);
 }
 
 // Adds a block's shared-memory histogram into the global one, then tells whether this block

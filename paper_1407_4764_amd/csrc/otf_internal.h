@@ -19,38 +19,67 @@ struct SelectWs {
 };
 
 struct WsLayout {
-    size_t st, hist1, hist2, blockhist3, eqoff, cand, lut_image, scores, total;
+    size_t st, hist1, hist2, blockhist3, eqoff, cand, sample_st, sample_hist1, sample_hist2, sample_scores,
+        lut_image, scores, total;
+    int64_t sample_ld;   // row stride (floats) of the sample score buffer
 };
 // Byte offsets of the workspace regions for N rows and Q classifiers (every offset 256-aligned).
 WsLayout ws_layout(int64_t N, int32_t Q);
-SelectWs select_ws(void *ws, const WsLayout &L);
+SelectWs select_ws(void *ws, const WsLayout &L);         // state of the full selection
+SelectWs sample_select_ws(void *ws, const WsLayout &L);  // state used to threshold the sample
 
 constexpr int kDenseMaxD = 16384;  // widest dense row any kernel takes (elements)
-constexpr size_t kLutImageBytes = 8u * 128u * 1024u;  // up to 8 splits of a 256 x 128 fp32 table
+constexpr size_t kLutImageBytes = 8u * 128u * 1024u + 4096u;  // up to 8 table images of 128 KiB, or one + side table
+
+// Rows of the strided sample of an N-row store (whole groups only).
+inline int64_t sample_rows(int64_t N) {
+    return N / ((int64_t)kSampleGroup * kSampleStride) * kSampleGroup;
+}
 
 // Zeroes the selection state and the pass-1/2 histograms of Q classifiers.
 hipError_t launch_select_init(const SelectWs &sw, int Q, hipStream_t s);
 // Radix pass 1 over ready-made scores (rows of length N, stride ld).
-hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw, hipStream_t s);
-// Passes 2 and 3 (skipped on the device when pass 1 was decisive), gather and final sort.
+hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw, int gated,
+                        hipStream_t s);
+// Passes 2 and 3 (skipped on the device when pass 1 was decisive), gather and final sort.  With
+// `gated` the kernels return at once unless sw.st[0].fallback is set.
 hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw,
-                              float *out_scores, int32_t *out_idx, hipStream_t s);
+                              float *out_scores, int32_t *out_idx, int gated, hipStream_t s);
+// Pass 2 over sample scores: publishes sample_sw.st[q].tau_key (the m-th largest sample key, 24 bits).
+hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64_t ld, int Q, int m,
+                                   const SelectWs &sample_sw, hipStream_t s);
+// End of a filtered scan: sort the appended candidates or raise sw.st[0].fallback.
+hipError_t launch_filter_sort(const SelectWs &sw, int Q, int k, float *out_scores, int32_t *out_idx, hipStream_t s);
 
 // Dense single-classifier scan: writes N scores (bias included) and builds the pass-1 histogram.
 hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int64_t ldx,
                              const void *w, int w_is_half, const float *bias_ptr, int bias_index,
                              float *scores, SelState *st, uint32_t *hist1, int k, hipStream_t s);
 
-// Multi-classifier fp16 scan on the matrix cores: scores[q][i], row stride lds_.  No histogram.
-hipError_t launch_dense_mfma(const void *X, int64_t N, int D, int64_t ldx, const void *W, int Q,
-                             const float *bias, float *scores, int64_t ld_scores, hipStream_t s);
+// Multi-classifier fp16 scan on the matrix cores (Q = 32 or 64 classifiers per call).
+//   kEmitScores  scores[q][i] for every row (row stride ld_scores); with `gate` set the kernel returns
+//                at once unless gate->fallback is raised
+//   kEmitSample  the same for the strided sample only (compact row numbering)
+//   kEmitFilter  nothing is stored but the rows with key >= tau[q].tau_key, appended to cand[q]
+enum ScanEmit { kEmitScores = 0, kEmitSample = 1, kEmitFilter = 2 };
+hipError_t launch_dense_mfma(const void *X, int64_t N, int D, int64_t ldx, const void *W, int Q, const float *bias,
+                             ScanEmit emit, float *scores, int64_t ld_scores, const SelState *tau, SelState *st,
+                             unsigned long long *cand, const SelState *gate, hipStream_t s);
 
 // Byte-indexed table scans (product-quantised codes, binary codes).
 hipError_t launch_pq_build_lut(const float *codebooks, int M, int K, int dsub, const float *w, float *lut, hipStream_t s);
-hipError_t launch_pq_prepare(const float *lut, int M, float *image, const SelectWs &sw, hipStream_t s);
-hipError_t launch_binary_prepare(const float *w, int D, float *image, const SelectWs &sw, hipStream_t s);
-hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int M, const float *image, float bias,
-                             float *scores, SelState *st, uint32_t *hist1, int k, hipStream_t s);
+// Table images in scan layout; also zero both selection states.
+hipError_t launch_pq_prepare(const float *lut, int M, float *image, const SelectWs &sw, const SelectWs &sample_sw,
+                             hipStream_t s);
+hipError_t launch_binary_prepare(const float *w, int D, float *image, const SelectWs &sw, const SelectWs &sample_sw,
+                                 hipStream_t s);
+// row_bytes = stored bytes per row; seven_bit = the 2048-bit binary layout (7+7+7+7+4 bits per word).
+//   kEmitScores  scores + pass-1 histogram into (st, hist1) for a top-k of k; `gate` as above
+//   kEmitSample  scores of the strided sample (compact numbering) + pass-1 histogram for rank k = m
+//   kEmitFilter  append rows with key >= tau->tau_key to cand (cursor in st)
+hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, int seven_bit, const float *image,
+                             float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
+                             const SelState *tau, unsigned long long *cand, const SelState *gate, hipStream_t s);
 
 hipError_t launch_sgd_step(float *w, float *b, int D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,
                            int n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int n_neg,

@@ -25,12 +25,17 @@ constexpr int kBM = 128;                 // dataset rows per tile
 constexpr int kBK = 128;                 // K elements (halves) per step
 constexpr int kRowStride = kBK * 2 + 16; // bytes per tile row in shared memory
 
-template <int QT>
+// EMIT (ScanEmit): all scores; the scores of the strided sample (compact row numbering, N = number
+// of sample rows); or only the rows at or above each classifier's threshold, appended to its list.
+template <int QT, int EMIT>
 __global__ __launch_bounds__(256) void dense_mfma_kernel(const uint8_t *__restrict__ X, long long N, int D,
                                                          long long row_bytes, const uint8_t *__restrict__ W,
                                                          const float *__restrict__ bias, float *__restrict__ scores,
-                                                         long long ld_scores, int vec_store) {
+                                                         long long ld_scores, int vec_store,
+                                                         const SelState *__restrict__ tau_state, SelState *st,
+                                                         unsigned long long *__restrict__ cand, const SelState *gate) {
     constexpr int QN = QT * 32;
+    if (gate && gate->fallback == 0u) return;     // uniform: only the fallback of a filtered scan
     __shared__ __attribute__((aligned(16))) uint8_t xs[kBM * kRowStride];
     __shared__ __attribute__((aligned(16))) uint8_t ws[QN * kRowStride];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -40,8 +45,12 @@ __global__ __launch_bounds__(256) void dense_mfma_kernel(const uint8_t *__restri
     const size_t w_row_bytes = (size_t)D * 2;
 
     float bq[QT];
+    uint32_t tau[QT];
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) bq[qt] = bias ? bias[qt * 32 + n] : 0.f;
+    for (int qt = 0; qt < QT; ++qt) {
+        bq[qt] = bias ? bias[qt * 32 + n] : 0.f;
+        tau[qt] = EMIT == kEmitFilter ? tau_state[qt * 32 + n].tau_key : 0u;
+    }
 
     for (long long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const long long row0 = tile * kBM;
@@ -59,6 +68,8 @@ __global__ __launch_bounds__(256) void dense_mfma_kernel(const uint8_t *__restri
             const int id = tid + 256 * u;
             long long row = row0 + (id >> 4);
             if (row >= N) row = N - 1;               // clamp: rows past the end are computed, never stored
+            if (EMIT == kEmitSample)                 // compact sample row -> store row
+                row = (row >> 10) * ((long long)kSampleGroup * kSampleStride) + (row & 1023);
             xsrc[u] = X + (size_t)row * row_bytes + (size_t)(id & 15) * 16;
         }
         auto load_step = [&](int ks) {
@@ -109,7 +120,19 @@ __global__ __launch_bounds__(256) void dense_mfma_kernel(const uint8_t *__restri
                 float o[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) o[j] = acc[qt][4 * g + j] + bq[qt];
-                if (vec_store && row + 3 < N) {
+                if (EMIT == kEmitFilter) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t key = float_to_key(o[j]);
+                        if (key >= tau[qt] && row + j < N) {
+                            const int q = qt * 32 + n;
+                            const uint32_t pos = atomicAdd(&st[q].cursor, 1u);
+                            if (pos < (uint32_t)kCandCap)
+                                cand[(size_t)q * kCandCap + pos] = ((unsigned long long)key << 32) |
+                                                                   (unsigned long long)(0xFFFFFFFFu - (uint32_t)(row + j));
+                        }
+                    }
+                } else if (vec_store && row + 3 < N) {
                     *reinterpret_cast<float4 *>(dst + row) = make_float4(o[0], o[1], o[2], o[3]);
                 } else {
 #pragma unroll
@@ -121,23 +144,31 @@ __global__ __launch_bounds__(256) void dense_mfma_kernel(const uint8_t *__restri
     }
 }
 
-// Q must be 32 or 64, D a multiple of 128, N >= 1.
-hipError_t launch_dense_mfma(const void *X, int64_t N, int D, int64_t ldx, const void *W, int Q, const float *bias,
-                             float *scores, int64_t ld_scores, hipStream_t s) {
+template <int QT>
+static hipError_t launch_mfma_qt(const uint8_t *X, int64_t N, int D, int64_t ldx, const uint8_t *W, const float *bias,
+                                 ScanEmit emit, float *scores, int64_t ld_scores, const SelState *tau, SelState *st,
+                                 unsigned long long *cand, const SelState *gate, hipStream_t s) {
     const int64_t ntiles = (N + kBM - 1) / kBM;
-    int grid = (int)std::min<int64_t>(ntiles, (int64_t)device_cu_count() * 3);
-    const int vec_store = (ld_scores % 4 == 0) && ((reinterpret_cast<uintptr_t>(scores) & 15) == 0);
+    const int grid = (int)std::min<int64_t>(ntiles, (int64_t)device_cu_count() * tune_int("OTF_MFMA_BLOCKS_PER_CU", 2));
+    const int vec_store = scores && (ld_scores % 4 == 0) && ((reinterpret_cast<uintptr_t>(scores) & 15) == 0);
+#define OTF_MFMA_ARGS X, (long long)N, D, (long long)ldx * 2, W, bias, scores, (long long)ld_scores, vec_store, tau, st, cand, gate
+    if (emit == kEmitScores) dense_mfma_kernel<QT, kEmitScores><<<grid, 256, 0, s>>>(OTF_MFMA_ARGS);
+    else if (emit == kEmitSample) dense_mfma_kernel<QT, kEmitSample><<<grid, 256, 0, s>>>(OTF_MFMA_ARGS);
+    else dense_mfma_kernel<QT, kEmitFilter><<<grid, 256, 0, s>>>(OTF_MFMA_ARGS);
+#undef OTF_MFMA_ARGS
+    return hipGetLastError();
+}
+
+// Q must be 32 or 64, D a multiple of 128, N >= 1 (for kEmitSample: N = sample rows, a multiple of 1024).
+// tau, st and cand point at the first of the Q classifiers of this call.
+hipError_t launch_dense_mfma(const void *X, int64_t N, int D, int64_t ldx, const void *W, int Q, const float *bias,
+                             ScanEmit emit, float *scores, int64_t ld_scores, const SelState *tau, SelState *st,
+                             unsigned long long *cand, const SelState *gate, hipStream_t s) {
     const uint8_t *Xb = reinterpret_cast<const uint8_t *>(X);
     const uint8_t *Wb = reinterpret_cast<const uint8_t *>(W);
-    if (Q == 32)
-        dense_mfma_kernel<1><<<grid, 256, 0, s>>>(Xb, (long long)N, D, (long long)ldx * 2, Wb, bias, scores,
-                                                  (long long)ld_scores, vec_store);
-    else if (Q == 64)
-        dense_mfma_kernel<2><<<grid, 256, 0, s>>>(Xb, (long long)N, D, (long long)ldx * 2, Wb, bias, scores,
-                                                  (long long)ld_scores, vec_store);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+    if (Q == 32) return launch_mfma_qt<1>(Xb, N, D, ldx, Wb, bias, emit, scores, ld_scores, tau, st, cand, gate, s);
+    if (Q == 64) return launch_mfma_qt<2>(Xb, N, D, ldx, Wb, bias, emit, scores, ld_scores, tau, st, cand, gate, s);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace otf

@@ -2,31 +2,42 @@
 //
 // PQ (paper Sec. 3, "Product quantization (PQ)"; Table 2: one byte per sub-block): the score of
 // a coded row is sum_m lut[m][code_m] with lut[m][k] = <w_m, centre_k of sub-block m>.
-// Binary (paper Sec. 3, "Binarization", Eq. (1)): the score is sum_d w_d (2 bit_d - 1).  Eight
-// consecutive dimensions form one byte g of the row, so with the table
-//     T[g][v] = sum_{j<8} (bit j of v ? +w[8g+j] : -w[8g+j])
-// the score is sum_g T[g][byte_g]: the same scan as PQ with M = D/8 "sub-blocks".  One table
-// lookup replaces eight signed adds, which keeps the scan below the vector-ALU ceiling.
+// Binary (paper Sec. 3, "Binarization", Eq. (1)): the score is sum_d w_d (2 bit_d - 1).  A group
+// of g consecutive dimensions forms an index v into the table
+//     T[group][v] = sum_{j<g} (bit j of v ? +w[first + j] : -w[first + j])
+// so the score is a sum of table entries: the same scan as PQ.  One lookup replaces g signed
+// adds, which keeps the scan below the vector-ALU ceiling.  Rows of up to 1024 bits use byte
+// groups (256-entry tables, 128 columns: 128 KiB of shared memory).  Rows of 2048 bits would need
+// 256 KiB that way, so each 32-bit word is cut into four 7-bit groups and one 4-bit group
+// instead: 256 columns of 128 entries plus 64 columns of 16 entries, 132 KiB, one pass per row.
 //
-// Both scans are one shared-memory gather per stored byte.  To keep the gathers free of bank
-// conflicts whatever the data, the table is stored value-major, image[v][column], so that the
-// bank of an access depends only on WHICH byte of the row is looked up, never on its value,
-// and lanes that execute the same instruction always look up different columns:
-//   * a row segment of 128 bytes is read by 8 lanes x 16 bytes (one 16-byte load per lane);
-//   * byte (dword tq, byte b) of lane-chunk c lives in column 32*tq + 4*c + b;
-//   * the four 128-byte segments handled by lanes 0..31 (and 32..63) read their dwords with
-//     four different byte rotations (b = tb ^ (segment & 3)), so at every step the 32 lanes
-//     touch columns 4*c + b with all 32 (c, b) pairs distinct: 32 lanes, 32 banks.
-// Rows shorter than 128 bytes are packed several to a segment (the table columns repeat);
-// rows longer than 128 bytes are processed in `nsplit` phases of 128 columns, the workgroup
-// reloading the table image between phases and carrying partial sums in the score array.
+// Both scans are one shared-memory gather per group.  To keep the gathers free of bank conflicts
+// whatever the data, the table is stored value-major, image[v][column], so that the bank of an
+// access depends only on WHICH group of the row is looked up, never on its value, and lanes that
+// execute the same instruction always look up different columns:
+//   * every lane loads 16 consecutive bytes of a row (4 words); 8 adjacent lanes cover 128 bytes;
+//   * group j of word tq of lane-chunk c lives in column (groups per word-column block)*tq + 4*c + j;
+//   * the four lane octets that execute together (lanes 0..31, and 32..63) read their words with
+//     four different group rotations (j = step ^ octet), so at every step the 32 lanes touch
+//     columns 4*c + j with all 32 (c, j) pairs distinct: 32 lanes, 32 banks.
+// Rows shorter than 128 bytes are packed several to a 128-byte segment (the table columns
+// repeat); byte-group rows longer than 128 bytes are processed in `nsplit` phases of 128 columns,
+// the workgroup reloading the table image between phases and carrying partial sums in the score
+// array.
+//
+// What a scan emits is a template parameter (ScanEmit): all scores plus the pass-1 histogram of
+// the selection; the scores of a strided sample of the rows; or, given a threshold, only the
+// rows at or above it, appended to a candidate list.  The last mode writes almost nothing, which
+// matters: interleaving even 3 % of score stores with the row stream costs ~20 % of HBM rate.
 #include "otf_internal.h"
 
 namespace otf {
 
-constexpr int kSegBytes = 128;                       // row bytes handled per phase
+constexpr int kSegBytes = 128;                       // row bytes handled per phase (byte groups)
 constexpr int kImageFloats = 256 * kSegBytes;        // one table image: 256 values x 128 columns
 constexpr int kImageBytes = kImageFloats * 4;        // 128 KiB
+constexpr int kSideFloats = 16 * 64;                 // 4-bit groups of a 2048-bit row: 16 values x 64 words
+constexpr int kImage7Bytes = kImageBytes + kSideFloats * 4;   // 7-bit groups: 128 values x 256 columns, + side
 constexpr int kScanMaxThreads = 1024;
 constexpr int kScanThreads = 512;
 
@@ -50,27 +61,44 @@ __global__ __launch_bounds__(256) void pq_build_lut_kernel(const float *__restri
     }
 }
 
+// Zeroes both selection states (full selection and sample thresholding) of one classifier.
+__device__ __forceinline__ void zero_states(int tid, int step, SelState *st, uint32_t *hist1, uint32_t *hist2,
+                                            SelState *sst, uint32_t *shist1, uint32_t *shist2) {
+    uint32_t *stw = reinterpret_cast<uint32_t *>(st), *sstw = reinterpret_cast<uint32_t *>(sst);
+    for (int i = tid; i < (int)(sizeof(SelState) / 4); i += step) {
+        stw[i] = 0u;
+        sstw[i] = 0u;
+    }
+    for (int i = tid; i < kBins1; i += step) {
+        hist1[i] = 0u;
+        shist1[i] = 0u;
+    }
+    for (int i = tid; i < kBins2; i += step) {
+        hist2[i] = 0u;
+        shist2[i] = 0u;
+    }
+}
+
 // Table images for PQ: image[sp][v][column(pos)] = lut[m][v],  m = sp*128 + pos (M >= 128) or
-// pos mod M (M < 128).  Also zeroes the selection state (one launch instead of two).
+// pos mod M (M < 128).  Also zeroes the selection states (one launch instead of two).
 __global__ __launch_bounds__(256) void pq_prepare_kernel(const float *__restrict__ lut, int M, int nsplit,
                                                          float *__restrict__ image, SelState *st, uint32_t *hist1,
-                                                         uint32_t *hist2) {
+                                                         uint32_t *hist2, SelState *sst, uint32_t *shist1,
+                                                         uint32_t *shist2) {
     const int tid = blockIdx.x * blockDim.x + threadIdx.x, step = gridDim.x * blockDim.x;
     for (int t = tid; t < nsplit * kImageFloats; t += step) {
         const int v = t & 255, pos = (t >> 8) & (kSegBytes - 1), sp = t >> 15;
         const int m = (M >= kSegBytes) ? sp * kSegBytes + pos : pos % M;
         image[(size_t)sp * kImageFloats + v * kSegBytes + image_column(pos)] = lut[(size_t)m * 256 + v];
     }
-    uint32_t *stw = reinterpret_cast<uint32_t *>(st);
-    for (int i = tid; i < (int)(sizeof(SelState) / 4); i += step) stw[i] = 0u;
-    for (int i = tid; i < kBins1; i += step) hist1[i] = 0u;
-    for (int i = tid; i < kBins2; i += step) hist2[i] = 0u;
+    zero_states(tid, step, st, hist1, hist2, sst, shist1, shist2);
 }
 
-// Table images for binary codes: byte g of a row covers dimensions 8g..8g+7, bit j = dim 8g+j.
+// Table images for binary codes with byte groups: byte g of a row covers dimensions 8g..8g+7.
 __global__ __launch_bounds__(256) void binary_prepare_kernel(const float *__restrict__ w, int row_bytes, int nsplit,
                                                              float *__restrict__ image, SelState *st, uint32_t *hist1,
-                                                             uint32_t *hist2) {
+                                                             uint32_t *hist2, SelState *sst, uint32_t *shist1,
+                                                             uint32_t *shist2) {
     const int tid = blockIdx.x * blockDim.x + threadIdx.x, step = gridDim.x * blockDim.x;
     for (int t = tid; t < nsplit * kImageFloats; t += step) {
         const int v = t & 255, pos = (t >> 8) & (kSegBytes - 1), sp = t >> 15;
@@ -83,10 +111,39 @@ __global__ __launch_bounds__(256) void binary_prepare_kernel(const float *__rest
         }
         image[(size_t)sp * kImageFloats + v * kSegBytes + image_column(pos)] = acc;
     }
-    uint32_t *stw = reinterpret_cast<uint32_t *>(st);
-    for (int i = tid; i < (int)(sizeof(SelState) / 4); i += step) stw[i] = 0u;
-    for (int i = tid; i < kBins1; i += step) hist1[i] = 0u;
-    for (int i = tid; i < kBins2; i += step) hist2[i] = 0u;
+    zero_states(tid, step, st, hist1, hist2, sst, shist1, shist2);
+}
+
+// Table image for 2048-bit rows: word q (0..63) of a row = lane-chunk q/4, word tq = q%4 of the chunk.
+//   main[v][64*tq + 4*chunk + j]  (v < 128)  group j of the word: dimensions 32q + 7j .. 32q + 7j + 6
+//   side[v][q]                    (v < 16)   the top four bits:   dimensions 32q + 28 .. 32q + 31
+__global__ __launch_bounds__(256) void binary7_prepare_kernel(const float *__restrict__ w, float *__restrict__ image,
+                                                              SelState *st, uint32_t *hist1, uint32_t *hist2,
+                                                              SelState *sst, uint32_t *shist1, uint32_t *shist2) {
+    const int tid = blockIdx.x * blockDim.x + threadIdx.x, step = gridDim.x * blockDim.x;
+    for (int t = tid; t < 128 * 256; t += step) {
+        const int v = t & 127, col = t >> 7;              // col = 4*q + j
+        const int q = col >> 2, j = col & 3;
+        float acc = 0.f;
+#pragma unroll
+        for (int b = 0; b < 7; ++b) {
+            const float wd = w[32 * q + 7 * j + b];
+            acc += ((v >> b) & 1) ? wd : -wd;
+        }
+        const int chunk = q >> 2, tq = q & 3;
+        image[v * 256 + 64 * tq + 4 * chunk + j] = acc;
+    }
+    for (int t = tid; t < kSideFloats; t += step) {
+        const int v = t & 15, q = t >> 4;
+        float acc = 0.f;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const float wd = w[32 * q + 28 + b];
+            acc += ((v >> b) & 1) ? wd : -wd;
+        }
+        image[kImageFloats + v * 64 + q] = acc;
+    }
+    zero_states(tid, step, st, hist1, hist2, sst, shist1, shist2);
 }
 
 template <int CTRL>
@@ -94,57 +151,68 @@ __device__ __forceinline__ float dpp_move(float v) {
     return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
 }
 
-// Sum over groups of LPR adjacent lanes (LPR = 1, 2, 4 or 8); every lane of a group receives it.
+// Sum over groups of LPR adjacent lanes (LPR = 1, 2, 4, 8 or 16); every lane of a group receives it.
 template <int LPR>
 __device__ __forceinline__ float group_sum(float v) {
     if (LPR >= 2) v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]: lane ^ 1
     if (LPR >= 4) v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]: lane ^ 2
     if (LPR >= 8) v += dpp_move<0x141>(v);   // row_half_mirror: lane i <-> 7 - i of each 8
+    if (LPR >= 16) v += dpp_move<0x140>(v);  // row_mirror: lane i <-> 15 - i of each 16
     return v;
 }
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Scan.  LPR = lanes per stored row within one phase = min(M, 128) / 16;  U = 16-byte loads per
-// lane per tile;  SPLIT = rows longer than 128 bytes (several phases, partial sums carried in
-// the score array).
+// Scan.
+//   GB     bits per group: 8 (bytes; LPR = min(row bytes, 128) / 16 lanes per row per phase) or 7
+//          (2048-bit rows, LPR = 16, each word = 4 x 7 bits + 4 bits)
+//   U      16-byte loads per lane per tile
+//   EMIT   what is produced (ScanEmit)
+//   SPLIT  byte-group rows longer than 128 bytes: several phases, partial sums carried in the score
+//          array (EMIT = kEmitScores only)
 //
 // The main loop is branch-free and software-pipelined: the loads of the wave's next tile are
-// issued before the current tile is looked up, and tiles or rows past the end are redirected
-// to the block's last row rather than skipped (an unconditional load keeps the in-order wait
+// issued before the current tile is looked up, and prefetches past the end re-read the block's
+// last full tile rather than being skipped (an unconditional load keeps the in-order wait
 // counters exact).  After the lookups the U row sums of a lane group are moved into U different
-// lanes so that storing, histogramming and (SPLIT) carrying happen once per tile, not per row.
-template <int LPR, int U, bool SPLIT, int MODE = 0>
-__global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(const uint8_t *__restrict__ codes, long long N,
-                                                                  int M, int nsplit,
-                                                                  const float *__restrict__ image, float bias,
-                                                                  float *__restrict__ scores, SelState *st,
-                                                                  uint32_t *hist1, int k) {
+// lanes so that the output step happens once per tile, not per row.
+template <int LPR, int U, int GB, int EMIT, bool SPLIT>
+__global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
+    const uint8_t *__restrict__ codes, long long N, int M, int nsplit, const float *__restrict__ image, float bias,
+    float *__restrict__ scores, SelState *st, uint32_t *hist1, int k, const SelState *tau_state,
+    unsigned long long *__restrict__ cand, const SelState *gate) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    float *table = reinterpret_cast<float *>(lds_raw);          // kImageFloats
-    __shared__ uint32_t lhist[kBins1];
+    __shared__ uint32_t lhist[EMIT == kEmitFilter ? 1 : kBins1];
     __shared__ uint32_t s_flag;
+    if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
     constexpr int RPW = 64 / LPR;                // rows per wave load
     constexpr int TILE = RPW * U;                // rows per wave iteration
     constexpr int ACTIVE = LPR < U ? LPR : U;    // lanes of a group that own an output row per round
     constexpr int ROUNDS = U / ACTIVE;           // output rounds per tile
+    constexpr int VSHIFT = GB == 8 ? 9 : 10;     // log2 of the byte stride between table values
+    constexpr int TQ_BYTES = GB == 8 ? 128 : 256;  // byte distance between the column blocks of the 4 words
+    constexpr int TABLE_VEC = (GB == 8 ? kImageBytes : kImage7Bytes) / 16;
 
-    for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
+    if (EMIT != kEmitFilter)
+        for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
+    const uint32_t tau = EMIT == kEmitFilter ? tau_state->tau_key : 0u;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    const int c = lane & 7;                      // 16-byte chunk inside the 128-byte segment
-    const int seg = lane >> 3;                   // segment inside the wave load
-    const int sub = lane % LPR, rr = lane / LPR; // chunk inside the row, row inside the wave load
+    const int chunk = GB == 8 ? (lane & 7) : (lane & 15);   // 16-byte chunk inside the table's row span
+    const int octet = (lane >> 3) & 3;                       // which of the 4 lane octets that execute together
+    const int sub = lane % LPR, rr = lane / LPR;             // chunk inside the row, row inside the wave load
     uint32_t shift[4], colbyte[4];
 #pragma unroll
-    for (int tb = 0; tb < 4; ++tb) {
-        const int b = tb ^ (seg & 3);
-        shift[tb] = 8u * (uint32_t)b;
-        colbyte[tb] = 4u * (uint32_t)(4 * c + b);
+    for (int t = 0; t < 4; ++t) {
+        const int j = t ^ octet;
+        shift[t] = (uint32_t)(GB * j);
+        colbyte[t] = 4u * (uint32_t)(4 * chunk + j);
     }
+    const uint32_t sidecol = (uint32_t)(kImageBytes + 16 * chunk);   // GB == 7 only
 
     // this block's rows: a contiguous range, a multiple of 1024 rows long (TILE divides 1024, so
-    // only the last block of the grid can end in a partial tile)
+    // only the last block of the grid can end in a partial tile).  For the sample scan the rows
+    // are numbered compactly: sample row v is store row (v / 1024) * 1024 * stride + v % 1024.
     long long per = (N + gridDim.x - 1) / gridDim.x;
     per = (per + 1023) / 1024 * 1024;
     long long begin = per * blockIdx.x, end = begin + per;
@@ -152,81 +220,99 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(const uint8
     if (end > N) end = N;
     const long long nfull = (end - begin) / TILE;          // full tiles
     const int rem = (int)((end - begin) % TILE);           // rows of the partial tile, if any
-    const size_t tile_bytes = (size_t)TILE * (size_t)M;
     const size_t u_bytes = (size_t)RPW * (size_t)M;        // distance between the U loads of a lane
-    const int out_u = sub % ACTIVE;                        // which of a round's rows this lane stores
+    const int out_u = sub % ACTIVE;                        // which of a round's rows this lane emits
+    auto store_row = [&](long long v) {                    // store row of compact row v
+        return EMIT == kEmitSample ? ((v >> 10) * ((long long)kSampleGroup * kSampleStride) + (v & 1023)) : v;
+    };
 
     auto lookup16 = [&](const u32x4 &d) {
-        if (MODE == 1) return __uint_as_float((d[0] ^ d[1] ^ d[2] ^ d[3]) & 0x3fffffffu);
         uint32_t addr[16];
 #pragma unroll
         for (int tq = 0; tq < 4; ++tq)
 #pragma unroll
-            for (int tb = 0; tb < 4; ++tb)
-                addr[4 * tq + tb] = (__builtin_amdgcn_ubfe(d[tq], shift[tb], 8u) << 9) + colbyte[tb];
-        float t[16];
+            for (int t = 0; t < 4; ++t)
+                addr[4 * tq + t] = (__builtin_amdgcn_ubfe(d[tq], shift[t], (uint32_t)GB) << VSHIFT) + colbyte[t];
+        float v[16];
 #pragma unroll
         for (int tq = 0; tq < 4; ++tq)
 #pragma unroll
-            for (int tb = 0; tb < 4; ++tb)
-                t[4 * tq + tb] = *reinterpret_cast<const float *>(lds_raw + addr[4 * tq + tb] + 128 * tq);
+            for (int t = 0; t < 4; ++t)
+                v[4 * tq + t] = *reinterpret_cast<const float *>(lds_raw + addr[4 * tq + t] + TQ_BYTES * tq);
+        if (GB == 7) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) t[i] += t[i + 8];
+            for (int tq = 0; tq < 4; ++tq)
+                v[4 * tq] += *reinterpret_cast<const float *>(lds_raw + ((d[tq] >> 28) << 8) + sidecol + 4 * tq);
+        }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) t[i] += t[i + 4];
-        return group_sum<LPR>((t[0] + t[1]) + (t[2] + t[3]));
+        for (int i = 0; i < 8; ++i) v[i] += v[i + 8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] += v[i + 4];
+        return group_sum<LPR>((v[0] + v[1]) + (v[2] + v[3]));
     };
 
     for (int sp = 0; sp < nsplit; ++sp) {
         __syncthreads();                          // previous phase done with the table
         {
             const u32x4 *src = reinterpret_cast<const u32x4 *>(image + (size_t)sp * kImageFloats);
-            u32x4 *dst = reinterpret_cast<u32x4 *>(table);
-            for (int i = threadIdx.x; i < kImageFloats / 4; i += blockDim.x) dst[i] = src[i];
+            u32x4 *dst = reinterpret_cast<u32x4 *>(lds_raw);
+            for (int i = threadIdx.x; i < TABLE_VEC; i += blockDim.x) dst[i] = src[i];
         }
         __syncthreads();
         const bool first = sp == 0, lastp = sp == nsplit - 1;
-        // lane's address in tile 0 of the block: row (begin + rr), this phase's columns
-        const uint8_t *lane_codes = codes + (size_t)(begin + rr) * (size_t)M + (size_t)sp * kSegBytes + (size_t)sub * 16;
-        // first row this lane stores in tile 0 (round 0)
-        float *lane_scores = scores + begin + (long long)out_u * RPW + rr;
+        // byte offset of this lane inside its row (this phase's columns) plus its row inside the wave load
+        const size_t lane_off = (size_t)rr * (size_t)M + (size_t)sp * kSegBytes + (size_t)sub * 16;
 
-        // one output round: the U row sums of a lane group go to U different lanes, which store
-        auto emit = [&](const float *s, const float *carry, float *dst, int e, bool ok) {
-            float mine = s[e * ACTIVE];
-#pragma unroll
-            for (int a = 1; a < ACTIVE; ++a) mine = out_u == a ? s[e * ACTIVE + a] : mine;
+        // one output round: lane `sub` of each group holds in `mine` the sum of the row it owns
+        auto emit = [&](float mine, const float *carry, long long v, int e, bool ok) {
             if (sub < ACTIVE && ok) {
                 if (SPLIT && !first) mine += carry[e];
-                if (lastp) {
-                    mine += bias;
-                    atomicAdd(&lhist[float_to_key(mine) >> 20], 1u);
+                if (lastp) mine += bias;
+                if (EMIT == kEmitFilter) {
+                    const uint32_t key = float_to_key(mine);
+                    if (key >= tau) {
+                        const uint32_t pos = atomicAdd(&st->cursor, 1u);
+                        if (pos < (uint32_t)kCandCap)
+                            cand[pos] = ((unsigned long long)key << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)v);
+                    }
+                } else {
+                    if (lastp) atomicAdd(&lhist[float_to_key(mine) >> 20], 1u);
+                    scores[v] = mine;
                 }
-                *dst = mine;
             }
         };
+        // looks up the U loads of a tile; the U row sums of a lane group (every lane of the group
+        // holds each sum) are kept by U different lanes: lane out_u keeps row e*ACTIVE + out_u
+        auto tile_sums = [&](const u32x4 *d, float *mine) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float su = lookup16(d[u]);
+                if (u % ACTIVE == 0) mine[u / ACTIVE] = su;
+                else mine[u / ACTIVE] = out_u == (u % ACTIVE) ? su : mine[u / ACTIVE];
+            }
+        };
+        // compact row that lane `sub` of its group emits in round e of the tile starting at row v0
+        auto out_row = [&](long long v0, int e) { return v0 + (long long)(e * ACTIVE + out_u) * RPW + rr; };
 
         if (wave < nfull) {                       // uniform per wave
             auto fetch = [&](u32x4 *d, float *carry, long long tile) {
                 if (tile > nfull - 1) tile = nfull - 1;      // uniform: prefetch past the end re-reads the last tile
-                if (MODE == 2 && tile >= 2 * nwaves) return;
-                const uint8_t *p = lane_codes + (size_t)tile * tile_bytes;
+                const long long v0 = begin + tile * TILE;
+                const uint8_t *p = codes + (size_t)store_row(v0) * (size_t)M + lane_off;
 #pragma unroll
                 for (int u = 0; u < U; ++u)
                     d[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + (size_t)u * u_bytes));
                 if (SPLIT) {
-                    const float *q = lane_scores + tile * TILE;
 #pragma unroll
-                    for (int e = 0; e < ROUNDS; ++e) carry[e] = q[e * ACTIVE * RPW];
+                    for (int e = 0; e < ROUNDS; ++e) carry[e] = scores[out_row(v0, e)];
                 }
             };
             auto consume = [&](const u32x4 *d, const float *carry, long long tile) {
-                float s[U];
+                float mine[ROUNDS];
+                tile_sums(d, mine);
+                const long long v0 = begin + tile * TILE;
 #pragma unroll
-                for (int u = 0; u < U; ++u) s[u] = lookup16(d[u]);
-                float *q = lane_scores + tile * TILE;
-#pragma unroll
-                for (int e = 0; e < ROUNDS; ++e) emit(s, carry, q + e * ACTIVE * RPW, e, true);
+                for (int e = 0; e < ROUNDS; ++e) emit(mine[e], carry, out_row(v0, e), e, true);
             };
             u32x4 da[U], db[U];
             float ca[ROUNDS], cb[ROUNDS];
@@ -239,32 +325,30 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(const uint8
             }
         }
         if (rem > 0 && wave == (int)(nfull % nwaves)) {   // the partial tile: same steps, row-checked
-            const long long row0 = begin + nfull * TILE;
+            const long long v0 = begin + nfull * TILE;
             u32x4 d[U];
-            float carry[ROUNDS], s[U];
+            float carry[ROUNDS], mine[ROUNDS];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const long long row = row0 + (long long)u * RPW + rr;
+                const long long v = v0 + (long long)u * RPW + rr;
                 d[u] = (u32x4){0u, 0u, 0u, 0u};
-                if (row < end)
-                    d[u] = *reinterpret_cast<const u32x4 *>(codes + (size_t)row * (size_t)M + (size_t)sp * kSegBytes +
-                                                            (size_t)sub * 16);
+                if (v < end)
+                    d[u] = *reinterpret_cast<const u32x4 *>(codes + (size_t)store_row(v - rr) * (size_t)M + lane_off);
             }
 #pragma unroll
             for (int e = 0; e < ROUNDS; ++e) {
-                const long long row = row0 + (long long)(e * ACTIVE + out_u) * RPW + rr;
-                carry[e] = (SPLIT && !first && row < end) ? scores[row] : 0.f;
+                const long long v = out_row(v0, e);
+                carry[e] = (SPLIT && !first && v < end) ? scores[v] : 0.f;
             }
-#pragma unroll
-            for (int u = 0; u < U; ++u) s[u] = lookup16(d[u]);
+            tile_sums(d, mine);
 #pragma unroll
             for (int e = 0; e < ROUNDS; ++e) {
-                const long long row = row0 + (long long)(e * ACTIVE + out_u) * RPW + rr;
-                emit(s, carry, scores + row, e, row < end);
+                const long long v = out_row(v0, e);
+                emit(mine[e], carry, v, e, v < end);
             }
         }
     }
-    finish_pass1(lhist, hist1, st, (uint32_t)k, gridDim.x, &s_flag);
+    if (EMIT != kEmitFilter) finish_pass1(lhist, hist1, st, (uint32_t)k, gridDim.x, &s_flag);
 }
 
 hipError_t launch_pq_build_lut(const float *codebooks, int M, int K, int dsub, const float *w, float *lut,
@@ -277,58 +361,84 @@ hipError_t launch_pq_build_lut(const float *codebooks, int M, int K, int dsub, c
 
 static int splits_of(int row_bytes) { return row_bytes >= kSegBytes ? row_bytes / kSegBytes : 1; }
 
-hipError_t launch_pq_prepare(const float *lut, int M, float *image, const SelectWs &sw, hipStream_t s) {
+hipError_t launch_pq_prepare(const float *lut, int M, float *image, const SelectWs &sw, const SelectWs &ssw,
+                             hipStream_t s) {
     const int nsplit = splits_of(M);
-    pq_prepare_kernel<<<nsplit * 32, 256, 0, s>>>(lut, M, nsplit, image, sw.st, sw.hist1, sw.hist2);
+    pq_prepare_kernel<<<nsplit * 32, 256, 0, s>>>(lut, M, nsplit, image, sw.st, sw.hist1, sw.hist2, ssw.st, ssw.hist1,
+                                                  ssw.hist2);
     return hipGetLastError();
 }
 
-hipError_t launch_binary_prepare(const float *w, int D, float *image, const SelectWs &sw, hipStream_t s) {
+// D == 2048 builds the 7-bit image, every other supported D the byte images.
+hipError_t launch_binary_prepare(const float *w, int D, float *image, const SelectWs &sw, const SelectWs &ssw,
+                                 hipStream_t s) {
+    if (D == 2048) {
+        binary7_prepare_kernel<<<64, 256, 0, s>>>(w, image, sw.st, sw.hist1, sw.hist2, ssw.st, ssw.hist1, ssw.hist2);
+        return hipGetLastError();
+    }
     const int row_bytes = D / 8, nsplit = splits_of(row_bytes);
-    binary_prepare_kernel<<<nsplit * 32, 256, 0, s>>>(w, row_bytes, nsplit, image, sw.st, sw.hist1, sw.hist2);
+    binary_prepare_kernel<<<nsplit * 32, 256, 0, s>>>(w, row_bytes, nsplit, image, sw.st, sw.hist1, sw.hist2, ssw.st,
+                                                      ssw.hist1, ssw.hist2);
     return hipGetLastError();
 }
 
-template <int LPR, int U, bool SPLIT, int MODE = 0>
-static hipError_t launch_scan_cfg(const uint8_t *codes, int64_t N, int M, int nsplit, const float *image, float bias,
-                                  float *scores, SelState *st, uint32_t *hist1, int k, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&table_scan_kernel<LPR, U, SPLIT, MODE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kImageBytes);
+struct ScanArgs {
+    const uint8_t *codes;
+    int64_t N;
+    int M, nsplit;
+    const float *image;
+    float bias;
+    float *scores;
+    SelState *st;
+    uint32_t *hist1;
+    int k;
+    const SelState *tau;
+    unsigned long long *cand;
+    const SelState *gate;
+};
+
+template <int LPR, int U, int GB, int EMIT, bool SPLIT>
+static hipError_t launch_scan_cfg(const ScanArgs &a, hipStream_t s) {
+    constexpr int lds = GB == 8 ? kImageBytes : kImage7Bytes;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&table_scan_kernel<LPR, U, GB, EMIT, SPLIT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     int grid = device_cu_count();
-    const int64_t max_useful = (N + 1023) / 1024;
+    const int64_t max_useful = (a.N + 1023) / 1024;
     if (grid > max_useful) grid = (int)max_useful;
     if (grid < 1) grid = 1;
     const int threads = tune_int("OTF_SCAN_THREADS", kScanThreads);
-    table_scan_kernel<LPR, U, SPLIT, MODE><<<grid, threads, kImageBytes, s>>>(codes, (long long)N, M, nsplit, image, bias,
-                                                                        scores, st, hist1, k);
+    table_scan_kernel<LPR, U, GB, EMIT, SPLIT><<<grid, threads, lds, s>>>(
+        a.codes, (long long)a.N, a.M, a.nsplit, a.image, a.bias, a.scores, a.st, a.hist1, a.k, a.tau, a.cand, a.gate);
     return hipGetLastError();
 }
 
-template <int LPR>
-static hipError_t launch_scan_lpr(const uint8_t *codes, int64_t N, int M, int nsplit, const float *image, float bias,
-                                  float *scores, SelState *st, uint32_t *hist1, int k, hipStream_t s) {
-    const int u = tune_int("OTF_SCAN_UNROLL", 8);
-    const int mode = tune_int("OTF_SCAN_MODE", 0);
-    if (LPR == 8 && mode == 1) return launch_scan_cfg<LPR, 4, false, 1>(codes, N, M, 1, image, bias, scores, st, hist1, k, s);
-    if (LPR == 8 && mode == 2) return launch_scan_cfg<LPR, 4, false, 2>(codes, N, M, 1, image, bias, scores, st, hist1, k, s);
-    if (nsplit > 1) {
-        if (u == 8) return launch_scan_cfg<LPR, 8, true>(codes, N, M, nsplit, image, bias, scores, st, hist1, k, s);
-        return launch_scan_cfg<LPR, 4, true>(codes, N, M, nsplit, image, bias, scores, st, hist1, k, s);
+template <int LPR, int GB>
+static hipError_t launch_scan_emit(const ScanArgs &a, ScanEmit emit, hipStream_t s) {
+    constexpr int U = LPR <= 2 ? 4 : 8;    // narrow rows own many outputs per lane: fewer loads per tile
+    if (a.nsplit > 1) {
+        if (GB != 8 || emit != kEmitScores) return hipErrorInvalidValue;
+        return launch_scan_cfg<LPR, U, 8, kEmitScores, true>(a, s);
     }
-    if (u == 8) return launch_scan_cfg<LPR, 8, false>(codes, N, M, nsplit, image, bias, scores, st, hist1, k, s);
-    return launch_scan_cfg<LPR, 4, false>(codes, N, M, nsplit, image, bias, scores, st, hist1, k, s);
+    switch (emit) {
+        case kEmitScores: return launch_scan_cfg<LPR, U, GB, kEmitScores, false>(a, s);
+        case kEmitSample: return launch_scan_cfg<LPR, U, GB, kEmitSample, false>(a, s);
+        default: return launch_scan_cfg<LPR, U, GB, kEmitFilter, false>(a, s);
+    }
 }
 
-// M = stored bytes per row: 16, 32, 64 or a multiple of 128.
-hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int M, const float *image, float bias, float *scores,
-                             SelState *st, uint32_t *hist1, int k, hipStream_t s) {
-    const int nsplit = splits_of(M);
-    switch (M) {
-        case 16: return launch_scan_lpr<1>(codes, N, M, nsplit, image, bias, scores, st, hist1, k, s);
-        case 32: return launch_scan_lpr<2>(codes, N, M, nsplit, image, bias, scores, st, hist1, k, s);
-        case 64: return launch_scan_lpr<4>(codes, N, M, nsplit, image, bias, scores, st, hist1, k, s);
-        default: return launch_scan_lpr<8>(codes, N, M, nsplit, image, bias, scores, st, hist1, k, s);
+// row_bytes = stored bytes per row: 16, 32, 64 or a multiple of 128; seven_bit only with 256.
+hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, int seven_bit, const float *image,
+                             float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
+                             const SelState *tau, unsigned long long *cand, const SelState *gate, hipStream_t s) {
+    ScanArgs a{codes, N, row_bytes, seven_bit ? 1 : splits_of(row_bytes), image, bias, scores, st, hist1, k, tau, cand,
+               gate};
+    if (seven_bit) return launch_scan_emit<16, 7>(a, emit, s);
+    switch (row_bytes) {
+        case 16: return launch_scan_emit<1, 8>(a, emit, s);
+        case 32: return launch_scan_emit<2, 8>(a, emit, s);
+        case 64: return launch_scan_emit<4, 8>(a, emit, s);
+        default: return launch_scan_emit<8, 8>(a, emit, s);
     }
 }
 

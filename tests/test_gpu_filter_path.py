@@ -1,0 +1,155 @@
+"""GPU parity of the filtered scans (stores of a million rows or more, k <= 1024, no all_scores
+output): a strided sample of the store sets a threshold, the scan keeps only rows at or above it,
+and a full selection stands behind it in case the list cannot serve.  Checked here: parity with
+the CPU oracle, bit-identical results with the full-selection path, and the cases built to make
+the candidate list fail (too few rows, too many rows, every score equal)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_1407_4764_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+RTOL32 = 1e-4
+RTOL16 = 2e-3
+SEED = synth.BASE_SEED + 1000
+DEV = "cuda"
+
+
+def _both_paths(fn):
+    """Runs fn() once on the default path and once with the full selection forced."""
+    a = fn()
+    torch.cuda.synchronize()
+    a = (a[0].clone(), a[1].clone())
+    os.environ["OTF_RANK_PATH"] = "1"
+    try:
+        b = fn()
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["OTF_RANK_PATH"]
+    return a, (b[0].clone(), b[1].clone())
+
+
+@pytest.mark.parametrize("N,M,dsub,k", [(1200003, 128, 16, 1000), (1150000, 32, 4, 100), (1100000, 64, 8, 1)])
+def test_pq_filtered_scan(oracle, N, M, dsub, k):
+    K = 256
+    cb = synth.pq_codebooks(M, K, dsub, SEED + 1)
+    codes = synth.pq_codes(N, M, K, SEED + 2)
+    w = synth.normal_vector(M * dsub, 1.0, SEED + 3)
+    cd, lut = codes.to(DEV), binding.pq_build_lut(cb.to(DEV), w.to(DEV))
+    ws = binding.make_workspace(N, k)
+    (val, idx), (val2, idx2) = _both_paths(lambda: binding.rank_pq(cd, lut, 0.125, k, ws))
+    assert torch.equal(idx, idx2) and torch.equal(val, val2)
+    os.environ.pop("OTF_RANK_PATH", None)
+    binding.rank_pq(cd, lut, 0.125, k, ws)
+    assert not binding.debug_fallback_taken(ws)
+    ref = oracle.pq_scores_reconstruct(codes.numpy(), cb.numpy(), w.numpy(), 0.125)
+    ok, msg = oracle.topk_parity_ok(ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), RTOL32)
+    assert ok, msg
+
+
+@pytest.mark.parametrize("N,D,k", [(1100000, 2048, 1000), (1300000, 1024, 64), (2200000, 256, 10)])
+def test_binary_filtered_scan(oracle, N, D, k):
+    bits = synth.binary_bits_random(N, D // 32, SEED + 4)
+    w = synth.normal_vector(D, 1.0, SEED + 5)
+    bd, wd = bits.to(DEV), w.to(DEV)
+    ws = binding.make_workspace(N, k)
+    (val, idx), (val2, idx2) = _both_paths(lambda: binding.rank_binary(bd, D, wd, 0.0, k, ws))
+    assert torch.equal(idx, idx2) and torch.equal(val, val2)
+    binding.rank_binary(bd, D, wd, 0.0, k, ws)
+    assert not binding.debug_fallback_taken(ws)
+    ref = oracle.binary_scores(synth.as_uint32(bits.numpy()), D, w.numpy(), 0.0)
+    ok, msg = oracle.topk_parity_ok(ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), RTOL32)
+    assert ok, msg
+
+
+def test_binary_2048_bit_groups_are_exact(oracle):
+    """The 2048-bit layout cuts every word into 7+7+7+7+4 bits.  With integer weights all sums
+    are exact, so the full scores must equal the oracle's bit for bit -- for random rows and for
+    every single-bit row (any slip in a group boundary or table column shows)."""
+    D = 2048
+    g = torch.Generator().manual_seed(SEED + 6)
+    w = torch.randint(-512, 512, (D,), generator=g).to(torch.float32)
+    rand = synth.binary_bits_random(3000, D // 32, SEED + 7)
+    single = torch.zeros((D, D // 32), dtype=torch.int64)
+    d = torch.arange(D)
+    single[d, d // 32] = 1 << (d % 32)
+    single = torch.where(single >= 2 ** 31, single - 2 ** 32, single).to(torch.int32)
+    bits = torch.cat([rand, single])
+    N = bits.shape[0]
+    ref = oracle.binary_scores(synth.as_uint32(bits.numpy()), D, w.numpy(), 1.0)
+    ws = binding.make_workspace(N, 10)
+    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
+    binding.rank_binary(bits.to(DEV), D, w.to(DEV), 1.0, 10, ws, all_scores=all_scores)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(all_scores.cpu().numpy().astype(np.float64), ref)
+
+
+def test_multi_classifier_filtered_scan(oracle):
+    N, D, Q, k = 1060000, 128, 64, 100
+    X = synth.dense_features(N, D, SEED + 8, dtype=torch.float16)
+    W = synth.normal_matrix(Q, D, 0.05, SEED + 9, dtype=torch.float16)
+    b = synth.normal_vector(Q, 0.01, SEED + 10)
+    Xd, Wd, bd = X.to(DEV), W.to(DEV), b.to(DEV)
+    ws = binding.make_workspace(N, k, Q)
+    (val, idx), (val2, idx2) = _both_paths(lambda: binding.rank_dense(Xd, Wd, bd, k, ws))
+    assert torch.equal(idx, idx2) and torch.equal(val, val2)
+    binding.rank_dense(Xd, Wd, bd, k, ws)
+    assert not binding.debug_fallback_taken(ws)
+    ref = oracle.dense_scores(X.numpy(), W.numpy(), b.numpy())
+    for q in range(0, Q, 7):
+        ok, msg = oracle.topk_parity_ok(ref[q], k, idx[q].cpu().numpy(), val[q].cpu().numpy(), RTOL16)
+        assert ok, "q=%d: %s" % (q, msg)
+
+
+def _planted_pq(N, rows_to_plant, seed):
+    """PQ store whose planted rows all carry the best code of every sub-block (the maximum score)."""
+    M, K, dsub = 128, 256, 4
+    cb = synth.pq_codebooks(M, K, dsub, seed)
+    codes = synth.pq_codes(N, M, K, seed + 1)
+    w = synth.normal_vector(M * dsub, 1.0, seed + 2)
+    lut = binding.pq_build_lut(cb.to(DEV), w.to(DEV))
+    torch.cuda.synchronize()
+    best = lut.argmax(dim=1).to(torch.uint8).cpu()
+    codes[rows_to_plant] = best
+    return cb, codes, w, lut
+
+
+def test_filter_falls_back_when_the_sample_overestimates(oracle):
+    """200 maximal rows sit inside the sampled groups only: the sample's threshold lands on them,
+    so fewer than k rows pass and the ranking must be redone by full selection."""
+    N, k = 1200000, 1000
+    cb, codes, w, lut = _planted_pq(N, torch.arange(0, 200), SEED + 11)       # rows 0..199 are sampled
+    ws = binding.make_workspace(N, k)
+    val, idx = binding.rank_pq(codes.to(DEV), lut, 0.0, k, ws)
+    assert binding.debug_fallback_taken(ws)
+    ref = oracle.pq_scores_reconstruct(codes.numpy(), cb.numpy(), w.numpy(), 0.0)
+    ok, msg = oracle.topk_parity_ok(ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), RTOL32)
+    assert ok, msg
+    assert set(idx[0, :200].cpu().tolist()) == set(range(200))
+
+
+def test_filter_falls_back_when_the_sample_underestimates(oracle):
+    """10,000 maximal rows sit outside every sampled group: the threshold comes from the bulk, the
+    list overflows, and the full selection has to split a 10,000-way tie by row index."""
+    N, k = 1200000, 1000
+    cb, codes, w, lut = _planted_pq(N, torch.arange(2048, 12048), SEED + 12)   # groups 2..11: never sampled
+    ws = binding.make_workspace(N, k)
+    val, idx = binding.rank_pq(codes.to(DEV), lut, 0.0, k, ws)
+    assert binding.debug_fallback_taken(ws)
+    np.testing.assert_array_equal(idx[0].cpu().numpy(), np.arange(2048, 3048))
+    assert torch.all(val[0] == val[0, 0])
+
+
+def test_filter_with_every_score_equal(oracle):
+    """A zero model scores every row the same: the answer is rows 0..k-1."""
+    N, D, k = 1100000, 2048, 500
+    bits = synth.binary_bits_random(N, D // 32, SEED + 13).to(DEV)
+    ws = binding.make_workspace(N, k)
+    val, idx = binding.rank_binary(bits, D, torch.zeros(D, device=DEV), 2.5, k, ws)
+    assert binding.debug_fallback_taken(ws)
+    np.testing.assert_array_equal(idx[0].cpu().numpy(), np.arange(k))
+    assert torch.all(val[0] == 2.5)
