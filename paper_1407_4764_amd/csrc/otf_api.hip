@@ -26,6 +26,7 @@ WsLayout ws_layout(int64_t N, int32_t Q) {
     L.st = take((size_t)Q * sizeof(SelState));
     L.hist1 = take((size_t)Q * kBins1 * 4);
     L.hist2 = take((size_t)Q * kBins2 * 4);
+    L.hist3 = take((size_t)Q * kBins3 * 4);
     L.blockhist3 = take((size_t)Q * kSelBlocks * kBins3 * 4);
     L.eqoff = take((size_t)Q * kSelBlocks * 4);
     L.cand = take((size_t)Q * kCandCap * 8);
@@ -46,6 +47,7 @@ SelectWs select_ws(void *ws, const WsLayout &L) {
     sw.st = reinterpret_cast<SelState *>(p + L.st);
     sw.hist1 = reinterpret_cast<uint32_t *>(p + L.hist1);
     sw.hist2 = reinterpret_cast<uint32_t *>(p + L.hist2);
+    sw.hist3 = reinterpret_cast<uint32_t *>(p + L.hist3);
     sw.blockhist3 = reinterpret_cast<uint32_t *>(p + L.blockhist3);
     sw.eqoff = reinterpret_cast<uint32_t *>(p + L.eqoff);
     sw.cand = reinterpret_cast<unsigned long long *>(p + L.cand);
@@ -59,6 +61,7 @@ SelectWs sample_select_ws(void *ws, const WsLayout &L) {
     sw.st = reinterpret_cast<SelState *>(p + L.sample_st);
     sw.hist1 = reinterpret_cast<uint32_t *>(p + L.sample_hist1);
     sw.hist2 = reinterpret_cast<uint32_t *>(p + L.sample_hist2);
+    sw.hist3 = nullptr;
     sw.blockhist3 = nullptr;
     sw.eqoff = nullptr;
     sw.cand = nullptr;
@@ -175,7 +178,7 @@ int otf_topk(const float *scores, int64_t N, int64_t ld, int32_t Q, int32_t k, f
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     SelectWs sw = select_ws(ws, L);
     hipError_t e = launch_select_init(sw, Q, s);
-    if (e == hipSuccess) e = launch_hist1(scores, N, ld, Q, k, sw, 0, s);
+    if (e == hipSuccess) e = launch_hist1(scores, N, ld, Q, sw, 0, s);
     if (e == hipSuccess) e = launch_select_tail(scores, N, ld, Q, k, sw, out_scores, out_idx, 0, s);
     return hip_status(e);
 }
@@ -227,14 +230,14 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
         const int m = sample_rank(N, Nv);
         if (e == hipSuccess) e = launch_select_init(ssw, Q, s);
         if (e == hipSuccess) e = mfma_scan(Nv, kEmitSample, sample, L.sample_ld, nullptr, nullptr, nullptr, nullptr);
-        if (e == hipSuccess) e = launch_hist1(sample, Nv, L.sample_ld, Q, m, ssw, 0, s);
-        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, Q, m, ssw, s);
+        if (e == hipSuccess) e = launch_hist1(sample, Nv, L.sample_ld, Q, ssw, 0, s);
+        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, Q, m, ssw, 1, s);
         ScanTimer timer(s);
         if (e == hipSuccess) e = mfma_scan(N, kEmitFilter, nullptr, 0, ssw.st, sw.st, sw.cand, nullptr);
         timer.stop();
         if (e == hipSuccess) e = launch_filter_sort(sw, Q, k, out_scores, out_idx, s);
         if (e == hipSuccess) e = mfma_scan(N, kEmitScores, S, ldS, nullptr, nullptr, nullptr, sw.st);
-        if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, k, sw, 1, s);
+        if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, sw, 1, s);
         if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, 1, s);
         return hip_status(e);
     }
@@ -242,11 +245,11 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
     if (e == hipSuccess && mfma) {
         e = mfma_scan(N, kEmitScores, S, ldS, nullptr, nullptr, nullptr, nullptr);
         timer.stop();
-        if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, k, sw, 0, s);
+        if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, sw, 0, s);
     } else if (e == hipSuccess) {
         for (int q = 0; q < Q && e == hipSuccess; ++q)
             e = launch_dense_scan(X, x_half, N, D, ldx, Wb + (size_t)q * D * wsize, w_half, bias, q,
-                                  S + (size_t)q * ldS, sw.st + q, sw.hist1 + (size_t)q * kBins1, k, s);
+                                  S + (size_t)q * ldS, sw.hist1 + (size_t)q * kBins1, s);
         timer.stop();
     }
     if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, 0, s);
@@ -279,23 +282,23 @@ static hipError_t rank_table(const uint8_t *codes, int64_t N, int row_bytes, int
         const int64_t Nv = sample_rows(N);
         const int m = sample_rank(N, Nv);
         e = launch_table_scan(codes, Nv, row_bytes, seven_bit, image, bias, kEmitSample, sample, ssw.st, ssw.hist1, m,
-                              nullptr, nullptr, nullptr, s);
-        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, s);
+                              nullptr, nullptr, nullptr, nullptr, s);
+        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, 0, s);
         ScanTimer timer(s);
         if (e == hipSuccess)
             e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitFilter, nullptr, sw.st, nullptr, k,
-                                  ssw.st, sw.cand, nullptr, s);
+                                  ssw.st, ssw.hist2, sw.cand, nullptr, s);
         timer.stop();
         if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
         if (e == hipSuccess)
             e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitScores, S, sw.st, sw.hist1, k,
-                                  nullptr, nullptr, sw.st, s);
+                                  nullptr, nullptr, nullptr, sw.st, s);
         if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 1, s);
         return e;
     }
     ScanTimer timer(s);
     e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitScores, S, sw.st, sw.hist1, k, nullptr,
-                          nullptr, nullptr, s);
+                          nullptr, nullptr, nullptr, s);
     timer.stop();
     if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 0, s);
     return e;

@@ -72,11 +72,9 @@ template <bool XHALF, int V, bool FULL>
 __global__ __launch_bounds__(256) void dense_wide_kernel(const uint8_t *__restrict__ X, long long N, int D,
                                                          long long row_bytes, const void *__restrict__ w,
                                                          int w_is_half, const float *__restrict__ bias_ptr,
-                                                         int bias_index, float *__restrict__ scores, SelState *st,
-                                                         uint32_t *hist1, int k) {
+                                                         int bias_index, float *__restrict__ scores, uint32_t *hist1) {
     constexpr int E = Elem<XHALF>::kPer16;
     __shared__ uint32_t lhist[kBins1];
-    __shared__ uint32_t s_flag;
     for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
     __syncthreads();
 
@@ -154,7 +152,7 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const uint8_t *__restri
             emit(r, dot(c));
         }
     }
-    finish_pass1(lhist, hist1, st, (uint32_t)k, gridDim.x, &s_flag);
+    merge_hist(lhist, kBins1, hist1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -164,13 +162,11 @@ template <bool XHALF, int LPR>
 __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__restrict__ X, long long N, int D,
                                                            long long row_bytes, const void *__restrict__ w,
                                                            int w_is_half, const float *__restrict__ bias_ptr, int bias_index,
-        float *__restrict__ scores,
-                                                           SelState *st, uint32_t *hist1, int k) {
+        float *__restrict__ scores, uint32_t *hist1) {
     constexpr int E = Elem<XHALF>::kPer16;
     constexpr int RPW = 64 / LPR;   // rows per wave load
     constexpr int U = 4;
     __shared__ uint32_t lhist[kBins1];
-    __shared__ uint32_t s_flag;
     for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
     __syncthreads();
 
@@ -215,7 +211,7 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
             }
         }
     }
-    finish_pass1(lhist, hist1, st, (uint32_t)k, gridDim.x, &s_flag);
+    merge_hist(lhist, kBins1, hist1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -225,12 +221,10 @@ template <bool XHALF>
 __global__ __launch_bounds__(256) void dense_huge_kernel(const uint8_t *__restrict__ X, long long N, int D,
                                                          long long row_bytes, const void *__restrict__ w,
                                                          int w_is_half, const float *__restrict__ bias_ptr, int bias_index,
-        float *__restrict__ scores,
-                                                         SelState *st, uint32_t *hist1, int k) {
+        float *__restrict__ scores, uint32_t *hist1) {
     constexpr int E = Elem<XHALF>::kPer16;
     extern __shared__ float w_lds[];   // D floats
     __shared__ uint32_t lhist[kBins1];
-    __shared__ uint32_t s_flag;
     for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
     for (int d = threadIdx.x; d < D; d += blockDim.x) w_lds[d] = load_w(w, w_is_half, d);
     __syncthreads();
@@ -268,18 +262,18 @@ __global__ __launch_bounds__(256) void dense_huge_kernel(const uint8_t *__restri
             atomicAdd(&lhist[float_to_key(acc) >> 20], 1u);
         }
     }
-    finish_pass1(lhist, hist1, st, (uint32_t)k, gridDim.x, &s_flag);
+    merge_hist(lhist, kBins1, hist1);
 }
 
 template <bool XHALF>
 static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t row_bytes, const void *w,
                                      int w_is_half, const float *bias_ptr, int bias_index, float *scores,
-                                     SelState *st, uint32_t *hist1, int k, hipStream_t s) {
+                                     uint32_t *hist1, hipStream_t s) {
     constexpr int E = Elem<XHALF>::kPer16;
     const int chunks = (D + E - 1) / E;              // 16-byte chunks per row
     const int cus = device_cu_count();
     int grid;
-#define OTF_ARGS X, (long long)N, D, (long long)row_bytes, w, w_is_half, bias_ptr, bias_index, scores, st, hist1, k
+#define OTF_ARGS X, (long long)N, D, (long long)row_bytes, w, w_is_half, bias_ptr, bias_index, scores, hist1
     if (chunks <= 32) {
         int lpr = 1;
         while (lpr < chunks) lpr <<= 1;
@@ -323,12 +317,12 @@ static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t
 }
 
 hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int64_t ldx, const void *w,
-                             int w_is_half, const float *bias_ptr, int bias_index, float *scores, SelState *st,
-                             uint32_t *hist1, int k, hipStream_t s) {
+                             int w_is_half, const float *bias_ptr, int bias_index, float *scores, uint32_t *hist1,
+                             hipStream_t s) {
     const uint8_t *Xb = reinterpret_cast<const uint8_t *>(X);
     if (x_is_half)
-        return launch_dense_typed<true>(Xb, N, D, ldx * 2, w, w_is_half, bias_ptr, bias_index, scores, st, hist1, k, s);
-    return launch_dense_typed<false>(Xb, N, D, ldx * 4, w, w_is_half, bias_ptr, bias_index, scores, st, hist1, k, s);
+        return launch_dense_typed<true>(Xb, N, D, ldx * 2, w, w_is_half, bias_ptr, bias_index, scores, hist1, s);
+    return launch_dense_typed<false>(Xb, N, D, ldx * 4, w, w_is_half, bias_ptr, bias_index, scores, hist1, s);
 }
 
 }  // namespace otf

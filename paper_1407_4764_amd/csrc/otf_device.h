@@ -42,15 +42,11 @@ struct SelState {
     uint32_t ncand;    // entries the gather pass writes to the candidate list
     long long tex;     // gather every key with (long long)key > tex
     uint32_t cursor;   // append cursor of the gather pass
-    uint32_t done1, done2, done3;  // block tickets of the three histogram passes
+    uint32_t spare[3];
     uint32_t tau_key;  // filter threshold: rows with key >= tau_key are candidates (filtered scans)
     uint32_t fallback; // set by the filtered path when its candidate list cannot serve: redo by full selection
 };
 static_assert(sizeof(SelState) == 64, "SelState layout");
-
-__device__ __forceinline__ uint32_t ld_coherent(const uint32_t *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -89,13 +85,6 @@ __device__ __forceinline__ uint32_t wave_suffix_sum(uint32_t v) {
     return v;
 }
 
-// Copies a global histogram (produced by other blocks with atomics or fenced stores) into
-// shared memory with device-coherent loads.  All threads of the block call; ends with a barrier.
-__device__ __forceinline__ void block_load_hist(uint32_t *lds, const uint32_t *ghist, int nbins) {
-    for (int b = threadIdx.x; b < nbins; b += blockDim.x) lds[b] = ld_coherent(ghist + b);
-    __syncthreads();
-}
-
 // Called by ONE full wave (64 lanes) on a histogram in shared memory with 64*per_lane bins
 // (per_lane <= 64).  Finds the bin b with  count(bins > b) < need <= count(bins >= b)  and
 // returns it; *above receives count(bins > b) and *inbin the population of b.
@@ -120,25 +109,6 @@ __device__ __forceinline__ uint32_t wave_find_bin(const uint32_t *hist, int per_
     return (uint32_t)(owner * per_lane + lb);
 }
 
-// End of radix pass 1, run by wave 0 of the block that finished last; hist1 is the complete
-// histogram, already copied to shared memory.
-__device__ __forceinline__ void resolve_pass1(SelState *st, const uint32_t *hist1, uint32_t k) {
-    uint32_t above, inbin;
-    uint32_t b1 = wave_find_bin(hist1, kBins1 / 64, k, &above, &inbin);
-    if ((threadIdx.x & 63) == 0) {
-        st->b1 = b1;
-        st->need1 = k - above;
-        uint32_t c1 = above + inbin;
-        if (c1 <= (uint32_t)kCandCap) {
-            st->mode = 0;
-            st->ncand = c1;
-            st->tex = ((long long)b1 << 20) - 1;
-        } else {
-            st->mode = 1;   // provisional: pass 2 decides between 1 and 2
-        }
-    }
-}
-
 // Histogram increment for a whole wave when many lanes are likely to hit the same bin (scores of
 // one classifier cluster in a few coarse bins): the bins held by the lowest active lanes are
 // counted with one atomic each, the rest individually.  All 64 lanes must call.
@@ -157,38 +127,43 @@ __device__ __forceinline__ void hist_add_wave(uint32_t *lhist, uint32_t bin, boo
     if (active) atomicAdd(&lhist[bin], 1u);
 }
 
-// Adds a block's shared-memory histogram into the global one, then tells whether this block
-// is the last of `nblocks` to have done so (the caller then resolves the pass).  All threads
-// must call; returns the same value to all threads.
-__device__ __forceinline__ bool merge_hist_and_ticket(const uint32_t *lhist, int nbins, uint32_t *ghist,
-                                                      uint32_t *ticket_counter, uint32_t nblocks,
-                                                      uint32_t *s_flag) {
+// Adds a block's shared-memory histogram into the global one (device-wide atomics).  Blocks of
+// one kernel never read each other's results: a histogram is consumed by the NEXT kernel on the
+// stream, each of whose blocks resolves it for itself (block_find_bin).  A device-wide fence per
+// block, as a "last block resolves" scheme needs, costs ~0.1 us and serialises across the chip.
+__device__ __forceinline__ void merge_hist(const uint32_t *lhist, int nbins, uint32_t *ghist) {
+    __syncthreads();
     for (int b = threadIdx.x; b < nbins; b += blockDim.x) {
         uint32_t c = lhist[b];
         if (c) atomicAdd(ghist + b, c);
     }
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t t = atomicAdd(ticket_counter, 1u);
-        *s_flag = (t == nblocks - 1) ? 1u : 0u;
-    }
-    __syncthreads();
-    bool last = *s_flag != 0;
-    if (last) __threadfence();
-    return last;
 }
 
-// Tail of every kernel that built a pass-1 histogram in shared memory: merge it, and let the
-// block that finishes last resolve the pass.  lhist must hold kBins1 words and is clobbered.
-__device__ __forceinline__ void finish_pass1(uint32_t *lhist, uint32_t *ghist1, SelState *st, uint32_t k,
-                                             uint32_t nblocks, uint32_t *s_flag) {
+struct BinChoice {
+    uint32_t bin, above, inbin;
+};
+
+// Whole block: loads a histogram that an EARLIER kernel completed into shared memory `lds`
+// (nbins words, nbins a multiple of 64 and at most 4096) and finds the bin of the need-th largest
+// entry.  `s_out` points at 3 words of shared memory.  Ends with a barrier; lds may be reused.
+__device__ __forceinline__ BinChoice block_find_bin(const uint32_t *ghist, int nbins, uint32_t need, uint32_t *lds,
+                                                    uint32_t *s_out) {
     __syncthreads();
-    bool last = merge_hist_and_ticket(lhist, kBins1, ghist1, &st->done1, nblocks, s_flag);
-    if (last) {
-        block_load_hist(lhist, ghist1, kBins1);
-        if (threadIdx.x < 64) resolve_pass1(st, lhist, k);
+    for (int b = threadIdx.x; b < nbins; b += blockDim.x) lds[b] = ghist[b];
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        uint32_t above, inbin;
+        uint32_t bin = wave_find_bin(lds, nbins / 64, need, &above, &inbin);
+        if (threadIdx.x == 0) {
+            s_out[0] = bin;
+            s_out[1] = above;
+            s_out[2] = inbin;
+        }
     }
+    __syncthreads();
+    BinChoice r{s_out[0], s_out[1], s_out[2]};
+    __syncthreads();
+    return r;
 }
 
 // Rows [begin, end) of the chunk that selection block b of kSelBlocks owns; chunks are

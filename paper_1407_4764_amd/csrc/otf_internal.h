@@ -13,13 +13,14 @@ struct SelectWs {
     SelState *st;              // [Q]
     uint32_t *hist1;           // [Q][kBins1]
     uint32_t *hist2;           // [Q][kBins2]
+    uint32_t *hist3;           // [Q][kBins3]
     uint32_t *blockhist3;      // [Q][kSelBlocks][kBins3]
     uint32_t *eqoff;           // [Q][kSelBlocks]
     unsigned long long *cand;  // [Q][kCandCap]   (key << 32 | ~index)
 };
 
 struct WsLayout {
-    size_t st, hist1, hist2, blockhist3, eqoff, cand, sample_st, sample_hist1, sample_hist2, sample_scores,
+    size_t st, hist1, hist2, hist3, blockhist3, eqoff, cand, sample_st, sample_hist1, sample_hist2, sample_scores,
         lut_image, scores, total;
     int64_t sample_ld;   // row stride (floats) of the sample score buffer
 };
@@ -39,22 +40,24 @@ inline int64_t sample_rows(int64_t N) {
 // Zeroes the selection state and the pass-1/2 histograms of Q classifiers.
 hipError_t launch_select_init(const SelectWs &sw, int Q, hipStream_t s);
 // Radix pass 1 over ready-made scores (rows of length N, stride ld).
-hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw, int gated,
+hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const SelectWs &sw, int gated,
                         hipStream_t s);
 // Passes 2 and 3 (skipped on the device when pass 1 was decisive), gather and final sort.  With
 // `gated` the kernels return at once unless sw.st[0].fallback is set.
 hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw,
                               float *out_scores, int32_t *out_idx, int gated, hipStream_t s);
-// Pass 2 over sample scores: publishes sample_sw.st[q].tau_key (the m-th largest sample key, 24 bits).
+// Pass 2 over sample scores for rank m.  With publish_tau, sample_sw.st[q].tau_key receives the
+// threshold (top 24 bits of the m-th largest sample key); otherwise the consumer resolves it from
+// sample_sw.st[q] and sample_sw.hist2 itself.
 hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64_t ld, int Q, int m,
-                                   const SelectWs &sample_sw, hipStream_t s);
+                                   const SelectWs &sample_sw, int publish_tau, hipStream_t s);
 // End of a filtered scan: sort the appended candidates or raise sw.st[0].fallback.
 hipError_t launch_filter_sort(const SelectWs &sw, int Q, int k, float *out_scores, int32_t *out_idx, hipStream_t s);
 
-// Dense single-classifier scan: writes N scores (bias included) and builds the pass-1 histogram.
+// Dense single-classifier scan: writes N scores (bias included) and accumulates the pass-1 histogram.
 hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int64_t ldx,
                              const void *w, int w_is_half, const float *bias_ptr, int bias_index,
-                             float *scores, SelState *st, uint32_t *hist1, int k, hipStream_t s);
+                             float *scores, uint32_t *hist1, hipStream_t s);
 
 // Multi-classifier fp16 scan on the matrix cores (Q = 32 or 64 classifiers per call).
 //   kEmitScores  scores[q][i] for every row (row stride ld_scores); with `gate` set the kernel returns
@@ -76,10 +79,12 @@ hipError_t launch_binary_prepare(const float *w, int D, float *image, const Sele
 // row_bytes = stored bytes per row; seven_bit = the 2048-bit binary layout (7+7+7+7+4 bits per word).
 //   kEmitScores  scores + pass-1 histogram into (st, hist1) for a top-k of k; `gate` as above
 //   kEmitSample  scores of the strided sample (compact numbering) + pass-1 histogram for rank k = m
-//   kEmitFilter  append rows with key >= tau->tau_key to cand (cursor in st)
+//   kEmitFilter  append rows at or above the threshold to cand (cursor in st); every block resolves
+//                the threshold from the sample's pass-2 state (tau, tau_hist2) for rank k = m
 hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, int seven_bit, const float *image,
                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
-                             const SelState *tau, unsigned long long *cand, const SelState *gate, hipStream_t s);
+                             const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
+                             const SelState *gate, hipStream_t s);
 
 hipError_t launch_sgd_step(float *w, float *b, int D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,
                            int n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int n_neg,

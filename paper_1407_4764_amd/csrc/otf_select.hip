@@ -10,8 +10,11 @@
 //   gather  every key above the resolved threshold is appended to a candidate list; in mode 2
 //           the rows whose key EQUALS the k-th key are taken in ascending row order
 //   sort    one block sorts the candidates by (key, ~index) descending and emits the first k
-// A pass ends in the block that finishes last (ticket counter), which resolves the bin; the
-// next pass is skipped on the device as soon as the candidates fit the list (mode 0 / 1).
+// A pass only accumulates its histogram (device-wide atomics).  The kernel of the NEXT pass
+// resolves it: every block finds the bin for itself from the finished histogram (a few
+// microseconds, no cross-block synchronisation inside a kernel) and block 0 records the result
+// for the kernels after it.  A pass returns at once when the previous one was decisive, i.e. the
+// candidates already fit the list (mode 0 / 1).
 //
 // The same passes serve the filtered scans: passes 1 and 2 over the scores of a small sample of
 // the store give a 24-bit threshold (`tau_key`); the full scan then appends only rows at or above
@@ -22,13 +25,16 @@
 
 namespace otf {
 
-__global__ __launch_bounds__(256) void select_init_kernel(SelState *st, uint32_t *hist1, uint32_t *hist2, int Q) {
+__global__ __launch_bounds__(256) void select_init_kernel(SelState *st, uint32_t *hist1, uint32_t *hist2,
+                                                          uint32_t *hist3, int Q) {
     const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t step = (size_t)gridDim.x * blockDim.x;
     uint32_t *stw = reinterpret_cast<uint32_t *>(st);
     for (size_t i = tid; i < (size_t)Q * (sizeof(SelState) / 4); i += step) stw[i] = 0u;
     for (size_t i = tid; i < (size_t)Q * kBins1; i += step) hist1[i] = 0u;
     for (size_t i = tid; i < (size_t)Q * kBins2; i += step) hist2[i] = 0u;
+    if (hist3)
+        for (size_t i = tid; i < (size_t)Q * kBins3; i += step) hist3[i] = 0u;
 }
 
 // Four consecutive scores of this thread for the tile starting at t0 (tile = 4 * blockDim rows);
@@ -50,9 +56,8 @@ __device__ __forceinline__ void load4(const float *s, long long i, long long end
 __device__ __forceinline__ bool row_vec_ok(const float *s) { return (reinterpret_cast<uintptr_t>(s) & 15u) == 0; }
 
 __global__ __launch_bounds__(512) void hist1_kernel(const float *__restrict__ scores, long long N, long long ld,
-                                                    int k, SelState *st_all, uint32_t *hist1_all, int gated) {
+                                                    SelState *st_all, uint32_t *hist1_all, int gated) {
     __shared__ uint32_t lhist[kBins1];
-    __shared__ uint32_t s_flag;
     if (gated && st_all[0].fallback == 0u) return;
     const int q = blockIdx.y;
     const float *s = scores + (long long)q * ld;
@@ -68,24 +73,34 @@ __global__ __launch_bounds__(512) void hist1_kernel(const float *__restrict__ sc
 #pragma unroll
         for (int j = 0; j < 4; ++j) hist_add_wave(lhist, float_to_key(v[j]) >> 20, ok[j]);
     }
-    finish_pass1(lhist, hist1_all + (size_t)q * kBins1, st_all + q, (uint32_t)k, gridDim.x, &s_flag);
+    merge_hist(lhist, kBins1, hist1_all + (size_t)q * kBins1);
 }
 
-// force_tau: always run (threshold estimation on a sample) and publish tau_key = top 24 bits of
-// the `need1`-th largest key, low bits zero.
+// Pass 2.  Resolves pass 1 first (rank k in hist1).  force: always run pass 2 (threshold
+// estimation on a sample); otherwise return when pass 1 was decisive.
 __global__ __launch_bounds__(512) void hist2_kernel(const float *__restrict__ scores, long long N, long long ld,
-                                                    int k, SelState *st_all, uint32_t *hist2_all, int gated,
-                                                    int force_tau, const SelState *gate_state) {
+                                                    int k, SelState *st_all, const uint32_t *hist1_all,
+                                                    uint32_t *hist2_all, int force, const SelState *gate) {
     __shared__ uint32_t lhist[kBins2];
-    __shared__ uint32_t s_flag;
-    if (gated && gate_state[0].fallback == 0u) return;
+    __shared__ uint32_t s_out[3];
+    if (gate && gate->fallback == 0u) return;
     const int q = blockIdx.y;
     SelState *st = st_all + q;
-    if (!force_tau && st->mode == 0u) return;         // pass 1 was decisive (uniform per block)
-    const uint32_t b1 = st->b1;
+    const BinChoice r1 = block_find_bin(hist1_all + (size_t)q * kBins1, kBins1, (uint32_t)k, lhist, s_out);
+    const uint32_t b1 = r1.bin, need1 = (uint32_t)k - r1.above, c1 = r1.above + r1.inbin;
+    const bool decisive = c1 <= (uint32_t)kCandCap;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        st->b1 = b1;
+        st->need1 = need1;
+        st->mode = decisive ? 0u : 1u;
+        if (decisive) {
+            st->ncand = c1;
+            st->tex = ((long long)b1 << 20) - 1;
+        }
+    }
+    if (decisive && !force) return;
     const float *s = scores + (long long)q * ld;
     const bool vec_ok = row_vec_ok(s);
-    uint32_t *ghist = hist2_all + (size_t)q * kBins2;
     for (int b = threadIdx.x; b < kBins2; b += blockDim.x) lhist[b] = 0u;
     __syncthreads();
     long long begin, end;
@@ -100,45 +115,57 @@ __global__ __launch_bounds__(512) void hist2_kernel(const float *__restrict__ sc
             hist_add_wave(lhist, (key >> 8) & 0xFFFu, ok[j] && (key >> 20) == b1);
         }
     }
-    __syncthreads();
-    bool last = merge_hist_and_ticket(lhist, kBins2, ghist, &st->done2, gridDim.x, &s_flag);
-    if (!last) return;
-    block_load_hist(lhist, ghist, kBins2);
-    if (threadIdx.x < 64) {
-        const uint32_t need1 = st->need1;
-        uint32_t above, inbin;
-        uint32_t b2 = wave_find_bin(lhist, kBins2 / 64, need1, &above, &inbin);
-        if (threadIdx.x == 0) {
-            uint32_t p24 = (b1 << 12) | b2;
-            st->p24 = p24;
-            st->need2 = need1 - above;
-            st->tau_key = p24 << 8;
-            uint32_t c2 = ((uint32_t)k - need1) + above + inbin;   // keys >= p24 << 8
-            if (c2 <= (uint32_t)kCandCap) {
-                st->mode = 1u;
-                st->ncand = c2;
-                st->tex = ((long long)p24 << 8) - 1;
-            } else {
-                st->mode = 2u;
-            }
-        }
-    }
+    merge_hist(lhist, kBins2, hist2_all + (size_t)q * kBins2);
 }
 
+// Resolution of pass 2 from the state pass 2's kernel left and its histogram.  Whole block.
+struct Pass2 {
+    uint32_t p24, need2, c2;
+};
+__device__ __forceinline__ Pass2 resolve_pass2(const SelState *st, const uint32_t *hist2, int k, uint32_t *lds,
+                                               uint32_t *s_out) {
+    const uint32_t b1 = st->b1, need1 = st->need1;
+    const BinChoice r2 = block_find_bin(hist2, kBins2, need1, lds, s_out);
+    Pass2 p;
+    p.p24 = (b1 << 12) | r2.bin;
+    p.need2 = need1 - r2.above;
+    p.c2 = ((uint32_t)k - need1) + r2.above + r2.inbin;     // keys >= p24 << 8
+    return p;
+}
+
+// One block per classifier: the threshold of a filtered scan from passes 1 and 2 over the sample.
+__global__ __launch_bounds__(512) void sample_tau_kernel(SelState *sample_st_all, const uint32_t *hist2_all, int m) {
+    __shared__ uint32_t lhist[kBins2];
+    __shared__ uint32_t s_out[3];
+    const int q = blockIdx.x;
+    const Pass2 p = resolve_pass2(sample_st_all + q, hist2_all + (size_t)q * kBins2, m, lhist, s_out);
+    if (threadIdx.x == 0) sample_st_all[q].tau_key = p.p24 << 8;
+}
+
+// Pass 3 (only when thousands of keys share the top 24 bits of the k-th: ties or near-ties).
 __global__ __launch_bounds__(512) void hist3_kernel(const float *__restrict__ scores, long long N, long long ld,
-                                                    int k, SelState *st_all, uint32_t *blockhist3_all,
-                                                    uint32_t *eqoff_all, int gated) {
-    __shared__ uint32_t lhist[kBins3];
-    __shared__ uint32_t lscan[kSelBlocks];
-    __shared__ uint32_t s_flag, s_b3;
+                                                    int k, SelState *st_all, const uint32_t *hist2_all,
+                                                    uint32_t *hist3_all, uint32_t *blockhist3_all, int gated) {
+    __shared__ uint32_t lhist[kBins2];
+    __shared__ uint32_t s_out[3];
     if (gated && st_all[0].fallback == 0u) return;
     const int q = blockIdx.y;
     SelState *st = st_all + q;
-    if (st->mode != 2u) return;
-    const uint32_t p24 = st->p24;
+    if (st->mode == 0u) return;                         // pass 1 was decisive
+    const Pass2 p = resolve_pass2(st, hist2_all + (size_t)q * kBins2, k, lhist, s_out);
+    const bool decisive = p.c2 <= (uint32_t)kCandCap;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        st->p24 = p.p24;
+        st->need2 = p.need2;
+        st->mode = decisive ? 1u : 2u;
+        if (decisive) {
+            st->ncand = p.c2;
+            st->tex = ((long long)p.p24 << 8) - 1;
+        }
+    }
+    if (decisive) return;
     const float *s = scores + (long long)q * ld;
     const bool vec_ok = row_vec_ok(s);
-    uint32_t *bh = blockhist3_all + (size_t)q * kSelBlocks * kBins3;
     for (int b = threadIdx.x; b < kBins3; b += blockDim.x) lhist[b] = 0u;
     __syncthreads();
     long long begin, end;
@@ -150,54 +177,14 @@ __global__ __launch_bounds__(512) void hist3_kernel(const float *__restrict__ sc
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t key = float_to_key(v[j]);
-            hist_add_wave(lhist, key & 0xFFu, ok[j] && (key >> 8) == p24);
+            hist_add_wave(lhist, key & 0xFFu, ok[j] && (key >> 8) == p.p24);
         }
     }
     __syncthreads();
-    for (int b = threadIdx.x; b < kBins3; b += blockDim.x) bh[(size_t)blockIdx.x * kBins3 + b] = lhist[b];
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t t = atomicAdd(&st->done3, 1u);
-        s_flag = (t == gridDim.x - 1) ? 1u : 0u;
-    }
-    __syncthreads();
-    if (!s_flag) return;
-    __threadfence();
-    // the last block: total histogram over the blocks, then the bin of the k-th key
-    if (threadIdx.x < kBins3) {
-        uint32_t acc = 0;
-        for (int b = 0; b < kSelBlocks; ++b) acc += ld_coherent(bh + (size_t)b * kBins3 + threadIdx.x);
-        lhist[threadIdx.x] = acc;
-    }
-    __syncthreads();
-    if (threadIdx.x < 64) {
-        const uint32_t need2 = st->need2;
-        uint32_t above, inbin;
-        uint32_t b3 = wave_find_bin(lhist, kBins3 / 64, need2, &above, &inbin);
-        if (threadIdx.x == 0) {
-            uint32_t T = (p24 << 8) | b3;
-            st->T = T;
-            st->r = need2 - above;
-            st->ncand = (uint32_t)k;
-            st->tex = (long long)T;
-            s_b3 = b3;
-        }
-    }
-    __syncthreads();
-    // rows equal to the k-th key are taken in ascending row order: exclusive prefix of their
-    // per-block counts gives each block the rank of its first such row
-    const uint32_t b3 = s_b3;
-    for (int b = threadIdx.x; b < kSelBlocks; b += blockDim.x) lscan[b] = ld_coherent(bh + (size_t)b * kBins3 + b3);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        uint32_t *eo = eqoff_all + (size_t)q * kSelBlocks;
-        for (int b = 0; b < kSelBlocks; ++b) {
-            eo[b] = run;
-            run += lscan[b];
-        }
-    }
+    // per-block counts (for the row-ordered split of ties) and the total histogram
+    uint32_t *bh = blockhist3_all + ((size_t)q * kSelBlocks + blockIdx.x) * kBins3;
+    for (int b = threadIdx.x; b < kBins3; b += blockDim.x) bh[b] = lhist[b];
+    merge_hist(lhist, kBins3, hist3_all + (size_t)q * kBins3);
 }
 
 __device__ __forceinline__ unsigned long long pack_cand(uint32_t key, long long row) {
@@ -205,21 +192,47 @@ __device__ __forceinline__ unsigned long long pack_cand(uint32_t key, long long 
 }
 
 __global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ scores, long long N, long long ld,
-                                                     int k, SelState *st_all, const uint32_t *eqoff_all,
-                                                     unsigned long long *cand_all, int gated) {
+                                                     int k, SelState *st_all, const uint32_t *hist3_all,
+                                                     const uint32_t *blockhist3_all, unsigned long long *cand_all,
+                                                     int gated) {
+    __shared__ uint32_t lhist[kBins3];
+    __shared__ uint32_t s_out[3];
     __shared__ uint32_t wave_cnt[8];
     if (gated && st_all[0].fallback == 0u) return;
     const int q = blockIdx.y;
     SelState *st = st_all + q;
     const uint32_t mode = st->mode;
-    const long long tex = st->tex;
-    const uint32_t T = st->T, r = st->r;
+    long long tex = st->tex;
+    uint32_t T = 0, r = 0, eqbase = 0;
+    if (mode == 2u) {
+        // resolve pass 3: the k-th key itself, how many rows equal to it belong to the list, and
+        // how many such rows lie in the blocks before this one (ties go to the lowest rows)
+        const uint32_t need2 = st->need2;
+        const BinChoice r3 = block_find_bin(hist3_all + (size_t)q * kBins3, kBins3, need2, lhist, s_out);
+        T = (st->p24 << 8) | r3.bin;
+        r = need2 - r3.above;
+        tex = (long long)T;
+        const uint32_t *bh = blockhist3_all + (size_t)q * kSelBlocks * kBins3 + r3.bin;
+        uint32_t mine = 0;
+        for (int b = threadIdx.x; b < (int)blockIdx.x; b += blockDim.x) mine += bh[(size_t)b * kBins3];
+        uint32_t acc = mine;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+        if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6] = acc;
+        __syncthreads();
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) eqbase += wave_cnt[w];
+        __syncthreads();
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            st->T = T;
+            st->r = r;
+            st->ncand = (uint32_t)k;
+        }
+    }
     const float *s = scores + (long long)q * ld;
     const bool vec_ok = row_vec_ok(s);
     unsigned long long *cand = cand_all + (size_t)q * kCandCap;
     long long begin, end;
     sel_chunk(N, blockIdx.x, &begin, &end);
-    uint32_t eqbase = (mode == 2u) ? eqoff_all[(size_t)q * kSelBlocks + blockIdx.x] : 0u;
     const bool ordered = (mode == 2u) && (eqbase < r);    // uniform over the block
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     for (long long t0 = begin; t0 < end; t0 += 4 * blockDim.x) {
@@ -271,54 +284,186 @@ __global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ s
     }
 }
 
-// Bitonic sort (descending) of P = 2^p >= n packed candidates in shared memory `a`, then the
-// first k are emitted.  All threads of the block call.
-__device__ __forceinline__ void sort_and_emit(unsigned long long *a, const unsigned long long *cand, uint32_t n, int k,
-                                              float *out_scores, int32_t *out_idx) {
-    uint32_t P = 2;
-    while (P < n) P <<= 1;
-    for (uint32_t i = threadIdx.x; i < P; i += blockDim.x) a[i] = (i < n) ? cand[i] : 0ull;
+// ---------------------------------------------------------------------------------------------
+// Final step, one block of 1024 threads per classifier: from n <= kCandCap packed candidates
+// (key << 32 | ~row, all distinct) emit the k largest in descending order.
+//
+//   1. pre-selection: a 4096-bin histogram over the candidates' own key range finds the bin of
+//      the k-th largest; candidates below that bin are dropped (usually n ~ 4k shrinks to ~k);
+//   2. bitonic sort of the survivors, padded to a power of two P: every thread keeps P/1024
+//      elements in registers; compare-exchange partners less than 64 apart are reached with
+//      wave shuffles, partners in another wave through shared memory, partners 1024 or more
+//      apart are the thread's own registers -- 10 shared-memory exchanges instead of ~90.
+constexpr int kSortThreads = 1024;
+constexpr int kSortLdsBytes = kBins1 * 4 + kCandCap * 8;
+
+__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int mask) {
+    const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)v, mask, 64);
+    const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(v >> 32), mask, 64);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+// Sorts a[0..P) descending.  P is a power of two, 64 <= P <= 1024 * E, and E = max(1, P / 1024).
+template <int E>
+__device__ __forceinline__ void bitonic_desc(unsigned long long *a, uint32_t P) {
+    const uint32_t tid = threadIdx.x;
+    const bool live = tid < P;                       // whole waves (P >= 64)
+    unsigned long long r[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) r[j] = live ? a[j * kSortThreads + tid] : 0ull;
     for (uint32_t size = 2; size <= P; size <<= 1) {
         for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
-            for (uint32_t i = threadIdx.x; i < (P >> 1); i += blockDim.x) {
-                uint32_t lo = 2u * i - (i & (stride - 1u));
-                uint32_t hi = lo + stride;
-                unsigned long long x = a[lo], y = a[hi];
-                bool desc = (lo & size) == 0u;
-                if (desc ? (x < y) : (x > y)) {
-                    a[lo] = y;
-                    a[hi] = x;
+            if (stride >= (uint32_t)kSortThreads) {              // partner is another register of this thread
+                const int dj = (int)(stride / kSortThreads);
+#pragma unroll
+                for (int j = 0; j < E; ++j) {
+                    if ((j & dj) == 0 && (j | dj) < E) {
+                        const uint32_t e = (uint32_t)j * kSortThreads + tid;
+                        const bool desc = (e & size) == 0u;
+                        unsigned long long x = r[j], y = r[j | dj];
+                        if (desc ? (x < y) : (x > y)) {
+                            r[j] = y;
+                            r[j | dj] = x;
+                        }
+                    }
+                }
+            } else if (stride >= 64u) {                           // partner in another wave: through shared memory
+                __syncthreads();
+                if (live) {
+#pragma unroll
+                    for (int j = 0; j < E; ++j) a[j * kSortThreads + tid] = r[j];
+                }
+                __syncthreads();
+                if (live) {
+#pragma unroll
+                    for (int j = 0; j < E; ++j) {
+                        const uint32_t e = (uint32_t)j * kSortThreads + tid;
+                        const unsigned long long y = a[e ^ stride];
+                        const bool keep_larger = ((e & stride) == 0u) == ((e & size) == 0u);
+                        r[j] = keep_larger ? (r[j] > y ? r[j] : y) : (r[j] < y ? r[j] : y);
+                    }
+                }
+            } else {                                              // partner in this wave
+#pragma unroll
+                for (int j = 0; j < E; ++j) {
+                    const uint32_t e = (uint32_t)j * kSortThreads + tid;
+                    const unsigned long long y = shfl_xor_u64(r[j], (int)stride);
+                    const bool keep_larger = ((e & stride) == 0u) == ((e & size) == 0u);
+                    r[j] = keep_larger ? (r[j] > y ? r[j] : y) : (r[j] < y ? r[j] : y);
                 }
             }
         }
     }
     __syncthreads();
-    for (uint32_t j = threadIdx.x; j < (uint32_t)k; j += blockDim.x) {
-        unsigned long long e = a[j];
+    if (live) {
+#pragma unroll
+        for (int j = 0; j < E; ++j) a[j * kSortThreads + tid] = r[j];
+    }
+    __syncthreads();
+}
+
+// lds: kSortLdsBytes of shared memory.  Every thread of the 1024 calls.
+__device__ __forceinline__ void select_sort_emit(uint8_t *lds, const unsigned long long *cand, uint32_t n, int k,
+                                                 float *out_scores, int32_t *out_idx) {
+    uint32_t *hist = reinterpret_cast<uint32_t *>(lds);
+    unsigned long long *a = reinterpret_cast<unsigned long long *>(lds + kBins1 * 4);
+    __shared__ uint32_t s_lo, s_hi, s_cnt, s_bin;
+    const uint32_t tid = threadIdx.x;
+    constexpr int EMAX = kCandCap / kSortThreads;
+    unsigned long long r[EMAX];
+    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+    for (int j = 0; j < EMAX; ++j) {
+        const uint32_t i = (uint32_t)j * kSortThreads + tid;
+        r[j] = i < n ? cand[i] : 0ull;
+        if (i < n) {
+            const uint32_t key = (uint32_t)(r[j] >> 32);
+            lo = key < lo ? key : lo;
+            hi = key > hi ? key : hi;
+        }
+    }
+    if (tid == 0) {
+        s_lo = 0xFFFFFFFFu;
+        s_hi = 0u;
+        s_cnt = 0u;
+    }
+    for (uint32_t b = tid; b < (uint32_t)kBins1; b += kSortThreads) hist[b] = 0u;
+    __syncthreads();
+    if (lo <= hi) {
+        atomicMin(&s_lo, lo);
+        atomicMax(&s_hi, hi);
+    }
+    __syncthreads();
+    lo = s_lo;
+    hi = s_hi;
+    uint32_t n2 = n;
+    if (n > (uint32_t)k) {
+        // bins over [lo, hi]: (key - lo) >> sh < 4096
+        const uint32_t range = hi - lo;
+        const int sh = range < (uint32_t)kBins1 ? 0 : (32 - __builtin_clz(range)) - 12;
+#pragma unroll
+        for (int j = 0; j < EMAX; ++j) {
+            const uint32_t i = (uint32_t)j * kSortThreads + tid;
+            if (i < n) atomicAdd(&hist[((uint32_t)(r[j] >> 32) - lo) >> sh], 1u);
+        }
+        __syncthreads();
+        if (tid < 64) {
+            uint32_t above, inbin;
+            const uint32_t bin = wave_find_bin(hist, kBins1 / 64, (uint32_t)k, &above, &inbin);
+            if (tid == 0) s_bin = bin;
+        }
+        __syncthreads();
+        const uint32_t bin = s_bin;
+#pragma unroll
+        for (int j = 0; j < EMAX; ++j) {
+            const uint32_t i = (uint32_t)j * kSortThreads + tid;
+            if (i < n && (((uint32_t)(r[j] >> 32) - lo) >> sh) >= bin) a[atomicAdd(&s_cnt, 1u)] = r[j];
+        }
+        __syncthreads();
+        n2 = s_cnt;
+    } else {
+#pragma unroll
+        for (int j = 0; j < EMAX; ++j) {
+            const uint32_t i = (uint32_t)j * kSortThreads + tid;
+            if (i < n) a[i] = r[j];
+        }
+    }
+    uint32_t P = 64;
+    while (P < n2) P <<= 1;
+    for (uint32_t i = n2 + tid; i < P; i += kSortThreads) a[i] = 0ull;     // padding sorts last
+    __syncthreads();
+    if (P <= 1024u) bitonic_desc<1>(a, P);
+    else if (P == 2048u) bitonic_desc<2>(a, P);
+    else if (P == 4096u) bitonic_desc<4>(a, P);
+    else bitonic_desc<8>(a, P);
+    for (uint32_t j = tid; j < (uint32_t)k; j += kSortThreads) {
+        const unsigned long long e = a[j];
         out_scores[j] = key_to_float((uint32_t)(e >> 32));
         out_idx[j] = (int32_t)(0xFFFFFFFFu - (uint32_t)(e & 0xFFFFFFFFull));
     }
 }
 
 // One block per classifier: sorts the candidate list of the full selection.
-__global__ __launch_bounds__(1024) void sort_emit_kernel(const SelState *st_all, const unsigned long long *cand_all,
-                                                         int k, float *out_scores, int32_t *out_idx, int gated) {
-    __shared__ unsigned long long a[kCandCap];
+__global__ __launch_bounds__(kSortThreads) void sort_emit_kernel(const SelState *st_all,
+                                                                 const unsigned long long *cand_all, int k,
+                                                                 float *out_scores, int32_t *out_idx, int gated) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t sort_lds[];
     if (gated && st_all[0].fallback == 0u) return;
     const int q = blockIdx.x;
     uint32_t n = st_all[q].ncand;
     if (n > (uint32_t)kCandCap) n = kCandCap;
-    sort_and_emit(a, cand_all + (size_t)q * kCandCap, n, k, out_scores + (size_t)q * k, out_idx + (size_t)q * k);
+    select_sort_emit(sort_lds, cand_all + (size_t)q * kCandCap, n, k, out_scores + (size_t)q * k,
+                     out_idx + (size_t)q * k);
 }
 
 // One block per classifier: end of a filtered scan.  The scan appended `cursor` rows (it stops
 // writing at the capacity but keeps counting).  With k <= cursor <= capacity the list holds
 // every row of the top k, so sorting it gives the exact answer; otherwise the fallback is raised
 // for all classifiers and the append cursor is cleared for the full selection that follows.
-__global__ __launch_bounds__(1024) void filter_sort_kernel(SelState *st_all, const unsigned long long *cand_all, int k,
-                                                           float *out_scores, int32_t *out_idx) {
-    __shared__ unsigned long long a[kCandCap];
+__global__ __launch_bounds__(kSortThreads) void filter_sort_kernel(SelState *st_all,
+                                                                   const unsigned long long *cand_all, int k,
+                                                                   float *out_scores, int32_t *out_idx) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t sort_lds[];
     const int q = blockIdx.x;
     SelState *st = st_all + q;
     const uint32_t n = st->cursor;
@@ -328,43 +473,58 @@ __global__ __launch_bounds__(1024) void filter_sort_kernel(SelState *st_all, con
         if (threadIdx.x == 0) atomicOr(&st_all[0].fallback, 1u);
         return;
     }
-    sort_and_emit(a, cand_all + (size_t)q * kCandCap, n, k, out_scores + (size_t)q * k, out_idx + (size_t)q * k);
+    select_sort_emit(sort_lds, cand_all + (size_t)q * kCandCap, n, k, out_scores + (size_t)q * k,
+                     out_idx + (size_t)q * k);
+}
+
+static hipError_t allow_sort_lds() {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&sort_emit_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSortLdsBytes);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&filter_sort_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kSortLdsBytes);
 }
 
 hipError_t launch_select_init(const SelectWs &sw, int Q, hipStream_t s) {
     int blocks = (int)(((size_t)Q * kBins1 + 255) / 256);
     if (blocks > 1024) blocks = 1024;
-    select_init_kernel<<<blocks, 256, 0, s>>>(sw.st, sw.hist1, sw.hist2, Q);
+    select_init_kernel<<<blocks, 256, 0, s>>>(sw.st, sw.hist1, sw.hist2, sw.hist3, Q);
     return hipGetLastError();
 }
 
-hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw, int gated,
+hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const SelectWs &sw, int gated,
                         hipStream_t s) {
-    hist1_kernel<<<dim3(kSelBlocks, Q), 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist1, gated);
+    hist1_kernel<<<dim3(kSelBlocks, Q), 512, 0, s>>>(scores, N, ld, sw.st, sw.hist1, gated);
     return hipGetLastError();
 }
 
 hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw,
                               float *out_scores, int32_t *out_idx, int gated, hipStream_t s) {
     dim3 grid(kSelBlocks, Q);
-    hist2_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist2, gated, 0, sw.st);
-    hist3_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.blockhist3, sw.eqoff, gated);
-    gather_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.eqoff, sw.cand, gated);
-    sort_emit_kernel<<<Q, 1024, 0, s>>>(sw.st, sw.cand, k, out_scores, out_idx, gated);
+    hist2_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist1, sw.hist2, 0, gated ? sw.st : nullptr);
+    hist3_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist2, sw.hist3, sw.blockhist3, gated);
+    gather_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist3, sw.blockhist3, sw.cand, gated);
+    hipError_t e = allow_sort_lds();
+    if (e != hipSuccess) return e;
+    sort_emit_kernel<<<Q, kSortThreads, kSortLdsBytes, s>>>(sw.st, sw.cand, k, out_scores, out_idx, gated);
     return hipGetLastError();
 }
 
-// Threshold from a sample: pass 2 over the sample scores (pass 1 was fused into the sample scan
-// or done by launch_hist1 on the sample state), publishing tau_key in the sample state.
+// Pass 2 over sample scores (pass 1 was accumulated by the sample scan or by launch_hist1 on the
+// sample state).  With publish_tau the thresholds are resolved into sample_sw.st[q].tau_key by a
+// one-block-per-classifier kernel; otherwise the consumer resolves them itself (resolve_tau).
 hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64_t ld, int Q, int m,
-                                   const SelectWs &sample_sw, hipStream_t s) {
-    hist2_kernel<<<dim3(kSelBlocks, Q), 512, 0, s>>>(sample_scores, Nv, ld, m, sample_sw.st, sample_sw.hist2, 0, 1,
-                                                    sample_sw.st);
+                                   const SelectWs &sample_sw, int publish_tau, hipStream_t s) {
+    hist2_kernel<<<dim3(kSelBlocks, Q), 512, 0, s>>>(sample_scores, Nv, ld, m, sample_sw.st, sample_sw.hist1,
+                                                    sample_sw.hist2, 1, nullptr);
+    if (publish_tau) sample_tau_kernel<<<Q, 512, 0, s>>>(sample_sw.st, sample_sw.hist2, m);
     return hipGetLastError();
 }
 
 hipError_t launch_filter_sort(const SelectWs &sw, int Q, int k, float *out_scores, int32_t *out_idx, hipStream_t s) {
-    filter_sort_kernel<<<Q, 1024, 0, s>>>(sw.st, sw.cand, k, out_scores, out_idx);
+    hipError_t e = allow_sort_lds();
+    if (e != hipSuccess) return e;
+    filter_sort_kernel<<<Q, kSortThreads, kSortLdsBytes, s>>>(sw.st, sw.cand, k, out_scores, out_idx);
     return hipGetLastError();
 }
 

@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void pq_build_lut_kernel(const float *__restri
 
 // Zeroes both selection states (full selection and sample thresholding) of one classifier.
 __device__ __forceinline__ void zero_states(int tid, int step, SelState *st, uint32_t *hist1, uint32_t *hist2,
-                                            SelState *sst, uint32_t *shist1, uint32_t *shist2) {
+                                            uint32_t *hist3, SelState *sst, uint32_t *shist1, uint32_t *shist2) {
     uint32_t *stw = reinterpret_cast<uint32_t *>(st), *sstw = reinterpret_cast<uint32_t *>(sst);
     for (int i = tid; i < (int)(sizeof(SelState) / 4); i += step) {
         stw[i] = 0u;
@@ -77,28 +77,29 @@ __device__ __forceinline__ void zero_states(int tid, int step, SelState *st, uin
         hist2[i] = 0u;
         shist2[i] = 0u;
     }
+    for (int i = tid; i < kBins3; i += step) hist3[i] = 0u;
 }
 
 // Table images for PQ: image[sp][v][column(pos)] = lut[m][v],  m = sp*128 + pos (M >= 128) or
 // pos mod M (M < 128).  Also zeroes the selection states (one launch instead of two).
 __global__ __launch_bounds__(256) void pq_prepare_kernel(const float *__restrict__ lut, int M, int nsplit,
                                                          float *__restrict__ image, SelState *st, uint32_t *hist1,
-                                                         uint32_t *hist2, SelState *sst, uint32_t *shist1,
-                                                         uint32_t *shist2) {
+                                                         uint32_t *hist2, uint32_t *hist3, SelState *sst,
+                                                         uint32_t *shist1, uint32_t *shist2) {
     const int tid = blockIdx.x * blockDim.x + threadIdx.x, step = gridDim.x * blockDim.x;
     for (int t = tid; t < nsplit * kImageFloats; t += step) {
         const int v = t & 255, pos = (t >> 8) & (kSegBytes - 1), sp = t >> 15;
         const int m = (M >= kSegBytes) ? sp * kSegBytes + pos : pos % M;
         image[(size_t)sp * kImageFloats + v * kSegBytes + image_column(pos)] = lut[(size_t)m * 256 + v];
     }
-    zero_states(tid, step, st, hist1, hist2, sst, shist1, shist2);
+    zero_states(tid, step, st, hist1, hist2, hist3, sst, shist1, shist2);
 }
 
 // Table images for binary codes with byte groups: byte g of a row covers dimensions 8g..8g+7.
 __global__ __launch_bounds__(256) void binary_prepare_kernel(const float *__restrict__ w, int row_bytes, int nsplit,
                                                              float *__restrict__ image, SelState *st, uint32_t *hist1,
-                                                             uint32_t *hist2, SelState *sst, uint32_t *shist1,
-                                                             uint32_t *shist2) {
+                                                             uint32_t *hist2, uint32_t *hist3, SelState *sst,
+                                                             uint32_t *shist1, uint32_t *shist2) {
     const int tid = blockIdx.x * blockDim.x + threadIdx.x, step = gridDim.x * blockDim.x;
     for (int t = tid; t < nsplit * kImageFloats; t += step) {
         const int v = t & 255, pos = (t >> 8) & (kSegBytes - 1), sp = t >> 15;
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(256) void binary_prepare_kernel(const float *__rest
         }
         image[(size_t)sp * kImageFloats + v * kSegBytes + image_column(pos)] = acc;
     }
-    zero_states(tid, step, st, hist1, hist2, sst, shist1, shist2);
+    zero_states(tid, step, st, hist1, hist2, hist3, sst, shist1, shist2);
 }
 
 // Table image for 2048-bit rows: word q (0..63) of a row = lane-chunk q/4, word tq = q%4 of the chunk.
@@ -119,7 +120,8 @@ __global__ __launch_bounds__(256) void binary_prepare_kernel(const float *__rest
 //   side[v][q]                    (v < 16)   the top four bits:   dimensions 32q + 28 .. 32q + 31
 __global__ __launch_bounds__(256) void binary7_prepare_kernel(const float *__restrict__ w, float *__restrict__ image,
                                                               SelState *st, uint32_t *hist1, uint32_t *hist2,
-                                                              SelState *sst, uint32_t *shist1, uint32_t *shist2) {
+                                                              uint32_t *hist3, SelState *sst, uint32_t *shist1,
+                                                              uint32_t *shist2) {
     const int tid = blockIdx.x * blockDim.x + threadIdx.x, step = gridDim.x * blockDim.x;
     for (int t = tid; t < 128 * 256; t += step) {
         const int v = t & 127, col = t >> 7;              // col = 4*q + j
@@ -143,7 +145,7 @@ __global__ __launch_bounds__(256) void binary7_prepare_kernel(const float *__res
         }
         image[kImageFloats + v * 64 + q] = acc;
     }
-    zero_states(tid, step, st, hist1, hist2, sst, shist1, shist2);
+    zero_states(tid, step, st, hist1, hist2, hist3, sst, shist1, shist2);
 }
 
 template <int CTRL>
@@ -180,10 +182,10 @@ template <int LPR, int U, int GB, int EMIT, bool SPLIT>
 __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     const uint8_t *__restrict__ codes, long long N, int M, int nsplit, const float *__restrict__ image, float bias,
     float *__restrict__ scores, SelState *st, uint32_t *hist1, int k, const SelState *tau_state,
-    unsigned long long *__restrict__ cand, const SelState *gate) {
+    const uint32_t *tau_hist2, unsigned long long *__restrict__ cand, const SelState *gate) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     __shared__ uint32_t lhist[EMIT == kEmitFilter ? 1 : kBins1];
-    __shared__ uint32_t s_flag;
+    __shared__ uint32_t s_out[3];
     if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
     constexpr int RPW = 64 / LPR;                // rows per wave load
     constexpr int TILE = RPW * U;                // rows per wave iteration
@@ -195,7 +197,15 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
 
     if (EMIT != kEmitFilter)
         for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
-    const uint32_t tau = EMIT == kEmitFilter ? tau_state->tau_key : 0u;
+    // Filtered scan: the threshold is the top 24 bits of the k-th largest sample key (k = the
+    // sample rank here); passes 1 and 2 over the sample left their state, every block resolves it
+    // (the table area of shared memory is still free at this point).
+    uint32_t tau = 0u;
+    if (EMIT == kEmitFilter) {
+        const BinChoice r2 = block_find_bin(tau_hist2, kBins2, tau_state->need1,
+                                            reinterpret_cast<uint32_t *>(lds_raw), s_out);
+        tau = ((tau_state->b1 << 12) | r2.bin) << 8;
+    }
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int chunk = GB == 8 ? (lane & 7) : (lane & 15);   // 16-byte chunk inside the table's row span
@@ -348,7 +358,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
             }
         }
     }
-    if (EMIT != kEmitFilter) finish_pass1(lhist, hist1, st, (uint32_t)k, gridDim.x, &s_flag);
+    if (EMIT != kEmitFilter) merge_hist(lhist, kBins1, hist1);
 }
 
 hipError_t launch_pq_build_lut(const float *codebooks, int M, int K, int dsub, const float *w, float *lut,
@@ -364,8 +374,8 @@ static int splits_of(int row_bytes) { return row_bytes >= kSegBytes ? row_bytes 
 hipError_t launch_pq_prepare(const float *lut, int M, float *image, const SelectWs &sw, const SelectWs &ssw,
                              hipStream_t s) {
     const int nsplit = splits_of(M);
-    pq_prepare_kernel<<<nsplit * 32, 256, 0, s>>>(lut, M, nsplit, image, sw.st, sw.hist1, sw.hist2, ssw.st, ssw.hist1,
-                                                  ssw.hist2);
+    pq_prepare_kernel<<<nsplit * 32, 256, 0, s>>>(lut, M, nsplit, image, sw.st, sw.hist1, sw.hist2, sw.hist3, ssw.st,
+                                                  ssw.hist1, ssw.hist2);
     return hipGetLastError();
 }
 
@@ -373,12 +383,13 @@ hipError_t launch_pq_prepare(const float *lut, int M, float *image, const Select
 hipError_t launch_binary_prepare(const float *w, int D, float *image, const SelectWs &sw, const SelectWs &ssw,
                                  hipStream_t s) {
     if (D == 2048) {
-        binary7_prepare_kernel<<<64, 256, 0, s>>>(w, image, sw.st, sw.hist1, sw.hist2, ssw.st, ssw.hist1, ssw.hist2);
+        binary7_prepare_kernel<<<64, 256, 0, s>>>(w, image, sw.st, sw.hist1, sw.hist2, sw.hist3, ssw.st, ssw.hist1,
+                                                  ssw.hist2);
         return hipGetLastError();
     }
     const int row_bytes = D / 8, nsplit = splits_of(row_bytes);
-    binary_prepare_kernel<<<nsplit * 32, 256, 0, s>>>(w, row_bytes, nsplit, image, sw.st, sw.hist1, sw.hist2, ssw.st,
-                                                      ssw.hist1, ssw.hist2);
+    binary_prepare_kernel<<<nsplit * 32, 256, 0, s>>>(w, row_bytes, nsplit, image, sw.st, sw.hist1, sw.hist2, sw.hist3,
+                                                      ssw.st, ssw.hist1, ssw.hist2);
     return hipGetLastError();
 }
 
@@ -393,6 +404,7 @@ struct ScanArgs {
     uint32_t *hist1;
     int k;
     const SelState *tau;
+    const uint32_t *tau_hist2;
     unsigned long long *cand;
     const SelState *gate;
 };
@@ -409,7 +421,8 @@ static hipError_t launch_scan_cfg(const ScanArgs &a, hipStream_t s) {
     if (grid < 1) grid = 1;
     const int threads = tune_int("OTF_SCAN_THREADS", kScanThreads);
     table_scan_kernel<LPR, U, GB, EMIT, SPLIT><<<grid, threads, lds, s>>>(
-        a.codes, (long long)a.N, a.M, a.nsplit, a.image, a.bias, a.scores, a.st, a.hist1, a.k, a.tau, a.cand, a.gate);
+        a.codes, (long long)a.N, a.M, a.nsplit, a.image, a.bias, a.scores, a.st, a.hist1, a.k, a.tau, a.tau_hist2, a.cand,
+        a.gate);
     return hipGetLastError();
 }
 
@@ -430,9 +443,10 @@ static hipError_t launch_scan_emit(const ScanArgs &a, ScanEmit emit, hipStream_t
 // row_bytes = stored bytes per row: 16, 32, 64 or a multiple of 128; seven_bit only with 256.
 hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, int seven_bit, const float *image,
                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
-                             const SelState *tau, unsigned long long *cand, const SelState *gate, hipStream_t s) {
-    ScanArgs a{codes, N, row_bytes, seven_bit ? 1 : splits_of(row_bytes), image, bias, scores, st, hist1, k, tau, cand,
-               gate};
+                             const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
+                             const SelState *gate, hipStream_t s) {
+    ScanArgs a{codes, N,  row_bytes, seven_bit ? 1 : splits_of(row_bytes), image, bias, scores, st, hist1, k, tau,
+               tau_hist2, cand, gate};
     if (seven_bit) return launch_scan_emit<16, 7>(a, emit, s);
     switch (row_bytes) {
         case 16: return launch_scan_emit<1, 8>(a, emit, s);
