@@ -166,10 +166,10 @@ __device__ __forceinline__ BinChoice block_find_bin(const uint32_t *ghist, int n
     return r;
 }
 
-// Rows [begin, end) of the chunk that selection block b of kSelBlocks owns; chunks are
+// Rows [begin, end) of the chunk that selection block b of nblocks owns; chunks are
 // contiguous, ascending in b, and a multiple of 1024 rows long (except the last).
-__device__ __forceinline__ void sel_chunk(long long N, int b, long long *begin, long long *end) {
-    long long per = (N + kSelBlocks - 1) / kSelBlocks;
+__device__ __forceinline__ void sel_chunk(long long N, int b, int nblocks, long long *begin, long long *end) {
+    long long per = (N + nblocks - 1) / nblocks;
     per = (per + 1023) / 1024 * 1024;
     long long s = per * b;
     long long e = s + per;

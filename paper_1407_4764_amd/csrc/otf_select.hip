@@ -65,7 +65,7 @@ __global__ __launch_bounds__(512) void hist1_kernel(const float *__restrict__ sc
     for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
     __syncthreads();
     long long begin, end;
-    sel_chunk(N, blockIdx.x, &begin, &end);
+    sel_chunk(N, blockIdx.x, gridDim.x, &begin, &end);
     for (long long t0 = begin; t0 < end; t0 += 4 * blockDim.x) {
         float v[4];
         bool ok[4];
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(512) void hist2_kernel(const float *__restrict__ sc
     for (int b = threadIdx.x; b < kBins2; b += blockDim.x) lhist[b] = 0u;
     __syncthreads();
     long long begin, end;
-    sel_chunk(N, blockIdx.x, &begin, &end);
+    sel_chunk(N, blockIdx.x, gridDim.x, &begin, &end);
     for (long long t0 = begin; t0 < end; t0 += 4 * blockDim.x) {
         float v[4];
         bool ok[4];
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(512) void hist3_kernel(const float *__restrict__ sc
     for (int b = threadIdx.x; b < kBins3; b += blockDim.x) lhist[b] = 0u;
     __syncthreads();
     long long begin, end;
-    sel_chunk(N, blockIdx.x, &begin, &end);
+    sel_chunk(N, blockIdx.x, gridDim.x, &begin, &end);
     for (long long t0 = begin; t0 < end; t0 += 4 * blockDim.x) {
         float v[4];
         bool ok[4];
@@ -198,10 +198,16 @@ __global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ s
     __shared__ uint32_t lhist[kBins3];
     __shared__ uint32_t s_out[3];
     __shared__ uint32_t wave_cnt[8];
+    // rows above the threshold are collected per block and appended with ONE device-wide atomic:
+    // thousands of atomics on the single cursor would serialise (~18 ns each)
+    constexpr uint32_t kLocalCap = 2048;
+    __shared__ unsigned long long local[kLocalCap];
+    __shared__ uint32_t s_local_n, s_base;
     if (gated && st_all[0].fallback == 0u) return;
     const int q = blockIdx.y;
     SelState *st = st_all + q;
     const uint32_t mode = st->mode;
+    if (threadIdx.x == 0) s_local_n = 0u;
     long long tex = st->tex;
     uint32_t T = 0, r = 0, eqbase = 0;
     if (mode == 2u) {
@@ -232,9 +238,10 @@ __global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ s
     const bool vec_ok = row_vec_ok(s);
     unsigned long long *cand = cand_all + (size_t)q * kCandCap;
     long long begin, end;
-    sel_chunk(N, blockIdx.x, &begin, &end);
+    sel_chunk(N, blockIdx.x, gridDim.x, &begin, &end);
     const bool ordered = (mode == 2u) && (eqbase < r);    // uniform over the block
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    __syncthreads();                                       // s_local_n is initialised
     for (long long t0 = begin; t0 < end; t0 += 4 * blockDim.x) {
         const long long i0 = t0 + 4 * threadIdx.x;
         float v[4];
@@ -246,8 +253,13 @@ __global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ s
         for (int j = 0; j < 4; ++j) {
             key[j] = float_to_key(v[j]);
             if (ok[j] && (long long)key[j] > tex) {
-                uint32_t pos = atomicAdd(&st->cursor, 1u);
-                if (pos < (uint32_t)kCandCap) cand[pos] = pack_cand(key[j], i0 + j);
+                const uint32_t lp = atomicAdd(&s_local_n, 1u);
+                if (lp < kLocalCap) {
+                    local[lp] = pack_cand(key[j], i0 + j);
+                } else {                                   // block buffer full: straight to the list
+                    uint32_t pos = atomicAdd(&st->cursor, 1u);
+                    if (pos < (uint32_t)kCandCap) cand[pos] = pack_cand(key[j], i0 + j);
+                }
             }
             neq += (ok[j] && key[j] == T) ? 1u : 0u;
         }
@@ -281,6 +293,14 @@ __global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ s
             eqbase += total;
             __syncthreads();
         }
+    }
+    __syncthreads();
+    const uint32_t nloc = s_local_n < kLocalCap ? s_local_n : kLocalCap;
+    if (threadIdx.x == 0 && nloc) s_base = atomicAdd(&st->cursor, nloc);
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < nloc; i += blockDim.x) {
+        const uint32_t pos = s_base + i;
+        if (pos < (uint32_t)kCandCap) cand[pos] = local[i];
     }
 }
 
@@ -485,6 +505,17 @@ static hipError_t allow_sort_lds() {
                                hipFuncAttributeMaxDynamicSharedMemorySize, kSortLdsBytes);
 }
 
+// Blocks per classifier of a selection pass: every block should have a few thousand rows, and
+// a few thousand blocks in total fill the chip (at most kSelBlocks: the pass-3 tables are that long).
+static int sel_blocks(int64_t N, int Q) {
+    int64_t by_rows = (N + 4095) / 4096;
+    int64_t by_chip = (4096 + Q - 1) / Q;
+    int64_t b = by_rows < by_chip ? by_rows : by_chip;
+    if (b > kSelBlocks) b = kSelBlocks;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
 hipError_t launch_select_init(const SelectWs &sw, int Q, hipStream_t s) {
     int blocks = (int)(((size_t)Q * kBins1 + 255) / 256);
     if (blocks > 1024) blocks = 1024;
@@ -494,13 +525,13 @@ hipError_t launch_select_init(const SelectWs &sw, int Q, hipStream_t s) {
 
 hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const SelectWs &sw, int gated,
                         hipStream_t s) {
-    hist1_kernel<<<dim3(kSelBlocks, Q), 512, 0, s>>>(scores, N, ld, sw.st, sw.hist1, gated);
+    hist1_kernel<<<dim3(sel_blocks(N, Q), Q), 512, 0, s>>>(scores, N, ld, sw.st, sw.hist1, gated);
     return hipGetLastError();
 }
 
 hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw,
                               float *out_scores, int32_t *out_idx, int gated, hipStream_t s) {
-    dim3 grid(kSelBlocks, Q);
+    dim3 grid(sel_blocks(N, Q), Q);
     hist2_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist1, sw.hist2, 0, gated ? sw.st : nullptr);
     hist3_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist2, sw.hist3, sw.blockhist3, gated);
     gather_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist3, sw.blockhist3, sw.cand, gated);
@@ -515,7 +546,7 @@ hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q,
 // one-block-per-classifier kernel; otherwise the consumer resolves them itself (resolve_tau).
 hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64_t ld, int Q, int m,
                                    const SelectWs &sample_sw, int publish_tau, hipStream_t s) {
-    hist2_kernel<<<dim3(kSelBlocks, Q), 512, 0, s>>>(sample_scores, Nv, ld, m, sample_sw.st, sample_sw.hist1,
+    hist2_kernel<<<dim3(sel_blocks(Nv, Q), Q), 512, 0, s>>>(sample_scores, Nv, ld, m, sample_sw.st, sample_sw.hist1,
                                                     sample_sw.hist2, 1, nullptr);
     if (publish_tau) sample_tau_kernel<<<Q, 512, 0, s>>>(sample_sw.st, sample_sw.hist2, m);
     return hipGetLastError();

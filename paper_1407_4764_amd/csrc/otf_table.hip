@@ -39,7 +39,7 @@ constexpr int kImageBytes = kImageFloats * 4;        // 128 KiB
 constexpr int kSideFloats = 16 * 64;                 // 4-bit groups of a 2048-bit row: 16 values x 64 words
 constexpr int kImage7Bytes = kImageBytes + kSideFloats * 4;   // 7-bit groups: 128 values x 256 columns, + side
 constexpr int kScanMaxThreads = 1024;
-constexpr int kScanThreads = 512;
+constexpr int kScanThreads = 1024;    // 16 waves per CU overlap the gathers with the row stream best
 
 __device__ __forceinline__ int image_column(int pos) {   // pos = byte position inside a 128-byte segment
     const int c = pos >> 4, tq = (pos >> 2) & 3, b = pos & 3;
@@ -429,6 +429,8 @@ static hipError_t launch_scan_cfg(const ScanArgs &a, hipStream_t s) {
 template <int LPR, int GB>
 static hipError_t launch_scan_emit(const ScanArgs &a, ScanEmit emit, hipStream_t s) {
     constexpr int U = LPR <= 2 ? 4 : 8;    // narrow rows own many outputs per lane: fewer loads per tile
+    if (LPR >= 8 && a.nsplit == 1 && emit == kEmitFilter && tune_int("OTF_SCAN_UNROLL", 8) == 4)
+        return launch_scan_cfg<LPR, 4, GB, kEmitFilter, false>(a, s);
     if (a.nsplit > 1) {
         if (GB != 8 || emit != kEmitScores) return hipErrorInvalidValue;
         return launch_scan_cfg<LPR, U, 8, kEmitScores, true>(a, s);
