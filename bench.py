@@ -31,12 +31,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the scoring kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/); filled in per workload once measured, None until then.
-MEASURED_TRAFFIC_BYTES = {
-    "dense": None,
-    "pq": None,
-    "binary": None,
-    "multiquery": None,
+# scaled by the same counters on a plain copy of known size (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).
+MEASURED_TRAFFIC_BYTES = {          # read + written, profiles/traffic_counters.md
+    "dense": 8.198e9 + 4.2e6,
+    "pq": 2.585e9 + 0.2e6,
+    "binary": 12.825e9 + 0.2e6,
+    "multiquery": 20.480e9 + 15.2e6,
 }
 
 WORKLOADS = {
@@ -167,7 +167,7 @@ def cpu_baseline(kind, cfg, torch):
     cores = orc.num_threads()
     keep = cfg["_keep"]
     k = cfg["k"]
-    budget_s = 8.0
+    budget_s = 10.0
     if kind == "dense":
         rows = min(cfg["N"], 262144)
         X = keep[0][:rows].cpu().numpy()
@@ -202,7 +202,7 @@ def cpu_baseline(kind, cfg, torch):
         run()
         reps += 1
         el = time.perf_counter() - t0
-        if el >= budget_s or reps >= 50:
+        if el >= budget_s:
             break
     return {"value": rows * reps / el, "unit": "vectors/s", "cores": cores, "kind": "oracle",
             "sample": "%s; %d repetitions in %.1f s" % (sample, reps, el)}
@@ -217,6 +217,8 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only; the result is then not the named workload)")
     ap.add_argument("--no-others", action="store_true", help="skip the other stores and the training pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of 2 GiB five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (each GPU would rank its own "
@@ -226,6 +228,14 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     binding.lib()                                  # fail loudly if the HIP library is missing
+    if args.calibrate_copy:
+        src = torch.full((1 << 29,), 1.0, dtype=torch.float32, device="cuda")     # 2 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "copies": 5}))
+        return
 
     res, cfg = measure(args.workload, args.steps, args.warmup, args.scale, torch, binding, synth)
     line = {
