@@ -409,7 +409,14 @@ __device__ __forceinline__ void select_sort_emit(uint8_t *lds, const unsigned lo
     }
     for (uint32_t b = tid; b < (uint32_t)kBins1; b += kSortThreads) hist[b] = 0u;
     __syncthreads();
-    if (lo <= hi) {
+    // block-wide range of the keys: one shared-memory atomic per wave
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t olo = (uint32_t)__shfl_xor((int)lo, o, 64), ohi = (uint32_t)__shfl_xor((int)hi, o, 64);
+        lo = olo < lo ? olo : lo;
+        hi = ohi > hi ? ohi : hi;
+    }
+    if ((tid & 63u) == 0u && lo <= hi) {
         atomicMin(&s_lo, lo);
         atomicMax(&s_hi, hi);
     }
@@ -434,10 +441,19 @@ __device__ __forceinline__ void select_sort_emit(uint8_t *lds, const unsigned lo
         }
         __syncthreads();
         const uint32_t bin = s_bin;
+        // survivors are compacted into a[]; slots are handed out per wave (one atomic per wave and step)
+        const uint32_t lane = tid & 63u;
 #pragma unroll
         for (int j = 0; j < EMAX; ++j) {
             const uint32_t i = (uint32_t)j * kSortThreads + tid;
-            if (i < n && (((uint32_t)(r[j] >> 32) - lo) >> sh) >= bin) a[atomicAdd(&s_cnt, 1u)] = r[j];
+            const bool keep = i < n && (((uint32_t)(r[j] >> 32) - lo) >> sh) >= bin;
+            const unsigned long long m = __ballot(keep);
+            if (m) {                                                   // uniform per wave
+                uint32_t base = 0;
+                if (lane == 0) base = atomicAdd(&s_cnt, (uint32_t)__popcll(m));
+                base = (uint32_t)__shfl((int)base, 0, 64);
+                if (keep) a[base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] = r[j];
+            }
         }
         __syncthreads();
         n2 = s_cnt;

@@ -178,7 +178,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // last full tile rather than being skipped (an unconditional load keeps the in-order wait
 // counters exact).  After the lookups the U row sums of a lane group are moved into U different
 // lanes so that the output step happens once per tile, not per row.
-template <int LPR, int U, int GB, int EMIT, bool SPLIT>
+template <int LPR, int U, int GB, int EMIT, bool SPLIT, int PD = 1>
 __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     const uint8_t *__restrict__ codes, long long N, int M, int nsplit, const float *__restrict__ image, float bias,
     float *__restrict__ scores, SelState *st, uint32_t *hist1, int k, const SelState *tau_state,
@@ -324,14 +324,21 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
 #pragma unroll
                 for (int e = 0; e < ROUNDS; ++e) emit(mine[e], carry, out_row(v0, e), e, true);
             };
-            u32x4 da[U], db[U];
-            float ca[ROUNDS], cb[ROUNDS];
-            fetch(da, ca, wave);
-            for (long long tile = wave; tile < nfull; tile += 2 * nwaves) {
-                fetch(db, cb, tile + nwaves);
-                consume(da, ca, tile);
-                fetch(da, ca, tile + 2 * nwaves);
-                if (tile + nwaves < nfull) consume(db, cb, tile + nwaves);
+            // ring of PD + 1 tile buffers: the loads of the tile PD steps ahead are issued before the
+            // current tile is consumed
+            constexpr int NB = PD + 1;
+            u32x4 buf[NB][U];
+            float car[NB][ROUNDS];
+#pragma unroll
+            for (int i = 0; i < PD; ++i) fetch(buf[i], car[i], wave + (long long)i * nwaves);
+            for (long long tile = wave; tile < nfull; tile += (long long)NB * nwaves) {
+#pragma unroll
+                for (int sl = 0; sl < NB; ++sl) {
+                    const long long t = tile + (long long)sl * nwaves;
+                    if (sl > 0 && t >= nfull) break;             // uniform
+                    fetch(buf[(sl + PD) % NB], car[(sl + PD) % NB], t + (long long)PD * nwaves);
+                    consume(buf[sl], car[sl], t);
+                }
             }
         }
         if (rem > 0 && wave == (int)(nfull % nwaves)) {   // the partial tile: same steps, row-checked
@@ -409,10 +416,10 @@ struct ScanArgs {
     const SelState *gate;
 };
 
-template <int LPR, int U, int GB, int EMIT, bool SPLIT>
+template <int LPR, int U, int GB, int EMIT, bool SPLIT, int PD = 1>
 static hipError_t launch_scan_cfg(const ScanArgs &a, hipStream_t s) {
     constexpr int lds = GB == 8 ? kImageBytes : kImage7Bytes;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&table_scan_kernel<LPR, U, GB, EMIT, SPLIT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&table_scan_kernel<LPR, U, GB, EMIT, SPLIT, PD>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     int grid = device_cu_count();
@@ -420,7 +427,7 @@ static hipError_t launch_scan_cfg(const ScanArgs &a, hipStream_t s) {
     if (grid > max_useful) grid = (int)max_useful;
     if (grid < 1) grid = 1;
     const int threads = tune_int("OTF_SCAN_THREADS", kScanThreads);
-    table_scan_kernel<LPR, U, GB, EMIT, SPLIT><<<grid, threads, lds, s>>>(
+    table_scan_kernel<LPR, U, GB, EMIT, SPLIT, PD><<<grid, threads, lds, s>>>(
         a.codes, (long long)a.N, a.M, a.nsplit, a.image, a.bias, a.scores, a.st, a.hist1, a.k, a.tau, a.tau_hist2, a.cand,
         a.gate);
     return hipGetLastError();
@@ -429,8 +436,12 @@ static hipError_t launch_scan_cfg(const ScanArgs &a, hipStream_t s) {
 template <int LPR, int GB>
 static hipError_t launch_scan_emit(const ScanArgs &a, ScanEmit emit, hipStream_t s) {
     constexpr int U = LPR <= 2 ? 4 : 8;    // narrow rows own many outputs per lane: fewer loads per tile
-    if (LPR >= 8 && a.nsplit == 1 && emit == kEmitFilter && tune_int("OTF_SCAN_UNROLL", 8) == 4)
-        return launch_scan_cfg<LPR, 4, GB, kEmitFilter, false>(a, s);
+    if (LPR >= 8 && a.nsplit == 1 && emit == kEmitFilter) {
+        const int u = tune_int("OTF_SCAN_UNROLL", 8), pd = tune_int("OTF_SCAN_PD", 1);
+        if (u == 4 && pd == 2) return launch_scan_cfg<LPR, 4, GB, kEmitFilter, false, 2>(a, s);
+        if (u == 4) return launch_scan_cfg<LPR, 4, GB, kEmitFilter, false>(a, s);
+
+    }
     if (a.nsplit > 1) {
         if (GB != 8 || emit != kEmitScores) return hipErrorInvalidValue;
         return launch_scan_cfg<LPR, U, 8, kEmitScores, true>(a, s);
