@@ -42,7 +42,8 @@ struct SelState {
     uint32_t ncand;    // entries the gather pass writes to the candidate list
     long long tex;     // gather every key with (long long)key > tex
     uint32_t cursor;   // append cursor of the gather pass
-    uint32_t spare[3];
+    uint32_t chunk_ctr[2];  // next chunk of a dynamically scheduled scan (two scans may share a state)
+    uint32_t spare;
     uint32_t tau_key;  // filter threshold: rows with key >= tau_key are candidates (filtered scans)
     uint32_t fallback; // set by the filtered path when its candidate list cannot serve: redo by full selection
 };

@@ -5,8 +5,8 @@
 //
 // Workgroup = 4 waves, tile = 128 dataset rows x QT*32 classifiers, K consumed 128 at a time.
 // X and W tiles go global -> registers -> shared memory (rows padded by 16 bytes so that the
-// 16-byte fragment reads of 8 consecutive lanes cover all 32 banks); the next tile's global
-// loads are issued before the matrix instructions of the current one.  Each wave owns 32 rows:
+// 16-byte fragment reads of 8 consecutive lanes cover all 32 banks); global loads run two K
+// steps ahead of the matrix instructions through two register stages.  Each wave owns 32 rows:
 // fragment A = 8 halves of a dataset row, fragment B = 8 halves of a classifier row, both from
 // the same K slots, fed to v_mfma_f32_32x32x16_f16.
 #include <hip/hip_fp16.h>
@@ -28,7 +28,7 @@ constexpr int kRowStride = kBK * 2 + 16; // bytes per tile row in shared memory
 // EMIT (ScanEmit): all scores; the scores of the strided sample (compact row numbering, N = number
 // of sample rows); or only the rows at or above each classifier's threshold, appended to its list.
 template <int QT, int EMIT>
-__global__ __launch_bounds__(256) void dense_mfma_kernel(const uint8_t *__restrict__ X, long long N, int D,
+__global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__restrict__ X, long long N, int D,
                                                          long long row_bytes, const uint8_t *__restrict__ W,
                                                          const float *__restrict__ bias, float *__restrict__ scores,
                                                          long long ld_scores, int vec_store,
@@ -52,63 +52,71 @@ __global__ __launch_bounds__(256) void dense_mfma_kernel(const uint8_t *__restri
         tau[qt] = EMIT == kEmitFilter ? tau_state[qt * 32 + n].tau_key : 0u;
     }
 
-    for (long long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const long long row0 = tile * kBM;
-        float16v acc[QT];
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[qt][v] = 0.f;
+    // The (tile, K step) pairs of this block form one flat sequence.  Global loads run two steps
+    // ahead of the matrix instructions through two register stages, across tile boundaries too,
+    // so there is no cold start per tile; loads past the block's last step re-read its last tile
+    // (unconditional loads keep the in-order wait counters exact).
+    const long long my_tiles = ntiles > (long long)blockIdx.x ? (ntiles - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
+    if (my_tiles == 0) return;
+    const long long total = my_tiles * ksteps;
 
-        // global -> register staging: X 8 chunks, W QT*2 chunks of 16 bytes per thread
-        u32x4 xr[8], wr[QT * 2];
-        const uint8_t *xsrc[8];
+    // load side
+    long long ltile = blockIdx.x;
+    // workgroups start at different K steps, so that those running in step do not ask the same
+    // memory channels for the same slice of W and of their rows at the same time
+    int lks = (int)(blockIdx.x % (unsigned)ksteps), lcount = 0;
+    // addresses = uniform base of the tile (scalar registers) + 32-bit per-lane offsets
+    const uint8_t *xbase;
+    uint32_t xoff[8], woff[QT * 2];
+#pragma unroll
+    for (int u = 0; u < QT * 2; ++u)
+        woff[u] = (uint32_t)((tid >> 4) + 16 * u) * (uint32_t)w_row_bytes + (uint32_t)(tid & 15) * 16u;
+    auto point_at_tile = [&](long long tile) {
+        long long row0 = tile * kBM;
+        const long long last = N - 1 - row0;          // rows past the end are computed (clamped), never stored
+        if (EMIT == kEmitSample)                      // compact sample row -> store row (tiles never straddle a group)
+            row0 = (row0 >> 10) * ((long long)kSampleGroup * kSampleStride) + (row0 & 1023);
+        xbase = X + (size_t)row0 * row_bytes;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int id = tid + 256 * u;
-            long long row = row0 + (id >> 4);
-            if (row >= N) row = N - 1;               // clamp: rows past the end are computed, never stored
-            if (EMIT == kEmitSample)                 // compact sample row -> store row
-                row = (row >> 10) * ((long long)kSampleGroup * kSampleStride) + (row & 1023);
-            xsrc[u] = X + (size_t)row * row_bytes + (size_t)(id & 15) * 16;
+            long long r = (tid >> 4) + 16 * u;
+            if (r > last) r = last;
+            xoff[u] = (uint32_t)r * (uint32_t)row_bytes + (uint32_t)(tid & 15) * 16u;
         }
-        auto load_step = [&](int ks) {
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                xr[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(xsrc[u] + (size_t)ks * (kBK * 2)));
-#pragma unroll
-            for (int u = 0; u < QT * 2; ++u) {
-                const int id = tid + 256 * u;
-                wr[u] = *reinterpret_cast<const u32x4 *>(W + (size_t)(id >> 4) * w_row_bytes + (size_t)ks * (kBK * 2) +
-                                                         (size_t)(id & 15) * 16);
-            }
-        };
-        load_step(0);
-        for (int ks = 0; ks < ksteps; ++ks) {
-            __syncthreads();                          // everyone has finished reading the previous tiles
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int id = tid + 256 * u;
-                *reinterpret_cast<u32x4 *>(xs + (id >> 4) * kRowStride + (id & 15) * 16) = xr[u];
-            }
-#pragma unroll
-            for (int u = 0; u < QT * 2; ++u) {
-                const int id = tid + 256 * u;
-                *reinterpret_cast<u32x4 *>(ws + (id >> 4) * kRowStride + (id & 15) * 16) = wr[u];
-            }
-            __syncthreads();
-            if (ks + 1 < ksteps) load_step(ks + 1);   // in flight while the matrix cores work
-            const uint8_t *arow = xs + (wave * 32 + n) * kRowStride + h * 16;
-#pragma unroll
-            for (int s = 0; s < kBK / 16; ++s) {
-                const half8 a = *reinterpret_cast<const half8 *>(arow + s * 32);
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt) {
-                    const half8 b = *reinterpret_cast<const half8 *>(ws + (qt * 32 + n) * kRowStride + h * 16 + s * 32);
-                    acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[qt], 0, 0, 0);
-                }
-            }
+    };
+    point_at_tile(ltile);
+    // piece p of 8: one X load, and one W load on the odd (QT = 2) or every fourth (QT = 1) piece
+    auto issue_piece = [&](u32x4 *xr, u32x4 *wr, int p) {
+        const uint8_t *xb = xbase + (size_t)lks * (kBK * 2);
+        const uint8_t *wb = W + (size_t)lks * (kBK * 2);
+        xr[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(xb + (size_t)xoff[p]));
+        constexpr int every = 8 / (QT * 2);
+        if (p % every == every - 1) wr[p / every] = *reinterpret_cast<const u32x4 *>(wb + (size_t)woff[p / every]);
+    };
+    auto advance_load = [&]() {
+        if (++lks == ksteps) lks = 0;
+        if (++lcount == ksteps) {                    // uniform
+            lcount = 0;
+            if (ltile + gridDim.x < ntiles) ltile += gridDim.x;
+            point_at_tile(ltile);
         }
+    };
+    auto issue_load = [&](u32x4 *xr, u32x4 *wr) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) issue_piece(xr, wr, p);
+        advance_load();
+    };
+
+    // compute side
+    long long ctile = blockIdx.x;
+    int cks = 0;
+    float16v acc[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[qt][v] = 0.f;
+
+    auto epilogue = [&](long long row0) {
         // accumulator element v of lane (n, h): dataset row 8*(v/4) + 4*h + v%4 of the wave's 32,
         // classifier n of the tile's 32
 #pragma unroll
@@ -140,8 +148,69 @@ __global__ __launch_bounds__(256) void dense_mfma_kernel(const uint8_t *__restri
                         if (row + j < N) dst[row + j] = o[j];
                 }
             }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[qt][v] = 0.f;
         }
+    };
+
+    auto body = [&](u32x4 *xr, u32x4 *wr) {
+        __syncthreads();                              // everyone has finished reading the previous tiles
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int id = tid + 256 * u;
+            *reinterpret_cast<u32x4 *>(xs + (id >> 4) * kRowStride + (id & 15) * 16) = xr[u];
+        }
+#pragma unroll
+        for (int u = 0; u < QT * 2; ++u) {
+            const int id = tid + 256 * u;
+            *reinterpret_cast<u32x4 *>(ws + (id >> 4) * kRowStride + (id & 15) * 16) = wr[u];
+        }
+        __syncthreads();
+        const uint8_t *arow = xs + (wave * 32 + n) * kRowStride + h * 16;
+        const uint8_t *brow = ws + n * kRowStride + h * 16;
+        {
+            // global loads spread between the matrix instructions, fragments read one slot ahead
+            half8 a = *reinterpret_cast<const half8 *>(arow), b[QT];
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) b[qt] = *reinterpret_cast<const half8 *>(brow + qt * 32 * kRowStride);
+#pragma unroll
+            for (int s = 0; s < kBK / 16; ++s) {
+                half8 an = a, bn[QT];
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) bn[qt] = b[qt];
+                if (s + 1 < kBK / 16) {
+                    an = *reinterpret_cast<const half8 *>(arow + (s + 1) * 32);
+#pragma unroll
+                    for (int qt = 0; qt < QT; ++qt)
+                        bn[qt] = *reinterpret_cast<const half8 *>(brow + qt * 32 * kRowStride + (s + 1) * 32);
+                }
+                issue_piece(xr, wr, s);
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b[qt], acc[qt], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                a = an;
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) b[qt] = bn[qt];
+            }
+            advance_load();
+        }
+        if (++cks == ksteps) {                        // uniform: the tile is complete
+            epilogue(ctile * kBM);
+            cks = 0;
+            ctile += gridDim.x;
+        }
+    };
+
+    u32x4 xr0[8], wr0[QT * 2], xr1[8], wr1[QT * 2];
+    issue_load(xr0, wr0);
+    issue_load(xr1, wr1);
+    // the odd last step stays outside the loop: a conditional second half would make the loop
+    // header see either stage as the younger one and wait for both
+    for (long long g = 0; g + 1 < total; g += 2) {
+        body(xr0, wr0);
+        body(xr1, wr1);
     }
+    if (total & 1) body(xr0, wr0);
 }
 
 template <int QT>

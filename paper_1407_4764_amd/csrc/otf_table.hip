@@ -118,6 +118,8 @@ __global__ __launch_bounds__(256) void binary_prepare_kernel(const float *__rest
 // Table image for 2048-bit rows: word q (0..63) of a row = lane-chunk q/4, word tq = q%4 of the chunk.
 //   main[v][64*tq + 4*chunk + j]  (v < 128)  group j of the word: dimensions 32q + 7j .. 32q + 7j + 6
 //   side[v][q]                    (v < 16)   the top four bits:   dimensions 32q + 28 .. 32q + 31
+// (The side reads are 4-way bank conflicts.  A duplicated, conflict-free side table was measured:
+// the conflict counter drops to zero and the scan gets 5 % slower, so the plain layout stays.)
 __global__ __launch_bounds__(256) void binary7_prepare_kernel(const float *__restrict__ w, float *__restrict__ image,
                                                               SelState *st, uint32_t *hist1, uint32_t *hist2,
                                                               uint32_t *hist3, SelState *sst, uint32_t *shist1,
@@ -173,12 +175,19 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 //   SPLIT  byte-group rows longer than 128 bytes: several phases, partial sums carried in the score
 //          array (EMIT = kEmitScores only)
 //
-// The main loop is branch-free and software-pipelined: the loads of the wave's next tile are
-// issued before the current tile is looked up, and prefetches past the end re-read the block's
-// last full tile rather than being skipped (an unconditional load keeps the in-order wait
-// counters exact).  After the lookups the U row sums of a lane group are moved into U different
-// lanes so that the output step happens once per tile, not per row.
-template <int LPR, int U, int GB, int EMIT, bool SPLIT, int PD = 1>
+// A tile is what one wave looks up per iteration: U loads of 64 lanes x 16 bytes.  The main loop
+// is software-pipelined: the loads of the wave's next tile are issued before the current tile is
+// looked up, and a prefetch with nothing left to fetch re-reads the current tile rather than
+// being skipped (an unconditional load keeps the in-order wait counters exact).  After the
+// lookups the U row sums of a lane group are moved into U different lanes so that the output
+// step happens once per tile, not per row.
+//
+// Work distribution (single-phase scans): the chip's eight dies stream at visibly different rates
+// and the waves of a workgroup drift apart, so a static split leaves a tail of 5-10 % in which
+// most of the chip idles.  Instead the rows are cut into chunks of 256 KiB; a workgroup draws
+// chunk numbers from a global counter (one atomic per chunk, fetched one chunk ahead) and its
+// waves draw the tiles of the current chunk from a ticket word in shared memory.
+template <int LPR, int U, int GB, int EMIT, bool SPLIT>
 __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     const uint8_t *__restrict__ codes, long long N, int M, int nsplit, const float *__restrict__ image, float bias,
     float *__restrict__ scores, SelState *st, uint32_t *hist1, int k, const SelState *tau_state,
@@ -186,6 +195,8 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     __shared__ uint32_t lhist[EMIT == kEmitFilter ? 1 : kBins1];
     __shared__ uint32_t s_out[3];
+    __shared__ unsigned long long s_cur;          // (chunk number << 32) | next tile ticket of that chunk
+    __shared__ uint32_t s_next;                   // number of the chunk after it, kNoChunk while being fetched
     if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
     constexpr int RPW = 64 / LPR;                // rows per wave load
     constexpr int TILE = RPW * U;                // rows per wave iteration
@@ -194,6 +205,19 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     constexpr int VSHIFT = GB == 8 ? 9 : 10;     // log2 of the byte stride between table values
     constexpr int TQ_BYTES = GB == 8 ? 128 : 256;  // byte distance between the column blocks of the 4 words
     constexpr int TABLE_VEC = (GB == 8 ? kImageBytes : kImage7Bytes) / 16;
+    constexpr uint32_t CHUNK_TILES = 256u / (uint32_t)U;          // x U KiB per tile = 256 KiB of rows
+    constexpr long long CHUNK_ROWS = (long long)CHUNK_TILES * TILE;
+    constexpr uint32_t kNoChunk = 0xFFFFFFFFu;
+
+    // the two scans that can follow each other on one state (filtered, then the gated full scan)
+    // count in different words; both were zeroed with the state
+    uint32_t *chunk_ctr = &st->chunk_ctr[EMIT == kEmitScores ? 1 : 0];
+    const uint32_t total_chunks = (uint32_t)((N + CHUNK_ROWS - 1) / CHUNK_ROWS);
+    if (!SPLIT && threadIdx.x == 0) {             // first two chunks of this workgroup (visible after the barriers below)
+        const uint32_t c = atomicAdd(chunk_ctr, 2u);
+        s_cur = (unsigned long long)c << 32;
+        s_next = c + 1u;
+    }
 
     if (EMIT != kEmitFilter)
         for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
@@ -220,19 +244,11 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     }
     const uint32_t sidecol = (uint32_t)(kImageBytes + 16 * chunk);   // GB == 7 only
 
-    // this block's rows: a contiguous range, a multiple of 1024 rows long (TILE divides 1024, so
-    // only the last block of the grid can end in a partial tile).  For the sample scan the rows
-    // are numbered compactly: sample row v is store row (v / 1024) * 1024 * stride + v % 1024.
-    long long per = (N + gridDim.x - 1) / gridDim.x;
-    per = (per + 1023) / 1024 * 1024;
-    long long begin = per * blockIdx.x, end = begin + per;
-    if (begin > N) begin = N;
-    if (end > N) end = N;
-    const long long nfull = (end - begin) / TILE;          // full tiles
-    const int rem = (int)((end - begin) % TILE);           // rows of the partial tile, if any
     const size_t u_bytes = (size_t)RPW * (size_t)M;        // distance between the U loads of a lane
     const int out_u = sub % ACTIVE;                        // which of a round's rows this lane emits
-    auto store_row = [&](long long v) {                    // store row of compact row v
+    // For the sample scan the rows are numbered compactly: sample row v is store row
+    // (v / 1024) * 1024 * stride + v % 1024 (a tile never straddles a group: TILE divides 1024).
+    auto store_row = [&](long long v) {
         return EMIT == kEmitSample ? ((v >> 10) * ((long long)kSampleGroup * kSampleStride) + (v & 1023)) : v;
     };
 
@@ -260,6 +276,18 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
         for (int i = 0; i < 4; ++i) v[i] += v[i + 4];
         return group_sum<LPR>((v[0] + v[1]) + (v[2] + v[3]));
     };
+    // looks up the U loads of a tile; the U row sums of a lane group (every lane of the group
+    // holds each sum) are kept by U different lanes: lane out_u keeps row e*ACTIVE + out_u
+    auto tile_sums = [&](const u32x4 *d, float *mine) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float su = lookup16(d[u]);
+            if (u % ACTIVE == 0) mine[u / ACTIVE] = su;
+            else mine[u / ACTIVE] = out_u == (u % ACTIVE) ? su : mine[u / ACTIVE];
+        }
+    };
+    // compact row that lane `sub` of its group emits in round e of the tile starting at row v0
+    auto out_row = [&](long long v0, int e) { return v0 + (long long)(e * ACTIVE + out_u) * RPW + rr; };
 
     for (int sp = 0; sp < nsplit; ++sp) {
         __syncthreads();                          // previous phase done with the table
@@ -270,8 +298,6 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
         }
         __syncthreads();
         const bool first = sp == 0, lastp = sp == nsplit - 1;
-        // byte offset of this lane inside its row (this phase's columns) plus its row inside the wave load
-        const size_t lane_off = (size_t)rr * (size_t)M + (size_t)sp * kSegBytes + (size_t)sub * 16;
 
         // one output round: lane `sub` of each group holds in `mine` the sum of the row it owns
         auto emit = [&](float mine, const float *carry, long long v, int e, bool ok) {
@@ -291,77 +317,163 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
                 }
             }
         };
-        // looks up the U loads of a tile; the U row sums of a lane group (every lane of the group
-        // holds each sum) are kept by U different lanes: lane out_u keeps row e*ACTIVE + out_u
-        auto tile_sums = [&](const u32x4 *d, float *mine) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const float su = lookup16(d[u]);
-                if (u % ACTIVE == 0) mine[u / ACTIVE] = su;
-                else mine[u / ACTIVE] = out_u == (u % ACTIVE) ? su : mine[u / ACTIVE];
-            }
-        };
-        // compact row that lane `sub` of its group emits in round e of the tile starting at row v0
-        auto out_row = [&](long long v0, int e) { return v0 + (long long)(e * ACTIVE + out_u) * RPW + rr; };
 
-        if (wave < nfull) {                       // uniform per wave
-            auto fetch = [&](u32x4 *d, float *carry, long long tile) {
-                if (tile > nfull - 1) tile = nfull - 1;      // uniform: prefetch past the end re-reads the last tile
-                const long long v0 = begin + tile * TILE;
-                const uint8_t *p = codes + (size_t)store_row(v0) * (size_t)M + lane_off;
+        if (!SPLIT) {
+            // next tile of this wave: first row, or -1 when the scan has no tile left (wave-uniform)
+            auto draw = [&]() -> long long {
+                uint32_t gid = 0u, off = 0u;
+                if (lane == 0) {
+                    for (;;) {
+                        const unsigned long long old =
+                            __hip_atomic_fetch_add(&s_cur, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        gid = (uint32_t)(old >> 32);
+                        off = (uint32_t)old;
+                        if (gid >= total_chunks) break;                       // nothing left
+                        if (off < CHUNK_TILES) {
+                            if ((long long)gid * CHUNK_ROWS + (long long)(off + 1u) * TILE <= N) break;   // a full tile
+                            continue;                                         // past the last full tile
+                        }
+                        if (off == CHUNK_TILES) {
+                            // first ticket past the chunk: this wave installs the next chunk and orders
+                            // the chunk after it (the others retry until the new chunk appears)
+                            uint32_t g;
+                            while ((g = __hip_atomic_exchange(&s_next, kNoChunk, __ATOMIC_RELAXED,
+                                                              __HIP_MEMORY_SCOPE_WORKGROUP)) == kNoChunk)
+                                __builtin_amdgcn_s_sleep(2);
+                            __hip_atomic_store(&s_cur, (unsigned long long)g << 32, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_WORKGROUP);
+                            const uint32_t after = g < total_chunks ? atomicAdd(chunk_ctr, 1u) : g;
+                            __hip_atomic_store(&s_next, after, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                            continue;                                         // and draws again like everyone else
+                        }
+                        __builtin_amdgcn_s_sleep(2);                          // another wave is installing
+                    }
+                }
+                gid = __builtin_amdgcn_readfirstlane(gid);
+                off = __builtin_amdgcn_readfirstlane(off);
+                return gid >= total_chunks ? -1LL : (long long)gid * CHUNK_ROWS + (long long)off * TILE;
+            };
+            // uniform base of the tile (scalar registers) + one 32-bit lane offset
+            const uint32_t lane_off = (uint32_t)rr * (uint32_t)M + (uint32_t)sub * 16u;
+            auto fetch = [&](u32x4 *d, long long v0) {
+                const unsigned long long a = (unsigned long long)store_row(v0) * (unsigned long long)M;
+                // (the builtin returns int: go through uint32_t, or offsets past 2 GiB are sign-extended)
+                const uint32_t a_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));
+                const uint32_t a_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+                const uint8_t *p = codes + (((unsigned long long)a_hi << 32) | (unsigned long long)a_lo);
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    d[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + (size_t)u * u_bytes));
-                if (SPLIT) {
-#pragma unroll
-                    for (int e = 0; e < ROUNDS; ++e) carry[e] = scores[out_row(v0, e)];
-                }
+                    d[u] = __builtin_nontemporal_load(
+                        reinterpret_cast<const u32x4 *>(p + (size_t)u * u_bytes + (size_t)lane_off));
             };
-            auto consume = [&](const u32x4 *d, const float *carry, long long tile) {
+            auto consume = [&](const u32x4 *d, long long v0) {
                 float mine[ROUNDS];
                 tile_sums(d, mine);
-                const long long v0 = begin + tile * TILE;
 #pragma unroll
-                for (int e = 0; e < ROUNDS; ++e) emit(mine[e], carry, out_row(v0, e), e, true);
+                for (int e = 0; e < ROUNDS; ++e) {
+                    const long long v = out_row(v0, e);
+                    emit(mine[e], nullptr, v, e, true);
+                }
             };
-            // ring of PD + 1 tile buffers: the loads of the tile PD steps ahead are issued before the
-            // current tile is consumed
-            constexpr int NB = PD + 1;
-            u32x4 buf[NB][U];
-            float car[NB][ROUNDS];
-#pragma unroll
-            for (int i = 0; i < PD; ++i) fetch(buf[i], car[i], wave + (long long)i * nwaves);
-            for (long long tile = wave; tile < nfull; tile += (long long)NB * nwaves) {
-#pragma unroll
-                for (int sl = 0; sl < NB; ++sl) {
-                    const long long t = tile + (long long)sl * nwaves;
-                    if (sl > 0 && t >= nfull) break;             // uniform
-                    fetch(buf[(sl + PD) % NB], car[(sl + PD) % NB], t + (long long)PD * nwaves);
-                    consume(buf[sl], car[sl], t);
+            long long cur = draw();
+            if (cur >= 0) {
+                u32x4 b0[U], b1[U];
+                fetch(b0, cur);
+                for (;;) {
+                    long long nxt = draw();
+                    fetch(b1, nxt >= 0 ? nxt : cur);
+                    consume(b0, cur);
+                    if (nxt < 0) break;
+                    cur = nxt;
+                    nxt = draw();
+                    fetch(b0, nxt >= 0 ? nxt : cur);
+                    consume(b1, cur);
+                    if (nxt < 0) break;
+                    cur = nxt;
                 }
             }
-        }
-        if (rem > 0 && wave == (int)(nfull % nwaves)) {   // the partial tile: same steps, row-checked
-            const long long v0 = begin + nfull * TILE;
-            u32x4 d[U];
-            float carry[ROUNDS], mine[ROUNDS];
+            // the rows after the last full tile (fewer than a tile): one wave, row-checked
+            const long long v0 = N / TILE * TILE;
+            if (v0 < N && blockIdx.x == 0 && wave == 0) {
+                u32x4 d[U];
+                float mine[ROUNDS];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const long long v = v0 + (long long)u * RPW + rr;
-                d[u] = (u32x4){0u, 0u, 0u, 0u};
-                if (v < end)
-                    d[u] = *reinterpret_cast<const u32x4 *>(codes + (size_t)store_row(v - rr) * (size_t)M + lane_off);
+                for (int u = 0; u < U; ++u) {
+                    const long long v = v0 + (long long)u * RPW + rr;
+                    d[u] = (u32x4){0u, 0u, 0u, 0u};
+                    if (v < N)
+                        d[u] = *reinterpret_cast<const u32x4 *>(codes + (size_t)store_row(v) * (size_t)M + (size_t)sub * 16);
+                }
+                tile_sums(d, mine);
+#pragma unroll
+                for (int e = 0; e < ROUNDS; ++e) {
+                    const long long v = out_row(v0, e);
+                    emit(mine[e], nullptr, v, e, v < N);
+                }
             }
+        } else {
+            // several phases: every phase must meet the partial sums of the one before, so each
+            // workgroup keeps a fixed contiguous range of rows (a multiple of 1024 long, so only the
+            // last workgroup can end in a partial tile) and its waves take the tiles round-robin
+            long long per = (N + gridDim.x - 1) / gridDim.x;
+            per = (per + 1023) / 1024 * 1024;
+            long long begin = per * blockIdx.x, end = begin + per;
+            if (begin > N) begin = N;
+            if (end > N) end = N;
+            const long long nfull = (end - begin) / TILE;          // full tiles
+            const int rem = (int)((end - begin) % TILE);           // rows of the partial tile, if any
+            // byte offset of this lane inside its row (this phase's columns) plus its row inside the wave load
+            const size_t lane_off = (size_t)rr * (size_t)M + (size_t)sp * kSegBytes + (size_t)sub * 16;
+            if (wave < nfull) {                       // uniform per wave
+                auto fetch = [&](u32x4 *d, float *carry, long long tile) {
+                    if (tile > nfull - 1) tile = nfull - 1;      // uniform: prefetch past the end re-reads the last tile
+                    const long long v0 = begin + tile * TILE;
+                    const uint8_t *p = codes + (size_t)v0 * (size_t)M + lane_off;
 #pragma unroll
-            for (int e = 0; e < ROUNDS; ++e) {
-                const long long v = out_row(v0, e);
-                carry[e] = (SPLIT && !first && v < end) ? scores[v] : 0.f;
+                    for (int u = 0; u < U; ++u)
+                        d[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + (size_t)u * u_bytes));
+#pragma unroll
+                    for (int e = 0; e < ROUNDS; ++e) carry[e] = scores[out_row(v0, e)];
+                };
+                auto consume = [&](const u32x4 *d, const float *carry, long long tile) {
+                    float mine[ROUNDS];
+                    tile_sums(d, mine);
+                    const long long v0 = begin + tile * TILE;
+#pragma unroll
+                    for (int e = 0; e < ROUNDS; ++e) emit(mine[e], carry, out_row(v0, e), e, true);
+                };
+                u32x4 buf[2][U];
+                float car[2][ROUNDS];
+                fetch(buf[0], car[0], wave);
+                for (long long tile = wave; tile < nfull; tile += 2LL * nwaves) {
+                    fetch(buf[1], car[1], tile + nwaves);
+                    consume(buf[0], car[0], tile);
+                    if (tile + nwaves >= nfull) break;           // uniform
+                    fetch(buf[0], car[0], tile + 2LL * nwaves);
+                    consume(buf[1], car[1], tile + nwaves);
+                }
             }
-            tile_sums(d, mine);
+            if (rem > 0 && wave == (int)(nfull % nwaves)) {   // the partial tile: same steps, row-checked
+                const long long v0 = begin + nfull * TILE;
+                u32x4 d[U];
+                float carry[ROUNDS], mine[ROUNDS];
 #pragma unroll
-            for (int e = 0; e < ROUNDS; ++e) {
-                const long long v = out_row(v0, e);
-                emit(mine[e], carry, v, e, v < end);
+                for (int u = 0; u < U; ++u) {
+                    const long long v = v0 + (long long)u * RPW + rr;
+                    d[u] = (u32x4){0u, 0u, 0u, 0u};
+                    if (v < end) d[u] = *reinterpret_cast<const u32x4 *>(codes + (size_t)(v - rr) * (size_t)M + lane_off);
+                }
+#pragma unroll
+                for (int e = 0; e < ROUNDS; ++e) {
+                    const long long v = out_row(v0, e);
+                    carry[e] = (!first && v < end) ? scores[v] : 0.f;
+                }
+                tile_sums(d, mine);
+#pragma unroll
+                for (int e = 0; e < ROUNDS; ++e) {
+                    const long long v = out_row(v0, e);
+                    emit(mine[e], carry, v, e, v < end);
+                }
             }
         }
     }
@@ -416,10 +528,10 @@ struct ScanArgs {
     const SelState *gate;
 };
 
-template <int LPR, int U, int GB, int EMIT, bool SPLIT, int PD = 1>
+template <int LPR, int U, int GB, int EMIT, bool SPLIT>
 static hipError_t launch_scan_cfg(const ScanArgs &a, hipStream_t s) {
     constexpr int lds = GB == 8 ? kImageBytes : kImage7Bytes;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&table_scan_kernel<LPR, U, GB, EMIT, SPLIT, PD>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&table_scan_kernel<LPR, U, GB, EMIT, SPLIT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     int grid = device_cu_count();
@@ -427,7 +539,7 @@ static hipError_t launch_scan_cfg(const ScanArgs &a, hipStream_t s) {
     if (grid > max_useful) grid = (int)max_useful;
     if (grid < 1) grid = 1;
     const int threads = tune_int("OTF_SCAN_THREADS", kScanThreads);
-    table_scan_kernel<LPR, U, GB, EMIT, SPLIT, PD><<<grid, threads, lds, s>>>(
+    table_scan_kernel<LPR, U, GB, EMIT, SPLIT><<<grid, threads, lds, s>>>(
         a.codes, (long long)a.N, a.M, a.nsplit, a.image, a.bias, a.scores, a.st, a.hist1, a.k, a.tau, a.tau_hist2, a.cand,
         a.gate);
     return hipGetLastError();
@@ -437,9 +549,7 @@ template <int LPR, int GB>
 static hipError_t launch_scan_emit(const ScanArgs &a, ScanEmit emit, hipStream_t s) {
     constexpr int U = LPR <= 2 ? 4 : 8;    // narrow rows own many outputs per lane: fewer loads per tile
     if (LPR >= 8 && a.nsplit == 1 && emit == kEmitFilter) {
-        const int u = tune_int("OTF_SCAN_UNROLL", 8), pd = tune_int("OTF_SCAN_PD", 1);
-        if (u == 4 && pd == 2) return launch_scan_cfg<LPR, 4, GB, kEmitFilter, false, 2>(a, s);
-        if (u == 4) return launch_scan_cfg<LPR, 4, GB, kEmitFilter, false>(a, s);
+        if (tune_int("OTF_SCAN_UNROLL", 8) == 4) return launch_scan_cfg<LPR, 4, GB, kEmitFilter, false>(a, s);
 
     }
     if (a.nsplit > 1) {
