@@ -249,7 +249,7 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
     } else if (e == hipSuccess) {
         for (int q = 0; q < Q && e == hipSuccess; ++q)
             e = launch_dense_scan(X, x_half, N, D, ldx, Wb + (size_t)q * D * wsize, w_half, bias, q,
-                                  S + (size_t)q * ldS, sw.hist1 + (size_t)q * kBins1, s);
+                                  S + (size_t)q * ldS, sw.hist1 + (size_t)q * kBins1, &sw.st[q].chunk_ctr[1], s);
         timer.stop();
     }
     if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, 0, s);

@@ -59,22 +59,25 @@ __device__ __forceinline__ float load_w(const void *w, int w_is_half, int d) {
 
 // ---------------------------------------------------------------------------------------------
 // Wide rows: one wave per row, V 16-byte chunks per lane (D <= 64 * V * elems-per-chunk).
-// Each block owns one contiguous range of rows, its waves taking rows of the range in turn, so
-// a block streams one contiguous region of the store.
 //
 // FULL (D == 64 * V * elems-per-chunk exactly, e.g. 2048 fp32 with V = 8): branch-free and
 // software-pipelined.  The loads of the wave's next row are issued before the current row is
 // reduced, so 2*V 16-byte loads per lane stay in flight; with few, long-lived waves this is what
-// saturates HBM (many waves with shallow queues do not).  Prefetches past the wave's last row
-// are redirected to its last valid row instead of being skipped: an unconditional load keeps the
-// in-order wait counters exact, a conditional one would force a full drain every iteration.
+// saturates HBM (many waves with shallow queues do not).  A prefetch with no row left re-reads
+// the current row instead of being skipped: an unconditional load keeps the in-order wait
+// counters exact, a conditional one would force a full drain every iteration.  Rows are handed
+// out dynamically (TileQueue: one row per ticket, chunks of 256 KiB of rows).
+// Otherwise each block owns one contiguous range of rows, its waves taking its rows in turn.
 template <bool XHALF, int V, bool FULL>
 __global__ __launch_bounds__(256) void dense_wide_kernel(const uint8_t *__restrict__ X, long long N, int D,
                                                          long long row_bytes, const void *__restrict__ w,
                                                          int w_is_half, const float *__restrict__ bias_ptr,
-                                                         int bias_index, float *__restrict__ scores, uint32_t *hist1) {
+                                                         int bias_index, float *__restrict__ scores, uint32_t *hist1,
+                                                         uint32_t *chunk_ctr) {
     constexpr int E = Elem<XHALF>::kPer16;
     __shared__ uint32_t lhist[kBins1];
+    __shared__ TileQueue s_queue;
+    if (FULL && threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);
     for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
     __syncthreads();
 
@@ -122,22 +125,28 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const uint8_t *__restri
     };
 
     if (FULL) {
-        if (begin + wave < end) {                           // uniform per wave
-            const long long last = begin + wave + ((end - 1 - begin - wave) / nwaves) * nwaves;  // wave's last row
-            const uint8_t *base = X + (size_t)lane * 16;
-            auto fetch = [&](Chunk16 *c, long long r) {
-                const uint8_t *p = base + (size_t)(r <= last ? r : last) * (size_t)row_bytes;
+        constexpr uint32_t CHUNK_ROWS = 256u / (uint32_t)V;   // x V KiB per row = 256 KiB
+        const uint8_t *base = X + (size_t)lane * 16;
+        auto fetch = [&](Chunk16 *c, long long r) {
+            const uint8_t *p = base + (size_t)r * (size_t)row_bytes;
 #pragma unroll
-                for (int j = 0; j < V; ++j) c[j] = load_stream16(p + (size_t)j * 1024);
-            };
+            for (int j = 0; j < V; ++j) c[j] = load_stream16(p + (size_t)j * 1024);
+        };
+        long long cur = tile_queue_draw(&s_queue, chunk_ctr, CHUNK_ROWS, N);
+        if (cur >= 0) {                                     // uniform per wave
             Chunk16 a[V], b[V];
-            fetch(a, begin + wave);
-            for (long long r = begin + wave; r <= last; r += 2 * nwaves) {
-                fetch(b, r + nwaves);
-                emit(r, dot(a));
-                fetch(a, r + 2 * nwaves);
-                const float sb = dot(b);
-                if (r + nwaves <= last) emit(r + nwaves, sb);
+            fetch(a, cur);
+            for (;;) {
+                long long nxt = tile_queue_draw(&s_queue, chunk_ctr, CHUNK_ROWS, N);
+                fetch(b, nxt >= 0 ? nxt : cur);
+                emit(cur, dot(a));
+                if (nxt < 0) break;
+                cur = nxt;
+                nxt = tile_queue_draw(&s_queue, chunk_ctr, CHUNK_ROWS, N);
+                fetch(a, nxt >= 0 ? nxt : cur);
+                emit(cur, dot(b));
+                if (nxt < 0) break;
+                cur = nxt;
             }
         }
     } else {
@@ -268,12 +277,13 @@ __global__ __launch_bounds__(256) void dense_huge_kernel(const uint8_t *__restri
 template <bool XHALF>
 static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t row_bytes, const void *w,
                                      int w_is_half, const float *bias_ptr, int bias_index, float *scores,
-                                     uint32_t *hist1, hipStream_t s) {
+                                     uint32_t *hist1, uint32_t *chunk_ctr, hipStream_t s) {
     constexpr int E = Elem<XHALF>::kPer16;
     const int chunks = (D + E - 1) / E;              // 16-byte chunks per row
     const int cus = device_cu_count();
     int grid;
 #define OTF_ARGS X, (long long)N, D, (long long)row_bytes, w, w_is_half, bias_ptr, bias_index, scores, hist1
+#define OTF_WIDE_ARGS OTF_ARGS, chunk_ctr
     if (chunks <= 32) {
         int lpr = 1;
         while (lpr < chunks) lpr <<= 1;
@@ -296,8 +306,8 @@ static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t
         const bool full = chunks == V * 64;
 #define OTF_WIDE(VV)                                                                        \
     do {                                                                                    \
-        if (full) dense_wide_kernel<XHALF, VV, true><<<grid, 256, 0, s>>>(OTF_ARGS);        \
-        else dense_wide_kernel<XHALF, VV, false><<<grid, 256, 0, s>>>(OTF_ARGS);            \
+        if (full) dense_wide_kernel<XHALF, VV, true><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS);   \
+        else dense_wide_kernel<XHALF, VV, false><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS);       \
     } while (0)
         if (V <= 1) OTF_WIDE(1);
         else if (V <= 2) OTF_WIDE(2);
@@ -312,17 +322,18 @@ static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t
             dense_huge_kernel<XHALF><<<grid, 256, (size_t)D * 4, s>>>(OTF_ARGS);
         }
     }
+#undef OTF_WIDE_ARGS
 #undef OTF_ARGS
     return hipGetLastError();
 }
 
 hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int64_t ldx, const void *w,
                              int w_is_half, const float *bias_ptr, int bias_index, float *scores, uint32_t *hist1,
-                             hipStream_t s) {
+                             uint32_t *chunk_ctr, hipStream_t s) {
     const uint8_t *Xb = reinterpret_cast<const uint8_t *>(X);
     if (x_is_half)
-        return launch_dense_typed<true>(Xb, N, D, ldx * 2, w, w_is_half, bias_ptr, bias_index, scores, hist1, s);
-    return launch_dense_typed<false>(Xb, N, D, ldx * 4, w, w_is_half, bias_ptr, bias_index, scores, hist1, s);
+        return launch_dense_typed<true>(Xb, N, D, ldx * 2, w, w_is_half, bias_ptr, bias_index, scores, hist1, chunk_ctr, s);
+    return launch_dense_typed<false>(Xb, N, D, ldx * 4, w, w_is_half, bias_ptr, bias_index, scores, hist1, chunk_ctr, s);
 }
 
 }  // namespace otf

@@ -167,6 +167,66 @@ __device__ __forceinline__ BinChoice block_find_bin(const uint32_t *ghist, int n
     return r;
 }
 
+// Dynamic work distribution for the streaming scans.  The chip's eight dies stream at visibly
+// different rates and the waves of a workgroup drift apart, so a static split of the rows leaves
+// a tail of 5-10 % in which most of the chip idles.  Instead the work is cut into tiles (what one
+// wave handles per iteration) and chunks of `chunk_tiles` consecutive tiles (about 256 KiB of
+// rows).  A workgroup draws chunk numbers from a counter in global memory (zero before the
+// launch; one atomic per chunk, ordered one chunk ahead so its latency hides behind a chunk of
+// work) and its waves draw the tiles of the current chunk from a ticket word in shared memory.
+struct TileQueue {
+    unsigned long long cur;   // (chunk number << 32) | next tile ticket of that chunk
+    uint32_t next;            // number of the chunk after it; kNoChunk while it is being ordered
+};
+constexpr uint32_t kNoChunk = 0xFFFFFFFFu;
+
+// One thread per workgroup, before a barrier that precedes the first tile_queue_draw.
+__device__ __forceinline__ void tile_queue_init(TileQueue *q, uint32_t *chunk_ctr) {
+    const uint32_t c = atomicAdd(chunk_ctr, 2u);
+    q->cur = (unsigned long long)c << 32;
+    q->next = c + 1u;
+}
+
+// Whole wave (all lanes active): the next tile of this wave, or -1 when none is left.  The result
+// is the same in every lane.  Tiles are numbered chunk * chunk_tiles + ticket; only tiles below
+// total_tiles exist.
+__device__ __forceinline__ long long tile_queue_draw(TileQueue *q, uint32_t *chunk_ctr, uint32_t chunk_tiles,
+                                                     long long total_tiles) {
+    const uint32_t total_chunks = (uint32_t)((total_tiles + chunk_tiles - 1) / chunk_tiles);
+    uint32_t gid = 0u, off = 0u;
+    if ((threadIdx.x & 63) == 0) {
+        for (;;) {
+            const unsigned long long old =
+                __hip_atomic_fetch_add(&q->cur, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            gid = (uint32_t)(old >> 32);
+            off = (uint32_t)old;
+            if (gid >= total_chunks) break;                                   // nothing left
+            if (off < chunk_tiles) {
+                if ((long long)gid * chunk_tiles + off < total_tiles) break;  // a tile
+                continue;                                                     // past the last tile of the last chunk
+            }
+            if (off == chunk_tiles) {
+                // first ticket past the chunk: this wave installs the next chunk and orders the
+                // chunk after it (the others retry until the new chunk appears)
+                uint32_t g;
+                while ((g = __hip_atomic_exchange(&q->next, kNoChunk, __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_WORKGROUP)) == kNoChunk)
+                    __builtin_amdgcn_s_sleep(2);
+                __hip_atomic_store(&q->cur, (unsigned long long)g << 32, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+                const uint32_t after = g < total_chunks ? atomicAdd(chunk_ctr, 1u) : g;
+                __hip_atomic_store(&q->next, after, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                continue;                                                     // and draws again like everyone else
+            }
+            __builtin_amdgcn_s_sleep(2);                                      // another wave is installing
+        }
+    }
+    // (the builtin works on int; the values are unsigned)
+    gid = (uint32_t)__builtin_amdgcn_readfirstlane((int)gid);
+    off = (uint32_t)__builtin_amdgcn_readfirstlane((int)off);
+    return gid >= total_chunks ? -1LL : (long long)gid * chunk_tiles + off;
+}
+
 // Rows [begin, end) of the chunk that selection block b of nblocks owns; chunks are
 // contiguous, ascending in b, and a multiple of 1024 rows long (except the last).
 __device__ __forceinline__ void sel_chunk(long long N, int b, int nblocks, long long *begin, long long *end) {

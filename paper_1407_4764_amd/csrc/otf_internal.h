@@ -55,9 +55,10 @@ hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64
 hipError_t launch_filter_sort(const SelectWs &sw, int Q, int k, float *out_scores, int32_t *out_idx, hipStream_t s);
 
 // Dense single-classifier scan: writes N scores (bias included) and accumulates the pass-1 histogram.
+// chunk_ctr: a zeroed word in global memory (work counter of the dynamically scheduled kernels).
 hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int64_t ldx,
                              const void *w, int w_is_half, const float *bias_ptr, int bias_index,
-                             float *scores, uint32_t *hist1, hipStream_t s);
+                             float *scores, uint32_t *hist1, uint32_t *chunk_ctr, hipStream_t s);
 
 // Multi-classifier fp16 scan on the matrix cores (Q = 32 or 64 classifiers per call).
 //   kEmitScores  scores[q][i] for every row (row stride ld_scores); with `gate` set the kernel returns

@@ -182,11 +182,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // lookups the U row sums of a lane group are moved into U different lanes so that the output
 // step happens once per tile, not per row.
 //
-// Work distribution (single-phase scans): the chip's eight dies stream at visibly different rates
-// and the waves of a workgroup drift apart, so a static split leaves a tail of 5-10 % in which
-// most of the chip idles.  Instead the rows are cut into chunks of 256 KiB; a workgroup draws
-// chunk numbers from a global counter (one atomic per chunk, fetched one chunk ahead) and its
-// waves draw the tiles of the current chunk from a ticket word in shared memory.
+// Work distribution (single-phase scans): dynamic, by a TileQueue with chunks of 256 KiB of rows.
 template <int LPR, int U, int GB, int EMIT, bool SPLIT>
 __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     const uint8_t *__restrict__ codes, long long N, int M, int nsplit, const float *__restrict__ image, float bias,
@@ -195,8 +191,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     __shared__ uint32_t lhist[EMIT == kEmitFilter ? 1 : kBins1];
     __shared__ uint32_t s_out[3];
-    __shared__ unsigned long long s_cur;          // (chunk number << 32) | next tile ticket of that chunk
-    __shared__ uint32_t s_next;                   // number of the chunk after it, kNoChunk while being fetched
+    __shared__ TileQueue s_queue;
     if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
     constexpr int RPW = 64 / LPR;                // rows per wave load
     constexpr int TILE = RPW * U;                // rows per wave iteration
@@ -206,18 +201,11 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     constexpr int TQ_BYTES = GB == 8 ? 128 : 256;  // byte distance between the column blocks of the 4 words
     constexpr int TABLE_VEC = (GB == 8 ? kImageBytes : kImage7Bytes) / 16;
     constexpr uint32_t CHUNK_TILES = 256u / (uint32_t)U;          // x U KiB per tile = 256 KiB of rows
-    constexpr long long CHUNK_ROWS = (long long)CHUNK_TILES * TILE;
-    constexpr uint32_t kNoChunk = 0xFFFFFFFFu;
 
     // the two scans that can follow each other on one state (filtered, then the gated full scan)
     // count in different words; both were zeroed with the state
     uint32_t *chunk_ctr = &st->chunk_ctr[EMIT == kEmitScores ? 1 : 0];
-    const uint32_t total_chunks = (uint32_t)((N + CHUNK_ROWS - 1) / CHUNK_ROWS);
-    if (!SPLIT && threadIdx.x == 0) {             // first two chunks of this workgroup (visible after the barriers below)
-        const uint32_t c = atomicAdd(chunk_ctr, 2u);
-        s_cur = (unsigned long long)c << 32;
-        s_next = c + 1u;
-    }
+    if (!SPLIT && threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);   // visible after the barriers below
 
     if (EMIT != kEmitFilter)
         for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
@@ -319,39 +307,11 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
         };
 
         if (!SPLIT) {
-            // next tile of this wave: first row, or -1 when the scan has no tile left (wave-uniform)
+            // first row of the next tile of this wave, or -1 when the scan has no full tile left
+            // (the rows after the last full tile are handled at the end)
             auto draw = [&]() -> long long {
-                uint32_t gid = 0u, off = 0u;
-                if (lane == 0) {
-                    for (;;) {
-                        const unsigned long long old =
-                            __hip_atomic_fetch_add(&s_cur, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                        gid = (uint32_t)(old >> 32);
-                        off = (uint32_t)old;
-                        if (gid >= total_chunks) break;                       // nothing left
-                        if (off < CHUNK_TILES) {
-                            if ((long long)gid * CHUNK_ROWS + (long long)(off + 1u) * TILE <= N) break;   // a full tile
-                            continue;                                         // past the last full tile
-                        }
-                        if (off == CHUNK_TILES) {
-                            // first ticket past the chunk: this wave installs the next chunk and orders
-                            // the chunk after it (the others retry until the new chunk appears)
-                            uint32_t g;
-                            while ((g = __hip_atomic_exchange(&s_next, kNoChunk, __ATOMIC_RELAXED,
-                                                              __HIP_MEMORY_SCOPE_WORKGROUP)) == kNoChunk)
-                                __builtin_amdgcn_s_sleep(2);
-                            __hip_atomic_store(&s_cur, (unsigned long long)g << 32, __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_WORKGROUP);
-                            const uint32_t after = g < total_chunks ? atomicAdd(chunk_ctr, 1u) : g;
-                            __hip_atomic_store(&s_next, after, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                            continue;                                         // and draws again like everyone else
-                        }
-                        __builtin_amdgcn_s_sleep(2);                          // another wave is installing
-                    }
-                }
-                gid = __builtin_amdgcn_readfirstlane(gid);
-                off = __builtin_amdgcn_readfirstlane(off);
-                return gid >= total_chunks ? -1LL : (long long)gid * CHUNK_ROWS + (long long)off * TILE;
+                const long long t = tile_queue_draw(&s_queue, chunk_ctr, CHUNK_TILES, N / TILE);
+                return t < 0 ? t : t * TILE;
             };
             // uniform base of the tile (scalar registers) + one 32-bit lane offset
             const uint32_t lane_off = (uint32_t)rr * (uint32_t)M + (uint32_t)sub * 16u;
