@@ -15,11 +15,15 @@ SOURCES = ["otf_api.hip", "otf_select.hip", "otf_dense.hip", "otf_table.hip", "o
 # packed-fp32 instructions are switched off for every device translation unit
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-I" + INCLUDE, "-I" + CSRC, "-Wall", "-Wno-unused-function"]
+# The matrix-core scan orders its next tile with a one-lane atomic whose result it reads two steps
+# later.  The compiler's wave-aggregation of atomics would insert a read of the result (and a full
+# memory wait) right behind the atomic, so it is switched off for that file.
+EXTRA_FLAGS = {"otf_mfma.hip": ["-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]}
 
 
 def _compile(src):
     obj = os.path.join(BUILD, src.replace(".hip", ".o"))
-    cmd = ["hipcc"] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = ["hipcc"] + FLAGS + EXTRA_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     msgs = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                      if "is not a recognized feature for this target" not in l)

@@ -209,14 +209,16 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
     hipError_t e = launch_select_init(sw, Q, s);
 
     // One matrix-core launch per group of 64 (or a last 32) classifiers.
+    // (ctr_states[q0].chunk_ctr[ctr_word]: the zeroed work counter of each launch)
     auto mfma_scan = [&](int64_t rows, ScanEmit emit, float *dst, int64_t ld, const SelState *tau, SelState *st,
-                         unsigned long long *cand, const SelState *gate) {
+                         unsigned long long *cand, const SelState *gate, SelState *ctr_states, int ctr_word) {
         hipError_t err = hipSuccess;
         for (int q0 = 0; q0 < Q && err == hipSuccess;) {
             const int qn = (Q - q0 >= 64) ? 64 : 32;
             err = launch_dense_mfma(X, rows, D, ldx, Wb + (size_t)q0 * D * wsize, qn, bias ? bias + q0 : nullptr, emit,
                                     dst ? dst + (size_t)q0 * ld : nullptr, ld, tau ? tau + q0 : nullptr,
-                                    st ? st + q0 : nullptr, cand ? cand + (size_t)q0 * kCandCap : nullptr, gate, s);
+                                    st ? st + q0 : nullptr, cand ? cand + (size_t)q0 * kCandCap : nullptr, gate,
+                                    &ctr_states[q0].chunk_ctr[ctr_word], s);
             q0 += qn;
         }
         return err;
@@ -229,21 +231,21 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
         const int64_t Nv = sample_rows(N);
         const int m = sample_rank(N, Nv);
         if (e == hipSuccess) e = launch_select_init(ssw, Q, s);
-        if (e == hipSuccess) e = mfma_scan(Nv, kEmitSample, sample, L.sample_ld, nullptr, nullptr, nullptr, nullptr);
+        if (e == hipSuccess) e = mfma_scan(Nv, kEmitSample, sample, L.sample_ld, nullptr, nullptr, nullptr, nullptr, ssw.st, 0);
         if (e == hipSuccess) e = launch_hist1(sample, Nv, L.sample_ld, Q, ssw, 0, s);
         if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, Q, m, ssw, 1, s);
         ScanTimer timer(s);
-        if (e == hipSuccess) e = mfma_scan(N, kEmitFilter, nullptr, 0, ssw.st, sw.st, sw.cand, nullptr);
+        if (e == hipSuccess) e = mfma_scan(N, kEmitFilter, nullptr, 0, ssw.st, sw.st, sw.cand, nullptr, sw.st, 0);
         timer.stop();
         if (e == hipSuccess) e = launch_filter_sort(sw, Q, k, out_scores, out_idx, s);
-        if (e == hipSuccess) e = mfma_scan(N, kEmitScores, S, ldS, nullptr, nullptr, nullptr, sw.st);
+        if (e == hipSuccess) e = mfma_scan(N, kEmitScores, S, ldS, nullptr, nullptr, nullptr, sw.st, sw.st, 1);
         if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, sw, 1, s);
         if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, 1, s);
         return hip_status(e);
     }
     ScanTimer timer(s);
     if (e == hipSuccess && mfma) {
-        e = mfma_scan(N, kEmitScores, S, ldS, nullptr, nullptr, nullptr, nullptr);
+        e = mfma_scan(N, kEmitScores, S, ldS, nullptr, nullptr, nullptr, nullptr, sw.st, 1);
         timer.stop();
         if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, sw, 0, s);
     } else if (e == hipSuccess) {

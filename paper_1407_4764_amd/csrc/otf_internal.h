@@ -65,10 +65,11 @@ hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int
 //                at once unless gate->fallback is raised
 //   kEmitSample  the same for the strided sample only (compact row numbering)
 //   kEmitFilter  nothing is stored but the rows with key >= tau[q].tau_key, appended to cand[q]
+// tile_ctr: a zeroed word in global memory (the kernel hands out its tiles dynamically).
 enum ScanEmit { kEmitScores = 0, kEmitSample = 1, kEmitFilter = 2 };
 hipError_t launch_dense_mfma(const void *X, int64_t N, int D, int64_t ldx, const void *W, int Q, const float *bias,
                              ScanEmit emit, float *scores, int64_t ld_scores, const SelState *tau, SelState *st,
-                             unsigned long long *cand, const SelState *gate, hipStream_t s);
+                             unsigned long long *cand, const SelState *gate, uint32_t *tile_ctr, hipStream_t s);
 
 // Byte-indexed table scans (product-quantised codes, binary codes).
 hipError_t launch_pq_build_lut(const float *codebooks, int M, int K, int dsub, const float *w, float *lut, hipStream_t s);

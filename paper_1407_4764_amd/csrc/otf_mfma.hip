@@ -33,11 +33,13 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__res
                                                          const float *__restrict__ bias, float *__restrict__ scores,
                                                          long long ld_scores, int vec_store,
                                                          const SelState *__restrict__ tau_state, SelState *st,
-                                                         unsigned long long *__restrict__ cand, const SelState *gate) {
+                                                         unsigned long long *__restrict__ cand, const SelState *gate,
+                                                         uint32_t *tile_ctr) {
     constexpr int QN = QT * 32;
     if (gate && gate->fallback == 0u) return;     // uniform: only the fallback of a filtered scan
     __shared__ __attribute__((aligned(16))) uint8_t xs[kBM * kRowStride];
     __shared__ __attribute__((aligned(16))) uint8_t ws[QN * kRowStride];
+    __shared__ uint32_t s_tile[8];                // ring: number of the block's j-th tile at slot j % 8
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, h = lane >> 5;
     const long long ntiles = (N + kBM - 1) / kBM;
@@ -54,17 +56,30 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__res
 
     // The (tile, K step) pairs of this block form one flat sequence.  Global loads run two steps
     // ahead of the matrix instructions through two register stages, across tile boundaries too,
-    // so there is no cold start per tile; loads past the block's last step re-read its last tile
-    // (unconditional loads keep the in-order wait counters exact).
-    const long long my_tiles = ntiles > (long long)blockIdx.x ? (ntiles - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
-    if (my_tiles == 0) return;
-    const long long total = my_tiles * ksteps;
+    // so there is no cold start per tile (unconditional loads keep the in-order wait counters
+    // exact; loads past the block's last tile re-read the store's last tile).
+    //
+    // Tiles are handed out dynamically, one atomic on a global counter per tile (a static split
+    // leaves a tail: the chip's dies stream at different rates).  The number of the block's j-th
+    // tile is ordered when the loads of its tile j - 3 begin, by thread 0, and the returned value is
+    // written to the ring two steps later, right after the wait for the loads that were issued
+    // behind the atomic, so that nobody ever waits for the atomic itself.
+    if (tid == 0) {
+        const uint32_t c = atomicAdd(tile_ctr, 3u);
+        s_tile[0] = c;
+        s_tile[1] = c + 1u;
+        s_tile[2] = c + 2u;
+    }
+    __syncthreads();
+    if ((long long)s_tile[0] >= ntiles) return;   // uniform
 
     // load side
-    long long ltile = blockIdx.x;
-    // workgroups start at different K steps, so that those running in step do not ask the same
+    uint32_t lj = 0u;                             // ordinal of the tile being loaded
+    long long ltile = s_tile[0];
+    // tiles start at different K steps (tile number mod steps: the order of the sum is a property
+    // of the tile, whoever computes it), so that workgroups running in step do not ask the same
     // memory channels for the same slice of W and of their rows at the same time
-    int lks = (int)(blockIdx.x % (unsigned)ksteps), lcount = 0;
+    int lks = (int)(ltile % ksteps), lcount = 0;
     // addresses = uniform base of the tile (scalar registers) + 32-bit per-lane offsets
     const uint8_t *xbase;
     uint32_t xoff[8], woff[QT * 2];
@@ -93,22 +108,35 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__res
         constexpr int every = 8 / (QT * 2);
         if (p % every == every - 1) wr[p / every] = *reinterpret_cast<const u32x4 *>(wb + (size_t)woff[p / every]);
     };
+    // before the first load of a step: when the step starts the block's tile lj, order tile lj + 3
+    auto begin_step = [&](uint32_t &pend, bool &has_pend, uint32_t &pend_slot) {
+        if (lcount == 0) {                           // uniform
+            if (tid == 0) pend = atomicAdd(tile_ctr, 1u);
+            has_pend = true;
+            pend_slot = (lj + 3u) & 7u;
+        }
+    };
     auto advance_load = [&]() {
         if (++lks == ksteps) lks = 0;
         if (++lcount == ksteps) {                    // uniform
             lcount = 0;
-            if (ltile + gridDim.x < ntiles) ltile += gridDim.x;
+            ++lj;
+            ltile = s_tile[lj & 7u];
+            if (ltile > ntiles - 1) ltile = ntiles - 1;   // nothing left: harmless re-read
+            lks = (int)(ltile % ksteps);
             point_at_tile(ltile);
         }
     };
-    auto issue_load = [&](u32x4 *xr, u32x4 *wr) {
+    auto issue_load = [&](u32x4 *xr, u32x4 *wr, uint32_t &pend, bool &has_pend, uint32_t &pend_slot) {
+        begin_step(pend, has_pend, pend_slot);
 #pragma unroll
         for (int p = 0; p < 8; ++p) issue_piece(xr, wr, p);
         advance_load();
     };
 
     // compute side
-    long long ctile = blockIdx.x;
+    uint32_t cj = 0u;
+    long long ctile = s_tile[0];
     int cks = 0;
     float16v acc[QT];
 #pragma unroll
@@ -153,7 +181,8 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__res
         }
     };
 
-    auto body = [&](u32x4 *xr, u32x4 *wr) {
+    // one step (after the block's last tile a step works on re-read rows and stores nothing)
+    auto body = [&](u32x4 *xr, u32x4 *wr, uint32_t &pend, bool &has_pend, uint32_t &pend_slot) {
         __syncthreads();                              // everyone has finished reading the previous tiles
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -165,7 +194,12 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__res
             const int id = tid + 256 * u;
             *reinterpret_cast<u32x4 *>(ws + (id >> 4) * kRowStride + (id & 15) * 16) = wr[u];
         }
+        if (has_pend) {                               // uniform; the atomic is older than the loads just waited for
+            if (tid == 0) s_tile[pend_slot] = pend;
+            has_pend = false;
+        }
         __syncthreads();
+        begin_step(pend, has_pend, pend_slot);
         const uint8_t *arow = xs + (wave * 32 + n) * kRowStride + h * 16;
         const uint8_t *brow = ws + n * kRowStride + h * 16;
         {
@@ -195,32 +229,37 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__res
             advance_load();
         }
         if (++cks == ksteps) {                        // uniform: the tile is complete
-            epilogue(ctile * kBM);
+            if (ctile < ntiles) {
+                epilogue(ctile * kBM);
+                ++cj;
+                ctile = s_tile[cj & 7u];
+            }
             cks = 0;
-            ctile += gridDim.x;
         }
     };
 
     u32x4 xr0[8], wr0[QT * 2], xr1[8], wr1[QT * 2];
-    issue_load(xr0, wr0);
-    issue_load(xr1, wr1);
-    // the odd last step stays outside the loop: a conditional second half would make the loop
-    // header see either stage as the younger one and wait for both
-    for (long long g = 0; g + 1 < total; g += 2) {
-        body(xr0, wr0);
-        body(xr1, wr1);
-    }
-    if (total & 1) body(xr0, wr0);
+    uint32_t pend0 = 0u, pend1 = 0u, slot0 = 0u, slot1 = 0u;
+    bool has0 = false, has1 = false;
+    issue_load(xr0, wr0, pend0, has0, slot0);
+    issue_load(xr1, wr1, pend1, has1, slot1);
+    // One exit, after the pair: a way out (or back to the loop header) from the middle would make
+    // the header see either stage as the younger one and wait for both.  When the last tile ends
+    // on the first step of a pair, the second one runs idle.
+    do {
+        body(xr0, wr0, pend0, has0, slot0);
+        body(xr1, wr1, pend1, has1, slot1);
+    } while (ctile < ntiles);
 }
 
 template <int QT>
 static hipError_t launch_mfma_qt(const uint8_t *X, int64_t N, int D, int64_t ldx, const uint8_t *W, const float *bias,
                                  ScanEmit emit, float *scores, int64_t ld_scores, const SelState *tau, SelState *st,
-                                 unsigned long long *cand, const SelState *gate, hipStream_t s) {
+                                 unsigned long long *cand, const SelState *gate, uint32_t *tile_ctr, hipStream_t s) {
     const int64_t ntiles = (N + kBM - 1) / kBM;
     const int grid = (int)std::min<int64_t>(ntiles, (int64_t)device_cu_count() * tune_int("OTF_MFMA_BLOCKS_PER_CU", 2));
     const int vec_store = scores && (ld_scores % 4 == 0) && ((reinterpret_cast<uintptr_t>(scores) & 15) == 0);
-#define OTF_MFMA_ARGS X, (long long)N, D, (long long)ldx * 2, W, bias, scores, (long long)ld_scores, vec_store, tau, st, cand, gate
+#define OTF_MFMA_ARGS X, (long long)N, D, (long long)ldx * 2, W, bias, scores, (long long)ld_scores, vec_store, tau, st, cand, gate, tile_ctr
     if (emit == kEmitScores) dense_mfma_kernel<QT, kEmitScores><<<grid, 256, 0, s>>>(OTF_MFMA_ARGS);
     else if (emit == kEmitSample) dense_mfma_kernel<QT, kEmitSample><<<grid, 256, 0, s>>>(OTF_MFMA_ARGS);
     else dense_mfma_kernel<QT, kEmitFilter><<<grid, 256, 0, s>>>(OTF_MFMA_ARGS);
@@ -229,14 +268,14 @@ static hipError_t launch_mfma_qt(const uint8_t *X, int64_t N, int D, int64_t ldx
 }
 
 // Q must be 32 or 64, D a multiple of 128, N >= 1 (for kEmitSample: N = sample rows, a multiple of 1024).
-// tau, st and cand point at the first of the Q classifiers of this call.
+// tau, st and cand point at the first of the Q classifiers of this call; tile_ctr at a zeroed word.
 hipError_t launch_dense_mfma(const void *X, int64_t N, int D, int64_t ldx, const void *W, int Q, const float *bias,
                              ScanEmit emit, float *scores, int64_t ld_scores, const SelState *tau, SelState *st,
-                             unsigned long long *cand, const SelState *gate, hipStream_t s) {
+                             unsigned long long *cand, const SelState *gate, uint32_t *tile_ctr, hipStream_t s) {
     const uint8_t *Xb = reinterpret_cast<const uint8_t *>(X);
     const uint8_t *Wb = reinterpret_cast<const uint8_t *>(W);
-    if (Q == 32) return launch_mfma_qt<1>(Xb, N, D, ldx, Wb, bias, emit, scores, ld_scores, tau, st, cand, gate, s);
-    if (Q == 64) return launch_mfma_qt<2>(Xb, N, D, ldx, Wb, bias, emit, scores, ld_scores, tau, st, cand, gate, s);
+    if (Q == 32) return launch_mfma_qt<1>(Xb, N, D, ldx, Wb, bias, emit, scores, ld_scores, tau, st, cand, gate, tile_ctr, s);
+    if (Q == 64) return launch_mfma_qt<2>(Xb, N, D, ldx, Wb, bias, emit, scores, ld_scores, tau, st, cand, gate, tile_ctr, s);
     return hipErrorInvalidValue;
 }
 
