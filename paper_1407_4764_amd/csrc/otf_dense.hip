@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const uint8_t *__restri
     };
 
     if (FULL) {
-        constexpr uint32_t CHUNK_ROWS = 256u / (uint32_t)V;   // x V KiB per row = 256 KiB
+        const uint32_t CHUNK_ROWS = tile_queue_chunk_tiles(N, 256u / (uint32_t)V);   // x V KiB per row = 256 KiB
         const uint8_t *base = X + (size_t)lane * 16;
         auto fetch = [&](Chunk16 *c, long long r) {
             const uint8_t *p = base + (size_t)r * (size_t)row_bytes;

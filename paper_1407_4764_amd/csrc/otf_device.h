@@ -180,6 +180,15 @@ struct TileQueue {
 };
 constexpr uint32_t kNoChunk = 0xFFFFFFFFu;
 
+// Tiles per chunk: `full` (about 256 KiB of rows) for long scans.  A short scan is cut into two
+// chunks per workgroup, which are exactly the two that tile_queue_init hands out, so that every
+// workgroup finds work and no further chunk is ever ordered.  Same value in every workgroup.
+__device__ __forceinline__ uint32_t tile_queue_chunk_tiles(long long total_tiles, uint32_t full) {
+    const long long parts = 2LL * gridDim.x;
+    const long long fair = (total_tiles + parts - 1) / parts;
+    return fair >= (long long)full ? full : (fair < 1 ? 1u : (uint32_t)fair);
+}
+
 // One thread per workgroup, before a barrier that precedes the first tile_queue_draw.
 __device__ __forceinline__ void tile_queue_init(TileQueue *q, uint32_t *chunk_ctr) {
     const uint32_t c = atomicAdd(chunk_ctr, 2u);
@@ -214,7 +223,8 @@ __device__ __forceinline__ long long tile_queue_draw(TileQueue *q, uint32_t *chu
                     __builtin_amdgcn_s_sleep(2);
                 __hip_atomic_store(&q->cur, (unsigned long long)g << 32, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_WORKGROUP);
-                const uint32_t after = g < total_chunks ? atomicAdd(chunk_ctr, 1u) : g;
+                // (with at most two chunks per workgroup every chunk was handed out at the start)
+                const uint32_t after = (g < total_chunks && total_chunks > 2u * gridDim.x) ? atomicAdd(chunk_ctr, 1u) : total_chunks;
                 __hip_atomic_store(&q->next, after, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 continue;                                                     // and draws again like everyone else
             }

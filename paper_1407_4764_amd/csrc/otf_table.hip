@@ -206,6 +206,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     // count in different words; both were zeroed with the state
     uint32_t *chunk_ctr = &st->chunk_ctr[EMIT == kEmitScores ? 1 : 0];
     if (!SPLIT && threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);   // visible after the barriers below
+    const uint32_t chunk_tiles = tile_queue_chunk_tiles(N / TILE, CHUNK_TILES);
 
     if (EMIT != kEmitFilter)
         for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
             // first row of the next tile of this wave, or -1 when the scan has no full tile left
             // (the rows after the last full tile are handled at the end)
             auto draw = [&]() -> long long {
-                const long long t = tile_queue_draw(&s_queue, chunk_ctr, CHUNK_TILES, N / TILE);
+                const long long t = tile_queue_draw(&s_queue, chunk_ctr, chunk_tiles, N / TILE);
                 return t < 0 ? t : t * TILE;
             };
             // uniform base of the tile (scalar registers) + one 32-bit lane offset
