@@ -36,7 +36,7 @@ namespace otf {
 constexpr int kSegBytes = 128;                       // row bytes handled per phase (byte groups)
 constexpr int kImageFloats = 256 * kSegBytes;        // one table image: 256 values x 128 columns
 constexpr int kImageBytes = kImageFloats * 4;        // 128 KiB
-constexpr int kSideFloats = 16 * 64;                 // 4-bit groups of a 2048-bit row: 16 values x 64 words
+constexpr int kSideFloats = 16 * 128;                // 4-bit groups of a 2048-bit row: 16 values x 64 words, twice
 constexpr int kImage7Bytes = kImageBytes + kSideFloats * 4;   // 7-bit groups: 128 values x 256 columns, + side
 constexpr int kScanMaxThreads = 1024;
 constexpr int kScanThreads = 1024;    // 16 waves per CU overlap the gathers with the row stream best
@@ -117,9 +117,11 @@ __global__ __launch_bounds__(256) void binary_prepare_kernel(const float *__rest
 
 // Table image for 2048-bit rows: word q (0..63) of a row = lane-chunk q/4, word tq = q%4 of the chunk.
 //   main[v][64*tq + 4*chunk + j]  (v < 128)  group j of the word: dimensions 32q + 7j .. 32q + 7j + 6
-//   side[v][q]                    (v < 16)   the top four bits:   dimensions 32q + 28 .. 32q + 31
-// (The side reads are 4-way bank conflicts.  A duplicated, conflict-free side table was measured:
-// the conflict counter drops to zero and the scan gets 5 % slower, so the plain layout stays.)
+//   side[v][32*tq + 8*o + c]      (v < 16)   the top four bits:   dimensions 32q + 28 .. 32q + 31 of word
+//        q = 4*chunk + tq, chunk = c + 8*(o & 1).  o is the lane octet (0..3) that reads the entry:
+//        octets 0 and 2 hold the same chunks, as do 1 and 3, so every word is stored twice and the
+//        32 lanes that execute together (4 octets x 8 chunks) read 32 different banks.  (A plain
+//        side[v][q] makes every side read a 4-way bank conflict: 37 % of the kernel's LDS cycles.)
 __global__ __launch_bounds__(256) void binary7_prepare_kernel(const float *__restrict__ w, float *__restrict__ image,
                                                               SelState *st, uint32_t *hist1, uint32_t *hist2,
                                                               uint32_t *hist3, SelState *sst, uint32_t *shist1,
@@ -138,14 +140,15 @@ __global__ __launch_bounds__(256) void binary7_prepare_kernel(const float *__res
         image[v * 256 + 64 * tq + 4 * chunk + j] = acc;
     }
     for (int t = tid; t < kSideFloats; t += step) {
-        const int v = t & 15, q = t >> 4;
+        const int c = t & 7, o = (t >> 3) & 3, tq = (t >> 5) & 3, v = t >> 7;
+        const int q = 4 * (c + 8 * (o & 1)) + tq;
         float acc = 0.f;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             const float wd = w[32 * q + 28 + b];
             acc += ((v >> b) & 1) ? wd : -wd;
         }
-        image[kImageFloats + v * 64 + q] = acc;
+        image[kImageFloats + t] = acc;
     }
     zero_states(tid, step, st, hist1, hist2, hist3, sst, shist1, shist2);
 }
@@ -231,7 +234,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
         shift[t] = (uint32_t)(GB * j);
         colbyte[t] = 4u * (uint32_t)(4 * chunk + j);
     }
-    const uint32_t sidecol = (uint32_t)(kImageBytes + 16 * chunk);   // GB == 7 only
+    const uint32_t sidecol = (uint32_t)(kImageBytes + 4 * (8 * octet + (chunk & 7)));   // GB == 7 only
 
     const size_t u_bytes = (size_t)RPW * (size_t)M;        // distance between the U loads of a lane
     const int out_u = sub % ACTIVE;                        // which of a round's rows this lane emits
@@ -257,7 +260,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
         if (GB == 7) {
 #pragma unroll
             for (int tq = 0; tq < 4; ++tq)
-                v[4 * tq] += *reinterpret_cast<const float *>(lds_raw + ((d[tq] >> 28) << 8) + sidecol + 4 * tq);
+                v[4 * tq] += *reinterpret_cast<const float *>(lds_raw + ((d[tq] >> 28) << 9) + sidecol + 128 * tq);
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] += v[i + 8];
