@@ -151,6 +151,36 @@ int otf_svm_sgd_step(float *w, float *b, int32_t D,
                      void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Binarisation encoder (paper Sec. 3, "Binarization", Eq. (1)): a zero-centred descriptor phi in
+ * R^m is coded as beta = sgn(U phi) in {0,1}^n, n > m, with sgn(a) = 1 iff a > 0 (a zero
+ * projection codes as 0) and U the first m columns of the orthogonal factor of a QR
+ * decomposition of a random n x n matrix.  The codes are the rows otf_rank_binary scans:
+ * dimension d is bit (d mod 32), least significant first, of word (d div 32).
+ *
+ * otf_tight_frame:  U from the random matrix (set-up, once per frame).
+ *   G   n x n floats, row-major, drawn by the caller.  Of the possible QR factorisations the one
+ *       with a positive diagonal of R is taken, so U is a function of G (it depends on the
+ *       first m columns of G only and is their Gram-Schmidt orthonormalisation, computed in fp64).
+ *       Linearly dependent leading columns give zero columns in U.
+ *   U   n x m floats, row-major (row d = the frame vector of code bit d).
+ *   ws  at least otf_tight_frame_workspace_bytes(n, m) bytes, 16-byte aligned.
+ *   1 <= m <= n; n <= 4096 and m <= 256, otherwise OTF_ERR_UNSUPPORTED.
+ *
+ * otf_binarize:  bits[i][d] = ( sum_j U[d][j] * phi[i][j] > 0 ), fp32 products and sums on the
+ *   matrix cores: a bit whose exact projection is within rounding of zero may differ from an
+ *   evaluation in another precision.
+ *   phi   N x m floats, leading dimension ld_phi (elements, >= m, a multiple of 4).
+ *   U     n x m floats as above, contiguous.      bits  N x (n/32) uint32, contiguous rows.
+ *   m a multiple of 4, at most 128; n a multiple of 32; otherwise OTF_ERR_UNSUPPORTED.
+ */
+size_t otf_tight_frame_workspace_bytes(int32_t n, int32_t m);
+
+int otf_tight_frame(const float *G, int32_t n, int32_t m, float *U, void *ws, size_t ws_bytes, void *stream);
+
+int otf_binarize(const float *phi, int64_t N, int32_t m, int64_t ld_phi, const float *U, int32_t n,
+                 uint32_t *bits, void *stream);
+
+/*
  * Diagnostics (host, not part of the paper's method; for benchmarks that must time the
  * scoring kernel by itself).  Between otf_profile_begin and otf_profile_end every otf_rank_*
  * call brackets its scoring kernel(s) with a pair of HIP events on the call's stream, at most

@@ -22,8 +22,8 @@ OTF_F16 = 1
 OTF_MAX_K = 8192
 
 EXPORTS = ["otf_status_string", "otf_workspace_bytes", "otf_rank_dense", "otf_pq_build_lut", "otf_rank_pq",
-           "otf_rank_binary", "otf_topk", "otf_sgd_workspace_bytes", "otf_svm_sgd_step", "otf_profile_begin",
-           "otf_profile_end"]
+           "otf_rank_binary", "otf_topk", "otf_sgd_workspace_bytes", "otf_svm_sgd_step", "otf_tight_frame_workspace_bytes",
+           "otf_tight_frame", "otf_binarize", "otf_profile_begin", "otf_profile_end"]
 
 _lib = None
 
@@ -62,6 +62,12 @@ def lib():
         L.otf_topk.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, sz, vp]
         L.otf_svm_sgd_step.restype = ctypes.c_int
         L.otf_svm_sgd_step.argtypes = [vp, vp, i32, vp, i64, vp, i32, vp, i64, vp, i32, f32, i64, i32, vp, sz, vp]
+        L.otf_tight_frame_workspace_bytes.restype = sz
+        L.otf_tight_frame_workspace_bytes.argtypes = [i32, i32]
+        L.otf_tight_frame.restype = ctypes.c_int
+        L.otf_tight_frame.argtypes = [vp, i32, i32, vp, vp, sz, vp]
+        L.otf_binarize.restype = ctypes.c_int
+        L.otf_binarize.argtypes = [vp, i64, i32, i64, vp, i32, vp, vp]
         L.otf_profile_begin.restype = ctypes.c_int
         L.otf_profile_begin.argtypes = [i32]
         L.otf_profile_end.restype = ctypes.c_int
@@ -186,6 +192,35 @@ def svm_sgd_step(w, b, Xpos, idx_pos, Xneg, idx_neg, lam, t, update_bias, ws):
                                 ws.numel(), _stream(w.device))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_svm_sgd_step")
+
+
+def tight_frame(G, m, U=None):
+    """U (n, m) fp32: the frame of the binarisation encoder from the random matrix G (n, n) fp32."""
+    assert G.is_contiguous() and G.dtype == torch.float32 and G.shape[0] == G.shape[1]
+    n = G.shape[0]
+    if U is None:
+        U = torch.empty((n, m), dtype=torch.float32, device=G.device)
+    nbytes = int(lib().otf_tight_frame_workspace_bytes(n, int(m)))
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=G.device)
+    rc = lib().otf_tight_frame(_ptr(G), n, int(m), _ptr(U), _ptr(ws), ws.numel(), _stream(G.device))
+    if rc != OTF_OK:
+        raise OtfError(rc, "otf_tight_frame")
+    torch.cuda.current_stream(G.device).synchronize()      # ws is released on return
+    return U
+
+
+def binarize(phi, U, bits=None):
+    """bits (N, n/32) int32 (the uint32 words of the codes): sign of U phi, packed LSB first."""
+    assert phi.dtype == torch.float32 and U.dtype == torch.float32 and U.is_contiguous() and phi.stride(1) == 1
+    N, m = phi.shape
+    n = U.shape[0]
+    assert U.shape[1] == m
+    if bits is None:
+        bits = torch.empty((N, n // 32), dtype=torch.int32, device=phi.device)
+    rc = lib().otf_binarize(_ptr(phi), N, m, phi.stride(0), _ptr(U), n, _ptr(bits), _stream(phi.device))
+    if rc != OTF_OK:
+        raise OtfError(rc, "otf_binarize")
+    return bits
 
 
 def debug_fallback_taken(ws):

@@ -361,6 +361,29 @@ int otf_svm_sgd_step(float *w, float *b, int32_t D, const float *Xpos, int64_t l
                                       reinterpret_cast<hipStream_t>(stream)));
 }
 
+size_t otf_tight_frame_workspace_bytes(int32_t n, int32_t m) {
+    if (n < 1 || m < 1 || m > n) return 0;
+    return (size_t)n * (size_t)m * sizeof(double);
+}
+
+int otf_tight_frame(const float *G, int32_t n, int32_t m, float *U, void *ws, size_t ws_bytes, void *stream) {
+    if (!G || !U || n < 1 || m < 1 || m > n) return OTF_ERR_INVALID_ARG;
+    if (n > 4096 || m > 256) return OTF_ERR_UNSUPPORTED;
+    if (!ws || ws_bytes < otf_tight_frame_workspace_bytes(n, m) || (reinterpret_cast<uintptr_t>(ws) & 15u))
+        return OTF_ERR_WORKSPACE;
+    return hip_status(launch_tight_frame(G, n, m, reinterpret_cast<double *>(ws), U,
+                                         reinterpret_cast<hipStream_t>(stream)));
+}
+
+int otf_binarize(const float *phi, int64_t N, int32_t m, int64_t ld_phi, const float *U, int32_t n, uint32_t *bits,
+                 void *stream) {
+    if (!phi || !U || !bits || N < 1 || m < 1 || n < 1 || ld_phi < m) return OTF_ERR_INVALID_ARG;
+    if (!aligned16(phi) || !aligned16(U) || ld_phi % 4 != 0) return OTF_ERR_INVALID_ARG;
+    if (N >= ((int64_t)1 << 31)) return OTF_ERR_UNSUPPORTED;
+    if (m % 4 != 0 || m > 128 || n % 32 != 0 || n > 65536) return OTF_ERR_UNSUPPORTED;
+    return hip_status(launch_binarize(phi, N, m, ld_phi, U, n, bits, reinterpret_cast<hipStream_t>(stream)));
+}
+
 int otf_profile_begin(int32_t max_records) {
     if (g_prof.on || max_records < 1 || max_records > 65536) return OTF_ERR_INVALID_ARG;
     g_prof.start.assign(max_records, nullptr);

@@ -1,0 +1,215 @@
+// Binarisation encoder (paper Sec. 3, "Binarization", Eq. (1)): a zero-centred descriptor phi in
+// R^m becomes the code beta = sgn(U phi) in {0,1}^n, n > m, sgn(a) = 1 iff a > 0, where the frame U
+// is the first m columns of the orthogonal factor of a QR decomposition of a random n x n matrix.
+//
+// tight_frame_kernel   U from the random matrix (set-up, once per frame)
+// binarize_kernel      the codes of N descriptors: an N x n x m matrix product on the matrix
+//                      cores (fp32 inputs, fp32 accumulation) whose epilogue keeps only the signs,
+//                      packed 32 to a word, dimension d at bit d mod 32 of word d div 32
+#include <algorithm>
+
+#include "otf_internal.h"
+
+namespace otf {
+
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// -------------------------------------------------------------------------------------------
+// U = first m columns of Q, G = QR with a positive diagonal of R.  Those columns depend on the
+// first m columns of G only: they are their Gram-Schmidt orthonormalisation.  One workgroup,
+// fp64, every column orthogonalised twice against its predecessors ("twice is enough": the
+// result is orthonormal to rounding whatever the conditioning of the random columns).
+//   G  n x n fp32 row-major.   Qd  n x m fp64 scratch, row-major.   U  n x m fp32 row-major.
+constexpr int kFrameThreads = 1024;
+constexpr int kFrameMaxN = 4096;     // v (fp64) lives in shared memory
+constexpr int kFrameMaxM = 256;
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__global__ __launch_bounds__(kFrameThreads) void tight_frame_kernel(const float *__restrict__ G, int n, int m,
+                                                                    double *__restrict__ Qd, float *__restrict__ U) {
+    __shared__ double v[kFrameMaxN];
+    __shared__ double coef[kFrameMaxM];
+    __shared__ double part[kFrameThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = kFrameThreads / 64;
+    for (int j = 0; j < m; ++j) {
+        for (int i = tid; i < n; i += kFrameThreads) v[i] = (double)G[(size_t)i * n + j];
+        __syncthreads();
+        for (int pass = 0; pass < 2; ++pass) {
+            // coef[c] = <q_c, v> for c < j: one wave per column c
+            for (int c = wave; c < j; c += nwaves) {
+                double s = 0.0;
+                for (int i = lane; i < n; i += 64) s += Qd[(size_t)i * m + c] * v[i];
+                s = wave_sum_f64(s);
+                if (lane == 0) coef[c] = s;
+            }
+            __syncthreads();
+            // v -= sum_c coef[c] q_c: one thread per row
+            for (int i = tid; i < n; i += kFrameThreads) {
+                const double *q = Qd + (size_t)i * m;
+                double s = 0.0;
+                for (int c = 0; c < j; ++c) s += coef[c] * q[c];
+                v[i] -= s;
+            }
+            __syncthreads();
+        }
+        double s = 0.0;
+        for (int i = tid; i < n; i += kFrameThreads) s += v[i] * v[i];
+        s = wave_sum_f64(s);
+        if (lane == 0) part[wave] = s;
+        __syncthreads();
+        double norm2 = 0.0;
+        for (int w = 0; w < nwaves; ++w) norm2 += part[w];
+        const double inv = norm2 > 0.0 ? 1.0 / sqrt(norm2) : 0.0;   // dependent columns give a zero column
+        for (int i = tid; i < n; i += kFrameThreads) {
+            const double q = v[i] * inv;
+            Qd[(size_t)i * m + j] = q;
+            U[(size_t)i * m + j] = (float)q;
+        }
+        __threadfence_block();
+        __syncthreads();
+    }
+}
+
+// -------------------------------------------------------------------------------------------
+// Codes.  2 m n flop per descriptor against 4 m + n/8 bytes: at m = 128, n = 2048 that is 680
+// flop per byte, so the kernel is bound by the fp32 rate of the matrix cores and is organised to
+// keep them issuing: one workgroup of four waves per compute unit, one wave per SIMD.
+//
+//   * A wave owns 64 descriptors for the whole of U.  Their values stay in registers for that
+//     time, already in the operand layout of v_mfma_f32_32x32x2_f32 (lane (r, h) = descriptor r
+//     of a 32-row half, K slots 64 h .. 64 h + 63: operands A and B only have to agree on which K
+//     goes into which slot, so each lane takes a contiguous half row instead of every other
+//     element).
+//   * U is streamed from L2 in blocks of 32 frame rows (= 32 code bits) through shared memory,
+//     double-buffered, one barrier per block; rows padded by 16 bytes so that the 16-byte
+//     operand reads of 8 consecutive lanes cover all 32 banks.
+//   * Per block and 32-row half the signs come out as 16 wave votes (v_cmp + the vote mask): lanes
+//     0..31 of vote v are the 32 bits of one output word, lanes 32..63 those of another.  The words
+//     are parked in lane (block mod 64) of one register per descriptor, and once
+//     64 blocks are done every descriptor's 256 bytes leave in one coalesced store.
+constexpr int kEncRowsPerWave = 64;
+constexpr int kEncRows = 4 * kEncRowsPerWave;   // descriptors per workgroup pass
+constexpr int kEncK = 128;                      // K slots (m is padded with zeros up to this)
+constexpr int kEncStride = kEncK * 4 + 16;      // bytes per frame row in shared memory
+
+__global__ __launch_bounds__(256) void binarize_kernel(const float *__restrict__ phi, long long N, int m, long long ld,
+                                                       const float *__restrict__ U, int n, uint32_t *__restrict__ bits) {
+    __shared__ __attribute__((aligned(16))) uint8_t us[2][32 * kEncStride];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int nblocks = n / 32;                  // blocks of 32 code bits
+    const int words = n / 32;                    // words per code
+    const long long ntiles = (N + kEncRows - 1) / kEncRows;
+
+    // global -> registers -> shared memory for one block of U: 32 rows x 512 bytes, 4 x 16 bytes per thread
+    f32x4 ustage[4];
+    auto load_u = [&](int cb) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int id = tid + 256 * u, row = id >> 5, c16 = id & 31;
+            ustage[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            if (4 * c16 < m) ustage[u] = *reinterpret_cast<const f32x4 *>(U + (size_t)(32 * cb + row) * m + 4 * c16);
+        }
+    };
+    auto store_u = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int id = tid + 256 * u, row = id >> 5, c16 = id & 31;
+            *reinterpret_cast<f32x4 *>(us[buf] + row * kEncStride + c16 * 16) = ustage[u];
+        }
+    };
+
+    for (long long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const long long row0 = tile * kEncRows + (long long)wave * kEncRowsPerWave;
+        // operand A: descriptor values of this lane's two rows, K slots 64 h + s
+        float a[2][64];
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            long long row = row0 + 32 * f + r;
+            if (row > N - 1) row = N - 1;                    // computed, never stored
+            const float *p = phi + (size_t)row * ld + 64 * h;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                f32x4 t = (f32x4){0.f, 0.f, 0.f, 0.f};
+                if (64 * h + 4 * q < m) t = *reinterpret_cast<const f32x4 *>(p + 4 * q);
+                a[f][4 * q + 0] = t.x; a[f][4 * q + 1] = t.y; a[f][4 * q + 2] = t.z; a[f][4 * q + 3] = t.w;
+            }
+        }
+        uint32_t outw[kEncRowsPerWave];                      // outw[row]: lane c holds word (64 * pass + c) of the row
+#pragma unroll
+        for (int i = 0; i < kEncRowsPerWave; ++i) outw[i] = 0u;
+
+        __syncthreads();                                     // the previous tile is done with shared memory
+        load_u(0);
+        store_u(0);
+        __syncthreads();
+        for (int cb = 0; cb < nblocks; ++cb) {
+            const int buf = cb & 1;
+            if (cb + 1 < nblocks) load_u(cb + 1);            // uniform; in flight during the matrix instructions
+            float16v acc[2];
+#pragma unroll
+            for (int f = 0; f < 2; ++f)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[f][v] = 0.f;
+            const uint8_t *brow = us[buf] + r * kEncStride + h * 256;
+            f32x4 b = *reinterpret_cast<const f32x4 *>(brow);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                f32x4 bn = b;
+                if (q + 1 < 16) bn = *reinterpret_cast<const f32x4 *>(brow + (q + 1) * 16);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int f = 0; f < 2; ++f)
+                        acc[f] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[f][4 * q + j], b[j], acc[f], 0, 0, 0);
+                b = bn;
+            }
+            // signs: accumulator element v of lane (r, h) is descriptor 8 (v / 4) + 4 h + v % 4 of the
+            // half, code bit 32 cb + r
+            const bool mine = lane == (cb & 63);             // the lane that keeps this block's words
+#pragma unroll
+            for (int f = 0; f < 2; ++f)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const unsigned long long vote = __ballot(acc[f][v] > 0.f);
+                    const int lo = 32 * f + 8 * (v / 4) + (v % 4);
+                    outw[lo] = mine ? (uint32_t)vote : outw[lo];
+                    outw[lo + 4] = mine ? (uint32_t)(vote >> 32) : outw[lo + 4];
+                }
+            if ((cb & 63) == 63 || cb == nblocks - 1) {      // uniform: 64 words per descriptor are complete
+                const int w0 = cb & ~63;
+#pragma unroll
+                for (int i = 0; i < kEncRowsPerWave; ++i) {
+                    const long long row = row0 + i;
+                    if (row < N && w0 + lane < words) bits[(size_t)row * words + w0 + lane] = outw[i];
+                    outw[i] = 0u;
+                }
+            }
+            if (cb + 1 < nblocks) store_u(buf ^ 1);          // last read of that buffer: block cb - 1, a barrier ago
+            __syncthreads();
+        }
+    }
+}
+
+hipError_t launch_tight_frame(const float *G, int n, int m, double *scratch, float *U, hipStream_t s) {
+    if (n > kFrameMaxN || m > kFrameMaxM) return hipErrorInvalidValue;
+    tight_frame_kernel<<<1, kFrameThreads, 0, s>>>(G, n, m, scratch, U);
+    return hipGetLastError();
+}
+
+hipError_t launch_binarize(const float *phi, int64_t N, int m, int64_t ld, const float *U, int n, uint32_t *bits,
+                           hipStream_t s) {
+    if (m > kEncK || m % 4 || n % 32) return hipErrorInvalidValue;
+    const int64_t ntiles = (N + kEncRows - 1) / kEncRows;
+    const int grid = (int)std::min<int64_t>(ntiles, device_cu_count());
+    binarize_kernel<<<grid, 256, 0, s>>>(phi, (long long)N, m, (long long)ld, U, n, bits);
+    return hipGetLastError();
+}
+
+}  // namespace otf

@@ -92,6 +92,11 @@ hipError_t launch_sgd_step(float *w, float *b, int D, const float *Xpos, int64_t
                            int n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int n_neg,
                            float lambda, int64_t t, int update_bias, float *coef, hipStream_t s);
 
+// Binarisation encoder: the frame from the random matrix (scratch: n*m doubles), and the codes.
+hipError_t launch_tight_frame(const float *G, int n, int m, double *scratch, float *U, hipStream_t s);
+hipError_t launch_binarize(const float *phi, int64_t N, int m, int64_t ld, const float *U, int n, uint32_t *bits,
+                           hipStream_t s);
+
 int device_cu_count();
 
 // Launch-shape knobs for tuning runs: integer environment variable `name`, else `fallback`.

@@ -124,5 +124,21 @@ def sgd_batches(n_pos_pool, n_neg_pool, batch, steps, seed):
     return pos, neg
 
 
+def centred_descriptors(N, m, seed, device="cpu", chunk_rows=65536):
+    """Descriptors for the binarisation encoder (Sec. 3 "Binarization": "zero-centred descriptors"):
+    the dense features above with one constant per dimension subtracted, the mean of a fixed
+    seeded sample of 4096 such rows (a stand-in for the mean of a training set)."""
+    centre = dense_features(4096, m, seed + 7919, device=device).mean(dim=0, keepdim=True)
+    out = dense_features(N, m, seed, device=device, chunk_rows=chunk_rows)
+    for r0 in range(0, N, chunk_rows):
+        out[r0:r0 + chunk_rows] -= centre
+    return out
+
+
+def random_square(n, seed, device="cpu"):
+    """The random n x n matrix whose QR decomposition gives the encoder's frame: N(0,1) entries, fp32."""
+    return torch.randn((n, n), generator=_gen(seed, device), device=device, dtype=torch.float32)
+
+
 def as_uint32(words_int32_numpy):
     return np.ascontiguousarray(words_int32_numpy).view(np.uint32)

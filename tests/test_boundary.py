@@ -121,3 +121,24 @@ def test_sgd_argument_errors(L):
     assert sgd(npos=4000, nneg=4000) == binding.OTF_ERR_UNSUPPORTED
     assert sgd(ws=None) == binding.OTF_ERR_WORKSPACE
     assert sgd(wsb=16) == binding.OTF_ERR_WORKSPACE
+
+
+def test_encoder_argument_errors(L):
+    def frame(G=FAKE, n=256, m=32, U=FAKE, ws=FAKE, wsb=BIG):
+        return L.otf_tight_frame(G, n, m, U, ws, wsb, None)
+
+    def binz(phi=FAKE, N=1000, m=128, ld=128, U=FAKE, n=2048, bits=FAKE):
+        return L.otf_binarize(phi, N, m, ld, U, n, bits, None)
+
+    assert L.otf_tight_frame_workspace_bytes(2048, 128) == 2048 * 128 * 8
+    assert L.otf_tight_frame_workspace_bytes(16, 32) == 0                  # m > n
+    assert frame(G=None) == binding.OTF_ERR_INVALID_ARG
+    assert frame(m=300, n=256) == binding.OTF_ERR_INVALID_ARG              # more columns than the matrix has
+    assert frame(n=16384, m=128) == binding.OTF_ERR_UNSUPPORTED
+    assert frame(wsb=1024) == binding.OTF_ERR_WORKSPACE
+    assert binz(bits=None) == binding.OTF_ERR_INVALID_ARG
+    assert binz(ld=64) == binding.OTF_ERR_INVALID_ARG                      # rows shorter than m
+    assert binz(phi=FAKE + 4) == binding.OTF_ERR_INVALID_ARG               # misaligned
+    assert binz(m=256, ld=256) == binding.OTF_ERR_UNSUPPORTED
+    assert binz(m=126, ld=128) == binding.OTF_ERR_UNSUPPORTED
+    assert binz(n=2040) == binding.OTF_ERR_UNSUPPORTED

@@ -1,0 +1,103 @@
+"""GPU parity of the binarisation encoder (paper Sec. 3, "Binarization", Eq. (1)) with the CPU
+oracle: the frame U, and the packed codes sgn(U phi).
+
+The codes are an integer result decided by a floating-point sign.  The kernel sums m fp32
+products per bit; the error of any such sum is at most gamma_m * sum_j |U_dj phi_j| with
+gamma_m ~ m * 2^-24, so a bit may differ from the fp64 oracle's only where the exact projection is
+smaller than that bound.  Everywhere else the codes must be identical, and where every product and
+sum is exact in fp32 (integer data) they must be identical without exception."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import otf_encoders as enc
+from paper_1407_4764_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+SEED = synth.BASE_SEED + 2000
+
+
+def _unpack(words, n):
+    w = words.astype(np.uint32)
+    return ((w[:, :, None] >> np.arange(32, dtype=np.uint32)[None, None, :]) & 1).reshape(w.shape[0], n).astype(bool)
+
+
+@pytest.mark.parametrize("n,m", [(256, 32), (1024, 128), (2048, 128), (96, 96)])
+def test_tight_frame_matches_the_oracle(n, m):
+    G = synth.random_square(n, SEED + n + m)
+    U = binding.tight_frame(G.to(DEV), m).cpu().numpy().astype(np.float64)
+    ref = enc.tight_frame(G.numpy(), m)
+    assert U.shape == (n, m)
+    assert np.max(np.abs(U - ref)) <= 1e-6                       # entries are ~ n^-1/2; fp32 storage
+    np.testing.assert_allclose(U.T @ U, np.eye(m), atol=2e-6)
+
+
+@pytest.mark.parametrize("N,m,n", [(3001, 128, 2048), (1, 128, 2048), (777, 128, 1024), (1000, 64, 512),
+                                   (515, 32, 4096), (256, 4, 32)])
+def test_codes_match_the_oracle_outside_the_rounding_band(N, m, n):
+    G = synth.random_square(n, SEED + 1)
+    Ud = binding.tight_frame(G.to(DEV), m)
+    phi = synth.centred_descriptors(N, m, SEED + 2)
+    got = binding.binarize(phi.to(DEV), Ud)
+    torch.cuda.synchronize()
+    got = _unpack(synth.as_uint32(got.cpu().numpy()), n)
+    U = Ud.cpu().numpy()                                          # both sides code with the same fp32 frame
+    proj, mag = enc.projections(phi.numpy(), U)
+    ref = proj > 0
+    band = np.abs(proj) <= 2.0 * m * 2.0 ** -24 * mag
+    diff = got != ref
+    assert not np.any(diff & ~band), "bits differ outside the rounding band: %d" % int(np.sum(diff & ~band))
+    assert diff.mean() < 1e-4
+    np.testing.assert_array_equal(_unpack(enc.binarize(phi.numpy(), U), n), ref)   # the packed form says the same
+
+
+def test_exact_data_gives_identical_codes_and_zero_codes_as_zero():
+    """Small-integer descriptors and a frame of -1/0/+1: every product and partial sum is exact in
+    fp32, many projections are exactly zero (sgn(0) = 0), so the codes must equal the oracle's."""
+    N, m, n = 2000, 128, 2048
+    g = torch.Generator().manual_seed(SEED + 3)
+    phi = torch.randint(-3, 4, (N, m), generator=g).to(torch.float32)
+    U = torch.randint(-1, 2, (n, m), generator=g).to(torch.float32)
+    U[:, 8:] *= (torch.rand((n, m - 8), generator=g) < 0.05)      # sparse rows: exact zeros are common
+    phi[5] = 0
+    got = binding.binarize(phi.to(DEV), U.to(DEV))
+    torch.cuda.synchronize()
+    ref = enc.binarize(phi.numpy(), U.numpy())
+    proj, _ = enc.projections(phi.numpy(), U.numpy())
+    assert (proj == 0).mean() > 0.01
+    np.testing.assert_array_equal(synth.as_uint32(got.cpu().numpy()), ref)
+    assert not got[5].any()
+
+
+def test_strided_descriptor_rows():
+    N, m, n = 600, 64, 1024
+    G = synth.random_square(n, SEED + 4)
+    Ud = binding.tight_frame(G.to(DEV), m)
+    wide = synth.centred_descriptors(N, 96, SEED + 5).to(DEV)      # rows of 96 floats, the first 64 are used
+    a = binding.binarize(wide[:, :m], Ud)
+    b = binding.binarize(wide[:, :m].contiguous(), Ud)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+def test_codes_feed_the_binary_scan(oracle):
+    """Encoder output goes straight into otf_rank_binary: its scores must be those the oracle gives
+    for the oracle's own codes, on every row whose code agrees (all but rounding-band rows)."""
+    N, m, n, k = 5000, 128, 2048, 50
+    G = synth.random_square(n, SEED + 6)
+    Ud = binding.tight_frame(G.to(DEV), m)
+    phi = synth.centred_descriptors(N, m, SEED + 7)
+    bits = binding.binarize(phi.to(DEV), Ud)
+    w = synth.normal_vector(n, 1.0, SEED + 8)
+    ws = binding.make_workspace(N, k)
+    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
+    binding.rank_binary(bits, n, w.to(DEV), 0.0, k, ws, all_scores=all_scores)
+    torch.cuda.synchronize()
+    ref_bits = enc.binarize(phi.numpy(), Ud.cpu().numpy())
+    same = np.all(synth.as_uint32(bits.cpu().numpy()) == ref_bits, axis=1)
+    assert same.mean() > 0.99
+    ref = oracle.binary_scores(ref_bits, n, w.numpy(), 0.0)
+    got = all_scores.cpu().numpy().astype(np.float64)
+    tol = 1e-4 * np.maximum(np.abs(ref), ref.std())
+    assert np.all(np.abs(got - ref)[same] <= tol[same])
