@@ -160,6 +160,39 @@ def measure_sgd(torch, binding, synth):
     return {"workload": "pegasos_pass_125steps_B256_D2048", "ms_per_pass": dt * 1e3, "us_per_step": dt / steps * 1e6}
 
 
+MFMA_FP32_PEAK_TFLOPS = 157.3                     # MI355X dense fp32 matrix rate
+
+
+def measure_encoder(torch, binding, synth):
+    """Binarisation encoder (paper Sec. 3, Table 2 row "128 BIN 2048 dims"): 1M descriptors of 128
+    dimensions to 2048-bit codes; timed with events on the stream the kernel runs on."""
+    N, m, n = 1_000_000, 128, 2048
+    G = synth.random_square(n, synth.BASE_SEED + 6, device="cuda")
+    U = binding.tight_frame(G, m)
+    phi = synth.centred_descriptors(N, m, synth.BASE_SEED + 7, device="cuda")
+    bits = torch.empty((N, n // 32), dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        binding.binarize(phi, U, bits)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 10
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        binding.binarize(phi, U, bits)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    t0 = time.perf_counter()
+    binding.tight_frame(G, m)
+    torch.cuda.synchronize()
+    frame_ms = (time.perf_counter() - t0) * 1e3
+    tflops = 2.0 * N * m * n / (ms * 1e-3) / 1e12
+    return {"workload": "binarize_1Mx128_to_2048bit", "ms_per_call": ms, "descriptors_per_s": N / (ms * 1e-3),
+            "frame_setup_ms": frame_ms,
+            "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": tflops / MFMA_FP32_PEAK_TFLOPS, "traffic": None}}
+
+
 def cpu_baseline(kind, cfg, torch):
     """Times the CPU oracle on this host on a bounded sample of the workload's own rows."""
     from oracle import otf_oracle as orc
@@ -217,6 +250,7 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only; the result is then not the named workload)")
     ap.add_argument("--no-others", action="store_true", help="skip the other stores and the training pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--encoder-only", action="store_true", help="only time the binarisation encoder")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 2 GiB five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -235,6 +269,10 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "copies": 5}))
+        return
+
+    if args.encoder_only:
+        print(json.dumps(measure_encoder(torch, binding, synth)))
         return
 
     res, cfg = measure(args.workload, args.steps, args.warmup, args.scale, torch, binding, synth)
@@ -270,6 +308,7 @@ def main():
             torch.cuda.empty_cache()
             others.append(r)
         others.append(measure_sgd(torch, binding, synth))
+        others.append(measure_encoder(torch, binding, synth))
         line["other_workloads"] = others
     line["paper_context"] = "paper: ~0.01 s to score + ~0.002 s to sort 1M x 128-D fp32 on a GTX Titan (Sec. 4)"
     print(json.dumps(line))

@@ -124,6 +124,21 @@ def sgd_batches(n_pos_pool, n_neg_pool, batch, steps, seed):
     return pos, neg
 
 
+def onthefly_schedule(rounds, steps_per_round, batch, n_pos_start, pos_per_round, n_pos_total, n_neg_pool, seed):
+    """Index schedule of an on-the-fly query (Sec. 4 "On-line (GPU back-end)": training starts with
+    the first positives and the pool of positives keeps growing while the model is trained and the
+    dataset re-ranked at intervals).  Round r trains `steps_per_round` steps on the first
+    min(n_pos_total, n_pos_start + r * pos_per_round) positives of the pool, each batch half
+    positives, half negatives, all drawn uniformly with replacement; a ranking follows each round.
+    Returns (pool_sizes [rounds], idx_pos [rounds, steps, batch/2], idx_neg [same]) as numpy int32."""
+    rng = np.random.Generator(np.random.Philox(int(seed)))
+    half = batch // 2
+    sizes = np.minimum(n_pos_total, n_pos_start + pos_per_round * np.arange(rounds)).astype(np.int32)
+    pos = np.stack([rng.integers(0, int(p), size=(steps_per_round, half), dtype=np.int64) for p in sizes]).astype(np.int32)
+    neg = rng.integers(0, n_neg_pool, size=(rounds, steps_per_round, half), dtype=np.int64).astype(np.int32)
+    return sizes, pos, neg
+
+
 def centred_descriptors(N, m, seed, device="cpu", chunk_rows=65536):
     """Descriptors for the binarisation encoder (Sec. 3 "Binarization": "zero-centred descriptors"):
     the dense features above with one constant per dimension subtracted, the mean of a fixed
