@@ -151,6 +151,18 @@ int otf_svm_sgd_step(float *w, float *b, int32_t D,
                      void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * n_steps consecutive Pegasos steps (iterations t_first, t_first + 1, ...), enqueued back to back:
+ * step s uses the batch idx_pos[s * n_pos .. (s+1) * n_pos), idx_neg[s * n_neg .. (s+1) * n_neg).
+ * Same arguments, limits and errors as otf_svm_sgd_step; n_steps >= 1.  (Paper Sec. 4: between two
+ * rankings the model takes as many steps as fit; one call keeps the host out of that loop.)
+ */
+int otf_svm_sgd_pass(float *w, float *b, int32_t D,
+                     const float *Xpos, int64_t ld_pos, const int32_t *idx_pos, int32_t n_pos,
+                     const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int32_t n_neg,
+                     float lambda, int64_t t_first, int32_t n_steps, int32_t update_bias,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Binarisation encoder (paper Sec. 3, "Binarization", Eq. (1)): a zero-centred descriptor phi in
  * R^m is coded as beta = sgn(U phi) in {0,1}^n, n > m, with sgn(a) = 1 iff a > 0 (a zero
  * projection codes as 0) and U the first m columns of the orthogonal factor of a QR

@@ -22,7 +22,8 @@ OTF_F16 = 1
 OTF_MAX_K = 8192
 
 EXPORTS = ["otf_status_string", "otf_workspace_bytes", "otf_rank_dense", "otf_pq_build_lut", "otf_rank_pq",
-           "otf_rank_binary", "otf_topk", "otf_sgd_workspace_bytes", "otf_svm_sgd_step", "otf_tight_frame_workspace_bytes",
+           "otf_rank_binary", "otf_topk", "otf_sgd_workspace_bytes", "otf_svm_sgd_step", "otf_svm_sgd_pass",
+           "otf_tight_frame_workspace_bytes",
            "otf_tight_frame", "otf_binarize", "otf_profile_begin", "otf_profile_end"]
 
 _lib = None
@@ -62,6 +63,8 @@ def lib():
         L.otf_topk.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, sz, vp]
         L.otf_svm_sgd_step.restype = ctypes.c_int
         L.otf_svm_sgd_step.argtypes = [vp, vp, i32, vp, i64, vp, i32, vp, i64, vp, i32, f32, i64, i32, vp, sz, vp]
+        L.otf_svm_sgd_pass.restype = ctypes.c_int
+        L.otf_svm_sgd_pass.argtypes = [vp, vp, i32, vp, i64, vp, i32, vp, i64, vp, i32, f32, i64, i32, i32, vp, sz, vp]
         L.otf_tight_frame_workspace_bytes.restype = sz
         L.otf_tight_frame_workspace_bytes.argtypes = [i32, i32]
         L.otf_tight_frame.restype = ctypes.c_int
@@ -192,6 +195,17 @@ def svm_sgd_step(w, b, Xpos, idx_pos, Xneg, idx_neg, lam, t, update_bias, ws):
                                 ws.numel(), _stream(w.device))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_svm_sgd_step")
+
+
+def svm_sgd_pass(w, b, Xpos, idx_pos, Xneg, idx_neg, lam, t_first, update_bias, ws):
+    """idx_pos, idx_neg: contiguous int32 (steps, half) tensors; runs the steps t_first, t_first + 1, ..."""
+    assert idx_pos.is_contiguous() and idx_neg.is_contiguous() and idx_pos.shape[0] == idx_neg.shape[0]
+    rc = lib().otf_svm_sgd_pass(_ptr(w), _ptr(b), w.shape[0], _ptr(Xpos), Xpos.stride(0), _ptr(idx_pos),
+                                idx_pos.shape[1], _ptr(Xneg), Xneg.stride(0), _ptr(idx_neg), idx_neg.shape[1],
+                                float(lam), int(t_first), idx_pos.shape[0], int(bool(update_bias)), _ptr(ws),
+                                ws.numel(), _stream(w.device))
+    if rc != OTF_OK:
+        raise OtfError(rc, "otf_svm_sgd_pass")
 
 
 def tight_frame(G, m, U=None):

@@ -361,6 +361,20 @@ int otf_svm_sgd_step(float *w, float *b, int32_t D, const float *Xpos, int64_t l
                                       reinterpret_cast<hipStream_t>(stream)));
 }
 
+int otf_svm_sgd_pass(float *w, float *b, int32_t D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,
+                     int32_t n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int32_t n_neg,
+                     float lambda, int64_t t_first, int32_t n_steps, int32_t update_bias, void *ws, size_t ws_bytes,
+                     void *stream) {
+    if (n_steps < 1) return OTF_ERR_INVALID_ARG;
+    for (int32_t s = 0; s < n_steps; ++s) {
+        const int rc = otf_svm_sgd_step(w, b, D, Xpos, ld_pos, idx_pos ? idx_pos + (size_t)s * n_pos : nullptr, n_pos,
+                                        Xneg, ld_neg, idx_neg ? idx_neg + (size_t)s * n_neg : nullptr, n_neg, lambda,
+                                        t_first + s, update_bias, ws, ws_bytes, stream);
+        if (rc != OTF_OK) return rc;      // argument errors show at s == 0, before anything is enqueued
+    }
+    return OTF_OK;
+}
+
 size_t otf_tight_frame_workspace_bytes(int32_t n, int32_t m) {
     if (n < 1 || m < 1 || m > n) return 0;
     return (size_t)n * (size_t)m * sizeof(double);

@@ -39,9 +39,8 @@ def run(X, Xpos, Xneg, idx_pos, idx_neg, k, lam, overlap=True):
         t_begin.record()
     for r in range(rounds):
         with torch.cuda.stream(train):
-            for s in range(steps):
-                t += 1
-                binding.svm_sgd_step(w, None, Xpos, idx_pos[r, s], Xneg, idx_neg[r, s], lam, t, False, sgd_ws)
+            binding.svm_sgd_pass(w, None, Xpos, idx_pos[r], Xneg, idx_neg[r], lam, t + 1, False, sgd_ws)
+            t += steps
             snaps[r].copy_(w)                      # the model this round's ranking sees
             snapped[r].record()
             if r == rounds - 1:

@@ -142,3 +142,15 @@ def test_encoder_argument_errors(L):
     assert binz(m=256, ld=256) == binding.OTF_ERR_UNSUPPORTED
     assert binz(m=126, ld=128) == binding.OTF_ERR_UNSUPPORTED
     assert binz(n=2040) == binding.OTF_ERR_UNSUPPORTED
+
+
+def test_sgd_pass_argument_errors(L):
+    def sgd(n_steps=4, w=FAKE, D=128, n=16, lam=1.0, t=1, wsb=BIG):
+        return L.otf_svm_sgd_pass(w, None, D, FAKE, D, FAKE, n, FAKE, D, FAKE, n, ctypes.c_float(lam), t, n_steps, 0,
+                                  FAKE, wsb, None)
+
+    assert sgd(n_steps=0) == binding.OTF_ERR_INVALID_ARG
+    assert sgd(w=None) == binding.OTF_ERR_INVALID_ARG
+    assert sgd(t=0) == binding.OTF_ERR_INVALID_ARG
+    assert sgd(D=126) == binding.OTF_ERR_UNSUPPORTED
+    assert sgd(wsb=16) == binding.OTF_ERR_WORKSPACE
