@@ -193,6 +193,36 @@ int otf_binarize(const float *phi, int64_t N, int32_t m, int64_t ld_phi, const f
                  uint32_t *bits, void *stream);
 
 /*
+ * Product-quantisation encoder and vocabulary training (paper Sec. 3, "Product quantization (PQ)":
+ * each sub-block is "encoded using a separate vocabulary of cluster centres pre-learned from a
+ * training set").  The codes are the rows otf_rank_pq scans.
+ *
+ * otf_pq_encode:  codes[i][m] = argmin_k || X[i][m*dsub .. (m+1)*dsub) - codebooks[m][k] ||^2, the
+ *   lowest k among equal distances.  Evaluated as argmin_k ||c_k||^2 - 2 <x, c_k> in fp32 on the matrix
+ *   cores: where two centres are equally near to within rounding, either may be returned.
+ *   X  N x (M*dsub) floats, leading dimension ldx (elements, a multiple of 4).
+ *   codebooks  M x K x dsub floats, contiguous.   codes  N x M bytes, contiguous rows, 4-byte aligned.
+ *   K must be 256, dsub 4, 8 or 16, M a multiple of 4; otherwise OTF_ERR_UNSUPPORTED.
+ *
+ * otf_pq_lloyd_step:  one k-means iteration on the training rows X.  The paper does not say how the
+ *   centres are learned; the PQ method it cites uses k-means, taken here as Lloyd iterations from
+ *   centres supplied by the caller: (1) codes = otf_pq_encode(X, codebooks); (2) every centre moves
+ *   to the mean of the sub-vectors assigned to it, a centre with none stays (fp32 sums in an
+ *   unspecified order).  codebooks is updated in place; codes receives the assignment of step (1);
+ *   *distortion (one double in device memory, may be NULL) the mean over rows of the summed squared
+ *   distances to the assigned centres, measured before the move.
+ *
+ *   ws  at least otf_pq_train_workspace_bytes(M, dsub) bytes, 256-byte aligned.
+ */
+size_t otf_pq_train_workspace_bytes(int32_t M, int32_t dsub);
+
+int otf_pq_encode(const float *X, int64_t N, int64_t ldx, const float *codebooks, int32_t M, int32_t K,
+                  int32_t dsub, uint8_t *codes, void *ws, size_t ws_bytes, void *stream);
+
+int otf_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *codebooks, int32_t M, int32_t K,
+                      int32_t dsub, uint8_t *codes, double *distortion, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Diagnostics (host, not part of the paper's method; for benchmarks that must time the
  * scoring kernel by itself).  Between otf_profile_begin and otf_profile_end every otf_rank_*
  * call brackets its scoring kernel(s) with a pair of HIP events on the call's stream, at most

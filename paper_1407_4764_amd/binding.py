@@ -24,7 +24,8 @@ OTF_MAX_K = 8192
 EXPORTS = ["otf_status_string", "otf_workspace_bytes", "otf_rank_dense", "otf_pq_build_lut", "otf_rank_pq",
            "otf_rank_binary", "otf_topk", "otf_sgd_workspace_bytes", "otf_svm_sgd_step", "otf_svm_sgd_pass",
            "otf_tight_frame_workspace_bytes",
-           "otf_tight_frame", "otf_binarize", "otf_profile_begin", "otf_profile_end"]
+           "otf_tight_frame", "otf_binarize", "otf_pq_train_workspace_bytes", "otf_pq_encode", "otf_pq_lloyd_step",
+           "otf_profile_begin", "otf_profile_end"]
 
 _lib = None
 
@@ -71,6 +72,12 @@ def lib():
         L.otf_tight_frame.argtypes = [vp, i32, i32, vp, vp, sz, vp]
         L.otf_binarize.restype = ctypes.c_int
         L.otf_binarize.argtypes = [vp, i64, i32, i64, vp, i32, vp, vp]
+        L.otf_pq_train_workspace_bytes.restype = sz
+        L.otf_pq_train_workspace_bytes.argtypes = [i32, i32]
+        L.otf_pq_encode.restype = ctypes.c_int
+        L.otf_pq_encode.argtypes = [vp, i64, i64, vp, i32, i32, i32, vp, vp, sz, vp]
+        L.otf_pq_lloyd_step.restype = ctypes.c_int
+        L.otf_pq_lloyd_step.argtypes = [vp, i64, i64, vp, i32, i32, i32, vp, vp, vp, sz, vp]
         L.otf_profile_begin.restype = ctypes.c_int
         L.otf_profile_begin.argtypes = [i32]
         L.otf_profile_end.restype = ctypes.c_int
@@ -235,6 +242,43 @@ def binarize(phi, U, bits=None):
     if rc != OTF_OK:
         raise OtfError(rc, "otf_binarize")
     return bits
+
+
+def pq_train_workspace(M, dsub, device="cuda"):
+    n = int(lib().otf_pq_train_workspace_bytes(int(M), int(dsub)))
+    if n == 0:
+        raise OtfError(OTF_ERR_INVALID_ARG, "otf_pq_train_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def pq_encode(X, codebooks, ws, codes=None):
+    """codes (N, M) uint8: nearest centre of every sub-block.  X (N, M*dsub) fp32, codebooks (M, 256, dsub)."""
+    assert X.dtype == torch.float32 and X.stride(1) == 1 and codebooks.is_contiguous()
+    M, K, dsub = codebooks.shape
+    N = X.shape[0]
+    if codes is None:
+        codes = torch.empty((N, M), dtype=torch.uint8, device=X.device)
+    rc = lib().otf_pq_encode(_ptr(X), N, X.stride(0), _ptr(codebooks), M, K, dsub, _ptr(codes), _ptr(ws), ws.numel(),
+                             _stream(X.device))
+    if rc != OTF_OK:
+        raise OtfError(rc, "otf_pq_encode")
+    return codes
+
+
+def pq_lloyd_step(X, codebooks, ws, codes=None, distortion=None):
+    """One k-means iteration; codebooks is updated in place.  Returns (codes, distortion (1,) float64 tensor)."""
+    assert X.dtype == torch.float32 and X.stride(1) == 1 and codebooks.is_contiguous()
+    M, K, dsub = codebooks.shape
+    N = X.shape[0]
+    if codes is None:
+        codes = torch.empty((N, M), dtype=torch.uint8, device=X.device)
+    if distortion is None:
+        distortion = torch.zeros(1, dtype=torch.float64, device=X.device)
+    rc = lib().otf_pq_lloyd_step(_ptr(X), N, X.stride(0), _ptr(codebooks), M, K, dsub, _ptr(codes), _ptr(distortion),
+                                 _ptr(ws), ws.numel(), _stream(X.device))
+    if rc != OTF_OK:
+        raise OtfError(rc, "otf_pq_lloyd_step")
+    return codes, distortion
 
 
 def debug_fallback_taken(ws):

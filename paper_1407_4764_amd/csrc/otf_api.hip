@@ -398,6 +398,39 @@ int otf_binarize(const float *phi, int64_t N, int32_t m, int64_t ld_phi, const f
     return hip_status(launch_binarize(phi, N, m, ld_phi, U, n, bits, reinterpret_cast<hipStream_t>(stream)));
 }
 
+size_t otf_pq_train_workspace_bytes(int32_t M, int32_t dsub) {
+    if (M < 1 || dsub < 1) return 0;
+    return pq_train_ws_bytes(M, dsub);
+}
+
+static int pq_train_args(const float *X, int64_t N, int64_t ldx, const float *codebooks, int32_t M, int32_t K,
+                         int32_t dsub, const uint8_t *codes, const void *ws, size_t ws_bytes) {
+    if (!X || !codebooks || !codes || N < 1 || M < 1 || K < 1 || dsub < 1 || ldx < (int64_t)M * dsub)
+        return OTF_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(codebooks) || ldx % 4 != 0 || (reinterpret_cast<uintptr_t>(codes) & 3u))
+        return OTF_ERR_INVALID_ARG;
+    if (N >= ((int64_t)1 << 31)) return OTF_ERR_UNSUPPORTED;
+    if (K != 256 || (dsub != 4 && dsub != 8 && dsub != 16) || M % 4 != 0 || M > 4096) return OTF_ERR_UNSUPPORTED;
+    if (!ws || ws_bytes < otf_pq_train_workspace_bytes(M, dsub) || (reinterpret_cast<uintptr_t>(ws) & 255u))
+        return OTF_ERR_WORKSPACE;
+    return OTF_OK;
+}
+
+int otf_pq_encode(const float *X, int64_t N, int64_t ldx, const float *codebooks, int32_t M, int32_t K, int32_t dsub,
+                  uint8_t *codes, void *ws, size_t ws_bytes, void *stream) {
+    const int rc = pq_train_args(X, N, ldx, codebooks, M, K, dsub, codes, ws, ws_bytes);
+    if (rc != OTF_OK) return rc;
+    return hip_status(launch_pq_encode(X, N, ldx, codebooks, M, dsub, codes, ws, reinterpret_cast<hipStream_t>(stream)));
+}
+
+int otf_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *codebooks, int32_t M, int32_t K, int32_t dsub,
+                      uint8_t *codes, double *distortion, void *ws, size_t ws_bytes, void *stream) {
+    const int rc = pq_train_args(X, N, ldx, codebooks, M, K, dsub, codes, ws, ws_bytes);
+    if (rc != OTF_OK) return rc;
+    return hip_status(launch_pq_lloyd_step(X, N, ldx, codebooks, M, dsub, codes, distortion, ws,
+                                           reinterpret_cast<hipStream_t>(stream)));
+}
+
 int otf_profile_begin(int32_t max_records) {
     if (g_prof.on || max_records < 1 || max_records > 65536) return OTF_ERR_INVALID_ARG;
     g_prof.start.assign(max_records, nullptr);

@@ -97,6 +97,13 @@ hipError_t launch_tight_frame(const float *G, int n, int m, double *scratch, flo
 hipError_t launch_binarize(const float *phi, int64_t N, int m, int64_t ld, const float *U, int n, uint32_t *bits,
                            hipStream_t s);
 
+// PQ encoder and one Lloyd iteration (K = 256; dsub 4, 8 or 16; M a multiple of 4).
+size_t pq_train_ws_bytes(int M, int dsub);
+hipError_t launch_pq_encode(const float *X, int64_t N, int64_t ldx, const float *codebooks, int M, int dsub,
+                            uint8_t *codes, void *ws, hipStream_t s);
+hipError_t launch_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *codebooks, int M, int dsub,
+                                uint8_t *codes, double *distortion_out, void *ws, hipStream_t s);
+
 int device_cu_count();
 
 // Launch-shape knobs for tuning runs: integer environment variable `name`, else `fallback`.

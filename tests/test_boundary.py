@@ -154,3 +154,19 @@ def test_sgd_pass_argument_errors(L):
     assert sgd(t=0) == binding.OTF_ERR_INVALID_ARG
     assert sgd(D=126) == binding.OTF_ERR_UNSUPPORTED
     assert sgd(wsb=16) == binding.OTF_ERR_WORKSPACE
+
+
+def test_pq_train_argument_errors(L):
+    def enc(X=FAKE, N=1000, ldx=2048, cb=FAKE, M=128, K=256, dsub=16, codes=FAKE, ws=FAKE, wsb=BIG):
+        return L.otf_pq_encode(X, N, ldx, cb, M, K, dsub, codes, ws, wsb, None)
+
+    assert L.otf_pq_train_workspace_bytes(128, 16) >= 128 * 256 * (4 + 64 + 4)
+    assert L.otf_pq_train_workspace_bytes(0, 16) == 0
+    assert enc(X=None) == binding.OTF_ERR_INVALID_ARG
+    assert enc(ldx=1024) == binding.OTF_ERR_INVALID_ARG                   # rows shorter than M * dsub
+    assert enc(codes=FAKE + 2) == binding.OTF_ERR_INVALID_ARG
+    assert enc(K=128) == binding.OTF_ERR_UNSUPPORTED
+    assert enc(dsub=12, ldx=4096) == binding.OTF_ERR_UNSUPPORTED
+    assert enc(M=126) == binding.OTF_ERR_UNSUPPORTED
+    assert enc(wsb=4096) == binding.OTF_ERR_WORKSPACE
+    assert L.otf_pq_lloyd_step(FAKE, 1000, 2048, None, 128, 256, 16, FAKE, None, FAKE, BIG, None) == binding.OTF_ERR_INVALID_ARG

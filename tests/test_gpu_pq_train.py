@@ -1,0 +1,136 @@
+"""GPU parity of the PQ encoder and the Lloyd iteration (paper Sec. 3, "Product quantization (PQ)")
+with the CPU oracle.
+
+A code is an integer decided by a floating-point comparison.  The kernel compares fp32 values of
+||c||^2 - 2 <x, c>; their rounding error is bounded by a small multiple of dsub * 2^-24 times
+(||x|| + ||c||)^2, so the kernel's centre may differ from the fp64 oracle's only when it is that
+close to being the nearest.  With integer data every value is exact in fp32 and the codes, ties
+included, must be identical."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import otf_pq_train as pq
+from paper_1407_4764_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+SEED = synth.BASE_SEED + 4000
+
+
+def _data(N, M, dsub, seed):
+    """Training/store rows and a vocabulary picked from other rows of the same distribution."""
+    X = synth.dense_features(N, M * dsub, seed)
+    picks = synth.dense_features(256, M * dsub, seed + 1)
+    C = picks.reshape(256, M, dsub).permute(1, 0, 2).contiguous()
+    return X, C
+
+
+def _check_codes(X, C, codes):
+    d = pq.distances(X, C)                                          # N x M x K, fp64
+    ref = np.argmin(d, axis=2)
+    got = codes.astype(np.int64)
+    chosen = np.take_along_axis(d, got[:, :, None], axis=2)[:, :, 0]
+    dsub = C.shape[2]
+    xs = X.astype(np.float64).reshape(X.shape[0], C.shape[0], dsub)
+    scale = (np.linalg.norm(xs, axis=2) + np.linalg.norm(C.astype(np.float64), axis=2).max(axis=1)[None, :]) ** 2
+    band = 8.0 * dsub * 2.0 ** -24 * scale
+    assert np.all(chosen <= d.min(axis=2) + band), "a code is not a nearest centre"
+    assert (got != ref).mean() < 1e-3
+    return ref
+
+
+@pytest.mark.parametrize("N,M,dsub", [(3001, 128, 16), (1, 128, 16), (2000, 32, 4), (1500, 16, 8), (700, 4, 16),
+                                      (513, 512, 4)])
+def test_codes_are_nearest_centres(N, M, dsub):
+    X, C = _data(N, M, dsub, SEED + M + dsub)
+    ws = binding.pq_train_workspace(M, dsub)
+    codes = binding.pq_encode(X.to(DEV), C.to(DEV), ws)
+    torch.cuda.synchronize()
+    _check_codes(X.numpy(), C.numpy(), codes.cpu().numpy())
+
+
+def test_exact_data_gives_identical_codes_with_ties_to_the_lower_index():
+    N, M, dsub = 3000, 8, 8
+    g = torch.Generator().manual_seed(SEED + 1)
+    X = torch.randint(-4, 5, (N, M * dsub), generator=g).to(torch.float32)
+    C = torch.randint(-4, 5, (M, 256, dsub), generator=g).to(torch.float32)
+    C[:, 200:] = C[:, :56]                                          # duplicate centres: exact ties
+    X[:56, :dsub] = C[0, 200:]                                      # rows sitting on a duplicated centre
+    ws = binding.pq_train_workspace(M, dsub)
+    codes = binding.pq_encode(X.to(DEV), C.to(DEV), ws).cpu().numpy()
+    ref = pq.encode(X.numpy(), C.numpy())
+    np.testing.assert_array_equal(codes, ref)
+    assert np.all(codes[:56, 0] < 200)
+
+
+def test_strided_rows_and_padding_columns():
+    N, M, dsub = 900, 16, 8
+    X, C = _data(N, M, dsub, SEED + 2)
+    wide = torch.zeros((N, M * dsub + 12))
+    wide[:, :M * dsub] = X
+    ws = binding.pq_train_workspace(M, dsub)
+    a = binding.pq_encode(wide.to(DEV)[:, :M * dsub], C.to(DEV), ws)
+    b = binding.pq_encode(X.to(DEV), C.to(DEV), ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("N,M,dsub", [(20000, 16, 8), (6000, 128, 16)])
+def test_lloyd_step_matches_the_oracle(N, M, dsub):
+    X, C = _data(N, M, dsub, SEED + 3)
+    C[0, 255] = 50.0                                                # a centre nothing is assigned to
+    Cd = C.to(DEV).clone()
+    ws = binding.pq_train_workspace(M, dsub)
+    codes, dist = binding.pq_lloyd_step(X.to(DEV), Cd, ws)
+    torch.cuda.synchronize()
+    codes = codes.cpu().numpy()
+    _check_codes(X.numpy(), C.numpy(), codes)
+    # the move, given the kernel's own assignment: means of the cells, in fp64
+    Xs = X.numpy().astype(np.float64).reshape(N, M, dsub)
+    want = C.numpy().astype(np.float64).copy()
+    d_sum = 0.0
+    for m in range(M):
+        cm = codes[:, m]
+        diff = Xs[:, m, :] - C.numpy().astype(np.float64)[m, cm]
+        d_sum += (diff * diff).sum()
+        counts = np.bincount(cm, minlength=256)
+        sums = np.zeros((256, dsub))
+        np.add.at(sums, cm, Xs[:, m, :])
+        nz = counts > 0
+        want[m, nz] = sums[nz] / counts[nz, None]
+    got = Cd.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got - want)) <= 1e-5 * np.abs(want).max()
+    np.testing.assert_array_equal(got[0, 255], np.full(dsub, 50.0))
+    np.testing.assert_allclose(float(dist.cpu()[0]), d_sum / N, rtol=1e-5)
+    # and against the oracle's own iteration (its assignment differs from the kernel's on near-ties only)
+    C_ref, _, dist_ref = pq.lloyd_step(X.numpy(), C.numpy())
+    np.testing.assert_allclose(float(dist.cpu()[0]), dist_ref, rtol=1e-5)
+    assert np.max(np.abs(got - C_ref)) <= 2e-3 * np.abs(C_ref).max()
+
+
+def test_iterations_decrease_the_distortion_and_codes_feed_the_scan(oracle):
+    N, M, dsub, k = 30000, 16, 8, 50
+    X, C = _data(N, M, dsub, SEED + 4)
+    Xd, Cd = X.to(DEV), C.to(DEV).clone()
+    ws = binding.pq_train_workspace(M, dsub)
+    dists = []
+    for _ in range(5):
+        _, dist = binding.pq_lloyd_step(Xd, Cd, ws)
+        dists.append(float(dist.cpu()[0]))
+    assert all(b <= a * (1 + 1e-6) for a, b in zip(dists, dists[1:])) and dists[-1] < 0.9 * dists[0]
+    C_ref = C.numpy().astype(np.float64)
+    for _ in range(5):
+        C_ref, _, dist_ref = pq.lloyd_step(X.numpy(), C_ref.astype(np.float32))
+    np.testing.assert_allclose(dists[-1], dist_ref, rtol=2e-3)
+    # encode with the trained vocabulary and rank: scores are those of the reconstruction
+    codes = binding.pq_encode(Xd, Cd, ws)
+    w = synth.normal_vector(M * dsub, 1.0, SEED + 5)
+    lut = binding.pq_build_lut(Cd, w.to(DEV))
+    rws = binding.make_workspace(N, k)
+    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
+    val, idx = binding.rank_pq(codes, lut, 0.0, k, rws, all_scores=all_scores)
+    torch.cuda.synchronize()
+    ref = oracle.pq_scores_reconstruct(codes.cpu().numpy(), Cd.cpu().numpy(), w.numpy(), 0.0)
+    ok, msg = oracle.topk_parity_ok(ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), 1e-4)
+    assert ok, msg
