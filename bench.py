@@ -187,6 +187,36 @@ def measure_onthefly(torch, binding, synth, X=None):
             "new_rows_in_list_per_round": churn, **res}
 
 
+def measure_pq_encoder(torch, binding, synth, X=None):
+    """PQ encoder and one Lloyd iteration (paper Sec. 3, "Product quantization (PQ)") on 1M x 2048
+    fp32 rows with the geometry of the PQ workload (M = 128 sub-blocks of 16 dimensions, K = 256)."""
+    N, M, dsub = 1_000_000, 128, 16
+    if X is None:
+        X = synth.dense_features(N, M * dsub, synth.BASE_SEED + 2, device="cuda")
+    C = X[:256].reshape(256, M, dsub).permute(1, 0, 2).contiguous()
+    ws = binding.pq_train_workspace(M, dsub)
+    codes = torch.empty((N, M), dtype=torch.uint8, device="cuda")
+    e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+    for _ in range(2):
+        binding.pq_encode(X, C, ws, codes)
+    reps = 5
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        binding.pq_encode(X, C, ws, codes)
+    e1.record()
+    for _ in range(reps):
+        binding.pq_lloyd_step(X, C, ws, codes)
+    e2.record()
+    torch.cuda.synchronize()
+    enc_ms, lloyd_ms = e0.elapsed_time(e1) / reps, e1.elapsed_time(e2) / reps
+    tflops = 2.0 * N * M * 256 * dsub / (enc_ms * 1e-3) / 1e12
+    return {"workload": "pq_encode_1Mx2048_M128_K256", "encode_ms": enc_ms, "rows_per_s": N / (enc_ms * 1e-3),
+            "lloyd_step_ms": lloyd_ms,
+            "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": tflops / MFMA_FP32_PEAK_TFLOPS, "traffic": None}}
+
+
 MFMA_FP32_PEAK_TFLOPS = 157.3                     # MI355X dense fp32 matrix rate
 
 
@@ -279,6 +309,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--encoder-only", action="store_true", help="only time the binarisation encoder")
     ap.add_argument("--loop-only", action="store_true", help="only run the on-the-fly loop")
+    ap.add_argument("--pqenc-only", action="store_true", help="only time the PQ encoder and a Lloyd iteration")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 2 GiB five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -301,6 +332,9 @@ def main():
 
     if args.encoder_only:
         print(json.dumps(measure_encoder(torch, binding, synth)))
+        return
+    if args.pqenc_only:
+        print(json.dumps(measure_pq_encoder(torch, binding, synth)))
         return
     if args.loop_only:
         print(json.dumps(measure_onthefly(torch, binding, synth)))
@@ -327,9 +361,10 @@ def main():
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(args.workload, cfg, torch)
-    loop = None
+    loop = pqenc = None
     if not args.no_others and args.workload == "dense" and args.scale == 1.0:
         loop = measure_onthefly(torch, binding, synth, cfg["_keep"][0])          # on the store already resident
+        pqenc = measure_pq_encoder(torch, binding, synth, cfg["_keep"][0])
     del cfg
     torch.cuda.empty_cache()
     if not args.no_others:
@@ -344,6 +379,7 @@ def main():
         others.append(measure_sgd(torch, binding, synth))
         others.append(measure_encoder(torch, binding, synth))
         others.append(loop if loop is not None else measure_onthefly(torch, binding, synth))
+        others.append(pqenc if pqenc is not None else measure_pq_encoder(torch, binding, synth))
         line["other_workloads"] = others
     line["paper_context"] = "paper: ~0.01 s to score + ~0.002 s to sort 1M x 128-D fp32 on a GTX Titan (Sec. 4)"
     print(json.dumps(line))

@@ -7,7 +7,7 @@
 // is common to all k), the lowest k among equals.  The inner products of 32 rows with 32 centres
 // are one v_mfma_f32_32x32x2_f32 chain of dsub/2 steps, so an encoding pass is an
 // N x 256 x dsub product per sub-block on the matrix cores, and what remains for the vector ALU
-// is the argmin: a running minimum per lane over the 8 blocks of 32 centres, then one butterfly
+// is the argmin: a running minimum per lane over the 8 blocks of 32 centres, then one reduction
 // over the 32 lanes that hold the candidates of a row.
 #include <algorithm>
 
@@ -19,6 +19,26 @@ typedef float float16v __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kPqK = 256;
+
+// Minimum over each half-wave (lanes 0..31, lanes 32..63); every lane receives it.
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v) {
+    return __builtin_amdgcn_mov_dpp(v, CTRL, 0xF, 0xF, true);
+}
+__device__ __forceinline__ float half_min_f32(float v) {
+    v = fminf(v, __int_as_float(dpp_i32<0xB1>(__float_as_int(v))));    // quad_perm [1,0,3,2]: lane ^ 1
+    v = fminf(v, __int_as_float(dpp_i32<0x4E>(__float_as_int(v))));    // quad_perm [2,3,0,1]: lane ^ 2
+    v = fminf(v, __int_as_float(dpp_i32<0x141>(__float_as_int(v))));   // row_half_mirror: lane i <-> 7 - i of each 8
+    v = fminf(v, __int_as_float(dpp_i32<0x140>(__float_as_int(v))));   // row_mirror: lane i <-> 15 - i of each 16
+    return fminf(v, __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F)));   // lane ^ 16
+}
+__device__ __forceinline__ int half_min_i32(int v) {
+    v = min(v, dpp_i32<0xB1>(v));
+    v = min(v, dpp_i32<0x4E>(v));
+    v = min(v, dpp_i32<0x141>(v));
+    v = min(v, dpp_i32<0x140>(v));
+    return min(v, __builtin_amdgcn_ds_swizzle(v, 0x401F));
+}
 
 // norms[m][k] = ||codebooks[m][k]||^2
 __global__ __launch_bounds__(256) void pq_centre_norms_kernel(const float *__restrict__ codebooks, int M, int dsub,
@@ -110,7 +130,7 @@ __global__ __launch_bounds__(256, 2) void pq_encode_kernel(const float *__restri
                     best[f][v] = __builtin_inff();
                     bestk[f][v] = 0;
                 }
-#pragma unroll 1
+#pragma unroll 2
             for (int cb = 0; cb < kPqK / 32; ++cb) {
                 float b[HALF];
                 const float *bp = reinterpret_cast<const float *>(cs[buf] + (32 * cb + r) * STRIDE) + h * HALF;
@@ -138,26 +158,18 @@ __global__ __launch_bounds__(256, 2) void pq_encode_kernel(const float *__restri
                         }
                     }
             }
-            // the 32 lanes of a half-wave hold 32 candidates of the same row: butterfly to the minimum
+            // The 32 lanes of a half-wave hold 32 candidates of the same row.  First the smallest value
+            // (four cross-lane steps inside the vector ALU, one swizzle across the two 16-lane rows), then,
+            // among the lanes that hold it, the smallest centre number the same way.
             int code = 0;
 #pragma unroll
             for (int f = 0; f < 2; ++f)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    float bv = best[f][v];
-                    int bk = bestk[f][v];
-#pragma unroll
-                    for (int o = 16; o > 0; o >>= 1) {
-                        const float ov = __shfl_xor(bv, o, 64);
-                        const int ok = __shfl_xor(bk, o, 64);
-                        if (ov < bv || (ov == bv && ok < bk)) {
-                            bv = ov;
-                            bk = ok;
-                        }
-                    }
-                    const int other = __shfl_xor(bk, 32, 64);  // the same element of the other half-wave
-                    const int rr = 8 * (v / 4) + (v % 4);      // row of the h = 0 lanes; h = 1: rr + 4
-                    const int k0 = h == 0 ? bk : other, k1 = h == 0 ? other : bk;
+                    const float mn = half_min_f32(best[f][v]);
+                    const int kk = half_min_i32(best[f][v] == mn ? bestk[f][v] : 0x7FFFFFFF);
+                    const int k0 = __builtin_amdgcn_readlane(kk, 0), k1 = __builtin_amdgcn_readlane(kk, 32);
+                    const int rr = 8 * (v / 4) + (v % 4);      // row of lanes 0..31 (h = 0); lanes 32..63: rr + 4
                     if (lane == 32 * f + rr) code = k0;
                     if (lane == 32 * f + rr + 4) code = k1;
                 }
