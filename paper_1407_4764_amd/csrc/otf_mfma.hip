@@ -64,11 +64,14 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__res
     // tile is ordered when the loads of its tile j - 3 begin, by thread 0, and the returned value is
     // written to the ring two steps later, right after the wait for the loads that were issued
     // behind the atomic, so that nobody ever waits for the atomic itself.
+    // (A short scan -- fewer than 8 tiles per workgroup, e.g. the sample -- deals the tiles round-robin
+    // instead: claiming three at a time would leave most workgroups without any.)
+    const bool dynamic = ntiles >= 8LL * gridDim.x;
     if (tid == 0) {
-        const uint32_t c = atomicAdd(tile_ctr, 3u);
-        s_tile[0] = c;
-        s_tile[1] = c + 1u;
-        s_tile[2] = c + 2u;
+        const uint32_t c = dynamic ? atomicAdd(tile_ctr, 3u) : 0u;
+        s_tile[0] = dynamic ? c : blockIdx.x;
+        s_tile[1] = dynamic ? c + 1u : blockIdx.x + gridDim.x;
+        s_tile[2] = dynamic ? c + 2u : blockIdx.x + 2u * gridDim.x;
     }
     __syncthreads();
     if ((long long)s_tile[0] >= ntiles) return;   // uniform
@@ -111,7 +114,7 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__res
     // before the first load of a step: when the step starts the block's tile lj, order tile lj + 3
     auto begin_step = [&](uint32_t &pend, bool &has_pend, uint32_t &pend_slot) {
         if (lcount == 0) {                           // uniform
-            if (tid == 0) pend = atomicAdd(tile_ctr, 1u);
+            if (tid == 0) pend = dynamic ? atomicAdd(tile_ctr, 1u) : blockIdx.x + (lj + 3u) * gridDim.x;
             has_pend = true;
             pend_slot = (lj + 3u) & 7u;
         }
