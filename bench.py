@@ -33,10 +33,10 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the scoring kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # scaled by the same counters on a plain copy of known size (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).
 MEASURED_TRAFFIC_BYTES = {          # read + written, profiles/traffic_counters.md
-    "dense": 8.198e9 + 4.2e6,
-    "pq": 2.585e9 + 0.2e6,
-    "binary": 12.825e9 + 0.2e6,
-    "multiquery": 20.480e9 + 15.2e6,
+    "dense": 8.196e9 + 5.2e6,
+    "pq": 2.589e9 + 0.5e6,
+    "binary": 12.829e9 + 1.8e6,
+    "multiquery": 20.480e9 + 16.5e6,
 }
 
 WORKLOADS = {
