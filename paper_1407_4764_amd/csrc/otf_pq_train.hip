@@ -3,12 +3,12 @@
 // of the K = 256 cluster centres of that sub-block's own vocabulary, the centres having been learned
 // from a training set).
 //
-// Nearest centre of sub-vector x among c_0..c_255: argmin_k ||c_k||^2 - 2 <x, c_k> (the term ||x||^2
-// is common to all k), the lowest k among equals.  The inner products of 32 rows with 32 centres
-// are one v_mfma_f32_32x32x2_f32 chain of dsub/2 steps, so an encoding pass is an
-// N x 256 x dsub product per sub-block on the matrix cores, and what remains for the vector ALU
-// is the argmin: a running minimum per lane over the 8 blocks of 32 centres, then one reduction
-// over the 32 lanes that hold the candidates of a row.
+// Nearest centre of sub-vector x among c_0..c_255: argmin_k ||x||^2/2 - <x, c_k> + ||c_k||^2/2, the lowest k
+// among equals.  For 32 rows and 32 centres that is one v_mfma_f32_32x32x2_f32 chain of dsub/2 + 1
+// steps (the last step adds the two norms), so an encoding pass is an N x 256 x (dsub + 2) product
+// per sub-block on the matrix cores, and what remains for the vector ALU is the argmin: a running
+// minimum per lane over the 8 blocks of 32 centres, then one reduction over the 32 lanes that hold
+// the candidates of a row.
 #include <algorithm>
 
 #include "otf_internal.h"
@@ -24,13 +24,6 @@ constexpr int kPqK = 256;
 template <int CTRL>
 __device__ __forceinline__ int dpp_i32(int v) {
     return __builtin_amdgcn_mov_dpp(v, CTRL, 0xF, 0xF, true);
-}
-__device__ __forceinline__ float half_min_f32(float v) {
-    v = fminf(v, __int_as_float(dpp_i32<0xB1>(__float_as_int(v))));    // quad_perm [1,0,3,2]: lane ^ 1
-    v = fminf(v, __int_as_float(dpp_i32<0x4E>(__float_as_int(v))));    // quad_perm [2,3,0,1]: lane ^ 2
-    v = fminf(v, __int_as_float(dpp_i32<0x141>(__float_as_int(v))));   // row_half_mirror: lane i <-> 7 - i of each 8
-    v = fminf(v, __int_as_float(dpp_i32<0x140>(__float_as_int(v))));   // row_mirror: lane i <-> 15 - i of each 16
-    return fminf(v, __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F)));   // lane ^ 16
 }
 __device__ __forceinline__ int half_min_i32(int v) {
     v = min(v, dpp_i32<0xB1>(v));
@@ -58,9 +51,9 @@ __global__ __launch_bounds__(256) void pq_centre_norms_kernel(const float *__res
 // centre r of a block of 32 (operand B), the components h * dsub/2 .. (h+1) * dsub/2 - 1: A and B
 // only have to agree on which component goes into which K slot.
 template <int DSUB>
-__global__ __launch_bounds__(256, 2) void pq_encode_kernel(const float *__restrict__ X, long long N, long long ldx,
+__global__ __launch_bounds__(256, 3) void pq_encode_kernel(const float *__restrict__ X, long long N, long long ldx,
                                                            const float *__restrict__ codebooks, const float *__restrict__ norms,
-                                                           int M, uint8_t *__restrict__ codes) {
+                                                           int M, int mr, uint8_t *__restrict__ codes) {
     constexpr int HALF = DSUB / 2;                         // components per lane = MFMA steps per chain
     constexpr int STRIDE = DSUB * 4 + (DSUB == 4 ? 32 : 16);   // bytes per centre in shared memory (see above)
     constexpr int VEC = DSUB * 4 / 16;                     // 16-byte pieces per centre
@@ -84,7 +77,13 @@ __global__ __launch_bounds__(256, 2) void pq_encode_kernel(const float *__restri
         ns[buf][tid] = nstage;
     };
 
-    for (long long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    // Work unit = (tile of 256 rows, range of `mr` sub-blocks): the codes of different sub-blocks are
+    // independent, and units a fraction of a tile long let the last round of the grid end together
+    // (whole tiles: 5.09 tiles per workgroup slot at 1M rows means six rounds for five rounds' work).
+    const int ranges = (M + mr - 1) / mr;
+    for (long long unit = blockIdx.x; unit < ntiles * ranges; unit += gridDim.x) {
+        const long long tile = unit / ranges;
+        const int m_begin = (int)(unit % ranges) * mr, m_end = m_begin + mr < M ? m_begin + mr : M;
         const long long row0 = tile * 256 + (long long)wave * 64;
         const float *xrow[2];
 #pragma unroll
@@ -100,43 +99,53 @@ __global__ __launch_bounds__(256, 2) void pq_encode_kernel(const float *__restri
 #pragma unroll
         for (int f = 0; f < 2; ++f)
 #pragma unroll
-            for (int s = 0; s < HALF; ++s) anext[f][s] = xrow[f][s];
-        __syncthreads();                                   // the previous tile is done with shared memory
-        load_c(0);
-        store_c(0);
+            for (int s = 0; s < HALF; ++s) anext[f][s] = xrow[f][(size_t)m_begin * DSUB + s];
+        __syncthreads();                                   // the previous unit is done with shared memory
+        load_c(m_begin);
+        store_c(m_begin & 1);
         __syncthreads();
-        for (int m = 0; m < M; ++m) {
+        for (int m = m_begin; m < m_end; ++m) {
             const int buf = m & 1;
-            if (m + 1 < M) load_c(m + 1);                  // uniform; in flight during the matrix instructions
-            float a[2][HALF];
+            if (m + 1 < m_end) load_c(m + 1);              // uniform; in flight during the matrix instructions
+            // Operand A carries the negated components, and one more K step carries the two norms:
+            // its slot of the h = 0 lanes multiplies ||x||^2 / 2 by 1, that of the h = 1 lanes 1 by
+            // ||c||^2 / 2.  The accumulators then hold half the squared distances themselves.
+            float a[2][HALF], ax[2];
 #pragma unroll
-            for (int f = 0; f < 2; ++f)
+            for (int f = 0; f < 2; ++f) {
+                float ss = 0.f;
 #pragma unroll
-                for (int s = 0; s < HALF; ++s) a[f][s] = anext[f][s];
+                for (int s = 0; s < HALF; ++s) {
+                    const float t = anext[f][s];
+                    a[f][s] = -t;
+                    ss = fmaf(t, t, ss);
+                }
+                const float other = __shfl_xor(ss, 32, 64);    // the other half of the row's components
+                ax[f] = h == 0 ? 0.5f * (ss + other) : 1.0f;
+            }
             {                                              // the next sub-block's components (the last one re-reads)
-                const int mn = m + 1 < M ? m + 1 : m;
+                const int mn = m + 1 < m_end ? m + 1 : m;
 #pragma unroll
                 for (int f = 0; f < 2; ++f)
 #pragma unroll
                     for (int s = 0; s < HALF; ++s) anext[f][s] = xrow[f][(size_t)mn * DSUB + s];
             }
 
-            float best[2][16];
-            int bestk[2][16];
+            // Running minimum per lane over the 8 blocks of 32 centres, two ALU instructions per value:
+            // the block number replaces the three lowest mantissa bits of the (non-negative) value and
+            // the minimum is taken on the bit patterns, so the lower block wins among equal values.
+            int best[2][16];
 #pragma unroll
             for (int f = 0; f < 2; ++f)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    best[f][v] = __builtin_inff();
-                    bestk[f][v] = 0;
-                }
-#pragma unroll 2
+                for (int v = 0; v < 16; ++v) best[f][v] = 0x7FFFFFFF;
+#pragma unroll 1
             for (int cb = 0; cb < kPqK / 32; ++cb) {
                 float b[HALF];
                 const float *bp = reinterpret_cast<const float *>(cs[buf] + (32 * cb + r) * STRIDE) + h * HALF;
 #pragma unroll
                 for (int s = 0; s < HALF; ++s) b[s] = bp[s];
-                const float cn = ns[buf][32 * cb + r];
+                const float bx = h == 0 ? 1.0f : 0.5f * ns[buf][32 * cb + r];
                 float16v acc[2];
 #pragma unroll
                 for (int f = 0; f < 2; ++f)
@@ -146,35 +155,32 @@ __global__ __launch_bounds__(256, 2) void pq_encode_kernel(const float *__restri
                 for (int s = 0; s < HALF; ++s)
 #pragma unroll
                     for (int f = 0; f < 2; ++f) acc[f] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[f][s], b[s], acc[f], 0, 0, 0);
+#pragma unroll
+                for (int f = 0; f < 2; ++f) acc[f] = __builtin_amdgcn_mfma_f32_32x32x2f32(ax[f], bx, acc[f], 0, 0, 0);
                 // accumulator element v of lane (r, h): row 8 (v / 4) + 4 h + v % 4 of the half, centre 32 cb + r
 #pragma unroll
                 for (int f = 0; f < 2; ++f)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const float val = fmaf(-2.f, acc[f][v], cn);
-                        if (val < best[f][v]) {                // strict: the lower centre keeps a tie
-                            best[f][v] = val;
-                            bestk[f][v] = 32 * cb + r;
-                        }
-                    }
+                    for (int v = 0; v < 16; ++v) best[f][v] = min(best[f][v], (__float_as_int(acc[f][v]) & ~7) | cb);
             }
-            // The 32 lanes of a half-wave hold 32 candidates of the same row.  First the smallest value
-            // (four cross-lane steps inside the vector ALU, one swizzle across the two 16-lane rows), then,
-            // among the lanes that hold it, the smallest centre number the same way.
+            // The 32 lanes of a half-wave hold 32 candidates of the same row: minimum of the keys (four
+            // cross-lane steps inside the vector ALU, one swizzle across the two 16-lane rows); it names
+            // the block, and the lowest lane that holds it names the centre inside the block.
             int code = 0;
 #pragma unroll
             for (int f = 0; f < 2; ++f)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const float mn = half_min_f32(best[f][v]);
-                    const int kk = half_min_i32(best[f][v] == mn ? bestk[f][v] : 0x7FFFFFFF);
-                    const int k0 = __builtin_amdgcn_readlane(kk, 0), k1 = __builtin_amdgcn_readlane(kk, 32);
+                    const int kmin = half_min_i32(best[f][v]);
+                    const unsigned long long vote = __ballot(best[f][v] == kmin);
+                    const int k0 = 32 * (__builtin_amdgcn_readlane(kmin, 0) & 7) + __builtin_ctz((uint32_t)vote);
+                    const int k1 = 32 * (__builtin_amdgcn_readlane(kmin, 32) & 7) + __builtin_ctz((uint32_t)(vote >> 32));
                     const int rr = 8 * (v / 4) + (v % 4);      // row of lanes 0..31 (h = 0); lanes 32..63: rr + 4
                     if (lane == 32 * f + rr) code = k0;
                     if (lane == 32 * f + rr + 4) code = k1;
                 }
             packed |= (uint32_t)code << (8 * (m & 3));
-            if ((m & 3) == 3 || m == M - 1) {              // uniform
+            if ((m & 3) == 3 || m == m_end - 1) {          // uniform (ranges begin at multiples of 4)
                 if (myrow < N) {
                     uint8_t *dst = codes + (size_t)myrow * M + (m & ~3);
                     if ((m & 3) == 3) *reinterpret_cast<uint32_t *>(dst) = packed;
@@ -183,7 +189,7 @@ __global__ __launch_bounds__(256, 2) void pq_encode_kernel(const float *__restri
                 }
                 packed = 0u;
             }
-            if (m + 1 < M) store_c(buf ^ 1);               // last read of that buffer: sub-block m - 1, a barrier ago
+            if (m + 1 < m_end) store_c(buf ^ 1);           // last read of that buffer: sub-block m - 1, a barrier ago
             __syncthreads();
         }
     }
@@ -277,11 +283,13 @@ hipError_t launch_pq_encode(const float *X, int64_t N, int64_t ldx, const float 
     PqTrainWs w = pq_train_ws(ws, M, dsub);
     pq_centre_norms_kernel<<<(M * kPqK + 255) / 256, 256, 0, s>>>(codebooks, M, dsub, w.norms);
     const int64_t ntiles = (N + 255) / 256;
-    const int grid = (int)std::min<int64_t>(ntiles, (int64_t)device_cu_count() * 2);
+    const int mr = std::min(M, std::max(4, tune_int("OTF_PQENC_RANGE", 16) & ~3));   // sub-blocks per work unit, a multiple of 4
+    const int64_t units = ntiles * ((M + mr - 1) / mr);
+    const int grid = (int)std::min<int64_t>(units, (int64_t)device_cu_count() * tune_int("OTF_PQENC_BLOCKS_PER_CU", 3));
     switch (dsub) {
-        case 4: pq_encode_kernel<4><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, codes); break;
-        case 8: pq_encode_kernel<8><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, codes); break;
-        case 16: pq_encode_kernel<16><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, codes); break;
+        case 4: pq_encode_kernel<4><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, mr, codes); break;
+        case 8: pq_encode_kernel<8><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, mr, codes); break;
+        case 16: pq_encode_kernel<16><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, mr, codes); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
