@@ -69,10 +69,10 @@ SelectWs sample_select_ws(void *ws, const WsLayout &L) {
 }
 
 // Filtered scan or full selection?  The filtered scan needs a sample large enough to place the
-// threshold (>= 16 groups) and a list that holds ~4x the requested rows.
+// threshold (>= 8 groups) and a list that holds ~4x the requested rows.
 static bool filter_eligible(int64_t N, int32_t k, const float *all_scores) {
     if (all_scores || k > kFilterMaxK) return false;
-    if (sample_rows(N) < 16 * kSampleGroup) return false;
+    if (sample_rows(N) < 8 * kSampleGroup) return false;
     return tune_int("OTF_RANK_PATH", 0) != 1;      // 1 forces the full selection (testing, comparison)
 }
 

@@ -14,7 +14,7 @@ constexpr int kSelBlocks = 256; // blocks per classifier in the selection passes
 // Filtered scans: a strided sample of the store (every kSampleStride-th group of kSampleGroup rows)
 // is scored first; the threshold is set so that about kFilterExpect rows of the full store pass it.
 constexpr int kSampleGroup = 1024;
-constexpr int kSampleStride = 64;
+constexpr int kSampleStride = 128;
 constexpr int kFilterExpect = 4096;
 constexpr int kFilterMaxK = 1024;
 
