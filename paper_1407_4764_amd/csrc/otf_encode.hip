@@ -79,27 +79,35 @@ __global__ __launch_bounds__(kFrameThreads) void tight_frame_kernel(const float 
 // -------------------------------------------------------------------------------------------
 // Codes.  2 m n flop per descriptor against 4 m + n/8 bytes: at m = 128, n = 2048 that is 680
 // flop per byte, so the kernel is bound by the fp32 rate of the matrix cores and is organised to
-// keep them issuing: one workgroup of four waves per compute unit, one wave per SIMD.
+// keep them issuing: one workgroup of eight waves per compute unit, two waves per SIMD.
 //
-//   * A wave owns 64 descriptors for the whole of U.  Their values stay in registers for that
-//     time, already in the operand layout of v_mfma_f32_32x32x2_f32 (lane (r, h) = descriptor r
-//     of a 32-row half, K slots 64 h .. 64 h + 63: operands A and B only have to agree on which K
-//     goes into which slot, so each lane takes a contiguous half row instead of every other
-//     element).
+//   * A wave owns 32 descriptors for the whole of U.  Their values stay in registers for that
+//     time, already in the operand layout of v_mfma_f32_32x32x2_f32 (lane (r, h) = descriptor r,
+//     K slots 64 h .. 64 h + 63: operands A and B only have to agree on which K goes into which
+//     slot, so each lane takes a contiguous half row instead of every other element).
 //   * U is streamed from L2 in blocks of 32 frame rows (= 32 code bits) through shared memory,
 //     double-buffered, one barrier per block; rows padded by 16 bytes so that the 16-byte
 //     operand reads of 8 consecutive lanes cover all 32 banks.
-//   * Per block and 32-row half the signs come out as 16 wave votes (v_cmp + the vote mask): lanes
-//     0..31 of vote v are the 32 bits of one output word, lanes 32..63 those of another.  The words
-//     are parked in lane (block mod 64) of one register per descriptor, and once
-//     64 blocks are done every descriptor's 256 bytes leave in one coalesced store.
-constexpr int kEncRowsPerWave = 64;
-constexpr int kEncRows = 4 * kEncRowsPerWave;   // descriptors per workgroup pass
+//   * Per block the signs come out as 16 wave votes (v_cmp + the vote mask): lanes 0..31 of vote v
+//     are the 32 bits of one output word, lanes 32..63 those of another.  The words are parked in
+//     lane (block mod 64) of one register per descriptor, and once 64 blocks are done every
+//     descriptor's 256 bytes leave in one coalesced store.
+//   * A wave issues in order, so its votes, stores and barrier waits stall its own matrix
+//     instructions; the second wave of the SIMD fills those gaps (74 % -> 78 % of peak against four
+//     waves of 64 descriptors with the whole register file each).
+constexpr int kEncRows = 256;                   // descriptors per workgroup pass
 constexpr int kEncK = 128;                      // K slots (m is padded with zeros up to this)
 constexpr int kEncStride = kEncK * 4 + 16;      // bytes per frame row in shared memory
 
-__global__ __launch_bounds__(256) void binarize_kernel(const float *__restrict__ phi, long long N, int m, long long ld,
-                                                       const float *__restrict__ U, int n, uint32_t *__restrict__ bits) {
+// F = 32-row halves per wave (2: four waves, one per SIMD with the whole register file; 1: eight waves, two per
+// SIMD, so that one wave's sign epilogue and barrier waits hide behind the other's matrix instructions)
+template <int F>
+__global__ __launch_bounds__(1024 / F / 2) void binarize_kernel(const float *__restrict__ phi, long long N, int m,
+                                                                long long ld, const float *__restrict__ U, int n,
+                                                                uint32_t *__restrict__ bits) {
+    constexpr int kEncRowsPerWave = 32 * F;
+    constexpr int THREADS = 1024 / F / 2;        // 256 or 512
+    constexpr int UL = 1024 / THREADS;           // 16-byte pieces of a block of U per thread
     __shared__ __attribute__((aligned(16))) uint8_t us[2][32 * kEncStride];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 31, h = lane >> 5;
@@ -108,19 +116,19 @@ __global__ __launch_bounds__(256) void binarize_kernel(const float *__restrict__
     const long long ntiles = (N + kEncRows - 1) / kEncRows;
 
     // global -> registers -> shared memory for one block of U: 32 rows x 512 bytes, 4 x 16 bytes per thread
-    f32x4 ustage[4];
+    f32x4 ustage[UL];
     auto load_u = [&](int cb) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int id = tid + 256 * u, row = id >> 5, c16 = id & 31;
+        for (int u = 0; u < UL; ++u) {
+            const int id = tid + THREADS * u, row = id >> 5, c16 = id & 31;
             ustage[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
             if (4 * c16 < m) ustage[u] = *reinterpret_cast<const f32x4 *>(U + (size_t)(32 * cb + row) * m + 4 * c16);
         }
     };
     auto store_u = [&](int buf) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int id = tid + 256 * u, row = id >> 5, c16 = id & 31;
+        for (int u = 0; u < UL; ++u) {
+            const int id = tid + THREADS * u, row = id >> 5, c16 = id & 31;
             *reinterpret_cast<f32x4 *>(us[buf] + row * kEncStride + c16 * 16) = ustage[u];
         }
     };
@@ -128,9 +136,9 @@ __global__ __launch_bounds__(256) void binarize_kernel(const float *__restrict__
     for (long long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const long long row0 = tile * kEncRows + (long long)wave * kEncRowsPerWave;
         // operand A: descriptor values of this lane's two rows, K slots 64 h + s
-        float a[2][64];
+        float a[F][64];
 #pragma unroll
-        for (int f = 0; f < 2; ++f) {
+        for (int f = 0; f < F; ++f) {
             long long row = row0 + 32 * f + r;
             if (row > N - 1) row = N - 1;                    // computed, never stored
             const float *p = phi + (size_t)row * ld + 64 * h;
@@ -152,9 +160,9 @@ __global__ __launch_bounds__(256) void binarize_kernel(const float *__restrict__
         for (int cb = 0; cb < nblocks; ++cb) {
             const int buf = cb & 1;
             if (cb + 1 < nblocks) load_u(cb + 1);            // uniform; in flight during the matrix instructions
-            float16v acc[2];
+            float16v acc[F];
 #pragma unroll
-            for (int f = 0; f < 2; ++f)
+            for (int f = 0; f < F; ++f)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[f][v] = 0.f;
             const uint8_t *brow = us[buf] + r * kEncStride + h * 256;
@@ -166,7 +174,7 @@ __global__ __launch_bounds__(256) void binarize_kernel(const float *__restrict__
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
-                    for (int f = 0; f < 2; ++f)
+                    for (int f = 0; f < F; ++f)
                         acc[f] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[f][4 * q + j], b[j], acc[f], 0, 0, 0);
                 b = bn;
             }
@@ -174,7 +182,7 @@ __global__ __launch_bounds__(256) void binarize_kernel(const float *__restrict__
             // half, code bit 32 cb + r
             const bool mine = lane == (cb & 63);             // the lane that keeps this block's words
 #pragma unroll
-            for (int f = 0; f < 2; ++f)
+            for (int f = 0; f < F; ++f)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const unsigned long long vote = __ballot(acc[f][v] > 0.f);
@@ -208,7 +216,10 @@ hipError_t launch_binarize(const float *phi, int64_t N, int m, int64_t ld, const
     if (m > kEncK || m % 4 || n % 32) return hipErrorInvalidValue;
     const int64_t ntiles = (N + kEncRows - 1) / kEncRows;
     const int grid = (int)std::min<int64_t>(ntiles, device_cu_count());
-    binarize_kernel<<<grid, 256, 0, s>>>(phi, (long long)N, m, (long long)ld, U, n, bits);
+    if (tune_int("OTF_BINARIZE_WAVES", 8) == 4)
+        binarize_kernel<2><<<grid, 256, 0, s>>>(phi, (long long)N, m, (long long)ld, U, n, bits);
+    else
+        binarize_kernel<1><<<grid, 512, 0, s>>>(phi, (long long)N, m, (long long)ld, U, n, bits);
     return hipGetLastError();
 }
 
