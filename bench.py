@@ -315,7 +315,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (each GPU would rank its own "
-                 "row shard; see DESIGN.md). Run with --gpus 1.")
+                 "row shard and the k-entry lists would be merged). Run with --gpus 1.")
     import torch
     from paper_1407_4764_amd import binding, synth
     if not torch.cuda.is_available():
