@@ -194,8 +194,8 @@ int otf_binarize(const float *phi, int64_t N, int32_t m, int64_t ld_phi, const f
 
 /*
  * Product-quantisation encoder and vocabulary training (paper Sec. 3, "Product quantization (PQ)":
- * each sub-block is "encoded using a separate vocabulary of cluster centres pre-learned from a
- * training set").  The codes are the rows otf_rank_pq scans.
+ * every sub-block has a vocabulary of its own, learned beforehand on training features, and is
+ * stored as the index of one of its centres).  The codes are the rows otf_rank_pq scans.
  *
  * otf_pq_encode:  codes[i][m] = argmin_k || X[i][m*dsub .. (m+1)*dsub) - codebooks[m][k] ||^2, the
  *   lowest k among equal distances.  Evaluated as argmin_k ||c_k||^2 - 2 <x, c_k> in fp32 on the matrix

@@ -3,8 +3,8 @@ INFRASTRUCTURE ONLY (plain numpy, float64).
 
 Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this module.
 
-Paper Sec. 3, "Product quantization (PQ)": the feature is split into sub-blocks, "each of which is
-encoded using a separate vocabulary of cluster centres pre-learned from a training set".  Encoding
+Paper Sec. 3, "Product quantization (PQ)": the feature is split into sub-blocks and every sub-block
+has a vocabulary of centres of its own, learned beforehand on training features.  Encoding
 a sub-block means replacing it by the index of its nearest centre (squared Euclidean distance;
 equal distances go to the lower index).  The paper does not say how the centres are learned; the
 method it cites for PQ uses k-means, so the oracle performs Lloyd iterations from centres handed

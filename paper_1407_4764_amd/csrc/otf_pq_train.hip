@@ -10,6 +10,7 @@
 // minimum per lane over the 8 blocks of 32 centres, then one reduction over the 32 lanes that hold
 // the candidates of a row.
 #include <algorithm>
+#include <type_traits>
 
 #include "otf_internal.h"
 
@@ -196,46 +197,201 @@ __global__ __launch_bounds__(256, 3) void pq_encode_kernel(const float *__restri
 }
 
 // Lloyd iteration, second half: per-centre sums of the assigned sub-vectors, counts, and the
-// distortion.  One workgroup per (sub-block, slice of rows); sums in shared memory, merged into
-// global memory by atomics at the end.
+// distortion.
+//
+// A floating-point add into shared memory by atomic is executed lane by lane on this chip (about
+// 190 cycles per wave instruction, against 8 for a plain read and write), so the sums are kept free
+// of atomics by ownership: a wave owns 16 consecutive feature dimensions (16/DSUB whole sub-blocks)
+// and their 16 KB of sums outright, and one wave instruction adds four rows x 16 dimensions with a
+// plain read-add-write.  The only hazard left is two of the four rows carrying the same code in the
+// same sub-block (about 2 % of the steps for well-spread codes): the four rows' codes are compared
+// and such a step is taken row by row instead.
+//
+// A workgroup is two waves, i.e. the 32 dimensions of one 128-byte line per row; grid = (runs of 32
+// dimensions, slices of rows).  The workgroup reads its rows in whole lines (eight lanes per row)
+// and hands each wave its half through a double-buffered stage in shared memory: 64-byte reads
+// straight from the waves fetched nearly three times the bytes of X from HBM.  Every wave merges
+// its sums into global memory with atomics at the end.
+template <int GW>
+__device__ __forceinline__ bool code_words_clash(uint32_t a, uint32_t b) {
+    const uint32_t x = a ^ b;  // a byte of x is zero where the two rows carry the same code
+    if (GW == 1) return x == 0u;
+    if (GW == 2) return (x & 0xffu) == 0u || (x & 0xff00u) == 0u;
+    return ((x - 0x01010101u) & ~x & 0x80808080u) != 0u;
+}
+
 template <int DSUB>
-__global__ __launch_bounds__(256) void pq_accumulate_kernel(const float *__restrict__ X, long long N, long long ldx,
+__global__ __launch_bounds__(128) void pq_accumulate_kernel(const float *__restrict__ X, long long N, long long ldx,
                                                             const float *__restrict__ codebooks,
                                                             const uint8_t *__restrict__ codes, int M, float *sums,
                                                             uint32_t *counts, double *distortion) {
-    __shared__ float lsum[kPqK * DSUB];
-    __shared__ uint32_t lcnt[kPqK];
-    __shared__ double ldist[4];
-    const int m = blockIdx.y, tid = threadIdx.x;
-    for (int i = tid; i < kPqK * DSUB; i += 256) lsum[i] = 0.f;
-    for (int i = tid; i < kPqK; i += 256) lcnt[i] = 0u;
-    __syncthreads();
-    const long long per = (N + gridDim.x - 1) / gridDim.x;
-    const long long begin = per * blockIdx.x, end = begin + per < N ? begin + per : N;
+    constexpr int GW = 16 / DSUB;  // sub-blocks per wave
+    constexpr int STEPS = 16;      // steps of four rows per batch: 64 rows, one row's codes per lane
+    constexpr int BATCH = 4 * STEPS;
+    __shared__ float lsum[2][GW * kPqK * DSUB];
+    __shared__ uint32_t lcnt[2][GW * kPqK];
+    __shared__ __align__(16) float stage[2][BATCH][32];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int col0 = (blockIdx.x * 2 + wv) * 16;
+    // M * DSUB is a multiple of 16: a wave's dimensions exist all or not at all.  A wave without
+    // any still takes part in the staging and the barriers.
+    const bool live = col0 < M * DSUB;
+    const int m0 = live ? col0 / DSUB : 0;
+    float *ls = lsum[wv];
+    uint32_t *lc = lcnt[wv];
+    for (int i = lane; i < GW * kPqK * DSUB; i += 64) ls[i] = 0.f;
+    for (int i = lane; i < GW * kPqK; i += 64) lc[i] = 0u;
+    const int r4 = lane >> 4, c = lane & 15, g = c / DSUB, j = c % DSUB;
+    const long long per = (N + gridDim.y - 1) / gridDim.y;
+    const long long begin = per * blockIdx.y, end = begin + per < N ? begin + per : N;
+    const int rows = end > begin ? (int)(end - begin) : 0;
+    const int batches = (rows + BATCH - 1) / BATCH;
+    // staging: thread = (row within 16, four of the 32 dimensions); four rows per thread and batch
+    const int srow = tid >> 3, scol = 4 * (tid & 7);
+    const bool scol_live = blockIdx.x * 32 + scol < M * DSUB;
+    const float *xstage = X + begin * ldx + (size_t)blockIdx.x * 32 + scol;
+    float4 xr[4];
+    // Rows past the end of the slice are read as its last row (in bounds) and left out by `valid`.
+    auto load_batch = [&](int n) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            int r = n * BATCH + srow + 16 * q;
+            r = r < rows ? r : rows - 1;
+            xr[q] = scol_live ? *reinterpret_cast<const float4 *>(xstage + (long long)r * ldx) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto store_batch = [&](int buf) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<float4 *>(&stage[buf][srow + 16 * q][scol]) = xr[q];
+    };
+    auto load_codes = [&](int n) -> uint32_t {
+        int r = n * BATCH + lane;
+        r = r < rows ? r : rows - 1;
+        const uint8_t *p = codes + (size_t)(begin + r) * M + m0;
+        return GW == 1 ? (uint32_t)*p : GW == 2 ? (uint32_t)*reinterpret_cast<const uint16_t *>(p)
+                                                : *reinterpret_cast<const uint32_t *>(p);
+    };
+    const float *cb = codebooks + (size_t)(m0 + g) * kPqK * DSUB + j;
+    float *lmine = ls + g * kPqK * DSUB + j;
+    uint32_t *cmine = lc + g * kPqK;
     double dist = 0.0;
-    for (long long i = begin + tid; i < end; i += 256) {
-        const int k = codes[(size_t)i * M + m];
-        const float *x = X + (size_t)i * ldx + (size_t)m * DSUB;
-        const float *c = codebooks + ((size_t)m * kPqK + k) * DSUB;
+    uint32_t kv = 0u;
+
+    // this lane's code in step s of a batch whose rows' codes are held one per lane
+    auto lane_code = [&](uint32_t codes_of_rows, int s) -> int {
+        const uint32_t kw = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (4 * s + r4), (int)codes_of_rows);
+        return (int)((kw >> (8 * g)) & 255u);
+    };
+    // The assigned centres' values, for the distortion: gathers, asked for one batch ahead of their
+    // use.  Every code is that of a row of the slice, so they are in bounds.
+    float cv[STEPS];
+    auto gather_centres = [&](uint32_t codes_of_rows, float (&out)[STEPS]) {
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) out[s] = cb[lane_code(codes_of_rows, s) * DSUB];
+    };
+
+    auto update = [&](int n, auto full) {
+        const float *xs = &stage[n & 1][r4][16 * wv + c];
+        // Rows that hold one code twice: within a step (its four rows sit in the four lanes of a
+        // quad of `kv`), and within a pair of steps (an octet of lanes), for all steps at once.
+        const uint32_t q1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)kv, 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
+        const uint32_t q2 = (uint32_t)__builtin_amdgcn_mov_dpp((int)kv, 0x4E, 0xF, 0xF, true);  // quad_perm [2,3,0,1]
+        const uint32_t q3 = (uint32_t)__builtin_amdgcn_mov_dpp((int)kv, 0x1B, 0xF, 0xF, true);  // quad_perm [3,2,1,0]
+        const uint32_t h0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)kv, 0x141, 0xF, 0xF, true);  // row_half_mirror: the other quad
+        const uint32_t h1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)h0, 0xB1, 0xF, 0xF, true);
+        const uint32_t h2 = (uint32_t)__builtin_amdgcn_mov_dpp((int)h0, 0x4E, 0xF, 0xF, true);
+        const uint32_t h3 = (uint32_t)__builtin_amdgcn_mov_dpp((int)h0, 0x1B, 0xF, 0xF, true);
+        const bool in_step = code_words_clash<GW>(kv, q1) || code_words_clash<GW>(kv, q2) || code_words_clash<GW>(kv, q3);
+        const bool in_pair = in_step || code_words_clash<GW>(kv, h0) || code_words_clash<GW>(kv, h1) ||
+                             code_words_clash<GW>(kv, h2) || code_words_clash<GW>(kv, h3);
+        const unsigned long long step_clashes = __ballot(in_step), pair_clashes = __ballot(in_pair);
+        // this lane's code in each step and the rows' values from the stage
+        int k[STEPS];
+        float x[STEPS];
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            k[s] = lane_code(kv, s);
+            x[s] = xs[4 * s * 32];
+        }
+        auto valid = [&](int s) { return full.value || n * BATCH + 4 * s + r4 < rows; };
+        auto one_step = [&](int s) {
+            float *dst = lmine + k[s] * DSUB;
+            if (((step_clashes >> (4 * s)) & 0xFull) == 0ull) {
+                if (valid(s)) *dst = *dst + x[s];
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if (valid(s) && r4 == r) *dst = *dst + x[s];
+                    __builtin_amdgcn_wave_barrier();  // keeps the four row turns apart and in this order
+                }
+            }
+        };
         float d = 0.f;
 #pragma unroll
-        for (int j = 0; j < DSUB; ++j) {
-            const float xv = x[j], t = xv - c[j];
-            d = fmaf(t, t, d);
-            atomicAdd(&lsum[k * DSUB + j], xv);
+        for (int p = 0; p < STEPS / 2; ++p) {
+            const int s0 = 2 * p, s1 = 2 * p + 1;
+            if (((pair_clashes >> (8 * p)) & 0xFFull) == 0ull) {
+                // eight rows, eight different cells per sub-block: the two steps' updates overlap
+                float *d0 = lmine + k[s0] * DSUB, *d1 = lmine + k[s1] * DSUB;
+                const float a0 = *d0, a1 = *d1;
+                if (valid(s0)) *d0 = a0 + x[s0];
+                if (valid(s1)) *d1 = a1 + x[s1];
+            } else {
+                one_step(s0);
+                one_step(s1);
+            }
+#pragma unroll
+            for (int s = s0; s <= s1; ++s) {
+                if (valid(s) && j == 0) atomicAdd(cmine + k[s], 1u);
+                const float t = valid(s) ? x[s] - cv[s] : 0.f;
+                d = fmaf(t, t, d);
+            }
         }
-        atomicAdd(&lcnt[k], 1u);
         dist += (double)d;
+    };
+
+    // Batch n is updated from stage[n & 1] while batch n + 1 moves from registers into the other
+    // half and batch n + 2 is on its way from memory; one barrier per batch.  Codes run two batches
+    // ahead of the updates, the centres' values one.
+    uint32_t kv1 = 0u;
+    if (batches > 0) {
+        load_batch(0);
+        store_batch(0);
+        if (batches > 1) load_batch(1);
+        if (live) {
+            kv = load_codes(0);
+            if (batches > 1) kv1 = load_codes(1);
+            gather_centres(kv, cv);
+        }
     }
+    __syncthreads();
+    for (int n = 0; n < batches; ++n) {
+        if (n + 1 < batches) store_batch((n + 1) & 1);
+        if (n + 2 < batches) load_batch(n + 2);
+        if (live) {
+            uint32_t kv2 = 0u;
+            float cv1[STEPS];
+            if (n + 2 < batches) kv2 = load_codes(n + 2);
+            if (n + 1 < batches) gather_centres(kv1, cv1);
+            if ((n + 1) * BATCH <= rows) update(n, std::true_type{});
+            else update(n, std::false_type{});
+            kv = kv1;
+            kv1 = kv2;
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) cv[s] = cv1[s];
+        }
+        __syncthreads();
+    }
+    if (!live) return;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) dist += __shfl_xor(dist, o, 64);
-    if ((tid & 63) == 0) ldist[tid >> 6] = dist;
-    __syncthreads();
-    for (int i = tid; i < kPqK * DSUB; i += 256)
-        if (lsum[i] != 0.f) atomicAdd(&sums[(size_t)m * kPqK * DSUB + i], lsum[i]);
-    for (int i = tid; i < kPqK; i += 256)
-        if (lcnt[i]) atomicAdd(&counts[(size_t)m * kPqK + i], lcnt[i]);
-    if (tid == 0) atomicAdd(distortion, ldist[0] + ldist[1] + ldist[2] + ldist[3]);
+    for (int i = lane; i < GW * kPqK * DSUB; i += 64) {
+        const float v = ls[i];
+        if (v != 0.f) atomicAdd(&sums[(size_t)m0 * kPqK * DSUB + i], v);
+    }
+    for (int i = lane; i < GW * kPqK; i += 64)
+        if (lc[i]) atomicAdd(&counts[(size_t)m0 * kPqK + i], lc[i]);
+    if (lane == 0) atomicAdd(distortion, dist);
 }
 
 __global__ __launch_bounds__(256) void pq_zero_kernel(float *sums, uint32_t *counts, double *distortion, int M, int dsub) {
@@ -302,13 +458,15 @@ hipError_t launch_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *c
     PqTrainWs w = pq_train_ws(ws, M, dsub);
     const size_t cells = (size_t)M * kPqK * dsub;
     pq_zero_kernel<<<(unsigned)((cells + 255) / 256), 256, 0, s>>>(w.sums, w.counts, w.distortion, M, dsub);
-    int slices = (int)std::min<int64_t>((N + 4095) / 4096, std::max(1, device_cu_count() * 8 / M));
+    const int groups = (M * dsub + 31) / 32;
+    // three workgroups fit a compute unit (50 KB of shared memory each): one full round of them
+    int slices = (int)std::min<int64_t>((N + 4095) / 4096, std::max(1, device_cu_count() * 3 / groups));
     if (slices < 1) slices = 1;
-    dim3 grid(slices, M);
+    dim3 grid(groups, slices);
     switch (dsub) {
-        case 4: pq_accumulate_kernel<4><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, codes, M, w.sums, w.counts, w.distortion); break;
-        case 8: pq_accumulate_kernel<8><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, codes, M, w.sums, w.counts, w.distortion); break;
-        case 16: pq_accumulate_kernel<16><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, codes, M, w.sums, w.counts, w.distortion); break;
+        case 4: pq_accumulate_kernel<4><<<grid, 128, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, codes, M, w.sums, w.counts, w.distortion); break;
+        case 8: pq_accumulate_kernel<8><<<grid, 128, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, codes, M, w.sums, w.counts, w.distortion); break;
+        case 16: pq_accumulate_kernel<16><<<grid, 128, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, codes, M, w.sums, w.counts, w.distortion); break;
         default: return hipErrorInvalidValue;
     }
     pq_move_centres_kernel<<<(unsigned)((cells + 255) / 256), 256, 0, s>>>(codebooks, w.sums, w.counts, M, dsub, w.distortion,

@@ -109,6 +109,27 @@ def test_lloyd_step_matches_the_oracle(N, M, dsub):
     assert np.max(np.abs(got - C_ref)) <= 2e-3 * np.abs(C_ref).max()
 
 
+@pytest.mark.parametrize("N,M,dsub", [(5003, 8, 4), (4999, 16, 8), (5001, 4, 16), (64, 4, 16), (130, 12, 4)])
+def test_lloyd_step_when_many_rows_share_a_code(N, M, dsub):
+    """Rows drawn from three distinct vectors only: nearly every group of rows the kernel adds in
+    one instruction holds the same code several times (the degenerate case of its update step)."""
+    g = torch.Generator().manual_seed(SEED + 6)
+    base, C = _data(3, M, dsub, SEED + 7)
+    pick = torch.randint(0, 3, (N,), generator=g)
+    pick[: min(N, 40)] = 0                                          # and a run of identical rows
+    X = base[pick].contiguous()
+    Cd = C.to(DEV).clone()
+    ws = binding.pq_train_workspace(M, dsub)
+    codes, dist = binding.pq_lloyd_step(X.to(DEV), Cd, ws)
+    torch.cuda.synchronize()
+    codes = codes.cpu().numpy()
+    C_ref, codes_ref, dist_ref = pq.lloyd_step(X.numpy(), C.numpy())
+    np.testing.assert_array_equal(codes, codes_ref)                 # three well-separated candidates: no near-ties
+    got = Cd.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got - C_ref)) <= 1e-5 * np.abs(C_ref).max()
+    np.testing.assert_allclose(float(dist.cpu()[0]), dist_ref, rtol=1e-5)
+
+
 def test_iterations_decrease_the_distortion_and_codes_feed_the_scan(oracle):
     N, M, dsub, k = 30000, 16, 8, 50
     X, C = _data(N, M, dsub, SEED + 4)
