@@ -34,6 +34,29 @@ __device__ __forceinline__ int half_min_i32(int v) {
     return min(v, __builtin_amdgcn_ds_swizzle(v, 0x401F));
 }
 
+// End of a sub-block: `best[f][v]` of lane (r, h) is the smallest key (half the squared distance
+// with the number of the block of 32 centres in its three lowest bits) seen in column r of the
+// blocks for row 8 (v / 4) + 4 h + v % 4 of half f.  The 32 lanes of a half-wave hold 32 candidates
+// of the same row: minimum of the keys (four cross-lane steps inside the vector ALU, one swizzle
+// across the two 16-lane rows); it names the block, and the lowest lane that holds it names the
+// centre inside the block.  Returns the code of row `lane` of the wave's 64 rows.
+__device__ __forceinline__ int code_from_minima(const int (&best)[2][16], int lane) {
+    int code = 0;
+#pragma unroll
+    for (int f = 0; f < 2; ++f)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int kmin = half_min_i32(best[f][v]);
+            const unsigned long long vote = __ballot(best[f][v] == kmin);
+            const int k0 = 32 * (__builtin_amdgcn_readlane(kmin, 0) & 7) + __builtin_ctz((uint32_t)vote);
+            const int k1 = 32 * (__builtin_amdgcn_readlane(kmin, 32) & 7) + __builtin_ctz((uint32_t)(vote >> 32));
+            const int rr = 8 * (v / 4) + (v % 4);      // row of lanes 0..31 (h = 0); lanes 32..63: rr + 4
+            if (lane == 32 * f + rr) code = k0;
+            if (lane == 32 * f + rr + 4) code = k1;
+        }
+    return code;
+}
+
 // norms[m][k] = ||codebooks[m][k]||^2
 __global__ __launch_bounds__(256) void pq_centre_norms_kernel(const float *__restrict__ codebooks, int M, int dsub,
                                                               float *__restrict__ norms) {
@@ -164,22 +187,7 @@ __global__ __launch_bounds__(256, 3) void pq_encode_kernel(const float *__restri
 #pragma unroll
                     for (int v = 0; v < 16; ++v) best[f][v] = min(best[f][v], (__float_as_int(acc[f][v]) & ~7) | cb);
             }
-            // The 32 lanes of a half-wave hold 32 candidates of the same row: minimum of the keys (four
-            // cross-lane steps inside the vector ALU, one swizzle across the two 16-lane rows); it names
-            // the block, and the lowest lane that holds it names the centre inside the block.
-            int code = 0;
-#pragma unroll
-            for (int f = 0; f < 2; ++f)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int kmin = half_min_i32(best[f][v]);
-                    const unsigned long long vote = __ballot(best[f][v] == kmin);
-                    const int k0 = 32 * (__builtin_amdgcn_readlane(kmin, 0) & 7) + __builtin_ctz((uint32_t)vote);
-                    const int k1 = 32 * (__builtin_amdgcn_readlane(kmin, 32) & 7) + __builtin_ctz((uint32_t)(vote >> 32));
-                    const int rr = 8 * (v / 4) + (v % 4);      // row of lanes 0..31 (h = 0); lanes 32..63: rr + 4
-                    if (lane == 32 * f + rr) code = k0;
-                    if (lane == 32 * f + rr + 4) code = k1;
-                }
+            const int code = code_from_minima(best, lane);
             packed |= (uint32_t)code << (8 * (m & 3));
             if ((m & 3) == 3 || m == m_end - 1) {          // uniform (ranges begin at multiples of 4)
                 if (myrow < N) {
@@ -191,6 +199,212 @@ __global__ __launch_bounds__(256, 3) void pq_encode_kernel(const float *__restri
                 packed = 0u;
             }
             if (m + 1 < m_end) store_c(buf ^ 1);           // last read of that buffer: sub-block m - 1, a barrier ago
+            __syncthreads();
+        }
+    }
+}
+
+// dsub = 16 on the bf16 matrix instructions, at fp32 accuracy.
+//
+// Measured on this chip: v_mfma_f32_32x32x2_f32 and the vector ALU do not overlap (a SIMD that
+// alternates eight of them with 192 ALU instructions takes the sum of the two times), whereas
+// v_mfma_f32_32x32x16_bf16 runs beside the ALU and does eight times the multiply-adds in half the
+// cycles.  An fp32 value is the exact sum of three bf16 pieces (8 mantissa bits each, truncating
+// splits), and a product of two pieces is exact in the fp32 accumulator, so <x, c> in fp32 accuracy
+// is the sum of the six piece products of order <= 2: x0c0 + x0c1 + x1c0 + x0c2 + x1c1 + x2c0 (the
+// three left out are below 2^-23 of |x_i c_i|).  One instruction covers all 16 components, so a
+// block of 32 rows x 32 centres takes 6 + 1 instructions of 32 cycles instead of 9 of 64, and the
+// argmin on the vector ALU proceeds meanwhile.  The seventh instruction adds the norms:
+// A = [nx0 nx1 nx2 1 1 1 0 0 | 0...], B = [1 1 1 nc0 nc1 nc2 0 0 | ...] with nx = ||x||^2 / 2 and
+// nc = ||c||^2 / 2 in three pieces each.
+//
+// Shared memory per sub-block: the centres' pieces as [piece][h][centre] x 16 bytes (lane (r, h)
+// reads components 8h .. 8h+7 of centre 32 cb + r: consecutive lanes read consecutive 16 bytes) and
+// two dwords of the norm operand per centre; 26 KB, double-buffered, three workgroups per CU.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float top16(float v) { return __uint_as_float(__float_as_uint(v) & 0xFFFF0000u); }
+
+// The three bf16 pieces of v0 and of v1, as dwords {low half: v0's piece, high half: v1's}.
+__device__ __forceinline__ void split3(float v0, float v1, uint32_t &p0, uint32_t &p1, uint32_t &p2) {
+    const float r0 = v0 - top16(v0), r1 = v1 - top16(v1);   // exact: the low 16 mantissa bits
+    const float s0 = r0 - top16(r0), s1 = r1 - top16(r1);   // exact: at most 8 bits are left
+    p0 = __builtin_amdgcn_perm(__float_as_uint(v1), __float_as_uint(v0), 0x07060302u);
+    p1 = __builtin_amdgcn_perm(__float_as_uint(r1), __float_as_uint(r0), 0x07060302u);
+    p2 = __builtin_amdgcn_perm(__float_as_uint(s1), __float_as_uint(s0), 0x07060302u);
+}
+
+__device__ __forceinline__ float16v mfma_bf16(u32x4 a, u32x4 b, float16v c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// Image of one sub-block's vocabulary as pq_encode16_kernel wants it in shared memory: the three
+// pieces of every centre as [piece][h][slot] x 16 bytes, then two dwords of the norm operand per
+// slot.  Built once per call (the centres do not change during an encoding pass), so the encoder
+// only copies it.
+constexpr int kImg16Pieces = 3 * 2 * kPqK * 16;            // 24576 bytes
+constexpr int kImg16Bytes = kImg16Pieces + kPqK * 8;       // 26624 bytes
+
+__global__ __launch_bounds__(256) void pq_centre_image16_kernel(const float *__restrict__ codebooks, int M,
+                                                                uint8_t *__restrict__ image) {
+    constexpr uint32_t kOne = 0x3F80u;                     // bf16 1.0
+    const int m = blockIdx.x, k = threadIdx.x;
+    if (m >= M) return;
+    const float *c = codebooks + ((size_t)m * kPqK + k) * 16;
+    uint8_t *img = image + (size_t)m * kImg16Bytes;
+    const int slot = k;
+    uint32_t p[3][8];                                      // [piece][pair of components]
+    float nn = 0.f;
+#pragma unroll
+    for (int d = 0; d < 8; ++d) {
+        const float c0 = c[2 * d], c1 = c[2 * d + 1];
+        nn = fmaf(c0, c0, fmaf(c1, c1, nn));
+        split3(c0, c1, p[0][d], p[1][d], p[2][d]);
+    }
+#pragma unroll
+    for (int pc = 0; pc < 3; ++pc)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const u32x4 q = {p[pc][4 * hh], p[pc][4 * hh + 1], p[pc][4 * hh + 2], p[pc][4 * hh + 3]};
+            *reinterpret_cast<u32x4 *>(img + ((pc * 2 + hh) * kPqK + slot) * 16) = q;
+        }
+    uint32_t n0, n1, n2;
+    split3(0.5f * nn, 0.f, n0, n1, n2);                    // low halves: the pieces of ||c||^2 / 2
+    *reinterpret_cast<uint2 *>(img + kImg16Pieces + slot * 8) = make_uint2(kOne | (n0 << 16), (n1 & 0xFFFFu) | (n2 << 16));
+}
+
+__global__ __launch_bounds__(256, 3) void pq_encode16_kernel(const float *__restrict__ X, long long N, long long ldx,
+                                                             const uint8_t *__restrict__ image, int M, int mr,
+                                                             uint8_t *__restrict__ codes) {
+    constexpr int DSUB = 16;
+    constexpr uint32_t kOne = 0x3F80u;                     // bf16 1.0
+    __shared__ __attribute__((aligned(16))) uint8_t img[2][kImg16Bytes];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const long long ntiles = (N + 255) / 256;
+
+    // The image of sub-block m goes from global memory straight into shared memory, 1 KB (64 lanes x
+    // 16 bytes) per instruction, without passing through registers; it is complete once the wave's
+    // outstanding loads have been waited for and the workgroup has met at a barrier.
+    auto copy_image = [&](int m, int buf) {
+        const uint8_t *src = image + (size_t)m * kImg16Bytes;
+        for (int j = wave; j < kImg16Bytes / 1024; j += 4)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + j * 1024 + lane * 16),
+                                             (__attribute__((address_space(3))) void *)(img[buf] + j * 1024), 16, 0, 0);
+    };
+
+    const int ranges = (M + mr - 1) / mr;
+    for (long long unit = blockIdx.x; unit < ntiles * ranges; unit += gridDim.x) {
+        const long long tile = unit / ranges;
+        const int m_begin = (int)(unit % ranges) * mr, m_end = m_begin + mr < M ? m_begin + mr : M;
+        const long long row0 = tile * 256 + (long long)wave * 64;
+        const float *xrow[2];
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            long long row = row0 + 32 * f + r;
+            if (row > N - 1) row = N - 1;                  // computed, never stored
+            xrow[f] = X + (size_t)row * ldx + h * 8;
+        }
+        const long long myrow = row0 + lane;               // the row whose codes this lane writes
+        uint32_t packed = 0u;                              // codes of up to four consecutive sub-blocks of myrow
+
+        f32x4 anext[2][2];
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+            for (int v = 0; v < 2; ++v) anext[f][v] = *reinterpret_cast<const f32x4 *>(xrow[f] + (size_t)m_begin * DSUB + 4 * v);
+        __syncthreads();                                   // the previous unit is done with shared memory
+        copy_image(m_begin, m_begin & 1);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        for (int m = m_begin; m < m_end; ++m) {
+            const int buf = m & 1;
+            if (m + 1 < m_end) copy_image(m + 1, buf ^ 1);  // uniform; that buffer was last read a barrier ago
+            // operand A: the pieces of the negated components, and the norm operand
+            u32x4 xa[2][3], xn[2];
+#pragma unroll
+            for (int f = 0; f < 2; ++f) {
+                float ss = 0.f;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const float t0 = anext[f][d / 2][2 * (d % 2)], t1 = anext[f][d / 2][2 * (d % 2) + 1];
+                    ss = fmaf(t0, t0, fmaf(t1, t1, ss));
+                    uint32_t p0, p1, p2;
+                    split3(-t0, -t1, p0, p1, p2);
+                    xa[f][0][d] = p0;
+                    xa[f][1][d] = p1;
+                    xa[f][2][d] = p2;
+                }
+                const float other = __shfl_xor(ss, 32, 64);    // the other half of the row's components
+                uint32_t n0, n1, n2;
+                split3(0.5f * (ss + other), 0.f, n0, n1, n2);
+                const u32x4 q = {(n0 & 0xFFFFu) | (n1 << 16), (n2 & 0xFFFFu) | (kOne << 16), kOne | (kOne << 16), 0u};
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                xn[f] = h == 0 ? q : zero;
+            }
+            {                                              // the next sub-block's components (the last one re-reads)
+                const int mn = m + 1 < m_end ? m + 1 : m;
+#pragma unroll
+                for (int f = 0; f < 2; ++f)
+#pragma unroll
+                    for (int v = 0; v < 2; ++v) anext[f][v] = *reinterpret_cast<const f32x4 *>(xrow[f] + (size_t)mn * DSUB + 4 * v);
+            }
+
+            // Running minimum per lane over the 8 blocks of 32 centres, two ALU instructions per value:
+            // the block number replaces the three lowest mantissa bits of the (non-negative) value and
+            // the minimum is taken on the bit patterns, so the lower block wins among equal values.
+            int best[2][16];
+#pragma unroll
+            for (int f = 0; f < 2; ++f)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) best[f][v] = 0x7FFFFFFF;
+#pragma unroll 1
+            for (int cb = 0; cb < kPqK / 32; ++cb) {
+                u32x4 cp[3];
+#pragma unroll
+                for (int pc = 0; pc < 3; ++pc)
+                    cp[pc] = *reinterpret_cast<const u32x4 *>(img[buf] + ((pc * 2 + h) * kPqK + 32 * cb + r) * 16);
+                const uint2 nn = *reinterpret_cast<const uint2 *>(img[buf] + kImg16Pieces + (32 * cb + r) * 8);
+                const u32x4 cnorm = {kOne | (kOne << 16), nn.x, nn.y, 0u};
+                float16v acc[2];
+#pragma unroll
+                for (int f = 0; f < 2; ++f)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[f][v] = 0.f;
+                // smallest terms first
+#pragma unroll
+                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xa[f][2], cp[0], acc[f]);
+#pragma unroll
+                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xa[f][1], cp[1], acc[f]);
+#pragma unroll
+                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xa[f][0], cp[2], acc[f]);
+#pragma unroll
+                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xa[f][1], cp[0], acc[f]);
+#pragma unroll
+                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xa[f][0], cp[1], acc[f]);
+#pragma unroll
+                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xa[f][0], cp[0], acc[f]);
+#pragma unroll
+                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xn[f], cnorm, acc[f]);
+                // accumulator element v of lane (r, h): row 8 (v / 4) + 4 h + v % 4 of the half, centre 32 cb + r
+#pragma unroll
+                for (int f = 0; f < 2; ++f)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) best[f][v] = min(best[f][v], (__float_as_int(acc[f][v]) & ~7) | cb);
+            }
+            const int code = code_from_minima(best, lane);
+            packed |= (uint32_t)code << (8 * (m & 3));
+            if ((m & 3) == 3 || m == m_end - 1) {          // uniform (ranges begin at multiples of 4)
+                if (myrow < N) {
+                    uint8_t *dst = codes + (size_t)myrow * M + (m & ~3);
+                    if ((m & 3) == 3) *reinterpret_cast<uint32_t *>(dst) = packed;
+                    else
+                        for (int j = 0; j <= (m & 3); ++j) dst[j] = (uint8_t)(packed >> (8 * j));
+                }
+                packed = 0u;
+            }
+            __builtin_amdgcn_s_waitcnt(0);                 // this wave's part of the next image has landed
             __syncthreads();
         }
     }
@@ -418,10 +632,16 @@ struct PqTrainWs {
     float *norms, *sums;
     uint32_t *counts;
     double *distortion;
+    uint8_t *image;                                        // dsub = 16 only
 };
 
+static size_t pq_train_ws_tables(int M, int dsub) {
+    const size_t b = 256 + (size_t)M * kPqK * 4 + (size_t)M * kPqK * dsub * 4 + (size_t)M * kPqK * 4;
+    return (b + 255) & ~(size_t)255;
+}
+
 size_t pq_train_ws_bytes(int M, int dsub) {
-    return 256 + (size_t)M * kPqK * 4 + (size_t)M * kPqK * dsub * 4 + (size_t)M * kPqK * 4;
+    return pq_train_ws_tables(M, dsub) + (dsub == 16 ? (size_t)M * kImg16Bytes : 0);
 }
 
 static PqTrainWs pq_train_ws(void *ws, int M, int dsub) {
@@ -431,6 +651,7 @@ static PqTrainWs pq_train_ws(void *ws, int M, int dsub) {
     w.norms = reinterpret_cast<float *>(p + 256);
     w.sums = w.norms + (size_t)M * kPqK;
     w.counts = reinterpret_cast<uint32_t *>(w.sums + (size_t)M * kPqK * dsub);
+    w.image = p + pq_train_ws_tables(M, dsub);
     return w;
 }
 
@@ -445,7 +666,14 @@ hipError_t launch_pq_encode(const float *X, int64_t N, int64_t ldx, const float 
     switch (dsub) {
         case 4: pq_encode_kernel<4><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, mr, codes); break;
         case 8: pq_encode_kernel<8><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, mr, codes); break;
-        case 16: pq_encode_kernel<16><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, mr, codes); break;
+        case 16:
+            if (tune_int("OTF_PQENC_FP32", 0))             // the fp32 matrix instructions, kept for comparison
+                pq_encode_kernel<16><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, mr, codes);
+            else {
+                pq_centre_image16_kernel<<<M, 256, 0, s>>>(codebooks, M, w.image);
+                pq_encode16_kernel<<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, w.image, M, mr, codes);
+            }
+            break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
