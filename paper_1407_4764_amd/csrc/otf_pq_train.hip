@@ -57,6 +57,57 @@ __device__ __forceinline__ int code_from_minima(const int (&best)[2][16], int la
     return code;
 }
 
+// The same end of a sub-block for pq_encode16_kernel, at half the instructions: a reduce-scatter.
+// Lane r of a half-wave holds candidates of 32 rows (registers j = 16 f + v) for one centre of the
+// block; five exchange steps, one per lane bit, each halve the registers a lane keeps while merging
+// in the partner's candidates for them, and leave lane r with the winner of row j = r.  A candidate
+// is (key, centre within the block).  Centres sit in the lanes bit-reversed (lane bit 4 = centre
+// bit 0, ...), and the lane bits are taken from 4 down to 0, i.e. the centre bits from the lowest up:
+// at every step the two candidates agree in all higher centre bits, so among equal keys the one
+// from the side whose bit is 0 is the lower centre, whatever the bits below.
+// Returns the code of row 32 (r >> 4) + 8 ((r & 15) >> 2) + 4 h + (r & 3) of the wave's 64 rows.
+__device__ __forceinline__ int rs_row_of_lane(int lane) {
+    const int r = lane & 31, h = lane >> 5;
+    return 32 * (r >> 4) + 8 * ((r & 15) >> 2) + 4 * h + (r & 3);
+}
+
+template <int PAIRS, int BIT, typename Partner>
+__device__ __forceinline__ void rs_step(int (&k)[16], int (&i)[16], int lane, Partner partner) {
+    const bool up = (lane & BIT) != 0;                     // this lane keeps the upper register of a pair
+    const int tie = up ? 1 : 0;                            // ... and then the partner's side has the lower centre
+#pragma unroll
+    for (int j = 0; j < PAIRS; ++j) {
+        const int keep_k = up ? k[j + PAIRS] : k[j], give_k = up ? k[j] : k[j + PAIRS];
+        const int keep_i = up ? i[j + PAIRS] : i[j], give_i = up ? i[j] : i[j + PAIRS];
+        const int got_k = partner(give_k), got_i = partner(give_i);
+        const bool take = got_k < keep_k + tie;
+        k[j] = min(keep_k, got_k);
+        i[j] = take ? got_i : keep_i;
+    }
+}
+
+__device__ __forceinline__ int code_by_reduce_scatter(const int (&best)[2][16], int lane) {
+    const int c = (int)(__brev((uint32_t)(lane & 31)) >> 27);   // this lane's centre within a block
+    const int c_lo = c & ~1, c_hi = c | 1;
+    int k[16], i[16];
+    // lane bit 4 (partner lane ^ 16): v_permlane16_swap exchanges the odd 16-lane rows of its first
+    // operand with the even rows of its second; afterwards the first holds, in every lane, the
+    // candidate of the side with lane bit 4 = 0 and the second that of the other side, both for
+    // the register this lane keeps (f = lane bit 4).
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const auto sw = __builtin_amdgcn_permlane16_swap((uint32_t)best[0][v], (uint32_t)best[1][v], false, false);
+        const int d = (int)sw[0], e = (int)sw[1];
+        k[v] = min(d, e);
+        i[v] = e < d ? c_hi : c_lo;
+    }
+    rs_step<8, 8>(k, i, lane, [](int x) { return dpp_i32<0x128>(x); });                    // row_ror:8 = lane ^ 8
+    rs_step<4, 4>(k, i, lane, [](int x) { return dpp_i32<0x1B>(dpp_i32<0x141>(x)); });     // half mirror, then quad reversed = lane ^ 4
+    rs_step<2, 2>(k, i, lane, [](int x) { return dpp_i32<0x4E>(x); });                     // lane ^ 2
+    rs_step<1, 1>(k, i, lane, [](int x) { return dpp_i32<0xB1>(x); });                     // lane ^ 1
+    return 32 * (k[0] & 7) + i[0];
+}
+
 // norms[m][k] = ||codebooks[m][k]||^2
 __global__ __launch_bounds__(256) void pq_centre_norms_kernel(const float *__restrict__ codebooks, int M, int dsub,
                                                               float *__restrict__ norms) {
@@ -253,14 +304,14 @@ __global__ __launch_bounds__(256) void pq_centre_image16_kernel(const float *__r
     if (m >= M) return;
     const float *c = codebooks + ((size_t)m * kPqK + k) * 16;
     uint8_t *img = image + (size_t)m * kImg16Bytes;
-    const int slot = k;
+    const int slot = (k & ~31) | (int)(__brev((uint32_t)(k & 31)) >> 27);   // lane r of the encoder holds the centre with r's bits reversed
     uint32_t p[3][8];                                      // [piece][pair of components]
     float nn = 0.f;
 #pragma unroll
     for (int d = 0; d < 8; ++d) {
         const float c0 = c[2 * d], c1 = c[2 * d + 1];
         nn = fmaf(c0, c0, fmaf(c1, c1, nn));
-        split3(c0, c1, p[0][d], p[1][d], p[2][d]);
+        split3(-c0, -c1, p[0][d], p[1][d], p[2][d]);       // negated: the products then sum to -<x, c>
     }
 #pragma unroll
     for (int pc = 0; pc < 3; ++pc)
@@ -306,7 +357,7 @@ __global__ __launch_bounds__(256, 3) void pq_encode16_kernel(const float *__rest
             if (row > N - 1) row = N - 1;                  // computed, never stored
             xrow[f] = X + (size_t)row * ldx + h * 8;
         }
-        const long long myrow = row0 + lane;               // the row whose codes this lane writes
+        const long long myrow = row0 + rs_row_of_lane(lane);   // the row whose codes this lane ends up with and writes
         uint32_t packed = 0u;                              // codes of up to four consecutive sub-blocks of myrow
 
         f32x4 anext[2][2];
@@ -321,7 +372,7 @@ __global__ __launch_bounds__(256, 3) void pq_encode16_kernel(const float *__rest
         for (int m = m_begin; m < m_end; ++m) {
             const int buf = m & 1;
             if (m + 1 < m_end) copy_image(m + 1, buf ^ 1);  // uniform; that buffer was last read a barrier ago
-            // operand A: the pieces of the negated components, and the norm operand
+            // operand A: the pieces of the components (the image holds the negated centres), and the norm operand
             u32x4 xa[2][3], xn[2];
 #pragma unroll
             for (int f = 0; f < 2; ++f) {
@@ -331,7 +382,7 @@ __global__ __launch_bounds__(256, 3) void pq_encode16_kernel(const float *__rest
                     const float t0 = anext[f][d / 2][2 * (d % 2)], t1 = anext[f][d / 2][2 * (d % 2) + 1];
                     ss = fmaf(t0, t0, fmaf(t1, t1, ss));
                     uint32_t p0, p1, p2;
-                    split3(-t0, -t1, p0, p1, p2);
+                    split3(t0, t1, p0, p1, p2);
                     xa[f][0][d] = p0;
                     xa[f][1][d] = p1;
                     xa[f][2][d] = p2;
@@ -343,6 +394,60 @@ __global__ __launch_bounds__(256, 3) void pq_encode16_kernel(const float *__rest
                 const u32x4 zero = {0u, 0u, 0u, 0u};
                 xn[f] = h == 0 ? q : zero;
             }
+            // Running minimum per lane over the 8 blocks of 32 centres, taken two blocks at a time: the
+            // block number replaces the three lowest mantissa bits of the (non-negative) value and the
+            // minimum is taken on the bit patterns, so the lower block wins among equal values; one
+            // three-way minimum folds two tagged values into the running one (1.5 ALU instructions
+            // per value).  One half f of the rows at a time keeps the accumulators at 32 registers.
+            int best[2][16];
+            auto two_blocks = [&](int cb0, auto first) {
+                // The two block numbers as separate opaque scalars: seen as cb0 and cb0 + 1 the compiler
+                // turns (bits & ~7) | tag into an AND and an ADD; like this it is one v_and_or_b32.
+                int tag0 = cb0, tag1 = cb0 + 1;
+                asm("" : "+s"(tag0));
+                asm("" : "+s"(tag1));
+                u32x4 cp[2][3], cnorm[2];
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+#pragma unroll
+                    for (int pc = 0; pc < 3; ++pc)
+                        cp[e][pc] = *reinterpret_cast<const u32x4 *>(img[buf] + ((pc * 2 + h) * kPqK + 32 * (cb0 + e) + r) * 16);
+                    const uint2 nn = *reinterpret_cast<const uint2 *>(img[buf] + kImg16Pieces + (32 * (cb0 + e) + r) * 8);
+                    cnorm[e] = u32x4{kOne | (kOne << 16), nn.x, nn.y, 0u};
+                }
+#pragma unroll
+                for (int f = 0; f < 2; ++f) {
+                    float16v acc[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[e][v] = 0.f;
+                    // smallest terms first
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xa[f][2], cp[e][0], acc[e]);
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xa[f][1], cp[e][1], acc[e]);
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xa[f][0], cp[e][2], acc[e]);
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xa[f][1], cp[e][0], acc[e]);
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xa[f][0], cp[e][1], acc[e]);
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xa[f][0], cp[e][0], acc[e]);
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xn[f], cnorm[e], acc[e]);
+                    // accumulator element v of lane (r, h): row 8 (v / 4) + 4 h + v % 4 of the half, centre slot 32 cb + r
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int ka = (__float_as_int(acc[0][v]) & ~7) | tag0, kb = (__float_as_int(acc[1][v]) & ~7) | tag1;
+                        best[f][v] = first.value ? min(ka, kb) : min(min(ka, kb), best[f][v]);
+                    }
+                }
+            };
+            two_blocks(0, std::true_type{});
+#pragma unroll 1
+            for (int cb0 = 2; cb0 < kPqK / 32; cb0 += 2) two_blocks(cb0, std::false_type{});
             {                                              // the next sub-block's components (the last one re-reads)
                 const int mn = m + 1 < m_end ? m + 1 : m;
 #pragma unroll
@@ -350,50 +455,7 @@ __global__ __launch_bounds__(256, 3) void pq_encode16_kernel(const float *__rest
 #pragma unroll
                     for (int v = 0; v < 2; ++v) anext[f][v] = *reinterpret_cast<const f32x4 *>(xrow[f] + (size_t)mn * DSUB + 4 * v);
             }
-
-            // Running minimum per lane over the 8 blocks of 32 centres, two ALU instructions per value:
-            // the block number replaces the three lowest mantissa bits of the (non-negative) value and
-            // the minimum is taken on the bit patterns, so the lower block wins among equal values.
-            int best[2][16];
-#pragma unroll
-            for (int f = 0; f < 2; ++f)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) best[f][v] = 0x7FFFFFFF;
-#pragma unroll 1
-            for (int cb = 0; cb < kPqK / 32; ++cb) {
-                u32x4 cp[3];
-#pragma unroll
-                for (int pc = 0; pc < 3; ++pc)
-                    cp[pc] = *reinterpret_cast<const u32x4 *>(img[buf] + ((pc * 2 + h) * kPqK + 32 * cb + r) * 16);
-                const uint2 nn = *reinterpret_cast<const uint2 *>(img[buf] + kImg16Pieces + (32 * cb + r) * 8);
-                const u32x4 cnorm = {kOne | (kOne << 16), nn.x, nn.y, 0u};
-                float16v acc[2];
-#pragma unroll
-                for (int f = 0; f < 2; ++f)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[f][v] = 0.f;
-                // smallest terms first
-#pragma unroll
-                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xa[f][2], cp[0], acc[f]);
-#pragma unroll
-                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xa[f][1], cp[1], acc[f]);
-#pragma unroll
-                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xa[f][0], cp[2], acc[f]);
-#pragma unroll
-                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xa[f][1], cp[0], acc[f]);
-#pragma unroll
-                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xa[f][0], cp[1], acc[f]);
-#pragma unroll
-                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xa[f][0], cp[0], acc[f]);
-#pragma unroll
-                for (int f = 0; f < 2; ++f) acc[f] = mfma_bf16(xn[f], cnorm, acc[f]);
-                // accumulator element v of lane (r, h): row 8 (v / 4) + 4 h + v % 4 of the half, centre 32 cb + r
-#pragma unroll
-                for (int f = 0; f < 2; ++f)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) best[f][v] = min(best[f][v], (__float_as_int(acc[f][v]) & ~7) | cb);
-            }
-            const int code = code_from_minima(best, lane);
+            const int code = code_by_reduce_scatter(best, lane);
             packed |= (uint32_t)code << (8 * (m & 3));
             if ((m & 3) == 3 || m == m_end - 1) {          // uniform (ranges begin at multiples of 4)
                 if (myrow < N) {
