@@ -2,10 +2,14 @@
 // R^m becomes the code beta = sgn(U phi) in {0,1}^n, n > m, sgn(a) = 1 iff a > 0, where the frame U
 // is the first m columns of the orthogonal factor of a QR decomposition of a random n x n matrix.
 //
-// tight_frame_kernel   U from the random matrix (set-up, once per frame)
-// binarize_kernel      the codes of N descriptors: an N x n x m matrix product on the matrix
-//                      cores (fp32 inputs, fp32 accumulation) whose epilogue keeps only the signs,
-//                      packed 32 to a word, dimension d at bit d mod 32 of word d div 32
+// tight_frame_kernel     U from the random matrix (set-up, once per frame)
+// binarize_bf16_kernel   the codes of N descriptors: an N x n x m matrix product on the matrix
+//                        cores at fp32 accuracy (three exact bf16 pieces per value, fp32
+//                        accumulation) whose epilogue keeps only the signs, packed 32 to a word,
+//                        dimension d at bit d mod 32 of word d div 32
+// binarize_kernel        the same product on the fp32 matrix instructions; 1.6 times slower (they do
+//                        not overlap with the vector ALU on this chip), kept behind
+//                        OTF_BINARIZE_FP32=1 for comparison
 #include <algorithm>
 
 #include "otf_bf16x3.h"
@@ -76,9 +80,9 @@ __global__ __launch_bounds__(kFrameThreads) void tight_frame_kernel(const float 
 }
 
 // -------------------------------------------------------------------------------------------
-// Codes.  2 m n flop per descriptor against 4 m + n/8 bytes: at m = 128, n = 2048 that is 680
-// flop per byte, so the kernel is bound by the fp32 rate of the matrix cores and is organised to
-// keep them issuing: one workgroup of eight waves per compute unit, two waves per SIMD.
+// Codes, fp32 matrix instructions.  2 m n flop per descriptor against 4 m + n/8 bytes: at m = 128,
+// n = 2048 that is 680 flop per byte, so the kernel is bound by the rate of the matrix cores and is
+// organised to keep them issuing: one workgroup of eight waves per compute unit, two waves per SIMD.
 //
 //   * A wave owns 32 descriptors for the whole of U.  Their values stay in registers for that
 //     time, already in the operand layout of v_mfma_f32_32x32x2_f32 (lane (r, h) = descriptor r,

@@ -4,11 +4,15 @@
 // from a training set).
 //
 // Nearest centre of sub-vector x among c_0..c_255: argmin_k ||x||^2/2 - <x, c_k> + ||c_k||^2/2, the lowest k
-// among equals.  For 32 rows and 32 centres that is one v_mfma_f32_32x32x2_f32 chain of dsub/2 + 1
-// steps (the last step adds the two norms), so an encoding pass is an N x 256 x (dsub + 2) product
-// per sub-block on the matrix cores, and what remains for the vector ALU is the argmin: a running
-// minimum per lane over the 8 blocks of 32 centres, then one reduction over the 32 lanes that hold
-// the candidates of a row.
+// among equals.  For 32 rows and 32 centres that is one chain of matrix instructions whose last
+// step adds the two norms, so an encoding pass is an N x 256 x (dsub + 2) product per sub-block on
+// the matrix cores, and what remains for the vector ALU is the argmin: a running minimum per lane
+// over the 8 blocks of 32 centres, then one reduction over the 32 lanes that hold the candidates of
+// a row.
+//
+// pq_encode16_kernel   dsub = 16: bf16 matrix instructions on three exact pieces per fp32 value
+// pq_encode_kernel     dsub = 4, 8 (and 16 under OTF_PQENC_FP32=1): fp32 matrix instructions
+// pq_accumulate_kernel, pq_move_centres_kernel   the second half of a Lloyd iteration
 #include <algorithm>
 #include <type_traits>
 
