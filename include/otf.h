@@ -200,7 +200,7 @@ int otf_binarize(const float *phi, int64_t N, int32_t m, int64_t ld_phi, const f
  *
  * otf_pq_encode:  codes[i][m] = argmin_k || X[i][m*dsub .. (m+1)*dsub) - codebooks[m][k] ||^2, the
  *   lowest k among equal distances.  Evaluated as argmin_k ||c_k||^2 - 2 <x, c_k> on the matrix cores
- *   at fp32 accuracy (dsub = 16: every value enters as three exact bf16 pieces and piece products below
+ *   at fp32 accuracy (every value enters as three exact bf16 pieces and piece products below
  *   2^-23 of |x_j c_j| are left out; sums in fp32): where two centres are equally near to within
  *   rounding, either may be returned.
  *   X  N x (M*dsub) floats, leading dimension ldx (elements, a multiple of 4).

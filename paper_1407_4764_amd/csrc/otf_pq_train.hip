@@ -10,8 +10,8 @@
 // over the 8 blocks of 32 centres, then one reduction over the 32 lanes that hold the candidates of
 // a row.
 //
-// pq_encode16_kernel   dsub = 16: bf16 matrix instructions on three exact pieces per fp32 value
-// pq_encode_kernel     dsub = 4, 8 (and 16 under OTF_PQENC_FP32=1): fp32 matrix instructions
+// pq_encode_bf16_kernel   bf16 matrix instructions on three exact pieces per fp32 value
+// pq_encode_kernel        the fp32 matrix instructions (OTF_PQENC_FP32=1), kept for comparison
 // pq_accumulate_kernel, pq_move_centres_kernel   the second half of a Lloyd iteration
 #include <algorithm>
 #include <type_traits>
@@ -60,7 +60,7 @@ __device__ __forceinline__ int code_from_minima(const int (&best)[2][16], int la
     return code;
 }
 
-// The same end of a sub-block for pq_encode16_kernel, at half the instructions: a reduce-scatter.
+// The same end of a sub-block for pq_encode_bf16_kernel, at half the instructions: a reduce-scatter.
 // Lane r of a half-wave holds candidates of 32 rows (registers j = 16 f + v) for one centre of the
 // block; five exchange steps, one per lane bit, each halve the registers a lane keeps while merging
 // in the partner's candidates for them, and leave lane r with the winner of row j = r.  A candidate
@@ -258,57 +258,114 @@ __global__ __launch_bounds__(256, 3) void pq_encode_kernel(const float *__restri
     }
 }
 
-// dsub = 16 on the bf16 matrix instructions, at fp32 accuracy (three exact pieces per value, see
-// otf_bf16x3.h).  One instruction covers all 16 components, so a block of 32 rows x 32 centres
-// takes 6 + 1 instructions of 32 cycles instead of 9 of 64, and the argmin on the vector ALU
-// proceeds meanwhile.  The seventh instruction adds the norms:
-// A = [nx0 nx1 nx2 1 1 1 0 0 | 0...], B = [1 1 1 nc0 nc1 nc2 0 0 | ...] with nx = ||x||^2 / 2 and
-// nc = ||c||^2 / 2 in three pieces each.
+// The encoder on the bf16 matrix instructions, at fp32 accuracy (three exact pieces per value, see
+// otf_bf16x3.h).  For dsub = 16 a block of 32 rows x 32 centres takes 6 + 1 instructions of 32 cycles
+// instead of 9 of 64 (dsub = 8: 4 instead of 5, dsub = 4: 2 instead of 3), and the argmin on the
+// vector ALU proceeds meanwhile.
 //
-// Shared memory per sub-block: the centres' pieces as [piece][h][centre] x 16 bytes (lane (r, h)
-// reads components 8h .. 8h+7 of centre 32 cb + r: consecutive lanes read consecutive 16 bytes) and
-// two dwords of the norm operand per centre; 26 KB, double-buffered, three workgroups per CU.
-// Image of one sub-block's vocabulary as pq_encode16_kernel wants it in shared memory: the three
-// pieces of every centre as [piece][h][slot] x 16 bytes, then two dwords of the norm operand per
-// slot.  Built once per call (the centres do not change during an encoding pass), so the encoder
-// only copies it.
-constexpr int kImg16Pieces = 3 * 2 * kPqK * 16;            // 24576 bytes
-constexpr int kImg16Bytes = kImg16Pieces + kPqK * 8;       // 26624 bytes
+// Shared memory per sub-block: the image described below, 26 KB, double-buffered, three workgroups
+// per CU; lane (r, h) reads the operand of centre slot 32 cb + r, consecutive lanes consecutive
+// 16 bytes.
+//
+// Which piece products go into which matrix instruction.  One instruction has 16 K slots = 16 / DSUB
+// "places" of DSUB dimensions; lane (r, h) supplies K slots 8 h .. 8 h + 7.
+//   DSUB = 16: one place.  Six instructions, one product each: operand A = piece kA[t] of x,
+//              operand B = piece kB[t] of c (three B entries per centre in the image); a seventh adds
+//              the norms: A = [nx0 nx1 nx2 1 1 1 0 0 | 0 ..], B = [1 1 1 nc0 nc1 nc2 0 0 | ..] with
+//              nx = ||x||^2 / 2, nc = ||c||^2 / 2 in three pieces each.
+//   DSUB = 8:  two places, the lanes h = 0 and h = 1.  Three instructions, two products each, plus
+//              the norm instruction.
+//   DSUB = 4:  four places, two per lane.  Two instructions: four products, then two products and
+//              the norm operand in the h = 1 lanes.
+// Smallest products first.  The image holds per centre slot the B operand of every instruction (for
+// DSUB = 16 the three pieces), as [entry][h][slot] x 16 bytes, then (DSUB = 16, 8) two dwords of the
+// norm operand per slot; the centres negated, so that the products sum to -<x, c>.  Built once per
+// call, so the encoder only copies it.
+template <int DSUB>
+struct Bf16Plan;
+template <>
+struct Bf16Plan<16> {
+    static constexpr int kEntries = 3, kProducts = 6;
+    static constexpr bool kNormInstr = true;
+    static constexpr int kA[6] = {2, 1, 0, 1, 0, 0}, kB[6] = {0, 1, 2, 0, 1, 0};
+};
+template <>
+struct Bf16Plan<8> {
+    static constexpr int kEntries = 3, kProducts = 3;
+    static constexpr bool kNormInstr = true;
+    static constexpr int kA[3] = {0, 1, 2}, kB[3] = {0, 1, 2};
+    // pieces (x, c) of instruction t in the lanes h = 0, 1
+    static constexpr int kX[3][2] = {{2, 1}, {0, 1}, {0, 0}}, kC[3][2] = {{0, 1}, {2, 0}, {1, 0}};
+};
+template <>
+struct Bf16Plan<4> {
+    static constexpr int kEntries = 2, kProducts = 2;
+    static constexpr bool kNormInstr = false;
+    static constexpr int kA[2] = {0, 1}, kB[2] = {0, 1};
+    // pieces (x, c) of instruction t in place 2 h + j; -1 = the norm operand (both places of the lane)
+    static constexpr int kX[2][2][2] = {{{2, 1}, {0, 1}}, {{0, 0}, {-1, -1}}};
+    static constexpr int kC[2][2][2] = {{{0, 1}, {2, 0}}, {{1, 0}, {-1, -1}}};
+};
+constexpr int kImgPieces = 3 * 2 * kPqK * 16;              // 24576 bytes (DSUB = 4 uses the first 16384)
+constexpr int kImgBytes = kImgPieces + kPqK * 8;           // 26624 bytes per sub-block, whatever DSUB
+constexpr uint32_t kBf16One = 0x3F80u;
 
-__global__ __launch_bounds__(256) void pq_centre_image16_kernel(const float *__restrict__ codebooks, int M,
-                                                                uint8_t *__restrict__ image) {
-    constexpr uint32_t kOne = 0x3F80u;                     // bf16 1.0
+// the norm operands from n = (half) a squared norm: [n0 n1 n2 1 1 1 0 0] and [1 1 1 n0 n1 n2 0 0]
+__device__ __forceinline__ u32x4 norm_operand_a(float n) {
+    uint32_t n0, n1, n2;
+    split3(n, 0.f, n0, n1, n2);                            // low halves: the pieces
+    return u32x4{(n0 & 0xFFFFu) | (n1 << 16), (n2 & 0xFFFFu) | (kBf16One << 16), kBf16One | (kBf16One << 16), 0u};
+}
+__device__ __forceinline__ u32x4 norm_operand_b(float n) {
+    uint32_t n0, n1, n2;
+    split3(n, 0.f, n0, n1, n2);
+    return u32x4{kBf16One | (kBf16One << 16), kBf16One | (n0 << 16), (n1 & 0xFFFFu) | (n2 << 16), 0u};
+}
+
+template <int DSUB>
+__global__ __launch_bounds__(256) void pq_centre_image_kernel(const float *__restrict__ codebooks, int M,
+                                                              uint8_t *__restrict__ image) {
+    using P = Bf16Plan<DSUB>;
     const int m = blockIdx.x, k = threadIdx.x;
     if (m >= M) return;
-    const float *c = codebooks + ((size_t)m * kPqK + k) * 16;
-    uint8_t *img = image + (size_t)m * kImg16Bytes;
+    const float *c = codebooks + ((size_t)m * kPqK + k) * DSUB;
+    uint8_t *img = image + (size_t)m * kImgBytes;
     const int slot = (k & ~31) | (int)(__brev((uint32_t)(k & 31)) >> 27);   // lane r of the encoder holds the centre with r's bits reversed
-    uint32_t p[3][8];                                      // [piece][pair of components]
+    uint32_t p[3][DSUB / 2];                               // [piece][pair of components]
     float nn = 0.f;
 #pragma unroll
-    for (int d = 0; d < 8; ++d) {
+    for (int d = 0; d < DSUB / 2; ++d) {
         const float c0 = c[2 * d], c1 = c[2 * d + 1];
         nn = fmaf(c0, c0, fmaf(c1, c1, nn));
         split3(-c0, -c1, p[0][d], p[1][d], p[2][d]);       // negated: the products then sum to -<x, c>
     }
+    const u32x4 nb = norm_operand_b(0.5f * nn);
 #pragma unroll
-    for (int pc = 0; pc < 3; ++pc)
+    for (int t = 0; t < P::kEntries; ++t)
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
-            const u32x4 q = {p[pc][4 * hh], p[pc][4 * hh + 1], p[pc][4 * hh + 2], p[pc][4 * hh + 3]};
-            *reinterpret_cast<u32x4 *>(img + ((pc * 2 + hh) * kPqK + slot) * 16) = q;
+            u32x4 q;
+            if constexpr (DSUB == 16) {
+                q = u32x4{p[t][4 * hh], p[t][4 * hh + 1], p[t][4 * hh + 2], p[t][4 * hh + 3]};
+            } else if constexpr (DSUB == 8) {
+                const int pc = P::kC[t][hh];
+                q = u32x4{p[pc][0], p[pc][1], p[pc][2], p[pc][3]};
+            } else {
+                const int pa = P::kC[t][hh][0], pb = P::kC[t][hh][1];
+                q = pa < 0 ? nb : u32x4{p[pa][0], p[pa][1], p[pb][0], p[pb][1]};
+            }
+            *reinterpret_cast<u32x4 *>(img + ((t * 2 + hh) * kPqK + slot) * 16) = q;
         }
-    uint32_t n0, n1, n2;
-    split3(0.5f * nn, 0.f, n0, n1, n2);                    // low halves: the pieces of ||c||^2 / 2
-    *reinterpret_cast<uint2 *>(img + kImg16Pieces + slot * 8) = make_uint2(kOne | (n0 << 16), (n1 & 0xFFFFu) | (n2 << 16));
+    if (P::kNormInstr) *reinterpret_cast<uint2 *>(img + kImgPieces + slot * 8) = make_uint2(nb[1], nb[2]);
 }
 
-__global__ __launch_bounds__(256, 3) void pq_encode16_kernel(const float *__restrict__ X, long long N, long long ldx,
-                                                             const uint8_t *__restrict__ image, int M, int mr,
-                                                             uint8_t *__restrict__ codes) {
-    constexpr int DSUB = 16;
-    constexpr uint32_t kOne = 0x3F80u;                     // bf16 1.0
-    __shared__ __attribute__((aligned(16))) uint8_t img[2][kImg16Bytes];
+template <int DSUB>
+__global__ __launch_bounds__(256, 3) void pq_encode_bf16_kernel(const float *__restrict__ X, long long N, long long ldx,
+                                                                const uint8_t *__restrict__ image, int M, int mr,
+                                                                uint8_t *__restrict__ codes) {
+    using P = Bf16Plan<DSUB>;
+    constexpr int NV = DSUB == 4 ? 1 : 2;                  // 16-byte loads of a row's components per lane and sub-block
+    __shared__ __attribute__((aligned(16))) uint8_t img[2][kImgBytes];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 31, h = lane >> 5;
     const long long ntiles = (N + 255) / 256;
@@ -317,8 +374,8 @@ __global__ __launch_bounds__(256, 3) void pq_encode16_kernel(const float *__rest
     // 16 bytes) per instruction, without passing through registers; it is complete once the wave's
     // outstanding loads have been waited for and the workgroup has met at a barrier.
     auto copy_image = [&](int m, int buf) {
-        const uint8_t *src = image + (size_t)m * kImg16Bytes;
-        for (int j = wave; j < kImg16Bytes / 1024; j += 4)
+        const uint8_t *src = image + (size_t)m * kImgBytes;
+        for (int j = wave; j < kImgBytes / 1024; j += 4)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + j * 1024 + lane * 16),
                                              (__attribute__((address_space(3))) void *)(img[buf] + j * 1024), 16, 0, 0);
     };
@@ -333,16 +390,16 @@ __global__ __launch_bounds__(256, 3) void pq_encode16_kernel(const float *__rest
         for (int f = 0; f < 2; ++f) {
             long long row = row0 + 32 * f + r;
             if (row > N - 1) row = N - 1;                  // computed, never stored
-            xrow[f] = X + (size_t)row * ldx + h * 8;
+            xrow[f] = X + (size_t)row * ldx + (DSUB == 16 ? h * 8 : 0);   // dsub 8, 4: both halves of the wave hold the whole sub-vector
         }
         const long long myrow = row0 + rs_row_of_lane(lane);   // the row whose codes this lane ends up with and writes
         uint32_t packed = 0u;                              // codes of up to four consecutive sub-blocks of myrow
 
-        f32x4 anext[2][2];
+        f32x4 anext[2][NV];
 #pragma unroll
         for (int f = 0; f < 2; ++f)
 #pragma unroll
-            for (int v = 0; v < 2; ++v) anext[f][v] = *reinterpret_cast<const f32x4 *>(xrow[f] + (size_t)m_begin * DSUB + 4 * v);
+            for (int v = 0; v < NV; ++v) anext[f][v] = *reinterpret_cast<const f32x4 *>(xrow[f] + (size_t)m_begin * DSUB + 4 * v);
         __syncthreads();                                   // the previous unit is done with shared memory
         copy_image(m_begin, m_begin & 1);
         __builtin_amdgcn_s_waitcnt(0);
@@ -350,27 +407,36 @@ __global__ __launch_bounds__(256, 3) void pq_encode16_kernel(const float *__rest
         for (int m = m_begin; m < m_end; ++m) {
             const int buf = m & 1;
             if (m + 1 < m_end) copy_image(m + 1, buf ^ 1);  // uniform; that buffer was last read a barrier ago
-            // operand A: the pieces of the components (the image holds the negated centres), and the norm operand
-            u32x4 xa[2][3], xn[2];
+            // operand A of every instruction (the image holds the negated centres), and the norm operand
+            u32x4 xa[2][P::kEntries], xn[2];
 #pragma unroll
             for (int f = 0; f < 2; ++f) {
                 float ss = 0.f;
+                uint32_t xp[3][2 * NV];                    // [piece][pair of components]
 #pragma unroll
-                for (int d = 0; d < 4; ++d) {
+                for (int d = 0; d < 2 * NV; ++d) {
                     const float t0 = anext[f][d / 2][2 * (d % 2)], t1 = anext[f][d / 2][2 * (d % 2) + 1];
                     ss = fmaf(t0, t0, fmaf(t1, t1, ss));
-                    uint32_t p0, p1, p2;
-                    split3(t0, t1, p0, p1, p2);
-                    xa[f][0][d] = p0;
-                    xa[f][1][d] = p1;
-                    xa[f][2][d] = p2;
+                    split3(t0, t1, xp[0][d], xp[1][d], xp[2][d]);
                 }
-                const float other = __shfl_xor(ss, 32, 64);    // the other half of the row's components
-                uint32_t n0, n1, n2;
-                split3(0.5f * (ss + other), 0.f, n0, n1, n2);
-                const u32x4 q = {(n0 & 0xFFFFu) | (n1 << 16), (n2 & 0xFFFFu) | (kOne << 16), kOne | (kOne << 16), 0u};
-                const u32x4 zero = {0u, 0u, 0u, 0u};
-                xn[f] = h == 0 ? q : zero;
+                if (DSUB == 16) ss += __shfl_xor(ss, 32, 64);  // the other half of the row's components
+                const u32x4 na = norm_operand_a(0.5f * ss), zero = {0u, 0u, 0u, 0u};
+                xn[f] = h == 0 ? na : zero;
+#pragma unroll
+                for (int t = 0; t < P::kEntries; ++t) {
+                    if constexpr (DSUB == 16) {
+                        xa[f][t] = u32x4{xp[t][0], xp[t][1], xp[t][2], xp[t][3]};
+                    } else if constexpr (DSUB == 8) {
+                        const int p0 = P::kX[t][0], p1 = P::kX[t][1];
+                        const u32x4 q0 = {xp[p0][0], xp[p0][1], xp[p0][2], xp[p0][3]}, q1 = {xp[p1][0], xp[p1][1], xp[p1][2], xp[p1][3]};
+                        xa[f][t] = h == 0 ? q0 : q1;
+                    } else {
+                        const int a0 = P::kX[t][0][0], b0 = P::kX[t][0][1], a1 = P::kX[t][1][0], b1 = P::kX[t][1][1];
+                        const u32x4 q0 = {xp[a0][0], xp[a0][1], xp[b0][0], xp[b0][1]};
+                        const u32x4 q1 = a1 < 0 ? na : u32x4{xp[a1][0], xp[a1][1], xp[b1][0], xp[b1][1]};
+                        xa[f][t] = h == 0 ? q0 : q1;
+                    }
+                }
             }
             // Running minimum per lane over the 8 blocks of 32 centres, taken two blocks at a time: the
             // block number replaces the three lowest mantissa bits of the (non-negative) value and the
@@ -384,14 +450,16 @@ __global__ __launch_bounds__(256, 3) void pq_encode16_kernel(const float *__rest
                 int tag0 = cb0, tag1 = cb0 + 1;
                 asm("" : "+s"(tag0));
                 asm("" : "+s"(tag1));
-                u32x4 cp[2][3], cnorm[2];
+                u32x4 cp[2][P::kEntries], cnorm[2];
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
 #pragma unroll
-                    for (int pc = 0; pc < 3; ++pc)
-                        cp[e][pc] = *reinterpret_cast<const u32x4 *>(img[buf] + ((pc * 2 + h) * kPqK + 32 * (cb0 + e) + r) * 16);
-                    const uint2 nn = *reinterpret_cast<const uint2 *>(img[buf] + kImg16Pieces + (32 * (cb0 + e) + r) * 8);
-                    cnorm[e] = u32x4{kOne | (kOne << 16), nn.x, nn.y, 0u};
+                    for (int t = 0; t < P::kEntries; ++t)
+                        cp[e][t] = *reinterpret_cast<const u32x4 *>(img[buf] + ((t * 2 + h) * kPqK + 32 * (cb0 + e) + r) * 16);
+                    if (P::kNormInstr) {
+                        const uint2 nn = *reinterpret_cast<const uint2 *>(img[buf] + kImgPieces + (32 * (cb0 + e) + r) * 8);
+                        cnorm[e] = u32x4{kBf16One | (kBf16One << 16), nn.x, nn.y, 0u};
+                    }
                 }
 #pragma unroll
                 for (int f = 0; f < 2; ++f) {
@@ -400,21 +468,14 @@ __global__ __launch_bounds__(256, 3) void pq_encode16_kernel(const float *__rest
                     for (int e = 0; e < 2; ++e)
 #pragma unroll
                         for (int v = 0; v < 16; ++v) acc[e][v] = 0.f;
-                    // smallest terms first
 #pragma unroll
-                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xa[f][2], cp[e][0], acc[e]);
+                    for (int t = 0; t < P::kProducts; ++t)
 #pragma unroll
-                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xa[f][1], cp[e][1], acc[e]);
+                        for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xa[f][P::kA[t]], cp[e][P::kB[t]], acc[e]);
+                    if (P::kNormInstr) {
 #pragma unroll
-                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xa[f][0], cp[e][2], acc[e]);
-#pragma unroll
-                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xa[f][1], cp[e][0], acc[e]);
-#pragma unroll
-                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xa[f][0], cp[e][1], acc[e]);
-#pragma unroll
-                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xa[f][0], cp[e][0], acc[e]);
-#pragma unroll
-                    for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xn[f], cnorm[e], acc[e]);
+                        for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xn[f], cnorm[e], acc[e]);
+                    }
                     // accumulator element v of lane (r, h): row 8 (v / 4) + 4 h + v % 4 of the half, centre slot 32 cb + r
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
@@ -431,7 +492,7 @@ __global__ __launch_bounds__(256, 3) void pq_encode16_kernel(const float *__rest
 #pragma unroll
                 for (int f = 0; f < 2; ++f)
 #pragma unroll
-                    for (int v = 0; v < 2; ++v) anext[f][v] = *reinterpret_cast<const f32x4 *>(xrow[f] + (size_t)mn * DSUB + 4 * v);
+                    for (int v = 0; v < NV; ++v) anext[f][v] = *reinterpret_cast<const f32x4 *>(xrow[f] + (size_t)mn * DSUB + 4 * v);
             }
             const int code = code_by_reduce_scatter(best, lane);
             packed |= (uint32_t)code << (8 * (m & 3));
@@ -672,7 +733,7 @@ struct PqTrainWs {
     float *norms, *sums;
     uint32_t *counts;
     double *distortion;
-    uint8_t *image;                                        // dsub = 16 only
+    uint8_t *image;                                        // the vocabulary as the bf16 encoder reads it
 };
 
 static size_t pq_train_ws_tables(int M, int dsub) {
@@ -681,7 +742,7 @@ static size_t pq_train_ws_tables(int M, int dsub) {
 }
 
 size_t pq_train_ws_bytes(int M, int dsub) {
-    return pq_train_ws_tables(M, dsub) + (dsub == 16 ? (size_t)M * kImg16Bytes : 0);
+    return pq_train_ws_tables(M, dsub) + (size_t)M * kImgBytes;
 }
 
 static PqTrainWs pq_train_ws(void *ws, int M, int dsub) {
@@ -703,19 +764,21 @@ hipError_t launch_pq_encode(const float *X, int64_t N, int64_t ldx, const float 
     const int mr = std::min(M, std::max(4, tune_int("OTF_PQENC_RANGE", 16) & ~3));   // sub-blocks per work unit, a multiple of 4
     const int64_t units = ntiles * ((M + mr - 1) / mr);
     const int grid = (int)std::min<int64_t>(units, (int64_t)device_cu_count() * tune_int("OTF_PQENC_BLOCKS_PER_CU", 3));
+    const bool fp32 = tune_int("OTF_PQENC_FP32", 0) != 0;   // the fp32 matrix instructions, kept for comparison
+#define OTF_PQENC_LAUNCH(D)                                                                                                   \
+    if (fp32) {                                                                                                               \
+        pq_encode_kernel<D><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, mr, codes);          \
+    } else {                                                                                                                  \
+        pq_centre_image_kernel<D><<<M, 256, 0, s>>>(codebooks, M, w.image);                                                  \
+        pq_encode_bf16_kernel<D><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, w.image, M, mr, codes);               \
+    }
     switch (dsub) {
-        case 4: pq_encode_kernel<4><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, mr, codes); break;
-        case 8: pq_encode_kernel<8><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, mr, codes); break;
-        case 16:
-            if (tune_int("OTF_PQENC_FP32", 0))             // the fp32 matrix instructions, kept for comparison
-                pq_encode_kernel<16><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, mr, codes);
-            else {
-                pq_centre_image16_kernel<<<M, 256, 0, s>>>(codebooks, M, w.image);
-                pq_encode16_kernel<<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, w.image, M, mr, codes);
-            }
-            break;
+        case 4: OTF_PQENC_LAUNCH(4) break;
+        case 8: OTF_PQENC_LAUNCH(8) break;
+        case 16: OTF_PQENC_LAUNCH(16) break;
         default: return hipErrorInvalidValue;
     }
+#undef OTF_PQENC_LAUNCH
     return hipGetLastError();
 }
 
