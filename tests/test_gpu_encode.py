@@ -52,6 +52,21 @@ def test_codes_match_the_oracle_outside_the_rounding_band(N, m, n):
     np.testing.assert_array_equal(_unpack(enc.binarize(phi.numpy(), U), n), ref)   # the packed form says the same
 
 
+@pytest.mark.parametrize("waves", ["8", "4"])
+def test_kernel_on_fp32_matrix_instructions_meets_the_same_bar(waves, monkeypatch):
+    """The comparison kernel (OTF_BINARIZE_FP32=1, read by the library at every call) stays correct."""
+    monkeypatch.setenv("OTF_BINARIZE_FP32", "1")
+    monkeypatch.setenv("OTF_BINARIZE_WAVES", waves)
+    test_codes_match_the_oracle_outside_the_rounding_band(1300, 128, 2048)
+    test_codes_match_the_oracle_outside_the_rounding_band(300, 32, 512)
+
+
+def test_eight_wave_workgroups_meet_the_same_bar(monkeypatch):
+    monkeypatch.setenv("OTF_BINARIZE_WAVES", "8")
+    test_codes_match_the_oracle_outside_the_rounding_band(1300, 128, 2048)
+    test_codes_match_the_oracle_outside_the_rounding_band(700, 64, 512)
+
+
 def test_exact_data_gives_identical_codes_and_zero_codes_as_zero():
     """Small-integer descriptors and a frame of -1/0/+1: every product and partial sum is exact in
     fp32, many projections are exactly zero (sgn(0) = 0), so the codes must equal the oracle's."""

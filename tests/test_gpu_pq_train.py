@@ -50,6 +50,17 @@ def test_codes_are_nearest_centres(N, M, dsub):
     _check_codes(X.numpy(), C.numpy(), codes.cpu().numpy())
 
 
+@pytest.mark.parametrize("N,M,dsub", [(1500, 128, 16), (900, 16, 8), (1100, 32, 4)])
+def test_kernel_on_fp32_matrix_instructions_meets_the_same_bar(N, M, dsub, monkeypatch):
+    """The comparison kernel (OTF_PQENC_FP32=1, read by the library at every call) stays correct."""
+    monkeypatch.setenv("OTF_PQENC_FP32", "1")
+    X, C = _data(N, M, dsub, SEED + 40 + dsub)
+    ws = binding.pq_train_workspace(M, dsub)
+    codes = binding.pq_encode(X.to(DEV), C.to(DEV), ws)
+    torch.cuda.synchronize()
+    _check_codes(X.numpy(), C.numpy(), codes.cpu().numpy())
+
+
 def test_exact_data_gives_identical_codes_with_ties_to_the_lower_index():
     N, M, dsub = 3000, 8, 8
     g = torch.Generator().manual_seed(SEED + 1)
