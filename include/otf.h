@@ -179,7 +179,7 @@ int otf_svm_sgd_pass(float *w, float *b, int32_t D,
  *   1 <= m <= n; n <= 4096 and m <= 256, otherwise OTF_ERR_UNSUPPORTED.
  *
  * otf_binarize:  bits[i][d] = ( sum_j U[d][j] * phi[i][j] > 0 ), evaluated on the matrix cores
- *   at fp32 accuracy (every value enters as three exact bf16 pieces, piece products below 2^-23 of
+ *   at fp32 accuracy (every value enters as three exact bf16 pieces, piece products below 2^-22 of
  *   |U[d][j] phi[i][j]| are left out, sums in fp32): a bit whose exact projection is within
  *   rounding of zero may differ from an evaluation in another precision.
  *   phi   N x m floats, leading dimension ld_phi (elements, >= m, a multiple of 4).
@@ -201,7 +201,7 @@ int otf_binarize(const float *phi, int64_t N, int32_t m, int64_t ld_phi, const f
  * otf_pq_encode:  codes[i][m] = argmin_k || X[i][m*dsub .. (m+1)*dsub) - codebooks[m][k] ||^2, the
  *   lowest k among equal distances.  Evaluated as argmin_k ||c_k||^2 - 2 <x, c_k> on the matrix cores
  *   at fp32 accuracy (every value enters as three exact bf16 pieces and piece products below
- *   2^-23 of |x_j c_j| are left out; sums in fp32): where two centres are equally near to within
+ *   2^-22 of |x_j c_j| are left out; sums in fp32): where two centres are equally near to within
  *   rounding, either may be returned.
  *   X  N x (M*dsub) floats, leading dimension ldx (elements, a multiple of 4).
  *   codebooks  M x K x dsub floats, contiguous.   codes  N x M bytes, contiguous rows, 4-byte aligned.

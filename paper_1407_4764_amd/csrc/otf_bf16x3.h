@@ -2,11 +2,13 @@
 //
 // Measured on this chip: v_mfma_f32_32x32x2_f32 and the vector ALU do not overlap (a SIMD that
 // alternates them takes the sum of the two times), whereas v_mfma_f32_32x32x16_bf16 runs beside the
-// ALU and does eight times the multiply-adds of the fp32 instruction in half the cycles.  An fp32
-// value is the exact sum of three bf16 pieces (8 mantissa bits each, truncating splits), and the
-// product of two pieces is exact in the fp32 accumulator, so <x, c> in fp32 accuracy is the sum of
-// the six piece products of order <= 2: x0c0 + x0c1 + x1c0 + x0c2 + x1c1 + x2c0 (the three left
-// out are below 2^-23 of |x_i c_i|).
+// ALU and does eight times the multiply-adds of the fp32 instruction in half the cycles.  A finite
+// fp32 value v is the exact sum of three bf16 pieces: p0 = bf16(v), p1 = bf16(v - p0),
+// p2 = v - p0 - p1 (round to nearest each time: both differences are exact in fp32 and the last
+// has at most 8 significant bits left), with |p1| <= 2^-8 |v| and |p2| <= 2^-16 |v| up to a factor
+// (1 + 2^-7).  The product of two pieces is exact in the fp32 accumulator, so <x, c> in fp32
+// accuracy is the sum of the six piece products of order <= 2: x0c0 + x0c1 + x1c0 + x0c2 + x1c1 +
+// x2c0; the three left out are below 2^-22 of |x_i c_i| together.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -18,15 +20,22 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ float top16(float v) { return __uint_as_float(__float_as_uint(v) & 0xFFFF0000u); }
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// {low half: bf16(lo), high half: bf16(hi)}, round to nearest even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){lo, hi}, bf16x2));
+}
+__device__ __forceinline__ float bf16_lo(uint32_t pk) { return __uint_as_float(pk << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t pk) { return __uint_as_float(pk & 0xFFFF0000u); }
 
 // The three bf16 pieces of v0 and of v1, as dwords {low half: v0's piece, high half: v1's}.
 __device__ __forceinline__ void split3(float v0, float v1, uint32_t &p0, uint32_t &p1, uint32_t &p2) {
-    const float r0 = v0 - top16(v0), r1 = v1 - top16(v1);   // exact: the low 16 mantissa bits
-    const float s0 = r0 - top16(r0), s1 = r1 - top16(r1);   // exact: at most 8 bits are left
-    p0 = __builtin_amdgcn_perm(__float_as_uint(v1), __float_as_uint(v0), 0x07060302u);
-    p1 = __builtin_amdgcn_perm(__float_as_uint(r1), __float_as_uint(r0), 0x07060302u);
-    p2 = __builtin_amdgcn_perm(__float_as_uint(s1), __float_as_uint(s0), 0x07060302u);
+    p0 = pack_bf16(v0, v1);
+    const float r0 = v0 - bf16_lo(p0), r1 = v1 - bf16_hi(p0);   // exact
+    p1 = pack_bf16(r0, r1);
+    p2 = pack_bf16(r0 - bf16_lo(p1), r1 - bf16_hi(p1));         // exact differences that fit a bf16
 }
 
 // Operands: lane (i, g) of the wave holds row i (A) or column i (B) of a 32 x 32 block and its K
