@@ -284,23 +284,26 @@ static hipError_t rank_table(const uint8_t *codes, int64_t N, int row_bytes, int
         const int64_t Nv = sample_rows(N);
         const int m = sample_rank(N, Nv);
         e = launch_table_scan(codes, Nv, row_bytes, seven_bit, image, bias, kEmitSample, sample, ssw.st, ssw.hist1, m,
-                              nullptr, nullptr, nullptr, nullptr, s);
+                              nullptr, nullptr, nullptr, nullptr, nullptr, s);
         if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, 0, s);
         ScanTimer timer(s);
         if (e == hipSuccess)
             e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitFilter, nullptr, sw.st, nullptr, k,
-                                  ssw.st, ssw.hist2, sw.cand, nullptr, s);
+                                  ssw.st, ssw.hist2, sw.cand, nullptr, nullptr, s);
         timer.stop();
         if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
         if (e == hipSuccess)
             e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitScores, S, sw.st, sw.hist1, k,
-                                  nullptr, nullptr, nullptr, sw.st, s);
+                                  nullptr, nullptr, nullptr, sw.st, nullptr, s);
         if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 1, s);
         return e;
     }
     ScanTimer timer(s);
+    // a multi-phase scan (rows longer than 128 bytes) counts its phases' chunks in the words of the
+    // sample state, which the prepare kernel zeroed and which no filtered scan is using here
+    static_assert(sizeof(SelState) >= 8 * sizeof(uint32_t), "one word per phase, at most 8 phases");
     e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitScores, S, sw.st, sw.hist1, k, nullptr,
-                          nullptr, nullptr, nullptr, s);
+                          nullptr, nullptr, nullptr, reinterpret_cast<uint32_t *>(sample_select_ws(ws, L).st), s);
     timer.stop();
     if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 0, s);
     return e;

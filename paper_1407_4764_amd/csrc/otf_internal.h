@@ -86,7 +86,7 @@ hipError_t launch_binary_prepare(const float *w, int D, float *image, const Sele
 hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, int seven_bit, const float *image,
                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
                              const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
-                             const SelState *gate, hipStream_t s);
+                             const SelState *gate, uint32_t *phase_ctr, hipStream_t s);
 
 hipError_t launch_sgd_step(float *w, float *b, int D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,
                            int n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int n_neg,

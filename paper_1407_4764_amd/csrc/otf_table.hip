@@ -175,8 +175,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 //          (2048-bit rows, LPR = 16, each word = 4 x 7 bits + 4 bits)
 //   U      16-byte loads per lane per tile
 //   EMIT   what is produced (ScanEmit)
-//   SPLIT  byte-group rows longer than 128 bytes: several phases, partial sums carried in the score
-//          array (EMIT = kEmitScores only)
+//   SPLIT  byte-group rows longer than 128 bytes: several phases of 128 columns, one launch each,
+//          partial sums carried in the score array (EMIT = kEmitScores only)
 //
 // A tile is what one wave looks up per iteration: U loads of 64 lanes x 16 bytes.  The main loop
 // is software-pipelined: the loads of the wave's next tile are issued before the current tile is
@@ -185,12 +185,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // lookups the U row sums of a lane group are moved into U different lanes so that the output
 // step happens once per tile, not per row.
 //
-// Work distribution (single-phase scans): dynamic, by a TileQueue with chunks of 256 KiB of rows.
+// Work distribution: dynamic, by a TileQueue with chunks of 256 KiB of rows.
 template <int LPR, int U, int GB, int EMIT, bool SPLIT>
 __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     const uint8_t *__restrict__ codes, long long N, int M, int nsplit, const float *__restrict__ image, float bias,
     float *__restrict__ scores, SelState *st, uint32_t *hist1, int k, const SelState *tau_state,
-    const uint32_t *tau_hist2, unsigned long long *__restrict__ cand, const SelState *gate) {
+    const uint32_t *tau_hist2, unsigned long long *__restrict__ cand, const SelState *gate, int sp0,
+    uint32_t *phase_ctr) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     __shared__ uint32_t lhist[EMIT == kEmitFilter ? 1 : kBins1];
     __shared__ uint32_t s_out[3];
@@ -206,9 +207,10 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     constexpr uint32_t CHUNK_TILES = 256u / (uint32_t)U;          // x U KiB per tile = 256 KiB of rows
 
     // the two scans that can follow each other on one state (filtered, then the gated full scan)
-    // count in different words; both were zeroed with the state
-    uint32_t *chunk_ctr = &st->chunk_ctr[EMIT == kEmitScores ? 1 : 0];
-    if (!SPLIT && threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);   // visible after the barriers below
+    // count in different words; both were zeroed with the state.  A phase of a multi-phase scan
+    // (one launch per phase) counts in a word of its own.
+    uint32_t *chunk_ctr = SPLIT ? phase_ctr + sp0 : &st->chunk_ctr[EMIT == kEmitScores ? 1 : 0];
+    if (threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);   // visible after the barriers below
     const uint32_t chunk_tiles = tile_queue_chunk_tiles(N / TILE, CHUNK_TILES);
 
     if (EMIT != kEmitFilter)
@@ -223,7 +225,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
         tau = ((tau_state->b1 << 12) | r2.bin) << 8;
     }
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int chunk = GB == 8 ? (lane & 7) : (lane & 15);   // 16-byte chunk inside the table's row span
     const int octet = (lane >> 3) & 3;                       // which of the 4 lane octets that execute together
     const int sub = lane % LPR, rr = lane / LPR;             // chunk inside the row, row inside the wave load
@@ -281,8 +283,8 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     // compact row that lane `sub` of its group emits in round e of the tile starting at row v0
     auto out_row = [&](long long v0, int e) { return v0 + (long long)(e * ACTIVE + out_u) * RPW + rr; };
 
-    for (int sp = 0; sp < nsplit; ++sp) {
-        __syncthreads();                          // previous phase done with the table
+    {
+        const int sp = SPLIT ? sp0 : 0;           // this launch's phase (columns 128 sp .. 128 sp + 127 of every row)
         {
             const u32x4 *src = reinterpret_cast<const u32x4 *>(image + (size_t)sp * kImageFloats);
             u32x4 *dst = reinterpret_cast<u32x4 *>(lds_raw);
@@ -310,16 +312,18 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
             }
         };
 
-        if (!SPLIT) {
+        {
             // first row of the next tile of this wave, or -1 when the scan has no full tile left
             // (the rows after the last full tile are handled at the end)
             auto draw = [&]() -> long long {
                 const long long t = tile_queue_draw(&s_queue, chunk_ctr, chunk_tiles, N / TILE);
                 return t < 0 ? t : t * TILE;
             };
-            // uniform base of the tile (scalar registers) + one 32-bit lane offset
-            const uint32_t lane_off = (uint32_t)rr * (uint32_t)M + (uint32_t)sub * 16u;
-            auto fetch = [&](u32x4 *d, long long v0) {
+            // uniform base of the tile (scalar registers) + one 32-bit lane offset; a phase reads its
+            // 128 columns of every row and meets the partial sums of the phases before in the score
+            // array (`carry`)
+            const uint32_t lane_off = (uint32_t)rr * (uint32_t)M + (SPLIT ? (uint32_t)sp * (uint32_t)kSegBytes : 0u) + (uint32_t)sub * 16u;
+            auto fetch = [&](u32x4 *d, float *carry, long long v0) {
                 const unsigned long long a = (unsigned long long)store_row(v0) * (unsigned long long)M;
                 // (the builtin returns int: go through uint32_t, or offsets past 2 GiB are sign-extended)
                 const uint32_t a_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));
@@ -329,29 +333,34 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
                 for (int u = 0; u < U; ++u)
                     d[u] = __builtin_nontemporal_load(
                         reinterpret_cast<const u32x4 *>(p + (size_t)u * u_bytes + (size_t)lane_off));
+                if (SPLIT && !first) {
+#pragma unroll
+                    for (int e = 0; e < ROUNDS; ++e) carry[e] = scores[out_row(v0, e)];
+                }
             };
-            auto consume = [&](const u32x4 *d, long long v0) {
+            auto consume = [&](const u32x4 *d, const float *carry, long long v0) {
                 float mine[ROUNDS];
                 tile_sums(d, mine);
 #pragma unroll
                 for (int e = 0; e < ROUNDS; ++e) {
                     const long long v = out_row(v0, e);
-                    emit(mine[e], nullptr, v, e, true);
+                    emit(mine[e], carry, v, e, true);
                 }
             };
             long long cur = draw();
             if (cur >= 0) {
                 u32x4 b0[U], b1[U];
-                fetch(b0, cur);
+                float c0[ROUNDS], c1[ROUNDS];
+                fetch(b0, c0, cur);
                 for (;;) {
                     long long nxt = draw();
-                    fetch(b1, nxt >= 0 ? nxt : cur);
-                    consume(b0, cur);
+                    fetch(b1, c1, nxt >= 0 ? nxt : cur);
+                    consume(b0, c0, cur);
                     if (nxt < 0) break;
                     cur = nxt;
                     nxt = draw();
-                    fetch(b0, nxt >= 0 ? nxt : cur);
-                    consume(b1, cur);
+                    fetch(b0, c0, nxt >= 0 ? nxt : cur);
+                    consume(b1, c1, cur);
                     if (nxt < 0) break;
                     cur = nxt;
                 }
@@ -360,83 +369,24 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
             const long long v0 = N / TILE * TILE;
             if (v0 < N && blockIdx.x == 0 && wave == 0) {
                 u32x4 d[U];
-                float mine[ROUNDS];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const long long v = v0 + (long long)u * RPW + rr;
-                    d[u] = (u32x4){0u, 0u, 0u, 0u};
-                    if (v < N)
-                        d[u] = *reinterpret_cast<const u32x4 *>(codes + (size_t)store_row(v) * (size_t)M + (size_t)sub * 16);
-                }
-                tile_sums(d, mine);
-#pragma unroll
-                for (int e = 0; e < ROUNDS; ++e) {
-                    const long long v = out_row(v0, e);
-                    emit(mine[e], nullptr, v, e, v < N);
-                }
-            }
-        } else {
-            // several phases: every phase must meet the partial sums of the one before, so each
-            // workgroup keeps a fixed contiguous range of rows (a multiple of 1024 long, so only the
-            // last workgroup can end in a partial tile) and its waves take the tiles round-robin
-            long long per = (N + gridDim.x - 1) / gridDim.x;
-            per = (per + 1023) / 1024 * 1024;
-            long long begin = per * blockIdx.x, end = begin + per;
-            if (begin > N) begin = N;
-            if (end > N) end = N;
-            const long long nfull = (end - begin) / TILE;          // full tiles
-            const int rem = (int)((end - begin) % TILE);           // rows of the partial tile, if any
-            // byte offset of this lane inside its row (this phase's columns) plus its row inside the wave load
-            const size_t lane_off = (size_t)rr * (size_t)M + (size_t)sp * kSegBytes + (size_t)sub * 16;
-            if (wave < nfull) {                       // uniform per wave
-                auto fetch = [&](u32x4 *d, float *carry, long long tile) {
-                    if (tile > nfull - 1) tile = nfull - 1;      // uniform: prefetch past the end re-reads the last tile
-                    const long long v0 = begin + tile * TILE;
-                    const uint8_t *p = codes + (size_t)v0 * (size_t)M + lane_off;
-#pragma unroll
-                    for (int u = 0; u < U; ++u)
-                        d[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + (size_t)u * u_bytes));
-#pragma unroll
-                    for (int e = 0; e < ROUNDS; ++e) carry[e] = scores[out_row(v0, e)];
-                };
-                auto consume = [&](const u32x4 *d, const float *carry, long long tile) {
-                    float mine[ROUNDS];
-                    tile_sums(d, mine);
-                    const long long v0 = begin + tile * TILE;
-#pragma unroll
-                    for (int e = 0; e < ROUNDS; ++e) emit(mine[e], carry, out_row(v0, e), e, true);
-                };
-                u32x4 buf[2][U];
-                float car[2][ROUNDS];
-                fetch(buf[0], car[0], wave);
-                for (long long tile = wave; tile < nfull; tile += 2LL * nwaves) {
-                    fetch(buf[1], car[1], tile + nwaves);
-                    consume(buf[0], car[0], tile);
-                    if (tile + nwaves >= nfull) break;           // uniform
-                    fetch(buf[0], car[0], tile + 2LL * nwaves);
-                    consume(buf[1], car[1], tile + nwaves);
-                }
-            }
-            if (rem > 0 && wave == (int)(nfull % nwaves)) {   // the partial tile: same steps, row-checked
-                const long long v0 = begin + nfull * TILE;
-                u32x4 d[U];
                 float carry[ROUNDS], mine[ROUNDS];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const long long v = v0 + (long long)u * RPW + rr;
                     d[u] = (u32x4){0u, 0u, 0u, 0u};
-                    if (v < end) d[u] = *reinterpret_cast<const u32x4 *>(codes + (size_t)(v - rr) * (size_t)M + lane_off);
+                    if (v < N)
+                        d[u] = *reinterpret_cast<const u32x4 *>(codes + (size_t)store_row(v - rr) * (size_t)M + (size_t)lane_off);
                 }
 #pragma unroll
                 for (int e = 0; e < ROUNDS; ++e) {
                     const long long v = out_row(v0, e);
-                    carry[e] = (!first && v < end) ? scores[v] : 0.f;
+                    carry[e] = (SPLIT && !first && v < N) ? scores[v] : 0.f;
                 }
                 tile_sums(d, mine);
 #pragma unroll
                 for (int e = 0; e < ROUNDS; ++e) {
                     const long long v = out_row(v0, e);
-                    emit(mine[e], carry, v, e, v < end);
+                    emit(mine[e], carry, v, e, v < N);
                 }
             }
         }
@@ -490,6 +440,7 @@ struct ScanArgs {
     const uint32_t *tau_hist2;
     unsigned long long *cand;
     const SelState *gate;
+    uint32_t *phase_ctr;   // nsplit > 1: one zeroed word per phase
 };
 
 template <int LPR, int U, int GB, int EMIT, bool SPLIT>
@@ -503,9 +454,12 @@ static hipError_t launch_scan_cfg(const ScanArgs &a, hipStream_t s) {
     if (grid > max_useful) grid = (int)max_useful;
     if (grid < 1) grid = 1;
     const int threads = tune_int("OTF_SCAN_THREADS", kScanThreads);
-    table_scan_kernel<LPR, U, GB, EMIT, SPLIT><<<grid, threads, lds, s>>>(
-        a.codes, (long long)a.N, a.M, a.nsplit, a.image, a.bias, a.scores, a.st, a.hist1, a.k, a.tau, a.tau_hist2, a.cand,
-        a.gate);
+    // a multi-phase scan is one launch per phase: each phase meets the partial sums of the one
+    // before in the score array, and the launch boundary is what orders them
+    for (int sp = 0; sp < (SPLIT ? a.nsplit : 1); ++sp)
+        table_scan_kernel<LPR, U, GB, EMIT, SPLIT><<<grid, threads, lds, s>>>(
+            a.codes, (long long)a.N, a.M, a.nsplit, a.image, a.bias, a.scores, a.st, a.hist1, a.k, a.tau, a.tau_hist2,
+            a.cand, a.gate, sp, a.phase_ctr);
     return hipGetLastError();
 }
 
@@ -517,7 +471,7 @@ static hipError_t launch_scan_emit(const ScanArgs &a, ScanEmit emit, hipStream_t
 
     }
     if (a.nsplit > 1) {
-        if (GB != 8 || emit != kEmitScores) return hipErrorInvalidValue;
+        if (GB != 8 || emit != kEmitScores || !a.phase_ctr) return hipErrorInvalidValue;
         return launch_scan_cfg<LPR, U, 8, kEmitScores, true>(a, s);
     }
     switch (emit) {
@@ -531,9 +485,9 @@ static hipError_t launch_scan_emit(const ScanArgs &a, ScanEmit emit, hipStream_t
 hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, int seven_bit, const float *image,
                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
                              const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
-                             const SelState *gate, hipStream_t s) {
+                             const SelState *gate, uint32_t *phase_ctr, hipStream_t s) {
     ScanArgs a{codes, N,  row_bytes, seven_bit ? 1 : splits_of(row_bytes), image, bias, scores, st, hist1, k, tau,
-               tau_hist2, cand, gate};
+               tau_hist2, cand, gate, phase_ctr};
     if (seven_bit) return launch_scan_emit<16, 7>(a, emit, s);
     switch (row_bytes) {
         case 16: return launch_scan_emit<1, 8>(a, emit, s);
