@@ -165,60 +165,148 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const uint8_t *__restri
 }
 
 // ---------------------------------------------------------------------------------------------
+// Cross-lane pieces of the narrow kernel's row sums (vector ALU only: DPP and v_permlane16_swap;
+// a shuffle through the LDS crossbar per step and value was the kernel's bottleneck).
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+// the value of lane ^ BIT, BIT = 1, 2, 4, 8
+template <int BIT>
+__device__ __forceinline__ float lane_xor(float v) {
+    if (BIT == 1) return dpp_f32<0xB1>(v);                       // quad_perm [1,0,3,2]
+    if (BIT == 2) return dpp_f32<0x4E>(v);                       // quad_perm [2,3,0,1]
+    if (BIT == 4) return dpp_f32<0x1B>(dpp_f32<0x141>(v));       // half mirror, then quad reversed
+    return dpp_f32<0x128>(v);                                    // row_ror:8
+}
+// One reduce-scatter step over lane bit BIT on the first NV values: afterwards v[0 .. NV/2) hold
+// the pairwise sums of entries 0 .. NV/2-1 in the lanes whose bit is 0 and of entries NV/2 .. NV-1
+// in the lanes whose bit is 1.
+template <int BIT, int NV>
+__device__ __forceinline__ void rs_add(float *v, int lane) {
+    if (BIT == 16) {
+#pragma unroll
+        for (int j = 0; j < NV / 2; ++j) {
+            const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(v[j]), __float_as_uint(v[j + NV / 2]), false, false);
+            v[j] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+        }
+    } else {
+        const bool up = (lane & BIT) != 0;
+#pragma unroll
+        for (int j = 0; j < NV / 2; ++j) {
+            const float keep = up ? v[j + NV / 2] : v[j], give = up ? v[j] : v[j + NV / 2];
+            v[j] = keep + lane_xor<BIT>(give);
+        }
+    }
+}
+// Sums over the LPR lanes of a row for the 8 loads of a tile: v[u] = this lane's partial sum of
+// load u.  Up to three scatter steps over the top bits of the lane's position in its row, then
+// plain exchanges over the remaining bits.  Afterwards value k < 8 >> steps of a lane is the full
+// sum of load ((position >> remaining bits) * (8 >> steps) + k).
+template <int LPR>
+__device__ __forceinline__ void tile_row_sums(float *v, int lane) {
+    if constexpr (LPR >= 2) rs_add<LPR / 2, 8>(v, lane);
+    if constexpr (LPR >= 4) rs_add<LPR / 4, 4>(v, lane);
+    if constexpr (LPR >= 8) rs_add<LPR / 8, 2>(v, lane);
+    if constexpr (LPR >= 16) v[0] += lane_xor<LPR / 16>(v[0]);
+    if constexpr (LPR >= 32) v[0] += lane_xor<1>(v[0]);
+}
+
 // Narrow rows: LPR = 1..32 lanes per row (a power of two), one 16-byte chunk per lane, so one
-// wave load covers 64/LPR consecutive rows; U loads in flight per wave.
+// wave load covers 64/LPR consecutive rows; a tile is U such loads.  Same scheme as the wide
+// kernel: tiles are handed out dynamically (TileQueue, chunks of 256 KiB of rows), the loads of a
+// wave's next tile are issued before the current one is reduced, and a prefetch with nothing left
+// re-reads the current tile.  The rows after the last full tile go to one wave, row-checked.
 template <bool XHALF, int LPR>
 __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__restrict__ X, long long N, int D,
                                                            long long row_bytes, const void *__restrict__ w,
                                                            int w_is_half, const float *__restrict__ bias_ptr, int bias_index,
-        float *__restrict__ scores, uint32_t *hist1) {
+                                                           float *__restrict__ scores, uint32_t *hist1,
+                                                           uint32_t *chunk_ctr) {
     constexpr int E = Elem<XHALF>::kPer16;
     constexpr int RPW = 64 / LPR;   // rows per wave load
-    constexpr int U = 4;
+    constexpr int U = 8;
+    constexpr int TILE = RPW * U;   // rows per wave iteration (U KiB of a dense store)
     __shared__ uint32_t lhist[kBins1];
+    __shared__ TileQueue s_queue;
+    if (threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);
     for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
     __syncthreads();
 
     const float bias = bias_ptr ? bias_ptr[bias_index] : 0.f;
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane % LPR, rr = lane / LPR;
     const int col = sub * E;
-    const bool live = col < D;
+    const bool live = col < D;      // D need not fill the LPR chunks: those lanes load nothing
     float wr[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) wr[e] = live ? load_w(w, w_is_half, col + e) : 0.f;
 
-    const long long waves_total = (long long)gridDim.x * (blockDim.x >> 6);
-    const long long wave_id = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    const long long rows_per_iter = (long long)RPW * U;
-
-    for (long long base = wave_id * rows_per_iter; base < N; base += waves_total * rows_per_iter) {
+    const long long ntiles = N / TILE;
+    const uint32_t chunk_tiles = tile_queue_chunk_tiles(ntiles, 256u / (uint32_t)U);
+    const size_t lane_off = (size_t)rr * (size_t)row_bytes + (size_t)sub * 16;
+    auto fetch = [&](Chunk16 *c, long long tile) {
+        const uint8_t *p = X + (size_t)tile * TILE * (size_t)row_bytes + lane_off;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (live) c[u] = load_stream16(p + (size_t)u * RPW * (size_t)row_bytes);
+    };
+    constexpr int LOG_LPR = LPR == 1 ? 0 : LPR == 2 ? 1 : LPR == 4 ? 2 : LPR == 8 ? 3 : LPR == 16 ? 4 : 5;
+    constexpr int STEPS = LOG_LPR < 3 ? LOG_LPR : 3;        // scatter steps of tile_row_sums
+    constexpr int NVF = 8 >> STEPS;                         // sums a lane ends up with
+    const bool owner = (sub & ((1 << (LOG_LPR - STEPS)) - 1)) == 0;
+    const int u0 = (sub >> (LOG_LPR - STEPS)) * NVF;        // ... those of loads u0 .. u0 + NVF - 1
+    auto partial = [&](const Chunk16 &c) {
+        float acc = 0.f;
+        if (live) {
+            float f[E];
+            Elem<XHALF>::unpack(c, f);
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc = fmaf(f[e], wr[e], acc);
+        }
+        return acc;
+    };
+    // the owners' stores of one value index cover 64 / LPR * (8 / NVF) consecutive rows
+    auto consume = [&](const Chunk16 *c, long long tile, long long nrows) {
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = partial(c[u]);
+        tile_row_sums<LPR>(v, lane);
+#pragma unroll
+        for (int k = 0; k < NVF; ++k) {
+            const long long row = tile * TILE + (long long)(u0 + k) * RPW + rr;
+            const bool ok = owner && row < nrows;
+            const float sc = v[k] + bias;
+            if (ok) scores[row] = sc;
+            hist_add_wave(lhist, float_to_key(sc) >> 20, ok);   // many rows per instruction, few bins: aggregate
+        }
+    };
+    long long cur = tile_queue_draw(&s_queue, chunk_ctr, chunk_tiles, ntiles);
+    if (cur >= 0) {
+        Chunk16 b0[U], b1[U];
+        fetch(b0, cur);
+        for (;;) {
+            long long nxt = tile_queue_draw(&s_queue, chunk_ctr, chunk_tiles, ntiles);
+            fetch(b1, nxt >= 0 ? nxt : cur);
+            consume(b0, cur, N);
+            if (nxt < 0) break;
+            cur = nxt;
+            nxt = tile_queue_draw(&s_queue, chunk_ctr, chunk_tiles, ntiles);
+            fetch(b0, nxt >= 0 ? nxt : cur);
+            consume(b1, cur, N);
+            if (nxt < 0) break;
+            cur = nxt;
+        }
+    }
+    if (ntiles * TILE < N && blockIdx.x == 0 && wave == 0) {
         Chunk16 c[U];
-        bool ok[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const long long row = base + (long long)u * RPW + rr;
-            ok[u] = live && row < N;
-            if (ok[u]) c[u] = load_stream16(X + (size_t)row * row_bytes + (size_t)sub * 16);
+            const long long row = ntiles * TILE + (long long)u * RPW + rr;
+            c[u] = Chunk16{};
+            if (live && row < N) c[u] = load_stream16(X + (size_t)row * (size_t)row_bytes + (size_t)sub * 16);
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float acc = 0.f;
-            if (ok[u]) {
-                float f[E];
-                Elem<XHALF>::unpack(c[u], f);
-#pragma unroll
-                for (int e = 0; e < E; ++e) acc = fmaf(f[e], wr[e], acc);
-            }
-#pragma unroll
-            for (int o = LPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-            const long long row = base + (long long)u * RPW + rr;
-            if (sub == 0 && row < N) {
-                acc += bias;
-                scores[row] = acc;
-                atomicAdd(&lhist[float_to_key(acc) >> 20], 1u);
-            }
-        }
+        consume(c, ntiles, N);
     }
     merge_hist(lhist, kBins1, hist1);
 }
@@ -287,17 +375,17 @@ static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t
     if (chunks <= 32) {
         int lpr = 1;
         while (lpr < chunks) lpr <<= 1;
-        const int64_t rows_per_wave_iter = (64 / lpr) * 4;
+        const int64_t rows_per_wave_iter = (64 / lpr) * 8;
         int64_t waves = (N + rows_per_wave_iter - 1) / rows_per_wave_iter;
-        grid = (int)std::min<int64_t>((waves + 3) / 4, (int64_t)cus * 8);
+        grid = (int)std::min<int64_t>((waves + 3) / 4, (int64_t)cus * tune_int("OTF_NARROW_BLOCKS_PER_CU", 2));
         if (grid < 1) grid = 1;
         switch (lpr) {
-            case 1: dense_narrow_kernel<XHALF, 1><<<grid, 256, 0, s>>>(OTF_ARGS); break;
-            case 2: dense_narrow_kernel<XHALF, 2><<<grid, 256, 0, s>>>(OTF_ARGS); break;
-            case 4: dense_narrow_kernel<XHALF, 4><<<grid, 256, 0, s>>>(OTF_ARGS); break;
-            case 8: dense_narrow_kernel<XHALF, 8><<<grid, 256, 0, s>>>(OTF_ARGS); break;
-            case 16: dense_narrow_kernel<XHALF, 16><<<grid, 256, 0, s>>>(OTF_ARGS); break;
-            default: dense_narrow_kernel<XHALF, 32><<<grid, 256, 0, s>>>(OTF_ARGS); break;
+            case 1: dense_narrow_kernel<XHALF, 1><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS); break;
+            case 2: dense_narrow_kernel<XHALF, 2><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS); break;
+            case 4: dense_narrow_kernel<XHALF, 4><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS); break;
+            case 8: dense_narrow_kernel<XHALF, 8><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS); break;
+            case 16: dense_narrow_kernel<XHALF, 16><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS); break;
+            default: dense_narrow_kernel<XHALF, 32><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS); break;
         }
     } else {
         grid = (int)std::min<int64_t>((N + 3) / 4, (int64_t)cus * tune_int("OTF_DENSE_BLOCKS_PER_CU", 1));

@@ -58,6 +58,27 @@ def test_binary_every_row_scored_once(oracle, N):
     np.testing.assert_array_equal(idx2[0].cpu().numpy(), i)
 
 
+@pytest.mark.parametrize("N,D,dtype", [(100003, 4, torch.float32), (100003, 8, torch.float32), (70001, 16, torch.float32),
+                                       (50021, 32, torch.float32), (40009, 64, torch.float32),
+                                       (30011, 128, torch.float32), (33333, 24, torch.float16),
+                                       (20001, 256, torch.float16), (129, 128, torch.float32)])
+def test_narrow_dense_rows_every_row_scored_once(oracle, N, D, dtype):
+    """Rows of at most 512 bytes: 1 to 32 lanes per row, several rows per wave load, the row sums
+    formed by exchanges between lanes; small integers make every sum exact."""
+    g = torch.Generator().manual_seed(SEED + 9)
+    X = torch.randint(-4, 5, (N, D), generator=g).to(dtype)
+    w = torch.randint(-8, 9, (D,), generator=g).to(torch.float32)
+    ref = oracle.dense_scores(X.numpy(), w.numpy())[0]
+    ws = binding.make_workspace(N, 64)
+    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
+    val, idx = binding.rank_dense(X.to(DEV), w.to(DEV), None, 64, ws, all_scores=all_scores)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(all_scores.cpu().numpy().astype(np.float64), ref)
+    i, v = oracle.topk(ref, 64)
+    np.testing.assert_array_equal(np.sort(val[0].cpu().numpy().astype(np.float64))[::-1], v)
+    assert np.all(ref[idx[0].cpu().numpy()] == val[0].cpu().numpy())
+
+
 @pytest.mark.parametrize("N,D", [(64 * 600 + 1, 2048), (128 * 530 + 77, 1024)])
 def test_dense_every_row_scored_once(oracle, N, D):
     """fp16 rows that fill the lanes exactly take the pipelined, dynamically scheduled kernel."""
