@@ -21,7 +21,6 @@
 
 namespace otf {
 
-
 constexpr int kPqK = 256;
 
 // Minimum over each half-wave (lanes 0..31, lanes 32..63); every lane receives it.
@@ -759,7 +758,6 @@ static PqTrainWs pq_train_ws(void *ws, int M, int dsub) {
 hipError_t launch_pq_encode(const float *X, int64_t N, int64_t ldx, const float *codebooks, int M, int dsub,
                             uint8_t *codes, void *ws, hipStream_t s) {
     PqTrainWs w = pq_train_ws(ws, M, dsub);
-    pq_centre_norms_kernel<<<(M * kPqK + 255) / 256, 256, 0, s>>>(codebooks, M, dsub, w.norms);
     const int64_t ntiles = (N + 255) / 256;
     const int mr = std::min(M, std::max(4, tune_int("OTF_PQENC_RANGE", 16) & ~3));   // sub-blocks per work unit, a multiple of 4
     const int64_t units = ntiles * ((M + mr - 1) / mr);
@@ -767,6 +765,7 @@ hipError_t launch_pq_encode(const float *X, int64_t N, int64_t ldx, const float 
     const bool fp32 = tune_int("OTF_PQENC_FP32", 0) != 0;   // the fp32 matrix instructions, kept for comparison
 #define OTF_PQENC_LAUNCH(D)                                                                                                   \
     if (fp32) {                                                                                                               \
+        pq_centre_norms_kernel<<<(M * kPqK + 255) / 256, 256, 0, s>>>(codebooks, M, dsub, w.norms);                          \
         pq_encode_kernel<D><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, mr, codes);          \
     } else {                                                                                                                  \
         pq_centre_image_kernel<D><<<M, 256, 0, s>>>(codebooks, M, w.image);                                                  \
