@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256) void pq_centre_image_kernel(const float *__res
 }
 
 template <int DSUB>
-__global__ __launch_bounds__(256, 3) void pq_encode_bf16_kernel(const float *__restrict__ X, long long N, long long ldx,
+__global__ __launch_bounds__(256, 2) void pq_encode_bf16_kernel(const float *__restrict__ X, long long N, long long ldx,
                                                                 const uint8_t *__restrict__ image, int M, int mr,
                                                                 uint8_t *__restrict__ codes) {
     using P = Bf16Plan<DSUB>;
@@ -441,28 +441,37 @@ __global__ __launch_bounds__(256, 3) void pq_encode_bf16_kernel(const float *__r
             // block number replaces the three lowest mantissa bits of the (non-negative) value and the
             // minimum is taken on the bit patterns, so the lower block wins among equal values; one
             // three-way minimum folds two tagged values into the running one (1.5 ALU instructions
-            // per value).  One half f of the rows at a time keeps the accumulators at 32 registers.
+            // per value).
+            //
+            // Eight stages per sub-block, stage = (pair of centre blocks, half f of the rows): 2 x
+            // (products + norm) matrix instructions into one accumulator pair.  Matrix instructions
+            // and vector work overlap inside a wave's own instruction stream, hardly between waves,
+            // so the loop is software-pipelined by hand: the instructions of stage s are interleaved
+            // with the folding of stage s - 1 (scheduling hints: one matrix instruction, then a few
+            // ALU ones), on two accumulator pairs in turn.  Fully unrolled, so the block numbers are
+            // instruction constants.
             int best[2][16];
-            auto two_blocks = [&](int cb0, auto first) {
-                // The two block numbers as separate opaque scalars: seen as cb0 and cb0 + 1 the compiler
-                // turns (bits & ~7) | tag into an AND and an ADD; like this it is one v_and_or_b32.
-                int tag0 = cb0, tag1 = cb0 + 1;
-                asm("" : "+s"(tag0));
-                asm("" : "+s"(tag1));
-                u32x4 cp[2][P::kEntries], cnorm[2];
+            u32x4 cp[2][P::kEntries], cnorm[2];
+            float16v accs[2][2];                           // [stage parity][block of the pair]
+            constexpr int kStages = 2 * (kPqK / 64);
+            constexpr int kInstr = 2 * (P::kProducts + (P::kNormInstr ? 1 : 0));   // matrix instructions per stage
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
+            for (int st = 0; st <= kStages; ++st) {
+                if (st < kStages) {
+                    const int cb0 = 2 * (st >> 1), f = st & 1;
+                    if (f == 0) {
 #pragma unroll
-                    for (int t = 0; t < P::kEntries; ++t)
-                        cp[e][t] = *reinterpret_cast<const u32x4 *>(img[buf] + ((t * 2 + h) * kPqK + 32 * (cb0 + e) + r) * 16);
-                    if (P::kNormInstr) {
-                        const uint2 nn = *reinterpret_cast<const uint2 *>(img[buf] + kImgPieces + (32 * (cb0 + e) + r) * 8);
-                        cnorm[e] = u32x4{kBf16One | (kBf16One << 16), nn.x, nn.y, 0u};
+                        for (int e = 0; e < 2; ++e) {
+#pragma unroll
+                            for (int t = 0; t < P::kEntries; ++t)
+                                cp[e][t] = *reinterpret_cast<const u32x4 *>(img[buf] + ((t * 2 + h) * kPqK + 32 * (cb0 + e) + r) * 16);
+                            if (P::kNormInstr) {
+                                const uint2 nn = *reinterpret_cast<const uint2 *>(img[buf] + kImgPieces + (32 * (cb0 + e) + r) * 8);
+                                cnorm[e] = u32x4{kBf16One | (kBf16One << 16), nn.x, nn.y, 0u};
+                            }
+                        }
                     }
-                }
-#pragma unroll
-                for (int f = 0; f < 2; ++f) {
-                    float16v acc[2];
+                    float16v(&acc)[2] = accs[st & 1];
 #pragma unroll
                     for (int e = 0; e < 2; ++e)
 #pragma unroll
@@ -475,17 +484,27 @@ __global__ __launch_bounds__(256, 3) void pq_encode_bf16_kernel(const float *__r
 #pragma unroll
                         for (int e = 0; e < 2; ++e) acc[e] = mfma_bf16(xn[f], cnorm[e], acc[e]);
                     }
-                    // accumulator element v of lane (r, h): row 8 (v / 4) + 4 h + v % 4 of the half, centre slot 32 cb + r
+                }
+                if (st > 0) {
+                    // fold the stage before: accumulator element v of lane (r, h) is row 8 (v / 4) + 4 h + v % 4
+                    // of the half, centre slot 32 cb + r
+                    const int pst = st - 1, cb0 = 2 * (pst >> 1), f = pst & 1;
+                    const float16v(&acc)[2] = accs[pst & 1];
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        const int ka = (__float_as_int(acc[0][v]) & ~7) | tag0, kb = (__float_as_int(acc[1][v]) & ~7) | tag1;
-                        best[f][v] = first.value ? min(ka, kb) : min(min(ka, kb), best[f][v]);
+                        const int ka = (__float_as_int(acc[0][v]) & ~7) | cb0, kb = (__float_as_int(acc[1][v]) & ~7) | (cb0 + 1);
+                        best[f][v] = cb0 == 0 ? min(ka, kb) : min(min(ka, kb), best[f][v]);
                     }
                 }
-            };
-            two_blocks(0, std::true_type{});
-#pragma unroll 1
-            for (int cb0 = 2; cb0 < kPqK / 32; cb0 += 2) two_blocks(cb0, std::false_type{});
+                if (st > 0 && st < kStages) {
+#pragma unroll
+                    for (int g = 0; g < kInstr; ++g) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one matrix instruction
+                        __builtin_amdgcn_sched_group_barrier(0x002, (48 + kInstr - 1) / kInstr, 0);   // its share of the 48 folding instructions
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);         // a stage and the fold beside it are one scheduling region
+            }
             {                                              // the next sub-block's components (the last one re-reads)
                 const int mn = m + 1 < m_end ? m + 1 : m;
 #pragma unroll
