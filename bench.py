@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Throughput of the ranking hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dense|pq|binary|multiquery]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dense|pq|binary|multiquery|dense128]
                     [--no-others] [--no-cpu-baseline]
 
 A step is one ranking pass of the workload: score every stored row with the current model and
@@ -46,6 +46,9 @@ WORKLOADS = {
     "binary": dict(name="binary_50Mx2048bit_top1000", N=50_000_000, D=2048, k=1000, row_bytes=256, dtype="f32"),
     "multiquery": dict(name="multiquery_5Mx2048_fp16_Q64_top1000", N=5_000_000, D=2048, Q=64, k=1000,
                        row_bytes=4096, dtype="f16"),
+    # the paper's own feature size (Sec. 3, Table 2: CNN 128), ten times its ~1M images so that the
+    # scan and not the launches is what is timed
+    "dense128": dict(name="dense_10Mx128_fp32_top1000", N=10_000_000, D=128, k=1000, row_bytes=512, dtype="f32"),
 }
 
 
@@ -55,9 +58,9 @@ def make_workload(kind, scale, torch, binding, synth):
     N = max(1024, int(cfg["N"] * scale))
     cfg["N"] = N
     dev = "cuda"
-    seed = synth.BASE_SEED + {"dense": 2, "pq": 3, "binary": 4, "multiquery": 5}[kind]
+    seed = synth.BASE_SEED + {"dense": 2, "pq": 3, "binary": 4, "multiquery": 5, "dense128": 8}[kind]
     k = cfg["k"]
-    if kind == "dense":
+    if kind in ("dense", "dense128"):
         X = synth.dense_features(N, cfg["D"], seed, device=dev)
         w = synth.normal_vector(cfg["D"], 0.05, seed + 100, device=dev)
         ws = binding.make_workspace(N, k, 1, dev)
@@ -269,8 +272,8 @@ def cpu_baseline(kind, cfg, torch):
     keep = cfg["_keep"]
     k = cfg["k"]
     budget_s = 10.0
-    if kind == "dense":
-        rows = min(cfg["N"], 262144)
+    if kind in ("dense", "dense128"):
+        rows = min(cfg["N"], 262144 if kind == "dense" else 1 << 21)
         X = keep[0][:rows].cpu().numpy()
         w = keep[1].cpu().numpy()
         run = lambda: orc.topk(orc.dense_scores(X, w)[0], min(k, rows))
