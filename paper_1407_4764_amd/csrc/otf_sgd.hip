@@ -56,14 +56,26 @@ __global__ __launch_bounds__(1024) void sgd_update_kernel(float *__restrict__ w,
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int d = blockIdx.x * 64 + lane;
     const int B = n_pos + n_neg;
+    // A wave adds its rows j = wave, wave + 16, ... in that order.  The loads of 16 of them are
+    // issued together (coefficients, then row numbers, then the values of the violators): taken one
+    // row at a time this loop was a chain of dependent memory latencies, 10 us for a batch of 256.
     float acc = 0.f;
     if (d < D) {
-        for (int j = wave; j < B; j += 16) {
-            const float c = coef[j];                 // same for the whole wave: uniform branch
-            if (c != 0.f) {
-                const float *x = batch_row(j, Xpos, ld_pos, idx_pos, n_pos, Xneg, ld_neg, idx_neg);
-                acc = fmaf(c, x[d], acc);
+        for (int j0 = wave; j0 < B; j0 += 16 * 16) {
+            float c[16], xv[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int j = j0 + 16 * i;
+                c[i] = j < B ? coef[j] : 0.f;        // same for the whole wave
             }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                xv[i] = 0.f;
+                if (c[i] != 0.f)                     // uniform: only violators are read
+                    xv[i] = batch_row(j0 + 16 * i, Xpos, ld_pos, idx_pos, n_pos, Xneg, ld_neg, idx_neg)[d];
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc = fmaf(c[i], xv[i], acc);
         }
     }
     part[wave][lane] = acc;
