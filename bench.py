@@ -163,6 +163,29 @@ def measure_sgd(torch, binding, synth):
     return {"workload": "pegasos_pass_125steps_B256_D2048", "ms_per_pass": dt * 1e3, "us_per_step": dt / steps * 1e6}
 
 
+def measure_topk(torch, binding, synth):
+    """otf_topk on ready-made scores: the exact sorted top 1000 of 50M fp32 scores (the size of the
+    binary store), one classifier.  A radix select reads the scores four times (three histogram
+    passes and the gather); the lower bound is one read."""
+    N, k = 50_000_000, 1000
+    S = synth.normal_vector(N, 1.0, synth.BASE_SEED + 9, device="cuda")
+    ws = binding.make_workspace(N, k, 1, "cuda")
+    out = binding._outputs(1, k, "cuda")
+    for _ in range(3):
+        binding.topk(S, k, ws, out=out)
+    reps = 20
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        binding.topk(S, k, ws, out=out)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    return {"workload": "topk_50M_scores_k1000", "ms_per_call": dt * 1e3, "scores_per_s": N / dt,
+            "roofline": {"bound": "hbm", "achieved": 4.0 * N / dt / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": 4.0 * N / dt / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                         "note": "algorithmic bytes = one read of the scores; the passes read them four times"}}
+
+
 def measure_onthefly(torch, binding, synth, X=None):
     """The on-the-fly loop on the dense store (paper Sec. 4, "On-line (GPU back-end)"): 12 rounds of
     64 Pegasos steps (B = 256) on a pool of positives growing by 12 per round, each followed by a
@@ -391,6 +414,7 @@ def main():
             torch.cuda.empty_cache()
             others.append(r)
         others.append(measure_sgd(torch, binding, synth))
+        others.append(measure_topk(torch, binding, synth))
         others.append(measure_encoder(torch, binding, synth))
         others.append(loop if loop is not None else measure_onthefly(torch, binding, synth))
         others.append(pqenc if pqenc is not None else measure_pq_encoder(torch, binding, synth))
