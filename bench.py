@@ -347,6 +347,8 @@ def main():
     ap.add_argument("--encoder-only", action="store_true", help="only time the binarisation encoder")
     ap.add_argument("--loop-only", action="store_true", help="only run the on-the-fly loop")
     ap.add_argument("--pqenc-only", action="store_true", help="only time the PQ encoder and a Lloyd iteration")
+    ap.add_argument("--topk-only", action="store_true", help="only time otf_topk on ready-made scores")
+    ap.add_argument("--sgd-only", action="store_true", help="only time the Pegasos training pass")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 2 GiB five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -369,6 +371,12 @@ def main():
 
     if args.encoder_only:
         print(json.dumps(measure_encoder(torch, binding, synth)))
+        return
+    if args.topk_only:
+        print(json.dumps(measure_topk(torch, binding, synth)))
+        return
+    if args.sgd_only:
+        print(json.dumps(measure_sgd(torch, binding, synth)))
         return
     if args.pqenc_only:
         print(json.dumps(measure_pq_encoder(torch, binding, synth)))
