@@ -206,6 +206,31 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
 
     const bool mfma = Q > 1 && x_half && w_half && Q % 32 == 0 && D % 128 == 0 && aligned16(W);
     const uint8_t *Wb = reinterpret_cast<const uint8_t *>(W);
+
+    if (Q == 1 && dense_scan_filters(x_half, D) && filter_eligible(N, k, all_scores)) {
+        // Short rows, one classifier: sample -> threshold -> filtered scan -> sort, with the full
+        // selection behind a gate, as for the table scans.
+        SelectWs ssw = sample_select_ws(ws, L);
+        float *sample = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + L.sample_scores);
+        const int64_t Nv = sample_rows(N);
+        const int m = sample_rank(N, Nv);
+        hipError_t e = launch_select_init_both(sw, ssw, 1, s);
+        if (e == hipSuccess)
+            e = launch_dense_scan_emit(X, x_half, Nv, D, ldx, W, w_half, bias, 0, kEmitSample, sample, ssw.hist1,
+                                       &ssw.st[0].chunk_ctr[0], ssw.st, nullptr, nullptr, nullptr, nullptr, s);
+        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, 0, s);
+        ScanTimer timer(s);
+        if (e == hipSuccess)
+            e = launch_dense_scan_emit(X, x_half, N, D, ldx, W, w_half, bias, 0, kEmitFilter, nullptr, nullptr,
+                                       &sw.st[0].chunk_ctr[0], sw.st, ssw.st, ssw.hist2, sw.cand, nullptr, s);
+        timer.stop();
+        if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
+        if (e == hipSuccess)
+            e = launch_dense_scan_emit(X, x_half, N, D, ldx, W, w_half, bias, 0, kEmitScores, S, sw.hist1,
+                                       &sw.st[0].chunk_ctr[1], sw.st, nullptr, nullptr, nullptr, sw.st, s);
+        if (e == hipSuccess) e = launch_select_tail(S, N, ldS, 1, k, sw, out_scores, out_idx, 1, s);
+        return hip_status(e);
+    }
     hipError_t e = launch_select_init(sw, Q, s);
 
     // One matrix-core launch per group of 64 (or a last 32) classifiers.

@@ -217,21 +217,40 @@ __device__ __forceinline__ void tile_row_sums(float *v, int lane) {
 // kernel: tiles are handed out dynamically (TileQueue, chunks of 256 KiB of rows), the loads of a
 // wave's next tile are issued before the current one is reduced, and a prefetch with nothing left
 // re-reads the current tile.  The rows after the last full tile go to one wave, row-checked.
-template <bool XHALF, int LPR>
+//
+// EMIT (ScanEmit) as in the table scans: every score plus the pass-1 histogram; the same for the
+// strided sample of the store (N = rows of the sample, numbered compactly); or, given the state
+// that passes 1 and 2 over the sample left, only the rows at or above the threshold, appended to
+// the candidate list.  With rows this short one score per row is a store every few hundred bytes
+// of the stream, and leaving it out is worth 7-11 % of the scan.
+template <bool XHALF, int LPR, int EMIT>
 __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__restrict__ X, long long N, int D,
                                                            long long row_bytes, const void *__restrict__ w,
                                                            int w_is_half, const float *__restrict__ bias_ptr, int bias_index,
                                                            float *__restrict__ scores, uint32_t *hist1,
-                                                           uint32_t *chunk_ctr) {
+                                                           uint32_t *chunk_ctr, SelState *st,
+                                                           const SelState *tau_state, const uint32_t *tau_hist2,
+                                                           unsigned long long *__restrict__ cand, const SelState *gate) {
     constexpr int E = Elem<XHALF>::kPer16;
     constexpr int RPW = 64 / LPR;   // rows per wave load
     constexpr int U = 8;
     constexpr int TILE = RPW * U;   // rows per wave iteration (U KiB of a dense store)
+    static_assert(kSampleGroup % TILE == 0, "a tile of the sample scan must not straddle a sample group");
+    static_assert(kBins2 <= kBins1, "the histogram area doubles as the buffer that resolves the threshold");
     __shared__ uint32_t lhist[kBins1];
+    __shared__ uint32_t s_out[3];
     __shared__ TileQueue s_queue;
-    if (threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);
-    for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
-    __syncthreads();
+    if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
+    if (threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);   // visible after the barriers below
+    uint32_t tau = 0u;
+    if (EMIT == kEmitFilter) {
+        // top 24 bits of the sample key of the requested rank, resolved by every workgroup for itself
+        const BinChoice r2 = block_find_bin(tau_hist2, kBins2, tau_state->need1, lhist, s_out);
+        tau = ((tau_state->b1 << 12) | r2.bin) << 8;
+    } else {
+        for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
+        __syncthreads();
+    }
 
     const float bias = bias_ptr ? bias_ptr[bias_index] : 0.f;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -245,8 +264,14 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
     const long long ntiles = N / TILE;
     const uint32_t chunk_tiles = tile_queue_chunk_tiles(ntiles, 256u / (uint32_t)U);
     const size_t lane_off = (size_t)rr * (size_t)row_bytes + (size_t)sub * 16;
+    // sample row v is store row (v / group) * group * stride + v % group
+    auto store_row = [&](long long v) {
+        return EMIT == kEmitSample
+                   ? (v / kSampleGroup) * ((long long)kSampleGroup * kSampleStride) + (v % kSampleGroup)
+                   : v;
+    };
     auto fetch = [&](Chunk16 *c, long long tile) {
-        const uint8_t *p = X + (size_t)tile * TILE * (size_t)row_bytes + lane_off;
+        const uint8_t *p = X + (size_t)store_row(tile * TILE) * (size_t)row_bytes + lane_off;
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (live) c[u] = load_stream16(p + (size_t)u * RPW * (size_t)row_bytes);
@@ -277,8 +302,17 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
             const long long row = tile * TILE + (long long)(u0 + k) * RPW + rr;
             const bool ok = owner && row < nrows;
             const float sc = v[k] + bias;
-            if (ok) scores[row] = sc;
-            hist_add_wave(lhist, float_to_key(sc) >> 20, ok);   // many rows per instruction, few bins: aggregate
+            const uint32_t key = float_to_key(sc);
+            if (EMIT == kEmitFilter) {
+                if (ok && key >= tau) {
+                    const uint32_t pos = atomicAdd(&st->cursor, 1u);
+                    if (pos < (uint32_t)kCandCap)
+                        cand[pos] = ((unsigned long long)key << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)row);
+                }
+            } else {
+                if (ok) scores[row] = sc;
+                hist_add_wave(lhist, key >> 20, ok);   // many rows per instruction, few bins: aggregate
+            }
         }
     };
     long long cur = tile_queue_draw(&s_queue, chunk_ctr, chunk_tiles, ntiles);
@@ -304,11 +338,11 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
         for (int u = 0; u < U; ++u) {
             const long long row = ntiles * TILE + (long long)u * RPW + rr;
             c[u] = Chunk16{};
-            if (live && row < N) c[u] = load_stream16(X + (size_t)row * (size_t)row_bytes + (size_t)sub * 16);
+            if (live && row < N) c[u] = load_stream16(X + (size_t)store_row(row) * (size_t)row_bytes + (size_t)sub * 16);
         }
         consume(c, ntiles, N);
     }
-    merge_hist(lhist, kBins1, hist1);
+    if (EMIT != kEmitFilter) merge_hist(lhist, kBins1, hist1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -362,10 +396,20 @@ __global__ __launch_bounds__(256) void dense_huge_kernel(const uint8_t *__restri
     merge_hist(lhist, kBins1, hist1);
 }
 
+// What the narrow kernel may be asked for beyond plain scores.
+struct NarrowExtra {
+    ScanEmit emit;
+    SelState *st;
+    const SelState *tau;
+    const uint32_t *tau_hist2;
+    unsigned long long *cand;
+    const SelState *gate;
+};
+
 template <bool XHALF>
 static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t row_bytes, const void *w,
                                      int w_is_half, const float *bias_ptr, int bias_index, float *scores,
-                                     uint32_t *hist1, uint32_t *chunk_ctr, hipStream_t s) {
+                                     uint32_t *hist1, uint32_t *chunk_ctr, const NarrowExtra &x, hipStream_t s) {
     constexpr int E = Elem<XHALF>::kPer16;
     const int chunks = (D + E - 1) / E;              // 16-byte chunks per row
     const int cus = device_cu_count();
@@ -379,15 +423,29 @@ static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t
         int64_t waves = (N + rows_per_wave_iter - 1) / rows_per_wave_iter;
         grid = (int)std::min<int64_t>((waves + 3) / 4, (int64_t)cus * tune_int("OTF_NARROW_BLOCKS_PER_CU", 2));
         if (grid < 1) grid = 1;
+#define OTF_NARROW(L)                                                                                              \
+    do {                                                                                                           \
+        if (x.emit == kEmitScores)                                                                                 \
+            dense_narrow_kernel<XHALF, L, kEmitScores><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS, x.st, x.tau, x.tau_hist2, \
+                                                                             x.cand, x.gate);                      \
+        else if (x.emit == kEmitSample)                                                                            \
+            dense_narrow_kernel<XHALF, L, kEmitSample><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS, x.st, x.tau, x.tau_hist2, \
+                                                                             x.cand, x.gate);                      \
+        else                                                                                                       \
+            dense_narrow_kernel<XHALF, L, kEmitFilter><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS, x.st, x.tau, x.tau_hist2, \
+                                                                             x.cand, x.gate);                      \
+    } while (0)
         switch (lpr) {
-            case 1: dense_narrow_kernel<XHALF, 1><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS); break;
-            case 2: dense_narrow_kernel<XHALF, 2><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS); break;
-            case 4: dense_narrow_kernel<XHALF, 4><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS); break;
-            case 8: dense_narrow_kernel<XHALF, 8><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS); break;
-            case 16: dense_narrow_kernel<XHALF, 16><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS); break;
-            default: dense_narrow_kernel<XHALF, 32><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS); break;
+            case 1: OTF_NARROW(1); break;
+            case 2: OTF_NARROW(2); break;
+            case 4: OTF_NARROW(4); break;
+            case 8: OTF_NARROW(8); break;
+            case 16: OTF_NARROW(16); break;
+            default: OTF_NARROW(32); break;
         }
+#undef OTF_NARROW
     } else {
+        if (x.emit != kEmitScores || x.gate) return hipErrorInvalidValue;   // only the narrow kernel filters
         grid = (int)std::min<int64_t>((N + 3) / 4, (int64_t)cus * tune_int("OTF_DENSE_BLOCKS_PER_CU", 1));
         if (grid < 1) grid = 1;
         const int V = (chunks + 63) / 64;
@@ -415,13 +473,29 @@ static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t
     return hipGetLastError();
 }
 
+bool dense_scan_filters(int x_is_half, int D) {
+    const int per16 = x_is_half ? 8 : 4;
+    return (D + per16 - 1) / per16 <= 32;
+}
+
 hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int64_t ldx, const void *w,
                              int w_is_half, const float *bias_ptr, int bias_index, float *scores, uint32_t *hist1,
                              uint32_t *chunk_ctr, hipStream_t s) {
+    return launch_dense_scan_emit(X, x_is_half, N, D, ldx, w, w_is_half, bias_ptr, bias_index, kEmitScores, scores,
+                                  hist1, chunk_ctr, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+}
+
+hipError_t launch_dense_scan_emit(const void *X, int x_is_half, int64_t N, int D, int64_t ldx, const void *w,
+                                  int w_is_half, const float *bias_ptr, int bias_index, ScanEmit emit, float *scores,
+                                  uint32_t *hist1, uint32_t *chunk_ctr, SelState *st, const SelState *tau,
+                                  const uint32_t *tau_hist2, unsigned long long *cand, const SelState *gate,
+                                  hipStream_t s) {
     const uint8_t *Xb = reinterpret_cast<const uint8_t *>(X);
+    const NarrowExtra x{emit, st, tau, tau_hist2, cand, gate};
+    if (emit == kEmitFilter && (!st || !tau || !tau_hist2 || !cand)) return hipErrorInvalidValue;
     if (x_is_half)
-        return launch_dense_typed<true>(Xb, N, D, ldx * 2, w, w_is_half, bias_ptr, bias_index, scores, hist1, chunk_ctr, s);
-    return launch_dense_typed<false>(Xb, N, D, ldx * 4, w, w_is_half, bias_ptr, bias_index, scores, hist1, chunk_ctr, s);
+        return launch_dense_typed<true>(Xb, N, D, ldx * 2, w, w_is_half, bias_ptr, bias_index, scores, hist1, chunk_ctr, x, s);
+    return launch_dense_typed<false>(Xb, N, D, ldx * 4, w, w_is_half, bias_ptr, bias_index, scores, hist1, chunk_ctr, x, s);
 }
 
 }  // namespace otf

@@ -39,6 +39,8 @@ inline int64_t sample_rows(int64_t N) {
 
 // Zeroes the selection state and the pass-1/2 histograms of Q classifiers.
 hipError_t launch_select_init(const SelectWs &sw, int Q, hipStream_t s);
+// The same for the full selection's state and the sample's in one launch.
+hipError_t launch_select_init_both(const SelectWs &sw, const SelectWs &sample_sw, int Q, hipStream_t s);
 // Radix pass 1 over ready-made scores (rows of length N, stride ld).
 hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const SelectWs &sw, int gated,
                         hipStream_t s);
@@ -54,11 +56,25 @@ hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64
 // End of a filtered scan: sort the appended candidates or raise sw.st[0].fallback.
 hipError_t launch_filter_sort(const SelectWs &sw, int Q, int k, float *out_scores, int32_t *out_idx, hipStream_t s);
 
+enum ScanEmit { kEmitScores = 0, kEmitSample = 1, kEmitFilter = 2 };
+
 // Dense single-classifier scan: writes N scores (bias included) and accumulates the pass-1 histogram.
 // chunk_ctr: a zeroed word in global memory (work counter of the dynamically scheduled kernels).
 hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int64_t ldx,
                              const void *w, int w_is_half, const float *bias_ptr, int bias_index,
                              float *scores, uint32_t *hist1, uint32_t *chunk_ctr, hipStream_t s);
+// True for rows of at most 512 bytes: those scans also come as sample and filtered scans.
+bool dense_scan_filters(int x_is_half, int D);
+// The same scan in the three forms of the table scans (narrow rows only for the last two):
+//   kEmitScores  as above; with `gate` set the kernel returns at once unless gate->fallback is raised
+//   kEmitSample  N = rows of the strided sample, numbered compactly: scores[v] + histogram
+//   kEmitFilter  rows at or above the threshold go to cand (cursor in st); every workgroup resolves
+//                the threshold from the state passes 1 and 2 over the sample left in (tau, tau_hist2)
+hipError_t launch_dense_scan_emit(const void *X, int x_is_half, int64_t N, int D, int64_t ldx, const void *w,
+                                  int w_is_half, const float *bias_ptr, int bias_index, ScanEmit emit, float *scores,
+                                  uint32_t *hist1, uint32_t *chunk_ctr, SelState *st, const SelState *tau,
+                                  const uint32_t *tau_hist2, unsigned long long *cand, const SelState *gate,
+                                  hipStream_t s);
 
 // Multi-classifier fp16 scan on the matrix cores (Q = 32 or 64 classifiers per call).
 //   kEmitScores  scores[q][i] for every row (row stride ld_scores); with `gate` set the kernel returns
@@ -66,7 +82,6 @@ hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int
 //   kEmitSample  the same for the strided sample only (compact row numbering)
 //   kEmitFilter  nothing is stored but the rows with key >= tau[q].tau_key, appended to cand[q]
 // tile_ctr: a zeroed word in global memory (the kernel hands out its tiles dynamically).
-enum ScanEmit { kEmitScores = 0, kEmitSample = 1, kEmitFilter = 2 };
 hipError_t launch_dense_mfma(const void *X, int64_t N, int D, int64_t ldx, const void *W, int Q, const float *bias,
                              ScanEmit emit, float *scores, int64_t ld_scores, const SelState *tau, SelState *st,
                              unsigned long long *cand, const SelState *gate, uint32_t *tile_ctr, hipStream_t s);

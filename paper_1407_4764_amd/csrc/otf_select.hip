@@ -28,7 +28,8 @@
 namespace otf {
 
 __global__ __launch_bounds__(256) void select_init_kernel(SelState *st, uint32_t *hist1, uint32_t *hist2,
-                                                          uint32_t *hist3, int Q) {
+                                                          uint32_t *hist3, SelState *sample_st,
+                                                          uint32_t *sample_hist1, uint32_t *sample_hist2, int Q) {
     const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t step = (size_t)gridDim.x * blockDim.x;
     uint32_t *stw = reinterpret_cast<uint32_t *>(st);
@@ -37,6 +38,12 @@ __global__ __launch_bounds__(256) void select_init_kernel(SelState *st, uint32_t
     for (size_t i = tid; i < (size_t)Q * kBins2; i += step) hist2[i] = 0u;
     if (hist3)
         for (size_t i = tid; i < (size_t)Q * kBins3; i += step) hist3[i] = 0u;
+    if (sample_st) {                                  // the state that thresholds a sample, in the same launch
+        uint32_t *sw = reinterpret_cast<uint32_t *>(sample_st);
+        for (size_t i = tid; i < (size_t)Q * (sizeof(SelState) / 4); i += step) sw[i] = 0u;
+        for (size_t i = tid; i < (size_t)Q * kBins1; i += step) sample_hist1[i] = 0u;
+        for (size_t i = tid; i < (size_t)Q * kBins2; i += step) sample_hist2[i] = 0u;
+    }
 }
 
 // Four consecutive scores of this thread for the tile starting at t0 (tile = 4 * blockDim rows);
@@ -560,7 +567,15 @@ static int sel_blocks(int64_t N, int Q) {
 hipError_t launch_select_init(const SelectWs &sw, int Q, hipStream_t s) {
     int blocks = (int)(((size_t)Q * kBins1 + 255) / 256);
     if (blocks > 1024) blocks = 1024;
-    select_init_kernel<<<blocks, 256, 0, s>>>(sw.st, sw.hist1, sw.hist2, sw.hist3, Q);
+    select_init_kernel<<<blocks, 256, 0, s>>>(sw.st, sw.hist1, sw.hist2, sw.hist3, nullptr, nullptr, nullptr, Q);
+    return hipGetLastError();
+}
+
+hipError_t launch_select_init_both(const SelectWs &sw, const SelectWs &sample_sw, int Q, hipStream_t s) {
+    int blocks = (int)(((size_t)Q * kBins1 + 255) / 256);
+    if (blocks > 1024) blocks = 1024;
+    select_init_kernel<<<blocks, 256, 0, s>>>(sw.st, sw.hist1, sw.hist2, sw.hist3, sample_sw.st, sample_sw.hist1,
+                                              sample_sw.hist2, Q);
     return hipGetLastError();
 }
 

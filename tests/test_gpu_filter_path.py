@@ -153,3 +153,60 @@ def test_filter_with_every_score_equal(oracle):
     assert binding.debug_fallback_taken(ws)
     np.testing.assert_array_equal(idx[0].cpu().numpy(), np.arange(k))
     assert torch.all(val[0] == 2.5)
+
+
+@pytest.mark.parametrize("N,D,dtype,k", [(1200003, 128, torch.float32, 1000), (1100000, 128, torch.float16, 100),
+                                         (1060000, 20, torch.float32, 7), (2100000, 4, torch.float32, 1024),
+                                         (1150016, 64, torch.float16, 1), (1100000, 256, torch.float16, 512)])
+def test_dense_short_rows_filtered_scan(oracle, N, D, dtype, k):
+    """Rows of at most 512 bytes with one classifier take the sample / filtered-scan route: every
+    lane width of that kernel, both element types, a width that leaves lanes idle (D = 20)."""
+    X = synth.dense_features(N, D, SEED + 20, dtype=dtype)
+    w = synth.normal_vector(D, 1.0, SEED + 21)
+    b = torch.tensor([0.25])
+    Xd, wd, bd = X.to(DEV), w.to(DEV), b.to(DEV)
+    ws = binding.make_workspace(N, k)
+    (val, idx), (val2, idx2) = _both_paths(lambda: binding.rank_dense(Xd, wd, bd, k, ws))
+    assert torch.equal(idx, idx2) and torch.equal(val, val2)
+    binding.rank_dense(Xd, wd, bd, k, ws)
+    assert not binding.debug_fallback_taken(ws)
+    ref = oracle.dense_scores(X.numpy(), w.numpy()[None, :], b.numpy())[0]
+    ok, msg = oracle.topk_parity_ok(ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(),
+                                    RTOL16 if dtype == torch.float16 else RTOL32)
+    assert ok, msg
+
+
+def test_dense_short_rows_filter_falls_back(oracle):
+    """The dense filtered scan's three ways to fail: every score equal (a zero model), maximal rows
+    only inside the sampled groups (too few pass), maximal rows only outside them (the list overflows)."""
+    N, D, k = 1200000, 128, 1000
+    X = synth.dense_features(N, D, SEED + 22)
+    w = synth.normal_vector(D, 1.0, SEED + 23)
+    ws = binding.make_workspace(N, k)
+    val, idx = binding.rank_dense(X.to(DEV), torch.zeros(D, device=DEV), torch.tensor([1.5], device=DEV), k, ws)
+    assert binding.debug_fallback_taken(ws)
+    np.testing.assert_array_equal(idx[0].cpu().numpy(), np.arange(k))
+    assert torch.all(val[0] == 1.5)
+
+    best = 64.0 * torch.sign(w)                       # scores far above every other row
+    Xa = X.clone()
+    Xa[:200] = best                                   # rows 0..199 are sampled
+    val, idx = binding.rank_dense(Xa.to(DEV), w.to(DEV), None, k, ws)
+    assert binding.debug_fallback_taken(ws)
+    ref = oracle.dense_scores(Xa.numpy(), w.numpy()[None, :], np.zeros(1, dtype=np.float32))[0]
+    ok, msg = oracle.topk_parity_ok(ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), RTOL32)
+    assert ok, msg
+    assert set(idx[0, :200].cpu().tolist()) == set(range(200))
+
+    Xb = X.clone()
+    Xb[2048:12048] = best                             # groups 2..11: never sampled
+    val, idx = binding.rank_dense(Xb.to(DEV), w.to(DEV), None, k, ws)
+    assert binding.debug_fallback_taken(ws)
+    np.testing.assert_array_equal(idx[0].cpu().numpy(), np.arange(2048, 3048))
+    assert torch.all(val[0] == val[0, 0])
+
+    val, idx = binding.rank_dense(X.to(DEV), w.to(DEV), None, k, ws)      # and the same workspace serves a plain call again
+    assert not binding.debug_fallback_taken(ws)
+    ref = oracle.dense_scores(X.numpy(), w.numpy()[None, :], np.zeros(1, dtype=np.float32))[0]
+    ok, msg = oracle.topk_parity_ok(ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), RTOL32)
+    assert ok, msg
