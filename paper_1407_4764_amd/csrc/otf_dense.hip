@@ -4,9 +4,11 @@
 //
 // Layout: a row is read by `LPR` adjacent lanes, 16 bytes per lane per load, so every wave
 // load covers whole 1 KiB-contiguous pieces of the store; w sits in registers (each lane keeps
-// the columns it reads).  Rows are dealt to waves round-robin and several rows are in flight
-// per wave.  Each finished score is written once and counted into the block's pass-1
-// histogram of the top-k selection, so ranking needs no further pass over the store.
+// the columns it reads).  Waves draw their rows from a work queue and keep the next tile's loads
+// in flight while they reduce the current one.  Each finished score is written once and counted
+// into the block's pass-1 histogram of the top-k selection, so ranking needs no further pass
+// over the store; rows of at most 512 bytes can instead be filtered against a threshold taken
+// from a sample, in which case the scan writes only the few rows that pass.
 #include <hip/hip_fp16.h>
 
 #include <algorithm>

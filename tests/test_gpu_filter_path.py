@@ -210,3 +210,22 @@ def test_dense_short_rows_filter_falls_back(oracle):
     ref = oracle.dense_scores(X.numpy(), w.numpy()[None, :], np.zeros(1, dtype=np.float32))[0]
     ok, msg = oracle.topk_parity_ok(ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), RTOL32)
     assert ok, msg
+
+
+def test_dense_short_rows_filtered_scan_strided_store(oracle):
+    """The same route on a store whose rows are a slice of wider rows (row stride 128, 96 columns
+    used: the last 8 of the 32 lanes of a row load nothing)."""
+    N, D, ld, k = 1100032, 96, 128, 300
+    wide = synth.dense_features(N, ld, SEED + 24)
+    w = synth.normal_vector(D, 1.0, SEED + 25)
+    Xd = wide.to(DEV)[:, 16:16 + D]
+    assert Xd.stride(0) == ld
+    ws = binding.make_workspace(N, k)
+    (val, idx), (val2, idx2) = _both_paths(lambda: binding.rank_dense(Xd, w.to(DEV), None, k, ws))
+    assert torch.equal(idx, idx2) and torch.equal(val, val2)
+    binding.rank_dense(Xd, w.to(DEV), None, k, ws)
+    assert not binding.debug_fallback_taken(ws)
+    ref = oracle.dense_scores(np.ascontiguousarray(wide.numpy()[:, 16:16 + D]), w.numpy()[None, :],
+                              np.zeros(1, dtype=np.float32))[0]
+    ok, msg = oracle.topk_parity_ok(ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), RTOL32)
+    assert ok, msg
