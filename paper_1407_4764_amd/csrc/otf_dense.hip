@@ -425,6 +425,9 @@ static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t
         int64_t waves = (N + rows_per_wave_iter - 1) / rows_per_wave_iter;
         grid = (int)std::min<int64_t>((waves + 3) / 4, (int64_t)cus * tune_int("OTF_NARROW_BLOCKS_PER_CU", 2));
         if (grid < 1) grid = 1;
+        // the short sample scan ends in every workgroup adding to the same hundred-odd bins of the
+        // global histogram at once: one workgroup per compute unit halves that queue (20.6 -> 16.7 us)
+        if (x.emit == kEmitSample) grid = std::min(grid, cus);
 #define OTF_NARROW(L)                                                                                              \
     do {                                                                                                           \
         if (x.emit == kEmitScores)                                                                                 \
