@@ -183,7 +183,7 @@ def measure_topk(torch, binding, synth):
     return {"workload": "topk_50M_scores_k1000", "ms_per_call": dt * 1e3, "scores_per_s": N / dt,
             "roofline": {"bound": "hbm", "achieved": 4.0 * N / dt / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": 4.0 * N / dt / 1e9 / HBM_PEAK_GBS, "traffic": None,
-                         "note": "algorithmic bytes = one read of the scores; the passes read them four times"}}
+                         "note": "algorithmic bytes = one read of the scores; the selection reads them twice here (histogram pass and gather; the two refining passes return at once when the first is decisive)"}}
 
 
 def measure_onthefly(torch, binding, synth, X=None):

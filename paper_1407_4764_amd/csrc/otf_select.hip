@@ -98,7 +98,7 @@ __device__ __forceinline__ void for_each_score(const float *s, long long begin, 
     }
 }
 
-__global__ __launch_bounds__(512) void hist1_kernel(const float *__restrict__ scores, long long N, long long ld,
+__global__ __launch_bounds__(1024) void hist1_kernel(const float *__restrict__ scores, long long N, long long ld,
                                                     SelState *st_all, uint32_t *hist1_all, int gated) {
     __shared__ uint32_t lhist[kBins1];
     if (gated && st_all[0].fallback == 0u) return;
@@ -581,11 +581,13 @@ hipError_t launch_select_init_both(const SelectWs &sw, const SelectWs &sample_sw
 
 hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const SelectWs &sw, int gated,
                         hipStream_t s) {
-    // A plain histogram, free of the per-block tables of the later passes, so it may use more blocks:
-    // each processes its loads before asking for the next, and four blocks per compute unit overlap that.
-    int64_t blocks = std::min<int64_t>((N + 8191) / 8192, std::max<int64_t>(1, (int64_t)device_cu_count() * 4 / Q));
+    // A plain histogram, free of the per-block tables of the later passes.  Every workgroup ends by
+    // adding its bins to the global histogram, and the scores crowd into a hundred-odd bins, so the
+    // adds to one bin queue up (~18 ns each) when the workgroups finish together: few, large
+    // workgroups (one of 1024 threads per compute unit: 35 us for 50M scores; four of 512: 42 us).
+    int64_t blocks = std::min<int64_t>((N + 8191) / 8192, std::max<int64_t>(1, (int64_t)device_cu_count() / Q));
     blocks = std::max<int64_t>(blocks, sel_blocks(N, Q));
-    hist1_kernel<<<dim3((unsigned)blocks, Q), 512, 0, s>>>(scores, N, ld, sw.st, sw.hist1, gated);
+    hist1_kernel<<<dim3((unsigned)blocks, Q), 1024, 0, s>>>(scores, N, ld, sw.st, sw.hist1, gated);
     return hipGetLastError();
 }
 
