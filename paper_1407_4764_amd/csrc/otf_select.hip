@@ -349,10 +349,47 @@ __global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ s
 constexpr int kSortThreads = 1024;
 constexpr int kSortLdsBytes = kBins1 * 4 + kCandCap * 8;
 
-__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int mask) {
-    const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)v, mask, 64);
-    const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(v >> 32), mask, 64);
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, CTRL, 0xF, 0xF, true);
+}
+// The 32-bit value of lane ^ BIT, through the vector ALU's own lane exchanges (data-parallel moves
+// within a row of 16 lanes, v_permlane16_swap / v_permlane32_swap across rows and halves) instead
+// of a shuffle through shared memory, whose latency a chain of dependent sorting steps pays in full.
+template <int BIT>
+__device__ __forceinline__ uint32_t lane_xor_u32(uint32_t v) {
+    if constexpr (BIT == 1) return dpp_u32<0xB1>(v);                       // quad_perm [1,0,3,2]
+    else if constexpr (BIT == 2) return dpp_u32<0x4E>(v);                  // quad_perm [2,3,0,1]
+    else if constexpr (BIT == 4) return dpp_u32<0x1B>(dpp_u32<0x141>(v));  // half mirror, then quad reversed
+    else if constexpr (BIT == 8) return dpp_u32<0x128>(v);                 // row_ror:8
+    else {
+        // swap(v, v): [0] = the value of the lane with bit BIT clear, [1] = of the one with it set
+        const bool up = (threadIdx.x & BIT) != 0;
+        if constexpr (BIT == 16) {
+            const auto sw = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+            return up ? sw[0] : sw[1];
+        } else {
+            static_assert(BIT == 32, "lane bit");
+            const auto sw = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+            return up ? sw[0] : sw[1];
+        }
+    }
+}
+template <int BIT>
+__device__ __forceinline__ unsigned long long lane_xor_u64(unsigned long long v) {
+    const uint32_t lo = lane_xor_u32<BIT>((uint32_t)v), hi = lane_xor_u32<BIT>((uint32_t)(v >> 32));
     return ((unsigned long long)hi << 32) | lo;
+}
+// One compare-exchange step of the bitonic network between lanes BIT apart.
+template <int E, int BIT>
+__device__ __forceinline__ void wave_exchange(unsigned long long *r, uint32_t size, uint32_t tid) {
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+        const uint32_t e = (uint32_t)j * kSortThreads + tid;
+        const unsigned long long y = lane_xor_u64<BIT>(r[j]);
+        const bool keep_larger = ((e & (uint32_t)BIT) == 0u) == ((e & size) == 0u);
+        r[j] = keep_larger ? (r[j] > y ? r[j] : y) : (r[j] < y ? r[j] : y);
+    }
 }
 
 // Sorts a[0..P) descending.  P is a power of two, 64 <= P <= 1024 * E, and E = max(1, P / 1024).
@@ -395,14 +432,16 @@ __device__ __forceinline__ void bitonic_desc(unsigned long long *a, uint32_t P) 
                         r[j] = keep_larger ? (r[j] > y ? r[j] : y) : (r[j] < y ? r[j] : y);
                     }
                 }
-            } else {                                              // partner in this wave
-#pragma unroll
-                for (int j = 0; j < E; ++j) {
-                    const uint32_t e = (uint32_t)j * kSortThreads + tid;
-                    const unsigned long long y = shfl_xor_u64(r[j], (int)stride);
-                    const bool keep_larger = ((e & stride) == 0u) == ((e & size) == 0u);
-                    r[j] = keep_larger ? (r[j] > y ? r[j] : y) : (r[j] < y ? r[j] : y);
+            } else {                                              // this and all smaller strides: partners in this wave
+                switch (stride) {
+                    case 32: wave_exchange<E, 32>(r, size, tid); [[fallthrough]];
+                    case 16: wave_exchange<E, 16>(r, size, tid); [[fallthrough]];
+                    case 8: wave_exchange<E, 8>(r, size, tid); [[fallthrough]];
+                    case 4: wave_exchange<E, 4>(r, size, tid); [[fallthrough]];
+                    case 2: wave_exchange<E, 2>(r, size, tid); [[fallthrough]];
+                    default: wave_exchange<E, 1>(r, size, tid);
                 }
+                break;
             }
         }
     }
