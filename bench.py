@@ -37,6 +37,7 @@ MEASURED_TRAFFIC_BYTES = {          # read + written, profiles/traffic_counters.
     "pq": 2.589e9 + 0.5e6,
     "binary": 12.829e9 + 1.8e6,
     "multiquery": 20.480e9 + 16.5e6,
+    "dense128": 5.132e9 + 0.9e6,
 }
 
 WORKLOADS = {
