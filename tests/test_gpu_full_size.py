@@ -57,6 +57,27 @@ def test_dense_full_size(oracle):
     assert np.all(np.abs(got - ref) <= 1e-4 * np.maximum(np.abs(ref), sigma))
 
 
+def test_dense_128d_full_size(oracle):
+    """The paper's own feature size, 10M rows: the default path here is the filtered scan, the
+    all_scores call the materialising one; both must give the same list."""
+    step, cfg = bench.make_workload("dense128", 1.0, torch, binding, synth)
+    X, w = cfg["_keep"]
+    N, k = cfg["N"], cfg["k"]
+    val, idx = step()
+    torch.cuda.synchronize()
+    ws = binding.make_workspace(N, k)
+    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
+    val2, idx2 = binding.rank_dense(X, w, None, k, ws, all_scores=all_scores)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(val, val2)
+    _check_list_against_own_scores(all_scores, idx[0], val[0], k)
+    rows = np.union1d(_sample_rows(N, 6), idx[0].cpu().numpy())
+    ref = oracle.dense_scores(X[torch.from_numpy(rows).to(DEV)].cpu().numpy(), w.cpu().numpy())[0]
+    got = all_scores[torch.from_numpy(rows).to(DEV)].cpu().numpy().astype(np.float64)
+    sigma = float(all_scores.std().item())
+    assert np.all(np.abs(got - ref) <= 1e-4 * np.maximum(np.abs(ref), sigma))
+
+
 def test_pq_full_size(oracle):
     step, cfg = bench.make_workload("pq", 1.0, torch, binding, synth)
     codes, cb, w = cfg["_keep"]
