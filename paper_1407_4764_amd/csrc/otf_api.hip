@@ -24,14 +24,14 @@ WsLayout ws_layout(int64_t N, int32_t Q) {
         return at;
     };
     L.st = take((size_t)Q * sizeof(SelState));
-    L.hist1 = take((size_t)Q * kBins1 * 4);
+    L.hist1 = take((size_t)Q * kHist1Words * 4);
     L.hist2 = take((size_t)Q * kBins2 * 4);
     L.hist3 = take((size_t)Q * kBins3 * 4);
     L.blockhist3 = take((size_t)Q * kSelBlocks * kBins3 * 4);
     L.eqoff = take((size_t)Q * kSelBlocks * 4);
     L.cand = take((size_t)Q * kCandCap * 8);
     L.sample_st = take((size_t)Q * sizeof(SelState));
-    L.sample_hist1 = take((size_t)Q * kBins1 * 4);
+    L.sample_hist1 = take((size_t)Q * kHist1Words * 4);
     L.sample_hist2 = take((size_t)Q * kBins2 * 4);
     L.sample_ld = padded_rows(sample_rows(N) + kSampleGroup);
     L.sample_scores = take((size_t)Q * (size_t)L.sample_ld * 4);
@@ -276,7 +276,7 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
     } else if (e == hipSuccess) {
         for (int q = 0; q < Q && e == hipSuccess; ++q)
             e = launch_dense_scan(X, x_half, N, D, ldx, Wb + (size_t)q * D * wsize, w_half, bias, q,
-                                  S + (size_t)q * ldS, sw.hist1 + (size_t)q * kBins1, &sw.st[q].chunk_ctr[1], s);
+                                  S + (size_t)q * ldS, sw.hist1 + (size_t)q * kHist1Words, &sw.st[q].chunk_ctr[1], s);
         timer.stop();
     }
     if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, 0, s);

@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(const uint8_t *__restri
             emit(r, dot(c));
         }
     }
-    merge_hist(lhist, kBins1, hist1);
+    merge_hist1(lhist, hist1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -344,7 +344,7 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
         }
         consume(c, ntiles, N);
     }
-    if (EMIT != kEmitFilter) merge_hist(lhist, kBins1, hist1);
+    if (EMIT != kEmitFilter) merge_hist1(lhist, hist1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -395,7 +395,7 @@ __global__ __launch_bounds__(256) void dense_huge_kernel(const uint8_t *__restri
             atomicAdd(&lhist[float_to_key(acc) >> 20], 1u);
         }
     }
-    merge_hist(lhist, kBins1, hist1);
+    merge_hist1(lhist, hist1);
 }
 
 // What the narrow kernel may be asked for beyond plain scores.

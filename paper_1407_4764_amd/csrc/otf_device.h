@@ -9,6 +9,12 @@ constexpr int kWave = 64;
 constexpr int kBins1 = 4096;   // radix pass 1: key bits 31..20
 constexpr int kBins2 = 4096;   // radix pass 2: key bits 19..8
 constexpr int kBins3 = 256;    // radix pass 3: key bits 7..0
+// The pass-1 histogram of a classifier is kept in kHistShards copies, a workgroup adding to copy
+// (its number mod kHistShards): scores crowd into a hundred-odd of the bins, the workgroups of a
+// scan finish together, and adds to one address take ~18 ns each one after the other, so a single
+// copy ends a 256-workgroup scan with a queue of ~4.6 us on every hot bin.
+constexpr int kHistShards = 4;
+constexpr int kHist1Words = kHistShards * kBins1;   // pass-1 words per classifier
 constexpr int kCandCap = 8192; // capacity of the candidate list that the final sort takes
 constexpr int kSelBlocks = 256; // blocks per classifier in the selection passes over scores
 // Filtered scans: a strided sample of the store (every kSampleStride-th group of kSampleGroup rows)
@@ -138,6 +144,10 @@ __device__ __forceinline__ void merge_hist(const uint32_t *lhist, int nbins, uin
         if (c) atomicAdd(ghist + b, c);
     }
 }
+// The same for a pass-1 histogram (ghist1: the kHist1Words words of one classifier).
+__device__ __forceinline__ void merge_hist1(const uint32_t *lhist, uint32_t *ghist1) {
+    merge_hist(lhist, kBins1, ghist1 + (blockIdx.x % (unsigned)kHistShards) * (unsigned)kBins1);
+}
 
 struct BinChoice {
     uint32_t bin, above, inbin;
@@ -146,10 +156,15 @@ struct BinChoice {
 // Whole block: loads a histogram that an EARLIER kernel completed into shared memory `lds`
 // (nbins words, nbins a multiple of 64 and at most 4096) and finds the bin of the need-th largest
 // entry.  `s_out` points at 3 words of shared memory.  Ends with a barrier; lds may be reused.
+// shards: the histogram is the sum of that many copies, nbins words apart.
 __device__ __forceinline__ BinChoice block_find_bin(const uint32_t *ghist, int nbins, uint32_t need, uint32_t *lds,
-                                                    uint32_t *s_out) {
+                                                    uint32_t *s_out, int shards = 1) {
     __syncthreads();
-    for (int b = threadIdx.x; b < nbins; b += blockDim.x) lds[b] = ghist[b];
+    for (int b = threadIdx.x; b < nbins; b += blockDim.x) {
+        uint32_t c = ghist[b];
+        for (int h = 1; h < shards; ++h) c += ghist[(size_t)h * nbins + b];
+        lds[b] = c;
+    }
     __syncthreads();
     if (threadIdx.x < 64) {
         uint32_t above, inbin;

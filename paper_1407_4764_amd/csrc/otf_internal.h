@@ -11,7 +11,7 @@ namespace otf {
 // Where the selection state of the Q classifiers lives inside the workspace.
 struct SelectWs {
     SelState *st;              // [Q]
-    uint32_t *hist1;           // [Q][kBins1]
+    uint32_t *hist1;           // [Q][kHistShards][kBins1]
     uint32_t *hist2;           // [Q][kBins2]
     uint32_t *hist3;           // [Q][kBins3]
     uint32_t *blockhist3;      // [Q][kSelBlocks][kBins3]

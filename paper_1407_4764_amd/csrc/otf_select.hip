@@ -34,14 +34,14 @@ __global__ __launch_bounds__(256) void select_init_kernel(SelState *st, uint32_t
     const size_t step = (size_t)gridDim.x * blockDim.x;
     uint32_t *stw = reinterpret_cast<uint32_t *>(st);
     for (size_t i = tid; i < (size_t)Q * (sizeof(SelState) / 4); i += step) stw[i] = 0u;
-    for (size_t i = tid; i < (size_t)Q * kBins1; i += step) hist1[i] = 0u;
+    for (size_t i = tid; i < (size_t)Q * kHist1Words; i += step) hist1[i] = 0u;
     for (size_t i = tid; i < (size_t)Q * kBins2; i += step) hist2[i] = 0u;
     if (hist3)
         for (size_t i = tid; i < (size_t)Q * kBins3; i += step) hist3[i] = 0u;
     if (sample_st) {                                  // the state that thresholds a sample, in the same launch
         uint32_t *sw = reinterpret_cast<uint32_t *>(sample_st);
         for (size_t i = tid; i < (size_t)Q * (sizeof(SelState) / 4); i += step) sw[i] = 0u;
-        for (size_t i = tid; i < (size_t)Q * kBins1; i += step) sample_hist1[i] = 0u;
+        for (size_t i = tid; i < (size_t)Q * kHist1Words; i += step) sample_hist1[i] = 0u;
         for (size_t i = tid; i < (size_t)Q * kBins2; i += step) sample_hist2[i] = 0u;
     }
 }
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(1024) void hist1_kernel(const float *__restrict__ s
     long long begin, end;
     sel_chunk(N, blockIdx.x, gridDim.x, &begin, &end);
     for_each_score(s, begin, end, vec_ok, [&](float v, bool ok, long long) { hist_add_wave(lhist, float_to_key(v) >> 20, ok); });
-    merge_hist(lhist, kBins1, hist1_all + (size_t)q * kBins1);
+    merge_hist1(lhist, hist1_all + (size_t)q * kHist1Words);
 }
 
 // Pass 2.  Resolves pass 1 first (rank k in hist1).  force: always run pass 2 (threshold
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(512) void hist2_kernel(const float *__restrict__ sc
     if (gate && gate->fallback == 0u) return;
     const int q = blockIdx.y;
     SelState *st = st_all + q;
-    const BinChoice r1 = block_find_bin(hist1_all + (size_t)q * kBins1, kBins1, (uint32_t)k, lhist, s_out);
+    const BinChoice r1 = block_find_bin(hist1_all + (size_t)q * kHist1Words, kBins1, (uint32_t)k, lhist, s_out, kHistShards);
     const uint32_t b1 = r1.bin, need1 = (uint32_t)k - r1.above, c1 = r1.above + r1.inbin;
     const bool decisive = c1 <= (uint32_t)kCandCap;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -604,14 +604,14 @@ static int sel_blocks(int64_t N, int Q) {
 }
 
 hipError_t launch_select_init(const SelectWs &sw, int Q, hipStream_t s) {
-    int blocks = (int)(((size_t)Q * kBins1 + 255) / 256);
+    int blocks = (int)(((size_t)Q * kHist1Words + 255) / 256);
     if (blocks > 1024) blocks = 1024;
     select_init_kernel<<<blocks, 256, 0, s>>>(sw.st, sw.hist1, sw.hist2, sw.hist3, nullptr, nullptr, nullptr, Q);
     return hipGetLastError();
 }
 
 hipError_t launch_select_init_both(const SelectWs &sw, const SelectWs &sample_sw, int Q, hipStream_t s) {
-    int blocks = (int)(((size_t)Q * kBins1 + 255) / 256);
+    int blocks = (int)(((size_t)Q * kHist1Words + 255) / 256);
     if (blocks > 1024) blocks = 1024;
     select_init_kernel<<<blocks, 256, 0, s>>>(sw.st, sw.hist1, sw.hist2, sw.hist3, sample_sw.st, sample_sw.hist1,
                                               sample_sw.hist2, Q);

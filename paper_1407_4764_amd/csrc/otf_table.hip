@@ -69,7 +69,7 @@ __device__ __forceinline__ void zero_states(int tid, int step, SelState *st, uin
         stw[i] = 0u;
         sstw[i] = 0u;
     }
-    for (int i = tid; i < kBins1; i += step) {
+    for (int i = tid; i < kHist1Words; i += step) {
         hist1[i] = 0u;
         shist1[i] = 0u;
     }
@@ -391,7 +391,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
             }
         }
     }
-    if (EMIT != kEmitFilter) merge_hist(lhist, kBins1, hist1);
+    if (EMIT != kEmitFilter) merge_hist1(lhist, hist1);
 }
 
 hipError_t launch_pq_build_lut(const float *codebooks, int M, int K, int dsub, const float *w, float *lut,
