@@ -217,17 +217,17 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
         hipError_t e = launch_select_init_both(sw, ssw, 1, s);
         if (e == hipSuccess)
             e = launch_dense_scan_emit(X, x_half, Nv, D, ldx, W, w_half, bias, 0, kEmitSample, sample, ssw.hist1,
-                                       &ssw.st[0].chunk_ctr[0], ssw.st, nullptr, nullptr, nullptr, nullptr, s);
-        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, 0, s);
+                                       &ssw.st[0].chunk_ctr[0], ssw.st, nullptr, nullptr, 0, nullptr, nullptr, s);
+        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, 0, nullptr, s);
         ScanTimer timer(s);
         if (e == hipSuccess)
             e = launch_dense_scan_emit(X, x_half, N, D, ldx, W, w_half, bias, 0, kEmitFilter, nullptr, nullptr,
-                                       &sw.st[0].chunk_ctr[0], sw.st, ssw.st, ssw.hist2, sw.cand, nullptr, s);
+                                       &sw.st[0].chunk_ctr[0], sw.st, ssw.st, ssw.hist2, m, sw.cand, nullptr, s);
         timer.stop();
         if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
         if (e == hipSuccess)
             e = launch_dense_scan_emit(X, x_half, N, D, ldx, W, w_half, bias, 0, kEmitScores, S, sw.hist1,
-                                       &sw.st[0].chunk_ctr[1], sw.st, nullptr, nullptr, nullptr, sw.st, s);
+                                       &sw.st[0].chunk_ctr[1], sw.st, nullptr, nullptr, 0, nullptr, sw.st, s);
         if (e == hipSuccess) e = launch_select_tail(S, N, ldS, 1, k, sw, out_scores, out_idx, 1, s);
         return hip_status(e);
     }
@@ -258,9 +258,9 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
         if (e == hipSuccess) e = launch_select_init(ssw, Q, s);
         if (e == hipSuccess) e = mfma_scan(Nv, kEmitSample, sample, L.sample_ld, nullptr, nullptr, nullptr, nullptr, ssw.st, 0);
         if (e == hipSuccess) e = launch_hist1(sample, Nv, L.sample_ld, Q, ssw, 0, s);
-        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, Q, m, ssw, 1, s);
+        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, Q, m, ssw, 1, sw.st, s);
         ScanTimer timer(s);
-        if (e == hipSuccess) e = mfma_scan(N, kEmitFilter, nullptr, 0, ssw.st, sw.st, sw.cand, nullptr, sw.st, 0);
+        if (e == hipSuccess) e = mfma_scan(N, kEmitFilter, nullptr, 0, ssw.st, sw.st, sw.cand, sw.st, sw.st, 0);
         timer.stop();
         if (e == hipSuccess) e = launch_filter_sort(sw, Q, k, out_scores, out_idx, s);
         if (e == hipSuccess) e = mfma_scan(N, kEmitScores, S, ldS, nullptr, nullptr, nullptr, sw.st, sw.st, 1);
@@ -310,10 +310,10 @@ static hipError_t rank_table(const uint8_t *codes, int64_t N, int row_bytes, int
         const int m = sample_rank(N, Nv);
         e = launch_table_scan(codes, Nv, row_bytes, seven_bit, image, bias, kEmitSample, sample, ssw.st, ssw.hist1, m,
                               nullptr, nullptr, nullptr, nullptr, nullptr, s);
-        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, 0, s);
+        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, 0, nullptr, s);
         ScanTimer timer(s);
         if (e == hipSuccess)
-            e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitFilter, nullptr, sw.st, nullptr, k,
+            e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitFilter, nullptr, sw.st, nullptr, m,
                                   ssw.st, ssw.hist2, sw.cand, nullptr, nullptr, s);
         timer.stop();
         if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);

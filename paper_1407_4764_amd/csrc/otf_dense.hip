@@ -232,7 +232,8 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
                                                            float *__restrict__ scores, uint32_t *hist1,
                                                            uint32_t *chunk_ctr, SelState *st,
                                                            const SelState *tau_state, const uint32_t *tau_hist2,
-                                                           unsigned long long *__restrict__ cand, const SelState *gate) {
+                                                           int sample_rank, unsigned long long *__restrict__ cand,
+                                                           const SelState *gate) {
     constexpr int E = Elem<XHALF>::kPer16;
     constexpr int RPW = 64 / LPR;   // rows per wave load
     constexpr int U = 8;
@@ -249,6 +250,7 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
         // top 24 bits of the sample key of the requested rank, resolved by every workgroup for itself
         const BinChoice r2 = block_find_bin(tau_hist2, kBins2, tau_state->need1, lhist, s_out);
         tau = ((tau_state->b1 << 12) | r2.bin) << 8;
+        if (filter_hopeless((uint32_t)sample_rank, tau_state->need1, r2)) return;   // uniform
     } else {
         for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
         __syncthreads();
@@ -293,7 +295,10 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
         }
         return acc;
     };
-    // the owners' stores of one value index cover 64 / LPR * (8 / NVF) consecutive rows
+    // the owners' stores of one value index cover 64 / LPR * (8 / NVF) consecutive rows.
+    // Filtered scan: a wave that has seen the candidate list full stops appending (the list is
+    // useless by then, and the appends are adds to one address, one after the other).
+    bool list_full = false;
     auto consume = [&](const Chunk16 *c, long long tile, long long nrows) {
         float v[U];
 #pragma unroll
@@ -306,16 +311,19 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
             const float sc = v[k] + bias;
             const uint32_t key = float_to_key(sc);
             if (EMIT == kEmitFilter) {
-                if (ok && key >= tau) {
+                if (ok && key >= tau && !list_full) {
                     const uint32_t pos = atomicAdd(&st->cursor, 1u);
                     if (pos < (uint32_t)kCandCap)
                         cand[pos] = ((unsigned long long)key << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)row);
+                    else
+                        list_full = true;
                 }
             } else {
                 if (ok) scores[row] = sc;
                 hist_add_wave(lhist, key >> 20, ok);   // many rows per instruction, few bins: aggregate
             }
         }
+        if (EMIT == kEmitFilter) list_full = __ballot(list_full) != 0ull;
     };
     long long cur = tile_queue_draw(&s_queue, chunk_ctr, chunk_tiles, ntiles);
     if (cur >= 0) {
@@ -404,6 +412,7 @@ struct NarrowExtra {
     SelState *st;
     const SelState *tau;
     const uint32_t *tau_hist2;
+    int sample_rank;
     unsigned long long *cand;
     const SelState *gate;
 };
@@ -432,13 +441,13 @@ static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t
     do {                                                                                                           \
         if (x.emit == kEmitScores)                                                                                 \
             dense_narrow_kernel<XHALF, L, kEmitScores><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS, x.st, x.tau, x.tau_hist2, \
-                                                                             x.cand, x.gate);                      \
+                                                                             x.sample_rank, x.cand, x.gate);                      \
         else if (x.emit == kEmitSample)                                                                            \
             dense_narrow_kernel<XHALF, L, kEmitSample><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS, x.st, x.tau, x.tau_hist2, \
-                                                                             x.cand, x.gate);                      \
+                                                                             x.sample_rank, x.cand, x.gate);                      \
         else                                                                                                       \
             dense_narrow_kernel<XHALF, L, kEmitFilter><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS, x.st, x.tau, x.tau_hist2, \
-                                                                             x.cand, x.gate);                      \
+                                                                             x.sample_rank, x.cand, x.gate);                      \
     } while (0)
         switch (lpr) {
             case 1: OTF_NARROW(1); break;
@@ -487,16 +496,16 @@ hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int
                              int w_is_half, const float *bias_ptr, int bias_index, float *scores, uint32_t *hist1,
                              uint32_t *chunk_ctr, hipStream_t s) {
     return launch_dense_scan_emit(X, x_is_half, N, D, ldx, w, w_is_half, bias_ptr, bias_index, kEmitScores, scores,
-                                  hist1, chunk_ctr, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+                                  hist1, chunk_ctr, nullptr, nullptr, nullptr, 0, nullptr, nullptr, s);
 }
 
 hipError_t launch_dense_scan_emit(const void *X, int x_is_half, int64_t N, int D, int64_t ldx, const void *w,
                                   int w_is_half, const float *bias_ptr, int bias_index, ScanEmit emit, float *scores,
                                   uint32_t *hist1, uint32_t *chunk_ctr, SelState *st, const SelState *tau,
-                                  const uint32_t *tau_hist2, unsigned long long *cand, const SelState *gate,
-                                  hipStream_t s) {
+                                  const uint32_t *tau_hist2, int sample_rank, unsigned long long *cand,
+                                  const SelState *gate, hipStream_t s) {
     const uint8_t *Xb = reinterpret_cast<const uint8_t *>(X);
-    const NarrowExtra x{emit, st, tau, tau_hist2, cand, gate};
+    const NarrowExtra x{emit, st, tau, tau_hist2, sample_rank, cand, gate};
     if (emit == kEmitFilter && (!st || !tau || !tau_hist2 || !cand)) return hipErrorInvalidValue;
     if (x_is_half)
         return launch_dense_typed<true>(Xb, N, D, ldx * 2, w, w_is_half, bias_ptr, bias_index, scores, hist1, chunk_ctr, x, s);

@@ -181,6 +181,17 @@ __device__ __forceinline__ BinChoice block_find_bin(const uint32_t *ghist, int n
     return r;
 }
 
+// Filtered scans.  Passes 1 and 2 over the sample resolved its m-th largest key to 24 bits: need1 of
+// the m lie in pass-1 bin b1, and r2 is the pass-2 choice inside it.  So (m - need1) + r2.above +
+// r2.inbin sample rows lie at or above the threshold, and about kSampleStride times as many rows
+// of the store will.  When that is far beyond the candidate list's capacity (ties: a zero model,
+// scores that take few values) the scan is pointless: it returns at once, the list stays empty,
+// and the sort behind it raises the fallback.  Same answer in every workgroup.
+__device__ __forceinline__ bool filter_hopeless(uint32_t m, uint32_t need1, const BinChoice &r2) {
+    const uint32_t at_or_above = (m - need1) + r2.above + r2.inbin;
+    return at_or_above > 2u * (uint32_t)kCandCap / (uint32_t)kSampleStride;
+}
+
 // Dynamic work distribution for the streaming scans.  The chip's eight dies stream at visibly
 // different rates and the waves of a workgroup drift apart, so a static split of the rows leaves
 // a tail of 5-10 % in which most of the chip idles.  Instead the work is cut into tiles (what one

@@ -49,10 +49,11 @@ hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const
 hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw,
                               float *out_scores, int32_t *out_idx, int gated, hipStream_t s);
 // Pass 2 over sample scores for rank m.  With publish_tau, sample_sw.st[q].tau_key receives the
-// threshold (top 24 bits of the m-th largest sample key); otherwise the consumer resolves it from
-// sample_sw.st[q] and sample_sw.hist2 itself.
+// threshold (top 24 bits of the m-th largest sample key), and main_st[0].fallback is raised when a
+// classifier's threshold would let far more rows pass than the candidate list holds; otherwise
+// the consumer resolves the threshold from sample_sw.st[q] and sample_sw.hist2 itself.
 hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64_t ld, int Q, int m,
-                                   const SelectWs &sample_sw, int publish_tau, hipStream_t s);
+                                   const SelectWs &sample_sw, int publish_tau, SelState *main_st, hipStream_t s);
 // End of a filtered scan: sort the appended candidates or raise sw.st[0].fallback.
 hipError_t launch_filter_sort(const SelectWs &sw, int Q, int k, float *out_scores, int32_t *out_idx, hipStream_t s);
 
@@ -70,17 +71,19 @@ bool dense_scan_filters(int x_is_half, int D);
 //   kEmitSample  N = rows of the strided sample, numbered compactly: scores[v] + histogram
 //   kEmitFilter  rows at or above the threshold go to cand (cursor in st); every workgroup resolves
 //                the threshold from the state passes 1 and 2 over the sample left in (tau, tau_hist2)
+//                for rank sample_rank
 hipError_t launch_dense_scan_emit(const void *X, int x_is_half, int64_t N, int D, int64_t ldx, const void *w,
                                   int w_is_half, const float *bias_ptr, int bias_index, ScanEmit emit, float *scores,
                                   uint32_t *hist1, uint32_t *chunk_ctr, SelState *st, const SelState *tau,
-                                  const uint32_t *tau_hist2, unsigned long long *cand, const SelState *gate,
-                                  hipStream_t s);
+                                  const uint32_t *tau_hist2, int sample_rank, unsigned long long *cand,
+                                  const SelState *gate, hipStream_t s);
 
 // Multi-classifier fp16 scan on the matrix cores (Q = 32 or 64 classifiers per call).
 //   kEmitScores  scores[q][i] for every row (row stride ld_scores); with `gate` set the kernel returns
 //                at once unless gate->fallback is raised
 //   kEmitSample  the same for the strided sample only (compact row numbering)
-//   kEmitFilter  nothing is stored but the rows with key >= tau[q].tau_key, appended to cand[q]
+//   kEmitFilter  nothing is stored but the rows with key >= tau[q].tau_key, appended to cand[q]; with
+//                `gate` set the kernel returns at once if gate->fallback is ALREADY raised
 // tile_ctr: a zeroed word in global memory (the kernel hands out its tiles dynamically).
 hipError_t launch_dense_mfma(const void *X, int64_t N, int D, int64_t ldx, const void *W, int Q, const float *bias,
                              ScanEmit emit, float *scores, int64_t ld_scores, const SelState *tau, SelState *st,
@@ -97,7 +100,8 @@ hipError_t launch_binary_prepare(const float *w, int D, float *image, const Sele
 //   kEmitScores  scores + pass-1 histogram into (st, hist1) for a top-k of k; `gate` as above
 //   kEmitSample  scores of the strided sample (compact numbering) + pass-1 histogram for rank k = m
 //   kEmitFilter  append rows at or above the threshold to cand (cursor in st); every block resolves
-//                the threshold from the sample's pass-2 state (tau, tau_hist2) for rank k = m
+//                the threshold from the sample's pass-2 state (tau, tau_hist2) for rank k = m (here k
+//                is the sample rank, not the length of the list)
 hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, int seven_bit, const float *image,
                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
                              const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,

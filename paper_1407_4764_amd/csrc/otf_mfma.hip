@@ -36,7 +36,8 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__res
                                                          unsigned long long *__restrict__ cand, const SelState *gate,
                                                          uint32_t *tile_ctr) {
     constexpr int QN = QT * 32;
-    if (gate && gate->fallback == 0u) return;     // uniform: only the fallback of a filtered scan
+    // uniform: a gated full scan is only the fallback of a filtered one; a gated filtered scan was called off
+    if (gate && (EMIT == kEmitFilter ? gate->fallback != 0u : gate->fallback == 0u)) return;
     __shared__ __attribute__((aligned(16))) uint8_t xs[kBM * kRowStride];
     __shared__ __attribute__((aligned(16))) uint8_t ws[QN * kRowStride];
     __shared__ uint32_t s_tile[8];                // ring: number of the block's j-th tile at slot j % 8
@@ -147,6 +148,11 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__res
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[qt][v] = 0.f;
 
+    // Filtered scan: a wave stops appending to a classifier's list once it has seen that list full
+    // (per lane: lane (n, h) only ever appends to classifiers n and n + 32).
+    bool list_full[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) list_full[qt] = false;
     auto epilogue = [&](long long row0) {
         // accumulator element v of lane (n, h): dataset row 8*(v/4) + 4*h + v%4 of the wave's 32,
         // classifier n of the tile's 32
@@ -163,12 +169,14 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__res
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const uint32_t key = float_to_key(o[j]);
-                        if (key >= tau[qt] && row + j < N) {
+                        if (key >= tau[qt] && row + j < N && !list_full[qt]) {
                             const int q = qt * 32 + n;
                             const uint32_t pos = atomicAdd(&st[q].cursor, 1u);
                             if (pos < (uint32_t)kCandCap)
                                 cand[(size_t)q * kCandCap + pos] = ((unsigned long long)key << 32) |
                                                                    (unsigned long long)(0xFFFFFFFFu - (uint32_t)(row + j));
+                            else
+                                list_full[qt] = true;
                         }
                     }
                 } else if (vec_store && row + 3 < N) {

@@ -165,12 +165,20 @@ __device__ __forceinline__ Pass2 resolve_pass2(const SelState *st, const uint32_
 }
 
 // One block per classifier: the threshold of a filtered scan from passes 1 and 2 over the sample.
-__global__ __launch_bounds__(512) void sample_tau_kernel(SelState *sample_st_all, const uint32_t *hist2_all, int m) {
+// p.c2 sample rows lie at or above it.  When that predicts far more rows of the store than the
+// candidate list holds (see filter_hopeless) the filtered scan is called off for the whole call:
+// the fallback flag of the full selection's state is raised here already, and the scan, which
+// is given that state as its gate, returns at once.
+__global__ __launch_bounds__(512) void sample_tau_kernel(SelState *sample_st_all, const uint32_t *hist2_all, int m,
+                                                         SelState *main_st_all) {
     __shared__ uint32_t lhist[kBins2];
     __shared__ uint32_t s_out[3];
     const int q = blockIdx.x;
     const Pass2 p = resolve_pass2(sample_st_all + q, hist2_all + (size_t)q * kBins2, m, lhist, s_out);
-    if (threadIdx.x == 0) sample_st_all[q].tau_key = p.p24 << 8;
+    if (threadIdx.x == 0) {
+        sample_st_all[q].tau_key = p.p24 << 8;
+        if (main_st_all && p.c2 > 2u * (uint32_t)kCandCap / (uint32_t)kSampleStride) atomicOr(&main_st_all[0].fallback, 1u);
+    }
 }
 
 // Pass 3 (only when thousands of keys share the top 24 bits of the k-th: ties or near-ties).
@@ -563,8 +571,9 @@ __global__ __launch_bounds__(kSortThreads) void sort_emit_kernel(const SelState 
                      out_idx + (size_t)q * k);
 }
 
-// One block per classifier: end of a filtered scan.  The scan appended `cursor` rows (it stops
-// writing at the capacity but keeps counting).  With k <= cursor <= capacity the list holds
+// One block per classifier: end of a filtered scan.  `cursor` counts the rows the scan appended, or
+// is some number above the capacity when more passed than the list holds (a wave stops counting
+// once it has seen the list full).  With k <= cursor <= capacity the list holds
 // every row of the top k, so sorting it gives the exact answer; otherwise the fallback is raised
 // for all classifiers and the append cursor is cleared for the full selection that follows.
 __global__ __launch_bounds__(kSortThreads) void filter_sort_kernel(SelState *st_all,
@@ -646,10 +655,10 @@ hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q,
 // sample state).  With publish_tau the thresholds are resolved into sample_sw.st[q].tau_key by a
 // one-block-per-classifier kernel; otherwise the consumer resolves them itself (resolve_tau).
 hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64_t ld, int Q, int m,
-                                   const SelectWs &sample_sw, int publish_tau, hipStream_t s) {
+                                   const SelectWs &sample_sw, int publish_tau, SelState *main_st, hipStream_t s) {
     hist2_kernel<<<dim3(sel_blocks(Nv, Q), Q), 512, 0, s>>>(sample_scores, Nv, ld, m, sample_sw.st, sample_sw.hist1,
                                                     sample_sw.hist2, 1, nullptr);
-    if (publish_tau) sample_tau_kernel<<<Q, 512, 0, s>>>(sample_sw.st, sample_sw.hist2, m);
+    if (publish_tau) sample_tau_kernel<<<Q, 512, 0, s>>>(sample_sw.st, sample_sw.hist2, m, main_st);
     return hipGetLastError();
 }
 

@@ -189,7 +189,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 template <int LPR, int U, int GB, int EMIT, bool SPLIT>
 __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     const uint8_t *__restrict__ codes, long long N, int M, int nsplit, const float *__restrict__ image, float bias,
-    float *__restrict__ scores, SelState *st, uint32_t *hist1, int k, const SelState *tau_state,
+    float *__restrict__ scores, SelState *st, uint32_t *hist1, int sample_rank, const SelState *tau_state,
     const uint32_t *tau_hist2, unsigned long long *__restrict__ cand, const SelState *gate, int sp0,
     uint32_t *phase_ctr) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
@@ -223,6 +223,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
         const BinChoice r2 = block_find_bin(tau_hist2, kBins2, tau_state->need1,
                                             reinterpret_cast<uint32_t *>(lds_raw), s_out);
         tau = ((tau_state->b1 << 12) | r2.bin) << 8;
+        if (filter_hopeless((uint32_t)sample_rank, tau_state->need1, r2)) return;   // uniform
     }
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -293,17 +294,23 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
         __syncthreads();
         const bool first = sp == 0, lastp = sp == nsplit - 1;
 
-        // one output round: lane `sub` of each group holds in `mine` the sum of the row it owns
+        // one output round: lane `sub` of each group holds in `mine` the sum of the row it owns.
+        // Filtered scan: a wave that has seen the list full stops appending (the list is already
+        // useless, and the appends are adds to one address, ~18 ns each one after the other: a
+        // threshold that lets a million rows pass would otherwise cost tens of milliseconds).
+        bool list_full = false;
         auto emit = [&](float mine, const float *carry, long long v, int e, bool ok) {
             if (sub < ACTIVE && ok) {
                 if (SPLIT && !first) mine += carry[e];
                 if (lastp) mine += bias;
                 if (EMIT == kEmitFilter) {
                     const uint32_t key = float_to_key(mine);
-                    if (key >= tau) {
+                    if (key >= tau && !list_full) {
                         const uint32_t pos = atomicAdd(&st->cursor, 1u);
                         if (pos < (uint32_t)kCandCap)
                             cand[pos] = ((unsigned long long)key << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)v);
+                        else
+                            list_full = true;
                     }
                 } else {
                     if (lastp) atomicAdd(&lhist[float_to_key(mine) >> 20], 1u);
@@ -346,6 +353,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
                     const long long v = out_row(v0, e);
                     emit(mine[e], carry, v, e, true);
                 }
+                if (EMIT == kEmitFilter) list_full = __ballot(list_full) != 0ull;   // one lane's news serves the wave
             };
             long long cur = draw();
             if (cur >= 0) {

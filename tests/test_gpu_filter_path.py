@@ -229,3 +229,24 @@ def test_dense_short_rows_filtered_scan_strided_store(oracle):
                               np.zeros(1, dtype=np.float32))[0]
     ok, msg = oracle.topk_parity_ok(ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), RTOL32)
     assert ok, msg
+
+
+def test_multi_classifier_zero_models_are_called_off(oracle):
+    """Half of the classifiers are zero models: their sample predicts that every row would pass the
+    threshold, so the filtered scan is called off and the full selection ranks all 64 -- the
+    zero models get rows 0..k-1, the others their oracle lists."""
+    N, D, Q, k = 1060000, 128, 64, 50
+    X = synth.dense_features(N, D, SEED + 30, dtype=torch.float16)
+    W = synth.normal_matrix(Q, D, 0.05, SEED + 31, dtype=torch.float16)
+    W[::2] = 0
+    b = synth.normal_vector(Q, 0.01, SEED + 32)
+    ws = binding.make_workspace(N, k, Q)
+    val, idx = binding.rank_dense(X.to(DEV), W.to(DEV), b.to(DEV), k, ws)
+    assert binding.debug_fallback_taken(ws)
+    ref = oracle.dense_scores(X.numpy(), W.numpy(), b.numpy())
+    for q in range(0, Q, 2):
+        np.testing.assert_array_equal(idx[q].cpu().numpy(), np.arange(k))
+        assert torch.all(val[q] == b[q].item())
+    for q in range(1, Q, 6):
+        ok, msg = oracle.topk_parity_ok(ref[q], k, idx[q].cpu().numpy(), val[q].cpu().numpy(), RTOL16)
+        assert ok, "q=%d: %s" % (q, msg)
