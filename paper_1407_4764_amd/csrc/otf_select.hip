@@ -115,7 +115,7 @@ __global__ __launch_bounds__(1024) void hist1_kernel(const float *__restrict__ s
 
 // Pass 2.  Resolves pass 1 first (rank k in hist1).  force: always run pass 2 (threshold
 // estimation on a sample); otherwise return when pass 1 was decisive.
-__global__ __launch_bounds__(512) void hist2_kernel(const float *__restrict__ scores, long long N, long long ld,
+__global__ __launch_bounds__(1024) void hist2_kernel(const float *__restrict__ scores, long long N, long long ld,
                                                     int k, SelState *st_all, const uint32_t *hist1_all,
                                                     uint32_t *hist2_all, int force, const SelState *gate) {
     __shared__ uint32_t lhist[kBins2];
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(512) void sample_tau_kernel(SelState *sample_st_all
 }
 
 // Pass 3 (only when thousands of keys share the top 24 bits of the k-th: ties or near-ties).
-__global__ __launch_bounds__(512) void hist3_kernel(const float *__restrict__ scores, long long N, long long ld,
+__global__ __launch_bounds__(1024) void hist3_kernel(const float *__restrict__ scores, long long N, long long ld,
                                                     int k, SelState *st_all, const uint32_t *hist2_all,
                                                     uint32_t *hist3_all, uint32_t *blockhist3_all, int gated) {
     __shared__ uint32_t lhist[kBins2];
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ s
                                                      int gated) {
     __shared__ uint32_t lhist[kBins3];
     __shared__ uint32_t s_out[3];
-    __shared__ uint32_t wave_cnt[8];
+    __shared__ uint32_t wave_cnt[32];                       // [step of a round][wave]
     // rows above the threshold are collected per block and appended with ONE device-wide atomic:
     // thousands of atomics on the single cursor would serialise (~18 ns each)
     constexpr uint32_t kLocalCap = 2048;
@@ -284,56 +284,66 @@ __global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ s
             if (pos < (uint32_t)kCandCap) cand[pos] = pack_cand(key, row);
         }
     };
-    if (!ordered) {                                        // uniform: no ties to place in row order here
-        for_each_score(s, begin, end, vec_ok, [&](float v, bool ok, long long row) {
-            const uint32_t key = float_to_key(v);
-            if (ok && (long long)key > tex) take(key, row);
-        });
-    }
-    for (long long t0 = ordered ? begin : end; t0 < end; t0 += 4 * blockDim.x) {
-        const long long i0 = t0 + 4 * threadIdx.x;
-        float v[4];
-        bool ok[4];
-        load4(s, i0, end, vec_ok, v, ok);
-        uint32_t key[4];
-        uint32_t neq = 0;
+    // Rows equal to the k-th key are placed in row order, a step of the block at a time, until the
+    // block has met all r of them (eqbase counts those before the current step); the rows after
+    // that, and all rows of a block with no ties to place, only need the keys above the threshold.
+    long long t0 = begin;
+    constexpr int OS = 4;                                  // steps of 4 * blockDim rows per round of barriers
+    const long long span = 4LL * blockDim.x;
+    for (; ordered && eqbase < r && t0 < end; t0 += OS * span) {
+        float v[OS][4];
+        bool ok[OS][4];
+        uint32_t key[OS][4], neq[OS], incl[OS];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            key[j] = float_to_key(v[j]);
-            if (ok[j] && (long long)key[j] > tex) take(key[j], i0 + j);
-            neq += (ok[j] && key[j] == T) ? 1u : 0u;
-        }
-        if (ordered) {
-            // rank of each row equal to T in row order: threads hold 4 consecutive rows
-            uint32_t incl = neq;                       // inclusive prefix over the lanes of the wave
+        for (int u = 0; u < OS; ++u) load4(s, t0 + u * span + 4 * threadIdx.x, end, vec_ok, v[u], ok[u]);
+#pragma unroll
+        for (int u = 0; u < OS; ++u) {
+            const long long i0 = t0 + u * span + 4 * threadIdx.x;
+            neq[u] = 0u;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                key[u][j] = float_to_key(v[u][j]);
+                if (ok[u][j] && (long long)key[u][j] > tex) take(key[u][j], i0 + j);
+                neq[u] += (ok[u][j] && key[u][j] == T) ? 1u : 0u;
+            }
+            // rank of each row equal to T in row order: threads hold 4 consecutive rows of a step
+            incl[u] = neq[u];                              // inclusive prefix over the lanes of the wave
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
-                uint32_t t = __shfl_up(incl, o, 64);
-                if (lane >= o) incl += t;
+                const uint32_t t = __shfl_up(incl[u], o, 64);
+                if (lane >= o) incl[u] += t;
             }
-            if (lane == 63) wave_cnt[wave] = incl;
-            __syncthreads();
+            if (lane == 63) wave_cnt[u * 8 + wave] = incl[u];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < OS; ++u) {
+            const long long i0 = t0 + u * span + 4 * threadIdx.x;
             uint32_t before = 0, total = 0;
             for (int w = 0; w < nwaves; ++w) {
-                uint32_t c = wave_cnt[w];
+                const uint32_t c = wave_cnt[u * 8 + w];
                 if (w < wave) before += c;
                 total += c;
             }
-            uint32_t rank = eqbase + before + incl - neq;
+            uint32_t rank = eqbase + before + incl[u] - neq[u];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if (ok[j] && key[j] == T) {
+                if (ok[u][j] && key[u][j] == T) {
                     if (rank < r) {
-                        uint32_t pos = (uint32_t)k - r + rank;
-                        if (pos < (uint32_t)kCandCap) cand[pos] = pack_cand(key[j], i0 + j);
+                        const uint32_t pos = (uint32_t)k - r + rank;
+                        if (pos < (uint32_t)kCandCap) cand[pos] = pack_cand(key[u][j], i0 + j);
                     }
                     ++rank;
                 }
             }
             eqbase += total;
-            __syncthreads();
         }
+        __syncthreads();
     }
+    for_each_score(s, t0, end, vec_ok, [&](float v, bool ok, long long row) {
+        const uint32_t key = float_to_key(v);
+        if (ok && (long long)key > tex) take(key, row);
+    });
     __syncthreads();
     const uint32_t nloc = s_local_n < kLocalCap ? s_local_n : kLocalCap;
     if (threadIdx.x == 0 && nloc) s_base = atomicAdd(&st->cursor, nloc);
@@ -642,8 +652,9 @@ hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const
 hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw,
                               float *out_scores, int32_t *out_idx, int gated, hipStream_t s) {
     dim3 grid(sel_blocks(N, Q), Q);
-    hist2_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist1, sw.hist2, 0, gated ? sw.st : nullptr);
-    hist3_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist2, sw.hist3, sw.blockhist3, gated);
+    // (1024 threads: the histogram passes hide the latency of their votes and shared-memory adds behind more waves)
+    hist2_kernel<<<grid, 1024, 0, s>>>(scores, N, ld, k, sw.st, sw.hist1, sw.hist2, 0, gated ? sw.st : nullptr);
+    hist3_kernel<<<grid, 1024, 0, s>>>(scores, N, ld, k, sw.st, sw.hist2, sw.hist3, sw.blockhist3, gated);
     gather_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist3, sw.blockhist3, sw.cand, gated);
     hipError_t e = allow_sort_lds();
     if (e != hipSuccess) return e;
@@ -656,7 +667,7 @@ hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q,
 // one-block-per-classifier kernel; otherwise the consumer resolves them itself (resolve_tau).
 hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64_t ld, int Q, int m,
                                    const SelectWs &sample_sw, int publish_tau, SelState *main_st, hipStream_t s) {
-    hist2_kernel<<<dim3(sel_blocks(Nv, Q), Q), 512, 0, s>>>(sample_scores, Nv, ld, m, sample_sw.st, sample_sw.hist1,
+    hist2_kernel<<<dim3(sel_blocks(Nv, Q), Q), 1024, 0, s>>>(sample_scores, Nv, ld, m, sample_sw.st, sample_sw.hist1,
                                                     sample_sw.hist2, 1, nullptr);
     if (publish_tau) sample_tau_kernel<<<Q, 512, 0, s>>>(sample_sw.st, sample_sw.hist2, m, main_st);
     return hipGetLastError();

@@ -239,6 +239,18 @@ def test_topk_ties_are_broken_by_row_index(oracle):
     assert np.all(val[0][:10] == 0.0)
 
 
+def test_topk_ties_placed_in_row_order_over_many_rounds_and_blocks(oracle):
+    """Few distinct values in a store large enough that the rows equal to the k-th score which belong
+    to the list span several workgroups and several rounds inside the first ones; also the same
+    with the values sorted, where whole waves fall into one histogram bin."""
+    rng = np.random.default_rng(SEED + 3)
+    ints = rng.integers(-20, 21, 3_000_000).astype(np.float64)
+    _check_topk_exact(oracle, ints, 1000)
+    _check_topk_exact(oracle, np.sort(ints), 1000)
+    _check_topk_exact(oracle, np.sort(ints)[::-1].copy(), 4000)
+    _check_topk_exact(oracle, rng.integers(0, 2, 2_500_000).astype(np.float64), 3000)
+
+
 def test_topk_clustered_scores_need_the_finer_passes(oracle):
     rng = np.random.default_rng(SEED + 2)
     # all scores inside one coarse bin (same sign, exponent and top mantissa bits)
