@@ -88,8 +88,9 @@ def test_binary_2048_bit_groups_are_exact(oracle):
     np.testing.assert_array_equal(all_scores.cpu().numpy().astype(np.float64), ref)
 
 
-def test_multi_classifier_filtered_scan(oracle):
-    N, D, Q, k = 1060000, 128, 64, 100
+@pytest.mark.parametrize("D", [128, 1024])
+def test_multi_classifier_filtered_scan(oracle, D):
+    N, Q, k = 1060000, 64, 100
     X = synth.dense_features(N, D, SEED + 8, dtype=torch.float16)
     W = synth.normal_matrix(Q, D, 0.05, SEED + 9, dtype=torch.float16)
     b = synth.normal_vector(Q, 0.01, SEED + 10)

@@ -98,7 +98,11 @@ def test_rank_dense_several_classifiers_one_by_one(oracle):
 
 
 @pytest.mark.parametrize("N,D,Q,k,with_all", [(1000, 256, 64, 50, True), (4133, 2048, 64, 100, False),
-                                                (515, 128, 32, 5, True), (900, 384, 96, 9, True)])
+                                                (515, 128, 32, 5, True), (900, 384, 96, 9, True),
+                                                # more rows of 1024 and 2048 columns, two groups of 64 classifiers, fewer rows than a tile
+                                                (1000, 1024, 64, 50, True), (2050, 2048, 128, 20, True),
+                                                (33, 2048, 64, 5, True), (31, 1024, 64, 3, True),
+                                                (70001, 2048, 64, 100, True)])
 def test_rank_dense_matrix_core_path(oracle, N, D, Q, k, with_all):
     X = synth.dense_features(N, D, SEED + 5, dtype=torch.float16)
     W = synth.normal_matrix(Q, D, 0.05, SEED + 15, dtype=torch.float16)
