@@ -33,7 +33,8 @@ def _both_paths(fn):
     return a, (b[0].clone(), b[1].clone())
 
 
-@pytest.mark.parametrize("N,M,dsub,k", [(1200003, 128, 16, 1000), (1150000, 32, 4, 100), (1100000, 64, 8, 1)])
+@pytest.mark.parametrize("N,M,dsub,k", [(1200003, 128, 16, 1000), (1150000, 32, 4, 100), (1100000, 64, 8, 1),
+                                         (2300007, 16, 8, 1024)])
 def test_pq_filtered_scan(oracle, N, M, dsub, k):
     K = 256
     cb = synth.pq_codebooks(M, K, dsub, SEED + 1)
@@ -51,7 +52,8 @@ def test_pq_filtered_scan(oracle, N, M, dsub, k):
     assert ok, msg
 
 
-@pytest.mark.parametrize("N,D,k", [(1100000, 2048, 1000), (1300000, 1024, 64), (2200000, 256, 10)])
+@pytest.mark.parametrize("N,D,k", [(1100000, 2048, 1000), (1300000, 1024, 64), (2200000, 256, 10),
+                                   (2500001, 128, 50), (1200000, 512, 300)])
 def test_binary_filtered_scan(oracle, N, D, k):
     bits = synth.binary_bits_random(N, D // 32, SEED + 4)
     w = synth.normal_vector(D, 1.0, SEED + 5)
