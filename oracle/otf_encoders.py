@@ -21,9 +21,29 @@ def tight_frame(G, m):
     if G.shape != (n, n) or not (1 <= m <= n):
         raise ValueError("tight_frame needs an n x n matrix and 1 <= m <= n")
     Q, R = np.linalg.qr(G)                      # library step: Householder QR (LAPACK)
-    s = np.sign(np.diag(R))
-    s[s == 0] = 1.0
-    return (Q * s[None, :])[:, :m].copy()
+    # A leading column in the span of its predecessors has no direction of its own: the
+    # Gram-Schmidt basis has a zero column there, while a Householder factorisation fills in an
+    # arbitrary unit vector (and lets it leak into the columns after it).  |R_jj| is the distance
+    # of column j from the span of the q before it; rounding leaves ~1e-16 of the column's
+    # length, so anything below n * eps of it counts as zero.
+    tol = n * np.finfo(np.float64).eps * np.linalg.norm(G[:, :m], axis=0)
+    if np.all(np.abs(np.diag(R)[:m]) > tol):
+        s = np.sign(np.diag(R))
+        return (Q * s[None, :])[:, :m].copy()
+    # rank-deficient leading block: column by column, each against an orthonormal basis (library
+    # QR) of the independent columns found so far; the residual's own direction makes R_jj positive
+    U = np.zeros((n, m))
+    independent = []
+    for j in range(m):
+        r = G[:, j].copy()
+        if independent:
+            B = np.linalg.qr(G[:, independent])[0]
+            r -= B @ (B.T @ r)
+            r -= B @ (B.T @ r)
+        if np.linalg.norm(r) > tol[j]:
+            U[:, j] = r / np.linalg.norm(r)
+            independent.append(j)
+    return U
 
 
 def projections(phi, U):

@@ -48,6 +48,35 @@ def test_frame_equals_gram_schmidt_of_the_first_columns():
     assert np.all(np.einsum("ij,ij->j", U, G[:, :m]) > 0)      # diag(R) > 0
 
 
+def _dependent_matrix(n, rng):
+    """Random n x n matrix whose columns 3, 5 and 7 lie in the span of earlier ones (a repeat, a
+    combination of two, a zero column)."""
+    G = rng.standard_normal((n, n))
+    G[:, 3] = G[:, 1]
+    G[:, 5] = 2.0 * G[:, 0] - 0.5 * G[:, 2]
+    G[:, 7] = 0.0
+    return G
+
+
+def test_dependent_leading_columns_give_zero_columns():
+    """A column in the span of its predecessors has no Gram-Schmidt direction: the frame has a zero
+    column there and the other columns are what the matrix without those columns gives (a
+    Householder factorisation alone would put an arbitrary unit vector there and let it leak
+    into the columns after it)."""
+    n, m = 40, 10
+    G = _dependent_matrix(n, np.random.default_rng(7))
+    U = enc.tight_frame(G, m)
+    dep, indep = [3, 5, 7], [0, 1, 2, 4, 6, 8, 9]
+    assert np.all(U[:, dep] == 0.0)
+    H = np.concatenate([G[:, indep], np.random.default_rng(8).standard_normal((n, n - len(indep)))], axis=1)
+    np.testing.assert_allclose(U[:, indep], _gram_schmidt(H, len(indep)), atol=1e-12)
+    np.testing.assert_allclose(U[:, indep].T @ U[:, indep], np.eye(len(indep)), atol=1e-12)
+    # a column that is merely nearly dependent (1e-6 away) keeps a direction
+    G[:, 3] += 1e-6 * np.random.default_rng(9).standard_normal(n)
+    U2 = enc.tight_frame(G, m)
+    assert abs(np.linalg.norm(U2[:, 3]) - 1.0) < 1e-9 and np.all(U2[:, [5, 7]] == 0.0)
+
+
 def test_binarize_equals_per_bit_loops():
     N, m, n = 7, 6, 64
     U = enc.tight_frame(RNG.standard_normal((n, n)), m)
