@@ -9,7 +9,8 @@
  *
  * Conventions shared by every entry point
  *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller owns
- *     every buffer; the library allocates nothing and keeps no state between calls.
+ *     every buffer; the library allocates nothing and keeps no state between calls (the
+ *     diagnostics at the end of this header are the exception and say so).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *     enqueued on it and the call returns without synchronising; outputs are valid once
  *     the caller has synchronised the stream.
@@ -17,7 +18,8 @@
  *     leading dimension), otherwise OTF_ERR_INVALID_ARG.
  *   - Row indices are int32: N must be below 2^31, otherwise OTF_ERR_UNSUPPORTED.
  *   - Ranked lists hold k entries, best first: score descending, equal scores by ascending
- *     row index.  1 <= k <= min(N, OTF_MAX_K).  A score of -0.0 is reported as +0.0.
+ *     row index.  1 <= k <= N, otherwise OTF_ERR_INVALID_ARG; k above OTF_MAX_K is a limit of
+ *     this build: OTF_ERR_UNSUPPORTED.  A score of -0.0 is reported as +0.0.
  *     Scores must be finite; NaN/Inf inputs give unspecified (but in-range) rankings.
  *   - Return value: OTF_OK (0) or a negative otf_status.  Argument errors are detected on
  *     the host before anything is enqueued: then no buffer has been written.
@@ -70,8 +72,9 @@ size_t otf_workspace_bytes(int64_t N, int32_t k, int32_t Q);
  *
  * Supported: xdt = F32 with wdt = F32; xdt = F16 with wdt = F32 or F16.  D a multiple of 4
  * (F32) or 8 (F16), at most 16384.  With Q > 1 and F16/F16 inputs, Q a multiple of 32 and D
- * a multiple of 128, scoring runs as an MFMA matrix product; other Q > 1 shapes are scored
- * one classifier at a time (X is then read Q times).  Anything else: OTF_ERR_UNSUPPORTED.
+ * a multiple of 128, scoring runs as an MFMA matrix product (unless 127 row strides exceed
+ * 4 GiB); other Q > 1 shapes are scored one classifier at a time (X is then read Q times).
+ * Anything else: OTF_ERR_UNSUPPORTED.
  */
 int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t ldx,
                    const void *W, otf_dtype wdt, int32_t Q, const float *bias,
@@ -173,7 +176,9 @@ int otf_svm_sgd_pass(float *w, float *b, int32_t D,
  *   G   n x n floats, row-major, drawn by the caller.  Of the possible QR factorisations the one
  *       with a positive diagonal of R is taken, so U is a function of G (it depends on the
  *       first m columns of G only and is their Gram-Schmidt orthonormalisation, computed in fp64).
- *       Linearly dependent leading columns give zero columns in U.
+ *       A leading column that lies in the span of its predecessors (what orthogonalisation
+ *       leaves of it is below n * 2^-52 of its length) gives a zero column in U, and the
+ *       columns after it are orthogonalised against the non-zero ones only.
  *   U   n x m floats, row-major (row d = the frame vector of code bit d).
  *   ws  at least otf_tight_frame_workspace_bytes(n, m) bytes, 16-byte aligned.
  *   1 <= m <= n; n <= 4096 and m <= 256, otherwise OTF_ERR_UNSUPPORTED.
@@ -235,6 +240,31 @@ int otf_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *codebooks, 
  */
 int otf_profile_begin(int32_t max_records);
 int otf_profile_end(double *scan_ms_total, int32_t *n_records);
+
+/*
+ * Diagnostic switches (host, not part of the paper's method; for tests that must force a code
+ * path and for launch-shape sweeps).  otf_debug_set(key, value) sets one process-wide switch that
+ * every later call reads; value 0 clears it (the built-in choice applies again).  The results of
+ * the library do not depend on any switch, only which kernels produce them and how they are
+ * launched.  Returns OTF_ERR_INVALID_ARG for an unknown key or a value the key does not accept.
+ * Not thread-safe against calls that are being enqueued at the same time.
+ */
+typedef enum {
+    OTF_DEBUG_RANK_PATH = 0,         /* 1: always rank by full selection over materialised scores */
+    OTF_DEBUG_BINARIZE_FP32,         /* 1: otf_binarize with fp32 matrix instructions (comparison kernel) */
+    OTF_DEBUG_PQENC_FP32,            /* 1: otf_pq_encode with fp32 matrix instructions (comparison kernel) */
+    OTF_DEBUG_SCAN_THREADS,          /* threads per workgroup of the table scans: a multiple of 64, 64..1024 */
+    OTF_DEBUG_SCAN_UNROLL,           /* 4 or 8 loads per lane and tile in the filtered table scan */
+    OTF_DEBUG_BINARIZE_WAVES,        /* 4 or 8 waves per workgroup of otf_binarize */
+    OTF_DEBUG_PQENC_RANGE,           /* sub-blocks per work unit of otf_pq_encode: a multiple of 4, 4..64 */
+    OTF_DEBUG_DENSE_BLOCKS_PER_CU,   /* 1..8 workgroups per compute unit, wide dense scan */
+    OTF_DEBUG_NARROW_BLOCKS_PER_CU,  /* 1..8, dense scan of rows up to 512 bytes */
+    OTF_DEBUG_MFMA_BLOCKS_PER_CU,    /* 1..8, multi-classifier scan */
+    OTF_DEBUG_PQENC_BLOCKS_PER_CU,   /* 1..8, otf_pq_encode */
+    OTF_DEBUG_KEYS
+} otf_debug_key;
+
+int otf_debug_set(int key, int value);
 
 #ifdef __cplusplus
 }

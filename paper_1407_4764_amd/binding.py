@@ -25,7 +25,12 @@ EXPORTS = ["otf_status_string", "otf_workspace_bytes", "otf_rank_dense", "otf_pq
            "otf_rank_binary", "otf_topk", "otf_sgd_workspace_bytes", "otf_svm_sgd_step", "otf_svm_sgd_pass",
            "otf_tight_frame_workspace_bytes",
            "otf_tight_frame", "otf_binarize", "otf_pq_train_workspace_bytes", "otf_pq_encode", "otf_pq_lloyd_step",
-           "otf_profile_begin", "otf_profile_end"]
+           "otf_profile_begin", "otf_profile_end", "otf_debug_set"]
+
+# otf_debug_key
+(DEBUG_RANK_PATH, DEBUG_BINARIZE_FP32, DEBUG_PQENC_FP32, DEBUG_SCAN_THREADS, DEBUG_SCAN_UNROLL, DEBUG_BINARIZE_WAVES,
+ DEBUG_PQENC_RANGE, DEBUG_DENSE_BLOCKS_PER_CU, DEBUG_NARROW_BLOCKS_PER_CU, DEBUG_MFMA_BLOCKS_PER_CU,
+ DEBUG_PQENC_BLOCKS_PER_CU, DEBUG_KEYS) = range(12)
 
 _lib = None
 
@@ -82,6 +87,8 @@ def lib():
         L.otf_profile_begin.argtypes = [i32]
         L.otf_profile_end.restype = ctypes.c_int
         L.otf_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+        L.otf_debug_set.restype = ctypes.c_int
+        L.otf_debug_set.argtypes = [ctypes.c_int, ctypes.c_int]
         _lib = L
     return _lib
 
@@ -92,6 +99,66 @@ def status_string(status):
 
 def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+class _Args:
+    """The C ABI sees addresses only; this layer sees the tensors, so dtype, size, layout and
+    device of every tensor of a call are checked here, before the call: a wrong dtype would be
+    read as garbage and a short buffer overrun on the device.  Type, shape and size errors are
+    raised as they are met; done() then requires every tensor to live on one GPU."""
+
+    def __init__(self):
+        self.seen = []
+
+    def check(self, t, name, dtypes, numel=None, shape=None, contiguous=True, optional=False):
+        if t is None:
+            if optional:
+                return
+            raise TypeError("%s is required" % name)
+        if not isinstance(t, torch.Tensor):
+            raise TypeError("%s must be a torch tensor" % name)
+        dtypes = dtypes if isinstance(dtypes, (tuple, list)) else (dtypes,)
+        if t.dtype not in dtypes:
+            raise TypeError("%s must have dtype %s, not %s" % (name, " or ".join(str(d) for d in dtypes), t.dtype))
+        if shape is not None and tuple(t.shape) != tuple(shape):
+            raise ValueError("%s must have shape %s, not %s" % (name, tuple(shape), tuple(t.shape)))
+        if numel is not None and t.numel() < numel:
+            raise ValueError("%s holds %d elements, the call needs %d" % (name, t.numel(), numel))
+        if contiguous and not t.is_contiguous():
+            raise ValueError("%s must be contiguous" % name)
+        self.seen.append((name, t))
+
+    def rows(self, t, name, dtypes):
+        """A 2-D row-major matrix whose rows may be padded (stride(1) == 1, stride(0) >= columns)."""
+        self.check(t, name, dtypes, contiguous=False)
+        if t.dim() != 2 or t.stride(1) != 1 or t.stride(0) < t.shape[1]:
+            raise ValueError("%s must be a 2-D tensor with unit column stride" % name)
+
+    def rank_buffers(self, Q, N, k, ws, all_scores, out):
+        if int(k) < 1:
+            raise ValueError("k must be at least 1")
+        if ws is not _NO_WS:
+            self.check(ws, "ws", torch.uint8, numel=workspace_bytes(N, k, Q))
+        self.check(all_scores, "all_scores", torch.float32, numel=Q * N, optional=True)
+        if all_scores is not None and all_scores.numel() != Q * N:
+            raise ValueError("all_scores must hold exactly Q * N = %d floats" % (Q * N))
+        if out is not None:
+            self.check(out[0], "out scores", torch.float32, numel=Q * k)
+            self.check(out[1], "out indices", torch.int32, numel=Q * k)
+
+    def done(self):
+        dev = None
+        for name, t in self.seen:
+            if not t.is_cuda:
+                raise ValueError("%s must live in GPU memory" % name)
+            if dev is None:
+                dev = t.device
+            elif t.device != dev:
+                raise ValueError("%s is on %s, the call runs on %s" % (name, t.device, dev))
+        return dev
+
+
+_NO_WS = object()
 
 
 def _stream(device):
@@ -122,39 +189,64 @@ def _outputs(Q, k, device):
             torch.empty((Q, k), dtype=torch.int32, device=device))
 
 
+def _dense_args(X, W, bias, k, ws, all_scores, out):
+    a = _Args()
+    a.rows(X, "X", (torch.float32, torch.float16))
+    a.check(W, "W", (torch.float32, torch.float16))
+    W2 = W if W.dim() == 2 else W.unsqueeze(0)
+    N, D = X.shape
+    if W2.dim() != 2 or W2.shape[1] != D:
+        raise ValueError("W must be (Q, %d) or (%d,)" % (D, D))
+    Q = W2.shape[0]
+    a.check(bias, "bias", torch.float32, numel=Q, optional=True)
+    a.rank_buffers(Q, N, k, ws, all_scores, out)
+    return a.done(), W2, N, D, Q
+
+
 def rank_dense(X, W, bias, k, ws, all_scores=None, out=None):
     """X (N,D) fp32/fp16 with row stride X.stride(0); W (Q,D) or (D,); bias (Q,) fp32 tensor or
     None.  Returns (scores (Q,k) fp32, idx (Q,k) int32) on X's device, valid after a stream sync."""
-    W2 = W if W.dim() == 2 else W.unsqueeze(0)
-    assert X.dim() == 2 and X.stride(1) == 1 and W2.is_contiguous()
-    N, D = X.shape
-    Q = W2.shape[0]
-    out_s, out_i = out if out is not None else _outputs(Q, k, X.device)
+    dev, W2, N, D, Q = _dense_args(X, W, bias, k, ws, all_scores, out)
+    out_s, out_i = out if out is not None else _outputs(Q, k, dev)
     rc = lib().otf_rank_dense(_ptr(X), _dtype_code(X), N, D, X.stride(0), _ptr(W2), _dtype_code(W2), Q, _ptr(bias),
-                              k, _ptr(out_s), _ptr(out_i), _ptr(all_scores), _ptr(ws), ws.numel(), _stream(X.device))
+                              k, _ptr(out_s), _ptr(out_i), _ptr(all_scores), _ptr(ws), ws.numel(), _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_rank_dense")
     return out_s, out_i
 
 
 def pq_build_lut(codebooks, w, lut=None):
-    assert codebooks.is_contiguous() and w.is_contiguous()
+    a = _Args()
+    a.check(codebooks, "codebooks", torch.float32)
+    if codebooks.dim() != 3:
+        raise ValueError("codebooks must be (M, K, dsub)")
     M, K, dsub = codebooks.shape
+    a.check(w, "w", torch.float32, numel=M * dsub)
+    a.check(lut, "lut", torch.float32, numel=M * K, optional=True)
+    dev = a.done()
     if lut is None:
-        lut = torch.empty((M, K), dtype=torch.float32, device=codebooks.device)
-    rc = lib().otf_pq_build_lut(_ptr(codebooks), M, K, dsub, _ptr(w), _ptr(lut), _stream(codebooks.device))
+        lut = torch.empty((M, K), dtype=torch.float32, device=dev)
+    rc = lib().otf_pq_build_lut(_ptr(codebooks), M, K, dsub, _ptr(w), _ptr(lut), _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_pq_build_lut")
     return lut
 
 
 def rank_pq(codes, lut, bias, k, ws, all_scores=None, out=None):
-    assert codes.is_contiguous() and lut.is_contiguous()
+    a = _Args()
+    a.check(codes, "codes", torch.uint8)
+    if codes.dim() != 2:
+        raise ValueError("codes must be (N, M)")
     N, M = codes.shape
+    a.check(lut, "lut", torch.float32)
+    if lut.dim() != 2 or lut.shape[0] != M:
+        raise ValueError("lut must be (%d, K)" % M)
     K = lut.shape[1]
-    out_s, out_i = out if out is not None else _outputs(1, k, codes.device)
+    a.rank_buffers(1, N, k, ws, all_scores, out)
+    dev = a.done()
+    out_s, out_i = out if out is not None else _outputs(1, k, dev)
     rc = lib().otf_rank_pq(_ptr(codes), N, M, K, _ptr(lut), float(bias), k, _ptr(out_s), _ptr(out_i),
-                           _ptr(all_scores), _ptr(ws), ws.numel(), _stream(codes.device))
+                           _ptr(all_scores), _ptr(ws), ws.numel(), _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_rank_pq")
     return out_s, out_i
@@ -162,23 +254,34 @@ def rank_pq(codes, lut, bias, k, ws, all_scores=None, out=None):
 
 def rank_binary(bits, D, w, bias, k, ws, all_scores=None, out=None):
     """bits (N, D/32) int32 tensor holding the packed words."""
-    assert bits.is_contiguous() and w.is_contiguous()
+    a = _Args()
+    a.check(bits, "bits", torch.int32)
+    if bits.dim() != 2 or bits.shape[1] * 32 != int(D):
+        raise ValueError("bits must be (N, D/32)")
     N = bits.shape[0]
-    out_s, out_i = out if out is not None else _outputs(1, k, bits.device)
+    a.check(w, "w", torch.float32, numel=int(D))
+    a.rank_buffers(1, N, k, ws, all_scores, out)
+    dev = a.done()
+    out_s, out_i = out if out is not None else _outputs(1, k, dev)
     rc = lib().otf_rank_binary(_ptr(bits), N, D, _ptr(w), float(bias), k, _ptr(out_s), _ptr(out_i),
-                               _ptr(all_scores), _ptr(ws), ws.numel(), _stream(bits.device))
+                               _ptr(all_scores), _ptr(ws), ws.numel(), _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_rank_binary")
     return out_s, out_i
 
 
 def topk(scores, k, ws, out=None):
+    a = _Args()
+    a.check(scores, "scores", torch.float32, contiguous=False)
     S = scores if scores.dim() == 2 else scores.unsqueeze(0)
-    assert S.stride(1) == 1
+    if S.dim() != 2 or S.stride(1) != 1 or (S.shape[0] > 1 and S.stride(0) < S.shape[1]):
+        raise ValueError("scores must be (N,) or (Q, N) with unit column stride")
     Q, N = S.shape
-    out_s, out_i = out if out is not None else _outputs(Q, k, S.device)
+    a.rank_buffers(Q, N, k, ws, None, out)
+    dev = a.done()
+    out_s, out_i = out if out is not None else _outputs(Q, k, dev)
     rc = lib().otf_topk(_ptr(S), N, S.stride(0) if Q > 1 else N, Q, k, _ptr(out_s), _ptr(out_i), _ptr(ws),
-                        ws.numel(), _stream(S.device))
+                        ws.numel(), _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_topk")
     return out_s, out_i
@@ -191,54 +294,88 @@ def sgd_workspace(B, device="cuda"):
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
+def _sgd_args(w, b, Xpos, idx_pos, Xneg, idx_neg, B, ws):
+    a = _Args()
+    a.check(w, "w", torch.float32)
+    if w.dim() != 1:
+        raise ValueError("w must be (D,)")
+    a.check(b, "b", torch.float32, numel=1, optional=True)
+    for X, idx, name in ((Xpos, idx_pos, "pos"), (Xneg, idx_neg, "neg")):
+        if idx is None:
+            continue
+        # row numbers are read as int32 on the device: an int64 tensor would be read as pairs
+        a.check(idx, "idx_" + name, torch.int32)
+        a.rows(X, "X" + name, torch.float32)
+        if X.shape[1] != w.shape[0]:
+            raise ValueError("X%s has %d columns, w has %d" % (name, X.shape[1], w.shape[0]))
+    if B >= 1:
+        a.check(ws, "ws", torch.uint8, numel=int(lib().otf_sgd_workspace_bytes(int(B))))
+    return a.done()
+
+
 def svm_sgd_step(w, b, Xpos, idx_pos, Xneg, idx_neg, lam, t, update_bias, ws):
     """Updates w (D,) fp32 and b (1,) fp32 (or None) in place on the current stream."""
-    D = w.shape[0]
     n_pos = 0 if idx_pos is None else idx_pos.numel()
     n_neg = 0 if idx_neg is None else idx_neg.numel()
-    rc = lib().otf_svm_sgd_step(_ptr(w), _ptr(b), D, _ptr(Xpos), 0 if Xpos is None else Xpos.stride(0),
+    dev = _sgd_args(w, b, Xpos, idx_pos, Xneg, idx_neg, n_pos + n_neg, ws)
+    rc = lib().otf_svm_sgd_step(_ptr(w), _ptr(b), w.shape[0], _ptr(Xpos), 0 if Xpos is None else Xpos.stride(0),
                                 _ptr(idx_pos), n_pos, _ptr(Xneg), 0 if Xneg is None else Xneg.stride(0),
                                 _ptr(idx_neg), n_neg, float(lam), int(t), int(bool(update_bias)), _ptr(ws),
-                                ws.numel(), _stream(w.device))
+                                ws.numel(), _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_svm_sgd_step")
 
 
 def svm_sgd_pass(w, b, Xpos, idx_pos, Xneg, idx_neg, lam, t_first, update_bias, ws):
     """idx_pos, idx_neg: contiguous int32 (steps, half) tensors; runs the steps t_first, t_first + 1, ..."""
-    assert idx_pos.is_contiguous() and idx_neg.is_contiguous() and idx_pos.shape[0] == idx_neg.shape[0]
+    for idx, name in ((idx_pos, "idx_pos"), (idx_neg, "idx_neg")):
+        if not isinstance(idx, torch.Tensor) or idx.dtype != torch.int32:
+            raise TypeError("%s must be an int32 tensor" % name)
+    if idx_pos.dim() != 2 or idx_neg.dim() != 2 or idx_pos.shape[0] != idx_neg.shape[0]:
+        raise ValueError("idx_pos and idx_neg must be (steps, n_pos) and (steps, n_neg)")
+    dev = _sgd_args(w, b, Xpos, idx_pos, Xneg, idx_neg, idx_pos.shape[1] + idx_neg.shape[1], ws)
     rc = lib().otf_svm_sgd_pass(_ptr(w), _ptr(b), w.shape[0], _ptr(Xpos), Xpos.stride(0), _ptr(idx_pos),
                                 idx_pos.shape[1], _ptr(Xneg), Xneg.stride(0), _ptr(idx_neg), idx_neg.shape[1],
                                 float(lam), int(t_first), idx_pos.shape[0], int(bool(update_bias)), _ptr(ws),
-                                ws.numel(), _stream(w.device))
+                                ws.numel(), _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_svm_sgd_pass")
 
 
 def tight_frame(G, m, U=None):
     """U (n, m) fp32: the frame of the binarisation encoder from the random matrix G (n, n) fp32."""
-    assert G.is_contiguous() and G.dtype == torch.float32 and G.shape[0] == G.shape[1]
+    a = _Args()
+    a.check(G, "G", torch.float32)
+    if G.dim() != 2 or G.shape[0] != G.shape[1]:
+        raise ValueError("G must be square")
     n = G.shape[0]
+    a.check(U, "U", torch.float32, shape=(n, int(m)), optional=True)
+    dev = a.done()
     if U is None:
-        U = torch.empty((n, m), dtype=torch.float32, device=G.device)
+        U = torch.empty((n, m), dtype=torch.float32, device=dev)
     nbytes = int(lib().otf_tight_frame_workspace_bytes(n, int(m)))
-    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=G.device)
-    rc = lib().otf_tight_frame(_ptr(G), n, int(m), _ptr(U), _ptr(ws), ws.numel(), _stream(G.device))
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
+    rc = lib().otf_tight_frame(_ptr(G), n, int(m), _ptr(U), _ptr(ws), ws.numel(), _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_tight_frame")
-    torch.cuda.current_stream(G.device).synchronize()      # ws is released on return
+    torch.cuda.current_stream(dev).synchronize()      # ws is released on return
     return U
 
 
 def binarize(phi, U, bits=None):
     """bits (N, n/32) int32 (the uint32 words of the codes): sign of U phi, packed LSB first."""
-    assert phi.dtype == torch.float32 and U.dtype == torch.float32 and U.is_contiguous() and phi.stride(1) == 1
+    a = _Args()
+    a.rows(phi, "phi", torch.float32)
     N, m = phi.shape
+    a.check(U, "U", torch.float32)
+    if U.dim() != 2 or U.shape[1] != m or U.shape[0] % 32:
+        raise ValueError("U must be (n, %d) with n a multiple of 32" % m)
     n = U.shape[0]
-    assert U.shape[1] == m
+    a.check(bits, "bits", torch.int32, shape=(N, n // 32), optional=True)
+    dev = a.done()
     if bits is None:
-        bits = torch.empty((N, n // 32), dtype=torch.int32, device=phi.device)
-    rc = lib().otf_binarize(_ptr(phi), N, m, phi.stride(0), _ptr(U), n, _ptr(bits), _stream(phi.device))
+        bits = torch.empty((N, n // 32), dtype=torch.int32, device=dev)
+    rc = lib().otf_binarize(_ptr(phi), N, m, phi.stride(0), _ptr(U), n, _ptr(bits), _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_binarize")
     return bits
@@ -251,15 +388,26 @@ def pq_train_workspace(M, dsub, device="cuda"):
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
+def _pq_train_args(X, codebooks, ws, codes, distortion=None):
+    a = _Args()
+    a.rows(X, "X", torch.float32)
+    a.check(codebooks, "codebooks", torch.float32)
+    if codebooks.dim() != 3 or codebooks.shape[0] * codebooks.shape[2] != X.shape[1]:
+        raise ValueError("codebooks must be (M, K, dsub) with M * dsub = %d" % X.shape[1])
+    M, K, dsub = codebooks.shape
+    a.check(ws, "ws", torch.uint8, numel=int(lib().otf_pq_train_workspace_bytes(int(M), int(dsub))))
+    a.check(codes, "codes", torch.uint8, shape=(X.shape[0], M), optional=True)
+    a.check(distortion, "distortion", torch.float64, numel=1, optional=True)
+    return a.done(), M, K, dsub, X.shape[0]
+
+
 def pq_encode(X, codebooks, ws, codes=None):
     """codes (N, M) uint8: nearest centre of every sub-block.  X (N, M*dsub) fp32, codebooks (M, 256, dsub)."""
-    assert X.dtype == torch.float32 and X.stride(1) == 1 and codebooks.is_contiguous()
-    M, K, dsub = codebooks.shape
-    N = X.shape[0]
+    dev, M, K, dsub, N = _pq_train_args(X, codebooks, ws, codes)
     if codes is None:
-        codes = torch.empty((N, M), dtype=torch.uint8, device=X.device)
+        codes = torch.empty((N, M), dtype=torch.uint8, device=dev)
     rc = lib().otf_pq_encode(_ptr(X), N, X.stride(0), _ptr(codebooks), M, K, dsub, _ptr(codes), _ptr(ws), ws.numel(),
-                             _stream(X.device))
+                             _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_pq_encode")
     return codes
@@ -267,15 +415,13 @@ def pq_encode(X, codebooks, ws, codes=None):
 
 def pq_lloyd_step(X, codebooks, ws, codes=None, distortion=None):
     """One k-means iteration; codebooks is updated in place.  Returns (codes, distortion (1,) float64 tensor)."""
-    assert X.dtype == torch.float32 and X.stride(1) == 1 and codebooks.is_contiguous()
-    M, K, dsub = codebooks.shape
-    N = X.shape[0]
+    dev, M, K, dsub, N = _pq_train_args(X, codebooks, ws, codes, distortion)
     if codes is None:
-        codes = torch.empty((N, M), dtype=torch.uint8, device=X.device)
+        codes = torch.empty((N, M), dtype=torch.uint8, device=dev)
     if distortion is None:
-        distortion = torch.zeros(1, dtype=torch.float64, device=X.device)
+        distortion = torch.zeros(1, dtype=torch.float64, device=dev)
     rc = lib().otf_pq_lloyd_step(_ptr(X), N, X.stride(0), _ptr(codebooks), M, K, dsub, _ptr(codes), _ptr(distortion),
-                                 _ptr(ws), ws.numel(), _stream(X.device))
+                                 _ptr(ws), ws.numel(), _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_pq_lloyd_step")
     return codes, distortion
@@ -286,6 +432,13 @@ def debug_fallback_taken(ws):
     ranking by full selection (reads the flag the kernels leave in the workspace; test use only)."""
     torch.cuda.synchronize()
     return int(ws[60:64].view(torch.int32).item()) != 0
+
+
+def debug_set(key, value):
+    """Sets one of the library's diagnostic switches (DEBUG_*); 0 clears it."""
+    rc = lib().otf_debug_set(int(key), int(value))
+    if rc != OTF_OK:
+        raise OtfError(rc, "otf_debug_set")
 
 
 def profile_begin(max_records):

@@ -4,7 +4,6 @@
 #include "otf.h"
 
 #include <atomic>
-#include <cstdlib>
 #include <vector>
 
 #include "otf_internal.h"
@@ -73,7 +72,7 @@ SelectWs sample_select_ws(void *ws, const WsLayout &L) {
 static bool filter_eligible(int64_t N, int32_t k, const float *all_scores) {
     if (all_scores || k > kFilterMaxK) return false;
     if (sample_rows(N) < 8 * kSampleGroup) return false;
-    return tune_int("OTF_RANK_PATH", 0) != 1;      // 1 forces the full selection (testing, comparison)
+    return tune_int(OTF_DEBUG_RANK_PATH, 0) != 1;      // 1 forces the full selection (testing, comparison)
 }
 
 // Rank of the sample key that becomes the threshold: the sample holds Nv of N rows, so the m-th
@@ -95,13 +94,30 @@ int device_cu_count() {
     return cus;
 }
 
-int tune_int(const char *name, int fallback) {
-    const char *v = std::getenv(name);
-    if (!v || !*v) return fallback;
-    char *endp = nullptr;
-    long x = std::strtol(v, &endp, 10);
-    if (endp == v || x < 1 || x > 65536) return fallback;
-    return (int)x;
+// Diagnostic switches (otf_debug_set): 0 = not set, the built-in choice applies.
+static std::atomic<int> g_debug[OTF_DEBUG_KEYS];
+
+int tune_int(int key, int fallback) {
+    const int v = g_debug[key].load(std::memory_order_relaxed);
+    return v > 0 ? v : fallback;
+}
+
+// Which values a switch accepts (besides 0, which clears it).
+static bool debug_value_ok(int key, int v) {
+    switch (key) {
+        case OTF_DEBUG_RANK_PATH:
+        case OTF_DEBUG_BINARIZE_FP32:
+        case OTF_DEBUG_PQENC_FP32: return v == 1;
+        case OTF_DEBUG_SCAN_THREADS: return v >= 64 && v <= 1024 && v % 64 == 0;   // whole waves, the kernels' launch bound
+        case OTF_DEBUG_SCAN_UNROLL:
+        case OTF_DEBUG_BINARIZE_WAVES: return v == 4 || v == 8;
+        case OTF_DEBUG_PQENC_RANGE: return v >= 4 && v <= 64 && v % 4 == 0;
+        case OTF_DEBUG_DENSE_BLOCKS_PER_CU:
+        case OTF_DEBUG_NARROW_BLOCKS_PER_CU:
+        case OTF_DEBUG_MFMA_BLOCKS_PER_CU:
+        case OTF_DEBUG_PQENC_BLOCKS_PER_CU: return v >= 1 && v <= 8;
+        default: return false;
+    }
 }
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -117,8 +133,8 @@ static int check_rank_common(int64_t N, int32_t k, int32_t Q, const float *out_s
                              const void *ws, size_t ws_bytes, WsLayout *L) {
     if (N < 1 || Q < 1 || k < 1 || !out_scores || !out_idx) return OTF_ERR_INVALID_ARG;
     if (N >= ((int64_t)1 << 31)) return OTF_ERR_UNSUPPORTED;
-    if (k > N || k > OTF_MAX_K) return OTF_ERR_INVALID_ARG;
-    if (Q > 65535) return OTF_ERR_UNSUPPORTED;
+    if (k > N) return OTF_ERR_INVALID_ARG;
+    if (k > OTF_MAX_K || Q > 65535) return OTF_ERR_UNSUPPORTED;     // limits of this build, not of the operation
     *L = ws_layout(N, Q);
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || ws_bytes < L->total) return OTF_ERR_WORKSPACE;
     return OTF_OK;
@@ -183,9 +199,10 @@ int otf_topk(const float *scores, int64_t N, int64_t ld, int32_t Q, int32_t k, f
     return hip_status(e);
 }
 
-int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t ldx, const void *W, otf_dtype wdt,
-                   int32_t Q, const float *bias, int32_t k, float *out_scores, int32_t *out_idx, float *all_scores,
-                   void *ws, size_t ws_bytes, void *stream) {
+// The argument checks of otf_rank_dense (host only: nothing is dereferenced or enqueued).
+static int otf_rank_dense_check(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t ldx, const void *W,
+                                otf_dtype wdt, int32_t Q, int32_t k, const float *out_scores, const int32_t *out_idx,
+                                const void *ws, size_t ws_bytes) {
     WsLayout L;
     if (!X || !W || D < 1) return OTF_ERR_INVALID_ARG;
     if ((xdt != OTF_F32 && xdt != OTF_F16) || (wdt != OTF_F32 && wdt != OTF_F16)) return OTF_ERR_INVALID_ARG;
@@ -196,6 +213,15 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
     if (!aligned16(X) || ((size_t)ldx * xsize) % 16 != 0) return OTF_ERR_INVALID_ARG;
     if (xdt == OTF_F32 && wdt != OTF_F32) return OTF_ERR_UNSUPPORTED;
     if (D % (16 / xsize) != 0 || D > kDenseMaxD) return OTF_ERR_UNSUPPORTED;
+    return OTF_OK;
+}
+
+int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t ldx, const void *W, otf_dtype wdt,
+                   int32_t Q, const float *bias, int32_t k, float *out_scores, int32_t *out_idx, float *all_scores,
+                   void *ws, size_t ws_bytes, void *stream) {
+    const int rc = otf_rank_dense_check(X, xdt, N, D, ldx, W, wdt, Q, k, out_scores, out_idx, ws, ws_bytes);
+    if (rc != OTF_OK) return rc;
+    const WsLayout L = ws_layout(N, Q);
 
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     SelectWs sw = select_ws(ws, L);
@@ -204,7 +230,10 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
     const int x_half = xdt == OTF_F16, w_half = wdt == OTF_F16;
     const size_t wsize = w_half ? 2 : 4;
 
-    const bool mfma = Q > 1 && x_half && w_half && Q % 32 == 0 && D % 128 == 0 && aligned16(W);
+    // (the matrix-core kernel addresses the 128 rows of a tile with 32-bit byte offsets from the tile's
+    //  base: a row stride that overflows them goes to the per-classifier scan instead)
+    const bool mfma = Q > 1 && x_half && w_half && Q % 32 == 0 && D % 128 == 0 && aligned16(W) &&
+                      (uint64_t)ldx * 2u * 127u + 256u < ((uint64_t)1 << 32);
     const uint8_t *Wb = reinterpret_cast<const uint8_t *>(W);
 
     if (Q == 1 && dense_scan_filters(x_half, D) && filter_eligible(N, k, all_scores)) {
@@ -457,6 +486,13 @@ int otf_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *codebooks, 
     if (rc != OTF_OK) return rc;
     return hip_status(launch_pq_lloyd_step(X, N, ldx, codebooks, M, dsub, codes, distortion, ws,
                                            reinterpret_cast<hipStream_t>(stream)));
+}
+
+int otf_debug_set(int key, int value) {
+    if (key < 0 || key >= OTF_DEBUG_KEYS) return OTF_ERR_INVALID_ARG;
+    if (value != 0 && !debug_value_ok(key, value)) return OTF_ERR_INVALID_ARG;
+    g_debug[key].store(value, std::memory_order_relaxed);
+    return OTF_OK;
 }
 
 int otf_profile_begin(int32_t max_records) {

@@ -432,7 +432,7 @@ static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t
         while (lpr < chunks) lpr <<= 1;
         const int64_t rows_per_wave_iter = (64 / lpr) * 8;
         int64_t waves = (N + rows_per_wave_iter - 1) / rows_per_wave_iter;
-        grid = (int)std::min<int64_t>((waves + 3) / 4, (int64_t)cus * tune_int("OTF_NARROW_BLOCKS_PER_CU", 2));
+        grid = (int)std::min<int64_t>((waves + 3) / 4, (int64_t)cus * tune_int(OTF_DEBUG_NARROW_BLOCKS_PER_CU, 2));
         if (grid < 1) grid = 1;
         // the short sample scan ends in every workgroup adding to the same hundred-odd bins of the
         // global histogram at once: one workgroup per compute unit halves that queue (20.6 -> 16.7 us)
@@ -460,7 +460,7 @@ static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t
 #undef OTF_NARROW
     } else {
         if (x.emit != kEmitScores || x.gate) return hipErrorInvalidValue;   // only the narrow kernel filters
-        grid = (int)std::min<int64_t>((N + 3) / 4, (int64_t)cus * tune_int("OTF_DENSE_BLOCKS_PER_CU", 1));
+        grid = (int)std::min<int64_t>((N + 3) / 4, (int64_t)cus * tune_int(OTF_DEBUG_DENSE_BLOCKS_PER_CU, 1));
         if (grid < 1) grid = 1;
         const int V = (chunks + 63) / 64;
         const bool full = chunks == V * 64;

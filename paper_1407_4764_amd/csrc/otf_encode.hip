@@ -41,7 +41,20 @@ __global__ __launch_bounds__(kFrameThreads) void tight_frame_kernel(const float 
     __shared__ double part[kFrameThreads / 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = kFrameThreads / 64;
     for (int j = 0; j < m; ++j) {
-        for (int i = tid; i < n; i += kFrameThreads) v[i] = (double)G[(size_t)i * n + j];
+        // norm of the column as given: what is left after orthogonalisation counts as zero when it is
+        // rounding noise relative to this (a column in the span of its predecessors leaves ~1e-16 of
+        // its length, not exactly 0)
+        double s0 = 0.0;
+        for (int i = tid; i < n; i += kFrameThreads) {
+            const double g = (double)G[(size_t)i * n + j];
+            v[i] = g;
+            s0 += g * g;
+        }
+        s0 = wave_sum_f64(s0);
+        if (lane == 0) part[wave] = s0;
+        __syncthreads();
+        double norm0_2 = 0.0;
+        for (int w = 0; w < nwaves; ++w) norm0_2 += part[w];
         __syncthreads();
         for (int pass = 0; pass < 2; ++pass) {
             // coef[c] = <q_c, v> for c < j: one wave per column c
@@ -68,7 +81,8 @@ __global__ __launch_bounds__(kFrameThreads) void tight_frame_kernel(const float 
         __syncthreads();
         double norm2 = 0.0;
         for (int w = 0; w < nwaves; ++w) norm2 += part[w];
-        const double inv = norm2 > 0.0 ? 1.0 / sqrt(norm2) : 0.0;   // dependent columns give a zero column
+        const double tol = (double)n * 2.220446049250313e-16;
+        const double inv = norm2 > tol * tol * norm0_2 ? 1.0 / sqrt(norm2) : 0.0;   // dependent columns give a zero column
         for (int i = tid; i < n; i += kFrameThreads) {
             const double q = v[i] * inv;
             Qd[(size_t)i * m + j] = q;
@@ -363,11 +377,11 @@ hipError_t launch_binarize(const float *phi, int64_t N, int m, int64_t ld, const
     if (m > kEncK || m % 4 || n % 32) return hipErrorInvalidValue;
     const int64_t ntiles = (N + kEncRows - 1) / kEncRows;
     const int grid = (int)std::min<int64_t>(ntiles, device_cu_count());
-    if (!tune_int("OTF_BINARIZE_FP32", 0)) {
+    if (!tune_int(OTF_DEBUG_BINARIZE_FP32, 0)) {
         // Two workgroups of four waves per compute unit rather than one of eight: each has its own
         // barrier, so the two waves of a SIMD drift apart and one's matrix instructions run beside
         // the other's vector work.
-        const bool four = tune_int("OTF_BINARIZE_WAVES", 4) == 4;
+        const bool four = tune_int(OTF_DEBUG_BINARIZE_WAVES, 4) == 4;
         const int64_t tiles = (N + (four ? 128 : 256) - 1) / (four ? 128 : 256);
         const int g = (int)std::min<int64_t>(tiles, (int64_t)device_cu_count() * (four ? 2 : 1));
 #define OTF_BIN_LAUNCH(NQP)                                                                                     \
@@ -380,7 +394,7 @@ hipError_t launch_binarize(const float *phi, int64_t N, int m, int64_t ld, const
             default: OTF_BIN_LAUNCH(4); break;
         }
 #undef OTF_BIN_LAUNCH
-    } else if (tune_int("OTF_BINARIZE_WAVES", 8) == 4)       // the fp32 matrix instructions, kept for comparison
+    } else if (tune_int(OTF_DEBUG_BINARIZE_WAVES, 8) == 4)       // the fp32 matrix instructions, kept for comparison
         binarize_kernel<2><<<grid, 256, 0, s>>>(phi, (long long)N, m, (long long)ld, U, n, bits);
     else
         binarize_kernel<1><<<grid, 512, 0, s>>>(phi, (long long)N, m, (long long)ld, U, n, bits);

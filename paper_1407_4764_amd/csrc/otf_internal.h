@@ -4,6 +4,7 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "otf.h"
 #include "otf_device.h"
 
 namespace otf {
@@ -125,7 +126,7 @@ hipError_t launch_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *c
 
 int device_cu_count();
 
-// Launch-shape knobs for tuning runs: integer environment variable `name`, else `fallback`.
-int tune_int(const char *name, int fallback);
+// Diagnostic switch `key` (an otf_debug_key, set through otf_debug_set), else `fallback`.
+int tune_int(int key, int fallback);
 
 }  // namespace otf

@@ -268,7 +268,7 @@ static hipError_t launch_mfma_qt(const uint8_t *X, int64_t N, int D, int64_t ldx
                                  ScanEmit emit, float *scores, int64_t ld_scores, const SelState *tau, SelState *st,
                                  unsigned long long *cand, const SelState *gate, uint32_t *tile_ctr, hipStream_t s) {
     const int64_t ntiles = (N + kBM - 1) / kBM;
-    const int grid = (int)std::min<int64_t>(ntiles, (int64_t)device_cu_count() * tune_int("OTF_MFMA_BLOCKS_PER_CU", 2));
+    const int grid = (int)std::min<int64_t>(ntiles, (int64_t)device_cu_count() * tune_int(OTF_DEBUG_MFMA_BLOCKS_PER_CU, 2));
     const int vec_store = scores && (ld_scores % 4 == 0) && ((reinterpret_cast<uintptr_t>(scores) & 15) == 0);
 #define OTF_MFMA_ARGS X, (long long)N, D, (long long)ldx * 2, W, bias, scores, (long long)ld_scores, vec_store, tau, st, cand, gate, tile_ctr
     if (emit == kEmitScores) dense_mfma_kernel<QT, kEmitScores><<<grid, 256, 0, s>>>(OTF_MFMA_ARGS);

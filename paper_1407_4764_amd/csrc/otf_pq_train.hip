@@ -778,10 +778,10 @@ hipError_t launch_pq_encode(const float *X, int64_t N, int64_t ldx, const float 
                             uint8_t *codes, void *ws, hipStream_t s) {
     PqTrainWs w = pq_train_ws(ws, M, dsub);
     const int64_t ntiles = (N + 255) / 256;
-    const int mr = std::min(M, std::max(4, tune_int("OTF_PQENC_RANGE", 16) & ~3));   // sub-blocks per work unit, a multiple of 4
+    const int mr = std::min(M, std::max(4, tune_int(OTF_DEBUG_PQENC_RANGE, 16) & ~3));   // sub-blocks per work unit, a multiple of 4
     const int64_t units = ntiles * ((M + mr - 1) / mr);
-    const int grid = (int)std::min<int64_t>(units, (int64_t)device_cu_count() * tune_int("OTF_PQENC_BLOCKS_PER_CU", 3));
-    const bool fp32 = tune_int("OTF_PQENC_FP32", 0) != 0;   // the fp32 matrix instructions, kept for comparison
+    const int grid = (int)std::min<int64_t>(units, (int64_t)device_cu_count() * tune_int(OTF_DEBUG_PQENC_BLOCKS_PER_CU, 3));
+    const bool fp32 = tune_int(OTF_DEBUG_PQENC_FP32, 0) != 0;   // the fp32 matrix instructions, kept for comparison
 #define OTF_PQENC_LAUNCH(D)                                                                                                   \
     if (fp32) {                                                                                                               \
         pq_centre_norms_kernel<<<(M * kPqK + 255) / 256, 256, 0, s>>>(codebooks, M, dsub, w.norms);                          \

@@ -98,7 +98,9 @@ hipError_t launch_sgd_step(float *w, float *b, int D, const float *Xpos, int64_t
                            float lambda, int64_t t, int update_bias, float *coef, hipStream_t s) {
     const int B = n_pos + n_neg;
     const double eta = 1.0 / ((double)lambda * (double)t);
-    const float shrink = (float)(1.0 - eta * (double)lambda);
+    // 1 - eta * lambda = 1 - 1/t whatever lambda is: formed that way it is exactly 0 at t = 1, as the
+    // recursion needs (w_1 must not depend on w_0 except through which rows violate)
+    const float shrink = (float)(1.0 - 1.0 / (double)t);
     const float scale = (float)(eta / (double)B);
     sgd_margin_kernel<<<(B + 3) / 4, 256, 0, s>>>(w, b, D, Xpos, (long long)ld_pos, idx_pos, n_pos, Xneg,
                                                   (long long)ld_neg, idx_neg, n_neg, coef);

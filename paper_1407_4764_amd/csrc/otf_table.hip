@@ -461,7 +461,7 @@ static hipError_t launch_scan_cfg(const ScanArgs &a, hipStream_t s) {
     const int64_t max_useful = (a.N + 1023) / 1024;
     if (grid > max_useful) grid = (int)max_useful;
     if (grid < 1) grid = 1;
-    const int threads = tune_int("OTF_SCAN_THREADS", kScanThreads);
+    const int threads = tune_int(OTF_DEBUG_SCAN_THREADS, kScanThreads);
     // a multi-phase scan is one launch per phase: each phase meets the partial sums of the one
     // before in the score array, and the launch boundary is what orders them
     for (int sp = 0; sp < (SPLIT ? a.nsplit : 1); ++sp)
@@ -475,7 +475,7 @@ template <int LPR, int GB>
 static hipError_t launch_scan_emit(const ScanArgs &a, ScanEmit emit, hipStream_t s) {
     constexpr int U = LPR <= 2 ? 4 : 8;    // narrow rows own many outputs per lane: fewer loads per tile
     if (LPR >= 8 && a.nsplit == 1 && emit == kEmitFilter) {
-        if (tune_int("OTF_SCAN_UNROLL", 8) == 4) return launch_scan_cfg<LPR, 4, GB, kEmitFilter, false>(a, s);
+        if (tune_int(OTF_DEBUG_SCAN_UNROLL, 8) == 4) return launch_scan_cfg<LPR, 4, GB, kEmitFilter, false>(a, s);
 
     }
     if (a.nsplit > 1) {

@@ -17,3 +17,18 @@ def oracle():
     from oracle import otf_oracle
     otf_oracle.build()
     return otf_oracle
+
+
+@pytest.fixture
+def debug_switches():
+    """Sets diagnostic switches of the library for one test and clears them afterwards."""
+    from paper_1407_4764_amd import binding
+    used = []
+
+    def set_all(switches):
+        for key, value in switches.items():
+            binding.debug_set(key, value)
+            used.append(key)
+    yield set_all
+    for key in used:
+        binding.debug_set(key, 0)

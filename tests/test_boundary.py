@@ -59,7 +59,8 @@ def test_topk_argument_errors(L):
     assert _topk(L, N=0) == binding.OTF_ERR_INVALID_ARG
     assert _topk(L, k=0) == binding.OTF_ERR_INVALID_ARG
     assert _topk(L, k=101) == binding.OTF_ERR_INVALID_ARG
-    assert _topk(L, N=100000, ld=100000, k=binding.OTF_MAX_K + 1) == binding.OTF_ERR_INVALID_ARG
+    assert _topk(L, N=100000, ld=100000, k=binding.OTF_MAX_K + 1) == binding.OTF_ERR_UNSUPPORTED   # a limit of the build
+    assert _topk(L, N=100, ld=100, k=binding.OTF_MAX_K + 1) == binding.OTF_ERR_INVALID_ARG         # k > N comes first
     assert _topk(L, ld=99) == binding.OTF_ERR_INVALID_ARG
     assert _topk(L, os_=None) == binding.OTF_ERR_INVALID_ARG
     assert _topk(L, N=1 << 31, ld=1 << 31) == binding.OTF_ERR_UNSUPPORTED
@@ -170,3 +171,25 @@ def test_pq_train_argument_errors(L):
     assert enc(M=126) == binding.OTF_ERR_UNSUPPORTED
     assert enc(wsb=4096) == binding.OTF_ERR_WORKSPACE
     assert L.otf_pq_lloyd_step(FAKE, 1000, 2048, None, 128, 256, 16, FAKE, None, FAKE, BIG, None) == binding.OTF_ERR_INVALID_ARG
+
+
+def test_debug_switches_accept_only_their_own_values(L):
+    assert L.otf_debug_set(-1, 1) == binding.OTF_ERR_INVALID_ARG
+    assert L.otf_debug_set(binding.DEBUG_KEYS, 1) == binding.OTF_ERR_INVALID_ARG
+    assert L.otf_debug_set(binding.DEBUG_RANK_PATH, 2) == binding.OTF_ERR_INVALID_ARG
+    assert L.otf_debug_set(binding.DEBUG_SCAN_THREADS, 100) == binding.OTF_ERR_INVALID_ARG      # not whole waves
+    assert L.otf_debug_set(binding.DEBUG_SCAN_THREADS, 2048) == binding.OTF_ERR_INVALID_ARG     # above the launch bound
+    assert L.otf_debug_set(binding.DEBUG_SCAN_UNROLL, 5) == binding.OTF_ERR_INVALID_ARG
+    assert L.otf_debug_set(binding.DEBUG_PQENC_RANGE, 6) == binding.OTF_ERR_INVALID_ARG
+    assert L.otf_debug_set(binding.DEBUG_MFMA_BLOCKS_PER_CU, 9) == binding.OTF_ERR_INVALID_ARG
+    for key, value in ((binding.DEBUG_RANK_PATH, 1), (binding.DEBUG_SCAN_THREADS, 512), (binding.DEBUG_SCAN_UNROLL, 4),
+                       (binding.DEBUG_PQENC_RANGE, 8), (binding.DEBUG_DENSE_BLOCKS_PER_CU, 2)):
+        assert L.otf_debug_set(key, value) == binding.OTF_OK
+        assert L.otf_debug_set(key, 0) == binding.OTF_OK                                        # cleared again
+
+
+def test_the_library_reads_no_environment_variables():
+    """Path and launch-shape switches go through otf_debug_set, never through the environment."""
+    csrc = os.path.join(ROOT, "paper_1407_4764_amd", "csrc")
+    for name in os.listdir(csrc):
+        assert "getenv" not in open(os.path.join(csrc, name)).read(), name

@@ -33,6 +33,20 @@ def test_tight_frame_matches_the_oracle(n, m):
     np.testing.assert_allclose(U.T @ U, np.eye(m), atol=2e-6)
 
 
+def test_dependent_columns_of_the_random_matrix_give_zero_frame_columns():
+    """Columns in the span of their predecessors (a repeat, a multiple, a zero column) must come
+    out as zero columns, not as normalised rounding noise, and must not disturb the others."""
+    n, m = 256, 16
+    G = synth.random_square(n, SEED + 50)
+    G[:, 3] = G[:, 1]
+    G[:, 5] = -2.0 * G[:, 2]                       # (exact in fp32, so exactly dependent)
+    G[:, 7] = 0.0
+    U = binding.tight_frame(G.to(DEV), m).cpu().numpy().astype(np.float64)
+    ref = enc.tight_frame(G.numpy(), m)
+    assert np.all(ref[:, [3, 5, 7]] == 0.0) and np.all(U[:, [3, 5, 7]] == 0.0)
+    assert np.max(np.abs(U - ref)) <= 1e-6
+
+
 @pytest.mark.parametrize("N,m,n", [(3001, 128, 2048), (1, 128, 2048), (777, 128, 1024), (1000, 64, 512),
                                    (515, 32, 4096), (256, 4, 32)])
 def test_codes_match_the_oracle_outside_the_rounding_band(N, m, n):
@@ -52,17 +66,16 @@ def test_codes_match_the_oracle_outside_the_rounding_band(N, m, n):
     np.testing.assert_array_equal(_unpack(enc.binarize(phi.numpy(), U), n), ref)   # the packed form says the same
 
 
-@pytest.mark.parametrize("waves", ["8", "4"])
-def test_kernel_on_fp32_matrix_instructions_meets_the_same_bar(waves, monkeypatch):
-    """The comparison kernel (OTF_BINARIZE_FP32=1, read by the library at every call) stays correct."""
-    monkeypatch.setenv("OTF_BINARIZE_FP32", "1")
-    monkeypatch.setenv("OTF_BINARIZE_WAVES", waves)
+@pytest.mark.parametrize("waves", [8, 4])
+def test_kernel_on_fp32_matrix_instructions_meets_the_same_bar(waves, debug_switches):
+    """The comparison kernel (diagnostic switch OTF_DEBUG_BINARIZE_FP32) stays correct."""
+    debug_switches({binding.DEBUG_BINARIZE_FP32: 1, binding.DEBUG_BINARIZE_WAVES: waves})
     test_codes_match_the_oracle_outside_the_rounding_band(1300, 128, 2048)
     test_codes_match_the_oracle_outside_the_rounding_band(300, 32, 512)
 
 
-def test_eight_wave_workgroups_meet_the_same_bar(monkeypatch):
-    monkeypatch.setenv("OTF_BINARIZE_WAVES", "8")
+def test_eight_wave_workgroups_meet_the_same_bar(debug_switches):
+    debug_switches({binding.DEBUG_BINARIZE_WAVES: 8})
     test_codes_match_the_oracle_outside_the_rounding_band(1300, 128, 2048)
     test_codes_match_the_oracle_outside_the_rounding_band(700, 64, 512)
 

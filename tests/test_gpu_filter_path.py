@@ -3,8 +3,6 @@ output): a strided sample of the store sets a threshold, the scan keeps only row
 and a full selection stands behind it in case the list cannot serve.  Checked here: parity with
 the CPU oracle, bit-identical results with the full-selection path, and the cases built to make
 the candidate list fail (too few rows, too many rows, every score equal)."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -24,12 +22,12 @@ def _both_paths(fn):
     a = fn()
     torch.cuda.synchronize()
     a = (a[0].clone(), a[1].clone())
-    os.environ["OTF_RANK_PATH"] = "1"
+    binding.debug_set(binding.DEBUG_RANK_PATH, 1)
     try:
         b = fn()
         torch.cuda.synchronize()
     finally:
-        del os.environ["OTF_RANK_PATH"]
+        binding.debug_set(binding.DEBUG_RANK_PATH, 0)
     return a, (b[0].clone(), b[1].clone())
 
 
@@ -44,7 +42,6 @@ def test_pq_filtered_scan(oracle, N, M, dsub, k):
     ws = binding.make_workspace(N, k)
     (val, idx), (val2, idx2) = _both_paths(lambda: binding.rank_pq(cd, lut, 0.125, k, ws))
     assert torch.equal(idx, idx2) and torch.equal(val, val2)
-    os.environ.pop("OTF_RANK_PATH", None)
     binding.rank_pq(cd, lut, 0.125, k, ws)
     assert not binding.debug_fallback_taken(ws)
     ref = oracle.pq_scores_reconstruct(codes.numpy(), cb.numpy(), w.numpy(), 0.125)

@@ -118,6 +118,23 @@ def test_rank_dense_matrix_core_path(oracle, N, D, Q, k, with_all):
         assert_topk_ok(oracle, ref[q], k, idx[q].cpu().numpy(), val[q].cpu().numpy(), RTOL16, "mfma q=%d" % q)
 
 
+def test_row_stride_beyond_the_matrix_core_kernels_offsets_takes_the_scan_per_classifier(oracle):
+    """The matrix-core kernel reaches the 128 rows of a tile with 32-bit byte offsets.  A strided view
+    whose 127 row strides pass 4 GiB must not wrap: it is scored one classifier at a time instead."""
+    N, D, Q, k = 150, 128, 32, 10
+    ldx = (1 << 24) + 8                                         # halves: 127 * ldx * 2 bytes > 4 GiB
+    X = synth.dense_features(N, D, SEED + 6, dtype=torch.float16)
+    W = synth.normal_matrix(Q, D, 0.05, SEED + 17, dtype=torch.float16)
+    ref = oracle.dense_scores(X.numpy(), W.numpy(), None)
+    big = torch.empty((N, ldx), dtype=torch.float16, device=DEV)  # 5 GB, only the first D columns are touched
+    big[:, :D] = X.to(DEV)
+    ws = binding.make_workspace(N, k, Q)
+    val, idx = binding.rank_dense(big[:, :D], W.to(DEV), None, k, ws)
+    _sync()
+    for q in range(Q):
+        assert_topk_ok(oracle, ref[q], k, idx[q].cpu().numpy(), val[q].cpu().numpy(), RTOL16, "wide stride q=%d" % q)
+
+
 # ---------------------------------------------------------------------------------- PQ
 @pytest.mark.parametrize("N,M,dsub,k", [(5000, 128, 16, 100), (40003, 128, 16, 1000), (1, 128, 4, 1),
                                          (1025, 16, 8, 33), (3000, 32, 4, 10), (2047, 64, 4, 64),
@@ -327,3 +344,11 @@ def test_sgd_closed_forms_on_gpu(oracle):
     binding.svm_sgd_step(w, None, Xp.to(DEV), ip.to(DEV), None, None, lam, 4, False, ws)
     _sync()
     np.testing.assert_allclose(w.cpu().numpy(), np.full(D, 7.5), rtol=1e-6)
+    # the same at t = 1, where the shrink factor 1 - 1/t is exactly 0 whatever lambda is: with no
+    # violator nothing of w0 may survive (1 - (1/(lambda t)) lambda formed in floating point leaves
+    # ~1e-16 of it for lambda = 1e-4)
+    for lam1 in (1e-4, 0.3, 1.0):
+        w = torch.full((D,), 10.0, device=DEV)
+        binding.svm_sgd_step(w, None, Xp.to(DEV), ip.to(DEV), None, None, lam1, 1, False, ws)
+        _sync()
+        assert torch.count_nonzero(w).item() == 0

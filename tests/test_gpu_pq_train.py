@@ -51,9 +51,9 @@ def test_codes_are_nearest_centres(N, M, dsub):
 
 
 @pytest.mark.parametrize("N,M,dsub", [(1500, 128, 16), (900, 16, 8), (1100, 32, 4)])
-def test_kernel_on_fp32_matrix_instructions_meets_the_same_bar(N, M, dsub, monkeypatch):
-    """The comparison kernel (OTF_PQENC_FP32=1, read by the library at every call) stays correct."""
-    monkeypatch.setenv("OTF_PQENC_FP32", "1")
+def test_kernel_on_fp32_matrix_instructions_meets_the_same_bar(N, M, dsub, debug_switches):
+    """The comparison kernel (diagnostic switch OTF_DEBUG_PQENC_FP32) stays correct."""
+    debug_switches({binding.DEBUG_PQENC_FP32: 1})
     X, C = _data(N, M, dsub, SEED + 40 + dsub)
     ws = binding.pq_train_workspace(M, dsub)
     codes = binding.pq_encode(X.to(DEV), C.to(DEV), ws)
