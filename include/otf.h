@@ -42,7 +42,8 @@ typedef enum {
     OTF_ERR_INVALID_ARG = -1, /* NULL pointer, non-positive size, k out of range, misalignment */
     OTF_ERR_UNSUPPORTED = -2, /* a shape this build has no kernel for (see each function)   */
     OTF_ERR_WORKSPACE = -3,   /* ws is NULL, misaligned or smaller than otf_workspace_bytes */
-    OTF_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed                 */
+    OTF_ERR_HIP = -4,         /* a HIP runtime call or kernel launch failed                 */
+    OTF_ERR_SCRATCH = -5      /* the call needs more scratch than a no-allocation entry point owns */
 } otf_status;
 
 typedef enum { OTF_F32 = 0, OTF_F16 = 1 } otf_dtype;
@@ -80,6 +81,27 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
                    const void *W, otf_dtype wdt, int32_t Q, const float *bias,
                    int32_t k, float *out_scores, int32_t *out_idx,
                    float *all_scores, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * otf_rank_dense for callers that cannot allocate device memory and so cannot bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors as otf_rank_dense without `ws`; the scratch is an array of
+ * OTF_NOALLOC_SCRATCH_BYTES that is part of the library's device code (each GPU the library runs
+ * on holds its own copy until the process ends).  The call allocates and frees nothing.
+ *   - Sizes whose otf_workspace_bytes(N, k, Q) exceed OTF_NOALLOC_SCRATCH_BYTES (one classifier:
+ *     above ~3.7 million rows) return OTF_ERR_SCRATCH and enqueue nothing.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ *     streams or host threads) race and give undefined results; calls on one stream are safe.
+ *     Every call clears the parts of the array that must start at zero itself.
+ *   - The first call on a GPU looks up that GPU's copy of the array (hipGetSymbolAddress); make it
+ *     outside a graph capture.
+ */
+#define OTF_NOALLOC_SCRATCH_BYTES (16u << 20)
+
+int otf_rank_dense_noalloc(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t ldx,
+                           const void *W, otf_dtype wdt, int32_t Q, const float *bias,
+                           int32_t k, float *out_scores, int32_t *out_idx,
+                           float *all_scores, void *stream);
 
 /*
  * Product-quantised store (paper Sec. 3, "Product quantization (PQ)": the feature is cut

@@ -17,6 +17,8 @@ OTF_ERR_INVALID_ARG = -1
 OTF_ERR_UNSUPPORTED = -2
 OTF_ERR_WORKSPACE = -3
 OTF_ERR_HIP = -4
+OTF_ERR_SCRATCH = -5
+OTF_NOALLOC_SCRATCH_BYTES = 16 << 20
 OTF_F32 = 0
 OTF_F16 = 1
 OTF_MAX_K = 8192
@@ -25,7 +27,7 @@ EXPORTS = ["otf_status_string", "otf_workspace_bytes", "otf_rank_dense", "otf_pq
            "otf_rank_binary", "otf_topk", "otf_sgd_workspace_bytes", "otf_svm_sgd_step", "otf_svm_sgd_pass",
            "otf_tight_frame_workspace_bytes",
            "otf_tight_frame", "otf_binarize", "otf_pq_train_workspace_bytes", "otf_pq_encode", "otf_pq_lloyd_step",
-           "otf_profile_begin", "otf_profile_end", "otf_debug_set"]
+           "otf_profile_begin", "otf_profile_end", "otf_debug_set", "otf_rank_dense_noalloc"]
 
 # otf_debug_key
 (DEBUG_RANK_PATH, DEBUG_BINARIZE_FP32, DEBUG_PQENC_FP32, DEBUG_SCAN_THREADS, DEBUG_SCAN_UNROLL, DEBUG_BINARIZE_WAVES,
@@ -59,6 +61,9 @@ def lib():
         L.otf_rank_dense.restype = ctypes.c_int
         L.otf_rank_dense.argtypes = [vp, ctypes.c_int, i64, i32, i64, vp, ctypes.c_int, i32, vp, i32, vp, vp, vp,
                                      vp, sz, vp]
+        L.otf_rank_dense_noalloc.restype = ctypes.c_int
+        L.otf_rank_dense_noalloc.argtypes = [vp, ctypes.c_int, i64, i32, i64, vp, ctypes.c_int, i32, vp, i32, vp, vp, vp,
+                                             vp]
         L.otf_pq_build_lut.restype = ctypes.c_int
         L.otf_pq_build_lut.argtypes = [vp, i32, i32, i32, vp, vp, vp]
         L.otf_rank_pq.restype = ctypes.c_int
@@ -213,6 +218,17 @@ def rank_dense(X, W, bias, k, ws, all_scores=None, out=None):
     if rc != OTF_OK:
         raise OtfError(rc, "otf_rank_dense")
     return out_s, out_i
+
+
+def rank_dense_noalloc(X, W, bias, k, out, all_scores=None):
+    """rank_dense on the library's own scratch: no workspace, and nothing is allocated here either,
+    so the caller supplies the outputs out = (scores (Q,k) fp32, idx (Q,k) int32)."""
+    dev, W2, N, D, Q = _dense_args(X, W, bias, k, _NO_WS, all_scores, out)
+    rc = lib().otf_rank_dense_noalloc(_ptr(X), _dtype_code(X), N, D, X.stride(0), _ptr(W2), _dtype_code(W2), Q,
+                                      _ptr(bias), k, _ptr(out[0]), _ptr(out[1]), _ptr(all_scores), _stream(dev))
+    if rc != OTF_OK:
+        raise OtfError(rc, "otf_rank_dense_noalloc")
+    return out
 
 
 def pq_build_lut(codebooks, w, lut=None):

@@ -162,6 +162,26 @@ struct ScanTimer {
     }
 };
 
+// Scratch of the no-allocation entry point: one array per GPU, living in the code object's own
+// device memory from the moment the library is loaded on that GPU until the process ends.  In
+// host code the array's name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[OTF_NOALLOC_SCRATCH_BYTES];
+static std::atomic<void *> g_scratch_ptr[64];   // per device: where that GPU's copy of the array lives
+
+// Address of the current device's scratch array (resolved once per device, then remembered).
+static int scratch_of_current_device(void **out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hip_status(hipErrorInvalidDevice);
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_status(e == hipSuccess ? hipErrorInvalidSymbol : e);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return OTF_OK;
+}
+
 }  // namespace otf
 
 using namespace otf;
@@ -175,6 +195,7 @@ const char *otf_status_string(int status) {
         case OTF_ERR_UNSUPPORTED: return "OTF_ERR_UNSUPPORTED";
         case OTF_ERR_WORKSPACE: return "OTF_ERR_WORKSPACE";
         case OTF_ERR_HIP: return "OTF_ERR_HIP";
+        case OTF_ERR_SCRATCH: return "OTF_ERR_SCRATCH";
         default: return "OTF_ERR_UNKNOWN";
     }
 }
@@ -310,6 +331,21 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
     }
     if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, 0, s);
     return hip_status(e);
+}
+
+int otf_rank_dense_noalloc(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t ldx, const void *W,
+                           otf_dtype wdt, int32_t Q, const float *bias, int32_t k, float *out_scores, int32_t *out_idx,
+                           float *all_scores, void *stream) {
+    // argument errors are reported as otf_rank_dense reports them (the stand-in workspace is never
+    // dereferenced); then the size against what the static array holds
+    void *ws = reinterpret_cast<void *>(256);
+    const int rc = otf_rank_dense_check(X, xdt, N, D, ldx, W, wdt, Q, k, out_scores, out_idx, ws, ~(size_t)0);
+    if (rc != OTF_OK) return rc;
+    if (ws_layout(N, Q).total > (size_t)OTF_NOALLOC_SCRATCH_BYTES) return OTF_ERR_SCRATCH;
+    const int rs = scratch_of_current_device(&ws);
+    if (rs != OTF_OK) return rs;
+    return otf_rank_dense(X, xdt, N, D, ldx, W, wdt, Q, bias, k, out_scores, out_idx, all_scores, ws,
+                          OTF_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 int otf_pq_build_lut(const float *codebooks, int32_t M, int32_t K, int32_t dsub, const float *w, float *lut,

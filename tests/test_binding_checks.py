@@ -49,6 +49,8 @@ def test_short_or_mistyped_ranking_buffers_are_rejected():
         binding.rank_dense(X, _f(12), None, 10, _ws())
     with pytest.raises(ValueError, match="bias"):
         binding.rank_dense(X, _f(3, 16), _f(2), 10, _ws())
+    with pytest.raises(ValueError, match="out scores"):
+        binding.rank_dense_noalloc(X, w, None, 10, (_f(1, 5), torch.zeros((1, 10), dtype=torch.int32)))
 
 
 def test_code_stores_must_have_their_own_dtypes():

@@ -35,6 +35,7 @@ def test_status_strings(L):
     assert binding.status_string(0) == "OTF_OK"
     assert binding.status_string(-1) == "OTF_ERR_INVALID_ARG"
     assert binding.status_string(-3) == "OTF_ERR_WORKSPACE"
+    assert binding.status_string(-5) == "OTF_ERR_SCRATCH"
     assert binding.status_string(-99) == "OTF_ERR_UNKNOWN"
 
 
@@ -193,3 +194,18 @@ def test_the_library_reads_no_environment_variables():
     csrc = os.path.join(ROOT, "paper_1407_4764_amd", "csrc")
     for name in os.listdir(csrc):
         assert "getenv" not in open(os.path.join(csrc, name)).read(), name
+
+
+def test_noalloc_entry_point_argument_errors(L):
+    def call(X=FAKE, N=1000, D=128, ldx=128, W=FAKE, Q=1, k=10, os_=FAKE):
+        return L.otf_rank_dense_noalloc(X, 0, N, D, ldx, W, 0, Q, None, k, os_, FAKE, None, None)
+    assert call(X=None) == binding.OTF_ERR_INVALID_ARG
+    assert call(os_=None) == binding.OTF_ERR_INVALID_ARG
+    assert call(k=2000) == binding.OTF_ERR_INVALID_ARG
+    assert call(D=6, ldx=8) == binding.OTF_ERR_UNSUPPORTED
+    assert call(N=1 << 31) == binding.OTF_ERR_UNSUPPORTED
+    # sizes whose workspace exceeds the static scratch are refused before anything is touched
+    assert binding.workspace_bytes(100_000_000, 10, 1) > binding.OTF_NOALLOC_SCRATCH_BYTES
+    assert call(N=100_000_000) == binding.OTF_ERR_SCRATCH
+    assert call(N=1_000_000, Q=64, k=10) == binding.OTF_ERR_SCRATCH
+    assert binding.workspace_bytes(1_000_000, 1000, 1) <= binding.OTF_NOALLOC_SCRATCH_BYTES   # the headline store fits
