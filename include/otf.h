@@ -116,8 +116,9 @@ int otf_rank_dense_noalloc(const void *X, otf_dtype xdt, int64_t N, int32_t D, i
  *
  * otf_rank_pq:       scores[i] = bias + sum_m lut[m][codes[i][m]]                  (fp32)
  *   codes  N x M bytes, contiguous rows (leading dimension M).  lut as built above.
- *   K must be 256 and M one of 16, 32, 64 or a multiple of 128 (up to 1024); other shapes
- *   return OTF_ERR_UNSUPPORTED.
+ *   K must be 256 and M a multiple of 16, at most 1024 (rows are read in 16-byte chunks; M = 512
+ *   is the paper's 2048-D feature at 4 dimensions per sub-block); other shapes return
+ *   OTF_ERR_UNSUPPORTED.
  */
 int otf_pq_build_lut(const float *codebooks, int32_t M, int32_t K, int32_t dsub,
                      const float *w, float *lut, void *stream);
@@ -134,8 +135,8 @@ int otf_rank_pq(const uint8_t *codes, int64_t N, int32_t M, int32_t K, const flo
  *   scores[i] = bias + sum_d w[d] * (2 * bit_{i,d} - 1)                           (fp32)
  *
  *   bits  N x (D/32) uint32, contiguous rows.   w  D floats.
- *   D must be a multiple of 1024 (up to 8192) or one of 128, 256, 512; other values return
- *   OTF_ERR_UNSUPPORTED.
+ *   D must be a multiple of 128 (rows are read in 16-byte chunks), at most 8192; other values
+ *   return OTF_ERR_UNSUPPORTED.
  */
 int otf_rank_binary(const uint32_t *bits, int64_t N, int32_t D, const float *w, float bias,
                     int32_t k, float *out_scores, int32_t *out_idx,
@@ -283,6 +284,7 @@ typedef enum {
     OTF_DEBUG_NARROW_BLOCKS_PER_CU,  /* 1..8, dense scan of rows up to 512 bytes */
     OTF_DEBUG_MFMA_BLOCKS_PER_CU,    /* 1..8, multi-classifier scan */
     OTF_DEBUG_PQENC_BLOCKS_PER_CU,   /* 1..8, otf_pq_encode */
+    OTF_DEBUG_WALK_TILES,            /* 2 or 4 tiles of 64 rows per wave and block, table scans of rows > 128 bytes */
     OTF_DEBUG_KEYS
 } otf_debug_key;
 

@@ -19,7 +19,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-tar
 # The matrix-core scan orders its next tile with a one-lane atomic whose result it reads two steps
 # later.  The compiler's wave-aggregation of atomics would insert a read of the result (and a full
 # memory wait) right behind the atomic, so it is switched off for that file.
-EXTRA_FLAGS = {"otf_mfma.hip": ["-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]}
+# The scan that walks long rows through several table images orders its next block the same way.
+NO_ATOMIC_AGGREGATION = ["-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]
+EXTRA_FLAGS = {"otf_mfma.hip": NO_ATOMIC_AGGREGATION, "otf_table.hip": NO_ATOMIC_AGGREGATION}
 
 
 def _compile(src):

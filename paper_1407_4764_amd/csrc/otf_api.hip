@@ -35,6 +35,7 @@ WsLayout ws_layout(int64_t N, int32_t Q) {
     L.sample_ld = padded_rows(sample_rows(N) + kSampleGroup);
     L.sample_scores = take((size_t)Q * (size_t)L.sample_ld * 4);
     L.lut_image = take(kLutImageBytes);
+    L.short_store = take(kShortStoreBytes);
     L.scores = take((size_t)Q * (size_t)padded_rows(N) * 4);
     L.total = off;
     return L;
@@ -111,6 +112,7 @@ static bool debug_value_ok(int key, int v) {
         case OTF_DEBUG_SCAN_THREADS: return v >= 64 && v <= 1024 && v % 64 == 0;   // whole waves, the kernels' launch bound
         case OTF_DEBUG_SCAN_UNROLL:
         case OTF_DEBUG_BINARIZE_WAVES: return v == 4 || v == 8;
+        case OTF_DEBUG_WALK_TILES: return v == 2 || v == 4;
         case OTF_DEBUG_PQENC_RANGE: return v >= 4 && v <= 64 && v % 4 == 0;
         case OTF_DEBUG_DENSE_BLOCKS_PER_CU:
         case OTF_DEBUG_NARROW_BLOCKS_PER_CU:
@@ -355,9 +357,8 @@ int otf_pq_build_lut(const float *codebooks, int32_t M, int32_t K, int32_t dsub,
     return hip_status(launch_pq_build_lut(codebooks, M, K, dsub, w, lut, reinterpret_cast<hipStream_t>(stream)));
 }
 
-static bool table_row_bytes_ok(int32_t rb) {
-    return rb == 16 || rb == 32 || rb == 64 || (rb >= 128 && rb % 128 == 0 && rb <= 1024);
-}
+// Stored bytes per row the table scans take: whole 16-byte chunks, at most 8 table images.
+static bool table_row_bytes_ok(int32_t rb) { return rb >= 16 && rb % 16 == 0 && rb <= 1024; }
 
 // Shared tail of otf_rank_pq / otf_rank_binary once the table image is in place.
 static hipError_t rank_table(const uint8_t *codes, int64_t N, int row_bytes, int seven_bit, const float *image,
@@ -366,34 +367,37 @@ static hipError_t rank_table(const uint8_t *codes, int64_t N, int row_bytes, int
     SelectWs sw = select_ws(ws, L);
     uint8_t *wsb = reinterpret_cast<uint8_t *>(ws);
     float *S = all_scores ? all_scores : reinterpret_cast<float *>(wsb + L.scores);
-    const bool one_phase = seven_bit || row_bytes <= 128;
     hipError_t e = hipSuccess;
-    if (one_phase && filter_eligible(N, k, all_scores)) {
+    if (!seven_bit && row_bytes > 128 && N < kShortStoreRows) {
+        // the scan of rows longer than one table image reads whole tiles of 64 rows: a shorter store
+        // is copied into a buffer of that many rows (the rows behind it are looked up, never emitted)
+        e = hipMemcpyAsync(wsb + L.short_store, codes, (size_t)N * row_bytes, hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return e;
+        codes = wsb + L.short_store;
+    }
+    if (filter_eligible(N, k, all_scores)) {
         SelectWs ssw = sample_select_ws(ws, L);
         float *sample = reinterpret_cast<float *>(wsb + L.sample_scores);
         const int64_t Nv = sample_rows(N);
         const int m = sample_rank(N, Nv);
         e = launch_table_scan(codes, Nv, row_bytes, seven_bit, image, bias, kEmitSample, sample, ssw.st, ssw.hist1, m,
-                              nullptr, nullptr, nullptr, nullptr, nullptr, s);
+                              nullptr, nullptr, nullptr, nullptr, s);
         if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, 0, nullptr, s);
         ScanTimer timer(s);
         if (e == hipSuccess)
             e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitFilter, nullptr, sw.st, nullptr, m,
-                                  ssw.st, ssw.hist2, sw.cand, nullptr, nullptr, s);
+                                  ssw.st, ssw.hist2, sw.cand, nullptr, s);
         timer.stop();
         if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
         if (e == hipSuccess)
             e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitScores, S, sw.st, sw.hist1, k,
-                                  nullptr, nullptr, nullptr, sw.st, nullptr, s);
+                                  nullptr, nullptr, nullptr, sw.st, s);
         if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 1, s);
         return e;
     }
     ScanTimer timer(s);
-    // a multi-phase scan (rows longer than 128 bytes) counts its phases' chunks in the words of the
-    // sample state, which the prepare kernel zeroed and which no filtered scan is using here
-    static_assert(sizeof(SelState) >= 8 * sizeof(uint32_t), "one word per phase, at most 8 phases");
     e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitScores, S, sw.st, sw.hist1, k, nullptr,
-                          nullptr, nullptr, nullptr, reinterpret_cast<uint32_t *>(sample_select_ws(ws, L).st), s);
+                          nullptr, nullptr, nullptr, s);
     timer.stop();
     if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 0, s);
     return e;
@@ -420,7 +424,7 @@ int otf_rank_binary(const uint32_t *bits, int64_t N, int32_t D, const float *w, 
     if (!bits || !w || D < 1) return OTF_ERR_INVALID_ARG;
     int rc = check_rank_common(N, k, 1, out_scores, out_idx, ws, ws_bytes, &L);
     if (rc != OTF_OK) return rc;
-    if (D % 32 != 0 || !table_row_bytes_ok(D / 8)) return OTF_ERR_UNSUPPORTED;
+    if (D % 128 != 0 || !table_row_bytes_ok(D / 8)) return OTF_ERR_UNSUPPORTED;
     if (!aligned16(bits)) return OTF_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     float *image = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + L.lut_image);

@@ -22,7 +22,7 @@ struct SelectWs {
 
 struct WsLayout {
     size_t st, hist1, hist2, hist3, blockhist3, eqoff, cand, sample_st, sample_hist1, sample_hist2, sample_scores,
-        lut_image, scores, total;
+        lut_image, short_store, scores, total;
     int64_t sample_ld;   // row stride (floats) of the sample score buffer
 };
 // Byte offsets of the workspace regions for N rows and Q classifiers (every offset 256-aligned).
@@ -32,6 +32,10 @@ SelectWs sample_select_ws(void *ws, const WsLayout &L);  // state used to thresh
 
 constexpr int kDenseMaxD = 16384;  // widest dense row any kernel takes (elements)
 constexpr size_t kLutImageBytes = 8u * 128u * 1024u + 4096u;  // up to 8 table images of 128 KiB, or one + side table
+
+// A table store of fewer rows than one tile of the multi-image scan is copied here first.
+constexpr int kShortStoreRows = 64;
+constexpr size_t kShortStoreBytes = (size_t)kShortStoreRows * 1024u;
 
 // Rows of the strided sample of an N-row store (whole groups only).
 inline int64_t sample_rows(int64_t N) {
@@ -97,7 +101,8 @@ hipError_t launch_pq_prepare(const float *lut, int M, float *image, const Select
                              hipStream_t s);
 hipError_t launch_binary_prepare(const float *w, int D, float *image, const SelectWs &sw, const SelectWs &sample_sw,
                                  hipStream_t s);
-// row_bytes = stored bytes per row; seven_bit = the 2048-bit binary layout (7+7+7+7+4 bits per word).
+// row_bytes = stored bytes per row (a multiple of 16, at most 1024; rows longer than 128 bytes are walked
+// through several table images); seven_bit = the 2048-bit binary layout (7+7+7+7+4 bits per word).
 //   kEmitScores  scores + pass-1 histogram into (st, hist1) for a top-k of k; `gate` as above
 //   kEmitSample  scores of the strided sample (compact numbering) + pass-1 histogram for rank k = m
 //   kEmitFilter  append rows at or above the threshold to cand (cursor in st); every block resolves
@@ -106,7 +111,7 @@ hipError_t launch_binary_prepare(const float *w, int D, float *image, const Sele
 hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, int seven_bit, const float *image,
                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
                              const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
-                             const SelState *gate, uint32_t *phase_ctr, hipStream_t s);
+                             const SelState *gate, hipStream_t s);
 
 hipError_t launch_sgd_step(float *w, float *b, int D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,
                            int n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int n_neg,

@@ -94,7 +94,9 @@ def test_pq_and_binary_argument_errors(L):
         return L.otf_rank_pq(codes, N, M, K, lut, 0.0, k, FAKE, FAKE, None, FAKE, wsb, None)
     assert pq(codes=None) == binding.OTF_ERR_INVALID_ARG
     assert pq(K=128) == binding.OTF_ERR_UNSUPPORTED
-    assert pq(M=48) == binding.OTF_ERR_UNSUPPORTED
+    assert pq(M=40) == binding.OTF_ERR_UNSUPPORTED              # rows are read in 16-byte chunks
+    assert pq(M=8) == binding.OTF_ERR_UNSUPPORTED
+    assert pq(M=1040) == binding.OTF_ERR_UNSUPPORTED            # more than 8 table images
     assert pq(M=2048) == binding.OTF_ERR_UNSUPPORTED
     assert pq(wsb=0) == binding.OTF_ERR_WORKSPACE
     assert pq(codes=FAKE + 1) == binding.OTF_ERR_INVALID_ARG
@@ -103,7 +105,8 @@ def test_pq_and_binary_argument_errors(L):
         return L.otf_rank_binary(bits, N, D, w, 0.0, k, FAKE, FAKE, None, FAKE, wsb, None)
     assert binr(bits=None) == binding.OTF_ERR_INVALID_ARG
     assert binr(D=100) == binding.OTF_ERR_UNSUPPORTED
-    assert binr(D=768) == binding.OTF_ERR_UNSUPPORTED
+    assert binr(D=96) == binding.OTF_ERR_UNSUPPORTED            # a multiple of 32 bits but not of 128
+    assert binr(D=8320) == binding.OTF_ERR_UNSUPPORTED          # beyond 8192 bits
     assert binr(k=0) == binding.OTF_ERR_INVALID_ARG
     assert L.otf_pq_build_lut(None, 1, 1, 1, FAKE, FAKE, None) == binding.OTF_ERR_INVALID_ARG
     assert L.otf_pq_build_lut(FAKE, 0, 1, 1, FAKE, FAKE, None) == binding.OTF_ERR_INVALID_ARG
