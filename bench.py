@@ -50,6 +50,12 @@ WORKLOADS = {
     # the paper's own feature size (Sec. 3, Table 2: CNN 128), ten times its ~1M images so that the
     # scan and not the launches is what is timed
     "dense128": dict(name="dense_10Mx128_fp32_top1000", N=10_000_000, D=128, k=1000, row_bytes=512, dtype="f32"),
+    # the paper's own PQ geometries on its 2048-D feature (Sec. 3: 4 or 8 dimensions per sub-block;
+    # Table 2 row "2048 PQ 4 dims/sq", 512 bytes per image): rows longer than one table image
+    "pq512": dict(name="pq_5Mx512B_M512_K256_top1000", N=5_000_000, M=512, K=256, dsub=4, k=1000, row_bytes=512,
+                  dtype="f32"),
+    "pq256": dict(name="pq_10Mx256B_M256_K256_top1000", N=10_000_000, M=256, K=256, dsub=8, k=1000, row_bytes=256,
+                  dtype="f32"),
 }
 
 
@@ -59,7 +65,8 @@ def make_workload(kind, scale, torch, binding, synth):
     N = max(1024, int(cfg["N"] * scale))
     cfg["N"] = N
     dev = "cuda"
-    seed = synth.BASE_SEED + {"dense": 2, "pq": 3, "binary": 4, "multiquery": 5, "dense128": 8}[kind]
+    seed = synth.BASE_SEED + {"dense": 2, "pq": 3, "binary": 4, "multiquery": 5, "dense128": 8, "pq512": 10,
+                              "pq256": 11}[kind]
     k = cfg["k"]
     if kind in ("dense", "dense128"):
         X = synth.dense_features(N, cfg["D"], seed, device=dev)
@@ -68,7 +75,7 @@ def make_workload(kind, scale, torch, binding, synth):
         out = binding._outputs(1, k, dev)
         step = lambda: binding.rank_dense(X, w, None, k, ws, out=out)
         keep = (X, w)
-    elif kind == "pq":
+    elif kind in ("pq", "pq512", "pq256"):
         codes = synth.pq_codes(N, cfg["M"], cfg["K"], seed, device=dev)
         cb = synth.pq_codebooks(cfg["M"], cfg["K"], cfg["dsub"], seed + 100, device=dev)
         w = synth.normal_vector(cfg["M"] * cfg["dsub"], 1.0, seed + 200, device=dev)
@@ -302,7 +309,7 @@ def cpu_baseline(kind, cfg, torch):
         w = keep[1].cpu().numpy()
         run = lambda: orc.topk(orc.dense_scores(X, w)[0], min(k, rows))
         sample = "first %d rows of the store, scored and fully sorted" % rows
-    elif kind == "pq":
+    elif kind in ("pq", "pq512", "pq256"):
         rows = min(cfg["N"], 1 << 20)
         codes = keep[0][:rows].cpu().numpy()
         cb, w = keep[1].cpu().numpy(), keep[2].cpu().numpy()

@@ -224,60 +224,24 @@ __device__ __forceinline__ unsigned long long pack_cand(uint32_t key, long long 
     return ((unsigned long long)key << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)row);
 }
 
-__global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ scores, long long N, long long ld,
-                                                     int k, SelState *st_all, const uint32_t *hist3_all,
-                                                     const uint32_t *blockhist3_all, unsigned long long *cand_all,
-                                                     int gated) {
-    __shared__ uint32_t lhist[kBins3];
-    __shared__ uint32_t s_out[3];
-    __shared__ uint32_t wave_cnt[32];                       // [step of a round][wave]
-    // rows above the threshold are collected per block and appended with ONE device-wide atomic:
-    // thousands of atomics on the single cursor would serialise (~18 ns each)
-    constexpr uint32_t kLocalCap = 2048;
-    __shared__ unsigned long long local[kLocalCap];
+// Gather pass over rows [begin, end) of one classifier's scores by one workgroup: every key above
+// `tex` goes to the candidate list (collected per workgroup and appended with ONE device-wide atomic:
+// thousands of atomics on the single cursor would serialise, ~18 ns each).  With `ordered`, the
+// rows whose key EQUALS T are placed in row order at list positions k - r + rank, rank counting
+// such rows from `eqbase` (those in the workgroups before this one) up to r.
+constexpr uint32_t kGatherLocalCap = 2048;
+__device__ __forceinline__ void gather_rows(const float *__restrict__ s, long long begin, long long end, bool vec_ok,
+                                            long long tex, bool ordered, uint32_t T, uint32_t r, uint32_t eqbase, int k,
+                                            SelState *st, unsigned long long *cand) {
+    __shared__ uint32_t wave_cnt[64];                       // [step of a round][wave]
+    __shared__ unsigned long long local[kGatherLocalCap];
     __shared__ uint32_t s_local_n, s_base;
-    if (gated && st_all[0].fallback == 0u) return;
-    const int q = blockIdx.y;
-    SelState *st = st_all + q;
-    const uint32_t mode = st->mode;
-    if (threadIdx.x == 0) s_local_n = 0u;
-    long long tex = st->tex;
-    uint32_t T = 0, r = 0, eqbase = 0;
-    if (mode == 2u) {
-        // resolve pass 3: the k-th key itself, how many rows equal to it belong to the list, and
-        // how many such rows lie in the blocks before this one (ties go to the lowest rows)
-        const uint32_t need2 = st->need2;
-        const BinChoice r3 = block_find_bin(hist3_all + (size_t)q * kBins3, kBins3, need2, lhist, s_out);
-        T = (st->p24 << 8) | r3.bin;
-        r = need2 - r3.above;
-        tex = (long long)T;
-        const uint32_t *bh = blockhist3_all + (size_t)q * kSelBlocks * kBins3 + r3.bin;
-        uint32_t mine = 0;
-        for (int b = threadIdx.x; b < (int)blockIdx.x; b += blockDim.x) mine += bh[(size_t)b * kBins3];
-        uint32_t acc = mine;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-        if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6] = acc;
-        __syncthreads();
-        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) eqbase += wave_cnt[w];
-        __syncthreads();
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            st->T = T;
-            st->r = r;
-            st->ncand = (uint32_t)k;
-        }
-    }
-    const float *s = scores + (long long)q * ld;
-    const bool vec_ok = row_vec_ok(s);
-    unsigned long long *cand = cand_all + (size_t)q * kCandCap;
-    long long begin, end;
-    sel_chunk(N, blockIdx.x, gridDim.x, &begin, &end);
-    const bool ordered = (mode == 2u) && (eqbase < r);    // uniform over the block
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    if (threadIdx.x == 0) s_local_n = 0u;
     __syncthreads();                                       // s_local_n is initialised
     auto take = [&](uint32_t key, long long row) {         // a row above the threshold
         const uint32_t lp = atomicAdd(&s_local_n, 1u);
-        if (lp < kLocalCap) {
+        if (lp < kGatherLocalCap) {
             local[lp] = pack_cand(key, row);
         } else {                                           // block buffer full: straight to the list
             uint32_t pos = atomicAdd(&st->cursor, 1u);
@@ -313,7 +277,7 @@ __global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ s
                 const uint32_t t = __shfl_up(incl[u], o, 64);
                 if (lane >= o) incl[u] += t;
             }
-            if (lane == 63) wave_cnt[u * 8 + wave] = incl[u];
+            if (lane == 63) wave_cnt[u * 16 + wave] = incl[u];
         }
         __syncthreads();
 #pragma unroll
@@ -321,7 +285,7 @@ __global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ s
             const long long i0 = t0 + u * span + 4 * threadIdx.x;
             uint32_t before = 0, total = 0;
             for (int w = 0; w < nwaves; ++w) {
-                const uint32_t c = wave_cnt[u * 8 + w];
+                const uint32_t c = wave_cnt[u * 16 + w];
                 if (w < wave) before += c;
                 total += c;
             }
@@ -345,13 +309,57 @@ __global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ s
         if (ok && (long long)key > tex) take(key, row);
     });
     __syncthreads();
-    const uint32_t nloc = s_local_n < kLocalCap ? s_local_n : kLocalCap;
+    const uint32_t nloc = s_local_n < kGatherLocalCap ? s_local_n : kGatherLocalCap;
     if (threadIdx.x == 0 && nloc) s_base = atomicAdd(&st->cursor, nloc);
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < nloc; i += blockDim.x) {
         const uint32_t pos = s_base + i;
         if (pos < (uint32_t)kCandCap) cand[pos] = local[i];
     }
+}
+
+__global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ scores, long long N, long long ld,
+                                                     int k, SelState *st_all, const uint32_t *hist3_all,
+                                                     const uint32_t *blockhist3_all, unsigned long long *cand_all,
+                                                     int gated) {
+    __shared__ uint32_t lhist[kBins3];
+    __shared__ uint32_t s_out[3];
+    __shared__ uint32_t wave_sum_s[16];
+    if (gated && st_all[0].fallback == 0u) return;
+    const int q = blockIdx.y;
+    SelState *st = st_all + q;
+    const uint32_t mode = st->mode;
+    long long tex = st->tex;
+    uint32_t T = 0, r = 0, eqbase = 0;
+    if (mode == 2u) {
+        // resolve pass 3: the k-th key itself, how many rows equal to it belong to the list, and
+        // how many such rows lie in the blocks before this one (ties go to the lowest rows)
+        const uint32_t need2 = st->need2;
+        const BinChoice r3 = block_find_bin(hist3_all + (size_t)q * kBins3, kBins3, need2, lhist, s_out);
+        T = (st->p24 << 8) | r3.bin;
+        r = need2 - r3.above;
+        tex = (long long)T;
+        const uint32_t *bh = blockhist3_all + (size_t)q * kSelBlocks * kBins3 + r3.bin;
+        uint32_t mine = 0;
+        for (int b = threadIdx.x; b < (int)blockIdx.x; b += blockDim.x) mine += bh[(size_t)b * kBins3];
+        uint32_t acc = mine;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+        if ((threadIdx.x & 63) == 0) wave_sum_s[threadIdx.x >> 6] = acc;
+        __syncthreads();
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) eqbase += wave_sum_s[w];
+        __syncthreads();
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            st->T = T;
+            st->r = r;
+            st->ncand = (uint32_t)k;
+        }
+    }
+    const float *s = scores + (long long)q * ld;
+    long long begin, end;
+    sel_chunk(N, blockIdx.x, gridDim.x, &begin, &end);
+    gather_rows(s, begin, end, row_vec_ok(s), tex, (mode == 2u) && (eqbase < r), T, r, eqbase, k, st,
+                cand_all + (size_t)q * kCandCap);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -603,9 +611,102 @@ __global__ __launch_bounds__(kSortThreads) void filter_sort_kernel(SelState *st_
                      out_idx + (size_t)q * k);
 }
 
+// Full selection in ONE launch, for the fallback of a filtered scan only.  A ranking call enqueues
+// its fallback behind the filtered scan whether it will be needed or not, and a kernel that
+// returns at once still costs ~4 us on the stream: four such launches (passes 2 and 3, gather,
+// sort) were a twentieth of a ranking call.  This kernel does their work behind one gate:
+//   every workgroup   resolves pass 1 (the gated scan accumulated its histogram).  Decisive (the
+//                     usual case): gathers the candidates of its share of the rows.  Not decisive:
+//                     adds its share of the pass-2 histogram.  Then it takes a ticket.
+//   the last one      (the ticket tells; device-wide fences on both sides of it make the others'
+//                     work visible) sorts the list, or -- scores that crowd into one 12-bit bin or tie
+//                     by the thousand -- finishes passes 2 and 3 and the gather by itself over all
+//                     rows: slower than the chain of launches, but only when a fallback meets such
+//                     scores, and always exact.
+// Stand-alone selection (otf_topk, scans that materialise their scores) keeps the chain: there
+// every pass runs, and a fence per workgroup would cost more than the launches.
+__global__ __launch_bounds__(kSortThreads) void select_fused_gated_kernel(const float *__restrict__ scores,
+                                                                           long long N, long long ld, int k,
+                                                                           SelState *st_all, const uint32_t *hist1_all,
+                                                                           uint32_t *hist2_all,
+                                                                           unsigned long long *cand_all,
+                                                                           float *out_scores, int32_t *out_idx) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t sort_lds[];
+    __shared__ uint32_t lhist[kBins2];
+    __shared__ uint32_t s_out[3];
+    __shared__ uint32_t s_last;
+    if (st_all[0].fallback == 0u) return;                  // uniform over the grid
+    const int q = blockIdx.y;
+    SelState *st = st_all + q;
+    const float *s = scores + (long long)q * ld;
+    const bool vec_ok = row_vec_ok(s);
+    unsigned long long *cand = cand_all + (size_t)q * kCandCap;
+    uint32_t *hist2 = hist2_all + (size_t)q * kBins2;
+    const BinChoice r1 = block_find_bin(hist1_all + (size_t)q * kHist1Words, kBins1, (uint32_t)k, lhist, s_out, kHistShards);
+    const uint32_t b1 = r1.bin, need1 = (uint32_t)k - r1.above, c1 = r1.above + r1.inbin;
+    const bool decisive1 = c1 <= (uint32_t)kCandCap;
+    long long begin, end;
+    sel_chunk(N, blockIdx.x, gridDim.x, &begin, &end);
+    if (decisive1) {
+        gather_rows(s, begin, end, vec_ok, ((long long)b1 << 20) - 1, false, 0u, 0u, 0u, k, st, cand);
+    } else {
+        for (int b = threadIdx.x; b < kBins2; b += blockDim.x) lhist[b] = 0u;
+        __syncthreads();
+        for_each_score(s, begin, end, vec_ok, [&](float v, bool ok, long long) {
+            const uint32_t key = float_to_key(v);
+            hist_add_wave(lhist, (key >> 8) & 0xFFFu, ok && (key >> 20) == b1);
+        });
+        merge_hist(lhist, kBins2, hist2);
+    }
+    // ticket: the workgroup that draws the last one continues alone
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) s_last = atomicAdd(&st->spare, 1u) == gridDim.x - 1u ? 1u : 0u;
+    __syncthreads();
+    if (s_last == 0u) return;                              // uniform over the workgroup
+    __threadfence();
+    uint32_t n = c1;
+    if (!decisive1) {
+        const BinChoice r2 = block_find_bin(hist2, kBins2, need1, lhist, s_out);
+        const uint32_t p24 = (b1 << 12) | r2.bin, need2 = need1 - r2.above;
+        const uint32_t c2 = ((uint32_t)k - need1) + r2.above + r2.inbin;     // keys >= p24 << 8
+        if (c2 <= (uint32_t)kCandCap) {
+            gather_rows(s, 0, N, vec_ok, ((long long)p24 << 8) - 1, false, 0u, 0u, 0u, k, st, cand);
+            n = c2;
+        } else {
+            // pass 3 over all rows by this workgroup: the k-th key itself and how many of its equals belong
+            for (int b = threadIdx.x; b < kBins3; b += blockDim.x) lhist[b] = 0u;
+            __syncthreads();
+            for_each_score(s, 0, N, vec_ok, [&](float v, bool ok, long long) {
+                const uint32_t key = float_to_key(v);
+                hist_add_wave(lhist, key & 0xFFu, ok && (key >> 8) == p24);
+            });
+            __syncthreads();
+            uint32_t above = 0u, inbin = 0u, bin3 = 0u;
+            if (threadIdx.x < 64) bin3 = wave_find_bin(lhist, kBins3 / 64, need2, &above, &inbin);
+            if (threadIdx.x == 0) {
+                s_out[0] = bin3;
+                s_out[1] = above;
+            }
+            __syncthreads();
+            const uint32_t T = (p24 << 8) | s_out[0], r = need2 - s_out[1];
+            __syncthreads();
+            gather_rows(s, 0, N, vec_ok, (long long)T, true, T, r, 0u, k, st, cand);
+            n = (uint32_t)k;
+        }
+    }
+    __threadfence();                                       // the list this workgroup wrote itself
+    __syncthreads();
+    select_sort_emit(sort_lds, cand, n > (uint32_t)kCandCap ? (uint32_t)kCandCap : n, k, out_scores + (size_t)q * k,
+                     out_idx + (size_t)q * k);
+}
+
 static hipError_t allow_sort_lds() {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&sort_emit_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSortLdsBytes);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&select_fused_gated_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kSortLdsBytes);
     if (e != hipSuccess) return e;
     return hipFuncSetAttribute(reinterpret_cast<const void *>(&filter_sort_kernel),
                                hipFuncAttributeMaxDynamicSharedMemorySize, kSortLdsBytes);
@@ -652,6 +753,13 @@ hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const
 hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw,
                               float *out_scores, int32_t *out_idx, int gated, hipStream_t s) {
     dim3 grid(sel_blocks(N, Q), Q);
+    if (gated) {                                   // the fallback of a filtered scan: one launch behind one gate
+        hipError_t e = allow_sort_lds();
+        if (e != hipSuccess) return e;
+        select_fused_gated_kernel<<<grid, kSortThreads, kSortLdsBytes, s>>>(scores, N, ld, k, sw.st, sw.hist1, sw.hist2,
+                                                                            sw.cand, out_scores, out_idx);
+        return hipGetLastError();
+    }
     // (1024 threads: the histogram passes hide the latency of their votes and shared-memory adds behind more waves)
     hist2_kernel<<<grid, 1024, 0, s>>>(scores, N, ld, k, sw.st, sw.hist1, sw.hist2, 0, gated ? sw.st : nullptr);
     hist3_kernel<<<grid, 1024, 0, s>>>(scores, N, ld, k, sw.st, sw.hist2, sw.hist3, sw.blockhist3, gated);
