@@ -79,13 +79,10 @@ def make_workload(kind, scale, torch, binding, synth):
         codes = synth.pq_codes(N, cfg["M"], cfg["K"], seed, device=dev)
         cb = synth.pq_codebooks(cfg["M"], cfg["K"], cfg["dsub"], seed + 100, device=dev)
         w = synth.normal_vector(cfg["M"] * cfg["dsub"], 1.0, seed + 200, device=dev)
-        lut = torch.empty((cfg["M"], cfg["K"]), dtype=torch.float32, device=dev)
         ws = binding.make_workspace(N, k, 1, dev)
         out = binding._outputs(1, k, dev)
-
-        def step():                      # a new model means a new table: the build is part of the pass
-            binding.pq_build_lut(cb, w, lut)
-            return binding.rank_pq(codes, lut, 0.0, k, ws, out=out)
+        # a new model means a new table: the build is part of the pass (one call: table build + ranking)
+        step = lambda: binding.rank_pq_model(codes, cb, w, 0.0, k, ws, out=out)
         keep = (codes, cb, w)
     elif kind == "binary":
         bits = synth.binary_bits_random(N, cfg["D"] // 32, seed, device=dev)

@@ -123,6 +123,17 @@ int otf_rank_dense_noalloc(const void *X, otf_dtype xdt, int64_t N, int32_t D, i
 int otf_pq_build_lut(const float *codebooks, int32_t M, int32_t K, int32_t dsub,
                      const float *w, float *lut, void *stream);
 
+/*
+ * otf_rank_pq_model: otf_pq_build_lut followed by otf_rank_pq in one call, for the on-line loop of
+ * Sec. 4, where every ranking runs under a new model and nobody reads the table: the table goes
+ * from the vocabularies and w straight into the layout the scan uses (one launch less).  Scores
+ * and lists are bit-identical to the two calls.  Same shapes and errors as otf_rank_pq; dsub >= 1.
+ */
+int otf_rank_pq_model(const uint8_t *codes, int64_t N, int32_t M, int32_t K, int32_t dsub,
+                      const float *codebooks, const float *w, float bias, int32_t k,
+                      float *out_scores, int32_t *out_idx, float *all_scores,
+                      void *ws, size_t ws_bytes, void *stream);
+
 int otf_rank_pq(const uint8_t *codes, int64_t N, int32_t M, int32_t K, const float *lut,
                 float bias, int32_t k, float *out_scores, int32_t *out_idx,
                 float *all_scores, void *ws, size_t ws_bytes, void *stream);

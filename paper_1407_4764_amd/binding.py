@@ -27,7 +27,7 @@ EXPORTS = ["otf_status_string", "otf_workspace_bytes", "otf_rank_dense", "otf_pq
            "otf_rank_binary", "otf_topk", "otf_sgd_workspace_bytes", "otf_svm_sgd_step", "otf_svm_sgd_pass",
            "otf_tight_frame_workspace_bytes",
            "otf_tight_frame", "otf_binarize", "otf_pq_train_workspace_bytes", "otf_pq_encode", "otf_pq_lloyd_step",
-           "otf_profile_begin", "otf_profile_end", "otf_debug_set", "otf_rank_dense_noalloc"]
+           "otf_profile_begin", "otf_profile_end", "otf_debug_set", "otf_rank_dense_noalloc", "otf_rank_pq_model"]
 
 # otf_debug_key
 (DEBUG_RANK_PATH, DEBUG_BINARIZE_FP32, DEBUG_PQENC_FP32, DEBUG_SCAN_THREADS, DEBUG_SCAN_UNROLL, DEBUG_BINARIZE_WAVES,
@@ -68,6 +68,8 @@ def lib():
         L.otf_pq_build_lut.argtypes = [vp, i32, i32, i32, vp, vp, vp]
         L.otf_rank_pq.restype = ctypes.c_int
         L.otf_rank_pq.argtypes = [vp, i64, i32, i32, vp, f32, i32, vp, vp, vp, vp, sz, vp]
+        L.otf_rank_pq_model.restype = ctypes.c_int
+        L.otf_rank_pq_model.argtypes = [vp, i64, i32, i32, i32, vp, vp, f32, i32, vp, vp, vp, vp, sz, vp]
         L.otf_rank_binary.restype = ctypes.c_int
         L.otf_rank_binary.argtypes = [vp, i64, i32, vp, f32, i32, vp, vp, vp, vp, sz, vp]
         L.otf_topk.restype = ctypes.c_int
@@ -265,6 +267,26 @@ def rank_pq(codes, lut, bias, k, ws, all_scores=None, out=None):
                            _ptr(all_scores), _ptr(ws), ws.numel(), _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_rank_pq")
+    return out_s, out_i
+
+
+def rank_pq_model(codes, codebooks, w, bias, k, ws, all_scores=None, out=None):
+    """Table build and ranking in one call: codes (N, M) uint8, codebooks (M, 256, dsub) fp32, w (M*dsub,) fp32."""
+    a = _Args()
+    a.check(codes, "codes", torch.uint8)
+    a.check(codebooks, "codebooks", torch.float32)
+    if codes.dim() != 2 or codebooks.dim() != 3 or codebooks.shape[0] != codes.shape[1]:
+        raise ValueError("codes must be (N, M) and codebooks (M, K, dsub)")
+    N, M = codes.shape
+    _, K, dsub = codebooks.shape
+    a.check(w, "w", torch.float32, numel=M * dsub)
+    a.rank_buffers(1, N, k, ws, all_scores, out)
+    dev = a.done()
+    out_s, out_i = out if out is not None else _outputs(1, k, dev)
+    rc = lib().otf_rank_pq_model(_ptr(codes), N, M, K, dsub, _ptr(codebooks), _ptr(w), float(bias), k, _ptr(out_s),
+                                 _ptr(out_i), _ptr(all_scores), _ptr(ws), ws.numel(), _stream(dev))
+    if rc != OTF_OK:
+        raise OtfError(rc, "otf_rank_pq_model")
     return out_s, out_i
 
 

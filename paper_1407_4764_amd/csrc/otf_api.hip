@@ -418,6 +418,22 @@ int otf_rank_pq(const uint8_t *codes, int64_t N, int32_t M, int32_t K, const flo
     return hip_status(e);
 }
 
+int otf_rank_pq_model(const uint8_t *codes, int64_t N, int32_t M, int32_t K, int32_t dsub, const float *codebooks,
+                      const float *w, float bias, int32_t k, float *out_scores, int32_t *out_idx, float *all_scores,
+                      void *ws, size_t ws_bytes, void *stream) {
+    WsLayout L;
+    if (!codes || !codebooks || !w || M < 1 || K < 1 || dsub < 1) return OTF_ERR_INVALID_ARG;
+    int rc = check_rank_common(N, k, 1, out_scores, out_idx, ws, ws_bytes, &L);
+    if (rc != OTF_OK) return rc;
+    if (K != 256 || !table_row_bytes_ok(M) || dsub > 4096) return OTF_ERR_UNSUPPORTED;
+    if (!aligned16(codes)) return OTF_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    float *image = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + L.lut_image);
+    hipError_t e = launch_pq_prepare_model(codebooks, w, M, dsub, image, select_ws(ws, L), sample_select_ws(ws, L), s);
+    if (e == hipSuccess) e = rank_table(codes, N, M, 0, image, bias, k, out_scores, out_idx, all_scores, ws, L, s);
+    return hip_status(e);
+}
+
 int otf_rank_binary(const uint32_t *bits, int64_t N, int32_t D, const float *w, float bias, int32_t k,
                     float *out_scores, int32_t *out_idx, float *all_scores, void *ws, size_t ws_bytes, void *stream) {
     WsLayout L;

@@ -99,6 +99,9 @@ hipError_t launch_pq_build_lut(const float *codebooks, int M, int K, int dsub, c
 // Table images in scan layout; also zero both selection states.
 hipError_t launch_pq_prepare(const float *lut, int M, float *image, const SelectWs &sw, const SelectWs &sample_sw,
                              hipStream_t s);
+// The PQ images straight from the vocabularies and the model (no table in between).
+hipError_t launch_pq_prepare_model(const float *codebooks, const float *w, int M, int dsub, float *image,
+                                   const SelectWs &sw, const SelectWs &sample_sw, hipStream_t s);
 hipError_t launch_binary_prepare(const float *w, int D, float *image, const SelectWs &sw, const SelectWs &sample_sw,
                                  hipStream_t s);
 // row_bytes = stored bytes per row (a multiple of 16, at most 1024; rows longer than 128 bytes are walked

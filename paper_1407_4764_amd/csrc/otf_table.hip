@@ -107,6 +107,29 @@ __global__ __launch_bounds__(256) void pq_prepare_kernel(const float *__restrict
     zero_states(tid, step, st, hist1, hist2, hist3, sst, shist1, shist2);
 }
 
+// The same straight from the vocabularies and the model, for a caller that ranks under a new model
+// every time and has no use for the table itself: image entry = sum_j w[m dsub + j] C[m][v][j], summed
+// in the order of pq_build_lut_kernel (the two routes give identical bits).
+__global__ __launch_bounds__(256) void pq_prepare_model_kernel(const float *__restrict__ codebooks,
+                                                               const float *__restrict__ w, int M, int dsub, int span,
+                                                               int nsplit, float *__restrict__ image, SelState *st,
+                                                               uint32_t *hist1, uint32_t *hist2, uint32_t *hist3,
+                                                               SelState *sst, uint32_t *shist1, uint32_t *shist2) {
+    const int tid = blockIdx.x * blockDim.x + threadIdx.x, step = gridDim.x * blockDim.x;
+    for (int t = tid; t < nsplit * kImageFloats; t += step) {
+        const int v = t & 255, pos = (t >> 8) & (kSegBytes - 1), sp = t >> 15;
+        const int m = row_byte_at(M, span, sp, pos);
+        float acc = 0.f;
+        if (m >= 0) {
+            const float *c = codebooks + ((size_t)m * 256 + v) * dsub;
+            const float *wm = w + (size_t)m * dsub;
+            for (int j = 0; j < dsub; ++j) acc = fmaf(wm[j], c[j], acc);
+        }
+        image[(size_t)sp * kImageFloats + v * kSegBytes + image_column(pos)] = acc;
+    }
+    zero_states(tid, step, st, hist1, hist2, hist3, sst, shist1, shist2);
+}
+
 // Table images for binary codes with byte groups: byte g of a row covers dimensions 8g..8g+7.
 __global__ __launch_bounds__(256) void binary_prepare_kernel(const float *__restrict__ w, int row_bytes, int span,
                                                              int nsplit, float *__restrict__ image, SelState *st,
@@ -596,6 +619,14 @@ hipError_t launch_pq_prepare(const float *lut, int M, float *image, const Select
     const int nphase = phases_of(M);
     pq_prepare_kernel<<<nphase * 32, 256, 0, s>>>(lut, M, span_of(M), nphase, image, sw.st, sw.hist1, sw.hist2, sw.hist3,
                                                   ssw.st, ssw.hist1, ssw.hist2);
+    return hipGetLastError();
+}
+
+hipError_t launch_pq_prepare_model(const float *codebooks, const float *w, int M, int dsub, float *image,
+                                   const SelectWs &sw, const SelectWs &ssw, hipStream_t s) {
+    const int nphase = phases_of(M);
+    pq_prepare_model_kernel<<<nphase * 64, 256, 0, s>>>(codebooks, w, M, dsub, span_of(M), nphase, image, sw.st, sw.hist1,
+                                                        sw.hist2, sw.hist3, ssw.st, ssw.hist1, ssw.hist2);
     return hipGetLastError();
 }
 

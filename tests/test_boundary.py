@@ -101,6 +101,15 @@ def test_pq_and_binary_argument_errors(L):
     assert pq(wsb=0) == binding.OTF_ERR_WORKSPACE
     assert pq(codes=FAKE + 1) == binding.OTF_ERR_INVALID_ARG
 
+    def pqm(codes=FAKE, M=128, K=256, dsub=16, cb=FAKE, w=FAKE, wsb=BIG):
+        return L.otf_rank_pq_model(codes, 1000, M, K, dsub, cb, w, 0.0, 10, FAKE, FAKE, None, FAKE, wsb, None)
+    assert pqm(cb=None) == binding.OTF_ERR_INVALID_ARG
+    assert pqm(w=None) == binding.OTF_ERR_INVALID_ARG
+    assert pqm(dsub=0) == binding.OTF_ERR_INVALID_ARG
+    assert pqm(K=16) == binding.OTF_ERR_UNSUPPORTED
+    assert pqm(M=40) == binding.OTF_ERR_UNSUPPORTED
+    assert pqm(wsb=0) == binding.OTF_ERR_WORKSPACE
+
     def binr(bits=FAKE, N=1000, D=2048, w=FAKE, k=10, wsb=BIG):
         return L.otf_rank_binary(bits, N, D, w, 0.0, k, FAKE, FAKE, None, FAKE, wsb, None)
     assert binr(bits=None) == binding.OTF_ERR_INVALID_ARG

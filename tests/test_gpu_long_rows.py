@@ -113,3 +113,23 @@ def test_paper_pq_geometries_against_the_reconstruction_oracle(oracle, N, M, dsu
     ref = oracle.pq_scores_reconstruct(codes.numpy(), cb.numpy(), w.numpy(), 0.25)
     ok, msg = oracle.topk_parity_ok(ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), 1e-4)
     assert ok, msg
+
+
+@pytest.mark.parametrize("N,M,dsub", [(30000, 128, 16), (5000, 512, 4), (1200000, 256, 8), (4000, 96, 4), (2000, 16, 8)])
+def test_ranking_straight_from_the_vocabularies_equals_table_build_plus_ranking(N, M, dsub):
+    """otf_rank_pq_model must give the bits of otf_pq_build_lut followed by otf_rank_pq."""
+    k = min(N, 100)
+    cb = synth.pq_codebooks(M, 256, dsub, SEED + 600).to(DEV)
+    codes = synth.pq_codes(N, M, 256, SEED + 601).to(DEV)
+    w = synth.normal_vector(M * dsub, 1.0, SEED + 602).to(DEV)
+    ws = binding.make_workspace(N, k)
+    a1 = torch.empty(N, dtype=torch.float32, device=DEV)
+    a2 = torch.empty(N, dtype=torch.float32, device=DEV)
+    v1, i1 = binding.rank_pq(codes, binding.pq_build_lut(cb, w), -0.5, k, ws, all_scores=a1)
+    v1, i1 = v1.clone(), i1.clone()
+    v2, i2 = binding.rank_pq_model(codes, cb, w, -0.5, k, ws, all_scores=a2)
+    torch.cuda.synchronize()
+    assert torch.equal(a1, a2) and torch.equal(i1, i2) and torch.equal(v1, v2)
+    v3, i3 = binding.rank_pq_model(codes, cb, w, -0.5, k, ws)          # and on the filtered route
+    torch.cuda.synchronize()
+    assert torch.equal(i1, i3) and torch.equal(v1, v3)
