@@ -23,6 +23,14 @@
  *   orc_binary_scores  Sec. 3, paragraph "Binarization", Eq. (1) (codes in {0,1}^n), ranked
  *                      by a linear SVM (Sec. 3.1, discussion after Table 2).  A bit b
  *                      enters the model as 2b-1.
+ *   orc_hamming_scores Sec. 3.1, discussion after Table 2: ranking binary codes by Hamming
+ *                      distance, which the paper names as the way to speed their ranking up
+ *                      and leaves for later.  The "different ranking model" it needs is taken
+ *                      to be a query code; a row's score is minus its distance to it.
+ *   orc_sparse_expand  Sec. 3.1, same discussion: ConvNet features are very sparse (the 128-D
+ *                      ones over 60 % zeros), a compression the paper points at but does not
+ *                      build.  The store keeps a presence mask and the non-zero values of a
+ *                      row; expanding it gives back the dense row, which orc_dense_f32 scores.
  *   orc_topk           Sec. 4, Ranking: the scores are sorted and the head of the list goes
  *                      to the front-end.
  *   orc_sgd_step       Sec. 4, Training: mini-batch SGD with Pegasos updates, learning rate
@@ -222,6 +230,50 @@ int orc_binary_scores(const uint32_t *bits, int64_t N, int32_t D, int64_t ld_wor
             acc += bit ? (double)w[d] : -(double)w[d];
         }
         out[i] = acc;
+    }
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------- Hamming ranking
+ * score[i] = -(number of dimensions d < D in which row i and the query differ), bit by bit.
+ * Same bit layout as orc_binary_scores.  The larger (less negative) score is the nearer row.
+ */
+int orc_hamming_scores(const uint32_t *bits, int64_t N, int32_t D, int64_t ld_words,
+                       const uint32_t *query, double *out) {
+    if (!bits || !query || !out || N < 0 || D < 1 || ld_words * 32 < D) return ORC_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i) {
+        const uint32_t *row = bits + i * ld_words;
+        int64_t differ = 0;
+        for (int32_t d = 0; d < D; ++d) {
+            uint32_t a = (row[d >> 5] >> (d & 31)) & 1u;
+            uint32_t b = (query[d >> 5] >> (d & 31)) & 1u;
+            if (a != b) ++differ;
+        }
+        out[i] = -(double)differ;
+    }
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------- sparse rows
+ * A sparse row i of D dimensions is stored as a presence mask of D bits (dimension d = bit
+ * d mod 32, least significant first, of word d div 32 of mask row i; rows ld_mask words apart)
+ * and its non-zero values in ascending order of dimension, values[start[i]] onwards.
+ * Expands N rows into the dense N x D matrix X (row-major, contiguous): a dimension whose mask
+ * bit is clear is 0, the others take the stored values in order.  start has N + 1 entries
+ * (start[N] = total number of stored values); it is checked against the masks.
+ */
+int orc_sparse_expand(const uint32_t *mask, int64_t ld_mask, const float *values, const int64_t *start,
+                      int64_t N, int32_t D, float *X) {
+    if (!mask || !values || !start || !X || N < 0 || D < 1 || ld_mask * 32 < D) return ORC_BAD_ARG;
+    for (int64_t i = 0; i < N; ++i) {
+        const uint32_t *mrow = mask + i * ld_mask;
+        int64_t next = start[i];
+        for (int32_t d = 0; d < D; ++d) {
+            if ((mrow[d >> 5] >> (d & 31)) & 1u) X[i * D + d] = values[next++];
+            else X[i * D + d] = 0.0f;
+        }
+        if (next != start[i + 1]) return ORC_BAD_ARG;   /* offsets and masks disagree */
     }
     return ORC_OK;
 }

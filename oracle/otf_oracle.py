@@ -136,6 +136,33 @@ def binary_scores(bits, D, w, bias=0.0):
     return out
 
 
+def hamming_scores(bits, D, query):
+    """bits (N, words) uint32, query (words,) uint32 -> minus the Hamming distance of every row to the query."""
+    bits = _c(bits, np.uint32)
+    query = _c(query, np.uint32)
+    N, words = bits.shape
+    assert query.shape == (words,) and words * 32 >= D
+    out = np.empty(N, dtype=np.float64)
+    rc = _load().orc_hamming_scores(_p(bits), ctypes.c_int64(N), ctypes.c_int32(D), ctypes.c_int64(words),
+                                    _p(query), _p(out))
+    _chk(rc, "orc_hamming_scores")
+    return out
+
+
+def sparse_expand(mask, values, start, D):
+    """mask (N, words) uint32, values (nnz,) float32, start (N+1,) int64 -> dense (N, D) float32."""
+    mask = _c(mask, np.uint32)
+    values = _c(values, np.float32)
+    start = _c(start, np.int64)
+    N, words = mask.shape
+    assert start.shape == (N + 1,)
+    X = np.empty((N, D), dtype=np.float32)
+    rc = _load().orc_sparse_expand(_p(mask), ctypes.c_int64(words), _p(values), _p(start), ctypes.c_int64(N),
+                                   ctypes.c_int32(D), _p(X))
+    _chk(rc, "orc_sparse_expand")
+    return X
+
+
 def topk(scores, k):
     """Full sort, score descending then index ascending; returns (idx int64[k], scores f64[k])."""
     s = _c(scores, np.float64)

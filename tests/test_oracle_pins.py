@@ -191,6 +191,70 @@ def test_binary_extremes_and_single_bit_words(oracle):
         assert abs(delta - (-2.0 if was_set else 2.0) * wd[d]) < 1e-12
 
 
+# ------------------------------------------------------------------------------ Hamming ranking
+def test_hamming_equals_unpacked_bit_counts_and_the_binary_score_identity(oracle):
+    """-distance against numpy's own unpacker, and through the +/-1 identity: with w_d = 2 q_d - 1 the
+    binary score of a row is D - 2 * distance(row, q), so distance = (D - score) / 2."""
+    N, D = 300, 160
+    bits = RNG.integers(0, 2 ** 32, size=(N, 5), dtype=np.uint64).astype(np.uint32)
+    q = RNG.integers(0, 2 ** 32, size=5, dtype=np.uint64).astype(np.uint32)
+    s = oracle.hamming_scores(bits, D, q)
+    ub = np.unpackbits(bits.view(np.uint8), axis=1, bitorder="little")[:, :D].astype(np.int64)
+    uq = np.unpackbits(q.view(np.uint8), bitorder="little")[:D].astype(np.int64)
+    np.testing.assert_array_equal(s, -np.abs(ub - uq[None, :]).sum(axis=1).astype(np.float64))
+    w = (2 * uq - 1).astype(np.float32)
+    np.testing.assert_array_equal(s, -(D - oracle.binary_scores(bits, D, w, 0.0)) / 2.0)
+
+
+def test_hamming_closed_forms(oracle):
+    D, words = 96, 3
+    q = RNG.integers(0, 2 ** 32, size=words, dtype=np.uint64).astype(np.uint32)
+    assert oracle.hamming_scores(q[None, :], D, q)[0] == 0.0                  # d(a, a) = 0
+    assert oracle.hamming_scores((~q)[None, :], D, q)[0] == -float(D)         # complement: every dimension differs
+    # one flipped bit costs exactly one, wherever it is; bits beyond D do not count
+    rows = np.tile(q, (D, 1))
+    for d in range(D):
+        rows[d, d // 32] ^= np.uint32(1) << np.uint32(d % 32)
+    np.testing.assert_array_equal(oracle.hamming_scores(rows, D, q), -np.ones(D))
+    r = q.copy()
+    r[2] ^= np.uint32(0x80000000)                                             # dimension 95: counts at D = 96 ...
+    assert oracle.hamming_scores(r[None, :], 96, q)[0] == -1.0
+    assert oracle.hamming_scores(r[None, :], 95, q)[0] == 0.0                 # ... and not at D = 95
+    # symmetric, and the triangle inequality on random triples
+    a, b, c = (RNG.integers(0, 2 ** 32, size=words, dtype=np.uint64).astype(np.uint32) for _ in range(3))
+    dab = -oracle.hamming_scores(a[None, :], D, b)[0]
+    assert dab == -oracle.hamming_scores(b[None, :], D, a)[0]
+    assert dab <= -oracle.hamming_scores(a[None, :], D, c)[0] - oracle.hamming_scores(c[None, :], D, b)[0]
+
+
+# ------------------------------------------------------------------------------ sparse rows
+def test_sparse_expand_inverts_compression_of_a_dense_matrix(oracle):
+    """Brute force: compress a dense matrix with python loops, expand it with the oracle."""
+    N, D = 40, 96
+    X = RNG.standard_normal((N, D)).astype(np.float32)
+    X[RNG.random((N, D)) < 0.6] = 0.0
+    X[3] = 0.0                                          # an empty row
+    X[4] = 1.5                                          # a full row
+    mask = np.zeros((N, 3), dtype=np.uint32)
+    values, start = [], [0]
+    for i in range(N):
+        for d in range(D):
+            if X[i, d] != 0.0:
+                mask[i, d // 32] |= np.uint32(1) << np.uint32(d % 32)
+                values.append(X[i, d])
+        start.append(len(values))
+    got = oracle.sparse_expand(mask, np.array(values, dtype=np.float32), np.array(start, dtype=np.int64), D)
+    np.testing.assert_array_equal(got, X)
+    # values land in ascending order of dimension: mask 0b101 with values (7, 9) is (7, 0, 9, 0, ...)
+    one = oracle.sparse_expand(np.array([[5, 0, 0]], dtype=np.uint32), np.array([7.0, 9.0], dtype=np.float32),
+                               np.array([0, 2], dtype=np.int64), D)
+    assert one[0, 0] == 7.0 and one[0, 1] == 0.0 and one[0, 2] == 9.0 and not one[0, 3:].any()
+    # offsets that disagree with the masks are refused
+    with pytest.raises(RuntimeError):
+        oracle.sparse_expand(np.array([[5, 0, 0]], dtype=np.uint32), np.array([7.0, 9.0], dtype=np.float32),
+                             np.array([0, 1], dtype=np.int64), D)
+
+
 def test_sign_convention_zero_is_bit_zero():
     import torch
     f = torch.tensor([[0.0, -0.0, 1e-30, -1e-30] + [0.0] * 28])
