@@ -54,6 +54,8 @@ WORKLOADS = {
     # Table 2 row "2048 PQ 4 dims/sq", 512 bytes per image): rows longer than one table image
     "pq512": dict(name="pq_5Mx512B_M512_K256_top1000", N=5_000_000, M=512, K=256, dsub=4, k=1000, row_bytes=512,
                   dtype="f32"),
+    # Hamming ranking of the binary store (Sec. 3.1, after Table 2: what the paper leaves for later)
+    "hamming": dict(name="hamming_50Mx2048bit_top1000", N=50_000_000, D=2048, k=1000, row_bytes=256, dtype="u32"),
     "pq256": dict(name="pq_10Mx256B_M256_K256_top1000", N=10_000_000, M=256, K=256, dsub=8, k=1000, row_bytes=256,
                   dtype="f32"),
 }
@@ -66,7 +68,7 @@ def make_workload(kind, scale, torch, binding, synth):
     cfg["N"] = N
     dev = "cuda"
     seed = synth.BASE_SEED + {"dense": 2, "pq": 3, "binary": 4, "multiquery": 5, "dense128": 8, "pq512": 10,
-                              "pq256": 11}[kind]
+                              "pq256": 11, "hamming": 4}[kind]
     k = cfg["k"]
     if kind in ("dense", "dense128"):
         X = synth.dense_features(N, cfg["D"], seed, device=dev)
@@ -91,6 +93,13 @@ def make_workload(kind, scale, torch, binding, synth):
         out = binding._outputs(1, k, dev)
         step = lambda: binding.rank_binary(bits, cfg["D"], w, 0.0, k, ws, out=out)
         keep = (bits, w)
+    elif kind == "hamming":
+        bits = synth.binary_bits_random(N, cfg["D"] // 32, seed, device=dev)
+        query = synth.binary_bits_random(1, cfg["D"] // 32, seed + 100, device=dev)[0].contiguous()
+        ws = binding.make_workspace(N, k, 1, dev)
+        out = binding._outputs(1, k, dev)
+        step = lambda: binding.rank_hamming(bits, cfg["D"], query, k, ws, out=out)
+        keep = (bits, query)
     elif kind == "multiquery":
         X = synth.dense_features(N, cfg["D"], seed, device=dev, dtype=torch.float16)
         W = synth.normal_matrix(cfg["Q"], cfg["D"], 0.05, seed + 100, device=dev, dtype=torch.float16)
@@ -312,6 +321,12 @@ def cpu_baseline(kind, cfg, torch):
         cb, w = keep[1].cpu().numpy(), keep[2].cpu().numpy()
         run = lambda: orc.topk(orc.pq_scores_reconstruct(codes, cb, w, 0.0), min(k, rows))
         sample = "first %d rows, scored by explicit reconstruction and fully sorted" % rows
+    elif kind == "hamming":
+        rows = min(cfg["N"], 1 << 20)
+        bits = keep[0][:rows].cpu().numpy().view(np.uint32)
+        query = keep[1].cpu().numpy().view(np.uint32)
+        run = lambda: orc.topk(orc.hamming_scores(bits, cfg["D"], query), min(k, rows))
+        sample = "first %d rows, distances counted bit by bit and fully sorted" % rows
     elif kind == "binary":
         rows = min(cfg["N"], 1 << 20)
         bits = keep[0][:rows].cpu().numpy().view(np.uint32)

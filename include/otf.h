@@ -154,6 +154,22 @@ int otf_rank_binary(const uint32_t *bits, int64_t N, int32_t D, const float *w, 
                     float *all_scores, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Hamming ranking of the binarised store (paper Sec. 3.1, discussion after Table 2: the ranking of
+ * binary codes "can also be significantly sped-up using hardware-accelerated Hamming distance",
+ * which needs a ranking model other than the linear SVM and is left open there).  The model here
+ * is a query code of D bits in the layout of the rows; nearer rows rank first:
+ *
+ *   scores[i] = -(number of dimensions d < D with bit_{i,d} != query bit d)      (exact)
+ *
+ *   bits   N x (D/32) uint32, contiguous rows.   query  D/32 uint32, 16-byte aligned.
+ *   Equal distances rank by ascending row index, like every list of this library.
+ *   D a multiple of 128, at most 8192; other values return OTF_ERR_UNSUPPORTED.
+ */
+int otf_rank_hamming(const uint32_t *bits, int64_t N, int32_t D, const uint32_t *query,
+                     int32_t k, float *out_scores, int32_t *out_idx,
+                     float *all_scores, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Ranking alone (paper Sec. 4: the scores are sorted on the GPU and the head of the list is
  * handed to the front-end).  For each of the Q rows of `scores` (row stride ld floats,
  * ld >= N) returns the k largest entries, sorted.

@@ -361,14 +361,14 @@ int otf_pq_build_lut(const float *codebooks, int32_t M, int32_t K, int32_t dsub,
 static bool table_row_bytes_ok(int32_t rb) { return rb >= 16 && rb % 16 == 0 && rb <= 1024; }
 
 // Shared tail of otf_rank_pq / otf_rank_binary once the table image is in place.
-static hipError_t rank_table(const uint8_t *codes, int64_t N, int row_bytes, int seven_bit, const float *image,
+static hipError_t rank_table(const uint8_t *codes, int64_t N, int row_bytes, TableKind kind, const float *image,
                              float bias, int32_t k, float *out_scores, int32_t *out_idx, float *all_scores, void *ws,
                              const WsLayout &L, hipStream_t s) {
     SelectWs sw = select_ws(ws, L);
     uint8_t *wsb = reinterpret_cast<uint8_t *>(ws);
     float *S = all_scores ? all_scores : reinterpret_cast<float *>(wsb + L.scores);
     hipError_t e = hipSuccess;
-    if (!seven_bit && row_bytes > 128 && N < kShortStoreRows) {
+    if (kind == kTableBytes && row_bytes > 128 && N < kShortStoreRows) {
         // the scan of rows longer than one table image reads whole tiles of 64 rows: a shorter store
         // is copied into a buffer of that many rows (the rows behind it are looked up, never emitted)
         e = hipMemcpyAsync(wsb + L.short_store, codes, (size_t)N * row_bytes, hipMemcpyDeviceToDevice, s);
@@ -380,23 +380,23 @@ static hipError_t rank_table(const uint8_t *codes, int64_t N, int row_bytes, int
         float *sample = reinterpret_cast<float *>(wsb + L.sample_scores);
         const int64_t Nv = sample_rows(N);
         const int m = sample_rank(N, Nv);
-        e = launch_table_scan(codes, Nv, row_bytes, seven_bit, image, bias, kEmitSample, sample, ssw.st, ssw.hist1, m,
+        e = launch_table_scan(codes, Nv, row_bytes, kind, image, bias, kEmitSample, sample, ssw.st, ssw.hist1, m,
                               nullptr, nullptr, nullptr, nullptr, s);
         if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, 0, nullptr, s);
         ScanTimer timer(s);
         if (e == hipSuccess)
-            e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitFilter, nullptr, sw.st, nullptr, m,
+            e = launch_table_scan(codes, N, row_bytes, kind, image, bias, kEmitFilter, nullptr, sw.st, nullptr, m,
                                   ssw.st, ssw.hist2, sw.cand, nullptr, s);
         timer.stop();
         if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
         if (e == hipSuccess)
-            e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitScores, S, sw.st, sw.hist1, k,
+            e = launch_table_scan(codes, N, row_bytes, kind, image, bias, kEmitScores, S, sw.st, sw.hist1, k,
                                   nullptr, nullptr, nullptr, sw.st, s);
         if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 1, s);
         return e;
     }
     ScanTimer timer(s);
-    e = launch_table_scan(codes, N, row_bytes, seven_bit, image, bias, kEmitScores, S, sw.st, sw.hist1, k, nullptr,
+    e = launch_table_scan(codes, N, row_bytes, kind, image, bias, kEmitScores, S, sw.st, sw.hist1, k, nullptr,
                           nullptr, nullptr, nullptr, s);
     timer.stop();
     if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 0, s);
@@ -414,7 +414,7 @@ int otf_rank_pq(const uint8_t *codes, int64_t N, int32_t M, int32_t K, const flo
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     float *image = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + L.lut_image);
     hipError_t e = launch_pq_prepare(lut, M, image, select_ws(ws, L), sample_select_ws(ws, L), s);
-    if (e == hipSuccess) e = rank_table(codes, N, M, 0, image, bias, k, out_scores, out_idx, all_scores, ws, L, s);
+    if (e == hipSuccess) e = rank_table(codes, N, M, kTableBytes, image, bias, k, out_scores, out_idx, all_scores, ws, L, s);
     return hip_status(e);
 }
 
@@ -430,7 +430,7 @@ int otf_rank_pq_model(const uint8_t *codes, int64_t N, int32_t M, int32_t K, int
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     float *image = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + L.lut_image);
     hipError_t e = launch_pq_prepare_model(codebooks, w, M, dsub, image, select_ws(ws, L), sample_select_ws(ws, L), s);
-    if (e == hipSuccess) e = rank_table(codes, N, M, 0, image, bias, k, out_scores, out_idx, all_scores, ws, L, s);
+    if (e == hipSuccess) e = rank_table(codes, N, M, kTableBytes, image, bias, k, out_scores, out_idx, all_scores, ws, L, s);
     return hip_status(e);
 }
 
@@ -446,8 +446,24 @@ int otf_rank_binary(const uint32_t *bits, int64_t N, int32_t D, const float *w, 
     float *image = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + L.lut_image);
     hipError_t e = launch_binary_prepare(w, D, image, select_ws(ws, L), sample_select_ws(ws, L), s);
     if (e == hipSuccess)
-        e = rank_table(reinterpret_cast<const uint8_t *>(bits), N, D / 8, D == 2048, image, bias, k, out_scores,
-                       out_idx, all_scores, ws, L, s);
+        e = rank_table(reinterpret_cast<const uint8_t *>(bits), N, D / 8, D == 2048 ? kTableSeven : kTableBytes, image,
+                       bias, k, out_scores, out_idx, all_scores, ws, L, s);
+    return hip_status(e);
+}
+
+int otf_rank_hamming(const uint32_t *bits, int64_t N, int32_t D, const uint32_t *query, int32_t k, float *out_scores,
+                     int32_t *out_idx, float *all_scores, void *ws, size_t ws_bytes, void *stream) {
+    WsLayout L;
+    if (!bits || !query || D < 1) return OTF_ERR_INVALID_ARG;
+    int rc = check_rank_common(N, k, 1, out_scores, out_idx, ws, ws_bytes, &L);
+    if (rc != OTF_OK) return rc;
+    if (D % 128 != 0 || !table_row_bytes_ok(D / 8)) return OTF_ERR_UNSUPPORTED;
+    if (!aligned16(bits) || !aligned16(query)) return OTF_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    hipError_t e = launch_select_init_both(select_ws(ws, L), sample_select_ws(ws, L), 1, s);
+    if (e == hipSuccess)
+        e = rank_table(reinterpret_cast<const uint8_t *>(bits), N, D / 8, kTableHamming,
+                       reinterpret_cast<const float *>(query), 0.f, k, out_scores, out_idx, all_scores, ws, L, s);
     return hip_status(e);
 }
 

@@ -105,13 +105,16 @@ hipError_t launch_pq_prepare_model(const float *codebooks, const float *w, int M
 hipError_t launch_binary_prepare(const float *w, int D, float *image, const SelectWs &sw, const SelectWs &sample_sw,
                                  hipStream_t s);
 // row_bytes = stored bytes per row (a multiple of 16, at most 1024; rows longer than 128 bytes are walked
-// through several table images); seven_bit = the 2048-bit binary layout (7+7+7+7+4 bits per word).
+// through several table images).  kind: byte groups; the 2048-bit binary layout (7+7+7+7+4 bits per
+// word); or no table at all: `image` is a query code of row_bytes bytes and the score is minus the
+// Hamming distance to it.
+enum TableKind { kTableBytes = 0, kTableSeven = 1, kTableHamming = 2 };
 //   kEmitScores  scores + pass-1 histogram into (st, hist1) for a top-k of k; `gate` as above
 //   kEmitSample  scores of the strided sample (compact numbering) + pass-1 histogram for rank k = m
 //   kEmitFilter  append rows at or above the threshold to cand (cursor in st); every block resolves
 //                the threshold from the sample's pass-2 state (tau, tau_hist2) for rank k = m (here k
 //                is the sample rank, not the length of the list)
-hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, int seven_bit, const float *image,
+hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, TableKind kind, const float *image,
                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
                              const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
                              const SelState *gate, hipStream_t s);

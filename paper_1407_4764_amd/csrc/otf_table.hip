@@ -194,13 +194,15 @@ __device__ __forceinline__ float dpp_move(float v) {
     return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
 }
 
-// Sum over groups of LPR adjacent lanes (LPR = 1, 2, 4, 8 or 16); every lane of a group receives it.
+// Sum over groups of LPR adjacent lanes (a power of two up to 64); every lane of a group receives it.
 template <int LPR>
 __device__ __forceinline__ float group_sum(float v) {
     if (LPR >= 2) v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]: lane ^ 1
     if (LPR >= 4) v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]: lane ^ 2
     if (LPR >= 8) v += dpp_move<0x141>(v);   // row_half_mirror: lane i <-> 7 - i of each 8
     if (LPR >= 16) v += dpp_move<0x140>(v);  // row_mirror: lane i <-> 15 - i of each 16
+    if (LPR >= 32) v += __shfl_xor(v, 16, 64);
+    if (LPR >= 64) v += __shfl_xor(v, 32, 64);
     return v;
 }
 
@@ -240,6 +242,17 @@ __device__ __forceinline__ float lookup16(const uint8_t *lds, const uint32_t (&d
     return group_sum<LPR>((v[0] + v[1]) + (v[2] + v[3]));
 }
 
+// Hamming ranking (paper Sec. 3.1, discussion after Table 2: binary codes can be ranked by
+// hardware-accelerated Hamming distance): the contribution of one 16-byte load is minus the number
+// of bits in which it differs from the query's bytes at the same position (XOR, population count),
+// summed over the lane group that shares a row.  Small integers: every sum is exact in fp32.
+template <int LPR>
+__device__ __forceinline__ float hamming16(const uint32_t (&d)[4], const uint32_t (&q)[4], bool live) {
+    int c = __builtin_popcount(d[0] ^ q[0]) + __builtin_popcount(d[1] ^ q[1]) + __builtin_popcount(d[2] ^ q[2]) +
+            __builtin_popcount(d[3] ^ q[3]);
+    return group_sum<LPR>(live ? -(float)c : 0.f);
+}
+
 // One row that a scan has finished: append it to the candidate list when it is at or above the
 // threshold (filtered scan), else store its score and count it in the pass-1 histogram.
 // Filtered scan: a wave that has seen the list full stops appending (the list is already
@@ -273,8 +286,9 @@ __device__ __forceinline__ long long store_row(long long v) {
 
 // Scan of rows that fit one table image.
 //   GB     bits per group: 8 (bytes; LPR = 1, 2, 4 or 8 lanes per row: the row occupies a span of
-//          16 LPR bytes of which the first M are stored) or 7 (2048-bit rows, LPR = 16, each
-//          word = 4 x 7 bits + 4 bits)
+//          16 LPR bytes of which the first M are stored), 7 (2048-bit rows, LPR = 16, each
+//          word = 4 x 7 bits + 4 bits), or 0: no table at all, the score is minus the Hamming
+//          distance to the query code that `image` then points at (LPR up to 64: rows up to 8192 bits)
 //   U      16-byte loads per lane per tile
 //   EMIT   what is produced (ScanEmit)
 //
@@ -300,7 +314,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     constexpr int TILE = RPW * U;                // rows per wave iteration
     constexpr int ACTIVE = LPR < U ? LPR : U;    // lanes of a group that own an output row per round
     constexpr int ROUNDS = U / ACTIVE;           // output rounds per tile
-    constexpr int TABLE_VEC = (GB == 8 ? kImageBytes : kImage7Bytes) / 16;
+    constexpr int TABLE_VEC = (GB == 8 ? kImageBytes : GB == 7 ? kImage7Bytes : 0) / 16;
     constexpr uint32_t CHUNK_TILES = 256u / (uint32_t)U;          // x U KiB per tile = 256 KiB of rows
 
     // the two scans that can follow each other on one state (filtered, then the gated full scan)
@@ -334,6 +348,13 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
         colbyte[t] = 4u * (uint32_t)(4 * chunk + j);
     }
     const uint32_t sidecol = (uint32_t)(kImageBytes + 4 * (8 * octet + (chunk & 7)));   // GB == 7 only
+    // GB == 0: the query's 16 bytes at this lane's position in the row (none: the lane is idle)
+    const bool q_live = (uint32_t)sub * 16u < (uint32_t)M;
+    uint32_t q4[4] = {0u, 0u, 0u, 0u};
+    if (GB == 0 && q_live) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) q4[t] = reinterpret_cast<const uint32_t *>(image)[4 * sub + t];
+    }
 
     const size_t u_bytes = (size_t)RPW * (size_t)M;        // distance between the U loads of a lane
     const int out_u = sub % ACTIVE;                        // which of a round's rows this lane emits
@@ -344,7 +365,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint32_t w4[4] = {d[u][0], d[u][1], d[u][2], d[u][3]};
-            const float su = lookup16<LPR, GB>(lds_raw, w4, shift, colbyte, sidecol);
+            const float su = GB == 0 ? hamming16<LPR>(w4, q4, q_live) : lookup16<LPR, GB == 0 ? 8 : GB>(lds_raw, w4, shift, colbyte, sidecol);
             if (u % ACTIVE == 0) mine[u / ACTIVE] = su;
             else mine[u / ACTIVE] = out_u == (u % ACTIVE) ? su : mine[u / ACTIVE];
         }
@@ -662,7 +683,8 @@ struct ScanArgs {
 
 template <int LPR, int U, int GB, int EMIT>
 static hipError_t launch_scan_cfg(const ScanArgs &a, hipStream_t s) {
-    constexpr int lds = GB == 8 ? kImageBytes : kImage7Bytes;
+    // (without a table the dynamic area only serves the threshold resolution of the filtered scan)
+    constexpr int lds = GB == 8 ? kImageBytes : GB == 7 ? kImage7Bytes : kBins2 * 4;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&table_scan_kernel<LPR, U, GB, EMIT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
@@ -717,13 +739,22 @@ static hipError_t launch_walk_emit(const ScanArgs &a, ScanEmit emit, hipStream_t
     }
 }
 
-// row_bytes = stored bytes per row, a multiple of 16 up to 1024; seven_bit only with 256.
-hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, int seven_bit, const float *image,
+// row_bytes = stored bytes per row, a multiple of 16 up to 1024; kTableSeven only with 256.
+hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, TableKind kind, const float *image,
                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
                              const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
                              const SelState *gate, hipStream_t s) {
     ScanArgs a{codes, N, row_bytes, image, bias, scores, st, hist1, k, tau, tau_hist2, cand, gate};
-    if (seven_bit) return launch_scan_emit<16, 7>(a, emit, s);
+    if (kind == kTableSeven) return launch_scan_emit<16, 7>(a, emit, s);
+    if (kind == kTableHamming) {                  // `image` is the query code; lanes per row = next power of two
+        if (row_bytes <= 16) return launch_scan_emit<1, 0>(a, emit, s);
+        if (row_bytes <= 32) return launch_scan_emit<2, 0>(a, emit, s);
+        if (row_bytes <= 64) return launch_scan_emit<4, 0>(a, emit, s);
+        if (row_bytes <= 128) return launch_scan_emit<8, 0>(a, emit, s);
+        if (row_bytes <= 256) return launch_scan_emit<16, 0>(a, emit, s);
+        if (row_bytes <= 512) return launch_scan_emit<32, 0>(a, emit, s);
+        return launch_scan_emit<64, 0>(a, emit, s);
+    }
     if (row_bytes > kSegBytes)
         return tune_int(OTF_DEBUG_WALK_TILES, 2) == 4 ? launch_walk_emit<4>(a, emit, s) : launch_walk_emit<2>(a, emit, s);
     switch (span_of(row_bytes)) {

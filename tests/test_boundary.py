@@ -117,6 +117,16 @@ def test_pq_and_binary_argument_errors(L):
     assert binr(D=96) == binding.OTF_ERR_UNSUPPORTED            # a multiple of 32 bits but not of 128
     assert binr(D=8320) == binding.OTF_ERR_UNSUPPORTED          # beyond 8192 bits
     assert binr(k=0) == binding.OTF_ERR_INVALID_ARG
+
+    def ham(bits=FAKE, N=1000, D=2048, q=FAKE, k=10, wsb=BIG):
+        return L.otf_rank_hamming(bits, N, D, q, k, FAKE, FAKE, None, FAKE, wsb, None)
+    assert ham(bits=None) == binding.OTF_ERR_INVALID_ARG
+    assert ham(q=None) == binding.OTF_ERR_INVALID_ARG
+    assert ham(q=FAKE + 4) == binding.OTF_ERR_INVALID_ARG
+    assert ham(D=96) == binding.OTF_ERR_UNSUPPORTED
+    assert ham(D=16384) == binding.OTF_ERR_UNSUPPORTED
+    assert ham(k=1001) == binding.OTF_ERR_INVALID_ARG
+    assert ham(wsb=0) == binding.OTF_ERR_WORKSPACE
     assert L.otf_pq_build_lut(None, 1, 1, 1, FAKE, FAKE, None) == binding.OTF_ERR_INVALID_ARG
     assert L.otf_pq_build_lut(FAKE, 0, 1, 1, FAKE, FAKE, None) == binding.OTF_ERR_INVALID_ARG
 
