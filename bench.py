@@ -50,6 +50,8 @@ WORKLOADS = {
     # the paper's own feature size (Sec. 3, Table 2: CNN 128), ten times its ~1M images so that the
     # scan and not the launches is what is timed
     "dense128": dict(name="dense_10Mx128_fp32_top1000", N=10_000_000, D=128, k=1000, row_bytes=512, dtype="f32"),
+    # the same feature size stored as fp16 (2 bytes per dimension), twice the rows in the same bytes
+    "dense128h": dict(name="dense_20Mx128_fp16_top1000", N=20_000_000, D=128, k=1000, row_bytes=256, dtype="f16"),
     # the paper's own PQ geometries on its 2048-D feature (Sec. 3: 4 or 8 dimensions per sub-block;
     # Table 2 row "2048 PQ 4 dims/sq", 512 bytes per image): rows longer than one table image
     "pq512": dict(name="pq_5Mx512B_M512_K256_top1000", N=5_000_000, M=512, K=256, dsub=4, k=1000, row_bytes=512,
@@ -68,10 +70,11 @@ def make_workload(kind, scale, torch, binding, synth):
     cfg["N"] = N
     dev = "cuda"
     seed = synth.BASE_SEED + {"dense": 2, "pq": 3, "binary": 4, "multiquery": 5, "dense128": 8, "pq512": 10,
-                              "pq256": 11, "hamming": 4}[kind]
+                              "pq256": 11, "hamming": 4, "dense128h": 12}[kind]
     k = cfg["k"]
-    if kind in ("dense", "dense128"):
-        X = synth.dense_features(N, cfg["D"], seed, device=dev)
+    if kind in ("dense", "dense128", "dense128h"):
+        X = synth.dense_features(N, cfg["D"], seed, device=dev,
+                                 dtype=torch.float16 if kind == "dense128h" else torch.float32)
         w = synth.normal_vector(cfg["D"], 0.05, seed + 100, device=dev)
         ws = binding.make_workspace(N, k, 1, dev)
         out = binding._outputs(1, k, dev)
@@ -309,8 +312,8 @@ def cpu_baseline(kind, cfg, torch):
     keep = cfg["_keep"]
     k = cfg["k"]
     budget_s = 10.0
-    if kind in ("dense", "dense128"):
-        rows = min(cfg["N"], 262144 if kind == "dense" else 1 << 21)
+    if kind in ("dense", "dense128", "dense128h"):
+        rows = min(cfg["N"], 1 << 20 if kind == "dense" else 1 << 22)
         X = keep[0][:rows].cpu().numpy()
         w = keep[1].cpu().numpy()
         run = lambda: orc.topk(orc.dense_scores(X, w)[0], min(k, rows))

@@ -1,11 +1,13 @@
 """Parity at the full benchmark sizes, in the launch configuration bench.py times (same store
-generators, same calls, default path).  The oracle cannot score 10^7..10^8 rows in test time, so:
-  * the returned top-k scores are compared with the oracle on exactly those rows;
-  * a random sample of rows is compared with the oracle through the all_scores output;
-  * completeness is checked as a property on the GPU's own fp32 scores: no row outside the
-    returned list scores above the list's last entry, and the list equals the first k of a full
-    sort of those scores (ties by row index).
-"""
+generators, same calls, default path).
+
+The oracle scores EVERY row of the dense, PQ, binary and Hamming stores (it does 1M x 2048 in a
+fraction of a second and the 20M- and 50M-row code stores in 5 to 30 seconds on the machine's cores; the
+store comes back from the GPU in chunks of a million rows): all scores are compared element by element
+and the returned list is checked against the oracle's full score vector with the top-k parity
+rule.  Only the 64-classifier store (655 G multiply-adds for the oracle) is checked on the
+returned rows plus a random sample.  In every case the list must also be exactly the first k of a
+full sort of the GPU's own fp32 scores (index work is bit-exact)."""
 import numpy as np
 import pytest
 import torch
@@ -38,85 +40,90 @@ def _sample_rows(N, seed):
     return np.sort(np.random.default_rng(seed).choice(N, SAMPLE, replace=False))
 
 
-def test_dense_full_size(oracle):
-    step, cfg = bench.make_workload("dense", 1.0, torch, binding, synth)
-    X, w = cfg["_keep"]
-    N, k = cfg["N"], cfg["k"]
+CHUNK = 1 << 20
+
+
+def _oracle_all_rows(N, score_chunk):
+    """Oracle scores of all N rows; score_chunk(r0, r1) -> float64 scores of rows [r0, r1)."""
+    out = np.empty(N, dtype=np.float64)
+    for r0 in range(0, N, CHUNK):
+        r1 = min(N, r0 + CHUNK)
+        out[r0:r1] = score_chunk(r0, r1)
+    return out
+
+
+def _check_all_scores_and_list(oracle, ref, all_scores, idx, val, k, rtol):
+    got = all_scores.cpu().numpy().astype(np.float64)
+    tol = oracle.score_tolerance(ref, rtol)
+    bad = np.nonzero(np.abs(got - ref) > tol)[0]
+    assert bad.size == 0, "%d of %d scores off, first row %d: got %r oracle %r" % (bad.size, ref.size, bad[0], got[bad[0]], ref[bad[0]])
+    ok, msg = oracle.topk_parity_ok(ref, k, idx.cpu().numpy(), val.cpu().numpy(), rtol)
+    assert ok, msg
+
+
+def _run_both(step, rank_with_scores, N, k):
+    """The benchmark's own call, then the same ranking with every score written out."""
     val, idx = step()
     torch.cuda.synchronize()
+    val, idx = val.clone(), idx.clone()
     ws = binding.make_workspace(N, k)
     all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
-    val2, idx2 = binding.rank_dense(X, w, None, k, ws, all_scores=all_scores)
+    val2, idx2 = rank_with_scores(ws, all_scores)
     torch.cuda.synchronize()
     assert torch.equal(idx, idx2) and torch.equal(val, val2)
     _check_list_against_own_scores(all_scores, idx[0], val[0], k)
-    rows = np.union1d(_sample_rows(N, 1), idx[0].cpu().numpy())
-    ref = oracle.dense_scores(X[torch.from_numpy(rows).to(DEV)].cpu().numpy(), w.cpu().numpy())[0]
-    got = all_scores[torch.from_numpy(rows).to(DEV)].cpu().numpy().astype(np.float64)
-    sigma = float(all_scores.std().item())
-    assert np.all(np.abs(got - ref) <= 1e-4 * np.maximum(np.abs(ref), sigma))
+    return all_scores, idx[0], val[0]
 
 
-def test_dense_128d_full_size(oracle):
-    """The paper's own feature size, 10M rows: the default path here is the filtered scan, the
-    all_scores call the materialising one; both must give the same list."""
-    step, cfg = bench.make_workload("dense128", 1.0, torch, binding, synth)
+@pytest.mark.parametrize("kind,rtol", [("dense", 1e-4), ("dense128", 1e-4), ("dense128h", 2e-3)])
+def test_dense_full_size(oracle, kind, rtol):
+    """1M x 2048 fp32 (the headline store), and the paper's own feature size: 10M x 128 fp32 and
+    20M x 128 fp16 (default path there: the filtered scan; the all_scores call materialises)."""
+    step, cfg = bench.make_workload(kind, 1.0, torch, binding, synth)
     X, w = cfg["_keep"]
     N, k = cfg["N"], cfg["k"]
-    val, idx = step()
-    torch.cuda.synchronize()
-    ws = binding.make_workspace(N, k)
-    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
-    val2, idx2 = binding.rank_dense(X, w, None, k, ws, all_scores=all_scores)
-    torch.cuda.synchronize()
-    assert torch.equal(idx, idx2) and torch.equal(val, val2)
-    _check_list_against_own_scores(all_scores, idx[0], val[0], k)
-    rows = np.union1d(_sample_rows(N, 6), idx[0].cpu().numpy())
-    ref = oracle.dense_scores(X[torch.from_numpy(rows).to(DEV)].cpu().numpy(), w.cpu().numpy())[0]
-    got = all_scores[torch.from_numpy(rows).to(DEV)].cpu().numpy().astype(np.float64)
-    sigma = float(all_scores.std().item())
-    assert np.all(np.abs(got - ref) <= 1e-4 * np.maximum(np.abs(ref), sigma))
+    all_scores, idx, val = _run_both(step, lambda ws, a: binding.rank_dense(X, w, None, k, ws, all_scores=a), N, k)
+    wn = w.cpu().numpy()
+    ref = _oracle_all_rows(N, lambda r0, r1: oracle.dense_scores(X[r0:r1].cpu().numpy(), wn)[0])
+    _check_all_scores_and_list(oracle, ref, all_scores, idx, val, k, rtol)
 
 
-def test_pq_full_size(oracle):
-    step, cfg = bench.make_workload("pq", 1.0, torch, binding, synth)
+@pytest.mark.parametrize("kind", ["pq", "pq512", "pq256"])
+def test_pq_full_size(oracle, kind):
+    """20M x 128 B (M = 128), and the paper's own geometries on 2048-D: 5M x 512 B and 10M x 256 B."""
+    step, cfg = bench.make_workload(kind, 1.0, torch, binding, synth)
     codes, cb, w = cfg["_keep"]
     N, k = cfg["N"], cfg["k"]
-    val, idx = step()
-    torch.cuda.synchronize()
-    ws = binding.make_workspace(N, k)
     lut = binding.pq_build_lut(cb, w)
-    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
-    val2, idx2 = binding.rank_pq(codes, lut, 0.0, k, ws, all_scores=all_scores)
-    torch.cuda.synchronize()
-    assert torch.equal(idx, idx2) and torch.equal(val, val2)
-    _check_list_against_own_scores(all_scores, idx[0], val[0], k)
-    rows = np.union1d(_sample_rows(N, 2), idx[0].cpu().numpy())
-    ref = oracle.pq_scores_reconstruct(codes[torch.from_numpy(rows).to(DEV)].cpu().numpy(), cb.cpu().numpy(),
-                                       w.cpu().numpy(), 0.0)
-    got = all_scores[torch.from_numpy(rows).to(DEV)].cpu().numpy().astype(np.float64)
-    sigma = float(all_scores.std().item())
-    assert np.all(np.abs(got - ref) <= 1e-4 * np.maximum(np.abs(ref), sigma))
+    all_scores, idx, val = _run_both(step, lambda ws, a: binding.rank_pq(codes, lut, 0.0, k, ws, all_scores=a), N, k)
+    cbn, wn = cb.cpu().numpy(), w.cpu().numpy()
+    ref = _oracle_all_rows(N, lambda r0, r1: oracle.pq_scores_reconstruct(codes[r0:r1].cpu().numpy(), cbn, wn, 0.0))
+    _check_all_scores_and_list(oracle, ref, all_scores, idx, val, k, 1e-4)
 
 
 def test_binary_full_size(oracle):
+    """50M x 2048 bit: the bit-by-bit oracle needs ~0.4 s per million of these rows on the box's 16
+    threads, half a minute for the whole store with the full sort of its 50M scores."""
     step, cfg = bench.make_workload("binary", 1.0, torch, binding, synth)
     bits, w = cfg["_keep"]
     N, k, D = cfg["N"], cfg["k"], cfg["D"]
-    val, idx = step()
-    torch.cuda.synchronize()
-    ws = binding.make_workspace(N, k)
-    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
-    val2, idx2 = binding.rank_binary(bits, D, w, 0.0, k, ws, all_scores=all_scores)
-    torch.cuda.synchronize()
-    assert torch.equal(idx, idx2) and torch.equal(val, val2)
-    _check_list_against_own_scores(all_scores, idx[0], val[0], k)
-    rows = np.union1d(_sample_rows(N, 3), idx[0].cpu().numpy())
-    ref = oracle.binary_scores(synth.as_uint32(bits[torch.from_numpy(rows).to(DEV)].cpu().numpy()), D,
-                               w.cpu().numpy(), 0.0)
-    got = all_scores[torch.from_numpy(rows).to(DEV)].cpu().numpy().astype(np.float64)
-    sigma = float(all_scores.std().item())
-    assert np.all(np.abs(got - ref) <= 1e-4 * np.maximum(np.abs(ref), sigma))
+    all_scores, idx, val = _run_both(step, lambda ws, a: binding.rank_binary(bits, D, w, 0.0, k, ws, all_scores=a), N, k)
+    wn = w.cpu().numpy()
+    ref = _oracle_all_rows(N, lambda r0, r1: oracle.binary_scores(synth.as_uint32(bits[r0:r1].cpu().numpy()), D, wn, 0.0))
+    _check_all_scores_and_list(oracle, ref, all_scores, idx, val, k, 1e-4)
+
+
+def test_hamming_full_size(oracle):
+    step, cfg = bench.make_workload("hamming", 1.0, torch, binding, synth)
+    bits, query = cfg["_keep"]
+    N, k, D = cfg["N"], cfg["k"], cfg["D"]
+    all_scores, idx, val = _run_both(step, lambda ws, a: binding.rank_hamming(bits, D, query, k, ws, all_scores=a), N, k)
+    qn = synth.as_uint32(query.cpu().numpy())
+    ref = _oracle_all_rows(N, lambda r0, r1: oracle.hamming_scores(synth.as_uint32(bits[r0:r1].cpu().numpy()), D, qn))
+    np.testing.assert_array_equal(all_scores.cpu().numpy().astype(np.float64), ref)       # integers: exact
+    i, v = oracle.topk(ref, k)
+    np.testing.assert_array_equal(idx.cpu().numpy(), i)
+    np.testing.assert_array_equal(val.cpu().numpy().astype(np.float64), v)
 
 
 def test_multi_classifier_full_size(oracle):
