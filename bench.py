@@ -30,14 +30,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the scoring kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# scaled by the same counters on a plain copy of known size (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).
-MEASURED_TRAFFIC_BYTES = {          # read + written, profiles/traffic_counters.md
-    "dense": 8.196e9 + 5.2e6,
-    "pq": 2.589e9 + 0.5e6,
-    "binary": 12.829e9 + 1.8e6,
-    "multiquery": 20.480e9 + 16.5e6,
-    "dense128": 5.132e9 + 0.9e6,
+# HBM bytes per launch of the scoring kernel.  NOT measured by this run: copied from
+# profiles/traffic_counters.md, i.e. from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
+# command scaled by the same counters on a plain copy of known size.  The line says so
+# ("traffic_source"), and a workload that is scaled down or has no counter run yet reports null.
+TRAFFIC_SOURCE = "profiles/traffic_counters.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not measured in this run)"
+MEASURED_TRAFFIC_BYTES = {          # read + written
 }
 
 WORKLOADS = {
@@ -131,6 +129,32 @@ def time_steps(step, steps, warmup, torch, binding):
     return (t1 - t0) / steps, (scan_ms_total / nrec if nrec else None)
 
 
+def graph_replay_ms(step, steps, torch):
+    """The same step captured once into a HIP graph and replayed `steps` times (no host work per
+    kernel between replays); milliseconds per replay, or None if the capture is refused."""
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        for _ in range(5):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+    except Exception as exc:                      # the figure is an extra: never fail the benchmark for it
+        sys.stderr.write("graph replay skipped: %r\n" % (exc,))
+        return None
+
+
 def measure(kind, steps, warmup, scale, torch, binding, synth):
     step, cfg = make_workload(kind, scale, torch, binding, synth)
     sec_per_step, scan_ms = time_steps(step, steps, warmup, torch, binding)
@@ -150,8 +174,10 @@ def measure(kind, steps, warmup, scale, torch, binding, synth):
     if scan_ms:
         achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
         res["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                           "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(kind),
-                           "kernel_ms": scan_ms, "algorithmic_bytes": alg_bytes}
+                           "frac": achieved / HBM_PEAK_GBS,
+                           "traffic": MEASURED_TRAFFIC_BYTES.get(kind) if scale == 1.0 else None,
+                           "traffic_source": TRAFFIC_SOURCE, "kernel_ms": scan_ms, "algorithmic_bytes": alg_bytes}
+    res["graph_replay_ms_per_step"] = graph_replay_ms(step, steps, torch)
     return res, cfg
 
 
@@ -256,13 +282,17 @@ def measure_pq_encoder(torch, binding, synth, X=None):
     # The kernel splits every fp32 value into three exact bf16 pieces and issues, per 32 rows x 32
     # centres x 16 dimensions, six bf16 matrix instructions for the product and one for the norms:
     # 7 x the useful multiply-adds run on the bf16 matrix pipe, so that pipe's peak is the roofline.
+    # `frac` counts the method's own flops, 2 N M K dsub, against the bf16 matrix peak (the pipe they run on).
     useful = 2.0 * N * M * 256 * dsub / (enc_ms * 1e-3) / 1e12
     executed = 7.0 * useful
     return {"workload": "pq_encode_1Mx2048_M128_K256", "encode_ms": enc_ms, "rows_per_s": N / (enc_ms * 1e-3),
             "lloyd_step_ms": lloyd_ms, "dtype": "bf16 x 3 pieces per fp32 value, fp32 accumulate",
             "useful_fp32_tflops": useful, "useful_frac_of_fp32_matrix_peak": useful / MFMA_FP32_PEAK_TFLOPS,
-            "roofline": {"bound": "mfma", "achieved": executed, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": executed / MFMA_BF16_PEAK_TFLOPS, "traffic": None}}
+            "executed_bf16_tflops": executed, "executed_frac_of_bf16_matrix_peak": executed / MFMA_BF16_PEAK_TFLOPS,
+            "roofline": {"bound": "mfma", "achieved": useful, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": useful / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                         "note": "algorithmic flops (2 N M K dsub) over the bf16 matrix peak; the kernel executes 7x as "
+                                 "many bf16 multiply-adds to reach fp32 accuracy (executed_* fields)"}}
 
 
 MFMA_FP32_PEAK_TFLOPS = 157.3                     # MI355X dense fp32 matrix rate
@@ -294,30 +324,35 @@ def measure_encoder(torch, binding, synth):
     frame_ms = (time.perf_counter() - t0) * 1e3
     # six bf16 matrix instructions (products of the three exact pieces of every fp32 value) do the
     # work of eight fp32 ones: 6 x the useful multiply-adds run on the bf16 matrix pipe
+    # `frac` counts the method's own flops, 2 N m n, against the bf16 matrix peak (the pipe they run on)
     useful = 2.0 * N * m * n / (ms * 1e-3) / 1e12
     executed = 6.0 * useful
     return {"workload": "binarize_1Mx128_to_2048bit", "ms_per_call": ms, "descriptors_per_s": N / (ms * 1e-3),
             "dtype": "bf16 x 3 pieces per fp32 value, fp32 accumulate", "useful_fp32_tflops": useful,
             "useful_frac_of_fp32_matrix_peak": useful / MFMA_FP32_PEAK_TFLOPS,
+            "executed_bf16_tflops": executed, "executed_frac_of_bf16_matrix_peak": executed / MFMA_BF16_PEAK_TFLOPS,
             "frame_setup_ms": frame_ms,
-            "roofline": {"bound": "mfma", "achieved": executed, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": executed / MFMA_BF16_PEAK_TFLOPS, "traffic": None}}
+            "roofline": {"bound": "mfma", "achieved": useful, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": useful / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                         "note": "algorithmic flops (2 N m n) over the bf16 matrix peak; the kernel executes 6x as many "
+                                 "bf16 multiply-adds to reach fp32 accuracy (executed_* fields)"}}
 
 
-def cpu_baseline(kind, cfg, torch):
-    """Times the CPU oracle on this host on a bounded sample of the workload's own rows."""
+def cpu_baseline(kind, cfg, torch, budget_s=10.0):
+    """Times the CPU oracle on this host on a bounded sample of the workload's own rows (the
+    headline store: all of its rows), repeated until budget_s seconds have passed."""
     from oracle import otf_oracle as orc
     import numpy as np
     cores = orc.num_threads()
     keep = cfg["_keep"]
     k = cfg["k"]
-    budget_s = 10.0
     if kind in ("dense", "dense128", "dense128h"):
         rows = min(cfg["N"], 1 << 20 if kind == "dense" else 1 << 22)
         X = keep[0][:rows].cpu().numpy()
         w = keep[1].cpu().numpy()
         run = lambda: orc.topk(orc.dense_scores(X, w)[0], min(k, rows))
-        sample = "first %d rows of the store, scored and fully sorted" % rows
+        sample = ("all %d rows of the store, scored and fully sorted" if rows == cfg["N"] else
+                  "first %d rows of the store, scored and fully sorted") % rows
     elif kind in ("pq", "pq512", "pq256"):
         rows = min(cfg["N"], 1 << 20)
         codes = keep[0][:rows].cpu().numpy()
@@ -426,6 +461,7 @@ def main():
                    "step": "one otf_rank_* call: scan of the whole store + exact sorted top-k"},
         "whole_path_frac_of_hbm_peak": res["whole_path_frac_of_hbm_peak"],
         "roofline": res.get("roofline"),
+        "graph_replay_ms_per_step": res.get("graph_replay_ms_per_step"),
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(args.workload, cfg, torch)
@@ -444,6 +480,8 @@ def main():
             # (0.453 -> 0.424 ms for the PQ store), so the side measurements warm up longer
             r, c = measure(kind, args.steps, max(args.warmup, 100), args.scale, torch, binding, synth)
             r["steps"], r["warmup"] = args.steps, max(args.warmup, 100)
+            if not args.no_cpu_baseline:
+                r["cpu_baseline"] = cpu_baseline(kind, c, torch, budget_s=2.5)
             del c
             torch.cuda.empty_cache()
             others.append(r)
