@@ -311,7 +311,7 @@ typedef enum {
     OTF_DEBUG_NARROW_BLOCKS_PER_CU,  /* 1..8, dense scan of rows up to 512 bytes */
     OTF_DEBUG_MFMA_BLOCKS_PER_CU,    /* 1..8, multi-classifier scan */
     OTF_DEBUG_PQENC_BLOCKS_PER_CU,   /* 1..8, otf_pq_encode */
-    OTF_DEBUG_WALK_TILES,            /* 2 or 4 tiles of 64 rows per wave and block, table scans of rows > 128 bytes */
+    OTF_DEBUG_WALK_TILES,            /* 2, 4 or 8 tiles of 64 rows per wave and block, table scans of rows > 128 bytes */
     OTF_DEBUG_KEYS
 } otf_debug_key;
 

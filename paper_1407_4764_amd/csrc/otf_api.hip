@@ -112,7 +112,7 @@ static bool debug_value_ok(int key, int v) {
         case OTF_DEBUG_SCAN_THREADS: return v >= 64 && v <= 1024 && v % 64 == 0;   // whole waves, the kernels' launch bound
         case OTF_DEBUG_SCAN_UNROLL:
         case OTF_DEBUG_BINARIZE_WAVES: return v == 4 || v == 8;
-        case OTF_DEBUG_WALK_TILES: return v == 2 || v == 4;
+        case OTF_DEBUG_WALK_TILES: return v == 2 || v == 4 || v == 8;
         case OTF_DEBUG_PQENC_RANGE: return v >= 4 && v <= 64 && v % 4 == 0;
         case OTF_DEBUG_DENSE_BLOCKS_PER_CU:
         case OTF_DEBUG_NARROW_BLOCKS_PER_CU:

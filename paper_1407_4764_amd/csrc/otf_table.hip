@@ -565,6 +565,15 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_walk_kernel(
                                              (__attribute__((address_space(3))) void *)(lds_raw + j * 1024), 16, 0, 0);
     };
 
+    // part[i] <- part[i + 2], the first two to the end
+    auto turn_ring = [&](float *part) {
+        const float x0 = part[0], x1 = part[1];
+#pragma unroll
+        for (int i = 0; i + 2 < TPW; ++i) part[i] = part[i + 2];
+        part[TPW - 2] = x0;
+        part[TPW - 1] = x1;
+    };
+
     long long blk = s_blk[0];
     if (blk >= nblocks) {                          // uniform: nothing for this workgroup
         if (EMIT != kEmitFilter) merge_hist1(lhist, hist1);
@@ -592,27 +601,37 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_walk_kernel(
             __builtin_amdgcn_s_waitcnt(0x0F78);    // vmcnt(8): all but the 8 loads just issued have landed
             lds_barrier();                         // the image is complete
             if (p == 0 && tid == 0) pend = atomicAdd(blk_ctr, 1u);   // the block after this one
-#pragma unroll
-            for (int t = 0; t < TPW; ++t) {
-                if (t > 0) {
-                    // the tile after this one: the next of the phase, the first of the next phase, the
-                    // first of the next block, or (nothing left) this block's first tile once more
-                    long long v0;
-                    int pp = p;
-                    if (t + 1 < TPW) v0 = tile_row0(blk, t + 1);
-                    else if (p + 1 < nphase) v0 = tile_row0(blk, 0), pp = p + 1;
-                    else if (next_blk < nblocks) v0 = tile_row0(next_blk, 0), pp = 0;
-                    else v0 = tile_row0(blk, 0), pp = 0;
-                    fetch((t & 1) ? b0 : b1, v0, pp);
-                }
-                const float su = tile_sum((t & 1) ? b1 : b0);
-                part[t] = p == 0 ? su : part[t] + su;
+            // The tiles of the phase go in pairs: even ones arrive in b0, odd ones in b1.  The partial sums
+            // sit in a ring of registers that turns by two after every pair, so the pair at hand is
+            // always elements 0 and 1 and the loop stays rolled (unrolled, four tiles per wave spilled
+            // a hundred registers).
+#pragma unroll 1
+            for (int t = 0; t < TPW; t += 2) {
+                if (t > 0) fetch(b1, tile_row0(blk, t + 1), p);      // (the phase's first odd tile went out with the image)
+                const float s0 = tile_sum(b0);
+                part[0] = p == 0 ? s0 : part[0] + s0;
+                // the even tile after this pair: the next of the phase, the first of the next phase, the
+                // first of the next block, or (nothing left) this block's first tile once more
+                long long v0;
+                int pp = p;
+                if (t + 2 < TPW) v0 = tile_row0(blk, t + 2);
+                else if (p + 1 < nphase) v0 = tile_row0(blk, 0), pp = p + 1;
+                else if (next_blk < nblocks) v0 = tile_row0(next_blk, 0), pp = 0;
+                else v0 = tile_row0(blk, 0), pp = 0;
+                fetch(b0, v0, pp);
+                const float s1 = tile_sum(b1);
+                part[1] = p == 0 ? s1 : part[1] + s1;
+                turn_ring(part);
             }
         }
+#pragma unroll 1
+        for (int t = 0; t < TPW; t += 2) {
 #pragma unroll
-        for (int t = 0; t < TPW; ++t) {
-            const long long v0 = tile_row0(blk, t), v = window(v0) + (long long)sub * RPW + rr;
-            if (v >= v0 && v < N) emit_row<EMIT>(part[t] + bias, v, tau, list_full, st, cand, scores, lhist);
+            for (int h = 0; h < 2; ++h) {
+                const long long v0 = tile_row0(blk, t + h), v = window(v0) + (long long)sub * RPW + rr;
+                if (v >= v0 && v < N) emit_row<EMIT>(part[h] + bias, v, tau, list_full, st, cand, scores, lhist);
+            }
+            turn_ring(part);
         }
         if (EMIT == kEmitFilter) list_full = __ballot(list_full) != 0ull;   // one lane's news serves the wave
         if (next_blk >= nblocks) break;            // uniform
@@ -756,7 +775,13 @@ hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, Tab
         return launch_scan_emit<64, 0>(a, emit, s);
     }
     if (row_bytes > kSegBytes)
-        return tune_int(OTF_DEBUG_WALK_TILES, 2) == 4 ? launch_walk_emit<4>(a, emit, s) : launch_walk_emit<2>(a, emit, s);
+        // four tiles per wave and block for the long scans (half as many image changes as with two:
+        // 0.410 -> 0.399 ms on 5M x 512 B; eight leave too few blocks to balance), two for short ones
+        switch (tune_int(OTF_DEBUG_WALK_TILES, N >= ((int64_t)1 << 20) ? 4 : 2)) {
+            case 4: return launch_walk_emit<4>(a, emit, s);
+            case 8: return launch_walk_emit<8>(a, emit, s);
+            default: return launch_walk_emit<2>(a, emit, s);
+        }
     switch (span_of(row_bytes)) {
         case 16: return launch_scan_emit<1, 8>(a, emit, s);
         case 32: return launch_scan_emit<2, 8>(a, emit, s);

@@ -68,10 +68,12 @@ def test_pq_rows_whose_length_is_not_a_power_of_two(oracle, N, M):
     _check_pq_exact(oracle, N, M, min(N, 50), SEED + 200 + M)
 
 
-def test_four_tiles_per_wave_give_the_same_scores(oracle, debug_switches):
-    debug_switches({binding.DEBUG_WALK_TILES: 4})
-    _check_pq_exact(oracle, 4096 * 270 + 5, 512, 64, SEED + 300)
+@pytest.mark.parametrize("tiles", [4, 8])
+def test_more_tiles_per_wave_give_the_same_scores(oracle, debug_switches, tiles):
+    debug_switches({binding.DEBUG_WALK_TILES: tiles})
+    _check_pq_exact(oracle, 1024 * tiles * 270 + 5, 512, 64, SEED + 300)
     _check_pq_exact(oracle, 5000, 256, 10, SEED + 301)
+    _check_pq_exact(oracle, 70, 384, 10, SEED + 302)
 
 
 @pytest.mark.parametrize("N,D", [(3000, 4096), (1100, 8192), (5000, 1536), (2500, 768), (700, 384), (1300000, 4096),
