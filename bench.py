@@ -54,6 +54,10 @@ WORKLOADS = {
     # Table 2 row "2048 PQ 4 dims/sq", 512 bytes per image): rows longer than one table image
     "pq512": dict(name="pq_5Mx512B_M512_K256_top1000", N=5_000_000, M=512, K=256, dsub=4, k=1000, row_bytes=512,
                   dtype="f32"),
+    # the same 10M rows of 128-D features, 60 % of their entries zero (Sec. 3.1), stored as presence
+    # mask + packed non-zero values; row_bytes is filled in from the store that was generated
+    "sparse128": dict(name="sparse_10Mx128_fp32_60pct_zeros_top1000", N=10_000_000, D=128, k=1000, row_bytes=None,
+                      dtype="f32"),
     # Hamming ranking of the binary store (Sec. 3.1, after Table 2: what the paper leaves for later)
     "hamming": dict(name="hamming_50Mx2048bit_top1000", N=50_000_000, D=2048, k=1000, row_bytes=256, dtype="u32"),
     "pq256": dict(name="pq_10Mx256B_M256_K256_top1000", N=10_000_000, M=256, K=256, dsub=8, k=1000, row_bytes=256,
@@ -68,7 +72,7 @@ def make_workload(kind, scale, torch, binding, synth):
     cfg["N"] = N
     dev = "cuda"
     seed = synth.BASE_SEED + {"dense": 2, "pq": 3, "binary": 4, "multiquery": 5, "dense128": 8, "pq512": 10,
-                              "pq256": 11, "hamming": 4, "dense128h": 12}[kind]
+                              "pq256": 11, "hamming": 4, "dense128h": 12, "sparse128": 13}[kind]
     k = cfg["k"]
     if kind in ("dense", "dense128", "dense128h"):
         X = synth.dense_features(N, cfg["D"], seed, device=dev,
@@ -94,6 +98,16 @@ def make_workload(kind, scale, torch, binding, synth):
         out = binding._outputs(1, k, dev)
         step = lambda: binding.rank_binary(bits, cfg["D"], w, 0.0, k, ws, out=out)
         keep = (bits, w)
+    elif kind == "sparse128":
+        X = synth.sparse_features(N, cfg["D"], seed, device=dev)
+        rows, start = synth.sparse_rows_from_dense(X)
+        del X
+        w = synth.normal_vector(cfg["D"], 0.05, seed + 100, device=dev)
+        ws = binding.make_workspace(N, k, 1, dev)
+        out = binding._outputs(1, k, dev)
+        step = lambda: binding.rank_sparse(rows, start, cfg["D"], w, 0.0, k, ws, out=out)
+        cfg["row_bytes"] = (rows.numel() * 4 + start.numel() * 8) / N      # stored bytes per row, offsets included
+        keep = (rows, start, w)
     elif kind == "hamming":
         bits = synth.binary_bits_random(N, cfg["D"] // 32, seed, device=dev)
         query = synth.binary_bits_random(1, cfg["D"] // 32, seed + 100, device=dev)[0].contiguous()
@@ -359,6 +373,19 @@ def cpu_baseline(kind, cfg, torch, budget_s=10.0):
         cb, w = keep[1].cpu().numpy(), keep[2].cpu().numpy()
         run = lambda: orc.topk(orc.pq_scores_reconstruct(codes, cb, w, 0.0), min(k, rows))
         sample = "first %d rows, scored by explicit reconstruction and fully sorted" % rows
+    elif kind == "sparse128":
+        rows = min(cfg["N"], 1 << 21)
+        st = keep[1][:rows + 1].cpu().numpy()
+        words = keep[0][:int(st[-1])].cpu().numpy().view(np.uint32)
+        w = keep[2].cpu().numpy()
+        idx = st[:-1, None] + np.arange(4)[None, :]
+        mask = words[idx]
+        is_value = np.ones(int(st[-1]), dtype=bool)
+        is_value[idx.reshape(-1)] = False
+        values = words[is_value].view(np.float32)
+        vstart = np.concatenate([[0], np.cumsum(st[1:] - st[:-1] - 4)]).astype(np.int64)
+        run = lambda: orc.topk(orc.dense_scores(orc.sparse_expand(mask, values, vstart, cfg["D"]), w)[0], min(k, rows))
+        sample = "first %d rows, expanded to dense rows, scored and fully sorted" % rows
     elif kind == "hamming":
         rows = min(cfg["N"], 1 << 20)
         bits = keep[0][:rows].cpu().numpy().view(np.uint32)

@@ -154,6 +154,25 @@ int otf_rank_binary(const uint32_t *bits, int64_t N, int32_t D, const float *w, 
                     float *all_scores, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Sparse-row store (paper Sec. 3.1, discussion after Table 2: the ConvNet features are very sparse,
+ * the 128-D ones over 60 % zeros, and compression that exploits it could shrink the store further).
+ * The scores are those of otf_rank_dense on the expanded rows; only the storage differs:
+ *
+ *   row i occupies the 32-bit words [start[i], start[i+1]) of `rows`: first D/32 words of presence
+ *   mask (dimension d = bit d mod 32, least significant first, of word d div 32; set iff the value
+ *   is stored), then the fp32 bit patterns of the stored values in ascending order of dimension.
+ *
+ *   scores[i] = bias + sum over stored d of w[d] * value_{i,d}                       (fp32)
+ *
+ *   rows   the word array, 16-byte aligned, readable up to start[N] rounded up to a multiple of 4 words.
+ *   start  N + 1 int64 word offsets, ascending, start[i+1] - start[i] = D/32 + popcount(mask of row i).
+ *   D must be 128 (the paper's compact feature); other values return OTF_ERR_UNSUPPORTED.
+ */
+int otf_rank_sparse(const uint32_t *rows, const int64_t *start, int64_t N, int32_t D, const float *w,
+                    float bias, int32_t k, float *out_scores, int32_t *out_idx,
+                    float *all_scores, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Hamming ranking of the binarised store (paper Sec. 3.1, discussion after Table 2: the ranking of
  * binary codes "can also be significantly sped-up using hardware-accelerated Hamming distance",
  * which needs a ranking model other than the linear SVM and is left open there).  The model here

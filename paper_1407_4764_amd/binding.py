@@ -27,7 +27,7 @@ EXPORTS = ["otf_status_string", "otf_workspace_bytes", "otf_rank_dense", "otf_pq
            "otf_rank_binary", "otf_topk", "otf_sgd_workspace_bytes", "otf_svm_sgd_step", "otf_svm_sgd_pass",
            "otf_tight_frame_workspace_bytes",
            "otf_tight_frame", "otf_binarize", "otf_pq_train_workspace_bytes", "otf_pq_encode", "otf_pq_lloyd_step",
-           "otf_profile_begin", "otf_profile_end", "otf_debug_set", "otf_rank_dense_noalloc", "otf_rank_pq_model", "otf_rank_hamming"]
+           "otf_profile_begin", "otf_profile_end", "otf_debug_set", "otf_rank_dense_noalloc", "otf_rank_pq_model", "otf_rank_hamming", "otf_rank_sparse"]
 
 # otf_debug_key
 (DEBUG_RANK_PATH, DEBUG_BINARIZE_FP32, DEBUG_PQENC_FP32, DEBUG_SCAN_THREADS, DEBUG_SCAN_UNROLL, DEBUG_BINARIZE_WAVES,
@@ -72,6 +72,8 @@ def lib():
         L.otf_rank_pq_model.argtypes = [vp, i64, i32, i32, i32, vp, vp, f32, i32, vp, vp, vp, vp, sz, vp]
         L.otf_rank_binary.restype = ctypes.c_int
         L.otf_rank_binary.argtypes = [vp, i64, i32, vp, f32, i32, vp, vp, vp, vp, sz, vp]
+        L.otf_rank_sparse.restype = ctypes.c_int
+        L.otf_rank_sparse.argtypes = [vp, vp, i64, i32, vp, f32, i32, vp, vp, vp, vp, sz, vp]
         L.otf_rank_hamming.restype = ctypes.c_int
         L.otf_rank_hamming.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
         L.otf_topk.restype = ctypes.c_int
@@ -307,6 +309,25 @@ def rank_binary(bits, D, w, bias, k, ws, all_scores=None, out=None):
                                _ptr(all_scores), _ptr(ws), ws.numel(), _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_rank_binary")
+    return out_s, out_i
+
+
+def rank_sparse(rows, start, D, w, bias, k, ws, all_scores=None, out=None):
+    """rows: int32 words of the sparse-row store (padded to a multiple of 4), start (N+1,) int64 word offsets."""
+    a = _Args()
+    a.check(rows, "rows", torch.int32)
+    a.check(start, "start", torch.int64)
+    if start.dim() != 1 or start.numel() < 2 or rows.numel() % 4:
+        raise ValueError("start must be (N+1,) and rows a multiple of 4 words long")
+    N = start.numel() - 1
+    a.check(w, "w", torch.float32, numel=int(D))
+    a.rank_buffers(1, N, k, ws, all_scores, out)
+    dev = a.done()
+    out_s, out_i = out if out is not None else _outputs(1, k, dev)
+    rc = lib().otf_rank_sparse(_ptr(rows), _ptr(start), N, int(D), _ptr(w), float(bias), k, _ptr(out_s), _ptr(out_i),
+                               _ptr(all_scores), _ptr(ws), ws.numel(), _stream(dev))
+    if rc != OTF_OK:
+        raise OtfError(rc, "otf_rank_sparse")
     return out_s, out_i
 
 

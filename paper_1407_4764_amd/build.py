@@ -12,7 +12,7 @@ BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libotf.so")
 
 SOURCES = ["otf_api.hip", "otf_select.hip", "otf_dense.hip", "otf_table.hip", "otf_mfma.hip", "otf_sgd.hip", "otf_encode.hip",
-           "otf_pq_train.hip"]
+           "otf_pq_train.hip", "otf_sparse.hip"]
 # packed-fp32 instructions are switched off for every device translation unit
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-I" + INCLUDE, "-I" + CSRC, "-Wall", "-Wno-unused-function"]

@@ -467,6 +467,48 @@ int otf_rank_hamming(const uint32_t *bits, int64_t N, int32_t D, const uint32_t 
     return hip_status(e);
 }
 
+int otf_rank_sparse(const uint32_t *rows, const int64_t *start, int64_t N, int32_t D, const float *w, float bias,
+                    int32_t k, float *out_scores, int32_t *out_idx, float *all_scores, void *ws, size_t ws_bytes,
+                    void *stream) {
+    WsLayout L;
+    if (!rows || !start || !w || D < 1) return OTF_ERR_INVALID_ARG;
+    int rc = check_rank_common(N, k, 1, out_scores, out_idx, ws, ws_bytes, &L);
+    if (rc != OTF_OK) return rc;
+    if (D != 128) return OTF_ERR_UNSUPPORTED;
+    if (!aligned16(rows) || (reinterpret_cast<uintptr_t>(start) & 7u)) return OTF_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    SelectWs sw = select_ws(ws, L), ssw = sample_select_ws(ws, L);
+    uint8_t *wsb = reinterpret_cast<uint8_t *>(ws);
+    float *S = all_scores ? all_scores : reinterpret_cast<float *>(wsb + L.scores);
+    hipError_t e = launch_select_init_both(sw, ssw, 1, s);
+    if (e == hipSuccess && filter_eligible(N, k, all_scores)) {
+        float *sample = reinterpret_cast<float *>(wsb + L.sample_scores);
+        const int64_t Nv = sample_rows(N);
+        const int m = sample_rank(N, Nv);
+        e = launch_sparse_scan(rows, start, Nv, N, w, bias, kEmitSample, sample, ssw.st, ssw.hist1, m, nullptr, nullptr,
+                               nullptr, nullptr, s);
+        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, 0, nullptr, s);
+        ScanTimer timer(s);
+        if (e == hipSuccess)
+            e = launch_sparse_scan(rows, start, N, N, w, bias, kEmitFilter, nullptr, sw.st, nullptr, m, ssw.st, ssw.hist2,
+                                   sw.cand, nullptr, s);
+        timer.stop();
+        if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
+        if (e == hipSuccess)
+            e = launch_sparse_scan(rows, start, N, N, w, bias, kEmitScores, S, sw.st, sw.hist1, k, nullptr, nullptr,
+                                   nullptr, sw.st, s);
+        if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 1, s);
+        return hip_status(e);
+    }
+    ScanTimer timer(s);
+    if (e == hipSuccess)
+        e = launch_sparse_scan(rows, start, N, N, w, bias, kEmitScores, S, sw.st, sw.hist1, k, nullptr, nullptr, nullptr,
+                               nullptr, s);
+    timer.stop();
+    if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 0, s);
+    return hip_status(e);
+}
+
 size_t otf_sgd_workspace_bytes(int32_t B) {
     if (B < 1 || B > 4096) return 0;
     return (size_t)4096 * sizeof(float);

@@ -119,6 +119,12 @@ hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, Tab
                              const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
                              const SelState *gate, hipStream_t s);
 
+// Sparse-row store of 128-D features (mask + packed non-zero values per row, word offsets in start).
+hipError_t launch_sparse_scan(const uint32_t *rows, const int64_t *start, int64_t N, int64_t store_rows, const float *w,
+                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
+                              const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
+                              const SelState *gate, hipStream_t s);
+
 hipError_t launch_sgd_step(float *w, float *b, int D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,
                            int n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int n_neg,
                            float lambda, int64_t t, int update_bias, float *coef, hipStream_t s);

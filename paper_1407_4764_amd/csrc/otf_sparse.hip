@@ -1,0 +1,240 @@
+// Dense scoring of a sparse-row store of 128-D features.
+//
+// Paper Sec. 3.1 (discussion after Table 2): the ConvNet features are very sparse, the 128-D ones
+// typically over 60 % zeros, and a compression "geared to capitalise on this sparsity" is named
+// as a way to shrink the store further.  This store keeps, per row, a presence mask of 128 bits
+// and the non-zero fp32 values in ascending order of dimension, rows back to back:
+//
+//     row i = words [start[i], start[i+1]) of `rows`: 4 mask words (dimension d = bit d mod 32,
+//             least significant first, of word d div 32), then one word per set bit
+//
+// (~225 bytes per row at 60 % zeros against 512 dense).  The score is the dense one,
+// s_i = b + sum_d w_d x_{i,d}: the zeros simply never reach the chip.
+//
+// The stream has no fixed row length, so a wave reads it in fixed WINDOWS instead: 8 KiB (eight
+// 16-byte loads per lane) from the 16-byte boundary at or below the first row it has not scored;
+// the rows that lie completely inside the window (at most 64 of them, found from the offsets of
+// the next 64 rows with one vote) are scored, the next window starts at the first row that did
+// not fit.  A row that straddles a window's end is read twice, ~1.4 % of the stream.  The loads
+// of the next window are issued before the current one is scored, so 8 KiB per wave stay in
+// flight; twelve waves per compute unit hide the bubble at the start of a tile.
+//
+// Scoring a window: its bytes go from registers to a buffer in shared memory that only this wave
+// uses.  Four rows are scored at a time, 16 lanes per row, lane l owning dimensions 8 l .. 8 l + 7:
+// it takes its byte of the mask, learns from a prefix sum over the row's lanes (four data-parallel
+// moves) how many values precede its own, and reads one value per set bit.  All sums are fp32.
+//
+// Work distribution: tiles of 256 rows from a TileQueue (chunks of 1024 rows).
+#include <algorithm>
+
+#include "otf_internal.h"
+
+namespace otf {
+
+constexpr int kSparseD = 128;
+constexpr int kSparseMaskWords = kSparseD / 32;
+constexpr int kWinWords = 2048;                       // window: 8 loads x 64 lanes x 4 words
+constexpr int kWinBufWords = kWinWords + 8;           // + slack: a lane may read one word past its row's last value
+constexpr int kSparseTileRows = 256;
+constexpr int kSparseThreads = 256;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_shr_u32(uint32_t v) {      // row_shr within 16 lanes, zero shifted in
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+// What a scan emits, as in the table scans (ScanEmit): all scores + pass-1 histogram; the scores of
+// the strided sample (N = number of sample rows, numbered compactly); or only the rows at or above
+// the threshold, appended to the candidate list.
+template <int EMIT>
+__global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
+    const uint32_t *__restrict__ rows, const long long *__restrict__ start, long long N, long long store_rows,
+    const float *__restrict__ w, float bias, float *__restrict__ scores, SelState *st, uint32_t *hist1,
+    int sample_rank, const SelState *tau_state, const uint32_t *tau_hist2, unsigned long long *__restrict__ cand,
+    const SelState *gate) {
+    __shared__ __attribute__((aligned(16))) uint32_t win[kSparseThreads / 64][kWinBufWords];
+    __shared__ uint32_t lhist[kBins1];            // (the filtered scan resolves its threshold in here)
+    __shared__ uint32_t s_out[3];
+    __shared__ TileQueue s_queue;
+    if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
+    uint32_t *chunk_ctr = &st->chunk_ctr[EMIT == kEmitScores ? 1 : 0];
+    if (threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);
+    const long long total_tiles = (N + kSparseTileRows - 1) / kSparseTileRows;
+    const uint32_t chunk_tiles = tile_queue_chunk_tiles(total_tiles, 4u);
+    uint32_t tau = 0u;
+    if (EMIT == kEmitFilter) {
+        const BinChoice r2 = block_find_bin(tau_hist2, kBins2, tau_state->need1, lhist, s_out);
+        tau = ((tau_state->b1 << 12) | r2.bin) << 8;
+        if (filter_hopeless((uint32_t)sample_rank, tau_state->need1, r2)) return;   // uniform
+    } else {
+        for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l = lane & 15, rq = lane >> 4;      // dimensions 8 l .. 8 l + 7 of row rq of the four scored together
+    uint32_t *buf = win[wave];
+    float wl[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) wl[j] = w[8 * l + j];
+    // last 16-byte piece of the stream that may be read (the array is padded to whole pieces)
+    const long long last_piece = ((start[store_rows] + 3) / 4 - 1) * 4;
+
+    // 8 KiB of the stream from word a0 (a multiple of 4) into registers; pieces past the end re-read the last one
+    auto fetch = [&](u32x4 *d, long long a0) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            long long wa = a0 + (long long)u * 256 + (long long)lane * 4;
+            wa = wa < last_piece ? wa : last_piece;
+            d[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(rows + wa));
+        }
+    };
+    bool list_full = false;
+    // scores the nrows rows of a window that is in `d`; rel = this lane's row's first word inside the window
+    // (lane r holds it for row r), row0 = store row of the window's first row, v0 = its number in the output
+    auto score_window = [&](const u32x4 *d, uint32_t rel, int nrows, long long v0) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) *reinterpret_cast<u32x4 *>(buf + u * 256 + lane * 4) = d[u];
+        for (int r0 = 0; r0 < nrows; r0 += 4) {                     // uniform trip count
+            const int rl = r0 + rq;
+            const bool valid = rl < nrows;
+            uint32_t off = (uint32_t)__shfl((int)rel, rl & 63, 64);
+            off = valid ? off : 0u;
+            const uint32_t mw = buf[off + (uint32_t)(l >> 2)];
+            const uint32_t byte = (mw >> (8 * (l & 3))) & 0xFFu;
+            const uint32_t cnt = (uint32_t)__builtin_popcount(byte);
+            uint32_t incl = cnt;                                    // values up to and including this lane's, in the row
+            incl += dpp_shr_u32<0x111>(incl);                       // row_shr:1
+            incl += dpp_shr_u32<0x112>(incl);                       // row_shr:2
+            incl += dpp_shr_u32<0x114>(incl);                       // row_shr:4
+            incl += dpp_shr_u32<0x118>(incl);                       // row_shr:8
+            uint32_t at = off + (uint32_t)kSparseMaskWords + incl - cnt;
+            float acc = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool bit = (byte >> j) & 1u;
+                const float x = __uint_as_float(buf[at]);
+                acc = bit ? fmaf(wl[j], x, acc) : acc;
+                at += bit ? 1u : 0u;
+            }
+            acc += dpp_f32<0xB1>(acc);    // quad_perm [1,0,3,2]
+            acc += dpp_f32<0x4E>(acc);    // quad_perm [2,3,0,1]
+            acc += dpp_f32<0x141>(acc);   // row_half_mirror
+            acc += dpp_f32<0x140>(acc);   // row_mirror: every lane of the 16 holds the row's sum
+            if (valid && l == 0) {
+                const float sc = acc + bias;
+                const long long v = v0 + rl;
+                if (EMIT == kEmitFilter) {
+                    const uint32_t key = float_to_key(sc);
+                    if (key >= tau && !list_full) {
+                        const uint32_t pos = atomicAdd(&st->cursor, 1u);
+                        if (pos < (uint32_t)kCandCap)
+                            cand[pos] = ((unsigned long long)key << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)v);
+                        else
+                            list_full = true;
+                    }
+                } else {
+                    atomicAdd(&lhist[float_to_key(sc) >> 20], 1u);
+                    scores[v] = sc;
+                }
+            }
+        }
+        if (EMIT == kEmitFilter) list_full = __ballot(list_full) != 0ull;
+    };
+
+    for (;;) {
+        const long long tile = tile_queue_draw(&s_queue, chunk_ctr, chunk_tiles, total_tiles);
+        if (tile < 0) break;                                        // uniform per wave
+        // output rows [v, ve) of this tile are store rows [r, r + ve - v) (the sample: a piece of one group)
+        long long v = tile * kSparseTileRows;
+        const long long ve = v + kSparseTileRows < N ? v + kSparseTileRows : N;
+        long long r = EMIT == kEmitSample ? ((v >> 10) * ((long long)kSampleGroup * kSampleStride) + (v & 1023)) : v;
+        const long long re = r + (ve - v);
+        // a window: offsets of the next 64 rows (lane i: row r + i and the one behind it, both capped at
+        // the tile's end), how many of those rows fit, and where the window after it begins
+        struct Win {
+            long long a0;        // first word of the window (a multiple of 4)
+            uint32_t rel;        // lane i: first word of row r + i inside the window
+            int nrows;           // rows that lie completely inside it (>= 1)
+            long long next_a0;   // the window of the first row that did not fit
+        };
+        auto plan = [&](long long row, long long a0) {
+            const long long i0 = row + lane < re ? row + lane : re;
+            const long long i1 = row + lane + 1 < re ? row + lane + 1 : re;
+            const long long s0 = start[i0], s1 = start[i1];
+            Win p;
+            p.a0 = a0;
+            const bool fits = (row + lane < re) && (s1 - a0 <= (long long)kWinWords);
+            p.nrows = __builtin_popcountll(__ballot(fits));         // rows are consecutive: the fitting ones come first
+            p.rel = (uint32_t)(s0 - a0);
+            const long long nxt = __shfl(s1, (p.nrows - 1) & 63, 64);   // = start[row + nrows]
+            p.next_a0 = nxt & ~3LL;
+            return p;
+        };
+        auto first_word = [&](long long row) {                      // window start of `row`, the same in every lane
+            const long long s0 = start[row];
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)s0);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(s0 >> 32));
+            return (long long)(((unsigned long long)hi << 32) | lo) & ~3LL;
+        };
+        u32x4 b0[8], b1[8];
+        Win cur = plan(r, first_word(r));
+        fetch(b0, cur.a0);
+        for (;;) {
+            // b0 holds (or is receiving) window `cur`; order the one after it, then score cur
+            const bool more0 = r + cur.nrows < re;
+            Win nxt = cur;
+            if (more0) nxt = plan(r + cur.nrows, cur.next_a0);      // uniform
+            fetch(b1, more0 ? nxt.a0 : cur.a0);
+            score_window(b0, cur.rel, cur.nrows, v);
+            if (!more0) break;
+            v += cur.nrows;
+            r += cur.nrows;
+            const bool more1 = r + nxt.nrows < re;
+            cur = nxt;
+            if (more1) cur = plan(r + nxt.nrows, nxt.next_a0);
+            fetch(b0, more1 ? cur.a0 : nxt.a0);
+            score_window(b1, nxt.rel, nxt.nrows, v);
+            if (!more1) break;
+            v += nxt.nrows;
+            r += nxt.nrows;
+        }
+    }
+    if (EMIT != kEmitFilter) merge_hist1(lhist, hist1);
+}
+
+template <int EMIT>
+static hipError_t launch_sparse_cfg(const uint32_t *rows, const int64_t *start, int64_t N, int64_t store_rows,
+                                    const float *w, float bias, float *scores, SelState *st, uint32_t *hist1, int k,
+                                    const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
+                                    const SelState *gate, hipStream_t s) {
+    const int64_t tiles = (N + kSparseTileRows - 1) / kSparseTileRows;
+    const int grid = (int)std::min<int64_t>((tiles + 3) / 4, (int64_t)device_cu_count() * 3);
+    sparse_scan_kernel<EMIT><<<grid < 1 ? 1 : grid, kSparseThreads, 0, s>>>(
+        rows, reinterpret_cast<const long long *>(start), (long long)N, (long long)store_rows, w, bias, scores, st, hist1,
+        k, tau, tau_hist2, cand, gate);
+    return hipGetLastError();
+}
+
+// N = rows to score (kEmitSample: the sample rows, compact numbering); store_rows = rows of the store.
+hipError_t launch_sparse_scan(const uint32_t *rows, const int64_t *start, int64_t N, int64_t store_rows, const float *w,
+                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
+                              const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
+                              const SelState *gate, hipStream_t s) {
+    switch (emit) {
+        case kEmitScores:
+            return launch_sparse_cfg<kEmitScores>(rows, start, N, store_rows, w, bias, scores, st, hist1, k, tau, tau_hist2, cand, gate, s);
+        case kEmitSample:
+            return launch_sparse_cfg<kEmitSample>(rows, start, N, store_rows, w, bias, scores, st, hist1, k, tau, tau_hist2, cand, gate, s);
+        default:
+            return launch_sparse_cfg<kEmitFilter>(rows, start, N, store_rows, w, bias, scores, st, hist1, k, tau, tau_hist2, cand, gate, s);
+    }
+}
+
+}  // namespace otf

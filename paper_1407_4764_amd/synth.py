@@ -41,6 +41,51 @@ def dense_features(N, D, seed, device="cpu", dtype=torch.float32, chunk_rows=655
     return out
 
 
+def sparse_features(N, D, seed, device="cpu", zero_fraction=0.6, chunk_rows=65536):
+    """Dense features with most entries exactly zero, as the paper reports for its 128-D ConvNet
+    features (Sec. 3.1: "over 60 % zeros"): |N(0,1)| entries, each zeroed with probability
+    zero_fraction, then every row scaled to unit L2 norm (an all-zero row stays zero)."""
+    g = _gen(seed, device)
+    out = torch.empty((N, D), dtype=torch.float32, device=device)
+    for r0 in range(0, N, chunk_rows):
+        r1 = min(N, r0 + chunk_rows)
+        x = torch.randn((r1 - r0, D), generator=g, device=device, dtype=torch.float32).abs_()
+        x *= (torch.rand((r1 - r0, D), generator=g, device=device) >= zero_fraction)
+        x /= x.norm(dim=1, keepdim=True).clamp_min_(1e-30)
+        out[r0:r1] = x
+    return out
+
+
+def sparse_rows_from_dense(X, chunk_rows=1 << 18):
+    """The sparse-row store of a dense matrix (storage format only, no arithmetic): for row i, D/32
+    presence-mask words (dimension d = bit d mod 32, least significant first, of word d div 32, set
+    iff X[i][d] != 0) followed by the bit patterns of its non-zero values in ascending order of
+    dimension.  Returns (rows int32 words, start int64 [N+1] word offsets); the word array is padded
+    to a multiple of 4 words (16 bytes)."""
+    N, D = X.shape
+    assert D % 32 == 0
+    wm = D // 32
+    dev = X.device
+    nnz = (X != 0).sum(dim=1, dtype=torch.int64)
+    start = torch.zeros(N + 1, dtype=torch.int64, device=dev)
+    start[1:] = torch.cumsum(nnz + wm, dim=0)
+    total = int(start[-1].item())
+    rows = torch.zeros((total + 3) // 4 * 4, dtype=torch.int32, device=dev)
+    weights = (torch.ones(32, dtype=torch.int64, device=dev) << torch.arange(32, device=dev, dtype=torch.int64))
+    for r0 in range(0, N, chunk_rows):
+        r1 = min(N, r0 + chunk_rows)
+        x = X[r0:r1]
+        nz = x != 0
+        words = (nz.reshape(r1 - r0, wm, 32).to(torch.int64) * weights).sum(dim=2)            # 0 .. 2^32 - 1
+        words = torch.where(words >= 2 ** 31, words - 2 ** 32, words).to(torch.int32)       # the same 32 bits
+        pos = start[r0:r1, None] + torch.arange(wm, device=dev, dtype=torch.int64)[None, :]
+        rows[pos.reshape(-1)] = words.reshape(-1)
+        rank = torch.cumsum(nz.to(torch.int64), dim=1) - 1                                   # rank of a non-zero in its row
+        vpos = (start[r0:r1, None] + wm + rank)[nz]
+        rows[vpos] = x[nz].view(torch.int32)
+    return rows, start
+
+
 def normal_vector(n, sigma, seed, device="cpu", dtype=torch.float32):
     g = _gen(seed, device)
     return (torch.randn(n, generator=g, device=device, dtype=torch.float32) * sigma).to(dtype)

@@ -127,6 +127,15 @@ def test_pq_and_binary_argument_errors(L):
     assert ham(D=16384) == binding.OTF_ERR_UNSUPPORTED
     assert ham(k=1001) == binding.OTF_ERR_INVALID_ARG
     assert ham(wsb=0) == binding.OTF_ERR_WORKSPACE
+
+    def sparse(rows=FAKE, start=FAKE, N=1000, D=128, w=FAKE, k=10, wsb=BIG):
+        return L.otf_rank_sparse(rows, start, N, D, w, 0.0, k, FAKE, FAKE, None, FAKE, wsb, None)
+    assert sparse(rows=None) == binding.OTF_ERR_INVALID_ARG
+    assert sparse(start=None) == binding.OTF_ERR_INVALID_ARG
+    assert sparse(rows=FAKE + 4) == binding.OTF_ERR_INVALID_ARG
+    assert sparse(D=2048) == binding.OTF_ERR_UNSUPPORTED
+    assert sparse(k=0) == binding.OTF_ERR_INVALID_ARG
+    assert sparse(wsb=0) == binding.OTF_ERR_WORKSPACE
     assert L.otf_pq_build_lut(None, 1, 1, 1, FAKE, FAKE, None) == binding.OTF_ERR_INVALID_ARG
     assert L.otf_pq_build_lut(FAKE, 0, 1, 1, FAKE, FAKE, None) == binding.OTF_ERR_INVALID_ARG
 

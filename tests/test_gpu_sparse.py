@@ -1,0 +1,98 @@
+"""GPU parity of the sparse-row store (paper Sec. 3.1, discussion after Table 2: the 128-D ConvNet
+features are over 60 % zeros) with the CPU oracle: the oracle expands the store back into dense
+rows (its own reading of the format) and scores them with the dense definition."""
+import numpy as np
+import pytest
+import torch
+
+from paper_1407_4764_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+SEED = synth.BASE_SEED + 12000
+RTOL = 1e-4
+
+
+def _oracle_scores(oracle, rows, start, D, w, bias):
+    words = synth.as_uint32(rows.numpy())
+    st = start.numpy()
+    N = st.size - 1
+    wm = D // 32
+    idx = st[:-1, None] + np.arange(wm)[None, :]
+    mask = words[idx]
+    nnz = st[1:] - st[:-1] - wm
+    vstart = np.concatenate([[0], np.cumsum(nnz)]).astype(np.int64)
+    is_value = np.ones(st[-1], dtype=bool)
+    is_value[idx.reshape(-1)] = False
+    values = words[:st[-1]][is_value].view(np.float32)
+    X = oracle.sparse_expand(mask, values, vstart, D)
+    return oracle.dense_scores(X, w, [bias])[0], X
+
+
+def _check(oracle, X, k, bias=0.125, exact=False):
+    N, D = X.shape
+    rows, start = synth.sparse_rows_from_dense(X)
+    w = synth.normal_vector(D, 1.0, SEED + 1)
+    if exact:
+        w = torch.round(w * 8)
+    ref, Xback = _oracle_scores(oracle, rows, start, D, w.numpy(), bias)
+    np.testing.assert_array_equal(Xback, X.numpy())
+    ws = binding.make_workspace(N, k)
+    all_scores = torch.empty(N, dtype=torch.float32, device=DEV)
+    rd, sd, wd = rows.to(DEV), start.to(DEV), w.to(DEV)
+    val, idx = binding.rank_sparse(rd, sd, D, wd, bias, k, ws, all_scores=all_scores)
+    torch.cuda.synchronize()
+    got = all_scores.cpu().numpy().astype(np.float64)
+    if exact:
+        np.testing.assert_array_equal(got, ref)
+    else:
+        tol = oracle.score_tolerance(ref, RTOL)
+        bad = np.nonzero(np.abs(got - ref) > tol)[0]
+        assert bad.size == 0, "%d scores off, first row %d: %r vs %r" % (bad.size, bad[0], got[bad[0]], ref[bad[0]])
+    ok, msg = oracle.topk_parity_ok(ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), RTOL)
+    assert ok, msg
+    oi, ov = oracle.topk(got, k)                               # exactly the first k of a full sort of its own scores
+    np.testing.assert_array_equal(idx[0].cpu().numpy(), oi)
+    val2, idx2 = binding.rank_sparse(rd, sd, D, wd, bias, k, ws)   # no score output: the filtered route if large
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(val, val2)
+    return ws
+
+
+@pytest.mark.parametrize("N,k", [(1, 1), (3, 2), (63, 10), (64, 64), (257, 50), (5000, 100), (70001, 1000)])
+def test_sparse_rows_match_the_dense_definition(oracle, N, k):
+    _check(oracle, synth.sparse_features(N, 128, SEED + N), k)
+
+
+def test_every_row_scored_once_on_integer_data(oracle):
+    """Small integers: every fp32 sum is exact, so a row scored from the wrong window, a value paired
+    with the wrong dimension or a row scored twice shows as a non-zero difference.  Row lengths
+    vary from empty to full, so windows end in every possible way; more than a million rows, so
+    every wave draws several tiles and the second call takes the filtered route."""
+    N = 256 * 4100 + 77
+    g = torch.Generator().manual_seed(SEED + 2)
+    X = torch.randint(-8, 9, (N, 128), generator=g).to(torch.float32)
+    keep = torch.rand((N, 1), generator=g)                      # per-row density from 0 to 1
+    X *= (torch.rand((N, 128), generator=g) < keep)
+    X[5] = 0.0
+    X[6] = 3.0
+    X[N - 1] = -2.0
+    ws = _check(oracle, X, 100, bias=2.0, exact=True)
+
+
+def test_extreme_rows(oracle):
+    """All rows empty (16 bytes each, 512 rows per window's worth of bytes but at most 64 scored per
+    window), all rows full (no row shares a window with more than 15 others), and a mix."""
+    N = 3000
+    w_rows = torch.zeros((N, 128))
+    _check(oracle, w_rows, 10)
+    _check(oracle, synth.dense_features(N, 128, SEED + 3), 10)
+    X = synth.sparse_features(N, 128, SEED + 4, zero_fraction=0.9)
+    X[::7] = synth.dense_features((N + 6) // 7, 128, SEED + 5)
+    _check(oracle, X, 30)
+
+
+def test_large_store_filtered_route(oracle):
+    N, k = 1300000, 1000
+    ws = _check(oracle, synth.sparse_features(N, 128, SEED + 6), k, bias=0.0)
+    assert not binding.debug_fallback_taken(ws)

@@ -255,6 +255,24 @@ def test_sparse_expand_inverts_compression_of_a_dense_matrix(oracle):
                              np.array([0, 1], dtype=np.int64), D)
 
 
+def test_sparse_store_generator_round_trips_through_the_oracle(oracle):
+    """The store the tests and the benchmark feed the GPU is what the oracle expands back to the dense
+    matrix it was made from; and scoring the expansion is scoring the dense matrix."""
+    X = synth.sparse_features(300, 128, seed=77)
+    assert 0.55 < float((X == 0).float().mean()) < 0.65
+    X[7] = 0.0
+    rows, start = synth.sparse_rows_from_dense(X)
+    words = synth.as_uint32(rows.numpy())
+    st = start.numpy()
+    mask = np.stack([words[st[i]:st[i] + 4] for i in range(300)])
+    values = np.concatenate([words[st[i] + 4:st[i + 1]] for i in range(300)]).view(np.float32)
+    vstart = np.concatenate([[0], np.cumsum(st[1:] - st[:-1] - 4)]).astype(np.int64)
+    back = oracle.sparse_expand(mask, values, vstart, 128)
+    np.testing.assert_array_equal(back, X.numpy())
+    w = RNG.standard_normal(128).astype(np.float32)
+    np.testing.assert_array_equal(oracle.dense_scores(back, w, [0.25]), oracle.dense_scores(X.numpy(), w, [0.25]))
+
+
 def test_sign_convention_zero_is_bit_zero():
     import torch
     f = torch.tensor([[0.0, -0.0, 1e-30, -1e-30] + [0.0] * 28])
