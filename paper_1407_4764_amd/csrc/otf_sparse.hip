@@ -20,9 +20,15 @@
 // flight; twelve waves per compute unit hide the bubble at the start of a tile.
 //
 // Scoring a window: its bytes go from registers to a buffer in shared memory that only this wave
-// uses.  Four rows are scored at a time, 16 lanes per row, lane l owning dimensions 8 l .. 8 l + 7:
-// it takes its byte of the mask, learns from a prefix sum over the row's lanes (four data-parallel
-// moves) how many values precede its own, and reads one value per set bit.  All sums are fp32.
+// uses.  Eight rows are scored at a time, 8 lanes per row, lane l owning dimensions 16 l .. 16 l + 15:
+// it takes its 16 bits of the mask, learns from a prefix sum over the row's lanes (three
+// data-parallel moves) how many values precede its own, and reads one value per dimension (a
+// cleared bit re-reads the next value and masks it out).  All sums are fp32.
+//
+// The row offsets a wave needs (64 rows ahead of its position) live in its registers: three
+// registers hold start[] for 192 consecutive rows, lane by lane; a window's offsets come out of
+// them with lane shuffles, and the third register is refilled from memory a window or more before
+// its contents are needed, so no load of an offset ever stands between two windows.
 //
 // Work distribution: tiles of 256 rows from a TileQueue (chunks of 1024 rows).
 #include <algorithm>
@@ -78,11 +84,11 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
     __syncthreads();
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int l = lane & 15, rq = lane >> 4;      // dimensions 8 l .. 8 l + 7 of row rq of the four scored together
+    const int l = lane & 7, rq = lane >> 3;       // dimensions 16 l .. 16 l + 15 of row rq of the eight scored together
     uint32_t *buf = win[wave];
-    float wl[8];
+    float wl[16];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) wl[j] = w[8 * l + j];
+    for (int j = 0; j < 16; ++j) wl[j] = w[16 * l + j];
     // last 16-byte piece of the stream that may be read (the array is padded to whole pieces)
     const long long last_piece = ((start[store_rows] + 3) / 4 - 1) * 4;
 
@@ -96,37 +102,40 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
         }
     };
     bool list_full = false;
-    // scores the nrows rows of a window that is in `d`; rel = this lane's row's first word inside the window
-    // (lane r holds it for row r), row0 = store row of the window's first row, v0 = its number in the output
+    // scores the nrows rows of a window that is in `d`; rel = first word of this lane's row inside the window
+    // (lane r holds it for row r); v0 = number of the window's first row in the output
     auto score_window = [&](const u32x4 *d, uint32_t rel, int nrows, long long v0) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) *reinterpret_cast<u32x4 *>(buf + u * 256 + lane * 4) = d[u];
-        for (int r0 = 0; r0 < nrows; r0 += 4) {                     // uniform trip count
+        for (int r0 = 0; r0 < nrows; r0 += 8) {                     // uniform trip count
             const int rl = r0 + rq;
             const bool valid = rl < nrows;
             uint32_t off = (uint32_t)__shfl((int)rel, rl & 63, 64);
             off = valid ? off : 0u;
-            const uint32_t mw = buf[off + (uint32_t)(l >> 2)];
-            const uint32_t byte = (mw >> (8 * (l & 3))) & 0xFFu;
-            const uint32_t cnt = (uint32_t)__builtin_popcount(byte);
+            const uint32_t mw = buf[off + (uint32_t)(l >> 1)];
+            const uint32_t bits16 = (mw >> (16 * (l & 1))) & 0xFFFFu;
+            const uint32_t cnt = (uint32_t)__builtin_popcount(bits16);
             uint32_t incl = cnt;                                    // values up to and including this lane's, in the row
-            incl += dpp_shr_u32<0x111>(incl);                       // row_shr:1
-            incl += dpp_shr_u32<0x112>(incl);                       // row_shr:2
-            incl += dpp_shr_u32<0x114>(incl);                       // row_shr:4
-            incl += dpp_shr_u32<0x118>(incl);                       // row_shr:8
+            uint32_t t = dpp_shr_u32<0x111>(incl);                  // row_shr:1 (a row of 16 lanes holds two rows of 8:
+            incl += l >= 1 ? t : 0u;                                //  what comes from the other one is dropped)
+            t = dpp_shr_u32<0x112>(incl);                           // row_shr:2
+            incl += l >= 2 ? t : 0u;
+            t = dpp_shr_u32<0x114>(incl);                           // row_shr:4
+            incl += l >= 4 ? t : 0u;
             uint32_t at = off + (uint32_t)kSparseMaskWords + incl - cnt;
-            float acc = 0.f;
+            float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const bool bit = (byte >> j) & 1u;
-                const float x = __uint_as_float(buf[at]);
-                acc = bit ? fmaf(wl[j], x, acc) : acc;
-                at += bit ? 1u : 0u;
+            for (int j = 0; j < 16; ++j) {
+                const int m = __builtin_amdgcn_sbfe((int)bits16, j, 1);   // 0, or -1 when dimension 16 l + j is stored
+                const float x = __uint_as_float(buf[at] & (uint32_t)m);
+                if (j & 1) acc1 = fmaf(wl[j], x, acc1);
+                else acc0 = fmaf(wl[j], x, acc0);
+                at -= (uint32_t)m;
             }
+            float acc = acc0 + acc1;
             acc += dpp_f32<0xB1>(acc);    // quad_perm [1,0,3,2]
             acc += dpp_f32<0x4E>(acc);    // quad_perm [2,3,0,1]
-            acc += dpp_f32<0x141>(acc);   // row_half_mirror
-            acc += dpp_f32<0x140>(acc);   // row_mirror: every lane of the 16 holds the row's sum
+            acc += dpp_f32<0x141>(acc);   // row_half_mirror: every lane of the 8 holds the row's sum
             if (valid && l == 0) {
                 const float sc = acc + bias;
                 const long long v = v0 + rl;
@@ -156,18 +165,38 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
         const long long ve = v + kSparseTileRows < N ? v + kSparseTileRows : N;
         long long r = EMIT == kEmitSample ? ((v >> 10) * ((long long)kSampleGroup * kSampleStride) + (v & 1023)) : v;
         const long long re = r + (ve - v);
-        // a window: offsets of the next 64 rows (lane i: row r + i and the one behind it, both capped at
-        // the tile's end), how many of those rows fit, and where the window after it begins
+        // start[] of rows rb + lane, rb + 64 + lane, rb + 128 + lane (capped at the tile's end, whose
+        // offset closes its last row)
+        long long rb = r;
+        auto load_starts = [&](long long first) {
+            const long long i = first + lane < re ? first + lane : re;
+            return start[i];
+        };
+        long long S0 = load_starts(rb), S1 = load_starts(rb + 64), S2 = load_starts(rb + 128);
+        // start[row + i] for lane i (i = 0..63) and one row further, rb <= row < rb + 64
+        auto offsets_from = [&](long long row, long long *s0, long long *s1) {
+            const int i0 = (int)(row - rb) + lane, i1 = i0 + 1;
+            const long long a = __shfl(S0, i0 & 63, 64), b = __shfl(S1, i0 & 63, 64);
+            const long long c = __shfl(S0, i1 & 63, 64), d2 = __shfl(S1, i1 & 63, 64);
+            *s0 = i0 < 64 ? a : b;
+            *s1 = i1 < 64 ? c : d2;
+        };
+        // a window: which rows fit, where each begins inside it, and where the window after it begins
         struct Win {
             long long a0;        // first word of the window (a multiple of 4)
-            uint32_t rel;        // lane i: first word of row r + i inside the window
+            uint32_t rel;        // lane i: first word of row (window's first row + i) inside the window
             int nrows;           // rows that lie completely inside it (>= 1)
             long long next_a0;   // the window of the first row that did not fit
         };
         auto plan = [&](long long row, long long a0) {
-            const long long i0 = row + lane < re ? row + lane : re;
-            const long long i1 = row + lane + 1 < re ? row + lane + 1 : re;
-            const long long s0 = start[i0], s1 = start[i1];
+            if (row - rb >= 64) {                                   // uniform: the registers move on by 64 rows
+                rb += 64;
+                S0 = S1;
+                S1 = S2;
+                S2 = load_starts(rb + 128);                         // needed a window from now at the earliest
+            }
+            long long s0, s1;
+            offsets_from(row, &s0, &s1);
             Win p;
             p.a0 = a0;
             const bool fits = (row + lane < re) && (s1 - a0 <= (long long)kWinWords);
@@ -177,14 +206,9 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
             p.next_a0 = nxt & ~3LL;
             return p;
         };
-        auto first_word = [&](long long row) {                      // window start of `row`, the same in every lane
-            const long long s0 = start[row];
-            const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)s0);
-            const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(s0 >> 32));
-            return (long long)(((unsigned long long)hi << 32) | lo) & ~3LL;
-        };
         u32x4 b0[8], b1[8];
-        Win cur = plan(r, first_word(r));
+        const long long first_a0 = __shfl(S0, 0, 64) & ~3LL;
+        Win cur = plan(r, first_a0);
         fetch(b0, cur.a0);
         for (;;) {
             // b0 holds (or is receiving) window `cur`; order the one after it, then score cur
