@@ -3,6 +3,7 @@
 // enqueued nothing and written nothing.
 #include "otf.h"
 
+#include <algorithm>
 #include <atomic>
 #include <vector>
 
@@ -33,7 +34,8 @@ WsLayout ws_layout(int64_t N, int32_t Q) {
     L.sample_hist1 = take((size_t)Q * kHist1Words * 4);
     L.sample_hist2 = take((size_t)Q * kBins2 * 4);
     L.sample_ld = padded_rows(sample_rows(N) + kSampleGroup);
-    L.sample_scores = take((size_t)Q * (size_t)L.sample_ld * 4);
+    // (the single-classifier scans keep one 8-byte slot per wave of the sample scan here instead: at most 4096)
+    L.sample_scores = take(std::max<size_t>((size_t)Q * (size_t)L.sample_ld * 4, (size_t)kMaxSampleSlots * sizeof(SampleSlot)));
     L.lut_image = take(kLutImageBytes);
     L.short_store = take(kShortStoreBytes);
     L.scores = take((size_t)Q * (size_t)padded_rows(N) * 4);
@@ -263,23 +265,21 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
         // Short rows, one classifier: sample -> threshold -> filtered scan -> sort, with the full
         // selection behind a gate, as for the table scans.
         SelectWs ssw = sample_select_ws(ws, L);
-        float *sample = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + L.sample_scores);
+        SampleSlot *slots = reinterpret_cast<SampleSlot *>(reinterpret_cast<uint8_t *>(ws) + L.sample_scores);
         const int64_t Nv = sample_rows(N);
-        const int m = sample_rank(N, Nv);
         hipError_t e = launch_select_init_both(sw, ssw, 1, s);
         if (e == hipSuccess)
-            e = launch_dense_scan_emit(X, x_half, Nv, D, ldx, W, w_half, bias, 0, kEmitSample, sample, ssw.hist1,
-                                       &ssw.st[0].chunk_ctr[0], ssw.st, nullptr, nullptr, 0, nullptr, nullptr, s);
-        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, 0, nullptr, s);
+            e = launch_dense_scan_emit(X, x_half, Nv, D, ldx, W, w_half, bias, 0, kEmitSample, nullptr, nullptr,
+                                       &ssw.st[0].chunk_ctr[0], ssw.st, nullptr, slots, nullptr, nullptr, s);
         ScanTimer timer(s);
         if (e == hipSuccess)
             e = launch_dense_scan_emit(X, x_half, N, D, ldx, W, w_half, bias, 0, kEmitFilter, nullptr, nullptr,
-                                       &sw.st[0].chunk_ctr[0], sw.st, ssw.st, ssw.hist2, m, sw.cand, nullptr, s);
+                                       &sw.st[0].chunk_ctr[0], sw.st, ssw.st, slots, sw.cand, nullptr, s);
         timer.stop();
         if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
         if (e == hipSuccess)
             e = launch_dense_scan_emit(X, x_half, N, D, ldx, W, w_half, bias, 0, kEmitScores, S, sw.hist1,
-                                       &sw.st[0].chunk_ctr[1], sw.st, nullptr, nullptr, 0, nullptr, sw.st, s);
+                                       &sw.st[0].chunk_ctr[1], sw.st, nullptr, nullptr, nullptr, sw.st, s);
         if (e == hipSuccess) e = launch_select_tail(S, N, ldS, 1, k, sw, out_scores, out_idx, 1, s);
         return hip_status(e);
     }
@@ -377,27 +377,24 @@ static hipError_t rank_table(const uint8_t *codes, int64_t N, int row_bytes, Tab
     }
     if (filter_eligible(N, k, all_scores)) {
         SelectWs ssw = sample_select_ws(ws, L);
-        float *sample = reinterpret_cast<float *>(wsb + L.sample_scores);
-        const int64_t Nv = sample_rows(N);
-        const int m = sample_rank(N, Nv);
-        e = launch_table_scan(codes, Nv, row_bytes, kind, image, bias, kEmitSample, sample, ssw.st, ssw.hist1, m,
-                              nullptr, nullptr, nullptr, nullptr, s);
-        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, 0, nullptr, s);
+        SampleSlot *slots = reinterpret_cast<SampleSlot *>(wsb + L.sample_scores);
+        e = launch_table_scan(codes, sample_rows(N), row_bytes, kind, image, bias, kEmitSample, nullptr, ssw.st, nullptr,
+                              nullptr, slots, nullptr, nullptr, s);
         ScanTimer timer(s);
         if (e == hipSuccess)
-            e = launch_table_scan(codes, N, row_bytes, kind, image, bias, kEmitFilter, nullptr, sw.st, nullptr, m,
-                                  ssw.st, ssw.hist2, sw.cand, nullptr, s);
+            e = launch_table_scan(codes, N, row_bytes, kind, image, bias, kEmitFilter, nullptr, sw.st, nullptr, ssw.st,
+                                  slots, sw.cand, nullptr, s);
         timer.stop();
         if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
         if (e == hipSuccess)
-            e = launch_table_scan(codes, N, row_bytes, kind, image, bias, kEmitScores, S, sw.st, sw.hist1, k,
-                                  nullptr, nullptr, nullptr, sw.st, s);
+            e = launch_table_scan(codes, N, row_bytes, kind, image, bias, kEmitScores, S, sw.st, sw.hist1, nullptr,
+                                  nullptr, nullptr, sw.st, s);
         if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 1, s);
         return e;
     }
     ScanTimer timer(s);
-    e = launch_table_scan(codes, N, row_bytes, kind, image, bias, kEmitScores, S, sw.st, sw.hist1, k, nullptr,
-                          nullptr, nullptr, nullptr, s);
+    e = launch_table_scan(codes, N, row_bytes, kind, image, bias, kEmitScores, S, sw.st, sw.hist1, nullptr, nullptr,
+                          nullptr, nullptr, s);
     timer.stop();
     if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 0, s);
     return e;
@@ -482,27 +479,24 @@ int otf_rank_sparse(const uint32_t *rows, const int64_t *start, int64_t N, int32
     float *S = all_scores ? all_scores : reinterpret_cast<float *>(wsb + L.scores);
     hipError_t e = launch_select_init_both(sw, ssw, 1, s);
     if (e == hipSuccess && filter_eligible(N, k, all_scores)) {
-        float *sample = reinterpret_cast<float *>(wsb + L.sample_scores);
-        const int64_t Nv = sample_rows(N);
-        const int m = sample_rank(N, Nv);
-        e = launch_sparse_scan(rows, start, Nv, N, w, bias, kEmitSample, sample, ssw.st, ssw.hist1, m, nullptr, nullptr,
-                               nullptr, nullptr, s);
-        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, 1, m, ssw, 0, nullptr, s);
+        SampleSlot *slots = reinterpret_cast<SampleSlot *>(wsb + L.sample_scores);
+        e = launch_sparse_scan(rows, start, sample_rows(N), N, w, bias, kEmitSample, nullptr, ssw.st, nullptr, nullptr,
+                               slots, nullptr, nullptr, s);
         ScanTimer timer(s);
         if (e == hipSuccess)
-            e = launch_sparse_scan(rows, start, N, N, w, bias, kEmitFilter, nullptr, sw.st, nullptr, m, ssw.st, ssw.hist2,
+            e = launch_sparse_scan(rows, start, N, N, w, bias, kEmitFilter, nullptr, sw.st, nullptr, ssw.st, slots,
                                    sw.cand, nullptr, s);
         timer.stop();
         if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
         if (e == hipSuccess)
-            e = launch_sparse_scan(rows, start, N, N, w, bias, kEmitScores, S, sw.st, sw.hist1, k, nullptr, nullptr,
-                                   nullptr, sw.st, s);
+            e = launch_sparse_scan(rows, start, N, N, w, bias, kEmitScores, S, sw.st, sw.hist1, nullptr, nullptr, nullptr,
+                                   sw.st, s);
         if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 1, s);
         return hip_status(e);
     }
     ScanTimer timer(s);
     if (e == hipSuccess)
-        e = launch_sparse_scan(rows, start, N, N, w, bias, kEmitScores, S, sw.st, sw.hist1, k, nullptr, nullptr, nullptr,
+        e = launch_sparse_scan(rows, start, N, N, w, bias, kEmitScores, S, sw.st, sw.hist1, nullptr, nullptr, nullptr,
                                nullptr, s);
     timer.stop();
     if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 0, s);

@@ -231,8 +231,8 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
                                                            int w_is_half, const float *__restrict__ bias_ptr, int bias_index,
                                                            float *__restrict__ scores, uint32_t *hist1,
                                                            uint32_t *chunk_ctr, SelState *st,
-                                                           const SelState *tau_state, const uint32_t *tau_hist2,
-                                                           int sample_rank, unsigned long long *__restrict__ cand,
+                                                           const SelState *tau_state, SampleSlot *sample_slots,
+                                                           unsigned long long *__restrict__ cand,
                                                            const SelState *gate) {
     constexpr int E = Elem<XHALF>::kPer16;
     constexpr int RPW = 64 / LPR;   // rows per wave load
@@ -247,14 +247,15 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
     if (threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);   // visible after the barriers below
     uint32_t tau = 0u;
     if (EMIT == kEmitFilter) {
-        // top 24 bits of the sample key of the requested rank, resolved by every workgroup for itself
-        const BinChoice r2 = block_find_bin(tau_hist2, kBins2, tau_state->need1, lhist, s_out);
-        tau = ((tau_state->b1 << 12) | r2.bin) << 8;
-        if (filter_hopeless((uint32_t)sample_rank, tau_state->need1, r2)) return;   // uniform
+        // the threshold from the wave maxima the sample scan left, resolved by every workgroup for itself
+        const TauChoice tc = resolve_tau_slots(sample_slots, tau_state, N, lhist, s_out);
+        if (tc.hopeless) return;                  // uniform
+        tau = tc.tau;
     } else {
         for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
         __syncthreads();
     }
+    uint32_t smx = 0u, scnt = 0u;                 // sample scan: this lane's largest key and its multiplicity
 
     const float bias = bias_ptr ? bias_ptr[bias_index] : 0.f;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -310,7 +311,9 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
             const bool ok = owner && row < nrows;
             const float sc = v[k] + bias;
             const uint32_t key = float_to_key(sc);
-            if (EMIT == kEmitFilter) {
+            if (EMIT == kEmitSample) {
+                if (ok) sample_note(smx, scnt, key);
+            } else if (EMIT == kEmitFilter) {
                 if (ok && key >= tau && !list_full) {
                     const uint32_t pos = atomicAdd(&st->cursor, 1u);
                     if (pos < (uint32_t)kCandCap)
@@ -352,7 +355,8 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
         }
         consume(c, ntiles, N);
     }
-    if (EMIT != kEmitFilter) merge_hist1(lhist, hist1);
+    if (EMIT == kEmitScores) merge_hist1(lhist, hist1);
+    if (EMIT == kEmitSample) sample_store(sample_slots, st, smx, scnt);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -411,8 +415,7 @@ struct NarrowExtra {
     ScanEmit emit;
     SelState *st;
     const SelState *tau;
-    const uint32_t *tau_hist2;
-    int sample_rank;
+    SampleSlot *slots;
     unsigned long long *cand;
     const SelState *gate;
 };
@@ -434,20 +437,18 @@ static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t
         int64_t waves = (N + rows_per_wave_iter - 1) / rows_per_wave_iter;
         grid = (int)std::min<int64_t>((waves + 3) / 4, (int64_t)cus * tune_int(OTF_DEBUG_NARROW_BLOCKS_PER_CU, 2));
         if (grid < 1) grid = 1;
-        // the short sample scan ends in every workgroup adding to the same hundred-odd bins of the
-        // global histogram at once: one workgroup per compute unit halves that queue (20.6 -> 16.7 us)
-        if (x.emit == kEmitSample) grid = std::min(grid, cus);
+        if (x.emit == kEmitSample) grid = std::min(grid, cus);       // (one slot per wave: at most 4 x 256 slots)
 #define OTF_NARROW(L)                                                                                              \
     do {                                                                                                           \
         if (x.emit == kEmitScores)                                                                                 \
-            dense_narrow_kernel<XHALF, L, kEmitScores><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS, x.st, x.tau, x.tau_hist2, \
-                                                                             x.sample_rank, x.cand, x.gate);                      \
+            dense_narrow_kernel<XHALF, L, kEmitScores><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS, x.st, x.tau, x.slots,     \
+                                                                             x.cand, x.gate);                                     \
         else if (x.emit == kEmitSample)                                                                            \
-            dense_narrow_kernel<XHALF, L, kEmitSample><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS, x.st, x.tau, x.tau_hist2, \
-                                                                             x.sample_rank, x.cand, x.gate);                      \
+            dense_narrow_kernel<XHALF, L, kEmitSample><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS, x.st, x.tau, x.slots,     \
+                                                                             x.cand, x.gate);                                     \
         else                                                                                                       \
-            dense_narrow_kernel<XHALF, L, kEmitFilter><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS, x.st, x.tau, x.tau_hist2, \
-                                                                             x.sample_rank, x.cand, x.gate);                      \
+            dense_narrow_kernel<XHALF, L, kEmitFilter><<<grid, 256, 0, s>>>(OTF_WIDE_ARGS, x.st, x.tau, x.slots,     \
+                                                                             x.cand, x.gate);                                     \
     } while (0)
         switch (lpr) {
             case 1: OTF_NARROW(1); break;
@@ -496,17 +497,17 @@ hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int
                              int w_is_half, const float *bias_ptr, int bias_index, float *scores, uint32_t *hist1,
                              uint32_t *chunk_ctr, hipStream_t s) {
     return launch_dense_scan_emit(X, x_is_half, N, D, ldx, w, w_is_half, bias_ptr, bias_index, kEmitScores, scores,
-                                  hist1, chunk_ctr, nullptr, nullptr, nullptr, 0, nullptr, nullptr, s);
+                                  hist1, chunk_ctr, nullptr, nullptr, nullptr, nullptr, nullptr, s);
 }
 
 hipError_t launch_dense_scan_emit(const void *X, int x_is_half, int64_t N, int D, int64_t ldx, const void *w,
                                   int w_is_half, const float *bias_ptr, int bias_index, ScanEmit emit, float *scores,
                                   uint32_t *hist1, uint32_t *chunk_ctr, SelState *st, const SelState *tau,
-                                  const uint32_t *tau_hist2, int sample_rank, unsigned long long *cand,
-                                  const SelState *gate, hipStream_t s) {
+                                  SampleSlot *slots, unsigned long long *cand, const SelState *gate, hipStream_t s) {
     const uint8_t *Xb = reinterpret_cast<const uint8_t *>(X);
-    const NarrowExtra x{emit, st, tau, tau_hist2, sample_rank, cand, gate};
-    if (emit == kEmitFilter && (!st || !tau || !tau_hist2 || !cand)) return hipErrorInvalidValue;
+    const NarrowExtra x{emit, st, tau, slots, cand, gate};
+    if (emit == kEmitFilter && (!st || !tau || !slots || !cand)) return hipErrorInvalidValue;
+    if (emit == kEmitSample && (!st || !slots)) return hipErrorInvalidValue;
     if (x_is_half)
         return launch_dense_typed<true>(Xb, N, D, ldx * 2, w, w_is_half, bias_ptr, bias_index, scores, hist1, chunk_ctr, x, s);
     return launch_dense_typed<false>(Xb, N, D, ldx * 4, w, w_is_half, bias_ptr, bias_index, scores, hist1, chunk_ctr, x, s);

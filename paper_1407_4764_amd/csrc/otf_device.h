@@ -204,6 +204,97 @@ __device__ __forceinline__ bool filter_hopeless(uint32_t m, uint32_t need1, cons
     return at_or_above > 2u * (uint32_t)kCandCap / (uint32_t)kSampleStride;
 }
 
+// Threshold of a filtered scan from the sample, second form (all single-classifier scans).  The scan
+// of the strided sample keeps no scores and no histogram: every wave only remembers the largest
+// key it met and how many of its rows had exactly that key, and leaves the pair in a slot of its
+// own (S slots = waves of the launch; block 0 records S in the sample state).  The j-th largest of
+// the S wave maxima estimates the threshold: with Nv sample rows spread over S waves, a wave's
+// maximum exceeds the level that a fraction p of all rows exceed with probability
+// 1 - (1 - p)^(Nv / S), so the level that kFilterExpect rows of the N-row store exceed is met by about
+// j = S (1 - exp(-kFilterExpect Nv / (N S))) of the maxima (about kFilterExpect Nv / N = 32 when the
+// waves' shares are small).  The consumer resolves that order statistic to 24 bits by two radix
+// passes over the S keys in shared memory; rows at or above it (~kFilterExpect, give or take a
+// fifth) are the candidates.  Ties show in the counts: when the maxima at or above the threshold
+// stand for far more sample rows than the candidate list has room for at the sampling rate, the
+// filtered scan is pointless (scores that are constant or take few values) and is called off.
+constexpr int kMaxSampleSlots = 4096;   // 256 workgroups of 16 waves
+struct SampleSlot {
+    uint32_t key;     // largest key among the wave's sample rows (0: it had none)
+    uint32_t count;   // how many of its rows had that key
+};
+
+__device__ __forceinline__ void sample_note(uint32_t &mx, uint32_t &cnt, uint32_t key) {
+    cnt = key > mx ? 1u : (key == mx ? cnt + 1u : cnt);
+    mx = key > mx ? key : mx;
+}
+
+// Whole wave, once, at the end of a sample scan: reduces the lanes' (mx, cnt) and stores the wave's slot;
+// thread 0 of block 0 records the number of slots in the sample state.
+__device__ __forceinline__ void sample_store(SampleSlot *slots, SelState *sample_st, uint32_t mx, uint32_t cnt) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t m2 = (uint32_t)__shfl_xor((int)mx, o, 64), c2 = (uint32_t)__shfl_xor((int)cnt, o, 64);
+        cnt = m2 > mx ? c2 : (m2 == mx ? cnt + c2 : cnt);
+        mx = m2 > mx ? m2 : mx;
+    }
+    const uint32_t nwaves = blockDim.x >> 6;
+    if ((threadIdx.x & 63) == 0) slots[blockIdx.x * nwaves + (threadIdx.x >> 6)] = SampleSlot{mx, cnt};
+    if (blockIdx.x == 0 && threadIdx.x == 0) sample_st->ncand = gridDim.x * nwaves;
+}
+
+struct TauChoice {
+    uint32_t tau;      // rows with key >= tau are candidates
+    bool hopeless;     // ties: call the filtered scan off (same answer in every workgroup)
+};
+
+// Whole block, before its scan: the threshold from the slots a sample scan left (see above).
+// N = rows of the store.  `lds` = kBins1 words of shared memory, `s_out` = 3 words.  Ends with a barrier.
+__device__ __forceinline__ TauChoice resolve_tau_slots(const SampleSlot *slots, const SelState *sample_st, long long N,
+                                                       uint32_t *lds, uint32_t *s_out) {
+    const uint32_t S = sample_st->ncand;
+    const float Nv = (float)(N / ((long long)kSampleGroup * kSampleStride) * kSampleGroup);
+    float jf = (float)S * (1.f - __expf(-(float)kFilterExpect * Nv / ((float)N * (float)S)));
+    uint32_t j = (uint32_t)(jf + 0.5f);
+    j = j < 1u ? 1u : (j > S ? S : j);
+    uint32_t b1 = 0u, need = j;
+#pragma unroll 1
+    for (int pass = 0; pass < 2; ++pass) {
+        __syncthreads();
+        for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lds[b] = 0u;
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < S; i += blockDim.x) {
+            const uint32_t k = slots[i].key;
+            if (pass == 0) atomicAdd(&lds[k >> 20], 1u);
+            else if ((k >> 20) == b1) atomicAdd(&lds[(k >> 8) & 0xFFFu], 1u);
+        }
+        __syncthreads();
+        if (threadIdx.x < 64) {
+            uint32_t above, inbin;
+            const uint32_t bin = wave_find_bin(lds, kBins1 / 64, need, &above, &inbin);
+            if (threadIdx.x == 0) {
+                s_out[0] = bin;
+                s_out[1] = above;
+                s_out[2] = 0u;
+            }
+        }
+        __syncthreads();
+        if (pass == 0) {
+            b1 = s_out[0];
+            need -= s_out[1];
+        }
+    }
+    TauChoice c;
+    c.tau = ((b1 << 12) | s_out[0]) << 8;
+    __syncthreads();
+    uint32_t mine = 0u;
+    for (uint32_t i = threadIdx.x; i < S; i += blockDim.x) mine += slots[i].key >= c.tau ? slots[i].count : 0u;
+    if (mine) atomicAdd(&s_out[2], mine);
+    __syncthreads();
+    c.hopeless = s_out[2] > 2u * (uint32_t)kCandCap / (uint32_t)kSampleStride;
+    __syncthreads();
+    return c;
+}
+
 // Dynamic work distribution for the streaming scans.  The chip's eight dies stream at visibly
 // different rates and the waves of a workgroup drift apart, so a static split of the rows leaves
 // a tail of 5-10 % in which most of the chip idles.  Instead the work is cut into tiles (what one

@@ -73,15 +73,14 @@ hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int
 bool dense_scan_filters(int x_is_half, int D);
 // The same scan in the three forms of the table scans (narrow rows only for the last two):
 //   kEmitScores  as above; with `gate` set the kernel returns at once unless gate->fallback is raised
-//   kEmitSample  N = rows of the strided sample, numbered compactly: scores[v] + histogram
-//   kEmitFilter  rows at or above the threshold go to cand (cursor in st); every workgroup resolves
-//                the threshold from the state passes 1 and 2 over the sample left in (tau, tau_hist2)
-//                for rank sample_rank
+//   kEmitSample  N = rows of the strided sample, numbered compactly: the waves' largest keys into `slots`,
+//                their number into st (the sample's state)
+//   kEmitFilter  rows at or above the threshold go to cand (cursor in st); every workgroup resolves the
+//                threshold from `slots` (their number in tau->ncand); store_rows = rows of the whole store
 hipError_t launch_dense_scan_emit(const void *X, int x_is_half, int64_t N, int D, int64_t ldx, const void *w,
                                   int w_is_half, const float *bias_ptr, int bias_index, ScanEmit emit, float *scores,
                                   uint32_t *hist1, uint32_t *chunk_ctr, SelState *st, const SelState *tau,
-                                  const uint32_t *tau_hist2, int sample_rank, unsigned long long *cand,
-                                  const SelState *gate, hipStream_t s);
+                                  SampleSlot *slots, unsigned long long *cand, const SelState *gate, hipStream_t s);
 
 // Multi-classifier fp16 scan on the matrix cores (Q = 32 or 64 classifiers per call).
 //   kEmitScores  scores[q][i] for every row (row stride ld_scores); with `gate` set the kernel returns
@@ -109,21 +108,21 @@ hipError_t launch_binary_prepare(const float *w, int D, float *image, const Sele
 // word); or no table at all: `image` is a query code of row_bytes bytes and the score is minus the
 // Hamming distance to it.
 enum TableKind { kTableBytes = 0, kTableSeven = 1, kTableHamming = 2 };
-//   kEmitScores  scores + pass-1 histogram into (st, hist1) for a top-k of k; `gate` as above
-//   kEmitSample  scores of the strided sample (compact numbering) + pass-1 histogram for rank k = m
-//   kEmitFilter  append rows at or above the threshold to cand (cursor in st); every block resolves
-//                the threshold from the sample's pass-2 state (tau, tau_hist2) for rank k = m (here k
-//                is the sample rank, not the length of the list)
+//   kEmitScores  scores + pass-1 histogram into (st, hist1); `gate` as above
+//   kEmitSample  N = rows of the strided sample (compact numbering): every wave leaves the largest key it
+//                met in its slot of `slots`; st = the sample's state, which receives the number of slots
+//   kEmitFilter  append rows at or above the threshold to cand (cursor in st); every block resolves the
+//                threshold from `slots` (their number in tau->ncand)
 hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, TableKind kind, const float *image,
-                             float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
-                             const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
-                             const SelState *gate, hipStream_t s);
+                             float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1,
+                             const SelState *tau, SampleSlot *slots, unsigned long long *cand, const SelState *gate,
+                             hipStream_t s);
 
 // Sparse-row store of 128-D features (mask + packed non-zero values per row, word offsets in start).
 hipError_t launch_sparse_scan(const uint32_t *rows, const int64_t *start, int64_t N, int64_t store_rows, const float *w,
-                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
-                              const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
-                              const SelState *gate, hipStream_t s);
+                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1,
+                              const SelState *tau, SampleSlot *slots, unsigned long long *cand, const SelState *gate,
+                              hipStream_t s);
 
 hipError_t launch_sgd_step(float *w, float *b, int D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,
                            int n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int n_neg,

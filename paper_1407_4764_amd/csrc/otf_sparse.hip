@@ -62,7 +62,7 @@ template <int EMIT>
 __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
     const uint32_t *__restrict__ rows, const long long *__restrict__ start, long long N, long long store_rows,
     const float *__restrict__ w, float bias, float *__restrict__ scores, SelState *st, uint32_t *hist1,
-    int sample_rank, const SelState *tau_state, const uint32_t *tau_hist2, unsigned long long *__restrict__ cand,
+    const SelState *tau_state, SampleSlot *sample_slots, unsigned long long *__restrict__ cand,
     const SelState *gate) {
     __shared__ __attribute__((aligned(16))) uint32_t win[kSparseThreads / 64][kWinBufWords];
     __shared__ uint32_t lhist[kBins1];            // (the filtered scan resolves its threshold in here)
@@ -75,12 +75,13 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
     const uint32_t chunk_tiles = tile_queue_chunk_tiles(total_tiles, 4u);
     uint32_t tau = 0u;
     if (EMIT == kEmitFilter) {
-        const BinChoice r2 = block_find_bin(tau_hist2, kBins2, tau_state->need1, lhist, s_out);
-        tau = ((tau_state->b1 << 12) | r2.bin) << 8;
-        if (filter_hopeless((uint32_t)sample_rank, tau_state->need1, r2)) return;   // uniform
+        const TauChoice tc = resolve_tau_slots(sample_slots, tau_state, store_rows, lhist, s_out);
+        if (tc.hopeless) return;                  // uniform
+        tau = tc.tau;
     } else {
         for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
     }
+    uint32_t smx = 0u, scnt = 0u;                 // sample scan: this lane's largest key and its multiplicity
     __syncthreads();
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -139,7 +140,9 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
             if (valid && l == 0) {
                 const float sc = acc + bias;
                 const long long v = v0 + rl;
-                if (EMIT == kEmitFilter) {
+                if (EMIT == kEmitSample) {
+                    sample_note(smx, scnt, float_to_key(sc));
+                } else if (EMIT == kEmitFilter) {
                     const uint32_t key = float_to_key(sc);
                     if (key >= tau && !list_full) {
                         const uint32_t pos = atomicAdd(&st->cursor, 1u);
@@ -230,34 +233,35 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
             r += nxt.nrows;
         }
     }
-    if (EMIT != kEmitFilter) merge_hist1(lhist, hist1);
+    if (EMIT == kEmitScores) merge_hist1(lhist, hist1);
+    if (EMIT == kEmitSample) sample_store(sample_slots, st, smx, scnt);
 }
 
 template <int EMIT>
 static hipError_t launch_sparse_cfg(const uint32_t *rows, const int64_t *start, int64_t N, int64_t store_rows,
-                                    const float *w, float bias, float *scores, SelState *st, uint32_t *hist1, int k,
-                                    const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
+                                    const float *w, float bias, float *scores, SelState *st, uint32_t *hist1,
+                                    const SelState *tau, SampleSlot *slots, unsigned long long *cand,
                                     const SelState *gate, hipStream_t s) {
     const int64_t tiles = (N + kSparseTileRows - 1) / kSparseTileRows;
     const int grid = (int)std::min<int64_t>((tiles + 3) / 4, (int64_t)device_cu_count() * 3);
     sparse_scan_kernel<EMIT><<<grid < 1 ? 1 : grid, kSparseThreads, 0, s>>>(
         rows, reinterpret_cast<const long long *>(start), (long long)N, (long long)store_rows, w, bias, scores, st, hist1,
-        k, tau, tau_hist2, cand, gate);
+        tau, slots, cand, gate);
     return hipGetLastError();
 }
 
 // N = rows to score (kEmitSample: the sample rows, compact numbering); store_rows = rows of the store.
 hipError_t launch_sparse_scan(const uint32_t *rows, const int64_t *start, int64_t N, int64_t store_rows, const float *w,
-                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
-                              const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
-                              const SelState *gate, hipStream_t s) {
+                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1,
+                              const SelState *tau, SampleSlot *slots, unsigned long long *cand, const SelState *gate,
+                              hipStream_t s) {
     switch (emit) {
         case kEmitScores:
-            return launch_sparse_cfg<kEmitScores>(rows, start, N, store_rows, w, bias, scores, st, hist1, k, tau, tau_hist2, cand, gate, s);
+            return launch_sparse_cfg<kEmitScores>(rows, start, N, store_rows, w, bias, scores, st, hist1, tau, slots, cand, gate, s);
         case kEmitSample:
-            return launch_sparse_cfg<kEmitSample>(rows, start, N, store_rows, w, bias, scores, st, hist1, k, tau, tau_hist2, cand, gate, s);
+            return launch_sparse_cfg<kEmitSample>(rows, start, N, store_rows, w, bias, scores, st, hist1, tau, slots, cand, gate, s);
         default:
-            return launch_sparse_cfg<kEmitFilter>(rows, start, N, store_rows, w, bias, scores, st, hist1, k, tau, tau_hist2, cand, gate, s);
+            return launch_sparse_cfg<kEmitFilter>(rows, start, N, store_rows, w, bias, scores, st, hist1, tau, slots, cand, gate, s);
     }
 }
 

@@ -258,11 +258,14 @@ __device__ __forceinline__ float hamming16(const uint32_t (&d)[4], const uint32_
 // Filtered scan: a wave that has seen the list full stops appending (the list is already
 // useless, and the appends are adds to one address, ~18 ns each one after the other: a
 // threshold that lets a million rows pass would otherwise cost tens of milliseconds).
+// Sample scan: the row only competes for the wave's largest key (sample_note).
 template <int EMIT>
 __device__ __forceinline__ void emit_row(float score, long long v, uint32_t tau, bool &list_full, SelState *st,
                                          unsigned long long *__restrict__ cand, float *__restrict__ scores,
-                                         uint32_t *lhist) {
-    if (EMIT == kEmitFilter) {
+                                         uint32_t *lhist, uint32_t &smx, uint32_t &scnt) {
+    if (EMIT == kEmitSample) {
+        sample_note(smx, scnt, float_to_key(score));
+    } else if (EMIT == kEmitFilter) {
         const uint32_t key = float_to_key(score);
         if (key >= tau && !list_full) {
             const uint32_t pos = atomicAdd(&st->cursor, 1u);
@@ -303,10 +306,10 @@ __device__ __forceinline__ long long store_row(long long v) {
 template <int LPR, int U, int GB, int EMIT>
 __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     const uint8_t *__restrict__ codes, long long N, int M, const float *__restrict__ image, float bias,
-    float *__restrict__ scores, SelState *st, uint32_t *hist1, int sample_rank, const SelState *tau_state,
-    const uint32_t *tau_hist2, unsigned long long *__restrict__ cand, const SelState *gate) {
+    float *__restrict__ scores, SelState *st, uint32_t *hist1, const SelState *tau_state,
+    SampleSlot *sample_slots, unsigned long long *__restrict__ cand, const SelState *gate) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    __shared__ uint32_t lhist[EMIT == kEmitFilter ? 1 : kBins1];
+    __shared__ uint32_t lhist[EMIT == kEmitScores ? kBins1 : 1];
     __shared__ uint32_t s_out[3];
     __shared__ TileQueue s_queue;
     if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
@@ -323,18 +326,17 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     if (threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);   // visible after the barriers below
     const uint32_t chunk_tiles = tile_queue_chunk_tiles(N / TILE, CHUNK_TILES);
 
-    if (EMIT != kEmitFilter)
+    if (EMIT == kEmitScores)
         for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
-    // Filtered scan: the threshold is the top 24 bits of the k-th largest sample key (k = the
-    // sample rank here); passes 1 and 2 over the sample left their state, every block resolves it
+    // Filtered scan: every block resolves the threshold from the wave maxima the sample scan left
     // (the table area of shared memory is still free at this point).
     uint32_t tau = 0u;
     if (EMIT == kEmitFilter) {
-        const BinChoice r2 = block_find_bin(tau_hist2, kBins2, tau_state->need1,
-                                            reinterpret_cast<uint32_t *>(lds_raw), s_out);
-        tau = ((tau_state->b1 << 12) | r2.bin) << 8;
-        if (filter_hopeless((uint32_t)sample_rank, tau_state->need1, r2)) return;   // uniform
+        const TauChoice tc = resolve_tau_slots(sample_slots, tau_state, N, reinterpret_cast<uint32_t *>(lds_raw), s_out);
+        if (tc.hopeless) return;                  // uniform
+        tau = tc.tau;
     }
+    uint32_t smx = 0u, scnt = 0u;                 // sample scan: this lane's largest key and its multiplicity
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int chunk = GB == 8 ? (lane & 7) : (lane & 15);   // 16-byte chunk inside the table's row span
@@ -383,7 +385,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     // one output round: lane `sub` of each group holds in `mine` the sum of the row it owns
     bool list_full = false;
     auto emit = [&](float mine, long long v, bool ok) {
-        if (sub < ACTIVE && ok) emit_row<EMIT>(mine + bias, v, tau, list_full, st, cand, scores, lhist);
+        if (sub < ACTIVE && ok) emit_row<EMIT>(mine + bias, v, tau, list_full, st, cand, scores, lhist, smx, scnt);
     };
 
     // first row of the next tile of this wave, or -1 when the scan has no full tile left
@@ -449,7 +451,8 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
             emit(mine[e], v, v < N);
         }
     }
-    if (EMIT != kEmitFilter) merge_hist1(lhist, hist1);
+    if (EMIT == kEmitScores) merge_hist1(lhist, hist1);
+    if (EMIT == kEmitSample) sample_store(sample_slots, st, smx, scnt);
 }
 
 // Scan of byte-group rows longer than 128 bytes: nphase = ceil(row_bytes / 128) column phases, each
@@ -480,12 +483,11 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
 template <int EMIT, int TPW>
 __global__ __launch_bounds__(kScanMaxThreads) void table_walk_kernel(
     const uint8_t *__restrict__ codes, long long N, int row_bytes, int nphase, const float *__restrict__ image,
-    float bias, float *__restrict__ scores, SelState *st, uint32_t *hist1, int sample_rank,
-    const SelState *tau_state, const uint32_t *tau_hist2, unsigned long long *__restrict__ cand,
-    const SelState *gate) {
+    float bias, float *__restrict__ scores, SelState *st, uint32_t *hist1, const SelState *tau_state,
+    SampleSlot *sample_slots, unsigned long long *__restrict__ cand, const SelState *gate) {
     static_assert(TPW % 2 == 0, "tiles alternate between two register buffers");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    __shared__ uint32_t lhist[EMIT == kEmitFilter ? 1 : kBins1];
+    __shared__ uint32_t lhist[EMIT == kEmitScores ? kBins1 : 1];
     __shared__ uint32_t s_out[3];
     __shared__ uint32_t s_blk[4];                 // ring: number of the workgroup's j-th block at slot j % 4
     if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
@@ -497,15 +499,15 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_walk_kernel(
     uint32_t *blk_ctr = &st->chunk_ctr[EMIT == kEmitScores ? 1 : 0];
     if (tid == 0) s_blk[0] = atomicAdd(blk_ctr, 1u);
 
-    if (EMIT != kEmitFilter)
+    if (EMIT == kEmitScores)
         for (int b = tid; b < kBins1; b += blockDim.x) lhist[b] = 0u;
     uint32_t tau = 0u;
     if (EMIT == kEmitFilter) {                    // as in table_scan_kernel (the image area is still free)
-        const BinChoice r2 = block_find_bin(tau_hist2, kBins2, tau_state->need1,
-                                            reinterpret_cast<uint32_t *>(lds_raw), s_out);
-        tau = ((tau_state->b1 << 12) | r2.bin) << 8;
-        if (filter_hopeless((uint32_t)sample_rank, tau_state->need1, r2)) return;   // uniform
+        const TauChoice tc = resolve_tau_slots(sample_slots, tau_state, N, reinterpret_cast<uint32_t *>(lds_raw), s_out);
+        if (tc.hopeless) return;                  // uniform
+        tau = tc.tau;
     }
+    uint32_t smx = 0u, scnt = 0u;                 // sample scan: this lane's largest key and its multiplicity
     __syncthreads();
 
     const int sub = lane & 7, rr = lane >> 3, octet = (lane >> 3) & 3;
@@ -576,7 +578,8 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_walk_kernel(
 
     long long blk = s_blk[0];
     if (blk >= nblocks) {                          // uniform: nothing for this workgroup
-        if (EMIT != kEmitFilter) merge_hist1(lhist, hist1);
+        if (EMIT == kEmitScores) merge_hist1(lhist, hist1);
+        if (EMIT == kEmitSample) sample_store(sample_slots, st, smx, scnt);
         return;
     }
     bool list_full = false;
@@ -629,7 +632,7 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_walk_kernel(
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const long long v0 = tile_row0(blk, t + h), v = window(v0) + (long long)sub * RPW + rr;
-                if (v >= v0 && v < N) emit_row<EMIT>(part[h] + bias, v, tau, list_full, st, cand, scores, lhist);
+                if (v >= v0 && v < N) emit_row<EMIT>(part[h] + bias, v, tau, list_full, st, cand, scores, lhist, smx, scnt);
             }
             turn_ring(part);
         }
@@ -638,7 +641,8 @@ __global__ __launch_bounds__(kScanMaxThreads) void table_walk_kernel(
         blk = next_blk;
         ++j;
     }
-    if (EMIT != kEmitFilter) merge_hist1(lhist, hist1);
+    if (EMIT == kEmitScores) merge_hist1(lhist, hist1);
+    if (EMIT == kEmitSample) sample_store(sample_slots, st, smx, scnt);
 }
 
 hipError_t launch_pq_build_lut(const float *codebooks, int M, int K, int dsub, const float *w, float *lut,
@@ -693,9 +697,8 @@ struct ScanArgs {
     float *scores;
     SelState *st;
     uint32_t *hist1;
-    int k;
-    const SelState *tau;
-    const uint32_t *tau_hist2;
+    const SelState *tau;         // filtered scan: the sample's state (number of slots)
+    SampleSlot *slots;           // sample scan: written; filtered scan: read
     unsigned long long *cand;
     const SelState *gate;
 };
@@ -713,8 +716,8 @@ static hipError_t launch_scan_cfg(const ScanArgs &a, hipStream_t s) {
     if (grid < 1) grid = 1;
     const int threads = tune_int(OTF_DEBUG_SCAN_THREADS, kScanThreads);
     table_scan_kernel<LPR, U, GB, EMIT><<<grid, threads, lds, s>>>(a.codes, (long long)a.N, a.M, a.image, a.bias,
-                                                                    a.scores, a.st, a.hist1, a.k, a.tau, a.tau_hist2,
-                                                                    a.cand, a.gate);
+                                                                    a.scores, a.st, a.hist1, a.tau, a.slots, a.cand,
+                                                                    a.gate);
     return hipGetLastError();
 }
 
@@ -744,8 +747,8 @@ static hipError_t launch_walk_cfg(const ScanArgs &a, hipStream_t s) {
     const int64_t nblocks = (a.N + R - 1) / R;
     const int grid = (int)std::min<int64_t>(nblocks, cus);
     table_walk_kernel<EMIT, TPW><<<grid, threads, kImageBytes, s>>>(a.codes, (long long)a.N, a.M, phases_of(a.M), a.image,
-                                                                    a.bias, a.scores, a.st, a.hist1, a.k, a.tau,
-                                                                    a.tau_hist2, a.cand, a.gate);
+                                                                    a.bias, a.scores, a.st, a.hist1, a.tau, a.slots,
+                                                                    a.cand, a.gate);
     return hipGetLastError();
 }
 
@@ -760,10 +763,10 @@ static hipError_t launch_walk_emit(const ScanArgs &a, ScanEmit emit, hipStream_t
 
 // row_bytes = stored bytes per row, a multiple of 16 up to 1024; kTableSeven only with 256.
 hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, TableKind kind, const float *image,
-                             float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1, int k,
-                             const SelState *tau, const uint32_t *tau_hist2, unsigned long long *cand,
-                             const SelState *gate, hipStream_t s) {
-    ScanArgs a{codes, N, row_bytes, image, bias, scores, st, hist1, k, tau, tau_hist2, cand, gate};
+                             float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1,
+                             const SelState *tau, SampleSlot *slots, unsigned long long *cand, const SelState *gate,
+                             hipStream_t s) {
+    ScanArgs a{codes, N, row_bytes, image, bias, scores, st, hist1, tau, slots, cand, gate};
     if (kind == kTableSeven) return launch_scan_emit<16, 7>(a, emit, s);
     if (kind == kTableHamming) {                  // `image` is the query code; lanes per row = next power of two
         if (row_bytes <= 16) return launch_scan_emit<1, 0>(a, emit, s);
