@@ -218,6 +218,10 @@ int otf_topk(const float *scores, int64_t N, int64_t ld, int32_t Q, int32_t k, f
     if (ld < N) return OTF_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     SelectWs sw = select_ws(ws, L);
+    if (Q == 1 && filter_eligible(N, k, nullptr))
+        return hip_status(launch_topk_filtered(
+            scores, N, k, sw, sample_select_ws(ws, L),
+            reinterpret_cast<SampleSlot *>(reinterpret_cast<uint8_t *>(ws) + L.sample_scores), out_scores, out_idx, s));
     hipError_t e = launch_select_init(sw, Q, s);
     if (e == hipSuccess) e = launch_hist1(scores, N, ld, Q, sw, 0, s);
     if (e == hipSuccess) e = launch_select_tail(scores, N, ld, Q, k, sw, out_scores, out_idx, 0, s);

@@ -59,6 +59,10 @@ hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q,
 // the consumer resolves the threshold from sample_sw.st[q] and sample_sw.hist2 itself.
 hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64_t ld, int Q, int m,
                                    const SelectWs &sample_sw, int publish_tau, SelState *main_st, hipStream_t s);
+// otf_topk in one read of the scores (one classifier, N large enough for a sample): zeroes the states
+// itself, sample -> threshold -> filter -> sort, the exact passes gated behind.
+hipError_t launch_topk_filtered(const float *scores, int64_t N, int k, const SelectWs &sw, const SelectWs &sample_sw,
+                                SampleSlot *slots, float *out_scores, int32_t *out_idx, hipStream_t s);
 // End of a filtered scan: sort the appended candidates or raise sw.st[0].fallback.
 hipError_t launch_filter_sort(const SelectWs &sw, int Q, int k, float *out_scores, int32_t *out_idx, hipStream_t s);
 

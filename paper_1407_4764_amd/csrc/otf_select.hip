@@ -701,6 +701,72 @@ __global__ __launch_bounds__(kSortThreads) void select_fused_gated_kernel(const 
                      out_idx + (size_t)q * k);
 }
 
+// Ranking of ready-made scores in one read (one classifier, a million scores or more): the scheme of
+// the filtered scans applied to otf_topk.  topk_sample_kernel zeroes the selection state and
+// leaves the largest key each of its waves met in a strided sample of the scores (every
+// kSampleStride-th group of kSampleGroup); topk_filter_kernel takes the threshold from those (see
+// resolve_tau_slots) and reads the scores once, keeping the ones at or above it; the list is
+// sorted by filter_sort_kernel, and the exact passes stand behind its flag as they do behind
+// every filtered scan.
+__global__ __launch_bounds__(256) void topk_sample_kernel(const float *__restrict__ scores, long long Nv, SelState *st,
+                                                          uint32_t *hist1, uint32_t *hist2, uint32_t *hist3,
+                                                          SelState *sample_st, SampleSlot *slots) {
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x, step = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = tid; i < (size_t)kHist1Words; i += step) hist1[i] = 0u;
+    for (size_t i = tid; i < (size_t)kBins2; i += step) hist2[i] = 0u;
+    for (size_t i = tid; i < (size_t)kBins3; i += step) hist3[i] = 0u;
+    if (blockIdx.x == 0) {                                  // (the block that records the number of slots below)
+        uint32_t *a = reinterpret_cast<uint32_t *>(st), *b = reinterpret_cast<uint32_t *>(sample_st);
+        for (int i = threadIdx.x; i < (int)(sizeof(SelState) / 4); i += blockDim.x) {
+            a[i] = 0u;
+            b[i] = 0u;
+        }
+        __syncthreads();
+    }
+    const long long waves = (long long)gridDim.x * (blockDim.x >> 6);
+    const long long wave = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    uint32_t mx = 0u, cnt = 0u;
+    for (long long v = wave * 64 + (threadIdx.x & 63); v < Nv; v += waves * 64) {
+        const long long row = (v >> 10) * ((long long)kSampleGroup * kSampleStride) + (v & 1023);
+        sample_note(mx, cnt, float_to_key(scores[row]));
+    }
+    sample_store(slots, sample_st, mx, cnt);
+}
+
+__global__ __launch_bounds__(512) void topk_filter_kernel(const float *__restrict__ scores, long long N, SelState *st,
+                                                          const SelState *sample_st, const SampleSlot *slots,
+                                                          unsigned long long *__restrict__ cand) {
+    constexpr uint32_t kLocal = 1024;                       // per workgroup; ~16 are expected
+    __shared__ uint32_t lds[kBins1];
+    __shared__ uint32_t s_out[3];
+    __shared__ unsigned long long local[kLocal];
+    __shared__ uint32_t s_n, s_base;
+    const TauChoice tc = resolve_tau_slots(slots, sample_st, N, lds, s_out);
+    if (tc.hopeless) return;                                // uniform: the list stays empty, the sort raises the fallback
+    if (threadIdx.x == 0) s_n = 0u;
+    __syncthreads();
+    long long begin, end;
+    sel_chunk(N, blockIdx.x, gridDim.x, &begin, &end);
+    for_each_score(scores, begin, end, row_vec_ok(scores), [&](float v, bool ok, long long row) {
+        const uint32_t key = float_to_key(v);
+        if (ok && key >= tc.tau) {
+            const uint32_t lp = atomicAdd(&s_n, 1u);
+            if (lp < kLocal) local[lp] = pack_cand(key, row);
+        }
+    });
+    __syncthreads();
+    const uint32_t n = s_n;
+    // a workgroup with more candidates than its buffer holds means the threshold is far too low:
+    // the count it reports then overflows the list on purpose, and the exact passes take over
+    if (threadIdx.x == 0 && n) s_base = atomicAdd(&st->cursor, n <= kLocal ? n : (uint32_t)kCandCap + 1u);
+    __syncthreads();
+    if (n > kLocal) return;
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) {
+        const uint32_t pos = s_base + i;
+        if (pos < (uint32_t)kCandCap) cand[pos] = local[i];
+    }
+}
+
 static hipError_t allow_sort_lds() {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&sort_emit_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSortLdsBytes);
@@ -779,6 +845,18 @@ hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64
                                                     sample_sw.hist2, 1, nullptr);
     if (publish_tau) sample_tau_kernel<<<Q, 512, 0, s>>>(sample_sw.st, sample_sw.hist2, m, main_st);
     return hipGetLastError();
+}
+
+hipError_t launch_topk_filtered(const float *scores, int64_t N, int k, const SelectWs &sw, const SelectWs &sample_sw,
+                                SampleSlot *slots, float *out_scores, int32_t *out_idx, hipStream_t s) {
+    const int64_t Nv = N / ((int64_t)kSampleGroup * kSampleStride) * kSampleGroup;
+    const int sample_grid = (int)std::min<int64_t>(std::max<int64_t>(1, Nv / 1024), device_cu_count());
+    topk_sample_kernel<<<sample_grid, 256, 0, s>>>(scores, Nv, sw.st, sw.hist1, sw.hist2, sw.hist3, sample_sw.st, slots);
+    topk_filter_kernel<<<kSelBlocks, 512, 0, s>>>(scores, N, sw.st, sample_sw.st, slots, sw.cand);
+    hipError_t e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
+    if (e == hipSuccess) e = launch_hist1(scores, N, N, 1, sw, 1, s);
+    if (e == hipSuccess) e = launch_select_tail(scores, N, N, 1, k, sw, out_scores, out_idx, 1, s);
+    return e;
 }
 
 hipError_t launch_filter_sort(const SelectWs &sw, int Q, int k, float *out_scores, int32_t *out_idx, hipStream_t s) {
