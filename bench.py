@@ -205,19 +205,29 @@ def measure_sgd(torch, binding, synth):
     ws = binding.sgd_workspace(batch, "cuda")
     w = torch.zeros(D, device="cuda")
 
-    def one_pass():
+    def one_call():                                   # otf_svm_sgd_pass: the steps enqueued back to back from C
         w.zero_()
-        for t in range(1, steps + 1):
-            binding.svm_sgd_step(w, None, Xp, ip[t - 1], Xn, ineg[t - 1], lam, t, False, ws)
-    one_pass()
-    torch.cuda.synchronize()
-    reps = 5
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        one_pass()
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / reps
-    return {"workload": "pegasos_pass_125steps_B256_D2048", "ms_per_pass": dt * 1e3, "us_per_step": dt / steps * 1e6}
+        binding.svm_sgd_pass(w, None, Xp, ip, Xn, ineg, lam, 1, False, ws)
+
+    def one_kernel():                                 # the same call as a single kernel (diagnostic route)
+        binding.debug_set(binding.DEBUG_SGD_PASS_PATH, 1)
+        try:
+            one_call()
+        finally:
+            binding.debug_set(binding.DEBUG_SGD_PASS_PATH, 0)
+    res = {}
+    for name, fn in (("call", one_call), ("kernel", one_kernel)):
+        fn()
+        torch.cuda.synchronize()
+        reps = 5
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        res[name] = (time.perf_counter() - t0) / reps
+    assert binding.sgd_pass_status(ws) == 0
+    return {"workload": "pegasos_pass_125steps_B256_D2048", "ms_per_pass": res["call"] * 1e3,
+            "us_per_step": res["call"] / steps * 1e6, "us_per_step_as_one_kernel": res["kernel"] / steps * 1e6}
 
 
 def measure_topk(torch, binding, synth):

@@ -223,16 +223,33 @@ int otf_svm_sgd_step(float *w, float *b, int32_t D,
                      void *ws, size_t ws_bytes, void *stream);
 
 /*
- * n_steps consecutive Pegasos steps (iterations t_first, t_first + 1, ...), enqueued back to back:
+ * n_steps consecutive Pegasos steps (iterations t_first, t_first + 1, ...) from one call:
  * step s uses the batch idx_pos[s * n_pos .. (s+1) * n_pos), idx_neg[s * n_neg .. (s+1) * n_neg).
  * Same arguments, limits and errors as otf_svm_sgd_step; n_steps >= 1.  (Paper Sec. 4: between two
  * rankings the model takes as many steps as fit; one call keeps the host out of that loop.)
+ *
+ * The steps are enqueued back to back, two kernels each.  A second route runs the whole call as ONE
+ * kernel (D <= 2048; diagnostic switch OTF_DEBUG_SGD_PASS_PATH): up to 32 workgroups share the batch
+ * rows and meet once per step through a counter in `ws`.  It is not the default because on this
+ * chip a step then costs a chain of round trips between dies, ~15 us against ~10 us.  Its waits
+ * are bounded: if one expires (the workgroups could not all become resident, e.g. on a GPU that
+ * other work keeps full for seconds) the kernel ends at once, w and b keep their values from before
+ * the call, and the 32-bit word at the start of `ws` reads 1 after the call has completed.  After
+ * any complete run, by either route, it reads 0.  The routes agree to rounding (the sums are
+ * formed in another order).
  */
 int otf_svm_sgd_pass(float *w, float *b, int32_t D,
                      const float *Xpos, int64_t ld_pos, const int32_t *idx_pos, int32_t n_pos,
                      const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int32_t n_neg,
                      float lambda, int64_t t_first, int32_t n_steps, int32_t update_bias,
                      void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Diagnostic: counts the entries of idx[0..n) that are not row numbers of a pool of `rows` rows into
+ * *bad (one int32 in device memory, which the caller has set to 0).  The training calls read their
+ * row numbers unchecked (they are not told the pools' sizes): check them once where they are made.
+ */
+int otf_check_indices(const int32_t *idx, int64_t n, int64_t rows, int32_t *bad, void *stream);
 
 /*
  * Binarisation encoder (paper Sec. 3, "Binarization", Eq. (1)): a zero-centred descriptor phi in
@@ -331,6 +348,8 @@ typedef enum {
     OTF_DEBUG_MFMA_BLOCKS_PER_CU,    /* 1..8, multi-classifier scan */
     OTF_DEBUG_PQENC_BLOCKS_PER_CU,   /* 1..8, otf_pq_encode */
     OTF_DEBUG_WALK_TILES,            /* 2, 4 or 8 tiles of 64 rows per wave and block, table scans of rows > 128 bytes */
+    OTF_DEBUG_SGD_PASS_PATH,         /* 1: otf_svm_sgd_pass as one kernel for the whole run (D <= 2048) */
+    OTF_DEBUG_SGD_SPIN_LIMIT,        /* polls after which a wait of the one-launch training run gives up (default 2^20) */
     OTF_DEBUG_KEYS
 } otf_debug_key;
 

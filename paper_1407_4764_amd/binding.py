@@ -27,12 +27,12 @@ EXPORTS = ["otf_status_string", "otf_workspace_bytes", "otf_rank_dense", "otf_pq
            "otf_rank_binary", "otf_topk", "otf_sgd_workspace_bytes", "otf_svm_sgd_step", "otf_svm_sgd_pass",
            "otf_tight_frame_workspace_bytes",
            "otf_tight_frame", "otf_binarize", "otf_pq_train_workspace_bytes", "otf_pq_encode", "otf_pq_lloyd_step",
-           "otf_profile_begin", "otf_profile_end", "otf_debug_set", "otf_rank_dense_noalloc", "otf_rank_pq_model", "otf_rank_hamming", "otf_rank_sparse"]
+           "otf_profile_begin", "otf_profile_end", "otf_debug_set", "otf_rank_dense_noalloc", "otf_rank_pq_model", "otf_rank_hamming", "otf_rank_sparse", "otf_check_indices"]
 
 # otf_debug_key
 (DEBUG_RANK_PATH, DEBUG_BINARIZE_FP32, DEBUG_PQENC_FP32, DEBUG_SCAN_THREADS, DEBUG_SCAN_UNROLL, DEBUG_BINARIZE_WAVES,
  DEBUG_PQENC_RANGE, DEBUG_DENSE_BLOCKS_PER_CU, DEBUG_NARROW_BLOCKS_PER_CU, DEBUG_MFMA_BLOCKS_PER_CU,
- DEBUG_PQENC_BLOCKS_PER_CU, DEBUG_WALK_TILES, DEBUG_KEYS) = range(13)
+ DEBUG_PQENC_BLOCKS_PER_CU, DEBUG_WALK_TILES, DEBUG_SGD_PASS_PATH, DEBUG_SGD_SPIN_LIMIT, DEBUG_KEYS) = range(15)
 
 _lib = None
 
@@ -82,6 +82,8 @@ def lib():
         L.otf_svm_sgd_step.argtypes = [vp, vp, i32, vp, i64, vp, i32, vp, i64, vp, i32, f32, i64, i32, vp, sz, vp]
         L.otf_svm_sgd_pass.restype = ctypes.c_int
         L.otf_svm_sgd_pass.argtypes = [vp, vp, i32, vp, i64, vp, i32, vp, i64, vp, i32, f32, i64, i32, i32, vp, sz, vp]
+        L.otf_check_indices.restype = ctypes.c_int
+        L.otf_check_indices.argtypes = [vp, i64, i64, vp, vp]
         L.otf_tight_frame_workspace_bytes.restype = sz
         L.otf_tight_frame_workspace_bytes.argtypes = [i32, i32]
         L.otf_tight_frame.restype = ctypes.c_int
@@ -419,6 +421,27 @@ def svm_sgd_pass(w, b, Xpos, idx_pos, Xneg, idx_neg, lam, t_first, update_bias, 
                                 ws.numel(), _stream(dev))
     if rc != OTF_OK:
         raise OtfError(rc, "otf_svm_sgd_pass")
+
+
+def sgd_pass_status(ws):
+    """0 after a complete svm_sgd_pass on this workspace, 1 if one of its bounded waits expired (synchronises)."""
+    torch.cuda.synchronize()
+    return int(ws[0:4].view(torch.int32).item())
+
+
+def check_indices(idx, rows):
+    """Raises IndexError if any entry of the int32 device tensor idx is not a row number of a pool of
+    `rows` rows (synchronises: for use where the batches are built, not in the loop)."""
+    a = _Args()
+    a.check(idx, "idx", torch.int32)
+    dev = a.done()
+    bad = torch.zeros(1, dtype=torch.int32, device=dev)
+    rc = lib().otf_check_indices(_ptr(idx), idx.numel(), int(rows), _ptr(bad), _stream(dev))
+    if rc != OTF_OK:
+        raise OtfError(rc, "otf_check_indices")
+    n = int(bad.item())
+    if n:
+        raise IndexError("%d of %d row numbers lie outside the pool of %d rows" % (n, idx.numel(), rows))
 
 
 def tight_frame(G, m, U=None):

@@ -115,6 +115,8 @@ static bool debug_value_ok(int key, int v) {
         case OTF_DEBUG_SCAN_UNROLL:
         case OTF_DEBUG_BINARIZE_WAVES: return v == 4 || v == 8;
         case OTF_DEBUG_WALK_TILES: return v == 2 || v == 4 || v == 8;
+        case OTF_DEBUG_SGD_PASS_PATH: return v == 1;
+        case OTF_DEBUG_SGD_SPIN_LIMIT: return v >= 1 && v <= (1 << 30);
         case OTF_DEBUG_PQENC_RANGE: return v >= 4 && v <= 64 && v % 4 == 0;
         case OTF_DEBUG_DENSE_BLOCKS_PER_CU:
         case OTF_DEBUG_NARROW_BLOCKS_PER_CU:
@@ -509,12 +511,14 @@ int otf_rank_sparse(const uint32_t *rows, const int64_t *start, int64_t N, int32
 
 size_t otf_sgd_workspace_bytes(int32_t B) {
     if (B < 1 || B > 4096) return 0;
-    return (size_t)4096 * sizeof(float);
+    // the coefficients of one step, or the control block and partial vectors of a one-launch run
+    return std::max<size_t>((size_t)4096 * sizeof(float), sgd_pass_ws_bytes(2048));
 }
 
-int otf_svm_sgd_step(float *w, float *b, int32_t D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,
-                     int32_t n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int32_t n_neg,
-                     float lambda, int64_t t, int32_t update_bias, void *ws, size_t ws_bytes, void *stream) {
+// The argument checks of a training step (host only).
+static int sgd_step_check(const float *w, int32_t D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,
+                          int32_t n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int32_t n_neg,
+                          float lambda, int64_t t, const void *ws, size_t ws_bytes) {
     if (!w || D < 1 || n_pos < 0 || n_neg < 0 || n_pos + n_neg < 1 || t < 1 || !(lambda > 0.f))
         return OTF_ERR_INVALID_ARG;
     if (n_pos > 0 && (!Xpos || !idx_pos || ld_pos < D)) return OTF_ERR_INVALID_ARG;
@@ -525,8 +529,17 @@ int otf_svm_sgd_step(float *w, float *b, int32_t D, const float *Xpos, int64_t l
         return OTF_ERR_INVALID_ARG;
     if (!ws || ws_bytes < otf_sgd_workspace_bytes(n_pos + n_neg) || (reinterpret_cast<uintptr_t>(ws) & 15u))
         return OTF_ERR_WORKSPACE;
+    return OTF_OK;
+}
+
+int otf_svm_sgd_step(float *w, float *b, int32_t D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,
+                     int32_t n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int32_t n_neg,
+                     float lambda, int64_t t, int32_t update_bias, void *ws, size_t ws_bytes, void *stream) {
+    const int rc = sgd_step_check(w, D, Xpos, ld_pos, idx_pos, n_pos, Xneg, ld_neg, idx_neg, n_neg, lambda, t, ws,
+                                  ws_bytes);
+    if (rc != OTF_OK) return rc;
     return hip_status(launch_sgd_step(w, b, D, Xpos, ld_pos, idx_pos, n_pos, Xneg, ld_neg, idx_neg, n_neg, lambda, t,
-                                      update_bias, reinterpret_cast<float *>(ws),
+                                      update_bias, reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + 256),
                                       reinterpret_cast<hipStream_t>(stream)));
 }
 
@@ -535,13 +548,32 @@ int otf_svm_sgd_pass(float *w, float *b, int32_t D, const float *Xpos, int64_t l
                      float lambda, int64_t t_first, int32_t n_steps, int32_t update_bias, void *ws, size_t ws_bytes,
                      void *stream) {
     if (n_steps < 1) return OTF_ERR_INVALID_ARG;
-    for (int32_t s = 0; s < n_steps; ++s) {
-        const int rc = otf_svm_sgd_step(w, b, D, Xpos, ld_pos, idx_pos ? idx_pos + (size_t)s * n_pos : nullptr, n_pos,
-                                        Xneg, ld_neg, idx_neg ? idx_neg + (size_t)s * n_neg : nullptr, n_neg, lambda,
-                                        t_first + s, update_bias, ws, ws_bytes, stream);
-        if (rc != OTF_OK) return rc;      // argument errors show at s == 0, before anything is enqueued
+    // the argument checks of a single step, without enqueuing anything
+    const int rc = sgd_step_check(w, D, Xpos, ld_pos, idx_pos, n_pos, Xneg, ld_neg, idx_neg, n_neg, lambda, t_first, ws,
+                                  ws_bytes);
+    if (rc != OTF_OK) return rc;
+    // One launch for the whole run exists (D <= 2048) but is not the default: its step is a chain of
+    // round trips between workgroups on different dies (~15 us), slower than two launches per step (~10 us).
+    if (sgd_pass_fits(D) && tune_int(OTF_DEBUG_SGD_PASS_PATH, 0) == 1) {
+        const uint32_t limit = (uint32_t)tune_int(OTF_DEBUG_SGD_SPIN_LIMIT, 1 << 20);
+        return hip_status(launch_sgd_pass(w, b, D, Xpos, ld_pos, idx_pos, n_pos, Xneg, ld_neg, idx_neg, n_neg, lambda,
+                                          t_first, n_steps, update_bias, ws, limit,
+                                          reinterpret_cast<hipStream_t>(stream)));
     }
-    return OTF_OK;
+    // two launches per step, enqueued back to back; the status word of the workspace reads 0 afterwards
+    hipError_t e = hipSuccess;
+    for (int32_t s = 0; s < n_steps && e == hipSuccess; ++s)
+        e = launch_sgd_step(w, b, D, Xpos, ld_pos, idx_pos ? idx_pos + (size_t)s * n_pos : nullptr, n_pos, Xneg, ld_neg,
+                            idx_neg ? idx_neg + (size_t)s * n_neg : nullptr, n_neg, lambda, t_first + s, update_bias,
+                            reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + 256),
+                            reinterpret_cast<hipStream_t>(stream));
+    if (e == hipSuccess) e = launch_sgd_pass_clear_status(ws, reinterpret_cast<hipStream_t>(stream));
+    return hip_status(e);
+}
+
+int otf_check_indices(const int32_t *idx, int64_t n, int64_t rows, int32_t *bad, void *stream) {
+    if (!idx || !bad || n < 1 || rows < 1) return OTF_ERR_INVALID_ARG;
+    return hip_status(launch_check_indices(idx, n, rows, bad, reinterpret_cast<hipStream_t>(stream)));
 }
 
 size_t otf_tight_frame_workspace_bytes(int32_t n, int32_t m) {

@@ -132,6 +132,17 @@ hipError_t launch_sgd_step(float *w, float *b, int D, const float *Xpos, int64_t
                            int n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int n_neg,
                            float lambda, int64_t t, int update_bias, float *coef, hipStream_t s);
 
+// A run of consecutive steps in one launch (D <= 2048); ws holds sgd_pass_ws_bytes(D) bytes, its first word
+// the status (0 complete, 1 a bounded wait expired).
+bool sgd_pass_fits(int D);
+size_t sgd_pass_ws_bytes(int D);
+hipError_t launch_sgd_pass(float *w, float *b, int D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,
+                           int n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int n_neg,
+                           float lambda, int64_t t_first, int n_steps, int update_bias, void *ws, uint32_t spin_limit,
+                           hipStream_t s);
+hipError_t launch_sgd_pass_clear_status(void *ws, hipStream_t s);
+hipError_t launch_check_indices(const int32_t *idx, int64_t n, int64_t rows, int32_t *bad, hipStream_t s);
+
 // Binarisation encoder: the frame from the random matrix (scratch: n*m doubles), and the codes.
 hipError_t launch_tight_frame(const float *G, int n, int m, double *scratch, float *U, hipStream_t s);
 hipError_t launch_binarize(const float *phi, int64_t N, int m, int64_t ld, const float *U, int n, uint32_t *bits,

@@ -26,6 +26,8 @@ def run(X, Xpos, Xneg, idx_pos, idx_neg, k, lam, overlap=True):
     snaps = torch.zeros((rounds, D), dtype=torch.float32, device=dev)
     out_val = torch.empty((rounds, k), dtype=torch.float32, device=dev)
     out_idx = torch.empty((rounds, k), dtype=torch.int32, device=dev)
+    binding.check_indices(idx_pos, Xpos.shape[0])          # the training kernels read row numbers unchecked
+    binding.check_indices(idx_neg, Xneg.shape[0])
     sgd_ws = binding.sgd_workspace(2 * half, dev)
     rank_ws = binding.make_workspace(N, k, 1, dev)
     snapped = [torch.cuda.Event() for _ in range(rounds)]

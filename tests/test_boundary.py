@@ -154,6 +154,7 @@ def test_sgd_argument_errors(L):
     assert sgd(npos=4000, nneg=4000) == binding.OTF_ERR_UNSUPPORTED
     assert sgd(ws=None) == binding.OTF_ERR_WORKSPACE
     assert sgd(wsb=16) == binding.OTF_ERR_WORKSPACE
+    assert sgd(wsb=L.otf_sgd_workspace_bytes(8) - 1) == binding.OTF_ERR_WORKSPACE
 
 
 def test_encoder_argument_errors(L):
@@ -187,6 +188,13 @@ def test_sgd_pass_argument_errors(L):
     assert sgd(t=0) == binding.OTF_ERR_INVALID_ARG
     assert sgd(D=126) == binding.OTF_ERR_UNSUPPORTED
     assert sgd(wsb=16) == binding.OTF_ERR_WORKSPACE
+
+
+def test_check_indices_argument_errors(L):
+    assert L.otf_check_indices(None, 10, 10, FAKE, None) == binding.OTF_ERR_INVALID_ARG
+    assert L.otf_check_indices(FAKE, 10, 10, None, None) == binding.OTF_ERR_INVALID_ARG
+    assert L.otf_check_indices(FAKE, 0, 10, FAKE, None) == binding.OTF_ERR_INVALID_ARG
+    assert L.otf_check_indices(FAKE, 10, 0, FAKE, None) == binding.OTF_ERR_INVALID_ARG
 
 
 def test_pq_train_argument_errors(L):
