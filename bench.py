@@ -309,8 +309,16 @@ def measure_pq_encoder(torch, binding, synth, X=None):
     # `frac` counts the method's own flops, 2 N M K dsub, against the bf16 matrix peak (the pipe they run on).
     useful = 2.0 * N * M * 256 * dsub / (enc_ms * 1e-3) / 1e12
     executed = 7.0 * useful
+    # second half of a Lloyd iteration (sums per centre, move): one read of X and of the codes
+    move_ms = max(lloyd_ms - enc_ms, 1e-6)
+    move_gbs = (N * M * dsub * 4.0 + N * M) / (move_ms * 1e-3) / 1e9
     return {"workload": "pq_encode_1Mx2048_M128_K256", "encode_ms": enc_ms, "rows_per_s": N / (enc_ms * 1e-3),
-            "lloyd_step_ms": lloyd_ms, "dtype": "bf16 x 3 pieces per fp32 value, fp32 accumulate",
+            "lloyd_step_ms": lloyd_ms, "lloyd_sums_and_move_ms": move_ms,
+            "lloyd_sums_and_move": {"bound": "hbm", "achieved": move_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                    "frac": move_gbs / HBM_PEAK_GBS,
+                                    "note": "lloyd_step_ms - encode_ms: zeroing, the per-centre sums (64-bit fixed "
+                                            "point in shared memory) and the move; bytes = X + codes once"},
+            "dtype": "bf16 x 3 pieces per fp32 value, fp32 accumulate",
             "useful_fp32_tflops": useful, "useful_frac_of_fp32_matrix_peak": useful / MFMA_FP32_PEAK_TFLOPS,
             "executed_bf16_tflops": executed, "executed_frac_of_bf16_matrix_peak": executed / MFMA_BF16_PEAK_TFLOPS,
             "roofline": {"bound": "mfma", "achieved": useful, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",

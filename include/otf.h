@@ -301,10 +301,15 @@ int otf_binarize(const float *phi, int64_t N, int32_t m, int64_t ld_phi, const f
  * otf_pq_lloyd_step:  one k-means iteration on the training rows X.  The paper does not say how the
  *   centres are learned; the PQ method it cites uses k-means, taken here as Lloyd iterations from
  *   centres supplied by the caller: (1) codes = otf_pq_encode(X, codebooks); (2) every centre moves
- *   to the mean of the sub-vectors assigned to it, a centre with none stays (fp32 sums in an
- *   unspecified order).  codebooks is updated in place; codes receives the assignment of step (1);
- *   *distortion (one double in device memory, may be NULL) the mean over rows of the summed squared
- *   distances to the assigned centres, measured before the move.
+ *   to the mean of the sub-vectors assigned to it, a centre with none stays.  The sums are taken
+ *   in 64-bit fixed point, scaled from the largest sub-vector norm of X and from N so that no sum can
+ *   overflow (resolution at most 2^-30 of that norm for N < 2^31, 2^-41 at a million rows): the
+ *   new centres and the distortion are the same bits whatever the order the rows are added in, run
+ *   after run.  X must be finite.  codebooks is updated in place; codes receives the assignment of
+ *   step (1); *distortion (one double in device memory, may be NULL) the mean over rows of the
+ *   summed squared distances to the assigned centres, measured before the move and evaluated in
+ *   double precision as sum ||x||^2 + sum_k (n_k ||c_k||^2 - 2 <c_k, S_k>), S_k the sum and n_k the
+ *   number of the sub-vectors assigned to centre k (exact up to ~1e-15 of sum ||x||^2).
  *
  *   ws  at least otf_pq_train_workspace_bytes(M, dsub) bytes, 256-byte aligned.
  */

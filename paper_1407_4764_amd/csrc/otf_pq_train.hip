@@ -323,10 +323,11 @@ __device__ __forceinline__ u32x4 norm_operand_b(float n) {
 
 template <int DSUB>
 __global__ __launch_bounds__(256) void pq_centre_image_kernel(const float *__restrict__ codebooks, int M,
-                                                              uint8_t *__restrict__ image) {
+                                                              uint8_t *__restrict__ image, uint32_t *bound) {
     using P = Bf16Plan<DSUB>;
     const int m = blockIdx.x, k = threadIdx.x;
     if (m >= M) return;
+    if (m == 0 && k == 0) *bound = 0u;                     // the encoder behind this kernel takes a maximum into it
     const float *c = codebooks + ((size_t)m * kPqK + k) * DSUB;
     uint8_t *img = image + (size_t)m * kImgBytes;
     const int slot = (k & ~31) | (int)(__brev((uint32_t)(k & 31)) >> 27);   // lane r of the encoder holds the centre with r's bits reversed
@@ -361,13 +362,14 @@ __global__ __launch_bounds__(256) void pq_centre_image_kernel(const float *__res
 template <int DSUB>
 __global__ __launch_bounds__(256, 2) void pq_encode_bf16_kernel(const float *__restrict__ X, long long N, long long ldx,
                                                                 const uint8_t *__restrict__ image, int M, int mr,
-                                                                uint8_t *__restrict__ codes) {
+                                                                uint8_t *__restrict__ codes, uint32_t *bound) {
     using P = Bf16Plan<DSUB>;
     constexpr int NV = DSUB == 4 ? 1 : 2;                  // 16-byte loads of a row's components per lane and sub-block
     __shared__ __attribute__((aligned(16))) uint8_t img[2][kImgBytes];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 31, h = lane >> 5;
     const long long ntiles = (N + 255) / 256;
+    float largest = 0.f;                                   // of the squared sub-vector norms this lane meets
 
     // The image of sub-block m goes from global memory straight into shared memory, 1 KB (64 lanes x
     // 16 bytes) per instruction, without passing through registers; it is complete once the wave's
@@ -419,6 +421,7 @@ __global__ __launch_bounds__(256, 2) void pq_encode_bf16_kernel(const float *__r
                     split3(t0, t1, xp[0][d], xp[1][d], xp[2][d]);
                 }
                 if (DSUB == 16) ss += __shfl_xor(ss, 32, 64);  // the other half of the row's components
+                largest = fmaxf(largest, ss);
                 const u32x4 na = norm_operand_a(0.5f * ss), zero = {0u, 0u, 0u, 0u};
                 xn[f] = h == 0 ? na : zero;
 #pragma unroll
@@ -527,235 +530,261 @@ __global__ __launch_bounds__(256, 2) void pq_encode_bf16_kernel(const float *__r
             __syncthreads();
         }
     }
+    // A bound on every |x| the call has seen, for the fixed-point sums of the Lloyd iteration: the
+    // bit patterns of non-negative floats order like the floats.
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) largest = fmaxf(largest, __shfl_xor(largest, o, 64));
+    if (lane == 0) atomicMax(bound, __float_as_uint(largest));
 }
 
 // Lloyd iteration, second half: per-centre sums of the assigned sub-vectors, counts, and the
 // distortion.
 //
 // A floating-point add into shared memory by atomic is executed lane by lane on this chip (about
-// 190 cycles per wave instruction, against 8 for a plain read and write), so the sums are kept free
-// of atomics by ownership: a wave owns 16 consecutive feature dimensions (16/DSUB whole sub-blocks)
-// and their 16 KB of sums outright, and one wave instruction adds four rows x 16 dimensions with a
-// plain read-add-write.  The only hazard left is two of the four rows carrying the same code in the
-// same sub-block (about 2 % of the steps for well-spread codes): the four rows' codes are compared
-// and such a step is taken row by row instead.
+// 130 cycles per wave instruction), a 64-bit integer add at about 7.  So the sums are kept in fixed
+// point: a value x becomes the integer round(x * 2^F), with F chosen from a bound on |x| (the
+// largest squared sub-vector norm, which the encoder notes on its way) and from N so that neither a
+// value nor the sum of all N can leave 63 bits; for a million rows that leaves 2^-41 of the bound as
+// the resolution, far below the fp32 spacing of the values themselves.  Integer sums do not depend
+// on the order of the adds: the new centres are the same bits from run to run.
 //
-// A workgroup is two waves, i.e. the 32 dimensions of one 128-byte line per row; grid = (runs of 32
-// dimensions, slices of rows).  The workgroup reads its rows in whole lines (eight lanes per row)
-// and hands each wave its half through a double-buffered stage in shared memory: 64-byte reads
-// straight from the waves fetched nearly three times the bytes of X from HBM.  Every wave merges
-// its sums into global memory with atomics at the end.
-template <int GW>
-__device__ __forceinline__ bool code_words_clash(uint32_t a, uint32_t b) {
-    const uint32_t x = a ^ b;  // a byte of x is zero where the two rows carry the same code
-    if (GW == 1) return x == 0u;
-    if (GW == 2) return (x & 0xffu) == 0u || (x & 0xff00u) == 0u;
-    return ((x - 0x01010101u) & ~x & 0x80808080u) != 0u;
+// The conversion costs two instructions: in double precision x * 2^F + 1.5 * 2^52 has round(x * 2^F)
+// in its low mantissa bits, so the bit pattern of that sum is the integer plus the pattern of the
+// constant, and what is added to the cell is the pattern as it is.  A cell with n entries then holds
+// the fixed-point sum plus n times the constant's pattern (mod 2^64); n is the centre's count, and
+// pq_move_centres_kernel takes the multiple off again.
+//
+// A workgroup of eight waves owns 64 dimensions (256 bytes of every row, 64/DSUB whole sub-blocks)
+// and a slice of the rows; grid = (runs of 64 dimensions, slices), one workgroup per compute unit.
+// Sixteen lanes read a row's 256 bytes, four dimensions each, and add them to the cells of the
+// row's code: 128 KB of cells per workgroup, [sub-block][code][slot], where the four dimensions a
+// lane holds sit DSUB/4 cells apart and slot s of a code is stored at s ^ (bits of the code), so
+// that one instruction's 64 adds spread over the banks whatever the codes.  At the end the
+// workgroup adds its non-empty cells to the global ones.
+//
+// Reading a column of a row-major matrix is the slow part: 128-byte pieces come in at 5.4 TB/s,
+// 256-byte pieces at 6 TB/s, and only with about 32 KB in flight per compute unit (eight waves,
+// four loads each); more waves or deeper unrolling make the memory system slower, not faster.
+//
+// The distortion is not summed row by row: sum_i ||x_i - c_k(i)||^2 = sum_i ||x_i||^2 +
+// sum_k (n_k ||c_k||^2 - 2 <c_k, S_k>) with S_k the sum of the rows of cell k, so this kernel only
+// adds up ||x||^2 (in double precision: every square is exact) and the second sum falls out of the
+// move.  Partial sums go to a slot per workgroup and are added in a fixed order.
+constexpr unsigned long long kFixMagicBits = 0x4338000000000000ull;   // the double 1.5 * 2^52
+constexpr int kAccThreads = 512, kAccDims = 64;                        // dimensions per workgroup
+constexpr int kAccCells = kPqK * kAccDims;                            // its cells: 128 KB
+constexpr int kAccLanesPerRow = kAccDims / 4, kAccRowsPerInstr = 64 / kAccLanesPerRow;
+
+// F of the fixed-point format from the encoder's bound (bit pattern of the largest squared
+// sub-vector norm, a float >= 0) and the number of rows.
+__device__ __forceinline__ int fixed_point_shift(uint32_t bound_bits, long long N) {
+    const float b2 = __uint_as_float(bound_bits);
+    int e = 0;
+    if (b2 > 0.f && b2 < INFINITY) frexpf(b2, &e);         // b2 = f 2^e, f in [0.5, 1): |x| <= 2^ceil(e / 2)
+    const int eb = ((e + 1) >> 1) + 1;                     // one more for the rounding of the norm itself
+    const int lgn = N > 1 ? 64 - __clzll(N - 1) : 0;       // N <= 2^lgn
+    const int fmax = 62 - lgn < 51 ? 62 - lgn : 51;        // |round(x 2^F)| < 2^fmax: sums below 2^62, values below 2^51
+    return fmax - 1 - eb;
 }
 
 template <int DSUB>
-__global__ __launch_bounds__(128) void pq_accumulate_kernel(const float *__restrict__ X, long long N, long long ldx,
-                                                            const float *__restrict__ codebooks,
-                                                            const uint8_t *__restrict__ codes, int M, float *sums,
-                                                            uint32_t *counts, double *distortion) {
-    constexpr int GW = 16 / DSUB;  // sub-blocks per wave
-    constexpr int STEPS = 16;      // steps of four rows per batch: 64 rows, one row's codes per lane
-    constexpr int BATCH = 4 * STEPS;
-    __shared__ float lsum[2][GW * kPqK * DSUB];
-    __shared__ uint32_t lcnt[2][GW * kPqK];
-    __shared__ __align__(16) float stage[2][BATCH][32];
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int col0 = (blockIdx.x * 2 + wv) * 16;
-    // M * DSUB is a multiple of 16: a wave's dimensions exist all or not at all.  A wave without
-    // any still takes part in the staging and the barriers.
-    const bool live = col0 < M * DSUB;
-    const int m0 = live ? col0 / DSUB : 0;
-    float *ls = lsum[wv];
-    uint32_t *lc = lcnt[wv];
-    for (int i = lane; i < GW * kPqK * DSUB; i += 64) ls[i] = 0.f;
-    for (int i = lane; i < GW * kPqK; i += 64) lc[i] = 0u;
-    const int r4 = lane >> 4, c = lane & 15, g = c / DSUB, j = c % DSUB;
+struct AccLayout {
+    static constexpr int G = kAccDims / DSUB;              // sub-blocks per workgroup
+    static constexpr int Q = DSUB / 4;                     // lanes per row and sub-block = cells between a lane's dimensions
+    static constexpr int kRotShift = DSUB == 16 ? 1 : DSUB == 8 ? 2 : 3;   // codes per 256 bytes of cells: 2, 4, 8
+    __device__ static uint32_t rot(uint32_t code) { return (code >> kRotShift) & 3u; }
+};
+
+template <int DSUB, int U>
+__global__ __launch_bounds__(kAccThreads) void pq_accumulate_kernel(const float *__restrict__ X, long long N, long long ldx,
+                                                                     const uint8_t *__restrict__ codes, int M,
+                                                                     const uint32_t *__restrict__ bound,
+                                                                     unsigned long long *sums, uint32_t *counts,
+                                                                     double *__restrict__ xsq) {
+    using L = AccLayout<DSUB>;
+    constexpr int G = L::G, Q = L::Q;
+    extern __shared__ __align__(16) unsigned char acc_lds[];
+    unsigned long long *cells = reinterpret_cast<unsigned long long *>(acc_lds);         // [G][256][DSUB]
+    uint32_t *cnt = reinterpret_cast<uint32_t *>(acc_lds + kAccCells * 8);                // [G][256]
+    double *red = reinterpret_cast<double *>(acc_lds + kAccCells * 8 + G * kPqK * 4);     // one per wave
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < kAccCells; i += kAccThreads) cells[i] = 0ull;
+    for (int i = tid; i < G * kPqK; i += kAccThreads) cnt[i] = 0u;
+    const int rr = lane / kAccLanesPerRow, cc = lane % kAccLanesPerRow;   // row of the instruction's four, run of four dimensions
+    const int g = (4 * cc) / DSUB, cq = cc % Q;
+    const int col = blockIdx.x * kAccDims + 4 * cc;
+    // M * DSUB is a multiple of 16: a lane's four dimensions exist all or not at all
+    const bool col_live = col < M * DSUB;
+    const int m = col_live ? blockIdx.x * G + g : 0;
     const long long per = (N + gridDim.y - 1) / gridDim.y;
     const long long begin = per * blockIdx.y, end = begin + per < N ? begin + per : N;
     const int rows = end > begin ? (int)(end - begin) : 0;
-    const int batches = (rows + BATCH - 1) / BATCH;
-    // staging: thread = (row within 16, four of the 32 dimensions); four rows per thread and batch
-    const int srow = tid >> 3, scol = 4 * (tid & 7);
-    const bool scol_live = blockIdx.x * 32 + scol < M * DSUB;
-    const float *xstage = X + begin * ldx + (size_t)blockIdx.x * 32 + scol;
-    float4 xr[4];
-    // Rows past the end of the slice are read as its last row (in bounds) and left out by `valid`.
-    auto load_batch = [&](int n) {
+    const double scale = ldexp(1.0, fixed_point_shift(*bound, N));
+    const double magic = __longlong_as_double((long long)kFixMagicBits);
+    const uint32_t lane_base = (uint32_t)(g * kPqK * DSUB * 8 + cq * 8);
+    const float *xlane = X + begin * ldx + (col_live ? col : 0);
+    const uint8_t *klane = codes + begin * M + m;
+    double sq = 0.0;
+    __syncthreads();
+
+    float4 xa[U], xb[U];                                   // two rounds of rows, by name: no indexed registers
+    uint32_t ka[U], kb[U];
+    // Rows past the end of the slice are read as its last row (in bounds) and left out of the adds.
+    auto load = [&](int base, float4 (&xs)[U], uint32_t (&ks)[U]) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            int r = n * BATCH + srow + 16 * q;
+        for (int u = 0; u < U; ++u) {
+            int r = base + (u * (kAccThreads / 64) + wave) * kAccRowsPerInstr + rr;
             r = r < rows ? r : rows - 1;
-            xr[q] = scol_live ? *reinterpret_cast<const float4 *>(xstage + (long long)r * ldx) : make_float4(0.f, 0.f, 0.f, 0.f);
+            xs[u] = *reinterpret_cast<const float4 *>(xlane + (long long)r * ldx);
+            ks[u] = klane[(long long)r * M];
         }
     };
-    auto store_batch = [&](int buf) {
+    auto add = [&](int base, const float4 (&xs)[U], const uint32_t (&ks)[U], auto full) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) *reinterpret_cast<float4 *>(&stage[buf][srow + 16 * q][scol]) = xr[q];
-    };
-    auto load_codes = [&](int n) -> uint32_t {
-        int r = n * BATCH + lane;
-        r = r < rows ? r : rows - 1;
-        const uint8_t *p = codes + (size_t)(begin + r) * M + m0;
-        return GW == 1 ? (uint32_t)*p : GW == 2 ? (uint32_t)*reinterpret_cast<const uint16_t *>(p)
-                                                : *reinterpret_cast<const uint32_t *>(p);
-    };
-    const float *cb = codebooks + (size_t)(m0 + g) * kPqK * DSUB + j;
-    float *lmine = ls + g * kPqK * DSUB + j;
-    uint32_t *cmine = lc + g * kPqK;
-    double dist = 0.0;
-    uint32_t kv = 0u;
-
-    // this lane's code in step s of a batch whose rows' codes are held one per lane
-    auto lane_code = [&](uint32_t codes_of_rows, int s) -> int {
-        const uint32_t kw = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (4 * s + r4), (int)codes_of_rows);
-        return (int)((kw >> (8 * g)) & 255u);
-    };
-    // The assigned centres' values, for the distortion: gathers, asked for one batch ahead of their
-    // use.  Every code is that of a row of the slice, so they are in bounds.
-    float cv[STEPS];
-    auto gather_centres = [&](uint32_t codes_of_rows, float (&out)[STEPS]) {
+        for (int u = 0; u < U; ++u) {
+            const int r = base + (u * (kAccThreads / 64) + wave) * kAccRowsPerInstr + rr;
+            if (!col_live || !(full.value || r < rows)) continue;
+            const uint32_t code = ks[u];
+            const uint32_t a0 = (lane_base + code * (DSUB * 8)) | (L::rot(code) * (Q * 8));
+            const float v[4] = {xs[u].x, xs[u].y, xs[u].z, xs[u].w};
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) out[s] = cb[lane_code(codes_of_rows, s) * DSUB];
-    };
-
-    auto update = [&](int n, auto full) {
-        const float *xs = &stage[n & 1][r4][16 * wv + c];
-        // Rows that hold one code twice: within a step (its four rows sit in the four lanes of a
-        // quad of `kv`), and within a pair of steps (an octet of lanes), for all steps at once.
-        const uint32_t q1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)kv, 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
-        const uint32_t q2 = (uint32_t)__builtin_amdgcn_mov_dpp((int)kv, 0x4E, 0xF, 0xF, true);  // quad_perm [2,3,0,1]
-        const uint32_t q3 = (uint32_t)__builtin_amdgcn_mov_dpp((int)kv, 0x1B, 0xF, 0xF, true);  // quad_perm [3,2,1,0]
-        const uint32_t h0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)kv, 0x141, 0xF, 0xF, true);  // row_half_mirror: the other quad
-        const uint32_t h1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)h0, 0xB1, 0xF, 0xF, true);
-        const uint32_t h2 = (uint32_t)__builtin_amdgcn_mov_dpp((int)h0, 0x4E, 0xF, 0xF, true);
-        const uint32_t h3 = (uint32_t)__builtin_amdgcn_mov_dpp((int)h0, 0x1B, 0xF, 0xF, true);
-        const bool in_step = code_words_clash<GW>(kv, q1) || code_words_clash<GW>(kv, q2) || code_words_clash<GW>(kv, q3);
-        const bool in_pair = in_step || code_words_clash<GW>(kv, h0) || code_words_clash<GW>(kv, h1) ||
-                             code_words_clash<GW>(kv, h2) || code_words_clash<GW>(kv, h3);
-        const unsigned long long step_clashes = __ballot(in_step), pair_clashes = __ballot(in_pair);
-        // this lane's code in each step and the rows' values from the stage
-        int k[STEPS];
-        float x[STEPS];
-#pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            k[s] = lane_code(kv, s);
-            x[s] = xs[4 * s * 32];
-        }
-        auto valid = [&](int s) { return full.value || n * BATCH + 4 * s + r4 < rows; };
-        auto one_step = [&](int s) {
-            float *dst = lmine + k[s] * DSUB;
-            if (((step_clashes >> (4 * s)) & 0xFull) == 0ull) {
-                if (valid(s)) *dst = *dst + x[s];
-            } else {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    if (valid(s) && r4 == r) *dst = *dst + x[s];
-                    __builtin_amdgcn_wave_barrier();  // keeps the four row turns apart and in this order
-                }
+            for (int i = 0; i < 4; ++i) {
+                const double d = (double)v[i];
+                sq = fma(d, d, sq);
+                const unsigned long long fixed = (unsigned long long)__double_as_longlong(fma(d, scale, magic));
+                atomicAdd(reinterpret_cast<unsigned long long *>(acc_lds + (a0 ^ (uint32_t)(i * Q * 8))), fixed);
             }
-        };
-        float d = 0.f;
-#pragma unroll
-        for (int p = 0; p < STEPS / 2; ++p) {
-            const int s0 = 2 * p, s1 = 2 * p + 1;
-            if (((pair_clashes >> (8 * p)) & 0xFFull) == 0ull) {
-                // eight rows, eight different cells per sub-block: the two steps' updates overlap
-                float *d0 = lmine + k[s0] * DSUB, *d1 = lmine + k[s1] * DSUB;
-                const float a0 = *d0, a1 = *d1;
-                if (valid(s0)) *d0 = a0 + x[s0];
-                if (valid(s1)) *d1 = a1 + x[s1];
-            } else {
-                one_step(s0);
-                one_step(s1);
-            }
-#pragma unroll
-            for (int s = s0; s <= s1; ++s) {
-                if (valid(s) && j == 0) atomicAdd(cmine + k[s], 1u);
-                const float t = valid(s) ? x[s] - cv[s] : 0.f;
-                d = fmaf(t, t, d);
-            }
+            if (cq == 0) atomicAdd(cnt + g * kPqK + code, 1u);
         }
-        dist += (double)d;
     };
-
-    // Batch n is updated from stage[n & 1] while batch n + 1 moves from registers into the other
-    // half and batch n + 2 is on its way from memory; one barrier per batch.  Codes run two batches
-    // ahead of the updates, the centres' values one.
-    uint32_t kv1 = 0u;
-    if (batches > 0) {
-        load_batch(0);
-        store_batch(0);
-        if (batches > 1) load_batch(1);
-        if (live) {
-            kv = load_codes(0);
-            if (batches > 1) kv1 = load_codes(1);
-            gather_centres(kv, cv);
+    // the loads of one round of rows are in flight while the round before is added
+    constexpr int ROUND = kAccRowsPerInstr * (kAccThreads / 64) * U;
+    auto add_round = [&](int base, const float4 (&xs)[U], const uint32_t (&ks)[U]) {
+        if (base + ROUND <= rows) add(base, xs, ks, std::true_type{});
+        else add(base, xs, ks, std::false_type{});
+    };
+    if (rows > 0) load(0, xa, ka);
+    for (int base = 0; base < rows; base += 2 * ROUND) {
+        const bool second = base + ROUND < rows;
+        if (second) load(base + ROUND, xb, kb);
+        add_round(base, xa, ka);
+        if (second) {
+            if (base + 2 * ROUND < rows) load(base + 2 * ROUND, xa, ka);
+            add_round(base + ROUND, xb, kb);
         }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
+    if (lane == 0) red[wave] = sq;
+    __syncthreads();
+    if (tid == 0) {
+        double t = 0.0;
+        for (int w = 0; w < kAccThreads / 64; ++w) t += red[w];
+        xsq[(size_t)blockIdx.y * gridDim.x + blockIdx.x] = t;
+    }
+    // cell index -> (sub-block, code, dimension): slot s = position / Q holds dimension 4 q + (s ^ rot)
+    for (int i = tid; i < kAccCells; i += kAccThreads) {
+        const unsigned long long v = cells[i];
+        if (v == 0ull) continue;                           // never touched: a touched cell holds at least the constant's pattern
+        const int gg = i / (kPqK * DSUB), code = (i / DSUB) % kPqK, pos = i % DSUB;
+        const int j = 4 * (pos % Q) + ((pos / Q) ^ (int)L::rot((uint32_t)code));
+        const int mm = blockIdx.x * G + gg;
+        atomicAdd(&sums[((size_t)mm * kPqK + code) * DSUB + j], v);
+    }
+    for (int i = tid; i < G * kPqK; i += kAccThreads)
+        if (cnt[i]) atomicAdd(&counts[(size_t)blockIdx.x * G * kPqK + i], cnt[i]);
+}
+
+// the largest square of any element: the bound for the fixed-point sums when the encoder that notes
+// it on its way is not the one that ran (comparison route)
+__global__ __launch_bounds__(256) void pq_bound_kernel(const float *__restrict__ X, long long N, long long ldx, int D,
+                                                       uint32_t *bound) {
+    float mx = 0.f;
+    const long long total = N * (long long)(D / 4);
+    for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long long)gridDim.x * blockDim.x) {
+        const float4 v = *reinterpret_cast<const float4 *>(X + (t / (D / 4)) * ldx + 4 * (t % (D / 4)));
+        mx = fmaxf(fmaxf(fmaxf(mx, v.x * v.x), fmaxf(v.y * v.y, v.z * v.z)), v.w * v.w);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    if ((threadIdx.x & 63) == 0) atomicMax(bound, __float_as_uint(mx));
+}
+
+__global__ __launch_bounds__(256) void pq_zero_kernel(unsigned long long *sums, uint32_t *counts, uint32_t *ticket, int M,
+                                                      int dsub) {
+    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < (size_t)M * kPqK * dsub) sums[t] = 0ull;
+    if (t < (size_t)M * kPqK) counts[t] = 0u;
+    if (t == 0) *ticket = 0u;
+}
+
+// centre <- mean of its cell; a centre with an empty cell stays.  Also the distortion (mean over
+// rows of the squared distance to the assigned centre, the centres being those the rows were
+// assigned with): every thread contributes n c^2 - 2 c S of its cell, a workgroup's total goes to
+// its slot, and the workgroup that finishes last adds the slots and those of the accumulation in a
+// fixed order.
+__global__ __launch_bounds__(256) void pq_move_centres_kernel(float *codebooks, const unsigned long long *sums,
+                                                              const uint32_t *counts, int M, int dsub,
+                                                              const uint32_t *bound, long long N, const double *xsq,
+                                                              int n_xsq, double *cross, uint32_t *ticket,
+                                                              double *distortion_out) {
+    __shared__ double red[256];
+    __shared__ bool last;
+    double term = 0.0;
+    const size_t cells = (size_t)M * kPqK * dsub;
+    const double unit = ldexp(1.0, -fixed_point_shift(*bound, N));
+    for (size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x; t < cells; t += (size_t)gridDim.x * blockDim.x) {
+        const uint32_t n = counts[t / dsub];
+        if (n) {
+            const double s = (double)(long long)(sums[t] - (unsigned long long)n * kFixMagicBits) * unit;
+            const double c = (double)codebooks[t];
+            term += c * ((double)n * c - 2.0 * s);
+            codebooks[t] = (float)(s / (double)n);
+        }
+    }
+    if (!distortion_out) return;
+    auto block_sum = [&](double v) -> double {             // fixed tree: the same bits every run
+        red[threadIdx.x] = v;
+        __syncthreads();
+        for (int o = 128; o > 0; o >>= 1) {
+            if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+            __syncthreads();
+        }
+        const double r = red[0];
+        __syncthreads();
+        return r;
+    };
+    const double total = block_sum(term);
+    if (threadIdx.x == 0) {
+        cross[blockIdx.x] = total;
+        __threadfence();                                   // the slot before the ticket
+        last = atomicAdd(ticket, 1u) == gridDim.x - 1;
     }
     __syncthreads();
-    for (int n = 0; n < batches; ++n) {
-        if (n + 1 < batches) store_batch((n + 1) & 1);
-        if (n + 2 < batches) load_batch(n + 2);
-        if (live) {
-            uint32_t kv2 = 0u;
-            float cv1[STEPS];
-            if (n + 2 < batches) kv2 = load_codes(n + 2);
-            if (n + 1 < batches) gather_centres(kv1, cv1);
-            if ((n + 1) * BATCH <= rows) update(n, std::true_type{});
-            else update(n, std::false_type{});
-            kv = kv1;
-            kv1 = kv2;
-#pragma unroll
-            for (int s = 0; s < STEPS; ++s) cv[s] = cv1[s];
-        }
-        __syncthreads();
-    }
-    if (!live) return;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) dist += __shfl_xor(dist, o, 64);
-    for (int i = lane; i < GW * kPqK * DSUB; i += 64) {
-        const float v = ls[i];
-        if (v != 0.f) atomicAdd(&sums[(size_t)m0 * kPqK * DSUB + i], v);
-    }
-    for (int i = lane; i < GW * kPqK; i += 64)
-        if (lc[i]) atomicAdd(&counts[(size_t)m0 * kPqK + i], lc[i]);
-    if (lane == 0) atomicAdd(distortion, dist);
-}
-
-__global__ __launch_bounds__(256) void pq_zero_kernel(float *sums, uint32_t *counts, double *distortion, int M, int dsub) {
-    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < (size_t)M * kPqK * dsub) sums[t] = 0.f;
-    if (t < (size_t)M * kPqK) counts[t] = 0u;
-    if (t == 0) *distortion = 0.0;
-}
-
-// centre <- mean of its cell; a centre with an empty cell stays.  Also publishes the distortion
-// (mean over rows of the summed squared distances to the assigned centres).
-__global__ __launch_bounds__(256) void pq_move_centres_kernel(float *codebooks, const float *sums, const uint32_t *counts,
-                                                              int M, int dsub, const double *distortion, long long N,
-                                                              double *distortion_out) {
-    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < (size_t)M * kPqK * dsub) {
-        const uint32_t n = counts[t / dsub];
-        if (n) codebooks[t] = sums[t] / (float)n;
-    }
-    if (t == 0 && distortion_out) *distortion_out = *distortion / (double)N;
+    if (!last) return;
+    __threadfence();                                       // every workgroup's slot
+    double a = 0.0;
+    for (int i = threadIdx.x; i < (int)gridDim.x; i += 256) a += cross[i];
+    for (int i = threadIdx.x; i < n_xsq; i += 256) a += xsq[i];
+    const double sum = block_sum(a);
+    if (threadIdx.x == 0) *distortion_out = sum > 0.0 ? sum / (double)N : 0.0;
 }
 
 struct PqTrainWs {
-    float *norms, *sums;
+    uint32_t *bound, *ticket;
+    float *norms;
+    unsigned long long *sums;
     uint32_t *counts;
-    double *distortion;
+    double *xsq, *cross;
     uint8_t *image;                                        // the vocabulary as the bf16 encoder reads it
 };
 
+constexpr int kAccMaxGrid = 2048;                          // workgroups of the accumulation: slots for their ||x||^2
+
 static size_t pq_train_ws_tables(int M, int dsub) {
-    const size_t b = 256 + (size_t)M * kPqK * 4 + (size_t)M * kPqK * dsub * 4 + (size_t)M * kPqK * 4;
+    const size_t cells = (size_t)M * kPqK * dsub;
+    const size_t b = 256 + (size_t)M * kPqK * 4 /* norms */ + cells * 8 /* sums */ + (size_t)M * kPqK * 4 /* counts */ +
+                     (size_t)kAccMaxGrid * 8 + ((cells + 255) / 256) * 8;
     return (b + 255) & ~(size_t)255;
 }
 
@@ -765,11 +794,15 @@ size_t pq_train_ws_bytes(int M, int dsub) {
 
 static PqTrainWs pq_train_ws(void *ws, int M, int dsub) {
     uint8_t *p = reinterpret_cast<uint8_t *>(ws);
+    const size_t cells = (size_t)M * kPqK * dsub;
     PqTrainWs w;
-    w.distortion = reinterpret_cast<double *>(p);
-    w.norms = reinterpret_cast<float *>(p + 256);
-    w.sums = w.norms + (size_t)M * kPqK;
-    w.counts = reinterpret_cast<uint32_t *>(w.sums + (size_t)M * kPqK * dsub);
+    w.bound = reinterpret_cast<uint32_t *>(p);
+    w.ticket = w.bound + 1;
+    w.sums = reinterpret_cast<unsigned long long *>(p + 256);
+    w.xsq = reinterpret_cast<double *>(w.sums + cells);
+    w.cross = w.xsq + kAccMaxGrid;
+    w.norms = reinterpret_cast<float *>(w.cross + (cells + 255) / 256);
+    w.counts = reinterpret_cast<uint32_t *>(w.norms + (size_t)M * kPqK);
     w.image = p + pq_train_ws_tables(M, dsub);
     return w;
 }
@@ -787,8 +820,8 @@ hipError_t launch_pq_encode(const float *X, int64_t N, int64_t ldx, const float 
         pq_centre_norms_kernel<<<(M * kPqK + 255) / 256, 256, 0, s>>>(codebooks, M, dsub, w.norms);                          \
         pq_encode_kernel<D><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, w.norms, M, mr, codes);          \
     } else {                                                                                                                  \
-        pq_centre_image_kernel<D><<<M, 256, 0, s>>>(codebooks, M, w.image);                                                  \
-        pq_encode_bf16_kernel<D><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, w.image, M, mr, codes);               \
+        pq_centre_image_kernel<D><<<M, 256, 0, s>>>(codebooks, M, w.image, w.bound);                                         \
+        pq_encode_bf16_kernel<D><<<grid, 256, 0, s>>>(X, (long long)N, (long long)ldx, w.image, M, mr, codes, w.bound);      \
     }
     switch (dsub) {
         case 4: OTF_PQENC_LAUNCH(4) break;
@@ -800,26 +833,51 @@ hipError_t launch_pq_encode(const float *X, int64_t N, int64_t ldx, const float 
     return hipGetLastError();
 }
 
+template <int DSUB>
+static hipError_t launch_accumulate(const float *X, int64_t N, int64_t ldx, const uint8_t *codes, int M, const PqTrainWs &w,
+                                    dim3 grid, hipStream_t s) {
+    constexpr int U = 4;
+    const int lds = kAccCells * 8 + (kAccDims / DSUB) * kPqK * 4 + (kAccThreads / 64) * 8;
+    static bool raised = false;                            // more shared memory than a kernel gets unasked
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pq_accumulate_kernel<DSUB, U>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    pq_accumulate_kernel<DSUB, U><<<grid, kAccThreads, lds, s>>>(X, (long long)N, (long long)ldx, codes, M, w.bound, w.sums,
+                                                                  w.counts, w.xsq);
+    return hipGetLastError();
+}
+
 hipError_t launch_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *codebooks, int M, int dsub,
                                 uint8_t *codes, double *distortion_out, void *ws, hipStream_t s) {
     hipError_t e = launch_pq_encode(X, N, ldx, codebooks, M, dsub, codes, ws, s);
     if (e != hipSuccess) return e;
     PqTrainWs w = pq_train_ws(ws, M, dsub);
+    if (tune_int(OTF_DEBUG_PQENC_FP32, 0) != 0) {          // that encoder leaves no bound behind
+        pq_zero_kernel<<<1, 256, 0, s>>>(w.sums, w.counts, w.bound, 0, 0);
+        pq_bound_kernel<<<device_cu_count() * 4, 256, 0, s>>>(X, (long long)N, (long long)ldx, M * dsub, w.bound);
+    }
     const size_t cells = (size_t)M * kPqK * dsub;
-    pq_zero_kernel<<<(unsigned)((cells + 255) / 256), 256, 0, s>>>(w.sums, w.counts, w.distortion, M, dsub);
-    const int groups = (M * dsub + 31) / 32;
-    // three workgroups fit a compute unit (50 KB of shared memory each): one full round of them
-    int slices = (int)std::min<int64_t>((N + 4095) / 4096, std::max(1, device_cu_count() * 3 / groups));
-    if (slices < 1) slices = 1;
+    const unsigned cell_blocks = (unsigned)((cells + 255) / 256);
+    pq_zero_kernel<<<cell_blocks, 256, 0, s>>>(w.sums, w.counts, w.ticket, M, dsub);
+    const int groups = (M * dsub + kAccDims - 1) / kAccDims;
+    // one workgroup per compute unit (its cells fill most of the shared memory): one full round of them
+    int slices = (int)std::min<int64_t>((N + 1023) / 1024, std::max(1, device_cu_count() / groups));
+    slices = std::max(1, std::min(slices, kAccMaxGrid / groups));
     dim3 grid(groups, slices);
     switch (dsub) {
-        case 4: pq_accumulate_kernel<4><<<grid, 128, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, codes, M, w.sums, w.counts, w.distortion); break;
-        case 8: pq_accumulate_kernel<8><<<grid, 128, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, codes, M, w.sums, w.counts, w.distortion); break;
-        case 16: pq_accumulate_kernel<16><<<grid, 128, 0, s>>>(X, (long long)N, (long long)ldx, codebooks, codes, M, w.sums, w.counts, w.distortion); break;
+        case 4: e = launch_accumulate<4>(X, N, ldx, codes, M, w, grid, s); break;
+        case 8: e = launch_accumulate<8>(X, N, ldx, codes, M, w, grid, s); break;
+        case 16: e = launch_accumulate<16>(X, N, ldx, codes, M, w, grid, s); break;
         default: return hipErrorInvalidValue;
     }
-    pq_move_centres_kernel<<<(unsigned)((cells + 255) / 256), 256, 0, s>>>(codebooks, w.sums, w.counts, M, dsub, w.distortion,
-                                                                            (long long)N, distortion_out);
+    if (e != hipSuccess) return e;
+    // a workgroup per compute unit: each one ends with a device-wide fence, and those cost more than the cells
+    const unsigned move_blocks = std::min<unsigned>(cell_blocks, (unsigned)device_cu_count());
+    pq_move_centres_kernel<<<move_blocks, 256, 0, s>>>(codebooks, w.sums, w.counts, M, dsub, w.bound, (long long)N, w.xsq,
+                                                       groups * slices, w.cross, w.ticket, distortion_out);
     return hipGetLastError();
 }
 

@@ -141,6 +141,90 @@ def test_lloyd_step_when_many_rows_share_a_code(N, M, dsub):
     np.testing.assert_allclose(float(dist.cpu()[0]), dist_ref, rtol=1e-5)
 
 
+def test_lloyd_step_gives_the_same_bits_every_run():
+    """Fixed-point sums do not depend on the order of the adds: centres and distortion repeat bit for bit."""
+    N, M, dsub = 40000, 32, 16
+    X, C = _data(N, M, dsub, SEED + 8)
+    Xd = X.to(DEV)
+    ws = binding.pq_train_workspace(M, dsub)
+    runs = []
+    for _ in range(3):
+        Cd = C.to(DEV).clone()
+        _, dist = binding.pq_lloyd_step(Xd, Cd, ws)
+        torch.cuda.synchronize()
+        runs.append((Cd.cpu().numpy().copy(), dist.cpu().numpy().copy()))
+    for c, d in runs[1:]:
+        np.testing.assert_array_equal(c.view(np.uint32), runs[0][0].view(np.uint32))
+        np.testing.assert_array_equal(d.view(np.uint64), runs[0][1].view(np.uint64))
+
+
+@pytest.mark.parametrize("scale", [2.0 ** -40, 3.0e-5, 1.0, 7.0e5, 2.0 ** 50])
+@pytest.mark.parametrize("N,M,dsub", [(9000, 16, 8), (5000, 8, 16), (7000, 16, 4)])
+def test_lloyd_step_at_any_magnitude_of_the_data(N, M, dsub, scale):
+    """The fixed-point format follows the largest sub-vector norm of the data: the means keep their
+    relative accuracy when every value is tiny or huge, and with mixed signs."""
+    X, C = _data(N, M, dsub, SEED + 9)
+    g = torch.Generator().manual_seed(SEED + 10)
+    sign = torch.where(torch.rand(X.shape, generator=g) < 0.5, -1.0, 1.0)
+    X = (X * sign * scale).contiguous()
+    C = (C * scale).contiguous()
+    C[:, 128:] *= -1.0                                              # centres among the negative values too
+    Cd = C.to(DEV).clone()
+    ws = binding.pq_train_workspace(M, dsub)
+    codes, dist = binding.pq_lloyd_step(X.to(DEV), Cd, ws)
+    torch.cuda.synchronize()
+    codes = codes.cpu().numpy().astype(np.int64)
+    Xs = X.numpy().astype(np.float64).reshape(N, M, dsub)
+    C64 = C.numpy().astype(np.float64)
+    want = C64.copy()
+    d_sum = 0.0
+    for m in range(M):
+        cm = codes[:, m]
+        diff = Xs[:, m, :] - C64[m, cm]
+        d_sum += (diff * diff).sum()
+        counts = np.bincount(cm, minlength=256)
+        sums = np.zeros((256, dsub))
+        np.add.at(sums, cm, Xs[:, m, :])
+        nz = counts > 0
+        want[m, nz] = sums[nz] / counts[nz, None]
+    got = Cd.cpu().numpy().astype(np.float64)
+    # the mean of n values of size <= B, each rounded to 2^-41 B or better, then rounded to fp32
+    assert np.max(np.abs(got - want)) <= 2.0 ** -23 * np.abs(Xs).max()
+    np.testing.assert_allclose(float(dist.cpu()[0]), d_sum / N, rtol=1e-9)
+
+
+def test_distortion_of_rows_that_sit_on_their_centres_is_zero():
+    """The distortion is a difference of large sums; in double precision with exact fixed-point
+    sums it cancels to (almost) nothing when every row coincides with its centre."""
+    N, M, dsub = 6000, 16, 8
+    _, C = _data(8, M, dsub, SEED + 11)
+    g = torch.Generator().manual_seed(SEED + 12)
+    pick = torch.randint(0, 256, (N, M), generator=g)
+    X = torch.stack([C[m, pick[:, m]] for m in range(M)], dim=1).reshape(N, M * dsub).contiguous()
+    Cd = C.to(DEV).clone()
+    ws = binding.pq_train_workspace(M, dsub)
+    codes, dist = binding.pq_lloyd_step(X.to(DEV), Cd, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(codes.cpu().numpy(), pick.numpy().astype(np.uint8))
+    per_row_energy = float((X.double() ** 2).sum()) / N
+    assert 0.0 <= float(dist.cpu()[0]) <= 1e-13 * per_row_energy
+    np.testing.assert_array_equal(Cd.cpu().numpy(), C.numpy())       # the mean of equal values is that value
+
+
+def test_lloyd_step_behind_the_comparison_encoder(debug_switches):
+    """With the fp32 comparison encoder the bound for the fixed-point sums comes from a pass of its own."""
+    debug_switches({binding.DEBUG_PQENC_FP32: 1})
+    N, M, dsub = 6000, 16, 8
+    X, C = _data(N, M, dsub, SEED + 13)
+    Cd = C.to(DEV).clone()
+    ws = binding.pq_train_workspace(M, dsub)
+    ws.zero_()
+    _, dist = binding.pq_lloyd_step((X * 300.0).to(DEV), (Cd * 300.0).contiguous(), ws)
+    torch.cuda.synchronize()
+    C_ref, _, dist_ref = pq.lloyd_step((X * 300.0).numpy(), (C * 300.0).numpy())
+    np.testing.assert_allclose(float(dist.cpu()[0]), dist_ref, rtol=1e-5)
+
+
 def test_iterations_decrease_the_distortion_and_codes_feed_the_scan(oracle):
     N, M, dsub, k = 30000, 16, 8, 50
     X, C = _data(N, M, dsub, SEED + 4)
