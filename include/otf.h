@@ -23,6 +23,8 @@
  *     Scores must be finite; NaN/Inf inputs give unspecified (but in-range) rankings.
  *   - Return value: OTF_OK (0) or a negative otf_status.  Argument errors are detected on
  *     the host before anything is enqueued: then no buffer has been written.
+ *   - A leading dimension (ldx, ld, ld_phi; in elements) is at least the row length and small
+ *     enough that the whole store spans less than 2^48 bytes; otherwise OTF_ERR_INVALID_ARG.
  *   - `ws` is scratch device memory of at least otf_workspace_bytes(N, k, Q) bytes,
  *     256-byte aligned.  Its contents are undefined on entry and on exit.  Two calls that
  *     overlap in time (different streams) need different workspaces.
@@ -46,7 +48,10 @@ typedef enum {
     OTF_ERR_SCRATCH = -5      /* the call needs more scratch than a no-allocation entry point owns */
 } otf_status;
 
-typedef enum { OTF_F32 = 0, OTF_F16 = 1 } otf_dtype;
+/* Element type of a dense store or model.  An integer at the boundary, so that a value that names
+ * no type arrives as it was passed (and is answered with OTF_ERR_INVALID_ARG) in C and C++ alike. */
+typedef int32_t otf_dtype;
+enum { OTF_F32 = 0, OTF_F16 = 1 };
 
 /* Largest k any ranking call accepts. */
 #define OTF_MAX_K 8192

@@ -48,5 +48,48 @@ def build_library(jobs=6):
     return LIB
 
 
+# Host-side sanitizer builds (CPU only): the argument validation, workspace layout and switches of
+# otf_api.hip are host code; these flags instrument that code and leave the device code alone.
+HOST_SANITIZERS = {
+    # no runtime library needed, so the result can be loaded into any process: undefined behaviour traps
+    "ubsan-trap": ["-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fsanitize-trap=undefined"],
+    # needs the sanitizer runtime first in the process: for executables of our own
+    "asan-ubsan": ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                   "-Xarch_host", "-fno-sanitize-recover=undefined"],
+}
+
+
+def build_host_checked(kind, driver=None):
+    """otf_api.hip rebuilt with HOST_SANITIZERS[kind] and linked with the ordinary objects of the
+    other sources: into _build/libotf_<kind>.so, or, with `driver` (a C++ source that calls the C
+    ABI), into the executable _build/<driver name>_<kind>.  Returns the path."""
+    os.makedirs(BUILD, exist_ok=True)
+    others = []
+    for src in SOURCES:
+        if src == "otf_api.hip":
+            continue
+        obj = os.path.join(BUILD, src.replace(".hip", ".o"))
+        if not os.path.exists(obj) or os.path.getmtime(obj) < os.path.getmtime(os.path.join(CSRC, src)):
+            obj = _compile(src)
+        others.append(obj)
+    api = os.path.join(BUILD, "otf_api.%s.o" % kind)
+    cmd = ["hipcc"] + FLAGS + ["-O1", "-g"] + HOST_SANITIZERS[kind] + ["-c", os.path.join(CSRC, "otf_api.hip"), "-o", api]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed on otf_api.hip (%s):\n%s" % (kind, r.stdout + r.stderr))
+    if driver is None:
+        out = os.path.join(BUILD, "libotf_%s.so" % kind)
+        cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, api] + others
+    else:
+        out = os.path.join(BUILD, "%s_%s" % (os.path.splitext(os.path.basename(driver))[0], kind))
+        cmd = ["hipcc", "--offload-arch=gfx950", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
+               "-fno-sanitize-recover=undefined", "-fno-gpu-sanitize", "-I" + INCLUDE, "-x", "c++", driver,
+               "-x", "none", api] + others + ["-o", out]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed (%s):\n%s" % (kind, r.stdout + r.stderr))
+    return out
+
+
 if __name__ == "__main__":
     print(build_library())

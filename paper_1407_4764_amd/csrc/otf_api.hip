@@ -126,6 +126,9 @@ static bool debug_value_ok(int key, int v) {
     }
 }
 
+// No store spans more bytes than this: offsets into one stay far inside 64 bits.
+constexpr int64_t kMaxStoreBytes = (int64_t)1 << 48;
+
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 static int hip_status(hipError_t e) {
@@ -217,7 +220,7 @@ int otf_topk(const float *scores, int64_t N, int64_t ld, int32_t Q, int32_t k, f
     if (!scores) return OTF_ERR_INVALID_ARG;
     int rc = check_rank_common(N, k, Q, out_scores, out_idx, ws, ws_bytes, &L);
     if (rc != OTF_OK) return rc;
-    if (ld < N) return OTF_ERR_INVALID_ARG;
+    if (ld < N || ld > kMaxStoreBytes / 4 / Q) return OTF_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     SelectWs sw = select_ws(ws, L);
     if (Q == 1 && filter_eligible(N, k, nullptr))
@@ -239,7 +242,7 @@ static int otf_rank_dense_check(const void *X, otf_dtype xdt, int64_t N, int32_t
     if ((xdt != OTF_F32 && xdt != OTF_F16) || (wdt != OTF_F32 && wdt != OTF_F16)) return OTF_ERR_INVALID_ARG;
     int rc = check_rank_common(N, k, Q, out_scores, out_idx, ws, ws_bytes, &L);
     if (rc != OTF_OK) return rc;
-    if (ldx < D) return OTF_ERR_INVALID_ARG;
+    if (ldx < D || ldx > kMaxStoreBytes / 4 / N) return OTF_ERR_INVALID_ARG;   // rows that overlap; a store beyond any address
     const int xsize = xdt == OTF_F16 ? 2 : 4;
     if (!aligned16(X) || ((size_t)ldx * xsize) % 16 != 0) return OTF_ERR_INVALID_ARG;
     if (xdt == OTF_F32 && wdt != OTF_F32) return OTF_ERR_UNSUPPORTED;
@@ -519,15 +522,15 @@ size_t otf_sgd_workspace_bytes(int32_t B) {
 static int sgd_step_check(const float *w, int32_t D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,
                           int32_t n_pos, const float *Xneg, int64_t ld_neg, const int32_t *idx_neg, int32_t n_neg,
                           float lambda, int64_t t, const void *ws, size_t ws_bytes) {
-    if (!w || D < 1 || n_pos < 0 || n_neg < 0 || n_pos + n_neg < 1 || t < 1 || !(lambda > 0.f))
-        return OTF_ERR_INVALID_ARG;
+    const int64_t batch = (int64_t)n_pos + n_neg;         // the two may each be the largest int32
+    if (!w || D < 1 || n_pos < 0 || n_neg < 0 || batch < 1 || t < 1 || !(lambda > 0.f)) return OTF_ERR_INVALID_ARG;
     if (n_pos > 0 && (!Xpos || !idx_pos || ld_pos < D)) return OTF_ERR_INVALID_ARG;
     if (n_neg > 0 && (!Xneg || !idx_neg || ld_neg < D)) return OTF_ERR_INVALID_ARG;
-    if (D % 4 != 0 || n_pos + n_neg > 4096) return OTF_ERR_UNSUPPORTED;
+    if (D % 4 != 0 || batch > 4096) return OTF_ERR_UNSUPPORTED;
     if (!aligned16(w) || (n_pos > 0 && (!aligned16(Xpos) || ld_pos % 4 != 0)) ||
         (n_neg > 0 && (!aligned16(Xneg) || ld_neg % 4 != 0)))
         return OTF_ERR_INVALID_ARG;
-    if (!ws || ws_bytes < otf_sgd_workspace_bytes(n_pos + n_neg) || (reinterpret_cast<uintptr_t>(ws) & 15u))
+    if (!ws || ws_bytes < otf_sgd_workspace_bytes((int32_t)batch) || (reinterpret_cast<uintptr_t>(ws) & 15u))
         return OTF_ERR_WORKSPACE;
     return OTF_OK;
 }
@@ -592,7 +595,8 @@ int otf_tight_frame(const float *G, int32_t n, int32_t m, float *U, void *ws, si
 
 int otf_binarize(const float *phi, int64_t N, int32_t m, int64_t ld_phi, const float *U, int32_t n, uint32_t *bits,
                  void *stream) {
-    if (!phi || !U || !bits || N < 1 || m < 1 || n < 1 || ld_phi < m) return OTF_ERR_INVALID_ARG;
+    if (!phi || !U || !bits || N < 1 || m < 1 || n < 1 || ld_phi < m || ld_phi > kMaxStoreBytes / 4 / N)
+        return OTF_ERR_INVALID_ARG;
     if (!aligned16(phi) || !aligned16(U) || ld_phi % 4 != 0) return OTF_ERR_INVALID_ARG;
     if (N >= ((int64_t)1 << 31)) return OTF_ERR_UNSUPPORTED;
     if (m % 4 != 0 || m > 128 || n % 32 != 0 || n > 65536) return OTF_ERR_UNSUPPORTED;
@@ -606,7 +610,8 @@ size_t otf_pq_train_workspace_bytes(int32_t M, int32_t dsub) {
 
 static int pq_train_args(const float *X, int64_t N, int64_t ldx, const float *codebooks, int32_t M, int32_t K,
                          int32_t dsub, const uint8_t *codes, const void *ws, size_t ws_bytes) {
-    if (!X || !codebooks || !codes || N < 1 || M < 1 || K < 1 || dsub < 1 || ldx < (int64_t)M * dsub)
+    if (!X || !codebooks || !codes || N < 1 || M < 1 || K < 1 || dsub < 1 || ldx < (int64_t)M * dsub ||
+        ldx > kMaxStoreBytes / 4 / N)
         return OTF_ERR_INVALID_ARG;
     if (!aligned16(X) || !aligned16(codebooks) || ldx % 4 != 0 || (reinterpret_cast<uintptr_t>(codes) & 3u))
         return OTF_ERR_INVALID_ARG;
