@@ -253,6 +253,32 @@ def measure_topk(torch, binding, synth):
                          "note": "algorithmic bytes = one read of the scores, which is what the call does; the rest of the time is five dependent launches (sample, filter, sort, two gated fallback kernels) and the final sort"}}
 
 
+def measure_filter_fallback(steps, warmup, torch, binding, synth):
+    """Worst case of the filtered ranking: the PQ store of the benchmark with 10,000 rows of the
+    maximum score planted where the sample never looks, so that the candidate list overflows after
+    a complete filtered scan and the call redoes the ranking by full selection (second scan, three
+    selection passes, exact split of a 10,000-way tie by row number)."""
+    step, cfg = make_workload("pq", 1.0, torch, binding, synth)
+    codes, cb, w = cfg["_keep"]
+    N, k = cfg["N"], cfg["k"]
+    lut = binding.pq_build_lut(cb, w)
+    best = lut.argmax(dim=1).to(torch.uint8)
+    normal_ms, _ = time_steps(step, steps, warmup, torch, binding)
+    codes[2048:12048] = best                               # row groups the sample scan skips
+    ws = binding.make_workspace(N, k, 1, "cuda")
+    out = binding._outputs(1, k, "cuda")
+    planted = lambda: binding.rank_pq_model(codes, cb, w, 0.0, k, ws, out=out)
+    planted()
+    taken = binding.debug_fallback_taken(ws)
+    first = int(out[1][0, 0].item())
+    worst_ms, _ = time_steps(planted, steps, warmup, torch, binding)
+    return {"workload": "pq_20Mx128B_filter_fallback_worst_case", "fallback_taken": bool(taken),
+            "first_row_returned": first,
+            "ms_per_step": worst_ms * 1e3, "ms_per_step_without_planted_rows": normal_ms * 1e3,
+            "slowdown": worst_ms / normal_ms, "value": N / worst_ms, "unit": "vectors/s",
+            "note": "filtered scan + gated rescan with histogram + passes 2 and 3 + gather + sort; rows 2048.. tie at the top"}
+
+
 def measure_onthefly(torch, binding, synth, X=None):
     """The on-the-fly loop on the dense store (paper Sec. 4, "On-line (GPU back-end)"): 12 rounds of
     64 Pegasos steps (B = 256) on a pool of positives growing by 12 per round, each followed by a
@@ -452,6 +478,7 @@ def main():
     ap.add_argument("--pqenc-only", action="store_true", help="only time the PQ encoder and a Lloyd iteration")
     ap.add_argument("--topk-only", action="store_true", help="only time otf_topk on ready-made scores")
     ap.add_argument("--sgd-only", action="store_true", help="only time the Pegasos training pass")
+    ap.add_argument("--fallback-only", action="store_true", help="only time the worst case of the filtered ranking")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 2 GiB five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -483,6 +510,9 @@ def main():
         return
     if args.pqenc_only:
         print(json.dumps(measure_pq_encoder(torch, binding, synth)))
+        return
+    if args.fallback_only:
+        print(json.dumps(measure_filter_fallback(args.steps, max(args.warmup, 100), torch, binding, synth)))
         return
     if args.loop_only:
         print(json.dumps(measure_onthefly(torch, binding, synth)))
@@ -532,6 +562,7 @@ def main():
             others.append(r)
         others.append(measure_sgd(torch, binding, synth))
         others.append(measure_topk(torch, binding, synth))
+        others.append(measure_filter_fallback(args.steps, max(args.warmup, 100), torch, binding, synth))
         others.append(measure_encoder(torch, binding, synth))
         others.append(loop if loop is not None else measure_onthefly(torch, binding, synth))
         others.append(pqenc if pqenc is not None else measure_pq_encoder(torch, binding, synth))

@@ -360,6 +360,8 @@ typedef enum {
     OTF_DEBUG_WALK_TILES,            /* 2, 4 or 8 tiles of 64 rows per wave and block, table scans of rows > 128 bytes */
     OTF_DEBUG_SGD_PASS_PATH,         /* 1: otf_svm_sgd_pass as one kernel for the whole run (D <= 2048) */
     OTF_DEBUG_SGD_SPIN_LIMIT,        /* polls after which a wait of the one-launch training run gives up (default 2^20) */
+    OTF_DEBUG_MEET_SPIN_LIMIT,       /* polls after which a workgroup of the fallback selection stops waiting for the
+                                        others between passes (default 2^16); then one workgroup finishes alone */
     OTF_DEBUG_KEYS
 } otf_debug_key;
 

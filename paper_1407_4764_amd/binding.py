@@ -32,7 +32,8 @@ EXPORTS = ["otf_status_string", "otf_workspace_bytes", "otf_rank_dense", "otf_pq
 # otf_debug_key
 (DEBUG_RANK_PATH, DEBUG_BINARIZE_FP32, DEBUG_PQENC_FP32, DEBUG_SCAN_THREADS, DEBUG_SCAN_UNROLL, DEBUG_BINARIZE_WAVES,
  DEBUG_PQENC_RANGE, DEBUG_DENSE_BLOCKS_PER_CU, DEBUG_NARROW_BLOCKS_PER_CU, DEBUG_MFMA_BLOCKS_PER_CU,
- DEBUG_PQENC_BLOCKS_PER_CU, DEBUG_WALK_TILES, DEBUG_SGD_PASS_PATH, DEBUG_SGD_SPIN_LIMIT, DEBUG_KEYS) = range(15)
+ DEBUG_PQENC_BLOCKS_PER_CU, DEBUG_WALK_TILES, DEBUG_SGD_PASS_PATH, DEBUG_SGD_SPIN_LIMIT, DEBUG_MEET_SPIN_LIMIT,
+ DEBUG_KEYS) = range(16)
 
 _lib = None
 

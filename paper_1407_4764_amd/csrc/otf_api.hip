@@ -116,7 +116,8 @@ static bool debug_value_ok(int key, int v) {
         case OTF_DEBUG_BINARIZE_WAVES: return v == 4 || v == 8;
         case OTF_DEBUG_WALK_TILES: return v == 2 || v == 4 || v == 8;
         case OTF_DEBUG_SGD_PASS_PATH: return v == 1;
-        case OTF_DEBUG_SGD_SPIN_LIMIT: return v >= 1 && v <= (1 << 30);
+        case OTF_DEBUG_SGD_SPIN_LIMIT:
+        case OTF_DEBUG_MEET_SPIN_LIMIT: return v >= 1 && v <= (1 << 30);
         case OTF_DEBUG_PQENC_RANGE: return v >= 4 && v <= 64 && v % 4 == 0;
         case OTF_DEBUG_DENSE_BLOCKS_PER_CU:
         case OTF_DEBUG_NARROW_BLOCKS_PER_CU:

@@ -52,8 +52,12 @@ struct SelState {
     uint32_t spare;
     uint32_t tau_key;  // filter threshold: rows with key >= tau_key are candidates (filtered scans)
     uint32_t fallback; // set by the filtered path when its candidate list cannot serve: redo by full selection
+    // meeting points of the workgroups of the one-launch selection (select_fused_gated_kernel)
+    uint32_t met[2];   // arrivals at meeting point 0, 1
+    uint32_t verdict[2];   // 0: open, 1: all arrived, go on together, 2: somebody stopped waiting, the last arrival goes on alone
+    uint32_t pad[12];
 };
-static_assert(sizeof(SelState) == 64, "SelState layout");
+static_assert(sizeof(SelState) == 128, "SelState layout");
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -616,37 +616,85 @@ __global__ __launch_bounds__(kSortThreads) void filter_sort_kernel(SelState *st_
 // returns at once still costs ~4 us on the stream: four such launches (passes 2 and 3, gather,
 // sort) were a twentieth of a ranking call.  This kernel does their work behind one gate:
 //   every workgroup   resolves pass 1 (the gated scan accumulated its histogram).  Decisive (the
-//                     usual case): gathers the candidates of its share of the rows.  Not decisive:
-//                     adds its share of the pass-2 histogram.  Then it takes a ticket.
-//   the last one      (the ticket tells; device-wide fences on both sides of it make the others'
-//                     work visible) sorts the list, or -- scores that crowd into one 12-bit bin or tie
-//                     by the thousand -- finishes passes 2 and 3 and the gather by itself over all
-//                     rows: slower than the chain of launches, but only when a fallback meets such
-//                     scores, and always exact.
+//                     usual case): gathers the candidates of its share of the rows, takes a ticket,
+//                     and the workgroup that draws the last one sorts the list.
+//   not decisive      (scores that crowd into one 12-bit bin or tie by the thousand: integer scores
+//                     of short binary codes, duplicated rows) the passes that follow each need
+//                     the sum of what all workgroups found in the pass before.  The workgroups
+//                     MEET between passes: each announces its arrival (a counter in global memory,
+//                     device-wide fences on both sides) and waits for the verdict of the last one
+//                     to arrive.  The wait is bounded.  If nobody has given up, the last arrival's
+//                     verdict is "together" and every workgroup takes its share of the next pass
+//                     (pass 2's histogram, then either the gather, or pass 3 with per-workgroup tie
+//                     counts and a gather that hands the ties out in row order).  If a wait ran out
+//                     first (the workgroups were not all resident: another kernel held the compute
+//                     units), the verdict is "alone": the waiting workgroups leave, and the last
+//                     arrival -- which exists, never waits, and finds the work of all the others
+//                     complete -- finishes the remaining passes over all rows by itself, slowly
+//                     but exactly.  `meet` = 0 (the grid may exceed what is resident at once: many
+//                     classifiers) goes that way from the start.
 // Stand-alone selection (otf_topk, scans that materialise their scores) keeps the chain: there
 // every pass runs, and a fence per workgroup would cost more than the launches.
+enum MeetRole : uint32_t { kTogether = 1u, kAlone = 2u, kLeave = 3u };
+constexpr uint32_t kMeetSpinLimit = 1u << 16;               // polls of ~1 us: far beyond a pass over any store
+                                                            // (diagnostic switch OTF_DEBUG_MEET_SPIN_LIMIT: 1 makes every wait give up)
+
+// Whole workgroup.  Everything this workgroup wrote before the call is visible to whoever goes on.
+__device__ __forceinline__ MeetRole meet(uint32_t *met, uint32_t *verdict, uint32_t groups, uint32_t spin_limit,
+                                         uint32_t *s_role) {
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t role;
+        const uint32_t before = __hip_atomic_fetch_add(met, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        if (before == groups - 1u) {                        // the last to arrive gives the verdict
+            role = atomicCAS(verdict, 0u, 1u) == 0u ? kTogether : kAlone;
+        } else {
+            uint32_t v = 0u;
+            for (uint32_t it = 0; it < spin_limit; ++it) {
+                v = __hip_atomic_load(verdict, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (v != 0u) break;
+                __builtin_amdgcn_s_sleep(8);
+            }
+            if (v == 0u) {                                  // gave up; unless the verdict came in this very moment
+                v = atomicCAS(verdict, 0u, 2u);
+                if (v == 0u) v = 2u;
+            }
+            role = v == 1u ? kTogether : kLeave;
+        }
+        *s_role = role;
+    }
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");      // the others' histograms, not stale cache lines
+    return (MeetRole)*s_role;
+}
+
 __global__ __launch_bounds__(kSortThreads) void select_fused_gated_kernel(const float *__restrict__ scores,
                                                                            long long N, long long ld, int k,
                                                                            SelState *st_all, const uint32_t *hist1_all,
-                                                                           uint32_t *hist2_all,
+                                                                           uint32_t *hist2_all, uint32_t *hist3_all,
+                                                                           uint32_t *blockhist3_all,
                                                                            unsigned long long *cand_all,
-                                                                           float *out_scores, int32_t *out_idx) {
+                                                                           float *out_scores, int32_t *out_idx, int meet_ok,
+                                                                           uint32_t spin_limit) {
     extern __shared__ __attribute__((aligned(16))) uint8_t sort_lds[];
     __shared__ uint32_t lhist[kBins2];
     __shared__ uint32_t s_out[3];
-    __shared__ uint32_t s_last;
+    __shared__ uint32_t s_last, s_role;
+    __shared__ uint32_t wave_sum_s[16];
     if (st_all[0].fallback == 0u) return;                  // uniform over the grid
     const int q = blockIdx.y;
     SelState *st = st_all + q;
     const float *s = scores + (long long)q * ld;
     const bool vec_ok = row_vec_ok(s);
     unsigned long long *cand = cand_all + (size_t)q * kCandCap;
-    uint32_t *hist2 = hist2_all + (size_t)q * kBins2;
+    uint32_t *hist2 = hist2_all + (size_t)q * kBins2, *hist3 = hist3_all + (size_t)q * kBins3;
     const BinChoice r1 = block_find_bin(hist1_all + (size_t)q * kHist1Words, kBins1, (uint32_t)k, lhist, s_out, kHistShards);
     const uint32_t b1 = r1.bin, need1 = (uint32_t)k - r1.above, c1 = r1.above + r1.inbin;
     const bool decisive1 = c1 <= (uint32_t)kCandCap;
     long long begin, end;
     sel_chunk(N, blockIdx.x, gridDim.x, &begin, &end);
+    uint32_t n = c1;
+    bool alone = false;                                    // this workgroup finishes over all rows by itself
     if (decisive1) {
         gather_rows(s, begin, end, vec_ok, ((long long)b1 << 20) - 1, false, 0u, 0u, 0u, k, st, cand);
     } else {
@@ -657,16 +705,70 @@ __global__ __launch_bounds__(kSortThreads) void select_fused_gated_kernel(const 
             hist_add_wave(lhist, (key >> 8) & 0xFFFu, ok && (key >> 20) == b1);
         });
         merge_hist(lhist, kBins2, hist2);
+        if (meet_ok) {
+            const MeetRole role = meet(&st->met[0], &st->verdict[0], gridDim.x, spin_limit, &s_role);
+            if (role == kLeave) return;                    // uniform over the workgroup
+            alone = role == kAlone;
+        }
     }
-    // ticket: the workgroup that draws the last one continues alone
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) s_last = atomicAdd(&st->spare, 1u) == gridDim.x - 1u ? 1u : 0u;
-    __syncthreads();
-    if (s_last == 0u) return;                              // uniform over the workgroup
-    __threadfence();
-    uint32_t n = c1;
-    if (!decisive1) {
+    if (!decisive1 && meet_ok && !alone) {
+        // together: pass 2 is complete in global memory
+        const BinChoice r2 = block_find_bin(hist2, kBins2, need1, lhist, s_out);
+        const uint32_t p24 = (b1 << 12) | r2.bin, need2 = need1 - r2.above;
+        const uint32_t c2 = ((uint32_t)k - need1) + r2.above + r2.inbin;     // keys >= p24 << 8
+        if (c2 <= (uint32_t)kCandCap) {
+            gather_rows(s, begin, end, vec_ok, ((long long)p24 << 8) - 1, false, 0u, 0u, 0u, k, st, cand);
+            n = c2;
+        } else {
+            // pass 3, every workgroup its share; its own counts stay behind for the split of the ties
+            __syncthreads();
+            for (int b = threadIdx.x; b < kBins3; b += blockDim.x) lhist[b] = 0u;
+            __syncthreads();
+            for_each_score(s, begin, end, vec_ok, [&](float v, bool ok, long long) {
+                const uint32_t key = float_to_key(v);
+                hist_add_wave(lhist, key & 0xFFu, ok && (key >> 8) == p24);
+            });
+            __syncthreads();
+            uint32_t *bh = blockhist3_all + ((size_t)q * kSelBlocks + blockIdx.x) * kBins3;
+            for (int b = threadIdx.x; b < kBins3; b += blockDim.x) bh[b] = lhist[b];
+            merge_hist(lhist, kBins3, hist3);
+            const MeetRole role = meet(&st->met[1], &st->verdict[1], gridDim.x, spin_limit, &s_role);
+            if (role == kLeave) return;
+            const BinChoice r3 = block_find_bin(hist3, kBins3, need2, lhist, s_out);
+            const uint32_t T = (p24 << 8) | r3.bin, r = need2 - r3.above;
+            if (role == kAlone) {
+                gather_rows(s, 0, N, vec_ok, (long long)T, true, T, r, 0u, k, st, cand);
+                __threadfence();
+                __syncthreads();
+                select_sort_emit(sort_lds, cand, (uint32_t)k, k, out_scores + (size_t)q * k, out_idx + (size_t)q * k);
+                return;
+            }
+            // ties of the workgroups before this one (their rows are lower): they are served first
+            const uint32_t *col = blockhist3_all + (size_t)q * kSelBlocks * kBins3 + r3.bin;
+            uint32_t mine = 0u, eqbase = 0u;
+            for (int b = threadIdx.x; b < (int)blockIdx.x; b += blockDim.x) mine += col[(size_t)b * kBins3];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o, 64);
+            if ((threadIdx.x & 63) == 0) wave_sum_s[threadIdx.x >> 6] = mine;
+            __syncthreads();
+            for (int w = 0; w < (int)(blockDim.x >> 6); ++w) eqbase += wave_sum_s[w];
+            __syncthreads();
+            gather_rows(s, begin, end, vec_ok, (long long)T, eqbase < r, T, r, eqbase, k, st, cand);
+            n = (uint32_t)k;
+        }
+    }
+    // ticket: the workgroup that draws the last one continues alone (and a workgroup that already
+    // is alone has no one to wait for)
+    if (!alone) {
+        __threadfence();
+        __syncthreads();
+        if (threadIdx.x == 0) s_last = atomicAdd(&st->spare, 1u) == gridDim.x - 1u ? 1u : 0u;
+        __syncthreads();
+        if (s_last == 0u) return;                          // uniform over the workgroup
+        __threadfence();
+    }
+    if (!decisive1 && (alone || !meet_ok)) {
+        // passes 2 (resolve), 3 and the gather over all rows by this workgroup
         const BinChoice r2 = block_find_bin(hist2, kBins2, need1, lhist, s_out);
         const uint32_t p24 = (b1 << 12) | r2.bin, need2 = need1 - r2.above;
         const uint32_t c2 = ((uint32_t)k - need1) + r2.above + r2.inbin;     // keys >= p24 << 8
@@ -674,7 +776,6 @@ __global__ __launch_bounds__(kSortThreads) void select_fused_gated_kernel(const 
             gather_rows(s, 0, N, vec_ok, ((long long)p24 << 8) - 1, false, 0u, 0u, 0u, k, st, cand);
             n = c2;
         } else {
-            // pass 3 over all rows by this workgroup: the k-th key itself and how many of its equals belong
             for (int b = threadIdx.x; b < kBins3; b += blockDim.x) lhist[b] = 0u;
             __syncthreads();
             for_each_score(s, 0, N, vec_ok, [&](float v, bool ok, long long) {
@@ -822,8 +923,12 @@ hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q,
     if (gated) {                                   // the fallback of a filtered scan: one launch behind one gate
         hipError_t e = allow_sort_lds();
         if (e != hipSuccess) return e;
+        // the workgroups may wait for each other only if all of them are resident at once: one per compute unit
+        const int meet_ok = (int64_t)grid.x * grid.y <= device_cu_count() && sw.hist3 && sw.blockhist3 ? 1 : 0;
         select_fused_gated_kernel<<<grid, kSortThreads, kSortLdsBytes, s>>>(scores, N, ld, k, sw.st, sw.hist1, sw.hist2,
-                                                                            sw.cand, out_scores, out_idx);
+                                                                            sw.hist3, sw.blockhist3, sw.cand, out_scores,
+                                                                            out_idx, meet_ok,
+                                                                            (uint32_t)tune_int(OTF_DEBUG_MEET_SPIN_LIMIT, (int)kMeetSpinLimit));
         return hipGetLastError();
     }
     // (1024 threads: the histogram passes hide the latency of their votes and shared-memory adds behind more waves)

@@ -87,6 +87,8 @@ def test_rank_dense_argument_errors(L):
     assert _dense(L, D=32768, ldx=32768) == binding.OTF_ERR_UNSUPPORTED
     assert _dense(L, wsb=1024) == binding.OTF_ERR_WORKSPACE
     assert _dense(L, k=2000) == binding.OTF_ERR_INVALID_ARG                # k > N
+    assert _dense(L, ldx=1 << 60) == binding.OTF_ERR_INVALID_ARG           # a store of more than 2^48 bytes
+    assert _dense(L, xdt=-3) == binding.OTF_ERR_INVALID_ARG
 
 
 def test_pq_and_binary_argument_errors(L):
@@ -152,6 +154,7 @@ def test_sgd_argument_errors(L):
     assert sgd(ldp=64) == binding.OTF_ERR_INVALID_ARG
     assert sgd(D=126, ldp=128, ldn=128) == binding.OTF_ERR_UNSUPPORTED
     assert sgd(npos=4000, nneg=4000) == binding.OTF_ERR_UNSUPPORTED
+    assert sgd(npos=2 ** 31 - 1, nneg=2 ** 31 - 1) == binding.OTF_ERR_UNSUPPORTED    # the sum does not wrap
     assert sgd(ws=None) == binding.OTF_ERR_WORKSPACE
     assert sgd(wsb=16) == binding.OTF_ERR_WORKSPACE
     assert sgd(wsb=L.otf_sgd_workspace_bytes(8) - 1) == binding.OTF_ERR_WORKSPACE

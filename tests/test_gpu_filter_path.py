@@ -250,3 +250,28 @@ def test_multi_classifier_zero_models_are_called_off(oracle):
     for q in range(1, Q, 6):
         ok, msg = oracle.topk_parity_ok(ref[q], k, idx[q].cpu().numpy(), val[q].cpu().numpy(), RTOL16)
         assert ok, "q=%d: %s" % (q, msg)
+
+
+@pytest.mark.parametrize("spin_limit", [0, 1])
+def test_fallback_with_crowded_scores_but_no_big_tie(oracle, spin_limit, debug_switches):
+    """Scores that crowd into one 12-bit bin of the key (all between 1 and 1.06) without tying: the
+    full selection behind a failed filtered scan needs pass 2 and a gather by all workgroups."""
+    if spin_limit:
+        debug_switches({binding.DEBUG_MEET_SPIN_LIMIT: spin_limit})
+    N, D, k = 1_400_000, 128, 700
+    g = torch.Generator().manual_seed(SEED + 40)
+    X = torch.zeros((N, D), dtype=torch.float32)
+    X[:, 0] = 1.0 + 0.06 * torch.rand(N, generator=g)              # one live dimension: the score is this value
+    X[65536 * 3 + 2048:65536 * 3 + 32048, 0] = 1.0599              # a plateau the sample never visits overflows the list
+    w = torch.zeros(D)
+    w[0] = 1.0
+    ws = binding.make_workspace(N, k)
+    val, idx = binding.rank_dense(X.to(DEV), w.to(DEV), None, k, ws)
+    torch.cuda.synchronize()
+    ref = oracle.dense_scores(X.numpy(), w.numpy())[0]
+    ok, msg = oracle.topk_parity_ok(ref, k, idx[0].cpu().numpy(), val[0].cpu().numpy(), RTOL32)
+    assert ok, msg
+    assert binding.debug_fallback_taken(ws)
+    i, v = oracle.topk(ref, k)                                      # one live dimension with weight 1: the scores are exact
+    np.testing.assert_array_equal(idx[0].cpu().numpy(), i)
+    np.testing.assert_array_equal(val[0].cpu().numpy().astype(np.float64), v)

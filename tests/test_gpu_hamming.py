@@ -73,3 +73,31 @@ def test_identical_rows_tie_by_row_index(oracle):
     bits = query[None, :].repeat(N, 1).contiguous()
     bits[:, 0] ^= 5
     _check(oracle, bits, D, query, k)
+
+
+@pytest.mark.parametrize("spin_limit", [0, 1])
+@pytest.mark.parametrize("N,D,k,free_bits", [(3_000_000, 128, 1000, 12), (2_200_000, 256, 1, 8), (1_300_000, 128, 1024, 6),
+                                             (1_300_000, 128, 8192, 10)])
+def test_ties_by_the_ten_thousand_at_the_kth_distance(oracle, N, D, k, free_bits, spin_limit, debug_switches):
+    """Rows that differ from the query in a few bit positions only: millions of rows share a handful
+    of distances and the k-th distance is shared by more rows than any candidate list holds.  The
+    filtered scan is called off, and the full selection behind it must split the tie by row number
+    with all its workgroups (passes 2 and 3 and the gather, between meeting points).  spin_limit = 1
+    makes every wait at a meeting point give up at once: then one workgroup finishes alone, and the
+    answer must be the same."""
+    if spin_limit:
+        debug_switches({binding.DEBUG_MEET_SPIN_LIMIT: spin_limit})
+    g = torch.Generator().manual_seed(SEED + 20 + D)
+    query = synth.binary_bits_random(1, D // 32, SEED + 21 + D)[0]
+    bits = query.repeat(N, 1)
+    bits[:, 1] ^= torch.randint(0, 1 << free_bits, (N,), generator=g, dtype=torch.int32)
+    bits = bits.contiguous()
+    ref = oracle.hamming_scores(synth.as_uint32(bits.numpy()), D, synth.as_uint32(query.numpy()))
+    i, v = oracle.topk(ref, k)
+    assert (ref == v[-1]).sum() > 8192                             # the tie the test is about
+    ws = binding.make_workspace(N, k)
+    val, idx = binding.rank_hamming(bits.to(DEV), D, query.to(DEV), k, ws)
+    torch.cuda.synchronize()
+    assert binding.debug_fallback_taken(ws) == (k <= 1024)          # longer lists never take the filtered route
+    np.testing.assert_array_equal(idx[0].cpu().numpy(), i)
+    np.testing.assert_array_equal(val[0].cpu().numpy().astype(np.float64), v)
