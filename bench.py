@@ -35,8 +35,13 @@ HBM_PEAK_GBS = 8000.0
 # command scaled by the same counters on a plain copy of known size.  The line says so
 # ("traffic_source"), and a workload that is scaled down or has no counter run yet reports null.
 TRAFFIC_SOURCE = "profiles/traffic_counters.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not measured in this run)"
-MEASURED_TRAFFIC_BYTES = {          # read + written
+MEASURED_TRAFFIC_BYTES = {          # read + written, per launch of the scoring kernel
+    "dense": 8198008010, "pq": 2590228917, "pq512": 2598162714, "pq256": 2594092640, "binary": 12825251201,
+    "hamming": 12825183612, "dense128": 5131105014, "dense128h": 5131044388, "sparse128": 2450816187,
+    "multiquery": 20488076562,
 }
+TOPK_TRAFFIC_BYTES = 200157996      # topk_filter_kernel on 50M scores
+LLOYD_SUMS_TRAFFIC_BYTES = 8597935062   # pq_accumulate_kernel on 1M x 2048 (X once, the codes once per die)
 
 WORKLOADS = {
     "dense": dict(name="dense_1Mx2048_fp32_top1000", N=1_000_000, D=2048, k=1000, row_bytes=8192, dtype="f32"),
@@ -249,7 +254,8 @@ def measure_topk(torch, binding, synth):
     dt = (time.perf_counter() - t0) / reps
     return {"workload": "topk_50M_scores_k1000", "ms_per_call": dt * 1e3, "scores_per_s": N / dt,
             "roofline": {"bound": "hbm", "achieved": 4.0 * N / dt / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": 4.0 * N / dt / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                         "frac": 4.0 * N / dt / 1e9 / HBM_PEAK_GBS, "traffic": TOPK_TRAFFIC_BYTES,
+                         "traffic_source": TRAFFIC_SOURCE,
                          "note": "algorithmic bytes = one read of the scores, which is what the call does; the rest of the time is five dependent launches (sample, filter, sort, two gated fallback kernels) and the final sort"}}
 
 
@@ -341,7 +347,8 @@ def measure_pq_encoder(torch, binding, synth, X=None):
     return {"workload": "pq_encode_1Mx2048_M128_K256", "encode_ms": enc_ms, "rows_per_s": N / (enc_ms * 1e-3),
             "lloyd_step_ms": lloyd_ms, "lloyd_sums_and_move_ms": move_ms,
             "lloyd_sums_and_move": {"bound": "hbm", "achieved": move_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                    "frac": move_gbs / HBM_PEAK_GBS,
+                                    "frac": move_gbs / HBM_PEAK_GBS, "traffic": LLOYD_SUMS_TRAFFIC_BYTES,
+                                    "traffic_source": TRAFFIC_SOURCE,
                                     "note": "lloyd_step_ms - encode_ms: zeroing, the per-centre sums (64-bit fixed "
                                             "point in shared memory) and the move; bytes = X + codes once"},
             "dtype": "bf16 x 3 pieces per fp32 value, fp32 accumulate",
@@ -479,6 +486,8 @@ def main():
     ap.add_argument("--topk-only", action="store_true", help="only time otf_topk on ready-made scores")
     ap.add_argument("--sgd-only", action="store_true", help="only time the Pegasos training pass")
     ap.add_argument("--fallback-only", action="store_true", help="only time the worst case of the filtered ranking")
+    ap.add_argument("--switch", action="append", default=[], metavar="NAME=VALUE",
+                    help="set a diagnostic switch of the library first (binding.DEBUG_<NAME>), e.g. --switch PQENC_FP32=1")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 2 GiB five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -490,6 +499,9 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     binding.lib()                                  # fail loudly if the HIP library is missing
+    for item in args.switch:
+        name, _, value = item.partition("=")
+        binding.debug_set(getattr(binding, "DEBUG_" + name.upper()), int(value))
     if args.calibrate_copy:
         src = torch.full((1 << 29,), 1.0, dtype=torch.float32, device="cuda")     # 2 GiB
         dst = torch.empty_like(src)

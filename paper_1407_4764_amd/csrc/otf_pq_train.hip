@@ -555,7 +555,7 @@ __global__ __launch_bounds__(256, 2) void pq_encode_bf16_kernel(const float *__r
 // pq_move_centres_kernel takes the multiple off again.
 //
 // A workgroup of eight waves owns 64 dimensions (256 bytes of every row, 64/DSUB whole sub-blocks)
-// and a slice of the rows; grid = (runs of 64 dimensions, slices), one workgroup per compute unit.
+// and a slice of the rows; runs x slices workgroups, one per compute unit.
 // Sixteen lanes read a row's 256 bytes, four dimensions each, and add them to the cells of the
 // row's code: 128 KB of cells per workgroup, [sub-block][code][slot], where the four dimensions a
 // lane holds sit DSUB/4 cells apart and slot s of a code is stored at s ^ (bits of the code), so
@@ -600,7 +600,7 @@ __global__ __launch_bounds__(kAccThreads) void pq_accumulate_kernel(const float 
                                                                      const uint8_t *__restrict__ codes, int M,
                                                                      const uint32_t *__restrict__ bound,
                                                                      unsigned long long *sums, uint32_t *counts,
-                                                                     double *__restrict__ xsq) {
+                                                                     double *__restrict__ xsq, int slices) {
     using L = AccLayout<DSUB>;
     constexpr int G = L::G, Q = L::Q;
     extern __shared__ __align__(16) unsigned char acc_lds[];
@@ -608,16 +608,21 @@ __global__ __launch_bounds__(kAccThreads) void pq_accumulate_kernel(const float 
     uint32_t *cnt = reinterpret_cast<uint32_t *>(acc_lds + kAccCells * 8);                // [G][256]
     double *red = reinterpret_cast<double *>(acc_lds + kAccCells * 8 + G * kPqK * 4);     // one per wave
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // Workgroups go to the chip's eight dies in turn.  Consecutive numbers are the slices of one run of
+    // dimensions, so (with eight slices) a die holds all the column runs of ONE slice of rows, and the
+    // line of codes of a row, which every run needs two to sixteen bytes of, is fetched into one
+    // die's cache instead of eight.
+    const int run = blockIdx.x / slices, slice = blockIdx.x % slices;
     for (int i = tid; i < kAccCells; i += kAccThreads) cells[i] = 0ull;
     for (int i = tid; i < G * kPqK; i += kAccThreads) cnt[i] = 0u;
     const int rr = lane / kAccLanesPerRow, cc = lane % kAccLanesPerRow;   // row of the instruction's four, run of four dimensions
     const int g = (4 * cc) / DSUB, cq = cc % Q;
-    const int col = blockIdx.x * kAccDims + 4 * cc;
+    const int col = run * kAccDims + 4 * cc;
     // M * DSUB is a multiple of 16: a lane's four dimensions exist all or not at all
     const bool col_live = col < M * DSUB;
-    const int m = col_live ? blockIdx.x * G + g : 0;
-    const long long per = (N + gridDim.y - 1) / gridDim.y;
-    const long long begin = per * blockIdx.y, end = begin + per < N ? begin + per : N;
+    const int m = col_live ? run * G + g : 0;
+    const long long per = (N + slices - 1) / slices;
+    const long long begin = per * slice, end = begin + per < N ? begin + per : N;
     const int rows = end > begin ? (int)(end - begin) : 0;
     const double scale = ldexp(1.0, fixed_point_shift(*bound, N));
     const double magic = __longlong_as_double((long long)kFixMagicBits);
@@ -680,7 +685,7 @@ __global__ __launch_bounds__(kAccThreads) void pq_accumulate_kernel(const float 
     if (tid == 0) {
         double t = 0.0;
         for (int w = 0; w < kAccThreads / 64; ++w) t += red[w];
-        xsq[(size_t)blockIdx.y * gridDim.x + blockIdx.x] = t;
+        xsq[blockIdx.x] = t;
     }
     // cell index -> (sub-block, code, dimension): slot s = position / Q holds dimension 4 q + (s ^ rot)
     for (int i = tid; i < kAccCells; i += kAccThreads) {
@@ -688,11 +693,11 @@ __global__ __launch_bounds__(kAccThreads) void pq_accumulate_kernel(const float 
         if (v == 0ull) continue;                           // never touched: a touched cell holds at least the constant's pattern
         const int gg = i / (kPqK * DSUB), code = (i / DSUB) % kPqK, pos = i % DSUB;
         const int j = 4 * (pos % Q) + ((pos / Q) ^ (int)L::rot((uint32_t)code));
-        const int mm = blockIdx.x * G + gg;
+        const int mm = run * G + gg;
         atomicAdd(&sums[((size_t)mm * kPqK + code) * DSUB + j], v);
     }
     for (int i = tid; i < G * kPqK; i += kAccThreads)
-        if (cnt[i]) atomicAdd(&counts[(size_t)blockIdx.x * G * kPqK + i], cnt[i]);
+        if (cnt[i]) atomicAdd(&counts[(size_t)run * G * kPqK + i], cnt[i]);
 }
 
 // the largest square of any element: the bound for the fixed-point sums when the encoder that notes
@@ -835,7 +840,7 @@ hipError_t launch_pq_encode(const float *X, int64_t N, int64_t ldx, const float 
 
 template <int DSUB>
 static hipError_t launch_accumulate(const float *X, int64_t N, int64_t ldx, const uint8_t *codes, int M, const PqTrainWs &w,
-                                    dim3 grid, hipStream_t s) {
+                                    int groups, int slices, hipStream_t s) {
     constexpr int U = 4;
     const int lds = kAccCells * 8 + (kAccDims / DSUB) * kPqK * 4 + (kAccThreads / 64) * 8;
     static bool raised = false;                            // more shared memory than a kernel gets unasked
@@ -845,8 +850,8 @@ static hipError_t launch_accumulate(const float *X, int64_t N, int64_t ldx, cons
         if (e != hipSuccess) return e;
         raised = true;
     }
-    pq_accumulate_kernel<DSUB, U><<<grid, kAccThreads, lds, s>>>(X, (long long)N, (long long)ldx, codes, M, w.bound, w.sums,
-                                                                  w.counts, w.xsq);
+    pq_accumulate_kernel<DSUB, U><<<groups * slices, kAccThreads, lds, s>>>(X, (long long)N, (long long)ldx, codes, M, w.bound,
+                                                                             w.sums, w.counts, w.xsq, slices);
     return hipGetLastError();
 }
 
@@ -866,11 +871,10 @@ hipError_t launch_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *c
     // one workgroup per compute unit (its cells fill most of the shared memory): one full round of them
     int slices = (int)std::min<int64_t>((N + 1023) / 1024, std::max(1, device_cu_count() / groups));
     slices = std::max(1, std::min(slices, kAccMaxGrid / groups));
-    dim3 grid(groups, slices);
     switch (dsub) {
-        case 4: e = launch_accumulate<4>(X, N, ldx, codes, M, w, grid, s); break;
-        case 8: e = launch_accumulate<8>(X, N, ldx, codes, M, w, grid, s); break;
-        case 16: e = launch_accumulate<16>(X, N, ldx, codes, M, w, grid, s); break;
+        case 4: e = launch_accumulate<4>(X, N, ldx, codes, M, w, groups, slices, s); break;
+        case 8: e = launch_accumulate<8>(X, N, ldx, codes, M, w, groups, slices, s); break;
+        case 16: e = launch_accumulate<16>(X, N, ldx, codes, M, w, groups, slices, s); break;
         default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;

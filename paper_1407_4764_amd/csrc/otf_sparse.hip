@@ -30,7 +30,7 @@
 // them with lane shuffles, and the third register is refilled from memory a window or more before
 // its contents are needed, so no load of an offset ever stands between two windows.
 //
-// Work distribution: tiles of 256 rows from a TileQueue (chunks of 1024 rows).
+// Work distribution: tiles of 1024 rows (256 in the sample scan) from a TileQueue, four tiles per chunk.
 #include <algorithm>
 
 #include "otf_internal.h"
@@ -41,7 +41,10 @@ constexpr int kSparseD = 128;
 constexpr int kSparseMaskWords = kSparseD / 32;
 constexpr int kWinWords = 2048;                       // window: 8 loads x 64 lanes x 4 words
 constexpr int kWinBufWords = kWinWords + 8;           // + slack: a lane may read one word past its row's last value
-constexpr int kSparseTileRows = 256;
+// rows per tile: a tile ends with a window that is only partly its own (the rest is read again by the
+// wave that owns the next tile), so long scans take large tiles; the sample's short pieces small ones
+template <int EMIT>
+constexpr int kSparseTileRows = EMIT == kEmitSample ? 256 : 1024;
 constexpr int kSparseThreads = 256;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -71,7 +74,7 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
     if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
     uint32_t *chunk_ctr = &st->chunk_ctr[EMIT == kEmitScores ? 1 : 0];
     if (threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);
-    const long long total_tiles = (N + kSparseTileRows - 1) / kSparseTileRows;
+    const long long total_tiles = (N + kSparseTileRows<EMIT> - 1) / kSparseTileRows<EMIT>;
     const uint32_t chunk_tiles = tile_queue_chunk_tiles(total_tiles, 4u);
     uint32_t tau = 0u;
     if (EMIT == kEmitFilter) {
@@ -164,8 +167,8 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
         const long long tile = tile_queue_draw(&s_queue, chunk_ctr, chunk_tiles, total_tiles);
         if (tile < 0) break;                                        // uniform per wave
         // output rows [v, ve) of this tile are store rows [r, r + ve - v) (the sample: a piece of one group)
-        long long v = tile * kSparseTileRows;
-        const long long ve = v + kSparseTileRows < N ? v + kSparseTileRows : N;
+        long long v = tile * kSparseTileRows<EMIT>;
+        const long long ve = v + kSparseTileRows<EMIT> < N ? v + kSparseTileRows<EMIT> : N;
         long long r = EMIT == kEmitSample ? ((v >> 10) * ((long long)kSampleGroup * kSampleStride) + (v & 1023)) : v;
         const long long re = r + (ve - v);
         // start[] of rows rb + lane, rb + 64 + lane, rb + 128 + lane (capped at the tile's end, whose
@@ -242,7 +245,7 @@ static hipError_t launch_sparse_cfg(const uint32_t *rows, const int64_t *start, 
                                     const float *w, float bias, float *scores, SelState *st, uint32_t *hist1,
                                     const SelState *tau, SampleSlot *slots, unsigned long long *cand,
                                     const SelState *gate, hipStream_t s) {
-    const int64_t tiles = (N + kSparseTileRows - 1) / kSparseTileRows;
+    const int64_t tiles = (N + kSparseTileRows<EMIT> - 1) / kSparseTileRows<EMIT>;
     const int grid = (int)std::min<int64_t>((tiles + 3) / 4, (int64_t)device_cu_count() * 3);
     sparse_scan_kernel<EMIT><<<grid < 1 ? 1 : grid, kSparseThreads, 0, s>>>(
         rows, reinterpret_cast<const long long *>(start), (long long)N, (long long)store_rows, w, bias, scores, st, hist1,
