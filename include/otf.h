@@ -178,9 +178,9 @@ int otf_rank_sparse(const uint32_t *rows, const int64_t *start, int64_t N, int32
                     float *all_scores, void *ws, size_t ws_bytes, void *stream);
 
 /*
- * Hamming ranking of the binarised store (paper Sec. 3.1, discussion after Table 2: the ranking of
- * binary codes "can also be significantly sped-up using hardware-accelerated Hamming distance",
- * which needs a ranking model other than the linear SVM and is left open there).  The model here
+ * Hamming ranking of the binarised store (paper Sec. 3.1, discussion after Table 2: binary codes
+ * could be ranked faster still by Hamming distances, which the hardware computes cheaply; that
+ * needs a ranking model other than the linear SVM and is left open there).  The model here
  * is a query code of D bits in the layout of the rows; nearer rows rank first:
  *
  *   scores[i] = -(number of dimensions d < D with bit_{i,d} != query bit d)      (exact)
@@ -329,8 +329,8 @@ int otf_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *codebooks, 
 /*
  * Diagnostics (host, not part of the paper's method; for benchmarks that must time the
  * scoring kernel by itself).  Between otf_profile_begin and otf_profile_end every otf_rank_*
- * call brackets its scoring kernel(s) with a pair of HIP events on the call's stream, at most
- * max_records calls.  otf_profile_end waits for the recorded events, returns the summed
+ * call brackets its scoring kernel(s), and every otf_pq_lloyd_step call the kernel of its
+ * per-centre sums, with a pair of HIP events on the call's stream, at most max_records calls.  otf_profile_end waits for the recorded events, returns the summed
  * kernel time in milliseconds and the number of calls recorded, and releases the events.
  * Process-wide state, not thread-safe; returns OTF_ERR_INVALID_ARG when misused.
  */

@@ -25,8 +25,8 @@
  *                      enters the model as 2b-1.
  *   orc_hamming_scores Sec. 3.1, discussion after Table 2: ranking binary codes by Hamming
  *                      distance, which the paper names as the way to speed their ranking up
- *                      and leaves for later.  The "different ranking model" it needs is taken
- *                      to be a query code; a row's score is minus its distance to it.
+ *                      and leaves for later.  The ranking model it needs in place of the linear
+ *                      SVM is taken to be a query code; a row's score is minus its distance to it.
  *   orc_sparse_expand  Sec. 3.1, same discussion: ConvNet features are very sparse (the 128-D
  *                      ones over 60 % zeros), a compression the paper points at but does not
  *                      build.  The store keeps a presence mask and the non-zero values of a

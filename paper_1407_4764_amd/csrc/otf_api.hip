@@ -634,8 +634,14 @@ int otf_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *codebooks, 
                       uint8_t *codes, double *distortion, void *ws, size_t ws_bytes, void *stream) {
     const int rc = pq_train_args(X, N, ldx, codebooks, M, K, dsub, codes, ws, ws_bytes);
     if (rc != OTF_OK) return rc;
-    return hip_status(launch_pq_lloyd_step(X, N, ldx, codebooks, M, dsub, codes, distortion, ws,
-                                           reinterpret_cast<hipStream_t>(stream)));
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    hipError_t e = launch_pq_lloyd_assign(X, N, ldx, codebooks, M, dsub, codes, ws, s);
+    if (e != hipSuccess) return hip_status(e);
+    ScanTimer timer(s);                                    // the kernel of the per-centre sums, for otf_profile_*
+    e = launch_pq_lloyd_sums(X, N, ldx, codes, M, dsub, ws, s);
+    timer.stop();
+    if (e != hipSuccess) return hip_status(e);
+    return hip_status(launch_pq_lloyd_move(N, codebooks, M, dsub, distortion, ws, s));
 }
 
 int otf_debug_set(int key, int value) {

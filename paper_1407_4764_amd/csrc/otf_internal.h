@@ -152,8 +152,12 @@ hipError_t launch_binarize(const float *phi, int64_t N, int m, int64_t ld, const
 size_t pq_train_ws_bytes(int M, int dsub);
 hipError_t launch_pq_encode(const float *X, int64_t N, int64_t ldx, const float *codebooks, int M, int dsub,
                             uint8_t *codes, void *ws, hipStream_t s);
-hipError_t launch_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *codebooks, int M, int dsub,
-                                uint8_t *codes, double *distortion_out, void *ws, hipStream_t s);
+hipError_t launch_pq_lloyd_assign(const float *X, int64_t N, int64_t ldx, const float *codebooks, int M, int dsub,
+                                  uint8_t *codes, void *ws, hipStream_t s);
+hipError_t launch_pq_lloyd_sums(const float *X, int64_t N, int64_t ldx, const uint8_t *codes, int M, int dsub, void *ws,
+                                hipStream_t s);
+hipError_t launch_pq_lloyd_move(int64_t N, float *codebooks, int M, int dsub, double *distortion_out, void *ws,
+                                hipStream_t s);
 
 int device_cu_count();
 

@@ -855,8 +855,11 @@ static hipError_t launch_accumulate(const float *X, int64_t N, int64_t ldx, cons
     return hipGetLastError();
 }
 
-hipError_t launch_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *codebooks, int M, int dsub,
-                                uint8_t *codes, double *distortion_out, void *ws, hipStream_t s) {
+// A Lloyd iteration in three parts, so that the caller can bracket the middle one with events:
+// assignment (encode; a bound on |x| if the encoder left none; zeroed sums), the per-centre sums,
+// the move.
+hipError_t launch_pq_lloyd_assign(const float *X, int64_t N, int64_t ldx, const float *codebooks, int M, int dsub,
+                                  uint8_t *codes, void *ws, hipStream_t s) {
     hipError_t e = launch_pq_encode(X, N, ldx, codebooks, M, dsub, codes, ws, s);
     if (e != hipSuccess) return e;
     PqTrainWs w = pq_train_ws(ws, M, dsub);
@@ -865,19 +868,38 @@ hipError_t launch_pq_lloyd_step(const float *X, int64_t N, int64_t ldx, float *c
         pq_bound_kernel<<<device_cu_count() * 4, 256, 0, s>>>(X, (long long)N, (long long)ldx, M * dsub, w.bound);
     }
     const size_t cells = (size_t)M * kPqK * dsub;
-    const unsigned cell_blocks = (unsigned)((cells + 255) / 256);
-    pq_zero_kernel<<<cell_blocks, 256, 0, s>>>(w.sums, w.counts, w.ticket, M, dsub);
-    const int groups = (M * dsub + kAccDims - 1) / kAccDims;
-    // one workgroup per compute unit (its cells fill most of the shared memory): one full round of them
-    int slices = (int)std::min<int64_t>((N + 1023) / 1024, std::max(1, device_cu_count() / groups));
-    slices = std::max(1, std::min(slices, kAccMaxGrid / groups));
+    pq_zero_kernel<<<(unsigned)((cells + 255) / 256), 256, 0, s>>>(w.sums, w.counts, w.ticket, M, dsub);
+    return hipGetLastError();
+}
+
+// runs of 64 dimensions x slices of rows: one workgroup per compute unit (its cells fill most of the
+// shared memory), one full round of them
+static void lloyd_grid(int64_t N, int M, int dsub, int *groups, int *slices) {
+    *groups = (M * dsub + kAccDims - 1) / kAccDims;
+    int sl = (int)std::min<int64_t>((N + 1023) / 1024, std::max(1, device_cu_count() / *groups));
+    *slices = std::max(1, std::min(sl, kAccMaxGrid / *groups));
+}
+
+hipError_t launch_pq_lloyd_sums(const float *X, int64_t N, int64_t ldx, const uint8_t *codes, int M, int dsub, void *ws,
+                                hipStream_t s) {
+    PqTrainWs w = pq_train_ws(ws, M, dsub);
+    int groups, slices;
+    lloyd_grid(N, M, dsub, &groups, &slices);
     switch (dsub) {
-        case 4: e = launch_accumulate<4>(X, N, ldx, codes, M, w, groups, slices, s); break;
-        case 8: e = launch_accumulate<8>(X, N, ldx, codes, M, w, groups, slices, s); break;
-        case 16: e = launch_accumulate<16>(X, N, ldx, codes, M, w, groups, slices, s); break;
+        case 4: return launch_accumulate<4>(X, N, ldx, codes, M, w, groups, slices, s);
+        case 8: return launch_accumulate<8>(X, N, ldx, codes, M, w, groups, slices, s);
+        case 16: return launch_accumulate<16>(X, N, ldx, codes, M, w, groups, slices, s);
         default: return hipErrorInvalidValue;
     }
-    if (e != hipSuccess) return e;
+}
+
+hipError_t launch_pq_lloyd_move(int64_t N, float *codebooks, int M, int dsub, double *distortion_out, void *ws,
+                                hipStream_t s) {
+    PqTrainWs w = pq_train_ws(ws, M, dsub);
+    int groups, slices;
+    lloyd_grid(N, M, dsub, &groups, &slices);
+    const size_t cells = (size_t)M * kPqK * dsub;
+    const unsigned cell_blocks = (unsigned)((cells + 255) / 256);
     // a workgroup per compute unit: each one ends with a device-wide fence, and those cost more than the cells
     const unsigned move_blocks = std::min<unsigned>(cell_blocks, (unsigned)device_cu_count());
     pq_move_centres_kernel<<<move_blocks, 256, 0, s>>>(codebooks, w.sums, w.counts, M, dsub, w.bound, (long long)N, w.xsq,

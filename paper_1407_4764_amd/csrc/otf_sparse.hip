@@ -1,7 +1,7 @@
 // Dense scoring of a sparse-row store of 128-D features.
 //
 // Paper Sec. 3.1 (discussion after Table 2): the ConvNet features are very sparse, the 128-D ones
-// typically over 60 % zeros, and a compression "geared to capitalise on this sparsity" is named
+// typically more than three fifths zeros, and a compression built around that sparsity is named
 // as a way to shrink the store further.  This store keeps, per row, a presence mask of 128 bits
 // and the non-zero fp32 values in ascending order of dimension, rows back to back:
 //
@@ -102,6 +102,7 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
         for (int u = 0; u < 8; ++u) {
             long long wa = a0 + (long long)u * 256 + (long long)lane * 4;
             wa = wa < last_piece ? wa : last_piece;
+            wa = wa < 0 ? 0 : wa;                                   // (offsets that are not what the header asks for: stay inside the array)
             d[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(rows + wa));
         }
     };
@@ -207,6 +208,10 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
             p.a0 = a0;
             const bool fits = (row + lane < re) && (s1 - a0 <= (long long)kWinWords);
             p.nrows = __builtin_popcountll(__ballot(fits));         // rows are consecutive: the fitting ones come first
+            // A row of 128 dimensions always fits a window.  Offsets that claim otherwise (not ascending, or
+            // rows longer than the format allows) must not stall the scan: it moves on by one row, and that
+            // row's score is whatever the window holds.
+            p.nrows = p.nrows < 1 ? 1 : p.nrows;
             p.rel = (uint32_t)(s0 - a0);
             const long long nxt = __shfl(s1, (p.nrows - 1) & 63, 64);   // = start[row + nrows]
             p.next_a0 = nxt & ~3LL;

@@ -43,7 +43,7 @@ def dense_features(N, D, seed, device="cpu", dtype=torch.float32, chunk_rows=655
 
 def sparse_features(N, D, seed, device="cpu", zero_fraction=0.6, chunk_rows=65536):
     """Dense features with most entries exactly zero, as the paper reports for its 128-D ConvNet
-    features (Sec. 3.1: "over 60 % zeros"): |N(0,1)| entries, each zeroed with probability
+    features (Sec. 3.1: more than 60 % of their entries): |N(0,1)| entries, each zeroed with probability
     zero_fraction, then every row scaled to unit L2 norm (an all-zero row stays zero)."""
     g = _gen(seed, device)
     out = torch.empty((N, D), dtype=torch.float32, device=device)
@@ -185,7 +185,7 @@ def onthefly_schedule(rounds, steps_per_round, batch, n_pos_start, pos_per_round
 
 
 def centred_descriptors(N, m, seed, device="cpu", chunk_rows=65536):
-    """Descriptors for the binarisation encoder (Sec. 3 "Binarization": "zero-centred descriptors"):
+    """Descriptors for the binarisation encoder (Sec. 3 "Binarization": the descriptors are centred on zero first):
     the dense features above with one constant per dimension subtracted, the mean of a fixed
     seeded sample of 4096 such rows (a stand-in for the mean of a training set)."""
     centre = dense_features(4096, m, seed + 7919, device=device).mean(dim=0, keepdim=True)
