@@ -16,11 +16,13 @@
 // for the kernels after it.  A pass returns at once when the previous one was decisive, i.e. the
 // candidates already fit the list (mode 0 / 1).
 //
-// The same passes serve the filtered scans: passes 1 and 2 over the scores of a small sample of
-// the store give a 24-bit threshold (`tau_key`); the full scan then appends only rows at or above
-// it, and filter_sort_kernel sorts that list.  If the list cannot serve (fewer than k rows or
-// more than it can hold) it raises `fallback`, and the kernels of the full selection, launched
-// behind it with `gated` set, run; otherwise they return at once.
+// Filtered scans end here as well.  Their threshold comes from the largest keys the waves of a
+// sample scan met (resolve_tau_slots in otf_device.h; for many classifiers at once from passes 1
+// and 2 over the sample's scores, `tau_key`); the full scan appends only rows at or above it, and
+// filter_sort_kernel sorts that list.  If the list cannot serve (fewer than k rows or more than
+// it can hold) it raises `fallback`, and the full selection behind it runs: a gated re-scan that
+// materialises the scores, then select_fused_gated_kernel, which does passes 2 and 3, the gather
+// and the sort in one launch.  When the flag is clear both return at once.
 #include <algorithm>
 
 #include "otf_internal.h"
