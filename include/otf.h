@@ -361,7 +361,7 @@ typedef enum {
     OTF_DEBUG_SGD_PASS_PATH,         /* 1: otf_svm_sgd_pass as one kernel for the whole run (D <= 2048) */
     OTF_DEBUG_SGD_SPIN_LIMIT,        /* polls after which a wait of the one-launch training run gives up (default 2^20) */
     OTF_DEBUG_MEET_SPIN_LIMIT,       /* polls after which a workgroup of the fallback selection stops waiting for the
-                                        others between passes (default 2^16); then one workgroup finishes alone */
+                                        others between passes (default 2^14); then one workgroup finishes alone */
     OTF_DEBUG_KEYS
 } otf_debug_key;
 

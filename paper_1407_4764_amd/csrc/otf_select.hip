@@ -638,7 +638,7 @@ __global__ __launch_bounds__(kSortThreads) void filter_sort_kernel(SelState *st_
 // Stand-alone selection (otf_topk, scans that materialise their scores) keeps the chain: there
 // every pass runs, and a fence per workgroup would cost more than the launches.
 enum MeetRole : uint32_t { kTogether = 1u, kAlone = 2u, kLeave = 3u };
-constexpr uint32_t kMeetSpinLimit = 1u << 16;               // polls of ~1 us: far beyond a pass over any store
+constexpr uint32_t kMeetSpinLimit = 1u << 14;               // polls of ~1-2 us: ten times a pass over any store
                                                             // (diagnostic switch OTF_DEBUG_MEET_SPIN_LIMIT: 1 makes every wait give up)
 
 // Whole workgroup.  Everything this workgroup wrote before the call is visible to whoever goes on.
