@@ -141,6 +141,36 @@ def test_lloyd_step_when_many_rows_share_a_code(N, M, dsub):
     np.testing.assert_allclose(float(dist.cpu()[0]), dist_ref, rtol=1e-5)
 
 
+@pytest.mark.parametrize("N,M,dsub", [(257, 1024, 16), (300, 4096, 4), (1, 4, 16), (70, 20, 8)])
+def test_lloyd_step_at_the_ends_of_the_shape_range(N, M, dsub):
+    """The widest vocabularies the entry point takes (16384 dimensions: 256 column runs of the sums
+    kernel, one slice), a single row, and a width that leaves the last column run partly empty."""
+    X, C = _data(N, M, dsub, SEED + 14)
+    Cd = C.to(DEV).clone()
+    ws = binding.pq_train_workspace(M, dsub)
+    codes, dist = binding.pq_lloyd_step(X.to(DEV), Cd, ws)
+    torch.cuda.synchronize()
+    codes = codes.cpu().numpy().astype(np.int64)
+    Xs = X.numpy().astype(np.float64).reshape(N, M, dsub)
+    C64 = C.numpy().astype(np.float64)
+    chosen = C64[np.arange(M)[None, :], codes]                       # N x M x dsub: the centres the kernel assigned
+    d_sum = ((Xs - chosen) ** 2).sum()
+    want = C64.copy()
+    for m in range(M):
+        counts = np.bincount(codes[:, m], minlength=256)
+        sums = np.zeros((256, dsub))
+        np.add.at(sums, codes[:, m], Xs[:, m, :])
+        nz = counts > 0
+        want[m, nz] = sums[nz] / counts[nz, None]
+    got = Cd.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got - want)) <= 2.0 ** -23 * np.abs(Xs).max()
+    np.testing.assert_allclose(float(dist.cpu()[0]), d_sum / N, rtol=1e-9)
+    d = ((Xs[:, :, None, :] - C64[None, :, :, :]) ** 2).sum(axis=3) if N * M <= 80000 else None
+    if d is not None:                                                # small enough for the full distance table
+        picked = np.take_along_axis(d, codes[:, :, None], axis=2)[:, :, 0]
+        assert np.all(picked <= d.min(axis=2) + 8.0 * dsub * 2.0 ** -24 * (np.sqrt(picked) + 1.0) ** 2)
+
+
 def test_lloyd_step_gives_the_same_bits_every_run():
     """Fixed-point sums do not depend on the order of the adds: centres and distortion repeat bit for bit."""
     N, M, dsub = 40000, 32, 16
