@@ -15,9 +15,11 @@
 // 16-byte loads per lane) from the 16-byte boundary at or below the first row it has not scored;
 // the rows that lie completely inside the window (at most 64 of them, found from the offsets of
 // the next 64 rows with one vote) are scored, the next window starts at the first row that did
-// not fit.  A row that straddles a window's end is read twice, ~1.4 % of the stream.  The loads
-// of the next window are issued before the current one is scored, so 8 KiB per wave stay in
-// flight; twelve waves per compute unit hide the bubble at the start of a tile.
+// not fit.  A row that straddles a window's end is read twice, ~1.4 % of the stream.  A window
+// arrives in registers, moves to shared memory, and the same registers take the loads of the next
+// window before the current one is scored: 8 KiB per wave stay in flight, and twelve waves per
+// compute unit hide the bubble at the start of a tile.  (Two sets of registers, one per window in
+// flight, cost 36 more registers and 4 % of the time.)
 //
 // Scoring a window: its bytes go from registers to a buffer in shared memory that only this wave
 // uses.  Eight rows are scored at a time, 8 lanes per row, lane l owning dimensions 16 l .. 16 l + 15:
@@ -68,7 +70,11 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
     const SelState *tau_state, SampleSlot *sample_slots, unsigned long long *__restrict__ cand,
     const SelState *gate) {
     __shared__ __attribute__((aligned(16))) uint32_t win[kSparseThreads / 64][kWinBufWords];
-    __shared__ uint32_t lhist[kBins1];            // (the filtered scan resolves its threshold in here)
+    // the pass-1 histogram of the scores; a scan that keeps no scores only needs the room once, before
+    // its first window, to resolve the threshold: it borrows the windows' buffers
+    __shared__ uint32_t lhist_own[EMIT == kEmitScores ? kBins1 : 1];
+    static_assert(sizeof(win) >= kBins1 * 4, "the threshold resolution fits the window buffers");
+    uint32_t *lhist = EMIT == kEmitScores ? lhist_own : &win[0][0];
     __shared__ uint32_t s_out[3];
     __shared__ TileQueue s_queue;
     if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
@@ -109,9 +115,11 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
     bool list_full = false;
     // scores the nrows rows of a window that is in `d`; rel = first word of this lane's row inside the window
     // (lane r holds it for row r); v0 = number of the window's first row in the output
-    auto score_window = [&](const u32x4 *d, uint32_t rel, int nrows, long long v0) {
+    auto store_window = [&](const u32x4 *d) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) *reinterpret_cast<u32x4 *>(buf + u * 256 + lane * 4) = d[u];
+    };
+    auto score_window = [&](uint32_t rel, int nrows, long long v0) {
         for (int r0 = 0; r0 < nrows; r0 += 8) {                     // uniform trip count
             const int rl = r0 + rq;
             const bool valid = rl < nrows;
@@ -217,28 +225,24 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
             p.next_a0 = nxt & ~3LL;
             return p;
         };
-        u32x4 b0[8], b1[8];
+        // One set of registers holds a window on its way in.  Once it has arrived it moves to the wave's
+        // buffer in shared memory, the registers take the loads of the NEXT window, and the current one
+        // is scored from shared memory while those are in flight.
+        u32x4 b[8];
         const long long first_a0 = __shfl(S0, 0, 64) & ~3LL;
         Win cur = plan(r, first_a0);
-        fetch(b0, cur.a0);
+        fetch(b, cur.a0);
         for (;;) {
-            // b0 holds (or is receiving) window `cur`; order the one after it, then score cur
-            const bool more0 = r + cur.nrows < re;
+            const bool more = r + cur.nrows < re;
             Win nxt = cur;
-            if (more0) nxt = plan(r + cur.nrows, cur.next_a0);      // uniform
-            fetch(b1, more0 ? nxt.a0 : cur.a0);
-            score_window(b0, cur.rel, cur.nrows, v);
-            if (!more0) break;
+            if (more) nxt = plan(r + cur.nrows, cur.next_a0);       // uniform
+            store_window(b);
+            fetch(b, more ? nxt.a0 : cur.a0);
+            score_window(cur.rel, cur.nrows, v);
+            if (!more) break;
             v += cur.nrows;
             r += cur.nrows;
-            const bool more1 = r + nxt.nrows < re;
             cur = nxt;
-            if (more1) cur = plan(r + nxt.nrows, nxt.next_a0);
-            fetch(b0, more1 ? cur.a0 : nxt.a0);
-            score_window(b1, nxt.rel, nxt.nrows, v);
-            if (!more1) break;
-            v += nxt.nrows;
-            r += nxt.nrows;
         }
     }
     if (EMIT == kEmitScores) merge_hist1(lhist, hist1);
@@ -251,6 +255,8 @@ static hipError_t launch_sparse_cfg(const uint32_t *rows, const int64_t *start, 
                                     const SelState *tau, SampleSlot *slots, unsigned long long *cand,
                                     const SelState *gate, hipStream_t s) {
     const int64_t tiles = (N + kSparseTileRows<EMIT> - 1) / kSparseTileRows<EMIT>;
+    // three workgroups per compute unit: with one or two the kernel takes 2.2x and 1.3x as long, and a
+    // fourth (the registers would allow it) makes it 3 % slower: the shared-memory unit is the limit
     const int grid = (int)std::min<int64_t>((tiles + 3) / 4, (int64_t)device_cu_count() * 3);
     sparse_scan_kernel<EMIT><<<grid < 1 ? 1 : grid, kSparseThreads, 0, s>>>(
         rows, reinterpret_cast<const long long *>(start), (long long)N, (long long)store_rows, w, bias, scores, st, hist1,
