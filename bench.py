@@ -36,8 +36,8 @@ HBM_PEAK_GBS = 8000.0
 # ("traffic_source"), and a workload that is scaled down or has no counter run yet reports null.
 TRAFFIC_SOURCE = "profiles/traffic_counters.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not measured in this run)"
 MEASURED_TRAFFIC_BYTES = {          # read + written, per launch of the scoring kernel
-    "dense": 8198008010, "pq": 2590228917, "pq512": 2598162714, "pq256": 2594092640, "binary": 12825251201,
-    "hamming": 12825183612, "dense128": 5131105014, "dense128h": 5131044388, "sparse128": 2450816187,
+    "dense": 8195955717, "pq": 2590228917, "pq512": 2598162714, "pq256": 2594092640, "binary": 12825251201,
+    "hamming": 12816993899, "dense128": 5131105014, "dense128h": 5131044388, "sparse128": 2450816290,
     "multiquery": 20488076562,
 }
 TOPK_TRAFFIC_BYTES = 200157996      # topk_filter_kernel on 50M scores
