@@ -8,8 +8,8 @@
 //                        accumulation) whose epilogue keeps only the signs, packed 32 to a word,
 //                        dimension d at bit d mod 32 of word d div 32
 // binarize_kernel        the same product on the fp32 matrix instructions; 1.6 times slower (they do
-//                        not overlap with the vector ALU on this chip), kept behind
-//                        OTF_BINARIZE_FP32=1 for comparison
+//                        not overlap with the vector ALU on this chip), kept behind the
+//                        switch OTF_DEBUG_BINARIZE_FP32 for comparison
 #include <algorithm>
 
 #include "otf_bf16x3.h"

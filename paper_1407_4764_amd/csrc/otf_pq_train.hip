@@ -11,7 +11,7 @@
 // a row.
 //
 // pq_encode_bf16_kernel   bf16 matrix instructions on three exact pieces per fp32 value
-// pq_encode_kernel        the fp32 matrix instructions (OTF_PQENC_FP32=1), kept for comparison
+// pq_encode_kernel        the fp32 matrix instructions (switch OTF_DEBUG_PQENC_FP32), kept for comparison
 // pq_accumulate_kernel, pq_move_centres_kernel   the second half of a Lloyd iteration
 #include <algorithm>
 #include <type_traits>
