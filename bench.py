@@ -133,7 +133,16 @@ def make_workload(kind, scale, torch, binding, synth):
     return step, cfg
 
 
+RAMP_S = 0.25      # seconds of untimed calls before the warm-up steps: a GPU that has been idle (the stores are
+                   # generated in short bursts) runs its first tens of milliseconds below its steady clock
+
+
 def time_steps(step, steps, warmup, torch, binding):
+    t_ramp = time.perf_counter()
+    while time.perf_counter() - t_ramp < RAMP_S:
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
@@ -474,6 +483,7 @@ def cpu_baseline(kind, cfg, torch, budget_s=10.0):
 
 
 def main():
+    global RAMP_S
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
@@ -488,6 +498,8 @@ def main():
     ap.add_argument("--topk-only", action="store_true", help="only time otf_topk on ready-made scores")
     ap.add_argument("--sgd-only", action="store_true", help="only time the Pegasos training pass")
     ap.add_argument("--fallback-only", action="store_true", help="only time the worst case of the filtered ranking")
+    ap.add_argument("--ramp-seconds", type=float, default=None,
+                    help="untimed calls for this long before the warm-up steps (default %.2f)" % RAMP_S)
     ap.add_argument("--switch", action="append", default=[], metavar="NAME=VALUE",
                     help="set a diagnostic switch of the library first (binding.DEBUG_<NAME>), e.g. --switch PQENC_FP32=1")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -501,6 +513,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     binding.lib()                                  # fail loudly if the HIP library is missing
+    if args.ramp_seconds is not None:
+        RAMP_S = max(0.0, args.ramp_seconds)
     for item in args.switch:
         name, _, value = item.partition("=")
         binding.debug_set(getattr(binding, "DEBUG_" + name.upper()), int(value))
@@ -549,6 +563,7 @@ def main():
         "config": {"workload": res["workload"], "N": res["N"], "k": res["k"],
                    "step": "one otf_rank_* call: scan of the whole store + exact sorted top-k"},
         "whole_path_frac_of_hbm_peak": res["whole_path_frac_of_hbm_peak"],
+        "ramp_s": RAMP_S,
         "roofline": res.get("roofline"),
         "graph_replay_ms_per_step": res.get("graph_replay_ms_per_step"),
     }
