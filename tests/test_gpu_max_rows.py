@@ -1,5 +1,5 @@
-"""The largest stores the interface admits: N = 2^31 - 1 rows (row indices are int32) of 16- and
-32-byte rows, and a sparse-row store whose word offsets pass 2^32.
+"""The largest sizes the interface admits: N = 2^31 - 1 rows (row indices are int32) of 16- and
+32-byte rows, a sparse-row store whose word offsets pass 2^32, and 65535 classifiers in one call.
 
 The oracle cannot score two thousand million rows in test time, so the expected list is PLANTED:
 1200 rows, spread over the store with its first and last rows among them, are built to score above
@@ -181,3 +181,31 @@ def test_sparse_store_with_offsets_past_32_bits(oracle):
     want = oracle_rows(sample)
     assert np.all(np.abs(scores[_dev_index(sample)].cpu().numpy() - want) <= oracle.score_tolerance(want, 1e-4))
     assert int((scores >= float(val[0, -1])).sum().item()) == K
+
+
+@pytest.mark.parametrize("half,Q,n_rows,D,k", [(False, 65535, 48, 16, 3), (True, 65504, 130, 128, 5)])
+def test_largest_classifier_count(oracle, half, Q, n_rows, D, k):
+    """65535 classifiers over a small store: one scan per classifier in fp32, the matrix-core scan
+    (classifier counts that are multiples of 32) in fp16; then otf_topk over the Q x N scores."""
+    dt = torch.float16 if half else torch.float32
+    rtol = 2e-3 if half else 1e-4
+    X = synth.dense_features(n_rows, D, 71, dtype=dt)
+    W = synth.normal_matrix(Q, D, 0.5, 72, dtype=dt)
+    ref = oracle.dense_scores(X.numpy(), W.numpy())
+    ws = binding.make_workspace(n_rows, k, Q)
+    scores = torch.empty((Q, n_rows), dtype=torch.float32, device=DEV)
+    val, idx = binding.rank_dense(X.to(DEV), W.to(DEV), None, k, ws, all_scores=scores)
+    val2, idx2 = binding.topk(scores, k, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(val, val2) and torch.equal(idx, idx2)
+    got = scores.cpu().numpy()
+    val, idx = val.cpu().numpy(), idx.cpu().numpy()
+    for q in range(Q):
+        assert np.all(np.abs(got[q] - ref[q]) <= oracle.score_tolerance(ref[q], rtol)), "classifier %d" % q
+    for q in list(range(0, Q, 997)) + [Q - 2, Q - 1]:
+        ok, msg = oracle.topk_parity_ok(ref[q], k, idx[q], val[q], rtol)
+        assert ok, "classifier %d: %s" % (q, msg)
+    # every list is the first k of a full sort of the GPU's own scores (score descending, row ascending)
+    order = np.lexsort((np.broadcast_to(np.arange(n_rows), got.shape), -got.astype(np.float64)), axis=1)[:, :k]
+    np.testing.assert_array_equal(idx, order)
+    np.testing.assert_array_equal(val, np.take_along_axis(got, order, axis=1))
