@@ -23,7 +23,7 @@ def _unpack(words, n):
     return ((w[:, :, None] >> np.arange(32, dtype=np.uint32)[None, None, :]) & 1).reshape(w.shape[0], n).astype(bool)
 
 
-@pytest.mark.parametrize("n,m", [(256, 32), (1024, 128), (2048, 128), (96, 96)])
+@pytest.mark.parametrize("n,m", [(256, 32), (1024, 128), (2048, 128), (96, 96), (4096, 256), (4096, 1), (257, 256), (1, 1)])
 def test_tight_frame_matches_the_oracle(n, m):
     G = synth.random_square(n, SEED + n + m)
     U = binding.tight_frame(G.to(DEV), m).cpu().numpy().astype(np.float64)
@@ -64,6 +64,20 @@ def test_codes_match_the_oracle_outside_the_rounding_band(N, m, n):
     assert not np.any(diff & ~band), "bits differ outside the rounding band: %d" % int(np.sum(diff & ~band))
     assert diff.mean() < 1e-4
     np.testing.assert_array_equal(_unpack(enc.binarize(phi.numpy(), U), n), ref)   # the packed form says the same
+
+
+@pytest.mark.parametrize("N,m,n", [(70, 128, 65536), (200, 4, 65536), (33, 128, 65504)])
+def test_longest_codes_the_call_takes(N, m, n):
+    """Codes of up to 65536 bits.  The frame routine stops at 4096 rows, so the projection matrix is
+    a plain random one here: the encoder's arithmetic does not depend on its columns being orthogonal."""
+    Ud = synth.normal_matrix(n, m, 1.0, SEED + 3).to(DEV)
+    phi = synth.centred_descriptors(N, m, SEED + 4)
+    got = _unpack(synth.as_uint32(binding.binarize(phi.to(DEV), Ud).cpu().numpy()), n)
+    proj, mag = enc.projections(phi.numpy(), Ud.cpu().numpy())
+    band = np.abs(proj) <= 2.0 * m * 2.0 ** -24 * mag
+    diff = got != (proj > 0)
+    assert not np.any(diff & ~band), "bits differ outside the rounding band: %d" % int(np.sum(diff & ~band))
+    assert diff.mean() < 1e-4
 
 
 @pytest.mark.parametrize("waves", [8, 4])

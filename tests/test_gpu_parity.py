@@ -55,6 +55,12 @@ DENSE_CASES = [
     (5003, 2048, torch.float16, torch.float32, 100, 0),
     (5003, 2048, torch.float16, torch.float16, 100, 0),
     (4100, 128, torch.float16, torch.float32, 64, 8),
+    (530, 16384, torch.float32, torch.float32, 9, 0),       # the longest rows the call takes
+    (530, 16384, torch.float16, torch.float16, 9, 0),
+    (410, 16380, torch.float32, torch.float32, 9, 4),       # ... and just below, ragged last step
+    (410, 16376, torch.float16, torch.float32, 9, 0),
+    (400, 2052, torch.float32, torch.float32, 9, 0),        # the first length past the register copy of w
+    (400, 4104, torch.float16, torch.float16, 9, 0),
 ]
 
 
