@@ -304,6 +304,9 @@ def test_ranking_is_reproducible(oracle):
     (2048, 1000, 16000, 256, 1e-4, False),      # the full-size training configuration
     (128, 200, 1600, 32, 1.0, True),            # the paper's own batch size and regulariser
     (260, 50, 70, 6, 0.01, True),
+    (4, 10, 10, 2, 0.5, True),                  # the shortest model, the smallest batch
+    (16384, 100, 400, 64, 1e-3, False),         # a model as long as the longest dense row
+    (2048, 300, 300, 4096, 1e-2, True),         # the largest batch
 ])
 def test_sgd_steps_teacher_forced(oracle, D, n_pos_pool, n_neg_pool, batch, lam, update_bias):
     Xp, Xn = synth.sgd_pools(D, n_pos_pool, n_neg_pool, SEED + 30)
