@@ -320,7 +320,7 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
         if (e == hipSuccess) e = launch_select_init(ssw, Q, s);
         if (e == hipSuccess) e = mfma_scan(Nv, kEmitSample, sample, L.sample_ld, nullptr, nullptr, nullptr, nullptr, ssw.st, 0);
         if (e == hipSuccess) e = launch_hist1(sample, Nv, L.sample_ld, Q, ssw, 0, s);
-        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, Q, m, ssw, 1, sw.st, s);
+        if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, Q, m, ssw, sw.st, s);
         ScanTimer timer(s);
         if (e == hipSuccess) e = mfma_scan(N, kEmitFilter, nullptr, 0, ssw.st, sw.st, sw.cand, sw.st, sw.st, 0);
         timer.stop();

@@ -49,16 +49,16 @@ hipError_t launch_select_init_both(const SelectWs &sw, const SelectWs &sample_sw
 // Radix pass 1 over ready-made scores (rows of length N, stride ld).
 hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const SelectWs &sw, int gated,
                         hipStream_t s);
-// Passes 2 and 3 (skipped on the device when pass 1 was decisive), gather and final sort.  With
-// `gated` the kernels return at once unless sw.st[0].fallback is set.
+// Passes 2 and 3 (skipped on the device when pass 1 was decisive), gather and final sort, as four
+// launches; with `gated` (the fallback of a filtered scan) as one launch that returns at once unless
+// sw.st[0].fallback is set.
 hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw,
                               float *out_scores, int32_t *out_idx, int gated, hipStream_t s);
-// Pass 2 over sample scores for rank m.  With publish_tau, sample_sw.st[q].tau_key receives the
-// threshold (top 24 bits of the m-th largest sample key), and main_st[0].fallback is raised when a
-// classifier's threshold would let far more rows pass than the candidate list holds; otherwise
-// the consumer resolves the threshold from sample_sw.st[q] and sample_sw.hist2 itself.
+// Pass 2 over sample scores for rank m (many classifiers at once): sample_sw.st[q].tau_key receives
+// the threshold (top 24 bits of the m-th largest sample key), and main_st[0].fallback is raised when
+// a classifier's threshold would let far more rows pass than the candidate list holds.
 hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64_t ld, int Q, int m,
-                                   const SelectWs &sample_sw, int publish_tau, SelState *main_st, hipStream_t s);
+                                   const SelectWs &sample_sw, SelState *main_st, hipStream_t s);
 // otf_topk in one read of the scores (one classifier, N large enough for a sample): zeroes the states
 // itself, sample -> threshold -> filter -> sort, the exact passes gated behind.
 hipError_t launch_topk_filtered(const float *scores, int64_t N, int k, const SelectWs &sw, const SelectWs &sample_sw,

@@ -119,10 +119,9 @@ __global__ __launch_bounds__(1024) void hist1_kernel(const float *__restrict__ s
 // estimation on a sample); otherwise return when pass 1 was decisive.
 __global__ __launch_bounds__(1024) void hist2_kernel(const float *__restrict__ scores, long long N, long long ld,
                                                     int k, SelState *st_all, const uint32_t *hist1_all,
-                                                    uint32_t *hist2_all, int force, const SelState *gate) {
+                                                    uint32_t *hist2_all, int force) {
     __shared__ uint32_t lhist[kBins2];
     __shared__ uint32_t s_out[3];
-    if (gate && gate->fallback == 0u) return;
     const int q = blockIdx.y;
     SelState *st = st_all + q;
     const BinChoice r1 = block_find_bin(hist1_all + (size_t)q * kHist1Words, kBins1, (uint32_t)k, lhist, s_out, kHistShards);
@@ -186,10 +185,9 @@ __global__ __launch_bounds__(512) void sample_tau_kernel(SelState *sample_st_all
 // Pass 3 (only when thousands of keys share the top 24 bits of the k-th: ties or near-ties).
 __global__ __launch_bounds__(1024) void hist3_kernel(const float *__restrict__ scores, long long N, long long ld,
                                                     int k, SelState *st_all, const uint32_t *hist2_all,
-                                                    uint32_t *hist3_all, uint32_t *blockhist3_all, int gated) {
+                                                    uint32_t *hist3_all, uint32_t *blockhist3_all) {
     __shared__ uint32_t lhist[kBins2];
     __shared__ uint32_t s_out[3];
-    if (gated && st_all[0].fallback == 0u) return;
     const int q = blockIdx.y;
     SelState *st = st_all + q;
     if (st->mode == 0u) return;                         // pass 1 was decisive
@@ -322,12 +320,10 @@ __device__ __forceinline__ void gather_rows(const float *__restrict__ s, long lo
 
 __global__ __launch_bounds__(512) void gather_kernel(const float *__restrict__ scores, long long N, long long ld,
                                                      int k, SelState *st_all, const uint32_t *hist3_all,
-                                                     const uint32_t *blockhist3_all, unsigned long long *cand_all,
-                                                     int gated) {
+                                                     const uint32_t *blockhist3_all, unsigned long long *cand_all) {
     __shared__ uint32_t lhist[kBins3];
     __shared__ uint32_t s_out[3];
     __shared__ uint32_t wave_sum_s[16];
-    if (gated && st_all[0].fallback == 0u) return;
     const int q = blockIdx.y;
     SelState *st = st_all + q;
     const uint32_t mode = st->mode;
@@ -581,9 +577,8 @@ __device__ __forceinline__ void select_sort_emit(uint8_t *lds, const unsigned lo
 // One block per classifier: sorts the candidate list of the full selection.
 __global__ __launch_bounds__(kSortThreads) void sort_emit_kernel(const SelState *st_all,
                                                                  const unsigned long long *cand_all, int k,
-                                                                 float *out_scores, int32_t *out_idx, int gated) {
+                                                                 float *out_scores, int32_t *out_idx) {
     extern __shared__ __attribute__((aligned(16))) uint8_t sort_lds[];
-    if (gated && st_all[0].fallback == 0u) return;
     const int q = blockIdx.x;
     uint32_t n = st_all[q].ncand;
     if (n > (uint32_t)kCandCap) n = kCandCap;
@@ -934,23 +929,22 @@ hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q,
         return hipGetLastError();
     }
     // (1024 threads: the histogram passes hide the latency of their votes and shared-memory adds behind more waves)
-    hist2_kernel<<<grid, 1024, 0, s>>>(scores, N, ld, k, sw.st, sw.hist1, sw.hist2, 0, gated ? sw.st : nullptr);
-    hist3_kernel<<<grid, 1024, 0, s>>>(scores, N, ld, k, sw.st, sw.hist2, sw.hist3, sw.blockhist3, gated);
-    gather_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist3, sw.blockhist3, sw.cand, gated);
+    hist2_kernel<<<grid, 1024, 0, s>>>(scores, N, ld, k, sw.st, sw.hist1, sw.hist2, 0);
+    hist3_kernel<<<grid, 1024, 0, s>>>(scores, N, ld, k, sw.st, sw.hist2, sw.hist3, sw.blockhist3);
+    gather_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist3, sw.blockhist3, sw.cand);
     hipError_t e = allow_sort_lds();
     if (e != hipSuccess) return e;
-    sort_emit_kernel<<<Q, kSortThreads, kSortLdsBytes, s>>>(sw.st, sw.cand, k, out_scores, out_idx, gated);
+    sort_emit_kernel<<<Q, kSortThreads, kSortLdsBytes, s>>>(sw.st, sw.cand, k, out_scores, out_idx);
     return hipGetLastError();
 }
 
-// Pass 2 over sample scores (pass 1 was accumulated by the sample scan or by launch_hist1 on the
-// sample state).  With publish_tau the thresholds are resolved into sample_sw.st[q].tau_key by a
-// one-block-per-classifier kernel; otherwise the consumer resolves them itself (resolve_tau).
+// Pass 2 over sample scores (pass 1 was accumulated by launch_hist1 on the sample state); the
+// thresholds are then resolved into sample_sw.st[q].tau_key by a one-block-per-classifier kernel.
 hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64_t ld, int Q, int m,
-                                   const SelectWs &sample_sw, int publish_tau, SelState *main_st, hipStream_t s) {
+                                   const SelectWs &sample_sw, SelState *main_st, hipStream_t s) {
     hist2_kernel<<<dim3(sel_blocks(Nv, Q), Q), 1024, 0, s>>>(sample_scores, Nv, ld, m, sample_sw.st, sample_sw.hist1,
-                                                    sample_sw.hist2, 1, nullptr);
-    if (publish_tau) sample_tau_kernel<<<Q, 512, 0, s>>>(sample_sw.st, sample_sw.hist2, m, main_st);
+                                                    sample_sw.hist2, 1);
+    sample_tau_kernel<<<Q, 512, 0, s>>>(sample_sw.st, sample_sw.hist2, m, main_st);
     return hipGetLastError();
 }
 
