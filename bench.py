@@ -265,7 +265,7 @@ def measure_topk(torch, binding, synth):
             "roofline": {"bound": "hbm", "achieved": 4.0 * N / dt / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": 4.0 * N / dt / 1e9 / HBM_PEAK_GBS, "traffic": TOPK_TRAFFIC_BYTES,
                          "traffic_source": TRAFFIC_SOURCE,
-                         "note": "algorithmic bytes = one read of the scores, which is what the call does; the rest of the time is five dependent launches (sample, filter, sort, two gated fallback kernels) and the final sort"}}
+                         "note": "algorithmic bytes = one read of the scores, which is what the call does; the rest of the time is four dependent launches (sample, filter, the gated pass 1 of the fallback, and the launch that sorts the list or runs the full selection)"}}
 
 
 def measure_filter_fallback(steps, warmup, torch, binding, synth):

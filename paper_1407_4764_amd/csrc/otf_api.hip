@@ -229,8 +229,8 @@ int otf_topk(const float *scores, int64_t N, int64_t ld, int32_t Q, int32_t k, f
             scores, N, k, sw, sample_select_ws(ws, L),
             reinterpret_cast<SampleSlot *>(reinterpret_cast<uint8_t *>(ws) + L.sample_scores), out_scores, out_idx, s));
     hipError_t e = launch_select_init(sw, Q, s);
-    if (e == hipSuccess) e = launch_hist1(scores, N, ld, Q, sw, 0, s);
-    if (e == hipSuccess) e = launch_select_tail(scores, N, ld, Q, k, sw, out_scores, out_idx, 0, s);
+    if (e == hipSuccess) e = launch_hist1(scores, N, ld, Q, sw, kNoGate, s);
+    if (e == hipSuccess) e = launch_select_tail(scores, N, ld, Q, k, sw, out_scores, out_idx, kTailPlain, s);
     return hip_status(e);
 }
 
@@ -280,17 +280,16 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
         hipError_t e = launch_select_init_both(sw, ssw, 1, s);
         if (e == hipSuccess)
             e = launch_dense_scan_emit(X, x_half, Nv, D, ldx, W, w_half, bias, 0, kEmitSample, nullptr, nullptr,
-                                       &ssw.st[0].chunk_ctr[0], ssw.st, nullptr, slots, nullptr, nullptr, s);
+                                       &ssw.st[0].chunk_ctr[0], ssw.st, nullptr, slots, nullptr, kNoGate, s);
         ScanTimer timer(s);
         if (e == hipSuccess)
             e = launch_dense_scan_emit(X, x_half, N, D, ldx, W, w_half, bias, 0, kEmitFilter, nullptr, nullptr,
-                                       &sw.st[0].chunk_ctr[0], sw.st, ssw.st, slots, sw.cand, nullptr, s);
+                                       &sw.st[0].chunk_ctr[0], sw.st, ssw.st, slots, sw.cand, kNoGate, s);
         timer.stop();
-        if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
         if (e == hipSuccess)
             e = launch_dense_scan_emit(X, x_half, N, D, ldx, W, w_half, bias, 0, kEmitScores, S, sw.hist1,
-                                       &sw.st[0].chunk_ctr[1], sw.st, nullptr, nullptr, nullptr, sw.st, s);
-        if (e == hipSuccess) e = launch_select_tail(S, N, ldS, 1, k, sw, out_scores, out_idx, 1, s);
+                                       &sw.st[0].chunk_ctr[1], sw.st, nullptr, nullptr, nullptr, Gate{sw.st, k}, s);
+        if (e == hipSuccess) e = launch_select_tail(S, N, ldS, 1, k, sw, out_scores, out_idx, kTailBehindScan, s);
         return hip_status(e);
     }
     hipError_t e = launch_select_init(sw, Q, s);
@@ -298,7 +297,7 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
     // One matrix-core launch per group of 64 (or a last 32) classifiers.
     // (ctr_states[q0].chunk_ctr[ctr_word]: the zeroed work counter of each launch)
     auto mfma_scan = [&](int64_t rows, ScanEmit emit, float *dst, int64_t ld, const SelState *tau, SelState *st,
-                         unsigned long long *cand, const SelState *gate, SelState *ctr_states, int ctr_word) {
+                         unsigned long long *cand, Gate gate, SelState *ctr_states, int ctr_word) {
         hipError_t err = hipSuccess;
         for (int q0 = 0; q0 < Q && err == hipSuccess;) {
             const int qn = (Q - q0 >= 64) ? 64 : 32;
@@ -318,30 +317,30 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
         const int64_t Nv = sample_rows(N);
         const int m = sample_rank(N, Nv);
         if (e == hipSuccess) e = launch_select_init(ssw, Q, s);
-        if (e == hipSuccess) e = mfma_scan(Nv, kEmitSample, sample, L.sample_ld, nullptr, nullptr, nullptr, nullptr, ssw.st, 0);
-        if (e == hipSuccess) e = launch_hist1(sample, Nv, L.sample_ld, Q, ssw, 0, s);
+        if (e == hipSuccess) e = mfma_scan(Nv, kEmitSample, sample, L.sample_ld, nullptr, nullptr, nullptr, kNoGate, ssw.st, 0);
+        if (e == hipSuccess) e = launch_hist1(sample, Nv, L.sample_ld, Q, ssw, kNoGate, s);
         if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, Q, m, ssw, sw.st, s);
         ScanTimer timer(s);
-        if (e == hipSuccess) e = mfma_scan(N, kEmitFilter, nullptr, 0, ssw.st, sw.st, sw.cand, sw.st, sw.st, 0);
+        if (e == hipSuccess) e = mfma_scan(N, kEmitFilter, nullptr, 0, ssw.st, sw.st, sw.cand, Gate{sw.st, 0}, sw.st, 0);
         timer.stop();
         if (e == hipSuccess) e = launch_filter_sort(sw, Q, k, out_scores, out_idx, s);
-        if (e == hipSuccess) e = mfma_scan(N, kEmitScores, S, ldS, nullptr, nullptr, nullptr, sw.st, sw.st, 1);
-        if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, sw, 1, s);
-        if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, 1, s);
+        if (e == hipSuccess) e = mfma_scan(N, kEmitScores, S, ldS, nullptr, nullptr, nullptr, Gate{sw.st, 0}, sw.st, 1);
+        if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, sw, Gate{sw.st, 0}, s);
+        if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, kTailBehindFlag, s);
         return hip_status(e);
     }
     ScanTimer timer(s);
     if (e == hipSuccess && mfma) {
-        e = mfma_scan(N, kEmitScores, S, ldS, nullptr, nullptr, nullptr, nullptr, sw.st, 1);
+        e = mfma_scan(N, kEmitScores, S, ldS, nullptr, nullptr, nullptr, kNoGate, sw.st, 1);
         timer.stop();
-        if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, sw, 0, s);
+        if (e == hipSuccess) e = launch_hist1(S, N, ldS, Q, sw, kNoGate, s);
     } else if (e == hipSuccess) {
         for (int q = 0; q < Q && e == hipSuccess; ++q)
             e = launch_dense_scan(X, x_half, N, D, ldx, Wb + (size_t)q * D * wsize, w_half, bias, q,
                                   S + (size_t)q * ldS, sw.hist1 + (size_t)q * kHist1Words, &sw.st[q].chunk_ctr[1], s);
         timer.stop();
     }
-    if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, 0, s);
+    if (e == hipSuccess) e = launch_select_tail(S, N, ldS, Q, k, sw, out_scores, out_idx, kTailPlain, s);
     return hip_status(e);
 }
 
@@ -389,24 +388,23 @@ static hipError_t rank_table(const uint8_t *codes, int64_t N, int row_bytes, Tab
         SelectWs ssw = sample_select_ws(ws, L);
         SampleSlot *slots = reinterpret_cast<SampleSlot *>(wsb + L.sample_scores);
         e = launch_table_scan(codes, sample_rows(N), row_bytes, kind, image, bias, kEmitSample, nullptr, ssw.st, nullptr,
-                              nullptr, slots, nullptr, nullptr, s);
+                              nullptr, slots, nullptr, kNoGate, s);
         ScanTimer timer(s);
         if (e == hipSuccess)
             e = launch_table_scan(codes, N, row_bytes, kind, image, bias, kEmitFilter, nullptr, sw.st, nullptr, ssw.st,
-                                  slots, sw.cand, nullptr, s);
+                                  slots, sw.cand, kNoGate, s);
         timer.stop();
-        if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
         if (e == hipSuccess)
             e = launch_table_scan(codes, N, row_bytes, kind, image, bias, kEmitScores, S, sw.st, sw.hist1, nullptr,
-                                  nullptr, nullptr, sw.st, s);
-        if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 1, s);
+                                  nullptr, nullptr, Gate{sw.st, k}, s);
+        if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, kTailBehindScan, s);
         return e;
     }
     ScanTimer timer(s);
     e = launch_table_scan(codes, N, row_bytes, kind, image, bias, kEmitScores, S, sw.st, sw.hist1, nullptr, nullptr,
-                          nullptr, nullptr, s);
+                          nullptr, kNoGate, s);
     timer.stop();
-    if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 0, s);
+    if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, kTailPlain, s);
     return e;
 }
 
@@ -491,25 +489,24 @@ int otf_rank_sparse(const uint32_t *rows, const int64_t *start, int64_t N, int32
     if (e == hipSuccess && filter_eligible(N, k, all_scores)) {
         SampleSlot *slots = reinterpret_cast<SampleSlot *>(wsb + L.sample_scores);
         e = launch_sparse_scan(rows, start, sample_rows(N), N, w, bias, kEmitSample, nullptr, ssw.st, nullptr, nullptr,
-                               slots, nullptr, nullptr, s);
+                               slots, nullptr, kNoGate, s);
         ScanTimer timer(s);
         if (e == hipSuccess)
             e = launch_sparse_scan(rows, start, N, N, w, bias, kEmitFilter, nullptr, sw.st, nullptr, ssw.st, slots,
-                                   sw.cand, nullptr, s);
+                                   sw.cand, kNoGate, s);
         timer.stop();
-        if (e == hipSuccess) e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
         if (e == hipSuccess)
             e = launch_sparse_scan(rows, start, N, N, w, bias, kEmitScores, S, sw.st, sw.hist1, nullptr, nullptr, nullptr,
-                                   sw.st, s);
-        if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 1, s);
+                                   Gate{sw.st, k}, s);
+        if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, kTailBehindScan, s);
         return hip_status(e);
     }
     ScanTimer timer(s);
     if (e == hipSuccess)
         e = launch_sparse_scan(rows, start, N, N, w, bias, kEmitScores, S, sw.st, sw.hist1, nullptr, nullptr, nullptr,
-                               nullptr, s);
+                               kNoGate, s);
     timer.stop();
-    if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, 0, s);
+    if (e == hipSuccess) e = launch_select_tail(S, N, N, 1, k, sw, out_scores, out_idx, kTailPlain, s);
     return hip_status(e);
 }
 

@@ -239,7 +239,7 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
                                                            uint32_t *chunk_ctr, SelState *st,
                                                            const SelState *tau_state, SampleSlot *sample_slots,
                                                            unsigned long long *__restrict__ cand,
-                                                           const SelState *gate) {
+                                                           Gate gate) {
     constexpr int E = Elem<XHALF>::kPer16;
     constexpr int RPW = 64 / LPR;   // rows per wave load
     constexpr int U = 8;
@@ -249,7 +249,7 @@ __global__ __launch_bounds__(256) void dense_narrow_kernel(const uint8_t *__rest
     __shared__ uint32_t lhist[kBins1];
     __shared__ uint32_t s_out[3];
     __shared__ TileQueue s_queue;
-    if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
+    if (!gate_open(gate)) return;                 // uniform: this launch is only the fallback of a filtered scan
     if (threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);   // visible after the barriers below
     uint32_t tau = 0u;
     if (EMIT == kEmitFilter) {
@@ -423,7 +423,7 @@ struct NarrowExtra {
     const SelState *tau;
     SampleSlot *slots;
     unsigned long long *cand;
-    const SelState *gate;
+    Gate gate;
 };
 
 template <bool XHALF>
@@ -466,7 +466,7 @@ static hipError_t launch_dense_typed(const uint8_t *X, int64_t N, int D, int64_t
         }
 #undef OTF_NARROW
     } else {
-        if (x.emit != kEmitScores || x.gate) return hipErrorInvalidValue;   // only the narrow kernel filters
+        if (x.emit != kEmitScores || x.gate.st) return hipErrorInvalidValue;   // only the narrow kernel filters
         grid = (int)std::min<int64_t>((N + 3) / 4, (int64_t)cus * tune_int(OTF_DEBUG_DENSE_BLOCKS_PER_CU, 1));
         if (grid < 1) grid = 1;
         const int V = (chunks + 63) / 64;
@@ -503,13 +503,13 @@ hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int
                              int w_is_half, const float *bias_ptr, int bias_index, float *scores, uint32_t *hist1,
                              uint32_t *chunk_ctr, hipStream_t s) {
     return launch_dense_scan_emit(X, x_is_half, N, D, ldx, w, w_is_half, bias_ptr, bias_index, kEmitScores, scores,
-                                  hist1, chunk_ctr, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+                                  hist1, chunk_ctr, nullptr, nullptr, nullptr, nullptr, kNoGate, s);
 }
 
 hipError_t launch_dense_scan_emit(const void *X, int x_is_half, int64_t N, int D, int64_t ldx, const void *w,
                                   int w_is_half, const float *bias_ptr, int bias_index, ScanEmit emit, float *scores,
                                   uint32_t *hist1, uint32_t *chunk_ctr, SelState *st, const SelState *tau,
-                                  SampleSlot *slots, unsigned long long *cand, const SelState *gate, hipStream_t s) {
+                                  SampleSlot *slots, unsigned long long *cand, Gate gate, hipStream_t s) {
     const uint8_t *Xb = reinterpret_cast<const uint8_t *>(X);
     const NarrowExtra x{emit, st, tau, slots, cand, gate};
     if (emit == kEmitFilter && (!st || !tau || !slots || !cand)) return hipErrorInvalidValue;

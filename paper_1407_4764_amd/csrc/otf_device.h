@@ -47,17 +47,38 @@ struct SelState {
     uint32_t r;        // how many rows with key == T belong to the list (mode 2), lowest indices first
     uint32_t ncand;    // entries the gather pass writes to the candidate list
     long long tex;     // gather every key with (long long)key > tex
-    uint32_t cursor;   // append cursor of the gather pass
+    uint32_t cursor;   // append cursor of a filtered scan: rows it put on the candidate list, or some number
+                       // beyond the list's capacity when more passed than it holds
     uint32_t chunk_ctr[2];  // next chunk of a dynamically scheduled scan (two scans may share a state)
-    uint32_t spare;
+    uint32_t spare;    // ticket of the one-launch selection: the workgroup that finishes last sorts
     uint32_t tau_key;  // filter threshold: rows with key >= tau_key are candidates (filtered scans)
     uint32_t fallback; // set by the filtered path when its candidate list cannot serve: redo by full selection
     // meeting points of the workgroups of the one-launch selection (select_fused_gated_kernel)
     uint32_t met[2];   // arrivals at meeting point 0, 1
     uint32_t verdict[2];   // 0: open, 1: all arrived, go on together, 2: somebody stopped waiting, the last arrival goes on alone
-    uint32_t pad[12];
+    uint32_t gcursor;  // append cursor of the gather pass of the full selection
+    uint32_t pad[11];
 };
 static_assert(sizeof(SelState) == 128, "SelState layout");
+
+// What stands behind a filtered scan (the re-scan that materialises the scores, the full selection)
+// is enqueued with the scan, whether it will be needed or not, and looks at the scan's state when
+// it starts.  The gate is OPEN -- the launch has work to do -- when the fallback flag of that
+// state is raised, or, with k > 0, when the scan's candidate list cannot serve a list of k rows:
+// fewer than k rows on it, or more passed than it holds.  (k = 0: the flag alone decides; whoever
+// judges the lists raises it.)  No state: no gate, always open.  Uniform over the grid.
+struct Gate {
+    const SelState *st;
+    int k;
+};
+constexpr Gate kNoGate{nullptr, 0};
+__device__ __forceinline__ bool gate_open(const Gate &g) {
+    if (!g.st) return true;
+    if (g.st->fallback != 0u) return true;
+    if (g.k <= 0) return false;
+    const uint32_t n = g.st->cursor;
+    return n < (uint32_t)g.k || n > (uint32_t)kCandCap;
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -202,7 +223,7 @@ __device__ __forceinline__ BinChoice block_find_bin(const uint32_t *ghist, int n
 // r2.inbin sample rows lie at or above the threshold, and about kSampleStride times as many rows
 // of the store will.  When that is far beyond the candidate list's capacity (ties: a zero model,
 // scores that take few values) the scan is pointless: it returns at once, the list stays empty,
-// and the sort behind it raises the fallback.  Same answer in every workgroup.
+// and an empty list opens the gate of the full selection behind it.  Same answer in every workgroup.
 __device__ __forceinline__ bool filter_hopeless(uint32_t m, uint32_t need1, const BinChoice &r2) {
     const uint32_t at_or_above = (m - need1) + r2.above + r2.inbin;
     return at_or_above > 2u * (uint32_t)kCandCap / (uint32_t)kSampleStride;

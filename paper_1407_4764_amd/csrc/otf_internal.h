@@ -47,13 +47,19 @@ hipError_t launch_select_init(const SelectWs &sw, int Q, hipStream_t s);
 // The same for the full selection's state and the sample's in one launch.
 hipError_t launch_select_init_both(const SelectWs &sw, const SelectWs &sample_sw, int Q, hipStream_t s);
 // Radix pass 1 over ready-made scores (rows of length N, stride ld).
-hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const SelectWs &sw, int gated,
+hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const SelectWs &sw, Gate gate,
                         hipStream_t s);
-// Passes 2 and 3 (skipped on the device when pass 1 was decisive), gather and final sort, as four
-// launches; with `gated` (the fallback of a filtered scan) as one launch that returns at once unless
-// sw.st[0].fallback is set.
+// Passes 2 and 3 (skipped on the device when pass 1 was decisive), gather and final sort.
+//   kTailPlain       four launches
+//   kTailBehindFlag  the fallback of filtered scans whose lists launch_filter_sort has judged (many
+//                    classifiers): one launch that returns at once unless sw.st[0].fallback is set
+//   kTailBehindScan  the end of ONE classifier's filtered scan, in one launch: when the scan's list
+//                    serves (Gate{sw.st, k} shut) one workgroup sorts it into the outputs; otherwise
+//                    the flag is raised (for whoever asks afterwards) and the full selection runs on the
+//                    scores that the gated re-scan before this launch has written
+enum SelectTail { kTailPlain = 0, kTailBehindFlag = 1, kTailBehindScan = 2 };
 hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw,
-                              float *out_scores, int32_t *out_idx, int gated, hipStream_t s);
+                              float *out_scores, int32_t *out_idx, SelectTail tail, hipStream_t s);
 // Pass 2 over sample scores for rank m (many classifiers at once): sample_sw.st[q].tau_key receives
 // the threshold (top 24 bits of the m-th largest sample key), and main_st[0].fallback is raised when
 // a classifier's threshold would let far more rows pass than the candidate list holds.
@@ -76,7 +82,7 @@ hipError_t launch_dense_scan(const void *X, int x_is_half, int64_t N, int D, int
 // True for rows of at most 512 bytes: those scans also come as sample and filtered scans.
 bool dense_scan_filters(int x_is_half, int D);
 // The same scan in the three forms of the table scans (narrow rows only for the last two):
-//   kEmitScores  as above; with `gate` set the kernel returns at once unless gate->fallback is raised
+//   kEmitScores  as above; behind a gate (see Gate) the kernel returns at once unless the gate is open
 //   kEmitSample  N = rows of the strided sample, numbered compactly: the waves' largest keys into `slots`,
 //                their number into st (the sample's state)
 //   kEmitFilter  rows at or above the threshold go to cand (cursor in st); every workgroup resolves the
@@ -84,18 +90,18 @@ bool dense_scan_filters(int x_is_half, int D);
 hipError_t launch_dense_scan_emit(const void *X, int x_is_half, int64_t N, int D, int64_t ldx, const void *w,
                                   int w_is_half, const float *bias_ptr, int bias_index, ScanEmit emit, float *scores,
                                   uint32_t *hist1, uint32_t *chunk_ctr, SelState *st, const SelState *tau,
-                                  SampleSlot *slots, unsigned long long *cand, const SelState *gate, hipStream_t s);
+                                  SampleSlot *slots, unsigned long long *cand, Gate gate, hipStream_t s);
 
 // Multi-classifier fp16 scan on the matrix cores (Q = 32 or 64 classifiers per call).
-//   kEmitScores  scores[q][i] for every row (row stride ld_scores); with `gate` set the kernel returns
-//                at once unless gate->fallback is raised
+//   kEmitScores  scores[q][i] for every row (row stride ld_scores); behind a gate (see Gate) the kernel
+//                returns at once unless the gate is open
 //   kEmitSample  the same for the strided sample only (compact row numbering)
 //   kEmitFilter  nothing is stored but the rows with key >= tau[q].tau_key, appended to cand[q]; with
-//                `gate` set the kernel returns at once if gate->fallback is ALREADY raised
+//                a gate the kernel returns at once if gate.st->fallback is ALREADY raised
 // tile_ctr: a zeroed word in global memory (the kernel hands out its tiles dynamically).
 hipError_t launch_dense_mfma(const void *X, int64_t N, int D, int64_t ldx, const void *W, int Q, const float *bias,
                              ScanEmit emit, float *scores, int64_t ld_scores, const SelState *tau, SelState *st,
-                             unsigned long long *cand, const SelState *gate, uint32_t *tile_ctr, hipStream_t s);
+                             unsigned long long *cand, Gate gate, uint32_t *tile_ctr, hipStream_t s);
 
 // Byte-indexed table scans (product-quantised codes, binary codes).
 hipError_t launch_pq_build_lut(const float *codebooks, int M, int K, int dsub, const float *w, float *lut, hipStream_t s);
@@ -119,13 +125,13 @@ enum TableKind { kTableBytes = 0, kTableSeven = 1, kTableHamming = 2 };
 //                threshold from `slots` (their number in tau->ncand)
 hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, TableKind kind, const float *image,
                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1,
-                             const SelState *tau, SampleSlot *slots, unsigned long long *cand, const SelState *gate,
+                             const SelState *tau, SampleSlot *slots, unsigned long long *cand, Gate gate,
                              hipStream_t s);
 
 // Sparse-row store of 128-D features (mask + packed non-zero values per row, word offsets in start).
 hipError_t launch_sparse_scan(const uint32_t *rows, const int64_t *start, int64_t N, int64_t store_rows, const float *w,
                               float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1,
-                              const SelState *tau, SampleSlot *slots, unsigned long long *cand, const SelState *gate,
+                              const SelState *tau, SampleSlot *slots, unsigned long long *cand, Gate gate,
                               hipStream_t s);
 
 hipError_t launch_sgd_step(float *w, float *b, int D, const float *Xpos, int64_t ld_pos, const int32_t *idx_pos,

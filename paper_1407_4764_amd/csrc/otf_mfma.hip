@@ -33,11 +33,11 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__res
                                                          const float *__restrict__ bias, float *__restrict__ scores,
                                                          long long ld_scores, int vec_store,
                                                          const SelState *__restrict__ tau_state, SelState *st,
-                                                         unsigned long long *__restrict__ cand, const SelState *gate,
+                                                         unsigned long long *__restrict__ cand, Gate gate,
                                                          uint32_t *tile_ctr) {
     constexpr int QN = QT * 32;
     // uniform: a gated full scan is only the fallback of a filtered one; a gated filtered scan was called off
-    if (gate && (EMIT == kEmitFilter ? gate->fallback != 0u : gate->fallback == 0u)) return;
+    if (gate.st && (EMIT == kEmitFilter ? gate.st->fallback != 0u : !gate_open(gate))) return;
     __shared__ __attribute__((aligned(16))) uint8_t xs[kBM * kRowStride];
     __shared__ __attribute__((aligned(16))) uint8_t ws[QN * kRowStride];
     __shared__ uint32_t s_tile[8];                // ring: number of the block's j-th tile at slot j % 8
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const uint8_t *__res
 template <int QT>
 static hipError_t launch_mfma_qt(const uint8_t *X, int64_t N, int D, int64_t ldx, const uint8_t *W, const float *bias,
                                  ScanEmit emit, float *scores, int64_t ld_scores, const SelState *tau, SelState *st,
-                                 unsigned long long *cand, const SelState *gate, uint32_t *tile_ctr, hipStream_t s) {
+                                 unsigned long long *cand, Gate gate, uint32_t *tile_ctr, hipStream_t s) {
     const int64_t ntiles = (N + kBM - 1) / kBM;
     const int grid = (int)std::min<int64_t>(ntiles, (int64_t)device_cu_count() * tune_int(OTF_DEBUG_MFMA_BLOCKS_PER_CU, 2));
     const int vec_store = scores && (ld_scores % 4 == 0) && ((reinterpret_cast<uintptr_t>(scores) & 15) == 0);
@@ -282,7 +282,7 @@ static hipError_t launch_mfma_qt(const uint8_t *X, int64_t N, int D, int64_t ldx
 // tau, st and cand point at the first of the Q classifiers of this call; tile_ctr at a zeroed word.
 hipError_t launch_dense_mfma(const void *X, int64_t N, int D, int64_t ldx, const void *W, int Q, const float *bias,
                              ScanEmit emit, float *scores, int64_t ld_scores, const SelState *tau, SelState *st,
-                             unsigned long long *cand, const SelState *gate, uint32_t *tile_ctr, hipStream_t s) {
+                             unsigned long long *cand, Gate gate, uint32_t *tile_ctr, hipStream_t s) {
     const uint8_t *Xb = reinterpret_cast<const uint8_t *>(X);
     const uint8_t *Wb = reinterpret_cast<const uint8_t *>(W);
     if (Q == 32) return launch_mfma_qt<1>(Xb, N, D, ldx, Wb, bias, emit, scores, ld_scores, tau, st, cand, gate, tile_ctr, s);

@@ -18,11 +18,13 @@
 //
 // Filtered scans end here as well.  Their threshold comes from the largest keys the waves of a
 // sample scan met (resolve_tau_slots in otf_device.h; for many classifiers at once from passes 1
-// and 2 over the sample's scores, `tau_key`); the full scan appends only rows at or above it, and
-// filter_sort_kernel sorts that list.  If the list cannot serve (fewer than k rows or more than
-// it can hold) it raises `fallback`, and the full selection behind it runs: a gated re-scan that
-// materialises the scores, then select_fused_gated_kernel, which does passes 2 and 3, the gather
-// and the sort in one launch.  When the flag is clear both return at once.
+// and 2 over the sample's scores, `tau_key`); the full scan appends only rows at or above it.
+// Two launches stand behind it, both gated on the state the scan left (Gate in otf_device.h): a
+// re-scan that materialises the scores, and select_fused_gated_kernel.  If the list serves (at
+// least k rows on it, none lost) the re-scan returns at once and one workgroup of the second
+// launch sorts the list; otherwise the re-scan runs and the second launch does passes 2 and 3,
+// the gather and the sort of the full selection.  (Many classifiers at once: filter_sort_kernel
+// sorts every list and raises one flag for all if any cannot serve.)
 #include <algorithm>
 
 #include "otf_internal.h"
@@ -101,9 +103,9 @@ __device__ __forceinline__ void for_each_score(const float *s, long long begin, 
 }
 
 __global__ __launch_bounds__(1024) void hist1_kernel(const float *__restrict__ scores, long long N, long long ld,
-                                                    SelState *st_all, uint32_t *hist1_all, int gated) {
+                                                    SelState *st_all, uint32_t *hist1_all, Gate gate) {
     __shared__ uint32_t lhist[kBins1];
-    if (gated && st_all[0].fallback == 0u) return;
+    if (!gate_open(gate)) return;                          // uniform over the grid
     const int q = blockIdx.y;
     const float *s = scores + (long long)q * ld;
     const bool vec_ok = row_vec_ok(s);
@@ -244,7 +246,7 @@ __device__ __forceinline__ void gather_rows(const float *__restrict__ s, long lo
         if (lp < kGatherLocalCap) {
             local[lp] = pack_cand(key, row);
         } else {                                           // block buffer full: straight to the list
-            uint32_t pos = atomicAdd(&st->cursor, 1u);
+            uint32_t pos = atomicAdd(&st->gcursor, 1u);
             if (pos < (uint32_t)kCandCap) cand[pos] = pack_cand(key, row);
         }
     };
@@ -310,7 +312,7 @@ __device__ __forceinline__ void gather_rows(const float *__restrict__ s, long lo
     });
     __syncthreads();
     const uint32_t nloc = s_local_n < kGatherLocalCap ? s_local_n : kGatherLocalCap;
-    if (threadIdx.x == 0 && nloc) s_base = atomicAdd(&st->cursor, nloc);
+    if (threadIdx.x == 0 && nloc) s_base = atomicAdd(&st->gcursor, nloc);
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < nloc; i += blockDim.x) {
         const uint32_t pos = s_base + i;
@@ -586,11 +588,12 @@ __global__ __launch_bounds__(kSortThreads) void sort_emit_kernel(const SelState 
                      out_idx + (size_t)q * k);
 }
 
-// One block per classifier: end of a filtered scan.  `cursor` counts the rows the scan appended, or
-// is some number above the capacity when more passed than the list holds (a wave stops counting
-// once it has seen the list full).  With k <= cursor <= capacity the list holds
+// One block per classifier: end of the filtered scans of many classifiers.  `cursor` counts the rows
+// a scan appended, or is some number above the capacity when more passed than the list holds (a
+// wave stops counting once it has seen the list full).  With k <= cursor <= capacity the list holds
 // every row of the top k, so sorting it gives the exact answer; otherwise the fallback is raised
-// for all classifiers and the append cursor is cleared for the full selection that follows.
+// for all classifiers.  (One classifier: the last launch of the call judges and sorts, see
+// select_fused_gated_kernel.)
 __global__ __launch_bounds__(kSortThreads) void filter_sort_kernel(SelState *st_all,
                                                                    const unsigned long long *cand_all, int k,
                                                                    float *out_scores, int32_t *out_idx) {
@@ -598,8 +601,6 @@ __global__ __launch_bounds__(kSortThreads) void filter_sort_kernel(SelState *st_
     const int q = blockIdx.x;
     SelState *st = st_all + q;
     const uint32_t n = st->cursor;
-    __syncthreads();
-    if (threadIdx.x == 0) st->cursor = 0u;
     if (n < (uint32_t)k || n > (uint32_t)kCandCap) {
         if (threadIdx.x == 0) atomicOr(&st_all[0].fallback, 1u);
         return;
@@ -608,10 +609,12 @@ __global__ __launch_bounds__(kSortThreads) void filter_sort_kernel(SelState *st_
                      out_idx + (size_t)q * k);
 }
 
-// Full selection in ONE launch, for the fallback of a filtered scan only.  A ranking call enqueues
-// its fallback behind the filtered scan whether it will be needed or not, and a kernel that
-// returns at once still costs ~4 us on the stream: four such launches (passes 2 and 3, gather,
-// sort) were a twentieth of a ranking call.  This kernel does their work behind one gate:
+// The last launch of a filtered ranking: the sort of the scan's list, or, behind a gate, the full
+// selection in ONE launch.  A ranking call enqueues its fallback behind the filtered scan whether
+// it will be needed or not, and a kernel that returns at once still costs ~4 us on the stream:
+// four such launches (passes 2 and 3, gather, sort) and a launch of its own for the sort of the
+// list were a fifteenth of a ranking call.  With the gate open this kernel does the work of the
+// four:
 //   every workgroup   resolves pass 1 (the gated scan accumulated its histogram).  Decisive (the
 //                     usual case): gathers the candidates of its share of the rows, takes a ticket,
 //                     and the workgroup that draws the last one sorts the list.
@@ -672,15 +675,24 @@ __global__ __launch_bounds__(kSortThreads) void select_fused_gated_kernel(const 
                                                                            uint32_t *blockhist3_all,
                                                                            unsigned long long *cand_all,
                                                                            float *out_scores, int32_t *out_idx, int meet_ok,
-                                                                           uint32_t spin_limit) {
+                                                                           uint32_t spin_limit, int judge_k) {
     extern __shared__ __attribute__((aligned(16))) uint8_t sort_lds[];
     __shared__ uint32_t lhist[kBins2];
     __shared__ uint32_t s_out[3];
     __shared__ uint32_t s_last, s_role;
     __shared__ uint32_t wave_sum_s[16];
-    if (st_all[0].fallback == 0u) return;                  // uniform over the grid
     const int q = blockIdx.y;
     SelState *st = st_all + q;
+    // judge_k = 0: the lists have been judged (filter_sort_kernel), the flag says whether there is work.
+    // judge_k = k (one classifier): this launch is also the end of the filtered scan.  Its list serves
+    // when it holds at least k rows and lost none: then one workgroup sorts it and that is all.
+    if (!gate_open(Gate{st_all, judge_k})) {               // uniform over the grid
+        if (judge_k > 0 && blockIdx.x == 0)
+            select_sort_emit(sort_lds, cand_all + (size_t)q * kCandCap, st->cursor, k, out_scores + (size_t)q * k,
+                             out_idx + (size_t)q * k);
+        return;
+    }
+    if (judge_k > 0 && blockIdx.x == 0 && threadIdx.x == 0) st_all[0].fallback = 1u;   // (for whoever asks afterwards)
     const float *s = scores + (long long)q * ld;
     const bool vec_ok = row_vec_ok(s);
     unsigned long long *cand = cand_all + (size_t)q * kCandCap;
@@ -803,9 +815,9 @@ __global__ __launch_bounds__(kSortThreads) void select_fused_gated_kernel(const 
 // the filtered scans applied to otf_topk.  topk_sample_kernel zeroes the selection state and
 // leaves the largest key each of its waves met in a strided sample of the scores (every
 // kSampleStride-th group of kSampleGroup); topk_filter_kernel takes the threshold from those (see
-// resolve_tau_slots) and reads the scores once, keeping the ones at or above it; the list is
-// sorted by filter_sort_kernel, and the exact passes stand behind its flag as they do behind
-// every filtered scan.
+// resolve_tau_slots) and reads the scores once, keeping the ones at or above it; pass 1 and
+// select_fused_gated_kernel stand behind it as the re-scan and the selection stand behind every
+// filtered scan.
 __global__ __launch_bounds__(256) void topk_sample_kernel(const float *__restrict__ scores, long long Nv, SelState *st,
                                                           uint32_t *hist1, uint32_t *hist2, uint32_t *hist3,
                                                           SelState *sample_st, SampleSlot *slots) {
@@ -840,7 +852,7 @@ __global__ __launch_bounds__(512) void topk_filter_kernel(const float *__restric
     __shared__ unsigned long long local[kLocal];
     __shared__ uint32_t s_n, s_base;
     const TauChoice tc = resolve_tau_slots(slots, sample_st, N, lds, s_out);
-    if (tc.hopeless) return;                                // uniform: the list stays empty, the sort raises the fallback
+    if (tc.hopeless) return;                                // uniform: the list stays empty, which opens the gate of the exact passes
     if (threadIdx.x == 0) s_n = 0u;
     __syncthreads();
     long long begin, end;
@@ -902,7 +914,7 @@ hipError_t launch_select_init_both(const SelectWs &sw, const SelectWs &sample_sw
     return hipGetLastError();
 }
 
-hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const SelectWs &sw, int gated,
+hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const SelectWs &sw, Gate gate,
                         hipStream_t s) {
     // A plain histogram, free of the per-block tables of the later passes.  Every workgroup ends by
     // adding its bins to the global histogram, and the scores crowd into a hundred-odd bins, so the
@@ -910,14 +922,15 @@ hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const
     // workgroups (one of 1024 threads per compute unit: 35 us for 50M scores; four of 512: 42 us).
     int64_t blocks = std::min<int64_t>((N + 8191) / 8192, std::max<int64_t>(1, (int64_t)device_cu_count() / Q));
     blocks = std::max<int64_t>(blocks, sel_blocks(N, Q));
-    hist1_kernel<<<dim3((unsigned)blocks, Q), 1024, 0, s>>>(scores, N, ld, sw.st, sw.hist1, gated);
+    hist1_kernel<<<dim3((unsigned)blocks, Q), 1024, 0, s>>>(scores, N, ld, sw.st, sw.hist1, gate);
     return hipGetLastError();
 }
 
 hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw,
-                              float *out_scores, int32_t *out_idx, int gated, hipStream_t s) {
+                              float *out_scores, int32_t *out_idx, SelectTail tail, hipStream_t s) {
     dim3 grid(sel_blocks(N, Q), Q);
-    if (gated) {                                   // the fallback of a filtered scan: one launch behind one gate
+    if (tail != kTailPlain) {                      // behind filtered scans: one launch behind one gate
+        if (tail == kTailBehindScan && Q != 1) return hipErrorInvalidValue;
         hipError_t e = allow_sort_lds();
         if (e != hipSuccess) return e;
         // the workgroups may wait for each other only if all of them are resident at once: one per compute unit
@@ -925,7 +938,8 @@ hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q,
         select_fused_gated_kernel<<<grid, kSortThreads, kSortLdsBytes, s>>>(scores, N, ld, k, sw.st, sw.hist1, sw.hist2,
                                                                             sw.hist3, sw.blockhist3, sw.cand, out_scores,
                                                                             out_idx, meet_ok,
-                                                                            (uint32_t)tune_int(OTF_DEBUG_MEET_SPIN_LIMIT, (int)kMeetSpinLimit));
+                                                                            (uint32_t)tune_int(OTF_DEBUG_MEET_SPIN_LIMIT, (int)kMeetSpinLimit),
+                                                                            tail == kTailBehindScan ? k : 0);
         return hipGetLastError();
     }
     // (1024 threads: the histogram passes hide the latency of their votes and shared-memory adds behind more waves)
@@ -954,9 +968,8 @@ hipError_t launch_topk_filtered(const float *scores, int64_t N, int k, const Sel
     const int sample_grid = (int)std::min<int64_t>(std::max<int64_t>(1, Nv / 1024), device_cu_count());
     topk_sample_kernel<<<sample_grid, 256, 0, s>>>(scores, Nv, sw.st, sw.hist1, sw.hist2, sw.hist3, sample_sw.st, slots);
     topk_filter_kernel<<<kSelBlocks, 512, 0, s>>>(scores, N, sw.st, sample_sw.st, slots, sw.cand);
-    hipError_t e = launch_filter_sort(sw, 1, k, out_scores, out_idx, s);
-    if (e == hipSuccess) e = launch_hist1(scores, N, N, 1, sw, 1, s);
-    if (e == hipSuccess) e = launch_select_tail(scores, N, N, 1, k, sw, out_scores, out_idx, 1, s);
+    hipError_t e = launch_hist1(scores, N, N, 1, sw, Gate{sw.st, k}, s);
+    if (e == hipSuccess) e = launch_select_tail(scores, N, N, 1, k, sw, out_scores, out_idx, kTailBehindScan, s);
     return e;
 }
 

@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
     const uint32_t *__restrict__ rows, const long long *__restrict__ start, long long N, long long store_rows,
     const float *__restrict__ w, float bias, float *__restrict__ scores, SelState *st, uint32_t *hist1,
     const SelState *tau_state, SampleSlot *sample_slots, unsigned long long *__restrict__ cand,
-    const SelState *gate) {
+    Gate gate) {
     __shared__ __attribute__((aligned(16))) uint32_t win[kSparseThreads / 64][kWinBufWords];
     // the pass-1 histogram of the scores; a scan that keeps no scores only needs the room once, before
     // its first window, to resolve the threshold: it borrows the windows' buffers
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kSparseThreads) void sparse_scan_kernel(
     uint32_t *lhist = EMIT == kEmitScores ? lhist_own : &win[0][0];
     __shared__ uint32_t s_out[3];
     __shared__ TileQueue s_queue;
-    if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
+    if (!gate_open(gate)) return;                 // uniform: this launch is only the fallback of a filtered scan
     uint32_t *chunk_ctr = &st->chunk_ctr[EMIT == kEmitScores ? 1 : 0];
     if (threadIdx.x == 0) tile_queue_init(&s_queue, chunk_ctr);
     const long long total_tiles = (N + kSparseTileRows<EMIT> - 1) / kSparseTileRows<EMIT>;
@@ -253,7 +253,7 @@ template <int EMIT>
 static hipError_t launch_sparse_cfg(const uint32_t *rows, const int64_t *start, int64_t N, int64_t store_rows,
                                     const float *w, float bias, float *scores, SelState *st, uint32_t *hist1,
                                     const SelState *tau, SampleSlot *slots, unsigned long long *cand,
-                                    const SelState *gate, hipStream_t s) {
+                                    Gate gate, hipStream_t s) {
     const int64_t tiles = (N + kSparseTileRows<EMIT> - 1) / kSparseTileRows<EMIT>;
     // three workgroups per compute unit: with one or two the kernel takes 2.2x and 1.3x as long, and a
     // fourth (the registers would allow it) makes it 3 % slower: the shared-memory unit is the limit
@@ -267,7 +267,7 @@ static hipError_t launch_sparse_cfg(const uint32_t *rows, const int64_t *start, 
 // N = rows to score (kEmitSample: the sample rows, compact numbering); store_rows = rows of the store.
 hipError_t launch_sparse_scan(const uint32_t *rows, const int64_t *start, int64_t N, int64_t store_rows, const float *w,
                               float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1,
-                              const SelState *tau, SampleSlot *slots, unsigned long long *cand, const SelState *gate,
+                              const SelState *tau, SampleSlot *slots, unsigned long long *cand, Gate gate,
                               hipStream_t s) {
     switch (emit) {
         case kEmitScores:

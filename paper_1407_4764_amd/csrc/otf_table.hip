@@ -307,12 +307,12 @@ template <int LPR, int U, int GB, int EMIT>
 __global__ __launch_bounds__(kScanMaxThreads) void table_scan_kernel(
     const uint8_t *__restrict__ codes, long long N, int M, const float *__restrict__ image, float bias,
     float *__restrict__ scores, SelState *st, uint32_t *hist1, const SelState *tau_state,
-    SampleSlot *sample_slots, unsigned long long *__restrict__ cand, const SelState *gate) {
+    SampleSlot *sample_slots, unsigned long long *__restrict__ cand, Gate gate) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     __shared__ uint32_t lhist[EMIT == kEmitScores ? kBins1 : 1];
     __shared__ uint32_t s_out[3];
     __shared__ TileQueue s_queue;
-    if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
+    if (!gate_open(gate)) return;                 // uniform: this launch is only the fallback of a filtered scan
     constexpr int RPW = 64 / LPR;                // rows per wave load
     constexpr int TILE = RPW * U;                // rows per wave iteration
     constexpr int ACTIVE = LPR < U ? LPR : U;    // lanes of a group that own an output row per round
@@ -484,13 +484,13 @@ template <int EMIT, int TPW>
 __global__ __launch_bounds__(kScanMaxThreads) void table_walk_kernel(
     const uint8_t *__restrict__ codes, long long N, int row_bytes, int nphase, const float *__restrict__ image,
     float bias, float *__restrict__ scores, SelState *st, uint32_t *hist1, const SelState *tau_state,
-    SampleSlot *sample_slots, unsigned long long *__restrict__ cand, const SelState *gate) {
+    SampleSlot *sample_slots, unsigned long long *__restrict__ cand, Gate gate) {
     static_assert(TPW % 2 == 0, "tiles alternate between two register buffers");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     __shared__ uint32_t lhist[EMIT == kEmitScores ? kBins1 : 1];
     __shared__ uint32_t s_out[3];
     __shared__ uint32_t s_blk[4];                 // ring: number of the workgroup's j-th block at slot j % 4
-    if (gate && gate->fallback == 0u) return;     // uniform: this launch is only the fallback of a filtered scan
+    if (!gate_open(gate)) return;                 // uniform: this launch is only the fallback of a filtered scan
     constexpr int U = 8, RPW = 8, TILE = 64;
     const int tid = threadIdx.x, lane = tid & 63, nwaves = blockDim.x >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: tile addresses are uniform
@@ -700,7 +700,7 @@ struct ScanArgs {
     const SelState *tau;         // filtered scan: the sample's state (number of slots)
     SampleSlot *slots;           // sample scan: written; filtered scan: read
     unsigned long long *cand;
-    const SelState *gate;
+    Gate gate;
 };
 
 template <int LPR, int U, int GB, int EMIT>
@@ -765,7 +765,7 @@ static hipError_t launch_walk_emit(const ScanArgs &a, ScanEmit emit, hipStream_t
 // row_bytes = stored bytes per row, a multiple of 16 up to 1024; kTableSeven only with 256.
 hipError_t launch_table_scan(const uint8_t *codes, int64_t N, int row_bytes, TableKind kind, const float *image,
                              float bias, ScanEmit emit, float *scores, SelState *st, uint32_t *hist1,
-                             const SelState *tau, SampleSlot *slots, unsigned long long *cand, const SelState *gate,
+                             const SelState *tau, SampleSlot *slots, unsigned long long *cand, Gate gate,
                              hipStream_t s) {
     ScanArgs a{codes, N, row_bytes, image, bias, scores, st, hist1, tau, slots, cand, gate};
     if (kind == kTableSeven) return launch_scan_emit<16, 7>(a, emit, s);
