@@ -633,8 +633,10 @@ __global__ __launch_bounds__(kSortThreads) void filter_sort_kernel(SelState *st_
 //                     complete -- finishes the remaining passes over all rows by itself, slowly
 //                     but exactly.  `meet` = 0 (the grid may exceed what is resident at once: many
 //                     classifiers) goes that way from the start.
-// Stand-alone selection (otf_topk, scans that materialise their scores) keeps the chain: there
-// every pass runs, and a fence per workgroup would cost more than the launches.
+// Stand-alone selection (otf_topk, scans that materialise their scores) keeps the chain of four
+// launches: there every pass runs, and when pass 1 does not decide -- the headline store: 1M scores
+// whose k-th shares its 12-bit bin with more rows than the list holds -- this kernel, with its
+// meetings, takes 60 us longer than the chain (1.238 against 1.180 ms per call).
 enum MeetRole : uint32_t { kTogether = 1u, kAlone = 2u, kLeave = 3u };
 constexpr uint32_t kMeetSpinLimit = 1u << 14;               // polls of ~1-2 us: ten times a pass over any store
                                                             // (diagnostic switch OTF_DEBUG_MEET_SPIN_LIMIT: 1 makes every wait give up)
@@ -675,7 +677,7 @@ __global__ __launch_bounds__(kSortThreads) void select_fused_gated_kernel(const 
                                                                            uint32_t *blockhist3_all,
                                                                            unsigned long long *cand_all,
                                                                            float *out_scores, int32_t *out_idx, int meet_ok,
-                                                                           uint32_t spin_limit, int judge_k) {
+                                                                           uint32_t spin_limit, Gate gate, int sorts_list) {
     extern __shared__ __attribute__((aligned(16))) uint8_t sort_lds[];
     __shared__ uint32_t lhist[kBins2];
     __shared__ uint32_t s_out[3];
@@ -683,16 +685,16 @@ __global__ __launch_bounds__(kSortThreads) void select_fused_gated_kernel(const 
     __shared__ uint32_t wave_sum_s[16];
     const int q = blockIdx.y;
     SelState *st = st_all + q;
-    // judge_k = 0: the lists have been judged (filter_sort_kernel), the flag says whether there is work.
-    // judge_k = k (one classifier): this launch is also the end of the filtered scan.  Its list serves
-    // when it holds at least k rows and lost none: then one workgroup sorts it and that is all.
-    if (!gate_open(Gate{st_all, judge_k})) {               // uniform over the grid
-        if (judge_k > 0 && blockIdx.x == 0)
+    // A gate on the flag alone: the lists of many classifiers have been judged (filter_sort_kernel).
+    // sorts_list (one classifier, gate on the scan's own cursor): this launch is also the end of the
+    // filtered scan; when the list serves, one workgroup sorts it and that is all.
+    if (!gate_open(gate)) {                                // uniform over the grid
+        if (sorts_list && blockIdx.x == 0)
             select_sort_emit(sort_lds, cand_all + (size_t)q * kCandCap, st->cursor, k, out_scores + (size_t)q * k,
                              out_idx + (size_t)q * k);
         return;
     }
-    if (judge_k > 0 && blockIdx.x == 0 && threadIdx.x == 0) st_all[0].fallback = 1u;   // (for whoever asks afterwards)
+    if (sorts_list && blockIdx.x == 0 && threadIdx.x == 0) st_all[0].fallback = 1u;   // (for whoever asks afterwards)
     const float *s = scores + (long long)q * ld;
     const bool vec_ok = row_vec_ok(s);
     unsigned long long *cand = cand_all + (size_t)q * kCandCap;
@@ -929,8 +931,8 @@ hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const
 hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw,
                               float *out_scores, int32_t *out_idx, SelectTail tail, hipStream_t s) {
     dim3 grid(sel_blocks(N, Q), Q);
+    if (tail == kTailBehindScan && Q != 1) return hipErrorInvalidValue;
     if (tail != kTailPlain) {                      // behind filtered scans: one launch behind one gate
-        if (tail == kTailBehindScan && Q != 1) return hipErrorInvalidValue;
         hipError_t e = allow_sort_lds();
         if (e != hipSuccess) return e;
         // the workgroups may wait for each other only if all of them are resident at once: one per compute unit
@@ -939,7 +941,8 @@ hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q,
                                                                             sw.hist3, sw.blockhist3, sw.cand, out_scores,
                                                                             out_idx, meet_ok,
                                                                             (uint32_t)tune_int(OTF_DEBUG_MEET_SPIN_LIMIT, (int)kMeetSpinLimit),
-                                                                            tail == kTailBehindScan ? k : 0);
+                                                                            Gate{sw.st, tail == kTailBehindScan ? k : 0},
+                                                                            tail == kTailBehindScan ? 1 : 0);
         return hipGetLastError();
     }
     // (1024 threads: the histogram passes hide the latency of their votes and shared-memory adds behind more waves)
