@@ -635,8 +635,13 @@ __global__ __launch_bounds__(kSortThreads) void filter_sort_kernel(SelState *st_
 //                     classifiers) goes that way from the start.
 // Stand-alone selection (otf_topk, scans that materialise their scores) keeps the chain of four
 // launches: there every pass runs, and when pass 1 does not decide -- the headline store: 1M scores
-// whose k-th shares its 12-bit bin with more rows than the list holds -- this kernel, with its
-// meetings, takes 60 us longer than the chain (1.238 against 1.180 ms per call).
+// whose k-th shares its 12-bit bin with more rows than the list holds -- this kernel takes 34 us
+// against the chain's 31 (a meeting costs what a launch costs).
+//
+// Fences: a meeting or a ticket is ONE thread's release or acquire, passed on to its workgroup by
+// the barriers around it.  Device-wide fences executed by every wave of every workgroup
+// (__threadfence() before the ticket, an acquire after each meeting) cost 40-55 us apiece on 256
+// workgroups of 16 waves: the worst case of the filtered ranking went from 1.10 to 0.97 ms.
 enum MeetRole : uint32_t { kTogether = 1u, kAlone = 2u, kLeave = 3u };
 constexpr uint32_t kMeetSpinLimit = 1u << 14;               // polls of ~1-2 us: ten times a pass over any store
                                                             // (diagnostic switch OTF_DEBUG_MEET_SPIN_LIMIT: 1 makes every wait give up)
@@ -663,10 +668,10 @@ __device__ __forceinline__ MeetRole meet(uint32_t *met, uint32_t *verdict, uint3
             }
             role = v == 1u ? kTogether : kLeave;
         }
-        *s_role = role;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // the others' histograms, not stale cache lines (one
+        *s_role = role;                                     // thread: the barrier passes it on to the workgroup)
     }
     __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");      // the others' histograms, not stale cache lines
     return (MeetRole)*s_role;
 }
 
@@ -771,12 +776,14 @@ __global__ __launch_bounds__(kSortThreads) void select_fused_gated_kernel(const 
     // ticket: the workgroup that draws the last one continues alone (and a workgroup that already
     // is alone has no one to wait for)
     if (!alone) {
-        __threadfence();
+        // one thread releases what the whole workgroup wrote (the barrier orders the others' stores
+        // before it): a device-wide fence by every wave of every workgroup costs ~55 us here
         __syncthreads();
-        if (threadIdx.x == 0) s_last = atomicAdd(&st->spare, 1u) == gridDim.x - 1u ? 1u : 0u;
+        if (threadIdx.x == 0)
+            s_last = __hip_atomic_fetch_add(&st->spare, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1u ? 1u : 0u;
         __syncthreads();
         if (s_last == 0u) return;                          // uniform over the workgroup
-        __threadfence();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // the others' parts of the list, not stale cache lines
     }
     if (!decisive1 && (alone || !meet_ok)) {
         // passes 2 (resolve), 3 and the gather over all rows by this workgroup
