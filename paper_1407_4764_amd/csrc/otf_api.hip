@@ -31,8 +31,6 @@ WsLayout ws_layout(int64_t N, int32_t Q) {
     L.eqoff = take((size_t)Q * kSelBlocks * 4);
     L.cand = take((size_t)Q * kCandCap * 8);
     L.sample_st = take((size_t)Q * sizeof(SelState));
-    L.sample_hist1 = take((size_t)Q * kHist1Words * 4);
-    L.sample_hist2 = take((size_t)Q * kBins2 * 4);
     L.sample_ld = padded_rows(sample_rows(N) + kSampleGroup);
     // (the single-classifier scans keep one 8-byte slot per wave of the sample scan here instead: at most 4096)
     L.sample_scores = take(std::max<size_t>((size_t)Q * (size_t)L.sample_ld * 4, (size_t)kMaxSampleSlots * sizeof(SampleSlot)));
@@ -56,13 +54,13 @@ SelectWs select_ws(void *ws, const WsLayout &L) {
     return sw;
 }
 
-// The sample thresholding only runs passes 1 and 2, so it has no pass-3 or candidate storage.
+// The sample side of a filtered ranking keeps states only (work counters, slot counts, thresholds).
 SelectWs sample_select_ws(void *ws, const WsLayout &L) {
     uint8_t *p = reinterpret_cast<uint8_t *>(ws);
     SelectWs sw;
     sw.st = reinterpret_cast<SelState *>(p + L.sample_st);
-    sw.hist1 = reinterpret_cast<uint32_t *>(p + L.sample_hist1);
-    sw.hist2 = reinterpret_cast<uint32_t *>(p + L.sample_hist2);
+    sw.hist1 = nullptr;
+    sw.hist2 = nullptr;
     sw.hist3 = nullptr;
     sw.blockhist3 = nullptr;
     sw.eqoff = nullptr;
@@ -292,7 +290,9 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
         if (e == hipSuccess) e = launch_select_tail(S, N, ldS, 1, k, sw, out_scores, out_idx, kTailBehindScan, s);
         return hip_status(e);
     }
-    hipError_t e = launch_select_init(sw, Q, s);
+    // (the filtered multi-classifier route also needs the states that threshold the sample: same launch)
+    const bool mfma_filtered = mfma && filter_eligible(N, k, all_scores);
+    hipError_t e = mfma_filtered ? launch_select_init_both(sw, sample_select_ws(ws, L), Q, s) : launch_select_init(sw, Q, s);
 
     // One matrix-core launch per group of 64 (or a last 32) classifiers.
     // (ctr_states[q0].chunk_ctr[ctr_word]: the zeroed work counter of each launch)
@@ -310,15 +310,13 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
         return err;
     };
 
-    if (mfma && filter_eligible(N, k, all_scores)) {
+    if (mfma_filtered) {
         // sample -> per-classifier thresholds -> filtered scan -> sort; full selection behind a gate
         SelectWs ssw = sample_select_ws(ws, L);
         float *sample = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ws) + L.sample_scores);
         const int64_t Nv = sample_rows(N);
         const int m = sample_rank(N, Nv);
-        if (e == hipSuccess) e = launch_select_init(ssw, Q, s);
         if (e == hipSuccess) e = mfma_scan(Nv, kEmitSample, sample, L.sample_ld, nullptr, nullptr, nullptr, kNoGate, ssw.st, 0);
-        if (e == hipSuccess) e = launch_hist1(sample, Nv, L.sample_ld, Q, ssw, kNoGate, s);
         if (e == hipSuccess) e = launch_sample_threshold(sample, Nv, L.sample_ld, Q, m, ssw, sw.st, s);
         ScanTimer timer(s);
         if (e == hipSuccess) e = mfma_scan(N, kEmitFilter, nullptr, 0, ssw.st, sw.st, sw.cand, Gate{sw.st, 0}, sw.st, 0);

@@ -21,7 +21,7 @@ struct SelectWs {
 };
 
 struct WsLayout {
-    size_t st, hist1, hist2, hist3, blockhist3, eqoff, cand, sample_st, sample_hist1, sample_hist2, sample_scores,
+    size_t st, hist1, hist2, hist3, blockhist3, eqoff, cand, sample_st, sample_scores,
         lut_image, short_store, scores, total;
     int64_t sample_ld;   // row stride (floats) of the sample score buffer
 };
@@ -60,9 +60,10 @@ hipError_t launch_hist1(const float *scores, int64_t N, int64_t ld, int Q, const
 enum SelectTail { kTailPlain = 0, kTailBehindFlag = 1, kTailBehindScan = 2 };
 hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q, int k, const SelectWs &sw,
                               float *out_scores, int32_t *out_idx, SelectTail tail, hipStream_t s);
-// Pass 2 over sample scores for rank m (many classifiers at once): sample_sw.st[q].tau_key receives
-// the threshold (top 24 bits of the m-th largest sample key), and main_st[0].fallback is raised when
-// a classifier's threshold would let far more rows pass than the candidate list holds.
+// Thresholds of the filtered scans of Q classifiers from the Nv sample scores of each (rank m):
+// sample_sw.st[q].tau_key receives the top 24 bits of the m-th largest sample key, and
+// main_st[0].fallback is raised when a classifier's threshold would let far more rows pass than the
+// candidate list holds.  Only the states of sample_sw are used.
 hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64_t ld, int Q, int m,
                                    const SelectWs &sample_sw, SelState *main_st, hipStream_t s);
 // otf_topk in one read of the scores (one classifier, N large enough for a sample): zeroes the states

@@ -32,8 +32,7 @@
 namespace otf {
 
 __global__ __launch_bounds__(256) void select_init_kernel(SelState *st, uint32_t *hist1, uint32_t *hist2,
-                                                          uint32_t *hist3, SelState *sample_st,
-                                                          uint32_t *sample_hist1, uint32_t *sample_hist2, int Q) {
+                                                          uint32_t *hist3, SelState *sample_st, int Q) {
     const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t step = (size_t)gridDim.x * blockDim.x;
     uint32_t *stw = reinterpret_cast<uint32_t *>(st);
@@ -45,8 +44,6 @@ __global__ __launch_bounds__(256) void select_init_kernel(SelState *st, uint32_t
     if (sample_st) {                                  // the state that thresholds a sample, in the same launch
         uint32_t *sw = reinterpret_cast<uint32_t *>(sample_st);
         for (size_t i = tid; i < (size_t)Q * (sizeof(SelState) / 4); i += step) sw[i] = 0u;
-        for (size_t i = tid; i < (size_t)Q * kHist1Words; i += step) sample_hist1[i] = 0u;
-        for (size_t i = tid; i < (size_t)Q * kBins2; i += step) sample_hist2[i] = 0u;
     }
 }
 
@@ -117,11 +114,10 @@ __global__ __launch_bounds__(1024) void hist1_kernel(const float *__restrict__ s
     merge_hist1(lhist, hist1_all + (size_t)q * kHist1Words);
 }
 
-// Pass 2.  Resolves pass 1 first (rank k in hist1).  force: always run pass 2 (threshold
-// estimation on a sample); otherwise return when pass 1 was decisive.
+// Pass 2.  Resolves pass 1 first (rank k in hist1); returns at once when pass 1 was decisive.
 __global__ __launch_bounds__(1024) void hist2_kernel(const float *__restrict__ scores, long long N, long long ld,
                                                     int k, SelState *st_all, const uint32_t *hist1_all,
-                                                    uint32_t *hist2_all, int force) {
+                                                    uint32_t *hist2_all) {
     __shared__ uint32_t lhist[kBins2];
     __shared__ uint32_t s_out[3];
     const int q = blockIdx.y;
@@ -138,7 +134,7 @@ __global__ __launch_bounds__(1024) void hist2_kernel(const float *__restrict__ s
             st->tex = ((long long)b1 << 20) - 1;
         }
     }
-    if (decisive && !force) return;
+    if (decisive) return;
     const float *s = scores + (long long)q * ld;
     const bool vec_ok = row_vec_ok(s);
     for (int b = threadIdx.x; b < kBins2; b += blockDim.x) lhist[b] = 0u;
@@ -167,20 +163,56 @@ __device__ __forceinline__ Pass2 resolve_pass2(const SelState *st, const uint32_
     return p;
 }
 
-// One block per classifier: the threshold of a filtered scan from passes 1 and 2 over the sample.
-// p.c2 sample rows lie at or above it.  When that predicts far more rows of the store than the
-// candidate list holds (see filter_hopeless) the filtered scan is called off for the whole call:
-// the fallback flag of the full selection's state is raised here already, and the scan, which
-// is given that state as its gate, returns at once.
-__global__ __launch_bounds__(512) void sample_tau_kernel(SelState *sample_st_all, const uint32_t *hist2_all, int m,
-                                                         SelState *main_st_all) {
-    __shared__ uint32_t lhist[kBins2];
+// One workgroup per classifier: the threshold of its filtered scan from the Nv scores of the strided
+// sample (many classifiers at once; a single classifier's scans use wave maxima instead, see
+// resolve_tau_slots).  Two radix passes in shared memory resolve the m-th largest sample key to 24
+// bits: tau_key; about m * N / Nv rows of the store lie at or above it.  c2 sample rows do.  When
+// that predicts far more rows of the store than the candidate list holds (ties: a zero model, scores
+// that take few values) the filtered scan is called off for the whole call: the fallback flag of the
+// full selection's state is raised here already, and the scan, which is given that state as its
+// gate, returns at once.  (As three launches -- pass 1, pass 2, resolution, each over all
+// classifiers -- this took 27 us of a 64-classifier call; a sample is a few tens of thousands of
+// scores per classifier.)  Requires 1 <= m <= Nv.
+__global__ __launch_bounds__(1024) void sample_threshold_kernel(const float *__restrict__ sample, long long Nv,
+                                                                long long ld, int m, SelState *sample_st_all,
+                                                                SelState *main_st_all) {
+    __shared__ uint32_t lhist[kBins1];
     __shared__ uint32_t s_out[3];
+    static_assert(kBins2 <= kBins1, "both passes use the same shared histogram");
     const int q = blockIdx.x;
-    const Pass2 p = resolve_pass2(sample_st_all + q, hist2_all + (size_t)q * kBins2, m, lhist, s_out);
+    const float *s = sample + (long long)q * ld;
+    const bool vec_ok = row_vec_ok(s);
+    uint32_t b1 = 0u, need = (uint32_t)m, above1 = 0u;
+#pragma unroll 1
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int b = threadIdx.x; b < kBins1; b += blockDim.x) lhist[b] = 0u;
+        __syncthreads();
+        for_each_score(s, 0, Nv, vec_ok, [&](float v, bool ok, long long) {
+            const uint32_t key = float_to_key(v);
+            if (pass == 0) hist_add_wave(lhist, key >> 20, ok);
+            else hist_add_wave(lhist, (key >> 8) & 0xFFFu, ok && (key >> 20) == b1);
+        });
+        __syncthreads();
+        if (threadIdx.x < 64) {
+            uint32_t above, inbin;
+            const uint32_t bin = wave_find_bin(lhist, kBins1 / 64, need, &above, &inbin);
+            if (threadIdx.x == 0) {
+                s_out[0] = bin;
+                s_out[1] = above;
+                s_out[2] = inbin;
+            }
+        }
+        __syncthreads();
+        if (pass == 0) {
+            b1 = s_out[0];
+            above1 = s_out[1];
+            need -= above1;
+        }
+    }
     if (threadIdx.x == 0) {
-        sample_st_all[q].tau_key = p.p24 << 8;
-        if (main_st_all && p.c2 > 2u * (uint32_t)kCandCap / (uint32_t)kSampleStride) atomicOr(&main_st_all[0].fallback, 1u);
+        sample_st_all[q].tau_key = ((b1 << 12) | s_out[0]) << 8;
+        const uint32_t c2 = above1 + s_out[1] + s_out[2];           // sample keys at or above the threshold
+        if (c2 > 2u * (uint32_t)kCandCap / (uint32_t)kSampleStride) atomicOr(&main_st_all[0].fallback, 1u);
     }
 }
 
@@ -911,15 +943,14 @@ static int sel_blocks(int64_t N, int Q) {
 hipError_t launch_select_init(const SelectWs &sw, int Q, hipStream_t s) {
     int blocks = (int)(((size_t)Q * kHist1Words + 255) / 256);
     if (blocks > 1024) blocks = 1024;
-    select_init_kernel<<<blocks, 256, 0, s>>>(sw.st, sw.hist1, sw.hist2, sw.hist3, nullptr, nullptr, nullptr, Q);
+    select_init_kernel<<<blocks, 256, 0, s>>>(sw.st, sw.hist1, sw.hist2, sw.hist3, nullptr, Q);
     return hipGetLastError();
 }
 
 hipError_t launch_select_init_both(const SelectWs &sw, const SelectWs &sample_sw, int Q, hipStream_t s) {
     int blocks = (int)(((size_t)Q * kHist1Words + 255) / 256);
     if (blocks > 1024) blocks = 1024;
-    select_init_kernel<<<blocks, 256, 0, s>>>(sw.st, sw.hist1, sw.hist2, sw.hist3, sample_sw.st, sample_sw.hist1,
-                                              sample_sw.hist2, Q);
+    select_init_kernel<<<blocks, 256, 0, s>>>(sw.st, sw.hist1, sw.hist2, sw.hist3, sample_sw.st, Q);
     return hipGetLastError();
 }
 
@@ -953,7 +984,7 @@ hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q,
         return hipGetLastError();
     }
     // (1024 threads: the histogram passes hide the latency of their votes and shared-memory adds behind more waves)
-    hist2_kernel<<<grid, 1024, 0, s>>>(scores, N, ld, k, sw.st, sw.hist1, sw.hist2, 0);
+    hist2_kernel<<<grid, 1024, 0, s>>>(scores, N, ld, k, sw.st, sw.hist1, sw.hist2);
     hist3_kernel<<<grid, 1024, 0, s>>>(scores, N, ld, k, sw.st, sw.hist2, sw.hist3, sw.blockhist3);
     gather_kernel<<<grid, 512, 0, s>>>(scores, N, ld, k, sw.st, sw.hist3, sw.blockhist3, sw.cand);
     hipError_t e = allow_sort_lds();
@@ -962,13 +993,11 @@ hipError_t launch_select_tail(const float *scores, int64_t N, int64_t ld, int Q,
     return hipGetLastError();
 }
 
-// Pass 2 over sample scores (pass 1 was accumulated by launch_hist1 on the sample state); the
-// thresholds are then resolved into sample_sw.st[q].tau_key by a one-block-per-classifier kernel.
+// Thresholds of the filtered scans of Q classifiers from their sample scores (rank m of Nv each).
 hipError_t launch_sample_threshold(const float *sample_scores, int64_t Nv, int64_t ld, int Q, int m,
                                    const SelectWs &sample_sw, SelState *main_st, hipStream_t s) {
-    hist2_kernel<<<dim3(sel_blocks(Nv, Q), Q), 1024, 0, s>>>(sample_scores, Nv, ld, m, sample_sw.st, sample_sw.hist1,
-                                                    sample_sw.hist2, 1);
-    sample_tau_kernel<<<Q, 512, 0, s>>>(sample_sw.st, sample_sw.hist2, m, main_st);
+    if (m < 1 || m > Nv || !main_st) return hipErrorInvalidValue;
+    sample_threshold_kernel<<<Q, 1024, 0, s>>>(sample_scores, Nv, ld, m, sample_sw.st, main_st);
     return hipGetLastError();
 }
 

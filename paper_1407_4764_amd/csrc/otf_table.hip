@@ -65,20 +65,14 @@ __global__ __launch_bounds__(256) void pq_build_lut_kernel(const float *__restri
 
 // Zeroes both selection states (full selection and sample thresholding) of one classifier.
 __device__ __forceinline__ void zero_states(int tid, int step, SelState *st, uint32_t *hist1, uint32_t *hist2,
-                                            uint32_t *hist3, SelState *sst, uint32_t *shist1, uint32_t *shist2) {
+                                            uint32_t *hist3, SelState *sst) {
     uint32_t *stw = reinterpret_cast<uint32_t *>(st), *sstw = reinterpret_cast<uint32_t *>(sst);
     for (int i = tid; i < (int)(sizeof(SelState) / 4); i += step) {
         stw[i] = 0u;
         sstw[i] = 0u;
     }
-    for (int i = tid; i < kHist1Words; i += step) {
-        hist1[i] = 0u;
-        shist1[i] = 0u;
-    }
-    for (int i = tid; i < kBins2; i += step) {
-        hist2[i] = 0u;
-        shist2[i] = 0u;
-    }
+    for (int i = tid; i < kHist1Words; i += step) hist1[i] = 0u;
+    for (int i = tid; i < kBins2; i += step) hist2[i] = 0u;
     for (int i = tid; i < kBins3; i += step) hist3[i] = 0u;
 }
 
@@ -96,15 +90,14 @@ __device__ __forceinline__ int row_byte_at(int row_bytes, int span, int sp, int 
 // the selection states (one launch instead of two).
 __global__ __launch_bounds__(256) void pq_prepare_kernel(const float *__restrict__ lut, int M, int span, int nsplit,
                                                          float *__restrict__ image, SelState *st, uint32_t *hist1,
-                                                         uint32_t *hist2, uint32_t *hist3, SelState *sst,
-                                                         uint32_t *shist1, uint32_t *shist2) {
+                                                         uint32_t *hist2, uint32_t *hist3, SelState *sst) {
     const int tid = blockIdx.x * blockDim.x + threadIdx.x, step = gridDim.x * blockDim.x;
     for (int t = tid; t < nsplit * kImageFloats; t += step) {
         const int v = t & 255, pos = (t >> 8) & (kSegBytes - 1), sp = t >> 15;
         const int m = row_byte_at(M, span, sp, pos);
         image[(size_t)sp * kImageFloats + v * kSegBytes + image_column(pos)] = m >= 0 ? lut[(size_t)m * 256 + v] : 0.f;
     }
-    zero_states(tid, step, st, hist1, hist2, hist3, sst, shist1, shist2);
+    zero_states(tid, step, st, hist1, hist2, hist3, sst);
 }
 
 // The same straight from the vocabularies and the model, for a caller that ranks under a new model
@@ -114,7 +107,7 @@ __global__ __launch_bounds__(256) void pq_prepare_model_kernel(const float *__re
                                                                const float *__restrict__ w, int M, int dsub, int span,
                                                                int nsplit, float *__restrict__ image, SelState *st,
                                                                uint32_t *hist1, uint32_t *hist2, uint32_t *hist3,
-                                                               SelState *sst, uint32_t *shist1, uint32_t *shist2) {
+                                                               SelState *sst) {
     const int tid = blockIdx.x * blockDim.x + threadIdx.x, step = gridDim.x * blockDim.x;
     for (int t = tid; t < nsplit * kImageFloats; t += step) {
         const int v = t & 255, pos = (t >> 8) & (kSegBytes - 1), sp = t >> 15;
@@ -127,15 +120,14 @@ __global__ __launch_bounds__(256) void pq_prepare_model_kernel(const float *__re
         }
         image[(size_t)sp * kImageFloats + v * kSegBytes + image_column(pos)] = acc;
     }
-    zero_states(tid, step, st, hist1, hist2, hist3, sst, shist1, shist2);
+    zero_states(tid, step, st, hist1, hist2, hist3, sst);
 }
 
 // Table images for binary codes with byte groups: byte g of a row covers dimensions 8g..8g+7.
 __global__ __launch_bounds__(256) void binary_prepare_kernel(const float *__restrict__ w, int row_bytes, int span,
                                                              int nsplit, float *__restrict__ image, SelState *st,
                                                              uint32_t *hist1,
-                                                             uint32_t *hist2, uint32_t *hist3, SelState *sst,
-                                                             uint32_t *shist1, uint32_t *shist2) {
+                                                             uint32_t *hist2, uint32_t *hist3, SelState *sst) {
     const int tid = blockIdx.x * blockDim.x + threadIdx.x, step = gridDim.x * blockDim.x;
     for (int t = tid; t < nsplit * kImageFloats; t += step) {
         const int v = t & 255, pos = (t >> 8) & (kSegBytes - 1), sp = t >> 15;
@@ -148,7 +140,7 @@ __global__ __launch_bounds__(256) void binary_prepare_kernel(const float *__rest
         }
         image[(size_t)sp * kImageFloats + v * kSegBytes + image_column(pos)] = acc;
     }
-    zero_states(tid, step, st, hist1, hist2, hist3, sst, shist1, shist2);
+    zero_states(tid, step, st, hist1, hist2, hist3, sst);
 }
 
 // Table image for 2048-bit rows: word q (0..63) of a row = lane-chunk q/4, word tq = q%4 of the chunk.
@@ -160,8 +152,7 @@ __global__ __launch_bounds__(256) void binary_prepare_kernel(const float *__rest
 //        side[v][q] makes every side read a 4-way bank conflict: 37 % of the kernel's LDS cycles.)
 __global__ __launch_bounds__(256) void binary7_prepare_kernel(const float *__restrict__ w, float *__restrict__ image,
                                                               SelState *st, uint32_t *hist1, uint32_t *hist2,
-                                                              uint32_t *hist3, SelState *sst, uint32_t *shist1,
-                                                              uint32_t *shist2) {
+                                                              uint32_t *hist3, SelState *sst) {
     const int tid = blockIdx.x * blockDim.x + threadIdx.x, step = gridDim.x * blockDim.x;
     for (int t = tid; t < 128 * 256; t += step) {
         const int v = t & 127, col = t >> 7;              // col = 4*q + j
@@ -186,7 +177,7 @@ __global__ __launch_bounds__(256) void binary7_prepare_kernel(const float *__res
         }
         image[kImageFloats + t] = acc;
     }
-    zero_states(tid, step, st, hist1, hist2, hist3, sst, shist1, shist2);
+    zero_states(tid, step, st, hist1, hist2, hist3, sst);
 }
 
 template <int CTRL>
@@ -662,7 +653,7 @@ hipError_t launch_pq_prepare(const float *lut, int M, float *image, const Select
                              hipStream_t s) {
     const int nphase = phases_of(M);
     pq_prepare_kernel<<<nphase * 32, 256, 0, s>>>(lut, M, span_of(M), nphase, image, sw.st, sw.hist1, sw.hist2, sw.hist3,
-                                                  ssw.st, ssw.hist1, ssw.hist2);
+                                                  ssw.st);
     return hipGetLastError();
 }
 
@@ -670,7 +661,7 @@ hipError_t launch_pq_prepare_model(const float *codebooks, const float *w, int M
                                    const SelectWs &sw, const SelectWs &ssw, hipStream_t s) {
     const int nphase = phases_of(M);
     pq_prepare_model_kernel<<<nphase * 64, 256, 0, s>>>(codebooks, w, M, dsub, span_of(M), nphase, image, sw.st, sw.hist1,
-                                                        sw.hist2, sw.hist3, ssw.st, ssw.hist1, ssw.hist2);
+                                                        sw.hist2, sw.hist3, ssw.st);
     return hipGetLastError();
 }
 
@@ -678,13 +669,12 @@ hipError_t launch_pq_prepare_model(const float *codebooks, const float *w, int M
 hipError_t launch_binary_prepare(const float *w, int D, float *image, const SelectWs &sw, const SelectWs &ssw,
                                  hipStream_t s) {
     if (D == 2048) {
-        binary7_prepare_kernel<<<64, 256, 0, s>>>(w, image, sw.st, sw.hist1, sw.hist2, sw.hist3, ssw.st, ssw.hist1,
-                                                  ssw.hist2);
+        binary7_prepare_kernel<<<64, 256, 0, s>>>(w, image, sw.st, sw.hist1, sw.hist2, sw.hist3, ssw.st);
         return hipGetLastError();
     }
     const int row_bytes = D / 8, nphase = phases_of(row_bytes);
     binary_prepare_kernel<<<nphase * 32, 256, 0, s>>>(w, row_bytes, span_of(row_bytes), nphase, image, sw.st, sw.hist1,
-                                                      sw.hist2, sw.hist3, ssw.st, ssw.hist1, ssw.hist2);
+                                                      sw.hist2, sw.hist3, ssw.st);
     return hipGetLastError();
 }
 
