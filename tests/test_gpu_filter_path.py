@@ -252,6 +252,33 @@ def test_multi_classifier_zero_models_are_called_off(oracle):
         assert ok, "q=%d: %s" % (q, msg)
 
 
+def test_multi_classifier_one_overflowing_list_sends_all_to_the_full_selection(oracle):
+    """One classifier of the 64 looks at a single dimension, and 20,000 rows outside every sampled
+    group are that dimension's unit vector: its threshold comes from the bulk, its candidate list
+    overflows, the sort kernel raises the flag, and the full selection ranks all classifiers --
+    that one gets the first k of the tied rows, the others their oracle lists."""
+    N, D, Q, k = 1060000, 128, 64, 50
+    X = synth.dense_features(N, D, SEED + 40, dtype=torch.float16)
+    X[2048:22048] = 0
+    X[2048:22048, 0] = 1                                       # groups 2..21 of 1024 rows: never sampled
+    W = synth.normal_matrix(Q, D, 0.05, SEED + 41, dtype=torch.float16)
+    W[5] = 0
+    W[5, 0] = 1
+    b = synth.normal_vector(Q, 0.01, SEED + 42)
+    ws = binding.make_workspace(N, k, Q)
+    val, idx = binding.rank_dense(X.to(DEV), W.to(DEV), b.to(DEV), k, ws)
+    assert binding.debug_fallback_taken(ws)
+    np.testing.assert_array_equal(idx[5].cpu().numpy(), np.arange(2048, 2048 + k))
+    assert torch.all(val[5] == val[5, 0])
+    ref = oracle.dense_scores(X.numpy(), W.numpy(), b.numpy())
+    all_scores = torch.empty((Q, N), dtype=torch.float32, device=DEV)
+    val2, idx2 = binding.rank_dense(X.to(DEV), W.to(DEV), b.to(DEV), k, ws, all_scores=all_scores)
+    assert torch.equal(idx, idx2) and torch.equal(val, val2)    # the route that never filters agrees
+    for q in range(0, Q, 5):
+        ok, msg = oracle.topk_parity_ok(ref[q], k, idx[q].cpu().numpy(), val[q].cpu().numpy(), RTOL16)
+        assert ok, "q=%d: %s" % (q, msg)
+
+
 @pytest.mark.parametrize("spin_limit", [0, 1])
 def test_fallback_with_crowded_scores_but_no_big_tie(oracle, spin_limit, debug_switches):
     """Scores that crowd into one 12-bit bin of the key (all between 1 and 1.06) without tying: the
