@@ -135,3 +135,29 @@ def test_ranking_straight_from_the_vocabularies_equals_table_build_plus_ranking(
     v3, i3 = binding.rank_pq_model(codes, cb, w, -0.5, k, ws)          # and on the filtered route
     torch.cuda.synchronize()
     assert torch.equal(i1, i3) and torch.equal(v1, v3)
+
+
+@pytest.mark.parametrize("M", [512, 272])
+def test_long_rows_fall_back_when_the_list_cannot_serve(oracle, M):
+    """Rows of several table images behind a failed filtered scan: under a zero model every score is
+    the bias (rows 0..k-1); with 10,000 maximal rows outside every sampled group the list overflows
+    and the full selection splits the tie by row."""
+    N, k, dsub = 1150000, 500, 4
+    cb = synth.pq_codebooks(M, 256, dsub, SEED + 600)
+    codes = synth.pq_codes(N, M, 256, SEED + 601)
+    ws = binding.make_workspace(N, k)
+    cd, cbd = codes.to(DEV), cb.to(DEV)
+    val, idx = binding.rank_pq_model(cd, cbd, torch.zeros(M * dsub, device=DEV), 0.75, k, ws)
+    assert binding.debug_fallback_taken(ws)
+    np.testing.assert_array_equal(idx[0].cpu().numpy(), np.arange(k))
+    assert torch.all(val[0] == 0.75)
+
+    w = synth.normal_vector(M * dsub, 1.0, SEED + 602)
+    lut = binding.pq_build_lut(cbd, w.to(DEV))
+    codes[2048:12048] = lut.argmax(dim=1).to(torch.uint8).cpu()          # the best code of every sub-block
+    cd = codes.to(DEV)
+    val, idx = binding.rank_pq(cd, lut, 0.0, k, ws)
+    assert binding.debug_fallback_taken(ws)
+    np.testing.assert_array_equal(idx[0].cpu().numpy(), np.arange(2048, 2048 + k))
+    ref = oracle.pq_scores_reconstruct(codes[2048:2049].numpy(), cb.numpy(), w.numpy(), 0.0)
+    assert abs(float(val[0, 0]) - ref[0]) <= 1e-4 * abs(ref[0]) and torch.all(val[0] == val[0, 0])

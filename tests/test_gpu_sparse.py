@@ -96,3 +96,28 @@ def test_large_store_filtered_route(oracle):
     N, k = 1300000, 1000
     ws = _check(oracle, synth.sparse_features(N, 128, SEED + 6), k, bias=0.0)
     assert not binding.debug_fallback_taken(ws)
+
+
+def test_large_store_whose_list_overflows_falls_back(oracle):
+    """10,000 equal rows outside every sampled group outscore the rest: the threshold comes from the
+    bulk, the candidate list overflows, and the gated re-scan and full selection give the answer (the
+    first k of the tied rows)."""
+    N, k = 1200000, 1000
+    X = synth.sparse_features(N, 128, SEED + 7)
+    w = synth.normal_vector(128, 1.0, SEED + 1)               # the model _check ranks under
+    top = torch.clamp(w, min=0.0)
+    top[torch.argsort(top)[:96]] = 0.0                        # its 32 largest weights: a sparse row
+    X[2048:12048] = top / top.norm()
+    ws = _check(oracle, X, k, bias=0.0)
+    assert binding.debug_fallback_taken(ws)
+
+
+def test_large_store_under_a_zero_model_falls_back(oracle):
+    """The first ranking of an on-the-fly query: w = 0, every score equals the bias, rows 0..k-1."""
+    N, k = 1100000, 300
+    rows, start = synth.sparse_rows_from_dense(synth.sparse_features(N, 128, SEED + 8))
+    ws = binding.make_workspace(N, k)
+    val, idx = binding.rank_sparse(rows.to(DEV), start.to(DEV), 128, torch.zeros(128, device=DEV), 0.5, k, ws)
+    assert binding.debug_fallback_taken(ws)
+    np.testing.assert_array_equal(idx[0].cpu().numpy(), np.arange(k))
+    assert torch.all(val[0] == 0.5)
