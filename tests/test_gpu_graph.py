@@ -55,6 +55,25 @@ def test_dense_rankings_replay(oracle):
                        lambda r: synth.normal_vector(D, 0.05, SEED + 20 + r, device=DEV))
 
 
+def test_replays_take_the_fallback_when_the_model_asks_for_it():
+    """One captured filtered ranking serves models whose filtered scan succeeds and a zero model, under
+    which every score ties and the gated re-scan and full selection of the same graph must answer."""
+    N, D, k = 1300000, 128, 200
+    X = synth.dense_features(N, D, SEED + 77, device=DEV)
+    w = synth.normal_vector(D, 0.05, SEED + 78, device=DEV)
+    ws = binding.make_workspace(N, k)
+    out = binding._outputs(1, k, DEV)
+    taken = []
+
+    def model(r):
+        if r > 0:
+            taken.append(binding.debug_fallback_taken(ws))          # of the replay before this one
+        return torch.zeros(D, device=DEV) if r == 1 else synth.normal_vector(D, 0.05, SEED + 80 + r, device=DEV)
+    _check_replays(lambda: binding.rank_dense(X, w, None, k, ws, out=out), w, out, model)
+    taken.append(binding.debug_fallback_taken(ws))
+    assert taken == [False, True, False]
+
+
 @pytest.mark.parametrize("N,M,dsub", [(1200000, 128, 16), (1100000, 512, 4), (3000, 256, 8), (40, 512, 4)])
 def test_pq_rankings_replay(N, M, dsub):
     k = min(N, 100)
