@@ -94,7 +94,7 @@ int otf_rank_dense(const void *X, otf_dtype xdt, int64_t N, int32_t D, int64_t l
  * OTF_NOALLOC_SCRATCH_BYTES that is part of the library's device code (each GPU the library runs
  * on holds its own copy until the process ends).  The call allocates and frees nothing.
  *   - Sizes whose otf_workspace_bytes(N, k, Q) exceed OTF_NOALLOC_SCRATCH_BYTES (one classifier:
- *     above ~3.7 million rows) return OTF_ERR_SCRATCH and enqueue nothing.
+ *     above ~3.8 million rows) return OTF_ERR_SCRATCH and enqueue nothing.
  *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
  *     streams or host threads) race and give undefined results; calls on one stream are safe.
  *     Every call clears the parts of the array that must start at zero itself.
